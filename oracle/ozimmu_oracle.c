@@ -1,0 +1,305 @@
+/*
+ * CPU oracle for the integer-slice (Ootomo-Ozaki-Yokota) matrix product.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain reference that the
+ * GPU library is checked against.  It shares no code, header, table or helper
+ * with the HIP path and must never be called from the product path.
+ *
+ * It follows the paper's Algorithm 1 ("Matrix multiplication using an integer
+ * MMA unit") step by step, in the paper's notation:
+ *   alpha_i, beta_j   eq. (alpha-def), (beta-def)          -> oz_oracle_exponents
+ *   A_(l), B^(h)      eq. (bit-splitting-alg), bit view     -> oz_oracle_split
+ *   A_(l) B^(h)       exact integer products, eq. (wtc-expr)-> oz_oracle_slice_product
+ *   S, C              Alg. 1 accumulation and final scaling -> oz_oracle_dgemm
+ *   kappa_A, kappa_B  eq. (a-bound-row-2), (b-bound)        -> oz_oracle_kappa
+ *   slice estimate    eq. (err-bound) and the recipe of the
+ *                     "Discussion" subsection of Sect. 4    -> oz_oracle_estimate_slices
+ *
+ * All matrices are column-major with BLAS-style leading dimensions.
+ * Slices are stored one int8 per entry (t <= 7, so |slice| <= 2^t - 1 <= 127).
+ * Integer products are formed in int64, so they are exact for every k an int
+ * can hold (k * 127^2 < 2^63).  The only rounding anywhere is in the binary64
+ * additions of the accumulation step.
+ *
+ * Parity status: every function here is pinned by tests/test_oracle_pins.py
+ * (worked example of Sect. 3, exact rational arithmetic, closed forms).
+ * Unpinned: the absolute error values plotted in the paper's figures (their
+ * data files are not available) -- "parity unpinned" for those only.
+ *
+ * Build:  gcc -O2 -fopenmp -ffp-contract=off -fPIC -shared -o liboracle.so ozimmu_oracle.c -lm
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define OZ_ORACLE_OK 0
+#define OZ_ORACLE_BAD_ARG 1
+#define OZ_ORACLE_NONFINITE 2
+#define OZ_ORACLE_UNREACHABLE 4
+
+#define OZ_ORACLE_MAX_SLICES 64
+
+int oz_oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* |x| = I * 2^q with I the integer significand (0 <= I < 2^53).  Sect. 2. */
+static void decompose(double x, int *neg, uint64_t *I, int *q)
+{
+    uint64_t u;
+    memcpy(&u, &x, 8);
+    *neg = (int)(u >> 63);
+    int E = (int)((u >> 52) & 0x7ff);
+    uint64_t f = u & 0xfffffffffffffULL;
+    if (E == 0) { *I = f; *q = -1074; }               /* subnormal or zero */
+    else        { *I = f | (1ULL << 52); *q = E - 1075; }
+}
+
+/*
+ * e = floor(log2 M) + 1, so that 2^e is the smallest power of two strictly
+ * larger than M -- eq. (alpha-def).  Computed from the representation, never
+ * through log2().  M = 0 gives the sentinel e = 0 (the paper assumes no zero
+ * row; any scale works because every slice of such a row is zero).
+ */
+static int exponent_above(double M)
+{
+    if (M == 0.0) return 0;
+    int e;
+    (void)frexp(M, &e);          /* M = f * 2^e, 0.5 <= f < 1 */
+    return e;
+}
+
+/*
+ * Scale exponents.  side 'A': one per row of X (rows entries);
+ * side 'B': one per column of X (cols entries).   alpha_i = 2^e[i].
+ */
+int oz_oracle_exponents(char side, int rows, int cols, const double *X, int ldx, int32_t *e)
+{
+    if ((side != 'A' && side != 'B') || rows < 0 || cols < 0 || ldx < (rows > 1 ? rows : 1)) return OZ_ORACLE_BAD_ARG;
+    int nblk = side == 'A' ? rows : cols;
+    int len = side == 'A' ? cols : rows;
+    for (int b = 0; b < nblk; ++b) {
+        double M = 0.0;
+        for (int r = 0; r < len; ++r) {
+            double x = side == 'A' ? X[b + (size_t)r * ldx] : X[r + (size_t)b * ldx];
+            if (!isfinite(x)) return OZ_ORACLE_NONFINITE;
+            if (fabs(x) > M) M = fabs(x);
+        }
+        e[b] = exponent_above(M);
+    }
+    return OZ_ORACLE_OK;
+}
+
+/*
+ * Slice l (1-based) of x relative to the scale 2^e, with t bits per slice:
+ * the bits of |x| / 2^e in positions (l-1)t+1 .. lt after the binary point,
+ * carrying the sign of x -- bit-level view of eq. (bit-splitting-alg).
+ * floor(|x| 2^{lt-e}) mod 2^t  with |x| = I 2^q  is a shift and a mask.
+ */
+static int slice_of(double x, int e, int l, int t)
+{
+    int neg, q;
+    uint64_t I;
+    decompose(x, &neg, &I, &q);
+    long sh = (long)e - q - (long)l * t;     /* right shift that aligns bit lt with bit 0 */
+    uint64_t v;
+    if (sh >= 64) v = 0;
+    else if (sh >= 0) v = I >> sh;
+    else if (-sh >= t) v = 0;                /* all of I lies above this slice's window */
+    else v = I << (-sh);
+    int d = (int)(v & ((1u << t) - 1u));
+    return neg ? -d : d;
+}
+
+/*
+ * planes[(l-1) * rows * cols + r + c * rows] = slice l of X[r, c]  (l = 1..s),
+ * each plane column-major with leading dimension rows.
+ * e: the exponents from oz_oracle_exponents for the same side.
+ */
+int oz_oracle_split(char side, int rows, int cols, const double *X, int ldx, int s, int t,
+                    const int32_t *e, int8_t *planes)
+{
+    if ((side != 'A' && side != 'B') || rows < 0 || cols < 0 || ldx < (rows > 1 ? rows : 1) ||
+        s < 1 || s > OZ_ORACLE_MAX_SLICES || t < 1 || t > 7) return OZ_ORACLE_BAD_ARG;
+    size_t plane = (size_t)rows * cols;
+    for (int c = 0; c < cols; ++c)
+        for (int r = 0; r < rows; ++r) {
+            double x = X[r + (size_t)c * ldx];
+            if (!isfinite(x)) return OZ_ORACLE_NONFINITE;
+            int ex = side == 'A' ? e[r] : e[c];
+            for (int l = 1; l <= s; ++l)
+                planes[(size_t)(l - 1) * plane + r + (size_t)c * rows] = (int8_t)slice_of(x, ex, l, t);
+        }
+    return OZ_ORACLE_OK;
+}
+
+/* P = Al * Bh exactly, Al m-by-k (ld m), Bh k-by-n (ld k), P m-by-n (ld m), all column-major. */
+int oz_oracle_slice_product(int m, int n, int k, const int8_t *Al, const int8_t *Bh, int64_t *P)
+{
+    if (m < 0 || n < 0 || k < 0) return OZ_ORACLE_BAD_ARG;
+#pragma omp parallel for schedule(static)
+    for (int j = 0; j < n; ++j) {
+        int64_t *p = P + (size_t)j * m;
+        for (int i = 0; i < m; ++i) p[i] = 0;
+        for (int kk = 0; kk < k; ++kk) {
+            int64_t b = Bh[kk + (size_t)j * k];
+            const int8_t *a = Al + (size_t)kk * m;
+            for (int i = 0; i < m; ++i) p[i] += (int64_t)a[i] * b;
+        }
+    }
+    return OZ_ORACLE_OK;
+}
+
+/*
+ * C ~ A B by Algorithm 1 with s slices of t bits.
+ *
+ * order 0  "by diagonals" (the accumulation order analysed in the subsection
+ *          "Accumulation in floating-point arithmetic" and the first tweak of
+ *          the "Enhanced algorithm"): D_d = sum of A_(l) B^(d-l) over the
+ *          computed pairs, exactly in integers; then S <- S + 2^{-dt} D_d for
+ *          d = 2, 3, ..., one binary64 rounding per addition.
+ * order 1  literal loop nest of Algorithm 1: l outer, h inner, one binary64
+ *          addition per product.
+ * full 0   only products with l + h <= s + 1 (Algorithm 1)
+ * full 1   all s^2 products (subsection "Computation of all products").
+ *
+ * Final step: C = diag(alpha) S diag(beta), i.e. ldexp(S_ij, eA_i + eB_j).
+ * Optional outputs (may be NULL): eA[m], eB[n].
+ */
+int oz_oracle_dgemm(int m, int n, int k, const double *A, int lda, const double *B, int ldb,
+                    double *C, int ldc, int s, int t, int order, int full,
+                    int32_t *eA_out, int32_t *eB_out)
+{
+    if (m < 0 || n < 0 || k < 0 || s < 1 || s > OZ_ORACLE_MAX_SLICES || t < 1 || t > 7 ||
+        lda < (m > 1 ? m : 1) || ldb < (k > 1 ? k : 1) || ldc < (m > 1 ? m : 1) ||
+        (order != 0 && order != 1) || (full != 0 && full != 1)) return OZ_ORACLE_BAD_ARG;
+    if (m == 0 || n == 0) return OZ_ORACLE_OK;
+
+    int32_t *eA = malloc(sizeof(int32_t) * (size_t)m);
+    int32_t *eB = malloc(sizeof(int32_t) * (size_t)n);
+    int8_t *pa = malloc((size_t)s * m * (k > 0 ? k : 1));
+    int8_t *pb = malloc((size_t)s * n * (k > 0 ? k : 1));
+    int rc = OZ_ORACLE_BAD_ARG;
+    if (!eA || !eB || !pa || !pb) goto done;
+    if ((rc = oz_oracle_exponents('A', m, k, A, lda, eA))) goto done;
+    if ((rc = oz_oracle_exponents('B', k, n, B, ldb, eB))) goto done;
+    if ((rc = oz_oracle_split('A', m, k, A, lda, s, t, eA, pa))) goto done;
+    if ((rc = oz_oracle_split('B', k, n, B, ldb, s, t, eB, pb))) goto done;
+
+    const size_t planeA = (size_t)m * k, planeB = (size_t)k * n;
+    const int dmax = full ? 2 * s : s + 1;
+
+#pragma omp parallel
+    {
+        int64_t *p = malloc(sizeof(int64_t) * (size_t)m);   /* one product column   */
+        int64_t *D = malloc(sizeof(int64_t) * (size_t)m);   /* one diagonal column  */
+        double *S = malloc(sizeof(double) * (size_t)m);
+#pragma omp for schedule(dynamic, 1)
+        for (int j = 0; j < n; ++j) {
+            for (int i = 0; i < m; ++i) S[i] = 0.0;
+            if (order == 0) {
+                for (int d = 2; d <= dmax; ++d) {
+                    for (int i = 0; i < m; ++i) D[i] = 0;
+                    for (int l = 1; l <= s; ++l) {
+                        int h = d - l;
+                        if (h < 1 || h > s) continue;
+                        const int8_t *al = pa + (size_t)(l - 1) * planeA;
+                        const int8_t *bh = pb + (size_t)(h - 1) * planeB + (size_t)j * k;
+                        for (int kk = 0; kk < k; ++kk) {
+                            int64_t b = bh[kk];
+                            const int8_t *a = al + (size_t)kk * m;
+                            for (int i = 0; i < m; ++i) D[i] += (int64_t)a[i] * b;
+                        }
+                    }
+                    for (int i = 0; i < m; ++i) S[i] = S[i] + ldexp((double)D[i], -d * t);
+                }
+            } else {
+                for (int l = 1; l <= s; ++l) {
+                    int hmax = full ? s : s - l + 1;
+                    for (int h = 1; h <= hmax; ++h) {
+                        const int8_t *al = pa + (size_t)(l - 1) * planeA;
+                        const int8_t *bh = pb + (size_t)(h - 1) * planeB + (size_t)j * k;
+                        for (int i = 0; i < m; ++i) p[i] = 0;
+                        for (int kk = 0; kk < k; ++kk) {
+                            int64_t b = bh[kk];
+                            const int8_t *a = al + (size_t)kk * m;
+                            for (int i = 0; i < m; ++i) p[i] += (int64_t)a[i] * b;
+                        }
+                        for (int i = 0; i < m; ++i) S[i] = S[i] + ldexp((double)p[i], -(l + h) * t);
+                    }
+                }
+            }
+            for (int i = 0; i < m; ++i) C[i + (size_t)j * ldc] = ldexp(S[i], eA[i] + eB[j]);
+        }
+        free(p); free(D); free(S);
+    }
+    if (eA_out) memcpy(eA_out, eA, sizeof(int32_t) * (size_t)m);
+    if (eB_out) memcpy(eB_out, eB, sizeof(int32_t) * (size_t)n);
+    rc = OZ_ORACLE_OK;
+done:
+    free(eA); free(eB); free(pa); free(pb);
+    return rc;
+}
+
+/*
+ * kappa = 2 max_blocks ( max |x| / min |x| ), eq. (a-bound-row-2) for side 'A'
+ * (blocks = rows) and eq. (b-bound) for side 'B' (blocks = columns).  The
+ * minimum runs over the nonzero entries of a block (a zero entry has no
+ * conversion error); a block of zeros is skipped; no nonzero entry: kappa = 0.
+ */
+int oz_oracle_kappa(char side, int rows, int cols, const double *X, int ldx, double *kappa)
+{
+    if ((side != 'A' && side != 'B') || rows < 0 || cols < 0 || ldx < (rows > 1 ? rows : 1)) return OZ_ORACLE_BAD_ARG;
+    int nblk = side == 'A' ? rows : cols;
+    int len = side == 'A' ? cols : rows;
+    double worst = 0.0;
+    for (int b = 0; b < nblk; ++b) {
+        double M = 0.0, mn = INFINITY;
+        for (int r = 0; r < len; ++r) {
+            double x = side == 'A' ? X[b + (size_t)r * ldx] : X[r + (size_t)b * ldx];
+            if (!isfinite(x)) return OZ_ORACLE_NONFINITE;
+            double ax = fabs(x);
+            if (ax > M) M = ax;
+            if (ax != 0.0 && ax < mn) mn = ax;
+        }
+        if (M == 0.0) continue;
+        double ratio = M / mn;
+        if (ratio > worst) worst = ratio;
+    }
+    *kappa = 2.0 * worst;
+    return OZ_ORACLE_OK;
+}
+
+/*
+ * Smallest s >= 1 (same count for A and B) with
+ *     kappa_A 2^{-st} + kappa_B 2^{-st} <= tol,
+ * the left-hand side of eq. (err-bound), evaluated for s = 1, 2, ... as the
+ * "Discussion" subsection of Sect. 4 prescribes.  s_max: largest s tried;
+ * if none meets tol the result is s_max and the return code says so.
+ */
+int oz_oracle_estimate_slices(int m, int n, int k, const double *A, int lda, const double *B, int ldb,
+                              double tol, int t, int s_max, int *s_out, double *kappaA_out, double *kappaB_out)
+{
+    if (!(tol > 0.0) || t < 1 || t > 7 || s_max < 1) return OZ_ORACLE_BAD_ARG;
+    double kA, kB;
+    int rc;
+    if ((rc = oz_oracle_kappa('A', m, k, A, lda, &kA))) return rc;
+    if ((rc = oz_oracle_kappa('B', k, n, B, ldb, &kB))) return rc;
+    if (kappaA_out) *kappaA_out = kA;
+    if (kappaB_out) *kappaB_out = kB;
+    for (int s = 1; s <= s_max; ++s) {
+        double lhs = ldexp(kA, -s * t) + ldexp(kB, -s * t);
+        if (lhs <= tol) { *s_out = s; return OZ_ORACLE_OK; }
+    }
+    *s_out = s_max;
+    return OZ_ORACLE_UNREACHABLE;
+}
