@@ -1,0 +1,147 @@
+/*
+ * ozimmu -- binary64 matrix multiplication through int8 slices on MI355X (gfx950).
+ *
+ * C ~ A B for binary64 A (m-by-k) and B (k-by-n) by the integer-slice scheme of Ootomo,
+ * Ozaki and Yokota as stated in Algorithm 1 of "Analysis of Floating-Point Matrix
+ * Multiplication Computed via Integer Arithmetic" (Sect. 3), with the accumulation order
+ * of the subsection "Accumulation in floating-point arithmetic" (Sect. 4) and the
+ * slice-count estimate of the "Discussion" subsection of Sect. 4.
+ *
+ * Conventions for every entry point
+ *   - Matrices are column-major with BLAS-style leading dimensions; D = A B (alpha = 1,
+ *     beta = 0, no transposes), the GEMM form the paper's GPU benchmark uses.
+ *   - A, B, C, X, planes, exps, workspace are DEVICE pointers owned by the caller.  The
+ *     library allocates no device memory.  Pointers marked [host] are host pointers.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls are
+ *     asynchronous on that stream unless stated otherwise.
+ *   - Slices hold t = 7 bits (int8 storage, values in [-127, 127]); 1 <= s <= OZIMMU_MAX_SLICES.
+ *   - Return value: one of the OZIMMU_* status codes; never throws or aborts.
+ *   - Inputs must be finite.  NaN or +-Inf are outside the method's domain (Sect. 3,
+ *     first paragraph of "Original algorithm"); they are detected, reported by
+ *     ozimmu_check(), and the output is then unspecified (but no fault occurs).
+ *     -0.0 is treated as +0.  An all-zero row of A / column of B gets exponent 0 and
+ *     yields a zero row / column of C.
+ *   - m, n or k equal to 0 is accepted (k = 0 gives C = 0).
+ */
+#ifndef OZIMMU_H
+#define OZIMMU_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define OZIMMU_OK 0
+#define OZIMMU_BAD_ARG 1      /* null pointer, negative size, ld too small, s out of range, workspace too small */
+#define OZIMMU_NONFINITE 2    /* NaN or Inf met in A or B */
+#define OZIMMU_HIP_ERROR 3    /* a HIP runtime call failed */
+#define OZIMMU_UNREACHABLE 4  /* estimator: tolerance not met by any s <= OZIMMU_MAX_SLICES */
+
+#define OZIMMU_MAX_SLICES 32
+#define OZIMMU_SLICE_BITS 7
+
+/* plane layouts for ozimmu_split */
+#define OZIMMU_LAYOUT_PLAIN 0 /* plane l (0-based) at planes + l*rows*cols, column-major like X, ld = rows */
+#define OZIMMU_LAYOUT_MFMA 1  /* tiled operand layout read by the GEMM kernel, see ozimmu_split */
+
+/* Human-readable name of a status code (static storage). */
+const char *ozimmu_status_string(int status);
+
+/*
+ * Bytes of device workspace ozimmu_dgemm / ozimmu_estimate_slices need for this problem:
+ * scale exponents, per-row/column reductions, and the int8 slice planes of A and B.
+ * Returns 0 for invalid arguments.  Alignment required of the workspace pointer: 256 bytes.
+ */
+size_t ozimmu_workspace_bytes(int m, int n, int k, int s);
+
+/* Bytes of the `planes` buffer ozimmu_split writes for the given layout (0 if invalid). */
+size_t ozimmu_planes_bytes(char side, int rows, int cols, int s, int layout);
+
+/*
+ * Slice-count estimate (Sect. 4, eq. (a-bound-row-2), (b-bound), (err-bound)):
+ *   kappa_A = 2 max_i ( max_j |a_ij| / min_j |a_ij| ),  kappa_B likewise over columns of B,
+ *   minima over the nonzero entries; all-zero rows/columns skipped;
+ *   *s_out = smallest s >= 1 with  kappa_A 2^{-7s} + kappa_B 2^{-7s} <= tol.
+ * One pass over A and B on the device; SYNCHRONISES the stream to return the result.
+ *   s_out  [host] receives s (OZIMMU_MAX_SLICES when unreachable)
+ *   kappa  [host] optional (may be NULL): kappa[0] = kappa_A, kappa[1] = kappa_B
+ * Returns OZIMMU_OK, OZIMMU_UNREACHABLE, OZIMMU_NONFINITE, OZIMMU_BAD_ARG (tol <= 0 or NaN,
+ * workspace smaller than ozimmu_workspace_bytes(m, n, k, 1)) or OZIMMU_HIP_ERROR.
+ */
+int ozimmu_estimate_slices(int m, int n, int k, const double *A, int lda, const double *B, int ldb,
+                           double tol, int *s_out, double *kappa,
+                           void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Scales and slices of one operand (Algorithm 1, the two scale loops and the two slicing
+ * loops; eq. (alpha-def), (beta-def), (bit-splitting-alg)).
+ *   side 'A': X is rows-by-cols = m-by-k; row i shares the scale 2^exps[i]; exps has `rows` entries.
+ *   side 'B': X is rows-by-cols = k-by-n; column j shares the scale 2^exps[j]; exps has `cols` entries.
+ *   exps[b] = floor(log2 max|x|) + 1 over the block (0 for an all-zero block).
+ *   Slice l (1-based) of an entry x of a block with exponent e is
+ *   sign(x) * ( floor(|x| 2^{7l - e}) mod 2^7 ).
+ * layout OZIMMU_LAYOUT_PLAIN: planes[(l-1)*rows*cols + r + c*rows].
+ * layout OZIMMU_LAYOUT_MFMA: the operand is viewed as R-by-K with R the scaled dimension
+ *   (rows of A / columns of B) and K the contraction dimension, zero-padded to
+ *   Rp = roundup(R, 128), Kp = roundup(K, 128), and cut into fragments of 32 (R) by 32 (K)
+ *   entries.  Fragment (rb, kb) of slice l starts at byte
+ *       (((size_t)rb * (Kp/32) + kb) * s + (l-1)) * 1024
+ *   and entry (r, kk) of the fragment sits at byte  ((r + 32*(kk/16)) * 16 + kk%16)  in it:
+ *   the 16 bytes lane (r + 32*(kk/16)) of a wavefront feeds to v_mfma_i32_32x32x32_i8.
+ * `scratch`: device buffer of ozimmu_split_scratch_bytes(side, rows, cols) bytes, 256-byte
+ * aligned, used for the reduction; a NaN/Inf in X is reported by ozimmu_check(scratch, stream).
+ */
+size_t ozimmu_split_scratch_bytes(char side, int rows, int cols);
+int ozimmu_split(char side, int rows, int cols, const double *X, int ldx, int s,
+                 int8_t *planes, int32_t *exps, int layout, void *scratch, void *stream);
+
+/*
+ * C = A B through s int8 slices (Algorithm 1 with k-blocked exact integer accumulation):
+ *   1. scale exponents of the rows of A and the columns of B,
+ *   2. s slices of each operand,
+ *   3. exact integer products A_(l) B^(h) for l + h <= s + 1 on the int8 matrix cores; the
+ *      products of one diagonal l + h = d are added exactly in integer arithmetic
+ *      (first tweak of the "Enhanced algorithm" paragraph of Sect. 3),
+ *   4. S = sum over d = 2, ..., s+1 in this order of 2^{-7d} D_d, one binary64 rounding per
+ *      addition; C_ij = 2^{eA_i + eB_j} S_ij.
+ * C is m-by-n with leading dimension ldc >= max(1, m).  The result is deterministic
+ * (bit-identical from run to run).  Non-finite input is reported by ozimmu_check().
+ */
+int ozimmu_dgemm(int m, int n, int k, const double *A, int lda, const double *B, int ldb,
+                 double *C, int ldc, int s, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Waits for the stream and returns OZIMMU_NONFINITE if the last ozimmu_dgemm /
+ * ozimmu_estimate_slices that used this workspace met a NaN or Inf, else OZIMMU_OK.
+ */
+int ozimmu_check(void *workspace, void *stream);
+
+/*
+ * After ozimmu_dgemm(m, n, k, ..., s, workspace, ...) on the same stream: copies the scale
+ * exponents it computed to eA[m] and eB[n] (device pointers, either may be NULL).
+ */
+int ozimmu_get_exponents(int m, int n, int k, int s, const void *workspace, int32_t *eA, int32_t *eB,
+                         void *stream);
+
+/*
+ * Test hooks (used by the parity tests to compare integer intermediates bit for bit).
+ * Both read the MFMA-layout planes that ozimmu_dgemm(m, n, k, ..., s, workspace) left in
+ * `workspace`, on the same stream.
+ *
+ * ozimmu_debug_diagonals: D[(d-2) * m * n + i + j*m] = sum_{l+h=d} (A_(l) B^(h))_ij as int32,
+ *   d = 2..s+1, produced by the main loop of the fused GEMM kernel (needs
+ *   s * k * 127^2 < 2^31 and s <= the fused kernel's limit, else OZIMMU_BAD_ARG).
+ * ozimmu_debug_slice_product: P[i + j*m] = sum_{kk = k0}^{k1-1} A_(l)[i,kk] B^(h)[kk,j] as int32
+ *   for one pair (l, h), 1-based, over the contraction range [k0, k1) with k0 a multiple of 32
+ *   and (k1-k0) * 127^2 < 2^31, produced by the generic (pair-by-pair) GEMM kernel.
+ */
+int ozimmu_debug_diagonals(int m, int n, int k, int s, const void *workspace, int32_t *D, void *stream);
+int ozimmu_debug_slice_product(int m, int n, int k, int s, const void *workspace, int l, int h,
+                               int k0, int k1, int32_t *P, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,199 @@
+// extern "C" boundary of libozimmu: argument checks, workspace carve-up, kernel sequencing.
+#include <cmath>
+#include <cstring>
+
+#include "oz_common.h"
+
+using namespace oz;
+
+namespace {
+
+inline bool bad_matrix(int rows, int cols, const void *p, int ld)
+{
+    if (rows < 0 || cols < 0) return true;
+    if (ld < (rows > 1 ? rows : 1)) return true;
+    return rows > 0 && cols > 0 && p == nullptr;
+}
+
+
+#define OZ_TRY(expr)                                        \
+    do {                                                    \
+        hipError_t e__ = (expr);                            \
+        if (e__ != hipSuccess) return OZIMMU_HIP_ERROR;     \
+    } while (0)
+
+// scales of both operands into the workspace (optionally with the minima for kappa)
+int scales_into_workspace(const Workspace &w, char *ws, int m, int n, int k, const double *A, int lda,
+                          const double *B, int ldb, bool with_min, hipStream_t st)
+{
+    auto *hdr = (unsigned long long *)(ws + w.off_header);
+    auto *flags = (unsigned int *)(ws + w.off_header);
+    auto *maxA = (unsigned long long *)(ws + w.off_maxA), *minA = (unsigned long long *)(ws + w.off_minA);
+    auto *maxB = (unsigned long long *)(ws + w.off_maxB), *minB = (unsigned long long *)(ws + w.off_minB);
+    OZ_TRY(launch_clear_header(hdr, st));
+    OZ_TRY(launch_reduce('A', m, k, A, lda, maxA, with_min ? minA : nullptr, flags, st));
+    OZ_TRY(launch_reduce('B', k, n, B, ldb, maxB, with_min ? minB : nullptr, flags, st));
+    OZ_TRY(launch_finalize(maxA, minA, (int32_t *)(ws + w.off_expA), m, w.mp, with_min ? hdr + 1 : nullptr, st));
+    OZ_TRY(launch_finalize(maxB, minB, (int32_t *)(ws + w.off_expB), n, w.np, with_min ? hdr + 2 : nullptr, st));
+    return OZIMMU_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *ozimmu_status_string(int status)
+{
+    switch (status) {
+        case OZIMMU_OK: return "ok";
+        case OZIMMU_BAD_ARG: return "bad argument";
+        case OZIMMU_NONFINITE: return "non-finite input";
+        case OZIMMU_HIP_ERROR: return "HIP runtime error";
+        case OZIMMU_UNREACHABLE: return "tolerance unreachable";
+    }
+    return "unknown status";
+}
+
+size_t ozimmu_workspace_bytes(int m, int n, int k, int s)
+{
+    if (m < 0 || n < 0 || k < 0 || s < 1 || s > OZIMMU_MAX_SLICES) return 0;
+    return carve(m, n, k, s).total;
+}
+
+size_t ozimmu_planes_bytes(char side, int rows, int cols, int s, int layout)
+{
+    if ((side != 'A' && side != 'B') || rows < 0 || cols < 0 || s < 1 || s > OZIMMU_MAX_SLICES) return 0;
+    if (layout == OZIMMU_LAYOUT_PLAIN) return (size_t)s * rows * cols;
+    if (layout != OZIMMU_LAYOUT_MFMA) return 0;
+    const int R = side == 'A' ? rows : cols, K = side == 'A' ? cols : rows;
+    return (size_t)s * round_up(R > 0 ? R : 1, kPad) * round_up(K > 0 ? K : 1, kPad);
+}
+
+size_t ozimmu_split_scratch_bytes(char side, int rows, int cols)
+{
+    if ((side != 'A' && side != 'B') || rows < 0 || cols < 0) return 0;
+    const int nblk = side == 'A' ? rows : cols;
+    return 256 + 8 * (size_t)(nblk > 0 ? nblk : 1);
+}
+
+int ozimmu_estimate_slices(int m, int n, int k, const double *A, int lda, const double *B, int ldb, double tol,
+                           int *s_out, double *kappa, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!s_out || !(tol > 0.0) || bad_matrix(m, k, A, lda) || bad_matrix(k, n, B, ldb)) return OZIMMU_BAD_ARG;
+    const Workspace w = carve(m, n, k, 1);
+    if (!workspace || workspace_bytes < w.total || ((uintptr_t)workspace & 255)) return OZIMMU_BAD_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    char *ws = (char *)workspace;
+    int rc = scales_into_workspace(w, ws, m, n, k, A, lda, B, ldb, true, st);
+    if (rc) return rc;
+    unsigned long long host[3];
+    OZ_TRY(hipMemcpyAsync(host, ws + w.off_header, sizeof(host), hipMemcpyDeviceToHost, st));
+    OZ_TRY(hipStreamSynchronize(st));
+    if (host[0] & 1ULL) return OZIMMU_NONFINITE;
+    double ratioA, ratioB;
+    std::memcpy(&ratioA, &host[1], 8);
+    std::memcpy(&ratioB, &host[2], 8);
+    const double kA = 2.0 * ratioA, kB = 2.0 * ratioB;
+    if (kappa) { kappa[0] = kA; kappa[1] = kB; }
+    // left-hand side of eq. (err-bound) with s_A = s_B = s, tried for s = 1, 2, ...
+    for (int s = 1; s <= OZIMMU_MAX_SLICES; ++s) {
+        const double lhs = std::ldexp(kA, -s * kSliceBits) + std::ldexp(kB, -s * kSliceBits);
+        if (lhs <= tol) { *s_out = s; return OZIMMU_OK; }
+    }
+    *s_out = OZIMMU_MAX_SLICES;
+    return OZIMMU_UNREACHABLE;
+}
+
+int ozimmu_split(char side, int rows, int cols, const double *X, int ldx, int s, int8_t *planes, int32_t *exps,
+                 int layout, void *scratch, void *stream)
+{
+    if ((side != 'A' && side != 'B') || bad_matrix(rows, cols, X, ldx) || s < 1 || s > OZIMMU_MAX_SLICES ||
+        (layout != OZIMMU_LAYOUT_PLAIN && layout != OZIMMU_LAYOUT_MFMA) || !scratch || ((uintptr_t)scratch & 255))
+        return OZIMMU_BAD_ARG;
+    const int nblk = side == 'A' ? rows : cols;
+    if (nblk > 0 && !exps) return OZIMMU_BAD_ARG;
+    if (ozimmu_planes_bytes(side, rows, cols, s, layout) > 0 && !planes) return OZIMMU_BAD_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    auto *hdr = (unsigned long long *)scratch;
+    auto *maxbits = hdr + 32;
+    OZ_TRY(launch_clear_header(hdr, st));
+    OZ_TRY(launch_reduce(side, rows, cols, X, ldx, maxbits, nullptr, (unsigned int *)hdr, st));
+    OZ_TRY(launch_finalize(maxbits, nullptr, exps, nblk, nblk, nullptr, st));
+    OZ_TRY(launch_split(side, rows, cols, X, ldx, s, exps, planes, layout, st));
+    return OZIMMU_OK;
+}
+
+int ozimmu_dgemm(int m, int n, int k, const double *A, int lda, const double *B, int ldb, double *C, int ldc, int s,
+                 void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (bad_matrix(m, k, A, lda) || bad_matrix(k, n, B, ldb) || bad_matrix(m, n, C, ldc) || s < 1 ||
+        s > OZIMMU_MAX_SLICES)
+        return OZIMMU_BAD_ARG;
+    const Workspace w = carve(m, n, k, s);
+    if (!workspace || workspace_bytes < w.total || ((uintptr_t)workspace & 255)) return OZIMMU_BAD_ARG;
+    // exact conversion of a diagonal sum to binary64 needs s * k * 127^2 < 2^53: true for every int k
+    hipStream_t st = (hipStream_t)stream;
+    char *ws = (char *)workspace;
+    int rc = scales_into_workspace(w, ws, m, n, k, A, lda, B, ldb, false, st);
+    if (rc) return rc;
+    if (m == 0 || n == 0) return OZIMMU_OK;
+    auto *eA = (int32_t *)(ws + w.off_expA), *eB = (int32_t *)(ws + w.off_expB);
+    auto *pA = (int8_t *)(ws + w.off_planesA), *pB = (int8_t *)(ws + w.off_planesB);
+    OZ_TRY(launch_split('A', m, k, A, lda, s, eA, pA, OZIMMU_LAYOUT_MFMA, st));
+    OZ_TRY(launch_split('B', k, n, B, ldb, s, eB, pB, OZIMMU_LAYOUT_MFMA, st));
+    if (fused_applicable(s, k))
+        OZ_TRY(launch_gemm_fused(m, n, w.kp, s, pA, pB, eA, eB, C, ldc, nullptr, st));
+    else
+        OZ_TRY(launch_gemm_generic(m, n, w.kp, s, pA, pB, eA, eB, C, ldc, 0, 0, 0, w.kp / kFrag, nullptr, st));
+    return OZIMMU_OK;
+}
+
+int ozimmu_check(void *workspace, void *stream)
+{
+    if (!workspace) return OZIMMU_BAD_ARG;
+    unsigned int flag = 0;
+    hipStream_t st = (hipStream_t)stream;
+    OZ_TRY(hipMemcpyAsync(&flag, workspace, sizeof(flag), hipMemcpyDeviceToHost, st));
+    OZ_TRY(hipStreamSynchronize(st));
+    return (flag & 1u) ? OZIMMU_NONFINITE : OZIMMU_OK;
+}
+
+int ozimmu_get_exponents(int m, int n, int k, int s, const void *workspace, int32_t *eA, int32_t *eB, void *stream)
+{
+    if (m < 0 || n < 0 || k < 0 || s < 1 || s > OZIMMU_MAX_SLICES || !workspace) return OZIMMU_BAD_ARG;
+    const Workspace w = carve(m, n, k, s);
+    hipStream_t st = (hipStream_t)stream;
+    const char *ws = (const char *)workspace;
+    if (eA && m) OZ_TRY(hipMemcpyAsync(eA, ws + w.off_expA, 4 * (size_t)m, hipMemcpyDeviceToDevice, st));
+    if (eB && n) OZ_TRY(hipMemcpyAsync(eB, ws + w.off_expB, 4 * (size_t)n, hipMemcpyDeviceToDevice, st));
+    return OZIMMU_OK;
+}
+
+int ozimmu_debug_diagonals(int m, int n, int k, int s, const void *workspace, int32_t *D, void *stream)
+{
+    if (m <= 0 || n <= 0 || k < 0 || !workspace || !D || !fused_applicable(s, k)) return OZIMMU_BAD_ARG;
+    const Workspace w = carve(m, n, k, s);
+    const char *ws = (const char *)workspace;
+    OZ_TRY(launch_gemm_fused(m, n, w.kp, s, (const int8_t *)(ws + w.off_planesA), (const int8_t *)(ws + w.off_planesB),
+                             nullptr, nullptr, nullptr, m, D, (hipStream_t)stream));
+    return OZIMMU_OK;
+}
+
+int ozimmu_debug_slice_product(int m, int n, int k, int s, const void *workspace, int l, int h, int k0, int k1,
+                               int32_t *P, void *stream)
+{
+    if (m <= 0 || n <= 0 || k < 0 || s < 1 || s > OZIMMU_MAX_SLICES || !workspace || !P || l < 1 || l > s || h < 1 ||
+        h > s || k0 < 0 || k1 < k0 || k1 > k || (k0 % kFrag) != 0 || (long long)(k1 - k0) > kMaxInt32K)
+        return OZIMMU_BAD_ARG;
+    const Workspace w = carve(m, n, k, s);
+    const char *ws = (const char *)workspace;
+    // the planes are zero beyond k, so the last (partial) fragment may be read whole
+    const int kb_begin = k0 / kFrag, kb_end = (k1 + kFrag - 1) / kFrag;
+    if (k1 != k && (k1 % kFrag) != 0) return OZIMMU_BAD_ARG;
+    OZ_TRY(launch_gemm_generic(m, n, w.kp, s, (const int8_t *)(ws + w.off_planesA),
+                               (const int8_t *)(ws + w.off_planesB), nullptr, nullptr, nullptr, m, l, h, kb_begin,
+                               kb_end, P, (hipStream_t)stream));
+    return OZIMMU_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,371 @@
+// Slice-pair products on the int8 matrix cores with the binary64 accumulation fused in.
+//
+// What is computed (Algorithm 1 of Sect. 3, lines "E <- A_(l) B^(h)" and "S <- S + 2^{-(l+h)t} E",
+// in the by-diagonal order of the subsection "Accumulation in floating-point arithmetic"):
+//   D_d  = sum_{l+h=d, l,h<=s} A_(l) B^(h)          exact, int32 (k-blocked: int64)
+//   S    = ((2^{-2t} D_2 + 2^{-3t} D_3) + 2^{-4t} D_4) + ...      one binary64 rounding per "+"
+//   C_ij = 2^{eA_i + eB_j} S_ij
+//
+// Operand planes are stored as 1 KiB fragments of 32 (R) x 32 (K) int8, byte (lane*16 + b)
+// of a fragment being what lane `lane` feeds to v_mfma_i32_32x32x32_i8 (lane%32 = row or
+// column inside the fragment, lane/32 and b select the K position).  The K position -> (lane/32, b)
+// map is the same for both operands, which is all an integer dot product needs.
+//
+// The MFMA is issued "transposed": the B-plane fragment is the first operand and the A-plane
+// fragment the second, so that in the 32x32 result lane%32 runs along m.  C is column-major, so
+// each accumulator register then stores 32 consecutive doubles of a column: 256 B segments.
+#include "oz_common.h"
+
+namespace oz {
+
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));   // 16-byte copy unit
+
+constexpr int kThreads = 256;   // 4 wavefronts, 2 (m) x 2 (n)
+
+// XCD-aware tile order.  Work-groups are dealt round-robin to the 8 XCDs (id % 8), each with
+// its own L2.  Renumber so that an XCD owns a contiguous run of tiles, and walk the run in
+// groups of GM tile-rows so that tiles resident at the same time share A and B panels in L2.
+__device__ __forceinline__ void tile_of_block(int b, int nb, int tiles_m, int tiles_n, int &tm, int &tn)
+{
+    const int xcd = b & 7, idx = b >> 3;
+    const int q = nb >> 3, rem = nb & 7;
+    const int lin = xcd * q + (xcd < rem ? xcd : rem) + idx;
+    constexpr int GM = 4;
+    const int group = GM * tiles_n;
+    const int g = lin / group, in = lin - g * group;
+    const int first = g * GM;
+    const int gm = tiles_m - first < GM ? tiles_m - first : GM;
+    tm = first + in % gm;
+    tn = in / gm;
+}
+
+// =============================== fused kernel ===========================================
+// All s diagonals live in int32 accumulators for the whole contraction; needs
+// s * k * 127^2 < 2^31.  Per k-step every slice of the A tile and of the B tile is staged
+// once in LDS and feeds all s(s+1)/2 products.
+//   S     slices (compile time: the pair loop is fully unrolled)
+//   WMF   fragments (of 32 rows of A) per wavefront along m;  WNF likewise along n
+//   KB32  32-deep k-blocks per LDS stage
+//   DUMP  write the int32 diagonal sums instead of C (test hook)
+template <int S, int WMF, int WNF, int KB32, bool DUMP>
+__global__ __launch_bounds__(kThreads) void gemm_fused_kernel(const int8_t *__restrict__ pA,
+                                                              const int8_t *__restrict__ pB,
+                                                              const int32_t *__restrict__ eA,
+                                                              const int32_t *__restrict__ eB, double *__restrict__ C,
+                                                              int ldc, int m, int n, int KB, int tiles_m, int tiles_n,
+                                                              int32_t *__restrict__ dump)
+{
+    constexpr int FA = 2 * WMF, FB = 2 * WNF;          // fragments per work-group tile along m / n
+    constexpr int CHUNK = KB32 * S * kFragBytes;       // bytes of one fragment row per stage (contiguous in HBM)
+    constexpr int STAGE = (FA + FB) * CHUNK;
+    constexpr int UNITS = STAGE / 16;                  // 16-byte units per stage
+    constexpr int UPT = (UNITS + kThreads - 1) / kThreads;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+
+    int tm, tn;
+    tile_of_block(blockIdx.x, gridDim.x, tiles_m, tiles_n, tm, tn);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave & 1, wn = wave >> 1;
+
+    // per-thread copy plan: unit u = tid + i*256 -> (chunk c, offset o) ; source pointer advances by CHUNK per stage
+    const v4u *src[UPT];
+    int dsto[UPT];
+#pragma unroll
+    for (int i = 0; i < UPT; ++i) {
+        const int u = tid + i * kThreads;
+        const int c = u / (CHUNK / 16), o = u % (CHUNK / 16);
+        dsto[i] = u * 16;
+        if (u < UNITS) {
+            const int8_t *base = c < FA ? pA + ((size_t)(tm * FA + c) * KB) * (size_t)(S * kFragBytes)
+                                        : pB + ((size_t)(tn * FB + (c - FA)) * KB) * (size_t)(S * kFragBytes);
+            src[i] = (const v4u *)base + o;
+        } else {
+            src[i] = nullptr;
+        }
+    }
+
+    v16i acc[S][WMF][WNF];
+#pragma unroll
+    for (int a = 0; a < S; ++a)
+#pragma unroll
+        for (int i = 0; i < WMF; ++i)
+#pragma unroll
+            for (int j = 0; j < WNF; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[a][i][j][r] = 0;
+
+    const int nst = KB / KB32;
+    v4u stg[UPT];
+#pragma unroll
+    for (int i = 0; i < UPT; ++i)
+        if ((i + 1) * kThreads <= UNITS || tid + i * kThreads < UNITS) stg[i] = src[i][0];
+#pragma unroll
+    for (int i = 0; i < UPT; ++i)
+        if ((i + 1) * kThreads <= UNITS || tid + i * kThreads < UNITS) *(v4u *)(lds + dsto[i]) = stg[i];
+    __syncthreads();
+
+    for (int st = 0; st < nst; ++st) {
+        const unsigned char *cur = lds + (st & 1) * STAGE;
+        unsigned char *nxt = lds + ((st + 1) & 1) * STAGE;
+        const bool more = st + 1 < nst;
+        if (more) {
+#pragma unroll
+            for (int i = 0; i < UPT; ++i)
+                if ((i + 1) * kThreads <= UNITS || tid + i * kThreads < UNITS)
+                    stg[i] = src[i][(size_t)(st + 1) * (CHUNK / 16)];
+        }
+#pragma unroll
+        for (int kbl = 0; kbl < KB32; ++kbl) {
+            v4i bf[S][WNF];
+#pragma unroll
+            for (int h = 0; h < S; ++h)
+#pragma unroll
+                for (int j = 0; j < WNF; ++j)
+                    bf[h][j] = *(const v4i *)(cur + (FA + wn * WNF + j) * CHUNK + (kbl * S + h) * kFragBytes + lane * 16);
+#pragma unroll
+            for (int l = 0; l < S; ++l) {
+                v4i af[WMF];
+#pragma unroll
+                for (int i = 0; i < WMF; ++i)
+                    af[i] = *(const v4i *)(cur + (wm * WMF + i) * CHUNK + (kbl * S + l) * kFragBytes + lane * 16);
+#pragma unroll
+                for (int h = 0; h < S - l; ++h)
+#pragma unroll
+                    for (int i = 0; i < WMF; ++i)
+#pragma unroll
+                        for (int j = 0; j < WNF; ++j)
+                            acc[l + h][i][j] =
+                                __builtin_amdgcn_mfma_i32_32x32x32_i8(bf[h][j], af[i], acc[l + h][i][j], 0, 0, 0);
+            }
+        }
+        if (more) {
+#pragma unroll
+            for (int i = 0; i < UPT; ++i)
+                if ((i + 1) * kThreads <= UNITS || tid + i * kThreads < UNITS) *(v4u *)(nxt + dsto[i]) = stg[i];
+        }
+        __syncthreads();
+    }
+
+    // epilogue: accumulator register r of lane holds  (n_local, m_local) = (8*(r/4) + 4*(lane/32) + r%4, lane%32)
+    const int m0 = tm * FA * 32 + wm * WMF * 32, n0 = tn * FB * 32 + wn * WNF * 32;
+#pragma unroll
+    for (int i = 0; i < WMF; ++i) {
+        const int mi = m0 + i * 32 + (lane & 31);
+        if (mi >= m) continue;
+        const int ea = DUMP ? 0 : eA[mi];
+#pragma unroll
+        for (int j = 0; j < WNF; ++j) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int nj = n0 + j * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                if (nj >= n) continue;
+                if (DUMP) {
+#pragma unroll
+                    for (int a = 0; a < S; ++a) dump[(size_t)a * m * n + mi + (size_t)nj * m] = acc[a][i][j][r];
+                } else {
+                    double sum = 0.0;
+#pragma unroll
+                    for (int a = 0; a < S; ++a)
+                        sum = sum + (double)acc[a][i][j][r] * __builtin_ldexp(1.0, -kSliceBits * (a + 2));
+                    C[mi + (size_t)nj * ldc] = ldexp(sum, ea + eB[nj]);
+                }
+            }
+        }
+    }
+}
+
+// =============================== generic kernel =========================================
+// Any s and any k: one slice pair at a time.  Each pair's product is accumulated in int32 over
+// k-blocks short enough not to overflow, k-block results are added exactly into an int64
+// diagonal sum, and after the last pair of a diagonal the sum is converted (exactly, since
+// s * k * 127^2 < 2^53) and added to S in binary64.  Work-group tile 128 (m) x 64 (n).
+// With dump != null it instead writes the int32 product of the single pair (pair_l, pair_h)
+// over k-blocks [kb_begin, kb_end).
+__global__ __launch_bounds__(kThreads) void gemm_generic_kernel(const int8_t *__restrict__ pA,
+                                                                const int8_t *__restrict__ pB,
+                                                                const int32_t *__restrict__ eA,
+                                                                const int32_t *__restrict__ eB,
+                                                                double *__restrict__ C, int ldc, int m, int n, int s,
+                                                                int KB, int tiles_m, int tiles_n, int kblk32,
+                                                                int pair_l, int pair_h, int kb_begin, int kb_end,
+                                                                int32_t *__restrict__ dump)
+{
+    constexpr int WMF = 2, FA = 4, FB = 2, KB32 = 4;
+    __shared__ __attribute__((aligned(16))) unsigned char lds[(FA + FB) * KB32 * kFragBytes];
+    int tm, tn;
+    tile_of_block(blockIdx.x, gridDim.x, tiles_m, tiles_n, tm, tn);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave & 1, wn = wave >> 1;
+
+    double sum[WMF][16];
+#pragma unroll
+    for (int i = 0; i < WMF; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sum[i][r] = 0.0;
+
+    const int d_lo = dump ? pair_l + pair_h : 2, d_hi = dump ? pair_l + pair_h : s + 1;
+    for (int d = d_lo; d <= d_hi; ++d) {
+        long long D[WMF][16];
+#pragma unroll
+        for (int i = 0; i < WMF; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) D[i][r] = 0;
+        int l_lo = d - s > 1 ? d - s : 1, l_hi = d - 1 < s ? d - 1 : s;
+        if (dump) l_lo = l_hi = pair_l;
+        for (int l = l_lo; l <= l_hi; ++l) {
+            const int h = d - l;
+            for (int kb0 = kb_begin; kb0 < kb_end; kb0 += kblk32) {
+                const int kb1 = kb0 + kblk32 < kb_end ? kb0 + kblk32 : kb_end;
+                v16i acc[WMF];
+#pragma unroll
+                for (int i = 0; i < WMF; ++i)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[i][r] = 0;
+                for (int kb = kb0; kb < kb1; kb += KB32) {
+                    // stage: (FA + FB) fragment rows x KB32 k-blocks of this pair's two slices
+                    // 6 * 4 * 64 = 1536 units of 16 B: 6 per thread
+#pragma unroll
+                    for (int i = 0; i < (FA + FB) * KB32 * 64 / kThreads; ++i) {
+                        const int u = tid + i * kThreads;
+                        const int c = u / (KB32 * 64), rest = u % (KB32 * 64);
+                        const int kbl = rest / 64, o = rest % 64;
+                        v4u v = {0u, 0u, 0u, 0u};
+                        if (kb + kbl < kb1) {
+                            const int8_t *base =
+                                c < FA ? pA + (((size_t)(tm * FA + c) * KB + kb + kbl) * s + (l - 1)) * kFragBytes
+                                       : pB + (((size_t)(tn * FB + c - FA) * KB + kb + kbl) * s + (h - 1)) * kFragBytes;
+                            v = ((const v4u *)base)[o];
+                        }
+                        *(v4u *)(lds + u * 16) = v;
+                    }
+                    __syncthreads();
+#pragma unroll
+                    for (int kbl = 0; kbl < KB32; ++kbl) {
+                        const v4i bf = *(const v4i *)(lds + ((FA + wn) * KB32 + kbl) * kFragBytes + lane * 16);
+#pragma unroll
+                        for (int i = 0; i < WMF; ++i) {
+                            const v4i af = *(const v4i *)(lds + ((wm * WMF + i) * KB32 + kbl) * kFragBytes + lane * 16);
+                            acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bf, af, acc[i], 0, 0, 0);
+                        }
+                    }
+                    __syncthreads();
+                }
+#pragma unroll
+                for (int i = 0; i < WMF; ++i)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) D[i][r] += (long long)acc[i][r];
+            }
+        }
+        if (!dump) {
+#pragma unroll
+            for (int i = 0; i < WMF; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) sum[i][r] = sum[i][r] + ldexp((double)D[i][r], -kSliceBits * d);
+        } else {
+            const int m0 = tm * FA * 32 + wm * WMF * 32, n0 = tn * FB * 32 + wn * 32;
+#pragma unroll
+            for (int i = 0; i < WMF; ++i) {
+                const int mi = m0 + i * 32 + (lane & 31);
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int nj = n0 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                    if (mi < m && nj < n) dump[mi + (size_t)nj * m] = (int32_t)D[i][r];
+                }
+            }
+        }
+    }
+    if (dump) return;
+    const int m0 = tm * FA * 32 + wm * WMF * 32, n0 = tn * FB * 32 + wn * 32;
+#pragma unroll
+    for (int i = 0; i < WMF; ++i) {
+        const int mi = m0 + i * 32 + (lane & 31);
+        if (mi >= m) continue;
+        const int ea = eA[mi];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int nj = n0 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+            if (nj < n) C[mi + (size_t)nj * ldc] = ldexp(sum[i][r], ea + eB[nj]);
+        }
+    }
+}
+
+// ------------------------------- launch tables --------------------------------------------
+template <int S>
+struct FusedCfg {
+    // k-blocks of 32 per LDS stage: deeper stages for few slices (fewer barriers per MFMA)
+    static constexpr int KB32 = S <= 2 ? 4 : (S <= 6 ? 2 : 1);
+    static constexpr int WMF = 2, WNF = 1;
+};
+
+constexpr int kFusedMaxS = 9;   // s = 10 no longer fits 512 registers per lane without spilling
+
+template <int S, bool DUMP>
+hipError_t launch_fused_s(int m, int n, int kp, const int8_t *pA, const int8_t *pB, const int32_t *eA,
+                          const int32_t *eB, double *C, int ldc, int32_t *dump, hipStream_t st)
+{
+    using Cfg = FusedCfg<S>;
+    constexpr int TM = 64 * Cfg::WMF, TN = 64 * Cfg::WNF;
+    constexpr int STAGE = (2 * Cfg::WMF + 2 * Cfg::WNF) * Cfg::KB32 * S * kFragBytes;
+    auto kern = gemm_fused_kernel<S, Cfg::WMF, Cfg::WNF, Cfg::KB32, DUMP>;
+    static bool configured = false;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * STAGE);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    const int tiles_m = (m + TM - 1) / TM, tiles_n = (n + TN - 1) / TN;
+    kern<<<tiles_m * tiles_n, kThreads, 2 * STAGE, st>>>(pA, pB, eA, eB, C, ldc, m, n, kp / kFrag, tiles_m, tiles_n,
+                                                         dump);
+    return hipGetLastError();
+}
+
+template <bool DUMP>
+hipError_t dispatch_fused(int s, int m, int n, int kp, const int8_t *pA, const int8_t *pB, const int32_t *eA,
+                          const int32_t *eB, double *C, int ldc, int32_t *dump, hipStream_t st)
+{
+    switch (s) {
+#define OZ_CASE(S_) \
+    case S_: return launch_fused_s<S_, DUMP>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, st);
+        OZ_CASE(1) OZ_CASE(2) OZ_CASE(3) OZ_CASE(4) OZ_CASE(5) OZ_CASE(6) OZ_CASE(7) OZ_CASE(8) OZ_CASE(9)
+#undef OZ_CASE
+    }
+    return hipErrorInvalidValue;
+}
+
+}  // namespace
+
+int fused_max_slices() { return kFusedMaxS; }
+
+bool fused_applicable(int s, int k)
+{
+    // the longest diagonal has s products of k terms each, every term at most 127^2 in magnitude
+    return s >= 1 && s <= kFusedMaxS && (long long)s * (long long)(k > 0 ? k : 1) <= kMaxInt32K;
+}
+
+hipError_t launch_gemm_fused(int m, int n, int kp, int s, const int8_t *pA, const int8_t *pB, const int32_t *eA,
+                             const int32_t *eB, double *C, int ldc, int32_t *dump, hipStream_t st)
+{
+    if (m <= 0 || n <= 0) return hipSuccess;
+    return dump ? dispatch_fused<true>(s, m, n, kp, pA, pB, eA, eB, C, ldc, dump, st)
+                : dispatch_fused<false>(s, m, n, kp, pA, pB, eA, eB, C, ldc, dump, st);
+}
+
+hipError_t launch_gemm_generic(int m, int n, int kp, int s, const int8_t *pA, const int8_t *pB, const int32_t *eA,
+                               const int32_t *eB, double *C, int ldc, int pair_l, int pair_h, int kb_begin,
+                               int kb_end, int32_t *dump, hipStream_t st)
+{
+    if (m <= 0 || n <= 0) return hipSuccess;
+    const int tiles_m = (m + 127) / 128, tiles_n = (n + 63) / 64;
+    // int32-safe k-block for one pair: kblk * 127^2 < 2^31, rounded down to a whole number of stages
+    const int kblk32 = (int)(kMaxInt32K / kFrag) / 4 * 4;
+    gemm_generic_kernel<<<tiles_m * tiles_n, kThreads, 0, st>>>(pA, pB, eA, eB, C, ldc, m, n, s, kp / kFrag, tiles_m,
+                                                                tiles_n, kblk32, pair_l, pair_h, kb_begin, kb_end,
+                                                                dump);
+    return hipGetLastError();
+}
+
+}  // namespace oz

@@ -1,0 +1,85 @@
+// Internal declarations shared by the HIP translation units of libozimmu.
+// (Nothing here is used by, or shared with, the CPU oracle.)
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/ozimmu.h"
+
+namespace oz {
+
+constexpr int kSliceBits = OZIMMU_SLICE_BITS;   // t = 7: INT8 = I_7 in the paper's notation
+constexpr int kFrag = 32;                       // fragment edge: 32 (R) x 32 (K) int8 = 1 KiB
+constexpr int kFragBytes = 1024;
+constexpr int kPad = 128;                       // R and K are zero-padded to multiples of this
+// largest contraction length whose int8 x int8 products sum without int32 overflow:
+// k * 127^2 <= 2^31 - 1  (accumulator-width discussion of Sect. 3, with the true constant)
+constexpr long long kMaxInt32K = 2147483647LL / (127LL * 127LL);   // 133144
+
+inline int round_up(int x, int q) { return (x + q - 1) / q * q; }
+
+// Workspace carve-up (all offsets multiples of 256 bytes).
+struct Workspace {
+    int mp, np, kp;                 // padded extents
+    size_t off_header;              // 256 B: [0] u32 non-finite flag, [8] u64 kappa_A bits, [16] u64 kappa_B bits
+    size_t off_maxA, off_minA;      // u64[mp]: integer view of max |a_ij| / min nonzero |a_ij| per row
+    size_t off_maxB, off_minB;      // u64[np]
+    size_t off_expA, off_expB;      // i32[mp], i32[np]
+    size_t off_planesA, off_planesB;
+    size_t total;
+};
+
+inline Workspace carve(int m, int n, int k, int s)
+{
+    Workspace w;
+    w.mp = round_up(m > 0 ? m : 1, kPad);
+    w.np = round_up(n > 0 ? n : 1, kPad);
+    w.kp = round_up(k > 0 ? k : 1, kPad);
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += (bytes + 255) / 256 * 256; return o; };
+    w.off_header = take(256);
+    w.off_maxA = take(8 * (size_t)w.mp);
+    w.off_minA = take(8 * (size_t)w.mp);
+    w.off_maxB = take(8 * (size_t)w.np);
+    w.off_minB = take(8 * (size_t)w.np);
+    w.off_expA = take(4 * (size_t)w.mp);
+    w.off_expB = take(4 * (size_t)w.np);
+    w.off_planesA = take((size_t)s * w.mp * w.kp);
+    w.off_planesB = take((size_t)s * w.np * w.kp);
+    w.total = off;
+    return w;
+}
+
+// ---- launchers implemented in reduce.hip -------------------------------------------------
+// side 'A': per-row reduction of a rows x cols matrix; side 'B': per-column.
+// maxbits/minbits: u64 per block (bit pattern of max |x| and of the smallest nonzero |x|;
+// minbits may be null).  flags: u32, bit 0 set when a NaN/Inf is met.
+hipError_t launch_reduce(char side, int rows, int cols, const double *X, int ldx,
+                         unsigned long long *maxbits, unsigned long long *minbits,
+                         unsigned int *flags, hipStream_t st);
+// exps[b] from maxbits[b]; entries b in [nblk, nblk_padded) get 0.  If kappa_bits is non-null
+// (needs minbits) also folds 2*max/min into *kappa_bits with an integer atomic max.
+hipError_t launch_finalize(const unsigned long long *maxbits, const unsigned long long *minbits,
+                           int32_t *exps, int nblk, int nblk_padded, unsigned long long *kappa_bits,
+                           hipStream_t st);
+hipError_t launch_clear_header(void *header, hipStream_t st);
+
+// ---- launchers implemented in split.hip --------------------------------------------------
+hipError_t launch_split(char side, int rows, int cols, const double *X, int ldx, int s,
+                        const int32_t *exps, int8_t *planes, int layout, hipStream_t st);
+
+// ---- launchers implemented in gemm.hip ---------------------------------------------------
+// largest s the fused (all diagonals in registers) kernel handles
+int fused_max_slices();
+// true when the fused kernel can run this problem without int32 overflow
+bool fused_applicable(int s, int k);
+hipError_t launch_gemm_fused(int m, int n, int kp, int s, const int8_t *pA, const int8_t *pB,
+                             const int32_t *eA, const int32_t *eB, double *C, int ldc,
+                             int32_t *dump, hipStream_t st);
+hipError_t launch_gemm_generic(int m, int n, int kp, int s, const int8_t *pA, const int8_t *pB,
+                               const int32_t *eA, const int32_t *eB, double *C, int ldc,
+                               int pair_l, int pair_h, int kb_begin, int kb_end, int32_t *dump,
+                               hipStream_t st);
+
+}  // namespace oz

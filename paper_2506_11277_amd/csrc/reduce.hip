@@ -1,0 +1,193 @@
+// Scale extraction: per-row (A) and per-column (B) reduction of |x| on the bit patterns.
+//
+// For finite non-negative binary64 values the order of the values is the order of their bit
+// patterns read as unsigned integers, so max |x| and the smallest nonzero |x| are integer
+// max/min reductions: exact and independent of the reduction order (Sect. 3, eq. (alpha-def),
+// (beta-def); the minimum feeds kappa of eq. (a-bound-row-2), (b-bound) in Sect. 4).
+#include "oz_common.h"
+
+namespace oz {
+
+namespace {
+
+constexpr unsigned long long kAbsMask = 0x7fffffffffffffffULL;
+constexpr unsigned long long kExpMask = 0x7ff0000000000000ULL;
+constexpr unsigned long long kNoMin = 0xffffffffffffffffULL;
+
+struct Acc {
+    unsigned long long mx, mn;
+    unsigned int bad;
+};
+
+__device__ __forceinline__ void fold(Acc &a, unsigned long long bits)
+{
+    unsigned long long v = bits & kAbsMask;
+    a.mx = v > a.mx ? v : a.mx;
+    unsigned long long w = v ? v : kNoMin;
+    a.mn = w < a.mn ? w : a.mn;
+    a.bad |= (v & kExpMask) == kExpMask;
+}
+
+// ---- side 'B': one work-group per column, wavefront-shuffle tree, then 4 partials via LDS ----
+__global__ __launch_bounds__(256) void colreduce_kernel(const unsigned long long *__restrict__ X, int ldx, int rows,
+                                                        unsigned long long *__restrict__ maxbits,
+                                                        unsigned long long *__restrict__ minbits,
+                                                        unsigned int *__restrict__ flags)
+{
+    const int j = blockIdx.x;
+    const unsigned long long *col = X + (size_t)j * ldx;
+    Acc a{0ULL, kNoMin, 0u};
+    int r = threadIdx.x;
+    // 4 independent loads in flight per lane
+    for (; r + 768 < rows; r += 1024) {
+        unsigned long long v0 = col[r], v1 = col[r + 256], v2 = col[r + 512], v3 = col[r + 768];
+        fold(a, v0); fold(a, v1); fold(a, v2); fold(a, v3);
+    }
+    for (; r < rows; r += 256) fold(a, col[r]);
+
+    for (int off = 32; off > 0; off >>= 1) {
+        unsigned long long omx = __shfl_xor(a.mx, off);
+        unsigned long long omn = __shfl_xor(a.mn, off);
+        unsigned int ob = __shfl_xor(a.bad, off);
+        a.mx = omx > a.mx ? omx : a.mx;
+        a.mn = omn < a.mn ? omn : a.mn;
+        a.bad |= ob;
+    }
+    __shared__ unsigned long long smx[4], smn[4];
+    __shared__ unsigned int sbad[4];
+    const int w = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) { smx[w] = a.mx; smn[w] = a.mn; sbad[w] = a.bad; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        unsigned long long mx = smx[0], mn = smn[0];
+        unsigned int bad = sbad[0];
+        for (int i = 1; i < 4; ++i) {
+            mx = smx[i] > mx ? smx[i] : mx;
+            mn = smn[i] < mn ? smn[i] : mn;
+            bad |= sbad[i];
+        }
+        maxbits[j] = mx;
+        if (minbits) minbits[j] = mn;
+        if (bad) atomicOr(flags, 1u);
+    }
+}
+
+// ---- side 'A': lane <-> row (coalesced along the column-major rows), 4 wavefronts split a
+//      chunk of columns, partials meet in LDS, one integer atomic per row and work-group ----
+constexpr int kRowChunk = 256;   // columns per work-group
+
+__global__ __launch_bounds__(256) void rowreduce_kernel(const unsigned long long *__restrict__ X, int ldx, int rows,
+                                                        int cols, unsigned long long *__restrict__ maxbits,
+                                                        unsigned long long *__restrict__ minbits,
+                                                        unsigned int *__restrict__ flags)
+{
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int r = blockIdx.x * 64 + lane;
+    const int c0 = blockIdx.y * kRowChunk + w * (kRowChunk / 4);
+    int c1 = c0 + kRowChunk / 4;
+    c1 = c1 < cols ? c1 : cols;
+    Acc a{0ULL, kNoMin, 0u};
+    if (r < rows) {
+        const unsigned long long *p = X + r;
+        int c = c0;
+        for (; c + 7 < c1; c += 8) {
+            unsigned long long v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = p[(size_t)(c + u) * ldx];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) fold(a, v[u]);
+        }
+        for (; c < c1; ++c) fold(a, p[(size_t)c * ldx]);
+    }
+    __shared__ unsigned long long smx[4][64], smn[4][64];
+    __shared__ unsigned int sbad[4][64];
+    smx[w][lane] = a.mx; smn[w][lane] = a.mn; sbad[w][lane] = a.bad;
+    __syncthreads();
+    if (w == 0 && r < rows) {
+        unsigned long long mx = smx[0][lane], mn = smn[0][lane];
+        unsigned int bad = sbad[0][lane];
+        for (int i = 1; i < 4; ++i) {
+            mx = smx[i][lane] > mx ? smx[i][lane] : mx;
+            mn = smn[i][lane] < mn ? smn[i][lane] : mn;
+            bad |= sbad[i][lane];
+        }
+        if (mx) atomicMax(&maxbits[r], mx);
+        if (minbits && mn != kNoMin) atomicMin(&minbits[r], mn);
+        if (bad) atomicOr(flags, 1u);
+    }
+}
+
+__global__ void fill_u64_kernel(unsigned long long *p, unsigned long long v, int n)
+{
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+__global__ void clear_header_kernel(unsigned long long *hdr)
+{
+    if (threadIdx.x < 32) hdr[threadIdx.x] = 0ULL;
+}
+
+// e = floor(log2 M) + 1 from the bit pattern of M >= 0 (eq. (alpha-def)); the exponent-field
+// shortcut described after eq. (beta-def) for normal numbers, leading-zero count for
+// subnormal ones, 0 for M = 0.
+__device__ __forceinline__ int exponent_above(unsigned long long bits)
+{
+    if (bits == 0) return 0;
+    int E = (int)(bits >> 52);
+    if (E) return E - 1022;
+    return (64 - __clzll((long long)bits)) - 1074;
+}
+
+__global__ void finalize_kernel(const unsigned long long *__restrict__ maxbits,
+                                const unsigned long long *__restrict__ minbits, int32_t *__restrict__ exps,
+                                int nblk, int nblk_padded, unsigned long long *kappa_bits)
+{
+    int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= nblk_padded) return;
+    if (b >= nblk) { exps[b] = 0; return; }
+    unsigned long long mx = maxbits[b];
+    exps[b] = exponent_above(mx);
+    if (kappa_bits && mx) {
+        double ratio = __longlong_as_double((long long)mx) / __longlong_as_double((long long)minbits[b]);
+        atomicMax(kappa_bits, (unsigned long long)__double_as_longlong(ratio));
+    }
+}
+
+}  // namespace
+
+hipError_t launch_clear_header(void *header, hipStream_t st)
+{
+    clear_header_kernel<<<1, 64, 0, st>>>((unsigned long long *)header);
+    return hipGetLastError();
+}
+
+hipError_t launch_reduce(char side, int rows, int cols, const double *X, int ldx, unsigned long long *maxbits,
+                         unsigned long long *minbits, unsigned int *flags, hipStream_t st)
+{
+    const int nblk = side == 'A' ? rows : cols;
+    if (nblk <= 0) return hipSuccess;
+    if (side == 'A') {
+        fill_u64_kernel<<<(nblk + 255) / 256, 256, 0, st>>>(maxbits, 0ULL, nblk);
+        if (minbits) fill_u64_kernel<<<(nblk + 255) / 256, 256, 0, st>>>(minbits, kNoMin, nblk);
+        if (cols > 0) {
+            dim3 grid((rows + 63) / 64, (cols + kRowChunk - 1) / kRowChunk);
+            if (grid.y > 65535) return hipErrorInvalidValue;
+            rowreduce_kernel<<<grid, 256, 0, st>>>((const unsigned long long *)X, ldx, rows, cols, maxbits, minbits,
+                                                   flags);
+        }
+    } else {
+        colreduce_kernel<<<cols, 256, 0, st>>>((const unsigned long long *)X, ldx, rows, maxbits, minbits, flags);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_finalize(const unsigned long long *maxbits, const unsigned long long *minbits, int32_t *exps,
+                           int nblk, int nblk_padded, unsigned long long *kappa_bits, hipStream_t st)
+{
+    if (nblk_padded <= 0) return hipSuccess;
+    finalize_kernel<<<(nblk_padded + 255) / 256, 256, 0, st>>>(maxbits, minbits, exps, nblk, nblk_padded, kappa_bits);
+    return hipGetLastError();
+}
+
+}  // namespace oz

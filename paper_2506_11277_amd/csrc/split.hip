@@ -1,0 +1,173 @@
+// Bit-splitting of a binary64 matrix into s signed 7-bit slices (Sect. 3, eq.
+// (bit-splitting-alg) in its bit-level reading: slice l holds bits (l-1)t+1 .. lt of
+// |x| / 2^e after the binary point, and carries the sign of x).
+//
+// |x| = I * 2^q with I the integer significand, so  floor(|x| 2^{lt - e}) mod 2^t  is a
+// shift of I by (e - q - lt) places and a mask: integer work only, exact.
+//
+// The MFMA layout written here is the one the GEMM kernel reads (see include/ozimmu.h):
+// fragments of 32 (R) x 32 (K) bytes, 16 contiguous K-bytes per wavefront lane.
+#include "oz_common.h"
+
+namespace oz {
+
+namespace {
+
+struct Elem {
+    unsigned long long I;   // integer significand
+    int base;               // e - q : right shift that would bring bit position 0 (the binary point) to bit 0
+    int neg;
+};
+
+__device__ __forceinline__ Elem decompose(unsigned long long bits, int e)
+{
+    Elem el;
+    const int E = (int)((bits >> 52) & 0x7ff);
+    const unsigned long long f = bits & 0xfffffffffffffULL;
+    el.I = E ? (f | (1ULL << 52)) : f;
+    el.base = e - ((E ? E : 1) - 1075);
+    el.neg = (int)(bits >> 63);
+    return el;
+}
+
+// slice l (1-based), as an unsigned byte holding the two's complement int8
+__device__ __forceinline__ unsigned int slice_byte(const Elem &el, int l)
+{
+    const int sh = el.base - kSliceBits * l;
+    unsigned long long v;
+    if (sh >= 64) v = 0;
+    else if (sh >= 0) v = el.I >> sh;
+    else if (sh <= -kSliceBits) v = 0;
+    else v = el.I << (-sh);
+    int d = (int)(v & 127ULL);
+    d = el.neg ? -d : d;
+    return (unsigned int)d & 0xffu;
+}
+
+// ---- side 'A': X is R x K column-major (R contiguous).  lane <-> row, each lane walks 16
+//      consecutive k, so the 16 K-bytes of a lane come out of registers: the transposition to
+//      K-contiguous fragments costs nothing, reads are 512 B per wavefront load, writes are
+//      512 B contiguous per half wavefront.
+__global__ __launch_bounds__(256) void split_rows_kernel(const unsigned long long *__restrict__ X, int ldx, int R,
+                                                         int K, int s, const int32_t *__restrict__ exps,
+                                                         int8_t *__restrict__ planes, int KB)
+{
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int r = blockIdx.x * 64 + lane;
+    const int k0 = blockIdx.y * 64 + w * 16;
+    const int e = r < R ? exps[r] : 0;
+    Elem el[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int kk = k0 + i;
+        unsigned long long bits = (r < R && kk < K) ? X[r + (size_t)kk * ldx] : 0ULL;
+        el[i] = decompose(bits, e);
+    }
+    const int rb = r >> 5, kb = k0 >> 5, half = (k0 >> 4) & 1;
+    uint4 *dst = (uint4 *)(planes + ((size_t)rb * KB + kb) * (size_t)s * kFragBytes) + ((r & 31) + 32 * half);
+    for (int l = 1; l <= s; ++l) {
+        unsigned int wd[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            wd[q] = slice_byte(el[4 * q], l) | (slice_byte(el[4 * q + 1], l) << 8) |
+                    (slice_byte(el[4 * q + 2], l) << 16) | (slice_byte(el[4 * q + 3], l) << 24);
+        dst[(size_t)(l - 1) * (kFragBytes / 16)] = make_uint4(wd[0], wd[1], wd[2], wd[3]);
+    }
+}
+
+// ---- side 'B': X is K x R column-major (K contiguous).  A work-group takes 32 columns x 128 k;
+//      lanes read along k (coalesced), slice bytes are packed four k at a time into LDS rows,
+//      then re-read so that lane <-> column and a wavefront emits whole 1 KiB fragments.
+constexpr int kColTileK = 128;
+constexpr int kColLdsRow = kColTileK + 16;   // bytes per (slice, column) row in LDS
+constexpr int kColGroup = 8;                 // slices per LDS pass
+
+__global__ __launch_bounds__(256) void split_cols_kernel(const unsigned long long *__restrict__ X, int ldx, int R,
+                                                         int K, int s, const int32_t *__restrict__ exps,
+                                                         int8_t *__restrict__ planes, int KB)
+{
+    __shared__ __attribute__((aligned(16))) unsigned char lds[kColGroup * 32 * kColLdsRow];
+    const int t = threadIdx.x;
+    const int j0 = blockIdx.x * 32, k0 = blockIdx.y * kColTileK;
+    const int kq = (t & 31) * 4;
+    Elem el[4][4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const int jj = p * 8 + (t >> 5);
+        const int j = j0 + jj;
+        const int e = j < R ? exps[j] : 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int kk = k0 + kq + i;
+            unsigned long long bits = (j < R && kk < K) ? X[kk + (size_t)j * ldx] : 0ULL;
+            el[p][i] = decompose(bits, e);
+        }
+    }
+    const int jj2 = t & 31, ch = t >> 5;                    // phase 2: column, 16-byte chunk along k
+    const int rb = j0 >> 5;
+    const int kb = (k0 + ch * 16) >> 5, half = ch & 1;
+    uint4 *dst = (uint4 *)(planes + ((size_t)rb * KB + kb) * (size_t)s * kFragBytes) + (jj2 + 32 * half);
+    for (int l0 = 1; l0 <= s; l0 += kColGroup) {
+        const int nl = (s - l0 + 1) < kColGroup ? (s - l0 + 1) : kColGroup;
+        for (int dl = 0; dl < nl; ++dl) {
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                const int jj = p * 8 + (t >> 5);
+                unsigned int wd = slice_byte(el[p][0], l0 + dl) | (slice_byte(el[p][1], l0 + dl) << 8) |
+                                  (slice_byte(el[p][2], l0 + dl) << 16) | (slice_byte(el[p][3], l0 + dl) << 24);
+                *(unsigned int *)(lds + ((size_t)dl * 32 + jj) * kColLdsRow + kq) = wd;
+            }
+        }
+        __syncthreads();
+        for (int dl = 0; dl < nl; ++dl) {
+            uint4 v = *(const uint4 *)(lds + ((size_t)dl * 32 + jj2) * kColLdsRow + ch * 16);
+            dst[(size_t)(l0 + dl - 1) * (kFragBytes / 16)] = v;
+        }
+        __syncthreads();
+    }
+}
+
+// ---- plain layout: plane l is a matrix shaped like X (utility / test path) ----
+__global__ __launch_bounds__(256) void split_plain_kernel(const unsigned long long *__restrict__ X, int ldx, int rows,
+                                                          int cols, int s, const int32_t *__restrict__ exps,
+                                                          int by_row, int8_t *__restrict__ planes)
+{
+    const int r = blockIdx.x * 256 + threadIdx.x;
+    if (r >= rows) return;
+    const size_t plane = (size_t)rows * cols;
+    for (int c = blockIdx.y; c < cols; c += gridDim.y) {
+        const int e = by_row ? exps[r] : exps[c];
+        const Elem el = decompose(X[r + (size_t)c * ldx], e);
+        for (int l = 1; l <= s; ++l)
+            planes[(size_t)(l - 1) * plane + r + (size_t)c * rows] = (int8_t)slice_byte(el, l);
+    }
+}
+
+}  // namespace
+
+hipError_t launch_split(char side, int rows, int cols, const double *X, int ldx, int s, const int32_t *exps,
+                        int8_t *planes, int layout, hipStream_t st)
+{
+    if (layout == OZIMMU_LAYOUT_PLAIN) {
+        if (rows <= 0 || cols <= 0) return hipSuccess;
+        dim3 grid((rows + 255) / 256, cols < 65535 ? cols : 65535);
+        split_plain_kernel<<<grid, 256, 0, st>>>((const unsigned long long *)X, ldx, rows, cols, s, exps,
+                                                 side == 'A' ? 1 : 0, planes);
+        return hipGetLastError();
+    }
+    const int R = side == 'A' ? rows : cols, K = side == 'A' ? cols : rows;
+    const int Rp = round_up(R > 0 ? R : 1, kPad), Kp = round_up(K > 0 ? K : 1, kPad);
+    const int KB = Kp / kFrag;
+    if (side == 'A') {
+        dim3 grid(Rp / 64, Kp / 64);
+        if (grid.y > 65535) return hipErrorInvalidValue;
+        split_rows_kernel<<<grid, 256, 0, st>>>((const unsigned long long *)X, ldx, R, K, s, exps, planes, KB);
+    } else {
+        dim3 grid(Rp / 32, Kp / kColTileK);
+        if (grid.y > 65535) return hipErrorInvalidValue;
+        split_cols_kernel<<<grid, 256, 0, st>>>((const unsigned long long *)X, ldx, R, K, s, exps, planes, KB);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace oz

@@ -1,0 +1,80 @@
+"""CPU-side checks of the C-ABI boundary: the library builds/loads and exports every symbol the
+public header declares; argument validation that needs no GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "ozimmu.h")
+
+
+@pytest.fixture(scope="module")
+def handle():
+    from paper_2506_11277_amd import ozimmu
+    if not os.path.exists(ozimmu.LIB_PATH):
+        from paper_2506_11277_amd import build
+        build.build_lib()
+    return ozimmu.lib()
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ozimmu_\w+)\s*\(", text)))
+
+
+def test_header_declares_the_three_named_entry_points():
+    names = declared_functions()
+    for required in ("ozimmu_estimate_slices", "ozimmu_split", "ozimmu_dgemm"):
+        assert required in names
+
+
+def test_library_exports_every_declared_symbol(handle):
+    raw = ctypes.CDLL(handle._name)
+    for name in declared_functions():
+        assert hasattr(raw, name), name
+
+
+def test_binding_covers_every_declared_symbol():
+    from paper_2506_11277_amd import ozimmu
+    assert sorted(ozimmu._SIGNATURES) == declared_functions()
+
+
+def test_status_strings(handle):
+    assert handle.ozimmu_status_string(0) == b"ok"
+    assert handle.ozimmu_status_string(2) == b"non-finite input"
+    assert handle.ozimmu_status_string(99) == b"unknown status"
+
+
+def test_size_queries_and_argument_validation_without_gpu(handle):
+    # workspace grows with s and covers the padded planes
+    w3 = handle.ozimmu_workspace_bytes(128, 128, 128, 3)
+    w4 = handle.ozimmu_workspace_bytes(128, 128, 128, 4)
+    assert w4 - w3 == 2 * 128 * 128
+    assert handle.ozimmu_workspace_bytes(100, 90, 70, 2) == handle.ozimmu_workspace_bytes(128, 128, 128, 2)
+    assert handle.ozimmu_workspace_bytes(8192, 8192, 8192, 7) >= 2 * 7 * 8192 * 8192
+    assert handle.ozimmu_workspace_bytes(-1, 1, 1, 1) == 0
+    assert handle.ozimmu_workspace_bytes(1, 1, 1, 0) == 0
+    assert handle.ozimmu_workspace_bytes(1, 1, 1, 33) == 0
+    assert handle.ozimmu_planes_bytes(b"A", 100, 200, 3, 0) == 3 * 100 * 200
+    assert handle.ozimmu_planes_bytes(b"A", 100, 200, 3, 1) == 3 * 128 * 256
+    assert handle.ozimmu_planes_bytes(b"B", 100, 200, 3, 1) == 3 * 256 * 128
+    assert handle.ozimmu_planes_bytes(b"C", 100, 200, 3, 1) == 0
+    # invalid arguments are rejected before any HIP call is made
+    ws = ctypes.c_void_p(256)
+    fake = ctypes.c_void_p(4096)
+    assert handle.ozimmu_dgemm(4, 4, 4, fake, 3, fake, 4, fake, 4, 2, ws, 1 << 30, None) == 1      # lda < m
+    assert handle.ozimmu_dgemm(4, 4, 4, fake, 4, fake, 4, fake, 4, 0, ws, 1 << 30, None) == 1      # s < 1
+    assert handle.ozimmu_dgemm(4, 4, 4, fake, 4, fake, 4, fake, 4, 33, ws, 1 << 30, None) == 1     # s > max
+    assert handle.ozimmu_dgemm(4, 4, 4, None, 4, fake, 4, fake, 4, 2, ws, 1 << 30, None) == 1      # null A
+    assert handle.ozimmu_dgemm(4, 4, 4, fake, 4, fake, 4, fake, 4, 2, ws, 16, None) == 1           # workspace too small
+    assert handle.ozimmu_dgemm(4, 4, 4, fake, 4, fake, 4, fake, 4, 2, ctypes.c_void_p(264), 1 << 30, None) == 1
+    assert handle.ozimmu_dgemm(-1, 4, 4, fake, 4, fake, 4, fake, 4, 2, ws, 1 << 30, None) == 1
+    s = ctypes.c_int(0)
+    assert handle.ozimmu_estimate_slices(4, 4, 4, fake, 4, fake, 4, 0.0, ctypes.byref(s), None, ws, 1 << 30, None) == 1
+    assert handle.ozimmu_estimate_slices(4, 4, 4, fake, 4, fake, 4, float("nan"), ctypes.byref(s), None, ws, 1 << 30,
+                                         None) == 1
+    assert handle.ozimmu_split(b"X", 4, 4, fake, 4, 2, fake, fake, 0, ws, None) == 1
+    assert handle.ozimmu_split(b"A", 4, 4, fake, 4, 2, fake, fake, 7, ws, None) == 1

@@ -1,0 +1,285 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element, on
+the same seeded inputs.  Integer stages (exponents, slices, slice products, diagonal sums) must
+agree bit for bit; C must agree to 1e-15 relative (the stated bar) and is also required to be
+bit-identical (the goal: the only roundings are the ordered binary64 additions, replicated)."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+from oracle import oracle
+from paper_2506_11277_amd import ozimmu, workloads
+
+REL_BAR = 1e-15
+
+
+def dev(X):
+    return ozimmu.to_colmajor(np.asarray(X, dtype=np.float64))
+
+
+def host(T):
+    return T.cpu().numpy()
+
+
+def untile(buf, R, K, s):
+    """MFMA layout (include/ozimmu.h) -> [s, R, K]; also returns the padded array for zero checks."""
+    Rp, Kp = -(-max(R, 1) // 128) * 128, -(-max(K, 1) // 128) * 128
+    a = np.asarray(buf, dtype=np.int8).reshape(Rp // 32, Kp // 32, s, 2, 32, 16)   # rb, kb, l, khalf, r, kbyte
+    full = a.transpose(2, 0, 4, 1, 3, 5).reshape(s, Rp, Kp)
+    return full[:, :R, :K], full
+
+
+def rel_err(C, Cref):
+    denom = np.abs(Cref)
+    diff = np.abs(C - Cref)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        r = np.where(diff == 0, 0.0, diff / denom)
+    return float(np.max(r)) if r.size else 0.0
+
+
+def assert_c_matches(C, Cref, what=""):
+    r = rel_err(C, Cref)
+    assert r <= REL_BAR, f"{what}: max relative difference {r:.3e} above the 1e-15 bar"
+    assert np.array_equal(C, Cref), f"{what}: within the bar (rel {r:.3e}) but not bit-identical"
+
+
+def inputs(kind, m, n, k, seed):
+    if kind == "uniform":
+        return workloads.uniform(m, n, k, seed)
+    if kind == "lognormal":
+        return workloads.lognormal(m, n, k, 2.0, seed)
+    if kind == "pow2":
+        return workloads.pow2_scaled(m, n, k, 30, seed)
+    if kind == "special":
+        A, B = workloads.lognormal(m, n, k, 4.0, seed)
+        rng = np.random.default_rng(seed)
+        if m > 2:
+            A[1, :] = 0.0                       # zero row
+        if n > 2:
+            B[:, 2] = 0.0                       # zero column
+        A[rng.random(A.shape) < 0.1] = 0.0
+        B[rng.random(B.shape) < 0.1] = -0.0     # negative zeros
+        if m > 3:
+            A[3, :] *= 2.0 ** -1040             # subnormal row
+        if m > 4 and k > 1:
+            A[4, :] = 0.0
+            A[4, k // 2] = 2.0 ** -3            # single power of two
+        if n > 5:
+            B[:, 5] *= 2.0 ** 900               # huge column
+        return A, B
+    raise ValueError(kind)
+
+
+SHAPES = [(1, 1, 1), (5, 3, 2), (33, 70, 17), (128, 128, 128), (100, 90, 70), (129, 65, 33), (257, 130, 300)]
+
+
+# ----------------------------------------------------------------------------- scales + slices
+
+@pytest.mark.parametrize("kind", ["uniform", "lognormal", "pow2", "special"])
+@pytest.mark.parametrize("m,n,k", SHAPES)
+@pytest.mark.parametrize("s", [1, 3, 7, 12, 32])
+def test_split_plain_layout_bit_exact(kind, m, n, k, s):
+    A, B = inputs(kind, m, n, k, 11)
+    for side, X in (("A", A), ("B", B)):
+        want_planes, want_e = oracle.split(side, X, s)
+        planes, e = ozimmu.split(side, dev(X), s, ozimmu.LAYOUT_PLAIN)
+        rows, cols = X.shape
+        got = host(planes).reshape(s, cols, rows).transpose(0, 2, 1)
+        assert np.array_equal(host(e), want_e), (side, "exponents")
+        assert np.array_equal(got, want_planes), (side, "slices")
+
+
+@pytest.mark.parametrize("kind", ["uniform", "special"])
+@pytest.mark.parametrize("m,n,k", SHAPES)
+@pytest.mark.parametrize("s", [1, 7, 9, 17, 32])
+def test_split_mfma_layout_bit_exact_and_zero_padded(kind, m, n, k, s):
+    A, B = inputs(kind, m, n, k, 12)
+    for side, X in (("A", A), ("B", B)):
+        want_planes, want_e = oracle.split(side, X, s)
+        planes, e = ozimmu.split(side, dev(X), s, ozimmu.LAYOUT_MFMA)
+        R, K = (X.shape[0], X.shape[1]) if side == "A" else (X.shape[1], X.shape[0])
+        got, full = untile(host(planes), R, K, s)
+        want = want_planes if side == "A" else want_planes.transpose(0, 2, 1)
+        assert np.array_equal(host(e), want_e)
+        assert np.array_equal(got, want), side
+        assert not full[:, R:, :].any() and not full[:, :, K:].any(), "padding must be zero"
+
+
+def test_split_with_leading_dimension_larger_than_rows():
+    A, B = workloads.lognormal(70, 50, 90, 1.0, 3)
+    big = ozimmu.colmajor_empty(100, 90)
+    big.fill_(7.0)
+    big[:70, :] = torch.as_tensor(A)
+    view = big[:70, :]
+    assert view.stride(1) == 100
+    planes, e = ozimmu.split("A", view, 5, ozimmu.LAYOUT_PLAIN)
+    want_planes, want_e = oracle.split("A", A, 5)
+    assert np.array_equal(host(e), want_e)
+    assert np.array_equal(host(planes).reshape(5, 90, 70).transpose(0, 2, 1), want_planes)
+
+
+# ----------------------------------------------------------------------------- integer products
+
+@pytest.mark.parametrize("m,n,k", [(33, 70, 17), (100, 90, 70), (200, 130, 1000)])
+def test_int32_slice_products_bit_exact(m, n, k):
+    s = 5
+    A, B = workloads.lognormal(m, n, k, 1.0, 21)
+    pa, _ = oracle.split("A", A, s)
+    pb, _ = oracle.split("B", B, s)
+    ws = ozimmu.alloc_workspace(m, n, k, s)
+    ozimmu.dgemm(dev(A), dev(B), s, workspace=ws)
+    for (l, h) in [(1, 1), (1, 5), (3, 2), (5, 1), (5, 5), (2, 4)]:
+        got = host(ozimmu.debug_slice_product(m, n, k, s, ws, l, h)).T
+        want = oracle.slice_product(pa[l - 1], pb[h - 1])
+        assert np.array_equal(got.astype(np.int64), want), (l, h)
+    if k > 64:
+        k0, k1 = 32, 32 * (k // 32)
+        got = host(ozimmu.debug_slice_product(m, n, k, s, ws, 2, 3, k0, k1)).T
+        want = oracle.slice_product(pa[1][:, k0:k1], pb[2][k0:k1, :])
+        assert np.array_equal(got.astype(np.int64), want)
+
+
+@pytest.mark.parametrize("m,n,k,s", [(33, 70, 17, 3), (128, 128, 128, 3), (100, 90, 70, 7), (257, 130, 300, 9),
+                                     (130, 257, 513, 1), (64, 64, 2048, 6)])
+def test_int32_diagonal_sums_of_fused_kernel_bit_exact(m, n, k, s):
+    A, B = workloads.uniform(m, n, k, 22)
+    pa, _ = oracle.split("A", A, s)
+    pb, _ = oracle.split("B", B, s)
+    ws = ozimmu.alloc_workspace(m, n, k, s)
+    ozimmu.dgemm(dev(A), dev(B), s, workspace=ws)
+    D = host(ozimmu.debug_diagonals(m, n, k, s, ws))          # [s, n, m]
+    for d in range(2, s + 2):
+        want = sum(oracle.slice_product(pa[l - 1], pb[d - l - 1]) for l in range(1, d) if l <= s and d - l <= s)
+        assert np.array_equal(D[d - 2].T.astype(np.int64), want), d
+
+
+def test_extreme_slices_do_not_overflow_int32_in_fused_kernel():
+    # 1 - 2^-53 has 53 one-bits: slices 1..7 all equal 127, the largest magnitude there is.  With
+    # s = 7 and k = 19008 (s * k just under the fused kernel's limit of 133144) the last diagonal
+    # reaches 7 * 19008 * 127^2 = 2 146 060 224, just below 2^31.
+    s, k = 7, 19008
+    x = 1.0 - 2.0 ** -53
+    A = np.full((40, k), x)
+    A[1::2, :] = -x
+    B = np.full((k, 40), x)
+    ws = ozimmu.alloc_workspace(40, 40, k, s)
+    C = host(ozimmu.dgemm(dev(A), dev(B), s, workspace=ws))
+    D = host(ozimmu.debug_diagonals(40, 40, k, s, ws))
+    assert int(D[s - 1].max()) == s * k * 127 * 127 and int(D[s - 1].min()) == -s * k * 127 * 127
+    assert_c_matches(C, oracle.dgemm(A, B, s), "extreme")
+
+
+# ----------------------------------------------------------------------------- C, small and ragged
+
+@pytest.mark.parametrize("kind", ["uniform", "lognormal", "pow2", "special"])
+@pytest.mark.parametrize("m,n,k", SHAPES)
+@pytest.mark.parametrize("s", [1, 2, 3, 5, 7, 9, 10, 13])
+def test_dgemm_matches_oracle(kind, m, n, k, s):
+    A, B = inputs(kind, m, n, k, 31)
+    ws = ozimmu.alloc_workspace(m, n, k, s)
+    C = ozimmu.dgemm(dev(A), dev(B), s, workspace=ws, check_finite=True)
+    Cref, eA, eB = oracle.dgemm(A, B, s, return_exponents=True)
+    gA, gB = ozimmu.get_exponents(m, n, k, s, ws)
+    assert np.array_equal(host(gA), eA) and np.array_equal(host(gB), eB)
+    assert_c_matches(host(C), Cref, f"{kind} {m}x{n}x{k} s={s}")
+
+
+def test_dgemm_config_uniform_128():
+    cfg = workloads.CONFIGS["uniform_128"]
+    A, B = cfg["gen"]()
+    for s in cfg["s"]:
+        assert_c_matches(host(ozimmu.dgemm(dev(A), dev(B), s)), oracle.dgemm(A, B, s), f"uniform_128 s={s}")
+
+
+def test_dgemm_config_lognormal_1024_all_slice_counts():
+    cfg = workloads.CONFIGS["lognormal_1024"]
+    A, B = cfg["gen"]()
+    dA, dB = dev(A), dev(B)
+    for s in cfg["s"]:
+        print(f"lognormal_1024 s={s}", flush=True)
+        assert_c_matches(host(ozimmu.dgemm(dA, dB, s)), oracle.dgemm(A, B, s), f"lognormal_1024 s={s}")
+
+
+def test_dgemm_with_leading_dimensions_and_c_view():
+    m, n, k, s = 70, 50, 90, 6
+    A, B = workloads.lognormal(m, n, k, 1.0, 4)
+    bigA = ozimmu.colmajor_empty(100, k); bigA.fill_(1e300); bigA[:m, :] = torch.as_tensor(A)
+    bigB = ozimmu.colmajor_empty(130, n); bigB.fill_(1e300); bigB[:k, :] = torch.as_tensor(B)
+    bigC = ozimmu.colmajor_empty(77, n); bigC.fill_(-1.0)
+    ozimmu.dgemm(bigA[:m, :], bigB[:k, :], s, C=bigC[:m, :])
+    assert_c_matches(host(bigC[:m, :]), oracle.dgemm(A, B, s), "ld")
+    assert bool((bigC[m:, :] == -1.0).all()), "rows of the C buffer outside the view must stay untouched"
+
+
+def test_k_blocked_accumulation_beyond_the_int32_range():
+    # k * 127^2 > 2^31 with all slices at +-127: a single int32 sum would overflow
+    k, s = 140000, 2
+    x = 1.0 - 2.0 ** -53
+    A = np.full((20, k), x); A[::3, :] = -x
+    B = np.full((k, 24), x); B[:, 1::2] *= 0.5
+    assert_c_matches(host(ozimmu.dgemm(dev(A), dev(B), s)), oracle.dgemm(A, B, s), "k-blocked extreme")
+    A, B = workloads.lognormal(40, 30, 150000, 2.0, 8)
+    assert_c_matches(host(ozimmu.dgemm(dev(A), dev(B), 7)), oracle.dgemm(A, B, 7), "k-blocked lognormal")
+
+
+def test_runs_are_bit_identical():
+    A, B = workloads.lognormal(300, 200, 500, 1.0, 5)
+    dA, dB = dev(A), dev(B)
+    for s in (7, 12):
+        C1 = host(ozimmu.dgemm(dA, dB, s))
+        C2 = host(ozimmu.dgemm(dA, dB, s))
+        assert np.array_equal(C1, C2)
+
+
+def test_degenerate_sizes():
+    A, B = workloads.uniform(8, 6, 0, 1)
+    C = ozimmu.dgemm(dev(A), dev(B), 3)
+    assert tuple(C.shape) == (8, 6) and bool((C == 0).all())
+    A, B = workloads.uniform(0, 6, 5, 1)
+    assert tuple(ozimmu.dgemm(dev(A), dev(B), 3).shape) == (0, 6)
+    A, B = workloads.uniform(4, 0, 5, 1)
+    assert tuple(ozimmu.dgemm(dev(A), dev(B), 3).shape) == (4, 0)
+    Z = np.zeros((5, 7))
+    A, B = workloads.uniform(5, 4, 7, 1)
+    assert bool((ozimmu.dgemm(dev(Z), dev(B), 4) == 0).all())
+
+
+def test_nonfinite_input_is_reported_not_fatal():
+    A, B = workloads.uniform(40, 30, 50, 2)
+    for bad in (np.nan, np.inf, -np.inf):
+        for which in (0, 1):
+            A2, B2 = A.copy(), B.copy()
+            (A2 if which == 0 else B2)[7, 9] = bad
+            ws = ozimmu.alloc_workspace(40, 30, 50, 4)
+            ozimmu.dgemm(dev(A2), dev(B2), 4, workspace=ws)
+            with pytest.raises(ozimmu.OzimmuError) as ei:
+                ozimmu.check(ws)
+            assert ei.value.code == ozimmu.NONFINITE
+            with pytest.raises(ozimmu.OzimmuError) as ei:
+                ozimmu.estimate_slices(dev(A2), dev(B2), 1e-9)
+            assert ei.value.code == ozimmu.NONFINITE
+    ws = ozimmu.alloc_workspace(40, 30, 50, 4)
+    ozimmu.dgemm(dev(A), dev(B), 4, workspace=ws)
+    ozimmu.check(ws)     # clean input: no error
+
+
+# ----------------------------------------------------------------------------- estimator
+
+@pytest.mark.parametrize("kind", ["uniform", "lognormal", "pow2", "special"])
+@pytest.mark.parametrize("m,n,k", [(5, 3, 2), (100, 90, 70), (257, 130, 300)])
+def test_estimator_matches_oracle(kind, m, n, k):
+    A, B = inputs(kind, m, n, k, 41)
+    dA, dB = dev(A), dev(B)
+    for tol in (1e-2, 1e-8, 1e-15, 2.0 ** -53, 1e-300):
+        assert ozimmu.estimate_slices(dA, dB, tol) == oracle.estimate_slices(A, B, tol, s_max=ozimmu.MAX_SLICES), tol
+
+
+def test_estimator_on_config_lognormal_1024():
+    A, B = workloads.CONFIGS["lognormal_1024"]["gen"]()
+    dA, dB = dev(A), dev(B)
+    for tol in (1e-8, 1e-15):
+        got = ozimmu.estimate_slices(dA, dB, tol)
+        assert got == oracle.estimate_slices(A, B, tol, s_max=ozimmu.MAX_SLICES)
+        print("lognormal_1024 tol", tol, "->", got, flush=True)
