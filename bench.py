@@ -1,0 +1,183 @@
+#!/usr/bin/env python3
+"""Benchmark of the ozimmu hot path on one MI355X.
+
+A "step" is one ozimmu_dgemm call: scale extraction, splitting of A and B into s int8 slices,
+and the fused int8-MFMA GEMM with the binary64 accumulation, on synthetic inputs that are
+resident in HBM before the timed region.  Prints ONE JSON line.
+
+  value      effective FP64 TFLOP/s = 2 m n k / (time per step)
+  roofline   fused GEMM kernel alone: int8 op/s = 2 m n k * s(s+1)/2 / (HIP-event time of the
+             kernel, recorded on its stream during the timed region) against the int8 MFMA peak
+  cpu_baseline  the CPU oracle, timed on a bounded sample (a block of rows of A times a block of
+             columns of B, full k) of the same inputs
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+INT8_PEAK_TOPS = 5000.0          # MI355X dense int8 MFMA, published
+HBM_PEAK_GBS = 8000.0
+
+
+def error_measures(C, A, B, Cref):
+    """Normwise measure eq. (err_higham) with alpha=1, beta=0, and max componentwise relative
+    error eq. (fwd-err-def-mat), both against a binary64 reference product."""
+    import torch
+    k = A.shape[1]
+    diff = C - Cref
+    normwise = (torch.linalg.norm(diff) / ((k + 2) ** 0.5 * torch.linalg.norm(A) * torch.linalg.norm(B))).item()
+    denom = Cref.abs()
+    comp = (diff.abs() / denom)[denom > 0].max().item()
+    return normwise, comp
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="pow2_scaled_8192")
+    ap.add_argument("--slices", type=int, default=7)
+    ap.add_argument("--sweep", action="store_true", help="also time every slice count of the workload (extra keys)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample", type=int, default=1024, help="rows of A and columns of B in the oracle sample")
+    ap.add_argument("--traffic-bytes", type=float, default=None,
+                    help="HBM bytes per GEMM launch from rocprofv3 --pmc runs (see profiles/)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (the method needs no exchange when C is tiled "
+              "over GPUs; see DESIGN.md); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2506_11277_amd import ozimmu, workloads
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    ozimmu.lib()   # fails loudly if the HIP library is missing
+
+    cfg = workloads.CONFIGS[args.workload]
+    m, n, k = cfg["m"], cfg["n"], cfg["k"]
+    A, B = cfg["gen"]()
+    dA, dB = ozimmu.to_colmajor(A), ozimmu.to_colmajor(B)
+    C = ozimmu.colmajor_empty(m, n)
+    flops = 2.0 * m * n * k
+
+    def run(s, steps, warmup):
+        ws = ozimmu.alloc_workspace(m, n, k, s)
+        for _ in range(warmup):
+            ozimmu.dgemm(dA, dB, s, C=C, workspace=ws)
+        ozimmu.check(ws)
+        torch.cuda.synchronize()
+        ozimmu.profile_start(steps)
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            ozimmu.dgemm(dA, dB, s, C=C, workspace=ws)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / steps
+        calls, phases = ozimmu.profile_stop()
+        assert calls == steps
+        return dt, phases
+
+    s = args.slices
+    dt, phases = run(s, args.steps, args.warmup)
+    pairs = s * (s + 1) // 2
+    gemm_s = phases["gemm"] * 1e-3
+    int8_tops = flops * pairs / gemm_s / 1e12
+    split_bytes = (8.0 + s) * (m * k + k * n)
+    scales_bytes = 8.0 * (m * k + k * n)
+
+    out = {
+        "metric": "effective FP64 TFLOP/s (2mnk/t) vs slices s; % of int8 MFMA peak",
+        "value": flops / dt / 1e12,
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": dt * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "i8",
+        "data": "synthetic",
+        "config": {"workload": args.workload, "m": m, "n": n, "k": k, "slices": s, "slice_pairs": pairs},
+        "roofline": {
+            "kernel": "gemm_fused_kernel",
+            "bound": "mfma",
+            "achieved": int8_tops,
+            "peak": INT8_PEAK_TOPS,
+            "unit": "TOP/s",
+            "frac": int8_tops / INT8_PEAK_TOPS,
+            "traffic": args.traffic_bytes,
+            "ms": phases["gemm"],
+        },
+        "phases_ms": phases,
+        "hbm_kernels": {
+            "scales_GBs": scales_bytes / (phases["scales"] * 1e-3) / 1e9 if phases["scales"] > 0 else None,
+            "split_GBs": split_bytes / (phases["split"] * 1e-3) / 1e9 if phases["split"] > 0 else None,
+            "peak_GBs": HBM_PEAK_GBS,
+        },
+    }
+
+    # context: native binary64 GEMM of the vendor library on the same tensors, and accuracy
+    Cref = torch.matmul(dA, dB)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    reps = 3
+    for _ in range(reps):
+        Cref = torch.matmul(dA, dB)
+    torch.cuda.synchronize()
+    t_native = (time.perf_counter() - t0) / reps
+    ozimmu.dgemm(dA, dB, s, C=C)
+    normwise, comp = error_measures(C, dA, dB, Cref)
+    out["native_dgemm"] = {"tflops": flops / t_native / 1e12, "ms": t_native * 1e3, "library": "rocBLAS/hipBLASLt via torch.matmul"}
+    out["error_vs_native"] = {"normwise_err_higham": normwise, "max_componentwise": comp}
+
+    if args.sweep:
+        sweep = []
+        for ss in cfg["s"]:
+            dts, ph = run(ss, max(3, args.steps // 2), 1)
+            pp = ss * (ss + 1) // 2
+            ozimmu.dgemm(dA, dB, ss, C=C)
+            nw, cw = error_measures(C, dA, dB, Cref)
+            sweep.append({"s": ss, "ms_per_step": dts * 1e3, "tflops_effective": flops / dts / 1e12,
+                          "gemm_ms": ph["gemm"], "int8_tops": flops * pp / (ph["gemm"] * 1e-3) / 1e12,
+                          "frac_int8_peak": flops * pp / (ph["gemm"] * 1e-3) / 1e12 / INT8_PEAK_TOPS,
+                          "normwise_err": nw, "max_componentwise_err": cw})
+        out["sweep"] = sweep
+        tol = 2.0 ** -53
+        est = ozimmu.estimate_slices(dA, dB, tol)
+        out["estimator"] = {"tol": tol, "s": est[0], "status": est[1], "kappa_A": est[2], "kappa_B": est[3]}
+
+    if not args.no_cpu_baseline:
+        from oracle import oracle
+        ms_ = min(args.cpu_sample, m)
+        ns_ = min(args.cpu_sample, n)
+        As = np.asfortranarray(A[:ms_, :])
+        Bs = np.asfortranarray(B[:, :ns_])
+        t0 = time.perf_counter()
+        Cs = oracle.dgemm(As, Bs, s)
+        t_cpu = time.perf_counter() - t0
+        ozimmu.dgemm(dA, dB, s, C=C)
+        same = bool(np.array_equal(C[:ms_, :ns_].cpu().numpy(), Cs))
+        out["cpu_baseline"] = {
+            "value": 2.0 * ms_ * ns_ * k / t_cpu / 1e12,
+            "unit": "TFLOP/s",
+            "cores": oracle.num_threads(),
+            "kind": "oracle",
+            "sample": f"C[0:{ms_}, 0:{ns_}] = A[0:{ms_}, :] B[:, 0:{ns_}] with full k={k}, s={s}: {t_cpu:.2f} s",
+            "gpu_matches_oracle_on_sample": same,
+        }
+
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -126,6 +126,18 @@ int ozimmu_get_exponents(int m, int n, int k, int s, const void *workspace, int3
                          void *stream);
 
 /*
+ * Per-phase timing of ozimmu_dgemm, for benchmarks.  Between ozimmu_profile_start(max_calls) and
+ * ozimmu_profile_stop(), each ozimmu_dgemm call (up to max_calls <= 4096 of them) records HIP
+ * events on its stream before and after its three phases; the calls stay asynchronous.
+ * ozimmu_profile_stop waits for the recorded events and returns in phase_ms [host, 3 floats] the
+ * average milliseconds per call of: [0] scale extraction (reductions), [1] splitting of A and B,
+ * [2] the GEMM kernel (a single launch); *calls [host] receives the number of calls averaged.
+ * Host-side state, not thread-safe; allocates no device memory.
+ */
+int ozimmu_profile_start(int max_calls);
+int ozimmu_profile_stop(int *calls, float *phase_ms);
+
+/*
  * Test hooks (used by the parity tests to compare integer intermediates bit for bit).
  * Both read the MFMA-layout planes that ozimmu_dgemm(m, n, k, ..., s, workspace) left in
  * `workspace`, on the same stream.

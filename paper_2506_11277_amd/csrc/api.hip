@@ -22,6 +22,18 @@ inline bool bad_matrix(int rows, int cols, const void *p, int ld)
         if (e__ != hipSuccess) return OZIMMU_HIP_ERROR;     \
     } while (0)
 
+// Optional per-phase timing of ozimmu_dgemm with HIP events recorded on the caller's stream.
+struct Profile {
+    bool on = false;
+    int capacity = 0, calls = 0;
+    hipEvent_t *ev = nullptr;   // 4 events per call: start, after scales, after split, after gemm
+} g_prof;
+
+inline void prof_mark(int phase, hipStream_t st)
+{
+    if (g_prof.on && g_prof.calls < g_prof.capacity) (void)hipEventRecord(g_prof.ev[4 * g_prof.calls + phase], st);
+}
+
 // scales of both operands into the workspace (optionally with the minima for kappa)
 int scales_into_workspace(const Workspace &w, char *ws, int m, int n, int k, const double *A, int lda,
                           const double *B, int ldb, bool with_min, hipStream_t st)
@@ -134,18 +146,59 @@ int ozimmu_dgemm(int m, int n, int k, const double *A, int lda, const double *B,
     // exact conversion of a diagonal sum to binary64 needs s * k * 127^2 < 2^53: true for every int k
     hipStream_t st = (hipStream_t)stream;
     char *ws = (char *)workspace;
+    prof_mark(0, st);
     int rc = scales_into_workspace(w, ws, m, n, k, A, lda, B, ldb, false, st);
     if (rc) return rc;
     if (m == 0 || n == 0) return OZIMMU_OK;
+    prof_mark(1, st);
     auto *eA = (int32_t *)(ws + w.off_expA), *eB = (int32_t *)(ws + w.off_expB);
     auto *pA = (int8_t *)(ws + w.off_planesA), *pB = (int8_t *)(ws + w.off_planesB);
     OZ_TRY(launch_split('A', m, k, A, lda, s, eA, pA, OZIMMU_LAYOUT_MFMA, st));
     OZ_TRY(launch_split('B', k, n, B, ldb, s, eB, pB, OZIMMU_LAYOUT_MFMA, st));
+    prof_mark(2, st);
     if (fused_applicable(s, k))
         OZ_TRY(launch_gemm_fused(m, n, w.kp, s, pA, pB, eA, eB, C, ldc, nullptr, st));
     else
         OZ_TRY(launch_gemm_generic(m, n, w.kp, s, pA, pB, eA, eB, C, ldc, 0, 0, 0, w.kp / kFrag, nullptr, st));
+    prof_mark(3, st);
+    if (g_prof.on && g_prof.calls < g_prof.capacity) ++g_prof.calls;
     return OZIMMU_OK;
+}
+
+int ozimmu_profile_start(int max_calls)
+{
+    if (max_calls < 1 || max_calls > 4096 || g_prof.on) return OZIMMU_BAD_ARG;
+    g_prof.ev = new hipEvent_t[4 * (size_t)max_calls];
+    for (int i = 0; i < 4 * max_calls; ++i)
+        if (hipEventCreate(&g_prof.ev[i]) != hipSuccess) return OZIMMU_HIP_ERROR;
+    g_prof.capacity = max_calls;
+    g_prof.calls = 0;
+    g_prof.on = true;
+    return OZIMMU_OK;
+}
+
+int ozimmu_profile_stop(int *calls, float *phase_ms)
+{
+    if (!g_prof.on || !calls || !phase_ms) return OZIMMU_BAD_ARG;
+    g_prof.on = false;
+    int rc = OZIMMU_OK;
+    double sum[3] = {0, 0, 0};
+    for (int c = 0; c < g_prof.calls; ++c) {
+        hipEvent_t *e = g_prof.ev + 4 * c;
+        if (hipEventSynchronize(e[3]) != hipSuccess) rc = OZIMMU_HIP_ERROR;
+        for (int p = 0; p < 3 && rc == OZIMMU_OK; ++p) {
+            float ms = 0.f;
+            if (hipEventElapsedTime(&ms, e[p], e[p + 1]) != hipSuccess) rc = OZIMMU_HIP_ERROR;
+            sum[p] += ms;
+        }
+    }
+    for (int i = 0; i < 4 * g_prof.capacity; ++i) (void)hipEventDestroy(g_prof.ev[i]);
+    delete[] g_prof.ev;
+    g_prof.ev = nullptr;
+    *calls = g_prof.calls;
+    for (int p = 0; p < 3; ++p) phase_ms[p] = g_prof.calls ? (float)(sum[p] / g_prof.calls) : 0.f;
+    g_prof.capacity = g_prof.calls = 0;
+    return rc;
 }
 
 int ozimmu_check(void *workspace, void *stream)

@@ -32,6 +32,8 @@ _SIGNATURES = {
     "ozimmu_check": (_c.c_int, [_c.c_void_p, _c.c_void_p]),
     "ozimmu_get_exponents": (_c.c_int, [_c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_void_p, _c.c_void_p,
                                         _c.c_void_p, _c.c_void_p]),
+    "ozimmu_profile_start": (_c.c_int, [_c.c_int]),
+    "ozimmu_profile_stop": (_c.c_int, [_c.POINTER(_c.c_int), _c.POINTER(_c.c_float)]),
     "ozimmu_debug_diagonals": (_c.c_int, [_c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_void_p, _c.c_void_p,
                                           _c.c_void_p]),
     "ozimmu_debug_slice_product": (_c.c_int, [_c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_void_p, _c.c_int,
@@ -185,6 +187,22 @@ def get_exponents(m, n, k, s, workspace):
     if rc != OK:
         raise OzimmuError(rc, "get_exponents")
     return eA[:m], eB[:n]
+
+
+def profile_start(max_calls):
+    rc = lib().ozimmu_profile_start(max_calls)
+    if rc != OK:
+        raise OzimmuError(rc, "profile_start")
+
+
+def profile_stop():
+    """Returns (calls, {"scales": ms, "split": ms, "gemm": ms}) averaged over the profiled dgemm calls."""
+    calls = ctypes.c_int(0)
+    ms = (ctypes.c_float * 3)()
+    rc = lib().ozimmu_profile_stop(ctypes.byref(calls), ms)
+    if rc != OK:
+        raise OzimmuError(rc, "profile_stop")
+    return calls.value, {"scales": ms[0], "split": ms[1], "gemm": ms[2]}
 
 
 def debug_diagonals(m, n, k, s, workspace):
