@@ -46,7 +46,10 @@ def main():
     ap.add_argument("--slices", type=int, default=7)
     ap.add_argument("--sweep", action="store_true", help="also time every slice count of the workload (extra keys)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample", type=int, default=1024, help="rows of A and columns of B in the oracle sample")
+    ap.add_argument("--cpu-sample", type=int, default=2048, help="rows of A and columns of B in the oracle sample")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (a known amount of HBM traffic) so that "
+                         "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings can be scaled")
     ap.add_argument("--traffic-bytes", type=float, default=None,
                     help="HBM bytes per GEMM launch from rocprofv3 --pmc runs (see profiles/)")
     args = ap.parse_args()
@@ -125,6 +128,14 @@ def main():
             "peak_GBs": HBM_PEAK_GBS,
         },
     }
+
+    if args.calibration_copy:
+        src = torch.empty(1 << 27, dtype=torch.float64, device="cuda").fill_(1.0)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # context: native binary64 GEMM of the vendor library on the same tensors, and accuracy
     Cref = torch.matmul(dA, dB)
