@@ -24,7 +24,7 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));   // 16-byte copy unit
 
-constexpr int kThreads = 256;   // 4 wavefronts, 2 (m) x 2 (n)
+constexpr int kThreads = 256;   // generic kernel: 4 wavefronts, 2 (m) x 2 (n)
 
 // XCD-aware tile order.  Work-groups are dealt round-robin to the 8 XCDs (id % 8), each with
 // its own L2.  Renumber so that an XCD owns a contiguous run of tiles, and walk the run in
@@ -47,46 +47,75 @@ __device__ __forceinline__ void tile_of_block(int b, int nb, int tiles_m, int ti
 // All s diagonals live in int32 accumulators for the whole contraction; needs
 // s * k * 127^2 < 2^31.  Per k-step every slice of the A tile and of the B tile is staged
 // once in LDS and feeds all s(s+1)/2 products.
-//   S     slices (compile time: the pair loop is fully unrolled)
-//   WMF   fragments (of 32 rows of A) per wavefront along m;  WNF likewise along n
-//   KB32  32-deep k-blocks per LDS stage
-//   DUMP  write the int32 diagonal sums instead of C (test hook)
-template <int S, int WMF, int WNF, int KB32, bool DUMP>
-__global__ __launch_bounds__(kThreads) void gemm_fused_kernel(const int8_t *__restrict__ pA,
-                                                              const int8_t *__restrict__ pB,
-                                                              const int32_t *__restrict__ eA,
-                                                              const int32_t *__restrict__ eB, double *__restrict__ C,
-                                                              int ldc, int m, int n, int KB, int tiles_m, int tiles_n,
-                                                              int32_t *__restrict__ dump)
+//
+// Work-group: WVM x WVN wavefronts (two per SIMD when 8), each owning WMF x WNF fragments of
+// 32 x 32 outputs for every diagonal.  Operand stages are copied HBM/L2 -> LDS by the
+// global_load_lds (LDS-DMA) form of the vector load, 1 KiB per wavefront instruction, into a
+// ring of NSTAGE buffers: no staging registers, no ds_write, and the loads of stage st+NSTAGE-1
+// are in flight while stage st is multiplied.  The loads are issued from inline asm, so the
+// waits on them (vmcnt) are placed by hand below.
+//   S      slices (compile time: the pair loop is fully unrolled)
+//   KB32   32-deep k-blocks per LDS stage
+//   DUMP   write the int32 diagonal sums instead of C (test hook)
+
+// 16 bytes per lane: global (sbase + voff)  ->  LDS (ldsaddr + lane * 16); ldsaddr is wavefront-uniform
+__device__ __forceinline__ void lds_dma16(const void *sbase, unsigned voff, unsigned ldsaddr)
 {
-    constexpr int FA = 2 * WMF, FB = 2 * WNF;          // fragments per work-group tile along m / n
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(ldsaddr), "v"(voff), "s"(sbase)
+                 : "memory", "m0");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+template <int S, int WVM, int WVN, int WMF, int WNF, int KB32, int NSTAGE, bool DUMP>
+__global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t *__restrict__ pA,
+                                                                    const int8_t *__restrict__ pB,
+                                                                    const int32_t *__restrict__ eA,
+                                                                    const int32_t *__restrict__ eB,
+                                                                    double *__restrict__ C, int ldc, int m, int n,
+                                                                    int KB, int tiles_m, int tiles_n,
+                                                                    int32_t *__restrict__ dump)
+{
+    constexpr int NW = WVM * WVN;                      // wavefronts
+    constexpr int FA = WVM * WMF, FB = WVN * WNF;      // fragment rows per work-group tile along m / n
     constexpr int CHUNK = KB32 * S * kFragBytes;       // bytes of one fragment row per stage (contiguous in HBM)
     constexpr int STAGE = (FA + FB) * CHUNK;
-    constexpr int UNITS = STAGE / 16;                  // 16-byte units per stage
-    constexpr int UPT = (UNITS + kThreads - 1) / kThreads;
+    constexpr int UNITS = STAGE / kFragBytes;          // 1 KiB copy units per stage
+    constexpr int UPW = UNITS / NW, UREM = UNITS % NW; // units per wavefront (+1 for the first UREM wavefronts)
+    static_assert(NSTAGE == 2 || NSTAGE == 3, "ring depth");
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds;
 
     int tm, tn;
     tile_of_block(blockIdx.x, gridDim.x, tiles_m, tiles_n, tm, tn);
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave & 1, wn = wave >> 1;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wm = wave % WVM, wn = wave / WVM;
+    const size_t row_bytes = (size_t)KB * (S * kFragBytes);     // one fragment row of an operand, all k
+    const int8_t *rowA = pA + (size_t)tm * FA * row_bytes;
+    const int8_t *rowB = pB + (size_t)tn * FB * row_bytes;
+    const bool extra = wave < UREM;
 
-    // per-thread copy plan: unit u = tid + i*256 -> (chunk c, offset o) ; source pointer advances by CHUNK per stage
-    const v4u *src[UPT];
-    int dsto[UPT];
+    // copy of stage `st` into ring buffer `buf`: unit u = wave + i*NW  ->  fragment row c = u / (KB32*S)
+    auto issue_stage = [&](int st, int buf) {
 #pragma unroll
-    for (int i = 0; i < UPT; ++i) {
-        const int u = tid + i * kThreads;
-        const int c = u / (CHUNK / 16), o = u % (CHUNK / 16);
-        dsto[i] = u * 16;
-        if (u < UNITS) {
-            const int8_t *base = c < FA ? pA + ((size_t)(tm * FA + c) * KB) * (size_t)(S * kFragBytes)
-                                        : pB + ((size_t)(tn * FB + (c - FA)) * KB) * (size_t)(S * kFragBytes);
-            src[i] = (const v4u *)base + o;
-        } else {
-            src[i] = nullptr;
+        for (int i = 0; i < UPW + (UREM ? 1 : 0); ++i) {
+            if (i == UPW && !extra) break;
+            const int u = wave + i * NW;
+            const int c = u / (KB32 * S), o = u % (KB32 * S);
+            const int8_t *src = (c < FA ? rowA + (size_t)c * row_bytes : rowB + (size_t)(c - FA) * row_bytes) +
+                                (size_t)st * CHUNK + (size_t)o * kFragBytes;
+            lds_dma16(src, lane * 16, lds0 + buf * STAGE + u * kFragBytes);
         }
-    }
+    };
+    // wait until at most `keep` stages issued by this wavefront are still in flight
+    auto wait_keep1 = [&]() {
+        if (extra) wait_vmcnt<UPW + 1>(); else wait_vmcnt<UPW>();
+    };
 
     v16i acc[S][WMF][WNF];
 #pragma unroll
@@ -99,25 +128,20 @@ __global__ __launch_bounds__(kThreads) void gemm_fused_kernel(const int8_t *__re
                 for (int r = 0; r < 16; ++r) acc[a][i][j][r] = 0;
 
     const int nst = KB / KB32;
-    v4u stg[UPT];
-#pragma unroll
-    for (int i = 0; i < UPT; ++i)
-        if ((i + 1) * kThreads <= UNITS || tid + i * kThreads < UNITS) stg[i] = src[i][0];
-#pragma unroll
-    for (int i = 0; i < UPT; ++i)
-        if ((i + 1) * kThreads <= UNITS || tid + i * kThreads < UNITS) *(v4u *)(lds + dsto[i]) = stg[i];
+    issue_stage(0, 0);
+    if (NSTAGE == 3 && nst > 1) {
+        issue_stage(1, 1);
+        wait_keep1();
+    } else {
+        wait_vmcnt<0>();
+    }
     __syncthreads();
 
+    int buf = 0;
     for (int st = 0; st < nst; ++st) {
-        const unsigned char *cur = lds + (st & 1) * STAGE;
-        unsigned char *nxt = lds + ((st + 1) & 1) * STAGE;
-        const bool more = st + 1 < nst;
-        if (more) {
-#pragma unroll
-            for (int i = 0; i < UPT; ++i)
-                if ((i + 1) * kThreads <= UNITS || tid + i * kThreads < UNITS)
-                    stg[i] = src[i][(size_t)(st + 1) * (CHUNK / 16)];
-        }
+        const bool ahead = st + NSTAGE - 1 < nst;
+        if (ahead) issue_stage(st + NSTAGE - 1, buf == 0 ? NSTAGE - 1 : buf - 1);
+        const unsigned char *cur = lds + buf * STAGE;
 #pragma unroll
         for (int kbl = 0; kbl < KB32; ++kbl) {
             v4i bf[S][WNF];
@@ -142,16 +166,15 @@ __global__ __launch_bounds__(kThreads) void gemm_fused_kernel(const int8_t *__re
                                 __builtin_amdgcn_mfma_i32_32x32x32_i8(bf[h][j], af[i], acc[l + h][i][j], 0, 0, 0);
             }
         }
-        if (more) {
-#pragma unroll
-            for (int i = 0; i < UPT; ++i)
-                if ((i + 1) * kThreads <= UNITS || tid + i * kThreads < UNITS) *(v4u *)(nxt + dsto[i]) = stg[i];
-        }
+        // stage st+1 must have landed before anyone reads it: with a ring of 3 the stage issued in
+        // this iteration may stay in flight, otherwise everything has to be back
+        if (NSTAGE == 3 && ahead) wait_keep1(); else wait_vmcnt<0>();
         __syncthreads();
+        buf = buf + 1 == NSTAGE ? 0 : buf + 1;
     }
 
     // epilogue: accumulator register r of lane holds  (n_local, m_local) = (8*(r/4) + 4*(lane/32) + r%4, lane%32)
-    const int m0 = tm * FA * 32 + wm * WMF * 32, n0 = tn * FB * 32 + wn * WNF * 32;
+    const int m0 = (tm * FA + wm * WMF) * 32, n0 = (tn * FB + wn * WNF) * 32;
 #pragma unroll
     for (int i = 0; i < WMF; ++i) {
         const int mi = m0 + i * 32 + (lane & 31);
@@ -294,32 +317,45 @@ __global__ __launch_bounds__(kThreads) void gemm_generic_kernel(const int8_t *__
 }
 
 // ------------------------------- launch tables --------------------------------------------
+constexpr int kLdsBytes = 160 * 1024;
+
+// Tile shapes per slice count, picked from a sweep at 8192^3 on random slices (all candidates
+// land within a few percent of each other: the kernel is limited by the chip's power budget
+// once the matrix cores are kept fed, not by a single pipe).
+//   WIDE: 8 wavefronts as 2 (m) x 4 (n), each 64 x 32 outputs: tile 128 x 128 (fewer L2->LDS bytes
+//         per product; fits the 256 registers of a two-per-SIMD wavefront while 32*S <= 192)
+//   else: 8 wavefronts as 4 (m) x 2 (n), each 32 x 32 outputs: tile 128 x 64
 template <int S>
 struct FusedCfg {
-    // k-blocks of 32 per LDS stage: deeper stages for few slices (fewer barriers per MFMA)
-    static constexpr int KB32 = S <= 2 ? 4 : (S <= 6 ? 2 : 1);
-    static constexpr int WMF = 2, WNF = 1;
+    static constexpr bool WIDE = S <= 4 || S == 6;
+    static constexpr int WVM = WIDE ? 2 : 4, WVN = WIDE ? 4 : 2, WMF = WIDE ? 2 : 1, WNF = 1;
+    static constexpr int FR = WVM * WMF + WVN * WNF;
+    static constexpr int KB32 = S == 4 ? 2 : 1;
+    static constexpr int NSTAGE = S <= 3 ? 3 : 2;
 };
 
-constexpr int kFusedMaxS = 9;   // s = 10 no longer fits 512 registers per lane without spilling
+constexpr int kFusedMaxS = 12;   // 16 accumulator registers per diagonal; beyond 12 the wavefront's 256 run out
 
 template <int S, bool DUMP>
 hipError_t launch_fused_s(int m, int n, int kp, const int8_t *pA, const int8_t *pB, const int32_t *eA,
                           const int32_t *eB, double *C, int ldc, int32_t *dump, hipStream_t st)
 {
     using Cfg = FusedCfg<S>;
-    constexpr int TM = 64 * Cfg::WMF, TN = 64 * Cfg::WNF;
-    constexpr int STAGE = (2 * Cfg::WMF + 2 * Cfg::WNF) * Cfg::KB32 * S * kFragBytes;
-    auto kern = gemm_fused_kernel<S, Cfg::WMF, Cfg::WNF, Cfg::KB32, DUMP>;
+    constexpr int TM = 32 * Cfg::WVM * Cfg::WMF, TN = 32 * Cfg::WVN * Cfg::WNF;
+    constexpr int STAGE = Cfg::FR * Cfg::KB32 * S * kFragBytes;
+    static_assert(Cfg::NSTAGE * STAGE <= kLdsBytes, "LDS ring too large");
+    static_assert(kPad % TM == 0 && kPad % TN == 0 && (kPad / kFrag) % Cfg::KB32 == 0, "tiles must divide the padding");
+    auto kern = gemm_fused_kernel<S, Cfg::WVM, Cfg::WVN, Cfg::WMF, Cfg::WNF, Cfg::KB32, Cfg::NSTAGE, DUMP>;
     static bool configured = false;
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * STAGE);
+        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           Cfg::NSTAGE * STAGE);
         if (e != hipSuccess) return e;
         configured = true;
     }
     const int tiles_m = (m + TM - 1) / TM, tiles_n = (n + TN - 1) / TN;
-    kern<<<tiles_m * tiles_n, kThreads, 2 * STAGE, st>>>(pA, pB, eA, eB, C, ldc, m, n, kp / kFrag, tiles_m, tiles_n,
-                                                         dump);
+    kern<<<tiles_m * tiles_n, 64 * Cfg::WVM * Cfg::WVN, Cfg::NSTAGE * STAGE, st>>>(pA, pB, eA, eB, C, ldc, m, n,
+                                                                                   kp / kFrag, tiles_m, tiles_n, dump);
     return hipGetLastError();
 }
 
@@ -330,7 +366,7 @@ hipError_t dispatch_fused(int s, int m, int n, int kp, const int8_t *pA, const i
     switch (s) {
 #define OZ_CASE(S_) \
     case S_: return launch_fused_s<S_, DUMP>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, st);
-        OZ_CASE(1) OZ_CASE(2) OZ_CASE(3) OZ_CASE(4) OZ_CASE(5) OZ_CASE(6) OZ_CASE(7) OZ_CASE(8) OZ_CASE(9)
+        OZ_CASE(1) OZ_CASE(2) OZ_CASE(3) OZ_CASE(4) OZ_CASE(5) OZ_CASE(6) OZ_CASE(7) OZ_CASE(8) OZ_CASE(9) OZ_CASE(10) OZ_CASE(11) OZ_CASE(12)
 #undef OZ_CASE
     }
     return hipErrorInvalidValue;

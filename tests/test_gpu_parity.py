@@ -142,7 +142,7 @@ def test_int32_slice_products_bit_exact(m, n, k):
 
 
 @pytest.mark.parametrize("m,n,k,s", [(33, 70, 17, 3), (128, 128, 128, 3), (100, 90, 70, 7), (257, 130, 300, 9),
-                                     (130, 257, 513, 1), (64, 64, 2048, 6)])
+                                     (130, 257, 513, 1), (64, 64, 2048, 6), (100, 300, 70, 12), (129, 129, 200, 4), (200, 100, 64, 2)])
 def test_int32_diagonal_sums_of_fused_kernel_bit_exact(m, n, k, s):
     A, B = workloads.uniform(m, n, k, 22)
     pa, _ = oracle.split("A", A, s)
@@ -175,7 +175,7 @@ def test_extreme_slices_do_not_overflow_int32_in_fused_kernel():
 
 @pytest.mark.parametrize("kind", ["uniform", "lognormal", "pow2", "special"])
 @pytest.mark.parametrize("m,n,k", SHAPES)
-@pytest.mark.parametrize("s", [1, 2, 3, 5, 7, 9, 10, 13])
+@pytest.mark.parametrize("s", [1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 12, 13])
 def test_dgemm_matches_oracle(kind, m, n, k, s):
     A, B = inputs(kind, m, n, k, 31)
     ws = ozimmu.alloc_workspace(m, n, k, s)
