@@ -151,6 +151,26 @@ def main():
     out["native_dgemm"] = {"tflops": flops / t_native / 1e12, "ms": t_native * 1e3, "library": "rocBLAS/hipBLASLt via torch.matmul"}
     out["error_vs_native"] = {"normwise_err_higham": normwise, "max_componentwise": comp}
 
+    # context: what the matrix cores sustain with nothing else running, and the vendor's int8 GEMM
+    out["int8_mfma_sustained_TOPs"] = {"constant_operands": ozimmu.measure_int8_ceiling(False),
+                                       "random_operands": ozimmu.measure_int8_ceiling(True),
+                                       "what": "register-only v_mfma_i32_32x32x32_i8 loop, 2 wavefronts per SIMD"}
+    try:
+        ia = torch.randint(-127, 128, (m, k), dtype=torch.int8, device="cuda")
+        ib = torch.randint(-127, 128, (n, k), dtype=torch.int8, device="cuda").t()
+        torch._int_mm(ia, ib)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(5):
+            torch._int_mm(ia, ib)
+        torch.cuda.synchronize()
+        t_i8 = (time.perf_counter() - t0) / 5
+        out["native_int8_gemm"] = {"tops": flops / t_i8 / 1e12, "ms": t_i8 * 1e3,
+                                   "what": "one int8 GEMM of the same shape, random entries, torch._int_mm (hipBLASLt)"}
+        del ia, ib
+    except Exception as exc:  # context only
+        out["native_int8_gemm"] = {"error": str(exc)[:200]}
+
     if args.sweep:
         sweep = []
         for ss in cfg["s"]:

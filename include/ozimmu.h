@@ -138,6 +138,15 @@ int ozimmu_profile_start(int max_calls);
 int ozimmu_profile_stop(int *calls, float *phase_ms);
 
 /*
+ * Benchmark aid: the int8 rate (TOP/s, written to *tops [host]) that a register-only loop of
+ * v_mfma_i32_32x32x32_i8 sustains on the current device for some tens of milliseconds, with
+ * constant (random_operands = 0) or pseudo-random (1) operand registers.  `sink`: device pointer
+ * to one int (never written in practice).  Synchronises.  Context for the roofline fraction of the
+ * GEMM kernel: the sustained clock of the matrix cores depends on the operand data.
+ */
+int ozimmu_measure_int8_ceiling(int random_operands, int *sink, float *tops, void *stream);
+
+/*
  * Test hooks (used by the parity tests to compare integer intermediates bit for bit).
  * Both read the MFMA-layout planes that ozimmu_dgemm(m, n, k, ..., s, workspace) left in
  * `workspace`, on the same stream.

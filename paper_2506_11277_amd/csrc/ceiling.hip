@@ -1,0 +1,71 @@
+// Measurement aid for the benchmark: what int8 rate do the matrix cores of THIS chip sustain
+// when nothing else happens?  A register-only loop of independent v_mfma_i32_32x32x32_i8 (no
+// LDS, no memory), two wavefronts per SIMD, with either constant or pseudo-random operands.
+// The two differ markedly on MI355X (the clock drops under the switching power of real data),
+// which is the context the roofline fraction of the GEMM kernel has to be read in.
+#include "oz_common.h"
+
+namespace oz {
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+__global__ __launch_bounds__(512) void mfma_loop_kernel(int iters, int random_operands, int *sink)
+{
+    unsigned x = threadIdx.x * 2654435761u + blockIdx.x * 40503u + 17u;
+    auto next = [&]() { x = x * 1664525u + 1013904223u; return (int)x; };
+    v4i a, b;
+    if (random_operands) {
+        a = v4i{next(), next(), next(), next()};
+        b = v4i{next(), next(), next(), next()};
+    } else {
+        a = v4i{0x01010101, 0x01010101, 0x01010101, 0x01010101};
+        b = v4i{0x02020202, 0x02020202, 0x02020202, 0x02020202};
+    }
+    v16i acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, acc[i], 0, 0, 0);
+    }
+    int s = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s ^= acc[i][r];
+    if (s == 0x7fffffff) sink[0] = s;   // keeps the loop alive; practically never taken
+}
+
+}  // namespace
+}  // namespace oz
+
+extern "C" int ozimmu_measure_int8_ceiling(int random_operands, int *sink, float *tops, void *stream)
+{
+    if (!sink || !tops) return OZIMMU_BAD_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    int cus = 0;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+        return OZIMMU_HIP_ERROR;
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return OZIMMU_HIP_ERROR;
+    const int iters = 12000, wgs = cus * 4;     // about 50-70 ms: long enough for the clock to settle
+    int rc = OZIMMU_OK;
+    float ms = 0.f;
+    oz::mfma_loop_kernel<<<wgs, 512, 0, st>>>(iters / 8, random_operands, sink);   // warm-up
+    if (hipEventRecord(e0, st) != hipSuccess) rc = OZIMMU_HIP_ERROR;
+    oz::mfma_loop_kernel<<<wgs, 512, 0, st>>>(iters, random_operands, sink);
+    if (hipGetLastError() != hipSuccess) rc = OZIMMU_HIP_ERROR;
+    if (hipEventRecord(e1, st) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+        hipEventElapsedTime(&ms, e0, e1) != hipSuccess)
+        rc = OZIMMU_HIP_ERROR;
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rc == OZIMMU_OK) *tops = (float)(2.0 * 32 * 32 * 32 * 8.0 * iters * 8.0 * wgs / (ms * 1e-3) / 1e12);
+    return rc;
+}

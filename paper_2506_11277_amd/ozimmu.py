@@ -34,6 +34,7 @@ _SIGNATURES = {
                                         _c.c_void_p, _c.c_void_p]),
     "ozimmu_profile_start": (_c.c_int, [_c.c_int]),
     "ozimmu_profile_stop": (_c.c_int, [_c.POINTER(_c.c_int), _c.POINTER(_c.c_float)]),
+    "ozimmu_measure_int8_ceiling": (_c.c_int, [_c.c_int, _c.c_void_p, _c.POINTER(_c.c_float), _c.c_void_p]),
     "ozimmu_debug_diagonals": (_c.c_int, [_c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_void_p, _c.c_void_p,
                                           _c.c_void_p]),
     "ozimmu_debug_slice_product": (_c.c_int, [_c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_void_p, _c.c_int,
@@ -203,6 +204,16 @@ def profile_stop():
     if rc != OK:
         raise OzimmuError(rc, "profile_stop")
     return calls.value, {"scales": ms[0], "split": ms[1], "gemm": ms[2]}
+
+
+def measure_int8_ceiling(random_operands):
+    """Sustained int8 MFMA rate (TOP/s) of a register-only loop on the current device."""
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    tops = ctypes.c_float(0.0)
+    rc = lib().ozimmu_measure_int8_ceiling(int(bool(random_operands)), sink.data_ptr(), ctypes.byref(tops), _stream())
+    if rc != OK:
+        raise OzimmuError(rc, "measure_int8_ceiling")
+    return tops.value
 
 
 def debug_diagonals(m, n, k, s, workspace):

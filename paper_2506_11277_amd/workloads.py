@@ -78,6 +78,27 @@ def diag_scaled(n, kappa_d, seed, rotate=True):
     return A, B
 
 
+def lognormal_device(m, n, k, phi, seed, device="cuda"):
+    """Same recipe as lognormal(), drawn on the GPU with torch's generator (for inputs too large to
+    draw on the host in reasonable time).  Returns column-major torch tensors; a different random
+    stream than lognormal(), so the two are not interchangeable for a given seed."""
+    import torch
+    g = torch.Generator(device=device)
+    g.manual_seed(seed)
+
+    def draw(rows, cols):
+        out = torch.empty((cols, rows), dtype=torch.float64, device=device)   # column-major rows x cols
+        step = max(1, (1 << 26) // max(rows, 1))
+        for c0 in range(0, cols, step):
+            c1 = min(cols, c0 + step)
+            u = torch.rand((c1 - c0, rows), dtype=torch.float64, device=device, generator=g) - 0.5
+            z = torch.randn((c1 - c0, rows), dtype=torch.float64, device=device, generator=g)
+            out[c0:c1] = u * torch.exp(phi * z)
+        return out.t()
+
+    return draw(m, k), draw(k, n)
+
+
 # The five benchmark configurations: name -> (generator thunk, slice counts)
 CONFIGS = {
     "uniform_128": dict(m=128, n=128, k=128, gen=lambda: uniform(128, 128, 128, 1000), s=[3]),

@@ -1,0 +1,85 @@
+"""GPU parity at the full sizes of the benchmark configurations, in the launch configuration
+bench.py times (same entry point, same workspace sizing).  The oracle cannot form a whole
+8192^3 product, but every row of A and column of B carries its own scale, so any sub-block
+C[rows, cols] is exactly the product of A[rows, :] and B[:, cols]: the oracle computes sampled
+sub-blocks one by one and the GPU's entries must match them bit for bit."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+from oracle import oracle
+from paper_2506_11277_amd import ozimmu, workloads
+
+
+def sample_indices(n, seed, count=20):
+    rng = np.random.default_rng(seed)
+    fixed = [0, 1, 31, 32, 33, 63, 64, 127, 128, 129, 255, 256, n // 2, n - 129, n - 128, n - 65, n - 33, n - 2, n - 1]
+    idx = sorted(set(i for i in fixed if 0 <= i < n) | set(rng.integers(0, n, size=count).tolist()))
+    return np.array(idx, dtype=np.int64)
+
+
+def check_sampled(dA, dB, s, tag):
+    m, k = dA.shape
+    n = dB.shape[1]
+    ws = ozimmu.alloc_workspace(m, n, k, s)
+    C = ozimmu.dgemm(dA, dB, s, workspace=ws, check_finite=True)
+    rows, cols = sample_indices(m, 1), sample_indices(n, 2)
+    tr, tc = torch.as_tensor(rows, device="cuda"), torch.as_tensor(cols, device="cuda")
+    As = dA[tr, :].cpu().numpy()
+    Bs = dB[:, tc].cpu().numpy()
+    want, eA, eB = oracle.dgemm(As, Bs, s, return_exponents=True)
+    got = C[tr][:, tc].cpu().numpy()
+    gA, gB = ozimmu.get_exponents(m, n, k, s, ws)
+    assert np.array_equal(gA[tr].cpu().numpy(), eA) and np.array_equal(gB[tc].cpu().numpy(), eB), tag
+    diff = np.abs(got - want)
+    rel = float(np.max(np.where(diff == 0, 0.0, diff / np.abs(want))))
+    assert rel <= 1e-15, f"{tag}: relative difference {rel:.3e}"
+    assert np.array_equal(got, want), f"{tag}: not bit-identical (rel {rel:.3e})"
+    # a second run is bit-identical everywhere (fixed summation order, no atomics on C)
+    C2 = ozimmu.dgemm(dA, dB, s, workspace=ws)
+    assert bool(torch.equal(C, C2)), f"{tag}: run-to-run difference"
+    return C
+
+
+def test_full_size_pow2_scaled_8192():
+    cfg = workloads.CONFIGS["pow2_scaled_8192"]
+    A, B = cfg["gen"]()
+    dA, dB = ozimmu.to_colmajor(A), ozimmu.to_colmajor(B)
+    for s in (2, 7, 9):
+        print("pow2_scaled_8192 s =", s, flush=True)
+        check_sampled(dA, dB, s, f"pow2_scaled_8192 s={s}")
+
+
+def test_power_of_two_scaling_is_removed_exactly_at_full_size():
+    # the row / column scalings of this workload only shift exponents: C must equal the product of
+    # the unscaled base matrices times the same powers of two, bit for bit
+    m = n = k = 2048
+    A, B = workloads.pow2_scaled(m, n, k, 30, 77)
+    ea = np.floor(np.log2(np.abs(A).max(axis=1))).astype(np.int64)
+    eb = np.floor(np.log2(np.abs(B).max(axis=0))).astype(np.int64)
+    A0 = A * np.ldexp(1.0, -ea)[:, None]
+    B0 = B * np.ldexp(1.0, -eb)[None, :]
+    C = ozimmu.dgemm(ozimmu.to_colmajor(A), ozimmu.to_colmajor(B), 7).cpu().numpy()
+    C0 = ozimmu.dgemm(ozimmu.to_colmajor(A0), ozimmu.to_colmajor(B0), 7).cpu().numpy()
+    assert np.array_equal(C, C0 * np.ldexp(1.0, ea)[:, None] * np.ldexp(1.0, eb)[None, :])
+
+
+def test_full_size_lognormal_4096():
+    cfg = workloads.CONFIGS["lognormal_4096"]
+    A, B = cfg["gen"]()
+    dA, dB = ozimmu.to_colmajor(A), ozimmu.to_colmajor(B)
+    s_est, status, kA, kB = ozimmu.estimate_slices(dA, dB, 2.0 ** -53)
+    assert (s_est, status, kA, kB) == oracle.estimate_slices(A, B, 2.0 ** -53, s_max=ozimmu.MAX_SLICES)
+    for s in sorted(set(cfg["s"] + [s_est])):
+        print("lognormal_4096 s =", s, flush=True)
+        check_sampled(dA, dB, s, f"lognormal_4096 s={s}")
+
+
+def test_full_size_long_k_forces_k_blocking():
+    # k = 262144: a single int32 sum would overflow (k * 127^2 > 2^31); inputs drawn on the device
+    dA, dB = workloads.lognormal_device(2048, 2048, 262144, 2.0, 1004)
+    print("long-k inputs ready", flush=True)
+    check_sampled(dA, dB, 7, "lognormal_longk s=7")
