@@ -97,6 +97,12 @@ def main():
     split_bytes = (8.0 + s) * (m * k + k * n)
     scales_bytes = 8.0 * (m * k + k * n)
 
+    traffic = args.traffic_bytes
+    if traffic is None:
+        tfile = os.path.join(ROOT, "paper_2506_11277_amd", "measured_traffic.json")
+        if os.path.exists(tfile):
+            traffic = json.load(open(tfile)).get(f"{args.workload}:{s}")
+
     out = {
         "metric": "effective FP64 TFLOP/s (2mnk/t) vs slices s; % of int8 MFMA peak",
         "value": flops / dt / 1e12,
@@ -118,7 +124,7 @@ def main():
             "peak": INT8_PEAK_TOPS,
             "unit": "TOP/s",
             "frac": int8_tops / INT8_PEAK_TOPS,
-            "traffic": args.traffic_bytes,
+            "traffic": traffic,
             "ms": phases["gemm"],
         },
         "phases_ms": phases,
