@@ -156,8 +156,10 @@ int ozimmu_dgemm(int m, int n, int k, const double *A, int lda, const double *B,
     OZ_TRY(launch_split('A', m, k, A, lda, s, eA, pA, OZIMMU_LAYOUT_MFMA, st));
     OZ_TRY(launch_split('B', k, n, B, ldb, s, eB, pB, OZIMMU_LAYOUT_MFMA, st));
     prof_mark(2, st);
-    if (fused_applicable(s, k))
-        OZ_TRY(launch_gemm_fused(m, n, w.kp, s, pA, pB, eA, eB, C, ldc, nullptr, st));
+    if (fused_single_block(s, k))
+        OZ_TRY(launch_gemm_fused(m, n, w.kp, s, pA, pB, eA, eB, C, ldc, nullptr, nullptr, st));
+    else if (s <= fused_max_slices())
+        OZ_TRY(launch_gemm_fused(m, n, w.kp, s, pA, pB, eA, eB, C, ldc, nullptr, (long long *)(ws + w.off_totals), st));
     else
         OZ_TRY(launch_gemm_generic(m, n, w.kp, s, pA, pB, eA, eB, C, ldc, 0, 0, 0, w.kp / kFrag, nullptr, st));
     prof_mark(3, st);
@@ -224,11 +226,11 @@ int ozimmu_get_exponents(int m, int n, int k, int s, const void *workspace, int3
 
 int ozimmu_debug_diagonals(int m, int n, int k, int s, const void *workspace, int32_t *D, void *stream)
 {
-    if (m <= 0 || n <= 0 || k < 0 || !workspace || !D || !fused_applicable(s, k)) return OZIMMU_BAD_ARG;
+    if (m <= 0 || n <= 0 || k < 0 || !workspace || !D || !fused_single_block(s, k)) return OZIMMU_BAD_ARG;
     const Workspace w = carve(m, n, k, s);
     const char *ws = (const char *)workspace;
     OZ_TRY(launch_gemm_fused(m, n, w.kp, s, (const int8_t *)(ws + w.off_planesA), (const int8_t *)(ws + w.off_planesB),
-                             nullptr, nullptr, nullptr, m, D, (hipStream_t)stream));
+                             nullptr, nullptr, nullptr, m, D, nullptr, (hipStream_t)stream));
     return OZIMMU_OK;
 }
 

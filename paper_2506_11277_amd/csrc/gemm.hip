@@ -56,7 +56,12 @@ __device__ __forceinline__ void tile_of_block(int b, int nb, int tiles_m, int ti
 // waits on them (vmcnt) are placed by hand below.
 //   S      slices (compile time: the pair loop is fully unrolled)
 //   KB32   32-deep k-blocks per LDS stage
-//   DUMP   write the int32 diagonal sums instead of C (test hook)
+//   MODE   kPlain: whole contraction in int32 (needs s * k * 127^2 < 2^31)
+//          kDump:  as kPlain, but write the int32 diagonal sums instead of C (test hook)
+//          kBlocked: any k.  The contraction is cut into k-blocks short enough for int32; at the end
+//                  of each block the diagonal sums are added, exactly, into int64 totals kept in a
+//                  per-tile scratch area in HBM (read-modify-write by the lanes that own them, so no
+//                  atomics and a fixed result), and the accumulators restart from zero
 
 // 16 bytes per lane: global (sbase + voff)  ->  LDS (ldsaddr + lane * 16); ldsaddr is wavefront-uniform
 __device__ __forceinline__ void lds_dma16(const void *sbase, unsigned voff, unsigned ldsaddr)
@@ -71,15 +76,20 @@ __device__ __forceinline__ void wait_vmcnt()
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-template <int S, int WVM, int WVN, int WMF, int WNF, int KB32, int NSTAGE, bool DUMP>
+enum FusedMode { kPlain = 0, kDump = 1, kBlocked = 2 };
+
+template <int S, int WVM, int WVN, int WMF, int WNF, int KB32, int NSTAGE, int MODE>
 __global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t *__restrict__ pA,
                                                                     const int8_t *__restrict__ pB,
                                                                     const int32_t *__restrict__ eA,
                                                                     const int32_t *__restrict__ eB,
                                                                     double *__restrict__ C, int ldc, int m, int n,
                                                                     int KB, int tiles_m, int tiles_n,
-                                                                    int32_t *__restrict__ dump)
+                                                                    int32_t *__restrict__ dump,
+                                                                    long long *__restrict__ totals,
+                                                                    int stages_per_block)
 {
+    constexpr bool DUMP = MODE == kDump;
     constexpr int NW = WVM * WVN;                      // wavefronts
     constexpr int FA = WVM * WMF, FB = WVN * WNF;      // fragment rows per work-group tile along m / n
     constexpr int CHUNK = KB32 * S * kFragBytes;       // bytes of one fragment row per stage (contiguous in HBM)
@@ -128,6 +138,11 @@ __global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t
                 for (int r = 0; r < 16; ++r) acc[a][i][j][r] = 0;
 
     const int nst = KB / KB32;
+    // k-blocked mode: this lane's slots in the int64 totals of its tile, [tile][wavefront][a][i][j][r][lane]
+    long long *tot = nullptr;
+    if (MODE == kBlocked)
+        tot = totals + ((size_t)(tm * tiles_n + tn) * NW + wave) * (size_t)(S * WMF * WNF * 16 * 64) + lane;
+    const bool spilled = MODE == kBlocked && nst > stages_per_block;   // at least one block went to the totals
     issue_stage(0, 0);
     if (NSTAGE == 3 && nst > 1) {
         issue_stage(1, 1);
@@ -171,6 +186,24 @@ __global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t
         if (NSTAGE == 3 && ahead) wait_keep1(); else wait_vmcnt<0>();
         __syncthreads();
         buf = buf + 1 == NSTAGE ? 0 : buf + 1;
+        if (MODE == kBlocked && st + 1 < nst && (st + 1) % stages_per_block == 0) {
+            // end of a k-block: totals (+)= accumulators, accumulators = 0
+            const bool first = st + 1 == stages_per_block;
+#pragma unroll
+            for (int a = 0; a < S; ++a)
+#pragma unroll
+                for (int i = 0; i < WMF; ++i)
+#pragma unroll
+                    for (int j = 0; j < WNF; ++j)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            long long *t = tot + ((((size_t)a * WMF + i) * WNF + j) * 16 + r) * 64;
+                            long long v = acc[a][i][j][r];
+                            if (!first) v += *t;
+                            *t = v;
+                            acc[a][i][j][r] = 0;
+                        }
+        }
     }
 
     // epilogue: accumulator register r of lane holds  (n_local, m_local) = (8*(r/4) + 4*(lane/32) + r%4, lane%32)
@@ -192,8 +225,17 @@ __global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t
                 } else {
                     double sum = 0.0;
 #pragma unroll
-                    for (int a = 0; a < S; ++a)
-                        sum = sum + (double)acc[a][i][j][r] * __builtin_ldexp(1.0, -kSliceBits * (a + 2));
+                    for (int a = 0; a < S; ++a) {
+                        double dd;
+                        if (MODE == kBlocked) {
+                            long long v = acc[a][i][j][r];
+                            if (spilled) v += tot[((((size_t)a * WMF + i) * WNF + j) * 16 + r) * 64];
+                            dd = (double)v;          // exact: |v| <= s * k * 127^2 < 2^53
+                        } else {
+                            dd = (double)acc[a][i][j][r];
+                        }
+                        sum = sum + dd * __builtin_ldexp(1.0, -kSliceBits * (a + 2));
+                    }
                     C[mi + (size_t)nj * ldc] = ldexp(sum, ea + eB[nj]);
                 }
             }
@@ -336,16 +378,24 @@ struct FusedCfg {
 
 constexpr int kFusedMaxS = 12;   // 16 accumulator registers per diagonal; beyond 12 the wavefront's 256 run out
 
-template <int S, bool DUMP>
+// Tile geometry of the fused kernel for a slice count (used for the size of the k-block totals).
+template <int S>
+void fused_tile(int &tm, int &tn)
+{
+    tm = 32 * FusedCfg<S>::WVM * FusedCfg<S>::WMF;
+    tn = 32 * FusedCfg<S>::WVN * FusedCfg<S>::WNF;
+}
+
+template <int S, int MODE>
 hipError_t launch_fused_s(int m, int n, int kp, const int8_t *pA, const int8_t *pB, const int32_t *eA,
-                          const int32_t *eB, double *C, int ldc, int32_t *dump, hipStream_t st)
+                          const int32_t *eB, double *C, int ldc, int32_t *dump, long long *totals, hipStream_t st)
 {
     using Cfg = FusedCfg<S>;
     constexpr int TM = 32 * Cfg::WVM * Cfg::WMF, TN = 32 * Cfg::WVN * Cfg::WNF;
     constexpr int STAGE = Cfg::FR * Cfg::KB32 * S * kFragBytes;
     static_assert(Cfg::NSTAGE * STAGE <= kLdsBytes, "LDS ring too large");
     static_assert(kPad % TM == 0 && kPad % TN == 0 && (kPad / kFrag) % Cfg::KB32 == 0, "tiles must divide the padding");
-    auto kern = gemm_fused_kernel<S, Cfg::WVM, Cfg::WVN, Cfg::WMF, Cfg::WNF, Cfg::KB32, Cfg::NSTAGE, DUMP>;
+    auto kern = gemm_fused_kernel<S, Cfg::WVM, Cfg::WVN, Cfg::WMF, Cfg::WNF, Cfg::KB32, Cfg::NSTAGE, MODE>;
     static bool configured = false;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -354,18 +404,20 @@ hipError_t launch_fused_s(int m, int n, int kp, const int8_t *pA, const int8_t *
         configured = true;
     }
     const int tiles_m = (m + TM - 1) / TM, tiles_n = (n + TN - 1) / TN;
-    kern<<<tiles_m * tiles_n, 64 * Cfg::WVM * Cfg::WVN, Cfg::NSTAGE * STAGE, st>>>(pA, pB, eA, eB, C, ldc, m, n,
-                                                                                   kp / kFrag, tiles_m, tiles_n, dump);
+    // longest k-block whose s products per diagonal cannot overflow int32, in whole stages
+    const int stages_per_block = (int)(kMaxInt32K / S / kFrag) / Cfg::KB32;
+    kern<<<tiles_m * tiles_n, 64 * Cfg::WVM * Cfg::WVN, Cfg::NSTAGE * STAGE, st>>>(
+        pA, pB, eA, eB, C, ldc, m, n, kp / kFrag, tiles_m, tiles_n, dump, totals, stages_per_block);
     return hipGetLastError();
 }
 
-template <bool DUMP>
+template <int MODE>
 hipError_t dispatch_fused(int s, int m, int n, int kp, const int8_t *pA, const int8_t *pB, const int32_t *eA,
-                          const int32_t *eB, double *C, int ldc, int32_t *dump, hipStream_t st)
+                          const int32_t *eB, double *C, int ldc, int32_t *dump, long long *totals, hipStream_t st)
 {
     switch (s) {
 #define OZ_CASE(S_) \
-    case S_: return launch_fused_s<S_, DUMP>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, st);
+    case S_: return launch_fused_s<S_, MODE>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, st);
         OZ_CASE(1) OZ_CASE(2) OZ_CASE(3) OZ_CASE(4) OZ_CASE(5) OZ_CASE(6) OZ_CASE(7) OZ_CASE(8) OZ_CASE(9) OZ_CASE(10) OZ_CASE(11) OZ_CASE(12)
 #undef OZ_CASE
     }
@@ -376,18 +428,32 @@ hipError_t dispatch_fused(int s, int m, int n, int kp, const int8_t *pA, const i
 
 int fused_max_slices() { return kFusedMaxS; }
 
-bool fused_applicable(int s, int k)
+bool fused_single_block(int s, int k)
 {
     // the longest diagonal has s products of k terms each, every term at most 127^2 in magnitude
     return s >= 1 && s <= kFusedMaxS && (long long)s * (long long)(k > 0 ? k : 1) <= kMaxInt32K;
 }
 
+size_t fused_totals_bytes(int s, int m, int n, int k)
+{
+    if (s < 1 || s > kFusedMaxS || fused_single_block(s, k) || m <= 0 || n <= 0) return 0;
+    int tm = 128, tn = 128;
+    switch (s) {
+#define OZ_CASE(S_) case S_: fused_tile<S_>(tm, tn); break;
+        OZ_CASE(1) OZ_CASE(2) OZ_CASE(3) OZ_CASE(4) OZ_CASE(5) OZ_CASE(6) OZ_CASE(7) OZ_CASE(8) OZ_CASE(9) OZ_CASE(10) OZ_CASE(11) OZ_CASE(12)
+#undef OZ_CASE
+    }
+    const size_t tiles = (size_t)((m + tm - 1) / tm) * ((n + tn - 1) / tn);
+    return tiles * (size_t)s * tm * tn * sizeof(long long);
+}
+
 hipError_t launch_gemm_fused(int m, int n, int kp, int s, const int8_t *pA, const int8_t *pB, const int32_t *eA,
-                             const int32_t *eB, double *C, int ldc, int32_t *dump, hipStream_t st)
+                             const int32_t *eB, double *C, int ldc, int32_t *dump, long long *totals, hipStream_t st)
 {
     if (m <= 0 || n <= 0) return hipSuccess;
-    return dump ? dispatch_fused<true>(s, m, n, kp, pA, pB, eA, eB, C, ldc, dump, st)
-                : dispatch_fused<false>(s, m, n, kp, pA, pB, eA, eB, C, ldc, dump, st);
+    if (dump) return dispatch_fused<kDump>(s, m, n, kp, pA, pB, eA, eB, C, ldc, dump, nullptr, st);
+    if (totals) return dispatch_fused<kBlocked>(s, m, n, kp, pA, pB, eA, eB, C, ldc, nullptr, totals, st);
+    return dispatch_fused<kPlain>(s, m, n, kp, pA, pB, eA, eB, C, ldc, nullptr, nullptr, st);
 }
 
 hipError_t launch_gemm_generic(int m, int n, int kp, int s, const int8_t *pA, const int8_t *pB, const int32_t *eA,

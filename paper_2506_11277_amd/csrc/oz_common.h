@@ -19,6 +19,8 @@ constexpr long long kMaxInt32K = 2147483647LL / (127LL * 127LL);   // 133144
 
 inline int round_up(int x, int q) { return (x + q - 1) / q * q; }
 
+size_t fused_totals_bytes(int s, int m, int n, int k);
+
 // Workspace carve-up (all offsets multiples of 256 bytes).
 struct Workspace {
     int mp, np, kp;                 // padded extents
@@ -27,6 +29,7 @@ struct Workspace {
     size_t off_maxB, off_minB;      // u64[np]
     size_t off_expA, off_expB;      // i32[mp], i32[np]
     size_t off_planesA, off_planesB;
+    size_t off_totals;              // int64 per-tile diagonal totals of the k-blocked fused GEMM (may be empty)
     size_t total;
 };
 
@@ -47,6 +50,7 @@ inline Workspace carve(int m, int n, int k, int s)
     w.off_expB = take(4 * (size_t)w.np);
     w.off_planesA = take((size_t)s * w.mp * w.kp);
     w.off_planesB = take((size_t)s * w.np * w.kp);
+    w.off_totals = take(fused_totals_bytes(s, m, n, k));
     w.total = off;
     return w;
 }
@@ -72,11 +76,14 @@ hipError_t launch_split(char side, int rows, int cols, const double *X, int ldx,
 // ---- launchers implemented in gemm.hip ---------------------------------------------------
 // largest s the fused (all diagonals in registers) kernel handles
 int fused_max_slices();
-// true when the fused kernel can run this problem without int32 overflow
-bool fused_applicable(int s, int k);
+// true when the fused kernel can keep the whole contraction in int32 (s * k * 127^2 < 2^31)
+bool fused_single_block(int s, int k);
+// bytes of int64 per-tile totals the fused kernel needs when it has to cut k into blocks (else 0)
+size_t fused_totals_bytes(int s, int m, int n, int k);
+// dump != null: write int32 diagonal sums (single block only); totals != null: k-blocked mode
 hipError_t launch_gemm_fused(int m, int n, int kp, int s, const int8_t *pA, const int8_t *pB,
                              const int32_t *eA, const int32_t *eB, double *C, int ldc,
-                             int32_t *dump, hipStream_t st);
+                             int32_t *dump, long long *totals, hipStream_t st);
 hipError_t launch_gemm_generic(int m, int n, int kp, int s, const int8_t *pA, const int8_t *pB,
                                const int32_t *eA, const int32_t *eB, double *C, int ldc,
                                int pair_l, int pair_h, int kb_begin, int kb_end, int32_t *dump,
