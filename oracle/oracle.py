@@ -119,6 +119,46 @@ def dgemm(A, B, s, t=7, order=0, full=False, return_exponents=False):
     return C.T
 
 
+def dgemm2(A, B, sA, sB, t=7, order=0, full=False, return_exponents=False):
+    """C ~ A @ B with sA slices of A and sB slices of B (products with l + h <= max(sA, sB) + 1)."""
+    A = _f64(A)
+    B = _f64(B)
+    m, k = A.shape
+    k2, n = B.shape
+    assert k == k2
+    C = np.zeros((n, m), dtype=np.float64)
+    eA = np.zeros(m, dtype=np.int32)
+    eB = np.zeros(n, dtype=np.int32)
+    _check(lib().oz_oracle_dgemm2(m, n, k, _p(A, ctypes.c_double), max(m, 1), _p(B, ctypes.c_double),
+                                  max(k, 1), _p(C, ctypes.c_double), max(m, 1), sA, sB, t, order, int(full),
+                                  _p(eA, ctypes.c_int32), _p(eB, ctypes.c_int32)))
+    if return_exponents:
+        return C.T, eA, eB
+    return C.T
+
+
+def chi(sA, sB):
+    return lib().oz_oracle_chi(sA, sB)
+
+
+def estimate_slices2(A, B, tol, t=7, s_max=32):
+    """Returns (sA, sB, status, kappa_A, kappa_B): cheapest pair meeting the tolerance."""
+    A = _f64(A)
+    B = _f64(B)
+    m, k = A.shape
+    k2, n = B.shape
+    assert k == k2
+    sA = ctypes.c_int(0)
+    sB = ctypes.c_int(0)
+    kA = ctypes.c_double(0.0)
+    kB = ctypes.c_double(0.0)
+    rc = _check(lib().oz_oracle_estimate_slices2(m, n, k, _p(A, ctypes.c_double), max(m, 1),
+                                                 _p(B, ctypes.c_double), max(k, 1), ctypes.c_double(tol), t,
+                                                 s_max, ctypes.byref(sA), ctypes.byref(sB), ctypes.byref(kA),
+                                                 ctypes.byref(kB)), allow=(UNREACHABLE,))
+    return sA.value, sB.value, rc, kA.value, kB.value
+
+
 def kappa(side, X):
     X = _f64(X)
     rows, cols = X.shape

@@ -160,7 +160,12 @@ int oz_oracle_slice_product(int m, int n, int k, const int8_t *Al, const int8_t 
 }
 
 /*
- * C ~ A B by Algorithm 1 with s slices of t bits.
+ * C ~ A B by Algorithm 1 with sA slices of A and sB slices of B, t bits each.
+ *
+ * Products computed (full = 0): A_(l) B^(h) with l <= sA, h <= sB and l + h <= max(sA, sB) + 1 --
+ * Algorithm 1's rule l + h <= s + 1 in the extension to different slice counts stated at the
+ * start of the subsection "Reduction in number of products".  full = 1: all sA * sB products
+ * (subsection "Computation of all products").
  *
  * order 0  "by diagonals" (the accumulation order analysed in the subsection
  *          "Accumulation in floating-point arithmetic" and the first tweak of
@@ -169,34 +174,33 @@ int oz_oracle_slice_product(int m, int n, int k, const int8_t *Al, const int8_t 
  *          d = 2, 3, ..., one binary64 rounding per addition.
  * order 1  literal loop nest of Algorithm 1: l outer, h inner, one binary64
  *          addition per product.
- * full 0   only products with l + h <= s + 1 (Algorithm 1)
- * full 1   all s^2 products (subsection "Computation of all products").
  *
  * Final step: C = diag(alpha) S diag(beta), i.e. ldexp(S_ij, eA_i + eB_j).
  * Optional outputs (may be NULL): eA[m], eB[n].
  */
-int oz_oracle_dgemm(int m, int n, int k, const double *A, int lda, const double *B, int ldb,
-                    double *C, int ldc, int s, int t, int order, int full,
-                    int32_t *eA_out, int32_t *eB_out)
+int oz_oracle_dgemm2(int m, int n, int k, const double *A, int lda, const double *B, int ldb,
+                     double *C, int ldc, int sA, int sB, int t, int order, int full,
+                     int32_t *eA_out, int32_t *eB_out)
 {
-    if (m < 0 || n < 0 || k < 0 || s < 1 || s > OZ_ORACLE_MAX_SLICES || t < 1 || t > 7 ||
-        lda < (m > 1 ? m : 1) || ldb < (k > 1 ? k : 1) || ldc < (m > 1 ? m : 1) ||
+    if (m < 0 || n < 0 || k < 0 || sA < 1 || sA > OZ_ORACLE_MAX_SLICES || sB < 1 || sB > OZ_ORACLE_MAX_SLICES ||
+        t < 1 || t > 7 || lda < (m > 1 ? m : 1) || ldb < (k > 1 ? k : 1) || ldc < (m > 1 ? m : 1) ||
         (order != 0 && order != 1) || (full != 0 && full != 1)) return OZ_ORACLE_BAD_ARG;
     if (m == 0 || n == 0) return OZ_ORACLE_OK;
 
     int32_t *eA = malloc(sizeof(int32_t) * (size_t)m);
     int32_t *eB = malloc(sizeof(int32_t) * (size_t)n);
-    int8_t *pa = malloc((size_t)s * m * (k > 0 ? k : 1));
-    int8_t *pb = malloc((size_t)s * n * (k > 0 ? k : 1));
+    int8_t *pa = malloc((size_t)sA * m * (k > 0 ? k : 1));
+    int8_t *pb = malloc((size_t)sB * n * (k > 0 ? k : 1));
     int rc = OZ_ORACLE_BAD_ARG;
     if (!eA || !eB || !pa || !pb) goto done;
     if ((rc = oz_oracle_exponents('A', m, k, A, lda, eA))) goto done;
     if ((rc = oz_oracle_exponents('B', k, n, B, ldb, eB))) goto done;
-    if ((rc = oz_oracle_split('A', m, k, A, lda, s, t, eA, pa))) goto done;
-    if ((rc = oz_oracle_split('B', k, n, B, ldb, s, t, eB, pb))) goto done;
+    if ((rc = oz_oracle_split('A', m, k, A, lda, sA, t, eA, pa))) goto done;
+    if ((rc = oz_oracle_split('B', k, n, B, ldb, sB, t, eB, pb))) goto done;
 
     const size_t planeA = (size_t)m * k, planeB = (size_t)k * n;
-    const int dmax = full ? 2 * s : s + 1;
+    const int smax = sA > sB ? sA : sB;
+    const int dmax = full ? sA + sB : smax + 1;     /* largest l + h of a computed product */
 
 #pragma omp parallel
     {
@@ -209,9 +213,9 @@ int oz_oracle_dgemm(int m, int n, int k, const double *A, int lda, const double 
             if (order == 0) {
                 for (int d = 2; d <= dmax; ++d) {
                     for (int i = 0; i < m; ++i) D[i] = 0;
-                    for (int l = 1; l <= s; ++l) {
+                    for (int l = 1; l <= sA; ++l) {
                         int h = d - l;
-                        if (h < 1 || h > s) continue;
+                        if (h < 1 || h > sB) continue;
                         const int8_t *al = pa + (size_t)(l - 1) * planeA;
                         const int8_t *bh = pb + (size_t)(h - 1) * planeB + (size_t)j * k;
                         for (int kk = 0; kk < k; ++kk) {
@@ -223,9 +227,8 @@ int oz_oracle_dgemm(int m, int n, int k, const double *A, int lda, const double 
                     for (int i = 0; i < m; ++i) S[i] = S[i] + ldexp((double)D[i], -d * t);
                 }
             } else {
-                for (int l = 1; l <= s; ++l) {
-                    int hmax = full ? s : s - l + 1;
-                    for (int h = 1; h <= hmax; ++h) {
+                for (int l = 1; l <= sA; ++l) {
+                    for (int h = 1; h <= sB && l + h <= dmax; ++h) {
                         const int8_t *al = pa + (size_t)(l - 1) * planeA;
                         const int8_t *bh = pb + (size_t)(h - 1) * planeB + (size_t)j * k;
                         for (int i = 0; i < m; ++i) p[i] = 0;
@@ -248,6 +251,25 @@ int oz_oracle_dgemm(int m, int n, int k, const double *A, int lda, const double 
 done:
     free(eA); free(eB); free(pa); free(pb);
     return rc;
+}
+
+/* Algorithm 1 as printed: the same number s of slices for A and B. */
+int oz_oracle_dgemm(int m, int n, int k, const double *A, int lda, const double *B, int ldb,
+                    double *C, int ldc, int s, int t, int order, int full,
+                    int32_t *eA_out, int32_t *eB_out)
+{
+    return oz_oracle_dgemm2(m, n, k, A, lda, B, ldb, C, ldc, s, s, t, order, full, eA_out, eB_out);
+}
+
+/*
+ * Number of products the reduced variant computes,
+ *   chi(sA, sB) = sm (2 sM - sm + 1) / 2,  sM = max, sm = min
+ * (subsection "Reduction in number of products").
+ */
+int oz_oracle_chi(int sA, int sB)
+{
+    int sM = sA > sB ? sA : sB, sm = sA > sB ? sB : sA;
+    return sm * (2 * sM - sm + 1) / 2;
 }
 
 /*
@@ -302,4 +324,38 @@ int oz_oracle_estimate_slices(int m, int n, int k, const double *A, int lda, con
     }
     *s_out = s_max;
     return OZ_ORACLE_UNREACHABLE;
+}
+
+/*
+ * Slice counts (sA, sB), 1 <= sA, sB <= s_max, that meet
+ *     kappa_A 2^{-sA t} + kappa_B 2^{-sB t} <= tol
+ * with the fewest products chi(sA, sB): the recipe at the end of the "Discussion" subsection of
+ * Sect. 4 (evaluate the left-hand side of eq. (err-bound) for small sA, sB and keep the
+ * cheapest combination that delivers the bound).  Ties: smaller sA + sB, then smaller sA.
+ * None feasible: (s_max, s_max) and the return code says so.
+ */
+int oz_oracle_estimate_slices2(int m, int n, int k, const double *A, int lda, const double *B, int ldb,
+                               double tol, int t, int s_max, int *sA_out, int *sB_out,
+                               double *kappaA_out, double *kappaB_out)
+{
+    if (!(tol > 0.0) || t < 1 || t > 7 || s_max < 1) return OZ_ORACLE_BAD_ARG;
+    double kA, kB;
+    int rc;
+    if ((rc = oz_oracle_kappa('A', m, k, A, lda, &kA))) return rc;
+    if ((rc = oz_oracle_kappa('B', k, n, B, ldb, &kB))) return rc;
+    if (kappaA_out) *kappaA_out = kA;
+    if (kappaB_out) *kappaB_out = kB;
+    int best = 0, bA = s_max, bB = s_max;
+    for (int sA = 1; sA <= s_max; ++sA)
+        for (int sB = 1; sB <= s_max; ++sB) {
+            double lhs = ldexp(kA, -sA * t) + ldexp(kB, -sB * t);
+            if (!(lhs <= tol)) continue;
+            int c = oz_oracle_chi(sA, sB);
+            int better = !best || c < oz_oracle_chi(bA, bB) ||
+                         (c == oz_oracle_chi(bA, bB) && (sA + sB < bA + bB || (sA + sB == bA + bB && sA < bA)));
+            if (better) { best = 1; bA = sA; bB = sB; }
+        }
+    *sA_out = bA;
+    *sB_out = bB;
+    return best ? OZ_ORACLE_OK : OZ_ORACLE_UNREACHABLE;
 }

@@ -71,24 +71,25 @@ def absmat(A):
     return [[abs(v) for v in row] for row in A]
 
 
-def diagonal_terms(A, B, s, t, full=False):
+def diagonal_terms(A, B, s, t, full=False, sB=None):
     """Exact value of each diagonal's contribution alpha beta^T o 2^{-dt} sum_{l+h=d} A_(l) B^(h),
     written with truncation operators only:  2^{-lt} alpha A_(l) = T_l(A) - T_{l-1}(A)  (this is
     eq. (slices-eq) read backwards).  Returns {d: matrix of Fractions}."""
     m, k, n = len(A), len(B), len(B[0])
+    sA, sB = s, (s if sB is None else sB)
     eA = block_exponents("A", A)
     eB = block_exponents("B", B)
     dA = {l: [[truncate(A[i][kk], eA[i], l, t) - truncate(A[i][kk], eA[i], l - 1, t) for kk in range(k)]
-              for i in range(m)] for l in range(1, s + 1)}
+              for i in range(m)] for l in range(1, sA + 1)}
     dB = {h: [[truncate(B[kk][j], eB[j], h, t) - truncate(B[kk][j], eB[j], h - 1, t) for j in range(n)]
-              for kk in range(k)] for h in range(1, s + 1)}
+              for kk in range(k)] for h in range(1, sB + 1)}
     out = {}
-    dmax = 2 * s if full else s + 1
+    dmax = sA + sB if full else max(sA, sB) + 1
     for d in range(2, dmax + 1):
         acc = [[Fraction(0)] * n for _ in range(m)]
-        for l in range(1, s + 1):
+        for l in range(1, sA + 1):
             h = d - l
-            if h < 1 or h > s:
+            if h < 1 or h > sB:
                 continue
             P = matmul(dA[l], dB[h])
             for i in range(m):
@@ -98,9 +99,10 @@ def diagonal_terms(A, B, s, t, full=False):
     return out, eA, eB
 
 
-def reduced_product_exact(A, B, s, t, full=False):
-    """C' of eq. (c-prime) (or C-tilde of eq. (wtc-expr) when full) as exact Fractions."""
-    terms, _, _ = diagonal_terms(A, B, s, t, full)
+def reduced_product_exact(A, B, s, t, full=False, sB=None):
+    """C' of eq. (c-prime) (or C-tilde of eq. (wtc-expr) when full) as exact Fractions;
+    s slices of A and sB (default s) slices of B."""
+    terms, _, _ = diagonal_terms(A, B, s, t, full, sB)
     m, n = len(A), len(B[0])
     C = [[Fraction(0)] * n for _ in range(m)]
     for d in sorted(terms):

@@ -435,3 +435,132 @@ def test_two_vector_example_needs_more_slices_when_badly_scaled():
         assert err(100, 8) > 1e-3
         assert err(100, 20) > 1e-14
         assert err(100, 24) < 8 * U
+
+
+# --------------------------------------------------------------------------- different slice counts
+
+def test_equal_slice_counts_reduce_to_algorithm_1():
+    A, B = workloads.lognormal(9, 8, 40, 2.0, 12)
+    for s in (1, 3, 8, 11):
+        for order in (0, 1):
+            for full in (False, True):
+                assert np.array_equal(oracle.dgemm2(A, B, s, s, order=order, full=full),
+                                      oracle.dgemm(A, B, s, order=order, full=full))
+
+
+@pytest.mark.parametrize("name,A,B", small_cases()[:4])
+@pytest.mark.parametrize("t,sA,sB", [(7, 1, 4), (7, 4, 1), (7, 2, 5), (7, 5, 3), (3, 2, 9), (4, 7, 3), (3, 6, 6)])
+def test_different_slice_counts_in_the_exact_regime(name, A, B, t, sA, sB):
+    # product set l <= sA, h <= sB, l + h <= max(sA, sB) + 1, written with truncation operators
+    k = A.shape[1]
+    assert math.ceil(math.log2(k)) + (max(sA, sB) + 1) * t + 1 <= 53
+    want = ex.reduced_product_exact(ex.frac_matrix(A), ex.frac_matrix(B), sA, t, sB=sB)
+    for order in (0, 1):
+        assert np.array_equal(oracle.dgemm2(A, B, sA, sB, t, order=order), to_float_matrix(want)), order
+    if math.ceil(math.log2(k)) + (sA + sB) * t + 1 <= 53:
+        want_full = ex.reduced_product_exact(ex.frac_matrix(A), ex.frac_matrix(B), sA, t, full=True, sB=sB)
+        assert np.array_equal(oracle.dgemm2(A, B, sA, sB, t, full=True), to_float_matrix(want_full))
+
+
+@pytest.mark.parametrize("sA,sB", [(3, 9), (9, 3), (8, 12), (13, 7), (1, 10)])
+def test_different_slice_counts_round_once_per_diagonal(sA, sB):
+    t = 7
+    A, B = workloads.lognormal(4, 5, 12, 2.0, 40 + sA)
+    terms, eA, eB = ex.diagonal_terms(ex.frac_matrix(A), ex.frac_matrix(B), sA, t, sB=sB)
+    assert sorted(terms) == list(range(2, max(sA, sB) + 2))
+    C = oracle.dgemm2(A, B, sA, sB, t)
+    for i in range(4):
+        for j in range(5):
+            S = 0.0
+            for d in sorted(terms):
+                term = terms[d][i][j] / Fraction(2) ** (eA[i] + eB[j])
+                f = float(term)
+                assert Fraction(f) == term
+                S = S + f
+            assert C[i, j] == math.ldexp(S, eA[i] + eB[j])
+
+
+@pytest.mark.parametrize("phi,sA,sB", [(0.5, 3, 6), (0.5, 6, 3), (2.0, 5, 9), (2.0, 9, 4), (4.0, 8, 12), (1.0, 1, 8)])
+def test_error_bounds_for_different_slice_counts(phi, sA, sB):
+    # sA <= sB: extra term 2^{-sB t} sA kA kB;  sA > sB: 2^{-sA t} sB kA kB
+    # (the two bounds at the end of the subsection "Reduction in number of products")
+    t = 7
+    A, B = workloads.lognormal(5, 6, 20, phi, seed=300 + sA * 17 + sB)
+    Af, Bf = ex.frac_matrix(A), ex.frac_matrix(B)
+    exact = ex.matmul(Af, Bf)
+    absprod = ex.matmul(ex.absmat(Af), ex.absmat(Bf))
+    kA, kB = ex.kappa("A", Af), ex.kappa("B", Bf)
+    wA, wB = Fraction(2) ** (-sA * t), Fraction(2) ** (-sB * t)
+    zeta = wA * kA + wB * kB + wA * wB * kA * kB
+    extra = (wB * sA if sA <= sB else wA * sB) * kA * kB
+    psi = max(sA, sB)
+    gamma = Fraction(psi) * Fraction(U) / (1 - Fraction(psi) * Fraction(U))
+    bound = zeta + extra + gamma * (1 + zeta + extra)
+    C = oracle.dgemm2(A, B, sA, sB, t)
+    for i in range(5):
+        for j in range(6):
+            assert abs(Fraction(float(C[i, j])) - exact[i][j]) <= bound * absprod[i][j]
+
+
+def test_well_scaled_operand_needs_a_single_slice():
+    # rows of A hold integers of magnitude <= 127 (times a power of two): A lives in its first slice,
+    # so one slice of A gives bit for bit what s slices give -- the flexibility the analysis points out
+    rng = np.random.default_rng(8)
+    A = rng.integers(-127, 128, size=(7, 30)) * np.ldexp(1.0, rng.integers(-20, 20, size=7))[:, None]
+    _, B = workloads.lognormal(7, 6, 30, 2.0, 9)
+    for s in (3, 8, 12):
+        ref = oracle.dgemm(A, B, s)
+        assert np.array_equal(oracle.dgemm2(A, B, 1, s), ref)
+        assert np.array_equal(oracle.dgemm2(A, B, 2, s), ref)
+        # and symmetrically for B
+        assert np.array_equal(oracle.dgemm2(B.T.copy(), A.T.copy(), s, 1), ref.T)
+
+
+def test_chi_counts_the_computed_products():
+    for sA in range(1, 10):
+        for sB in range(1, 10):
+            pairs = [(l, h) for l in range(1, sA + 1) for h in range(1, sB + 1) if l + h <= max(sA, sB) + 1]
+            assert oracle.chi(sA, sB) == len(pairs)
+    # the value of C identifies the set of products (every slice of the (0,0) entries equals 1)
+    t = 3
+    for sA, sB in ((2, 5), (5, 2), (4, 4), (1, 6)):
+        xa = float(sum(Fraction(2) ** (-l * t) for l in range(1, sA + 1)))
+        xb = float(sum(Fraction(2) ** (-l * t) for l in range(1, sB + 1)))
+        A = np.array([[xa, 0.75]])
+        B = np.array([[xb, 0.75], [0.0, 0.0]])
+        C = oracle.dgemm2(A, B, sA, sB, t)
+        want = sum(Fraction(2) ** (-(l + h) * t) for l in range(1, sA + 1) for h in range(1, sB + 1)
+                   if l + h <= max(sA, sB) + 1)
+        assert Fraction(float(C[0, 0])) == want
+
+
+def test_two_dimensional_estimator_against_brute_force():
+    t = 7
+    rng = np.random.default_rng(5)
+    for case in range(6):
+        A, B = workloads.lognormal(12, 10, 16, [0.2, 1.0, 3.0][case % 3], 60 + case)
+        if case >= 3:       # A well scaled (kappa_A = 2: equal magnitudes per row), B badly scaled
+            A = np.sign(A) * np.ldexp(1.0, rng.integers(-5, 6, size=A.shape[0]))[:, None]
+            _, B = workloads.lognormal(12, 10, 16, 3.0, 90 + case)
+        kA = Fraction(oracle.kappa("A", A))
+        kB = Fraction(oracle.kappa("B", B))
+        for tol in (1e-3, 1e-9, 1e-15):
+            sA, sB, rc, gA, gB = oracle.estimate_slices2(A, B, tol, t, s_max=32)
+            feas = [(a, b) for a in range(1, 33) for b in range(1, 33)
+                    if kA * Fraction(2) ** (-a * t) + kB * Fraction(2) ** (-b * t) <= Fraction(tol) * (1 - Fraction(2) ** -40)]
+            chi = lambda a, b: min(a, b) * (2 * max(a, b) - min(a, b) + 1) // 2
+            assert rc == oracle.OK and feas
+            best = min(chi(a, b) for a, b in feas)
+            assert chi(sA, sB) <= best                       # optimal cost (boundary cases aside)
+            assert kA * Fraction(2) ** (-sA * t) + kB * Fraction(2) ** (-sB * t) <= Fraction(tol) * (1 + Fraction(2) ** -40)
+            s1 = oracle.estimate_slices(A, B, tol, t)[0]
+            assert chi(sA, sB) <= chi(s1, s1)                # never more products than equal counts
+            if case >= 3 and tol < 1e-8:
+                assert sA < sB                               # the well scaled operand gets fewer slices
+    # swapping the roles of A and B swaps the answer
+    A, B = workloads.lognormal(6, 6, 10, 2.0, 5)
+    A = np.abs(A) + 1.0
+    r = oracle.estimate_slices2(A, B, 1e-12)
+    rT = oracle.estimate_slices2(B.T.copy(), A.T.copy(), 1e-12)
+    assert oracle.chi(r[0], r[1]) == oracle.chi(rT[0], rT[1])
+    assert oracle.estimate_slices2(A, B, 1e-300)[:3] == (32, 32, oracle.UNREACHABLE)
