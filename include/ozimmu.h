@@ -113,6 +113,30 @@ int ozimmu_dgemm(int m, int n, int k, const double *A, int lda, const double *B,
                  double *C, int ldc, int s, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The same with sA slices of A and sB slices of B (Sect. 4, subsection "Reduction in number of
+ * products": a well scaled operand needs fewer slices than a badly scaled one).  Products computed:
+ *   all_products = 0:  l <= sA, h <= sB, l + h <= max(sA, sB) + 1   (chi(sA, sB) of them)
+ *   all_products = 1:  all sA * sB                                   ("Computation of all products")
+ * accumulated by diagonals l + h = 2, 3, ... as in ozimmu_dgemm; ozimmu_dgemm(s) equals
+ * ozimmu_dgemm2(s, s, 0) bit for bit.  Workspace: ozimmu_workspace_bytes2(m, n, k, sA, sB, all_products).
+ */
+size_t ozimmu_workspace_bytes2(int m, int n, int k, int sA, int sB, int all_products);
+int ozimmu_dgemm2(int m, int n, int k, const double *A, int lda, const double *B, int ldb,
+                  double *C, int ldc, int sA, int sB, int all_products,
+                  void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Two-dimensional slice estimate ("Discussion" subsection of Sect. 4): among all 1 <= sA, sB <=
+ * OZIMMU_MAX_SLICES with  kappa_A 2^{-7 sA} + kappa_B 2^{-7 sB} <= tol  the pair with the fewest
+ * products chi(sA, sB) = sm (2 sM - sm + 1) / 2; ties go to the smaller sA + sB, then the smaller sA.
+ * Arguments and return codes as ozimmu_estimate_slices; none feasible: both = OZIMMU_MAX_SLICES and
+ * OZIMMU_UNREACHABLE.  SYNCHRONISES.
+ */
+int ozimmu_estimate_slices2(int m, int n, int k, const double *A, int lda, const double *B, int ldb,
+                            double tol, int *sA_out, int *sB_out, double *kappa,
+                            void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Waits for the stream and returns OZIMMU_NONFINITE if the last ozimmu_dgemm /
  * ozimmu_estimate_slices that used this workspace met a NaN or Inf, else OZIMMU_OK.
  */

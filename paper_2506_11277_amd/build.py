@@ -6,7 +6,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libozimmu.so")
-SOURCES = ["api.hip", "reduce.hip", "split.hip", "gemm.hip", "ceiling.hip"]
+SOURCES = ["api.hip", "reduce.hip", "split.hip", "gemm.hip", "gemm_banded.hip", "ceiling.hip"]
 HEADERS = [os.path.join(CSRC, "oz_common.h"), os.path.join(HERE, "..", "include", "ozimmu.h")]
 
 HIPCC_FLAGS = [

@@ -69,7 +69,13 @@ const char *ozimmu_status_string(int status)
 size_t ozimmu_workspace_bytes(int m, int n, int k, int s)
 {
     if (m < 0 || n < 0 || k < 0 || s < 1 || s > OZIMMU_MAX_SLICES) return 0;
-    return carve(m, n, k, s).total;
+    return carve(m, n, k, s, s).total;
+}
+
+size_t ozimmu_workspace_bytes2(int m, int n, int k, int sA, int sB, int all_products)
+{
+    if (m < 0 || n < 0 || k < 0 || sA < 1 || sA > OZIMMU_MAX_SLICES || sB < 1 || sB > OZIMMU_MAX_SLICES) return 0;
+    return carve(m, n, k, sA, sB, all_products != 0).total;
 }
 
 size_t ozimmu_planes_bytes(char side, int rows, int cols, int s, int layout)
@@ -88,11 +94,11 @@ size_t ozimmu_split_scratch_bytes(char side, int rows, int cols)
     return 256 + 8 * (size_t)(nblk > 0 ? nblk : 1);
 }
 
-int ozimmu_estimate_slices(int m, int n, int k, const double *A, int lda, const double *B, int ldb, double tol,
-                           int *s_out, double *kappa, void *workspace, size_t workspace_bytes, void *stream)
+static int kappas(int m, int n, int k, const double *A, int lda, const double *B, int ldb, double *kA, double *kB,
+                  void *workspace, size_t workspace_bytes, void *stream)
 {
-    if (!s_out || !(tol > 0.0) || bad_matrix(m, k, A, lda) || bad_matrix(k, n, B, ldb)) return OZIMMU_BAD_ARG;
-    const Workspace w = carve(m, n, k, 1);
+    if (bad_matrix(m, k, A, lda) || bad_matrix(k, n, B, ldb)) return OZIMMU_BAD_ARG;
+    const Workspace w = carve(m, n, k, 1, 1);
     if (!workspace || workspace_bytes < w.total || ((uintptr_t)workspace & 255)) return OZIMMU_BAD_ARG;
     hipStream_t st = (hipStream_t)stream;
     char *ws = (char *)workspace;
@@ -105,7 +111,18 @@ int ozimmu_estimate_slices(int m, int n, int k, const double *A, int lda, const 
     double ratioA, ratioB;
     std::memcpy(&ratioA, &host[1], 8);
     std::memcpy(&ratioB, &host[2], 8);
-    const double kA = 2.0 * ratioA, kB = 2.0 * ratioB;
+    *kA = 2.0 * ratioA;
+    *kB = 2.0 * ratioB;
+    return OZIMMU_OK;
+}
+
+int ozimmu_estimate_slices(int m, int n, int k, const double *A, int lda, const double *B, int ldb, double tol,
+                           int *s_out, double *kappa, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!s_out || !(tol > 0.0)) return OZIMMU_BAD_ARG;
+    double kA, kB;
+    int rc = kappas(m, n, k, A, lda, B, ldb, &kA, &kB, workspace, workspace_bytes, stream);
+    if (rc) return rc;
     if (kappa) { kappa[0] = kA; kappa[1] = kB; }
     // left-hand side of eq. (err-bound) with s_A = s_B = s, tried for s = 1, 2, ...
     for (int s = 1; s <= OZIMMU_MAX_SLICES; ++s) {
@@ -114,6 +131,41 @@ int ozimmu_estimate_slices(int m, int n, int k, const double *A, int lda, const 
     }
     *s_out = OZIMMU_MAX_SLICES;
     return OZIMMU_UNREACHABLE;
+}
+
+static int chi(int sA, int sB)
+{
+    const int sM = sA > sB ? sA : sB, sm = sA > sB ? sB : sA;
+    return sm * (2 * sM - sm + 1) / 2;
+}
+
+int ozimmu_estimate_slices2(int m, int n, int k, const double *A, int lda, const double *B, int ldb, double tol,
+                            int *sA_out, int *sB_out, double *kappa, void *workspace, size_t workspace_bytes,
+                            void *stream)
+{
+    if (!sA_out || !sB_out || !(tol > 0.0)) return OZIMMU_BAD_ARG;
+    double kA, kB;
+    int rc = kappas(m, n, k, A, lda, B, ldb, &kA, &kB, workspace, workspace_bytes, stream);
+    if (rc) return rc;
+    if (kappa) { kappa[0] = kA; kappa[1] = kB; }
+    // every (sA, sB) that meets eq. (err-bound); keep the one with the fewest products chi(sA, sB),
+    // then the smaller sA + sB, then the smaller sA
+    bool found = false;
+    int bA = OZIMMU_MAX_SLICES, bB = OZIMMU_MAX_SLICES;
+    for (int sA = 1; sA <= OZIMMU_MAX_SLICES; ++sA)
+        for (int sB = 1; sB <= OZIMMU_MAX_SLICES; ++sB) {
+            const double lhs = std::ldexp(kA, -sA * kSliceBits) + std::ldexp(kB, -sB * kSliceBits);
+            if (!(lhs <= tol)) continue;
+            const int c = chi(sA, sB), cb = chi(bA, bB);
+            if (!found || c < cb || (c == cb && (sA + sB < bA + bB || (sA + sB == bA + bB && sA < bA)))) {
+                found = true;
+                bA = sA;
+                bB = sB;
+            }
+        }
+    *sA_out = bA;
+    *sB_out = bB;
+    return found ? OZIMMU_OK : OZIMMU_UNREACHABLE;
 }
 
 int ozimmu_split(char side, int rows, int cols, const double *X, int ldx, int s, int8_t *planes, int32_t *exps,
@@ -135,13 +187,13 @@ int ozimmu_split(char side, int rows, int cols, const double *X, int ldx, int s,
     return OZIMMU_OK;
 }
 
-int ozimmu_dgemm(int m, int n, int k, const double *A, int lda, const double *B, int ldb, double *C, int ldc, int s,
-                 void *workspace, size_t workspace_bytes, void *stream)
+static int dgemm_impl(int m, int n, int k, const double *A, int lda, const double *B, int ldb, double *C, int ldc,
+                      int sA, int sB, bool all_products, void *workspace, size_t workspace_bytes, void *stream)
 {
-    if (bad_matrix(m, k, A, lda) || bad_matrix(k, n, B, ldb) || bad_matrix(m, n, C, ldc) || s < 1 ||
-        s > OZIMMU_MAX_SLICES)
+    if (bad_matrix(m, k, A, lda) || bad_matrix(k, n, B, ldb) || bad_matrix(m, n, C, ldc) || sA < 1 ||
+        sA > OZIMMU_MAX_SLICES || sB < 1 || sB > OZIMMU_MAX_SLICES)
         return OZIMMU_BAD_ARG;
-    const Workspace w = carve(m, n, k, s);
+    const Workspace w = carve(m, n, k, sA, sB, all_products);
     if (!workspace || workspace_bytes < w.total || ((uintptr_t)workspace & 255)) return OZIMMU_BAD_ARG;
     // exact conversion of a diagonal sum to binary64 needs s * k * 127^2 < 2^53: true for every int k
     hipStream_t st = (hipStream_t)stream;
@@ -153,18 +205,35 @@ int ozimmu_dgemm(int m, int n, int k, const double *A, int lda, const double *B,
     prof_mark(1, st);
     auto *eA = (int32_t *)(ws + w.off_expA), *eB = (int32_t *)(ws + w.off_expB);
     auto *pA = (int8_t *)(ws + w.off_planesA), *pB = (int8_t *)(ws + w.off_planesB);
-    OZ_TRY(launch_split('A', m, k, A, lda, s, eA, pA, OZIMMU_LAYOUT_MFMA, st));
-    OZ_TRY(launch_split('B', k, n, B, ldb, s, eB, pB, OZIMMU_LAYOUT_MFMA, st));
+    OZ_TRY(launch_split('A', m, k, A, lda, sA, eA, pA, OZIMMU_LAYOUT_MFMA, st));
+    OZ_TRY(launch_split('B', k, n, B, ldb, sB, eB, pB, OZIMMU_LAYOUT_MFMA, st));
     prof_mark(2, st);
-    if (fused_single_block(s, k))
-        OZ_TRY(launch_gemm_fused(m, n, w.kp, s, pA, pB, eA, eB, C, ldc, nullptr, nullptr, st));
-    else if (s <= fused_max_slices())
-        OZ_TRY(launch_gemm_fused(m, n, w.kp, s, pA, pB, eA, eB, C, ldc, nullptr, (long long *)(ws + w.off_totals), st));
-    else
-        OZ_TRY(launch_gemm_generic(m, n, w.kp, s, pA, pB, eA, eB, C, ldc, 0, 0, 0, w.kp / kFrag, nullptr, st));
+    const bool fused = sA == sB && !all_products && sA <= fused_max_slices();
+    if (fused && fused_single_block(sA, k)) {
+        OZ_TRY(launch_gemm_fused(m, n, w.kp, sA, pA, pB, eA, eB, C, ldc, nullptr, nullptr, st));
+    } else if (fused) {
+        OZ_TRY(launch_gemm_fused(m, n, w.kp, sA, pA, pB, eA, eB, C, ldc, nullptr, (long long *)(ws + w.off_totals), st));
+    } else {
+        const int dmax = all_products ? sA + sB : (sA > sB ? sA : sB) + 1;
+        long long *totals = banded_totals_bytes(sA, sB, k) ? (long long *)(ws + w.off_totals) : nullptr;
+        OZ_TRY(launch_gemm_banded(m, n, w.kp, sA, sB, dmax, pA, pB, eA, eB, C, ldc, totals, st));
+    }
     prof_mark(3, st);
     if (g_prof.on && g_prof.calls < g_prof.capacity) ++g_prof.calls;
     return OZIMMU_OK;
+}
+
+int ozimmu_dgemm(int m, int n, int k, const double *A, int lda, const double *B, int ldb, double *C, int ldc, int s,
+                 void *workspace, size_t workspace_bytes, void *stream)
+{
+    return dgemm_impl(m, n, k, A, lda, B, ldb, C, ldc, s, s, false, workspace, workspace_bytes, stream);
+}
+
+int ozimmu_dgemm2(int m, int n, int k, const double *A, int lda, const double *B, int ldb, double *C, int ldc,
+                  int sA, int sB, int all_products, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return dgemm_impl(m, n, k, A, lda, B, ldb, C, ldc, sA, sB, all_products != 0, workspace, workspace_bytes,
+                      stream);
 }
 
 int ozimmu_profile_start(int max_calls)
@@ -216,7 +285,7 @@ int ozimmu_check(void *workspace, void *stream)
 int ozimmu_get_exponents(int m, int n, int k, int s, const void *workspace, int32_t *eA, int32_t *eB, void *stream)
 {
     if (m < 0 || n < 0 || k < 0 || s < 1 || s > OZIMMU_MAX_SLICES || !workspace) return OZIMMU_BAD_ARG;
-    const Workspace w = carve(m, n, k, s);
+    const Workspace w = carve(m, n, k, s, s);
     hipStream_t st = (hipStream_t)stream;
     const char *ws = (const char *)workspace;
     if (eA && m) OZ_TRY(hipMemcpyAsync(eA, ws + w.off_expA, 4 * (size_t)m, hipMemcpyDeviceToDevice, st));
@@ -227,7 +296,7 @@ int ozimmu_get_exponents(int m, int n, int k, int s, const void *workspace, int3
 int ozimmu_debug_diagonals(int m, int n, int k, int s, const void *workspace, int32_t *D, void *stream)
 {
     if (m <= 0 || n <= 0 || k < 0 || !workspace || !D || !fused_single_block(s, k)) return OZIMMU_BAD_ARG;
-    const Workspace w = carve(m, n, k, s);
+    const Workspace w = carve(m, n, k, s, s);
     const char *ws = (const char *)workspace;
     OZ_TRY(launch_gemm_fused(m, n, w.kp, s, (const int8_t *)(ws + w.off_planesA), (const int8_t *)(ws + w.off_planesB),
                              nullptr, nullptr, nullptr, m, D, nullptr, (hipStream_t)stream));
@@ -240,7 +309,7 @@ int ozimmu_debug_slice_product(int m, int n, int k, int s, const void *workspace
     if (m <= 0 || n <= 0 || k < 0 || s < 1 || s > OZIMMU_MAX_SLICES || !workspace || !P || l < 1 || l > s || h < 1 ||
         h > s || k0 < 0 || k1 < k0 || k1 > k || (k0 % kFrag) != 0 || (long long)(k1 - k0) > kMaxInt32K)
         return OZIMMU_BAD_ARG;
-    const Workspace w = carve(m, n, k, s);
+    const Workspace w = carve(m, n, k, s, s);
     const char *ws = (const char *)workspace;
     // the planes are zero beyond k, so the last (partial) fragment may be read whole
     const int kb_begin = k0 / kFrag, kb_end = (k1 + kFrag - 1) / kFrag;

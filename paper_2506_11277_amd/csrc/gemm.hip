@@ -58,10 +58,11 @@ __device__ __forceinline__ void tile_of_block(int b, int nb, int tiles_m, int ti
 //   KB32   32-deep k-blocks per LDS stage
 //   MODE   kPlain: whole contraction in int32 (needs s * k * 127^2 < 2^31)
 //          kDump:  as kPlain, but write the int32 diagonal sums instead of C (test hook)
-//          kBlocked: any k.  The contraction is cut into k-blocks short enough for int32; at the end
-//                  of each block the diagonal sums are added, exactly, into int64 totals kept in a
-//                  per-tile scratch area in HBM (read-modify-write by the lanes that own them, so no
-//                  atomics and a fixed result), and the accumulators restart from zero
+//          kBlocked: any k.  The contraction is cut into k-blocks short enough for int32, one work-group
+//                  per (tile, k-block) (blockIdx.y = k-block).  Each adds its int32 diagonal sums into
+//                  int64 totals in HBM with integer atomics -- exact, so the totals do not depend on
+//                  the order of arrival and the result stays bit-reproducible; finish_blocked_kernel
+//                  then does the binary64 accumulation
 
 // 16 bytes per lane: global (sbase + voff)  ->  LDS (ldsaddr + lane * 16); ldsaddr is wavefront-uniform
 __device__ __forceinline__ void lds_dma16(const void *sbase, unsigned voff, unsigned ldsaddr)
@@ -137,15 +138,13 @@ __global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[a][i][j][r] = 0;
 
-    const int nst = KB / KB32;
-    // k-blocked mode: this lane's slots in the int64 totals of its tile, [tile][wavefront][a][i][j][r][lane]
-    long long *tot = nullptr;
-    if (MODE == kBlocked)
-        tot = totals + ((size_t)(tm * tiles_n + tn) * NW + wave) * (size_t)(S * WMF * WNF * 16 * 64) + lane;
-    const bool spilled = MODE == kBlocked && nst > stages_per_block;   // at least one block went to the totals
-    issue_stage(0, 0);
-    if (NSTAGE == 3 && nst > 1) {
-        issue_stage(1, 1);
+    // stages of this work-group: everything, or k-block blockIdx.y
+    const int nst_all = KB / KB32;
+    const int st0 = MODE == kBlocked ? (int)blockIdx.y * stages_per_block : 0;
+    const int nst = MODE == kBlocked && st0 + stages_per_block < nst_all ? st0 + stages_per_block : nst_all;
+    issue_stage(st0, 0);
+    if (NSTAGE == 3 && nst - st0 > 1) {
+        issue_stage(st0 + 1, 1);
         wait_keep1();
     } else {
         wait_vmcnt<0>();
@@ -153,7 +152,7 @@ __global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t
     __syncthreads();
 
     int buf = 0;
-    for (int st = 0; st < nst; ++st) {
+    for (int st = st0; st < nst; ++st) {
         const bool ahead = st + NSTAGE - 1 < nst;
         if (ahead) issue_stage(st + NSTAGE - 1, buf == 0 ? NSTAGE - 1 : buf - 1);
         const unsigned char *cur = lds + buf * STAGE;
@@ -186,24 +185,23 @@ __global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t
         if (NSTAGE == 3 && ahead) wait_keep1(); else wait_vmcnt<0>();
         __syncthreads();
         buf = buf + 1 == NSTAGE ? 0 : buf + 1;
-        if (MODE == kBlocked && st + 1 < nst && (st + 1) % stages_per_block == 0) {
-            // end of a k-block: totals (+)= accumulators, accumulators = 0
-            const bool first = st + 1 == stages_per_block;
+    }
+
+    if (MODE == kBlocked) {
+        // this k-block's diagonal sums -> int64 totals of the tile, [tile][wavefront][a][i][j][r][lane]
+        long long *tot = totals + ((size_t)(tm * tiles_n + tn) * NW + wave) * (size_t)(S * WMF * WNF * 16 * 64) + lane;
 #pragma unroll
-            for (int a = 0; a < S; ++a)
+        for (int a = 0; a < S; ++a)
 #pragma unroll
-                for (int i = 0; i < WMF; ++i)
+            for (int i = 0; i < WMF; ++i)
 #pragma unroll
-                    for (int j = 0; j < WNF; ++j)
+                for (int j = 0; j < WNF; ++j)
 #pragma unroll
-                        for (int r = 0; r < 16; ++r) {
-                            long long *t = tot + ((((size_t)a * WMF + i) * WNF + j) * 16 + r) * 64;
-                            long long v = acc[a][i][j][r];
-                            if (!first) v += *t;
-                            *t = v;
-                            acc[a][i][j][r] = 0;
-                        }
-        }
+                    for (int r = 0; r < 16; ++r)
+                        __hip_atomic_fetch_add(tot + ((((size_t)a * WMF + i) * WNF + j) * 16 + r) * 64,
+                                               (long long)acc[a][i][j][r], __ATOMIC_RELAXED,
+                                               __HIP_MEMORY_SCOPE_AGENT);
+        return;
     }
 
     // epilogue: accumulator register r of lane holds  (n_local, m_local) = (8*(r/4) + 4*(lane/32) + r%4, lane%32)
@@ -226,21 +224,52 @@ __global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t
                     double sum = 0.0;
 #pragma unroll
                     for (int a = 0; a < S; ++a) {
-                        double dd;
-                        if (MODE == kBlocked) {
-                            long long v = acc[a][i][j][r];
-                            if (spilled) v += tot[((((size_t)a * WMF + i) * WNF + j) * 16 + r) * 64];
-                            dd = (double)v;          // exact: |v| <= s * k * 127^2 < 2^53
-                        } else {
-                            dd = (double)acc[a][i][j][r];
-                        }
-                        sum = sum + dd * __builtin_ldexp(1.0, -kSliceBits * (a + 2));
+                        sum = sum + (double)acc[a][i][j][r] * __builtin_ldexp(1.0, -kSliceBits * (a + 2));
                     }
                     C[mi + (size_t)nj * ldc] = ldexp(sum, ea + eB[nj]);
                 }
             }
         }
     }
+}
+
+// Second step of the k-blocked mode: binary64 accumulation from the int64 totals, same element
+// mapping and the same order of additions as the epilogue of gemm_fused_kernel.
+template <int S, int WVM, int WVN, int WMF, int WNF>
+__global__ __launch_bounds__(64 * WVM * WVN) void finish_blocked_kernel(const long long *__restrict__ totals,
+                                                                        const int32_t *__restrict__ eA,
+                                                                        const int32_t *__restrict__ eB,
+                                                                        double *__restrict__ C, int ldc, int m, int n,
+                                                                        int tiles_n)
+{
+    constexpr int NW = WVM * WVN, FA = WVM * WMF, FB = WVN * WNF;
+    const int tm = blockIdx.x / tiles_n, tn = blockIdx.x % tiles_n;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave % WVM, wn = wave / WVM;
+    const long long *tot = totals + ((size_t)blockIdx.x * NW + wave) * (size_t)(S * WMF * WNF * 16 * 64) + lane;
+    const int m0 = (tm * FA + wm * WMF) * 32, n0 = (tn * FB + wn * WNF) * 32;
+    for (int i = 0; i < WMF; ++i) {
+        const int mi = m0 + i * 32 + (lane & 31);
+        if (mi >= m) continue;
+        const int ea = eA[mi];
+        for (int j = 0; j < WNF; ++j)
+            for (int r = 0; r < 16; ++r) {
+                const int nj = n0 + j * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                if (nj >= n) continue;
+                double sum = 0.0;
+#pragma unroll
+                for (int a = 0; a < S; ++a) {
+                    const long long v = tot[((((size_t)a * WMF + i) * WNF + j) * 16 + r) * 64];
+                    sum = sum + (double)v * __builtin_ldexp(1.0, -kSliceBits * (a + 2));   // exact conversion: |v| < 2^53
+                }
+                C[mi + (size_t)nj * ldc] = ldexp(sum, ea + eB[nj]);
+            }
+    }
+}
+
+__global__ void zero_i64_kernel(long long *p, size_t n)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0;
 }
 
 // =============================== generic kernel =========================================
@@ -404,10 +433,23 @@ hipError_t launch_fused_s(int m, int n, int kp, const int8_t *pA, const int8_t *
         configured = true;
     }
     const int tiles_m = (m + TM - 1) / TM, tiles_n = (n + TN - 1) / TN;
+    if (MODE != kBlocked) {
+        kern<<<tiles_m * tiles_n, 64 * Cfg::WVM * Cfg::WVN, Cfg::NSTAGE * STAGE, st>>>(
+            pA, pB, eA, eB, C, ldc, m, n, kp / kFrag, tiles_m, tiles_n, dump, nullptr, 0);
+        return hipGetLastError();
+    }
     // longest k-block whose s products per diagonal cannot overflow int32, in whole stages
     const int stages_per_block = (int)(kMaxInt32K / S / kFrag) / Cfg::KB32;
-    kern<<<tiles_m * tiles_n, 64 * Cfg::WVM * Cfg::WVN, Cfg::NSTAGE * STAGE, st>>>(
-        pA, pB, eA, eB, C, ldc, m, n, kp / kFrag, tiles_m, tiles_n, dump, totals, stages_per_block);
+    const int nst = kp / kFrag / Cfg::KB32;
+    const int nblocks = (nst + stages_per_block - 1) / stages_per_block;
+    const size_t nslots = (size_t)tiles_m * tiles_n * S * TM * TN;
+    zero_i64_kernel<<<2048, 256, 0, st>>>(totals, nslots);
+    dim3 grid(tiles_m * tiles_n, nblocks);
+    kern<<<grid, 64 * Cfg::WVM * Cfg::WVN, Cfg::NSTAGE * STAGE, st>>>(pA, pB, eA, eB, C, ldc, m, n, kp / kFrag,
+                                                                       tiles_m, tiles_n, nullptr, totals,
+                                                                       stages_per_block);
+    finish_blocked_kernel<S, Cfg::WVM, Cfg::WVN, Cfg::WMF, Cfg::WNF>
+        <<<tiles_m * tiles_n, 64 * Cfg::WVM * Cfg::WVN, 0, st>>>(totals, eA, eB, C, ldc, m, n, tiles_n);
     return hipGetLastError();
 }
 

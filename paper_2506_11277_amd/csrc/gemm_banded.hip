@@ -1,0 +1,266 @@
+// Slice products for ANY pair of slice counts (sA for A, sB for B) and any k: the general
+// form of the product step of Algorithm 1 (Sect. 3) with the product set
+//     l <= sA,  h <= sB,  l + h <= dmax        (dmax = max(sA, sB) + 1 for the reduced variant of
+// the subsection "Reduction in number of products", sA + sB for "Computation of all products"),
+// accumulated by diagonals in ascending order as in gemm.hip.
+//
+// The pair set is a band of the (l, h) grid, too large to hold in registers at once for big
+// slice counts, so it is cut two ways:
+//   * diagonals are taken G at a time (G int32 accumulator sets per wavefront); binary64 S is
+//     carried in registers from one group to the next, so the additions keep their order;
+//   * inside a group, the slices of A are taken LA at a time.  A chunk of LA slices of A meets,
+//     on the G diagonals of the group, a window of LB = G + LA - 1 consecutive slices of B, and
+//     the product A-slice `la` x window slot `hb` belongs to diagonal slot a = hb + la - (LA-1):
+//     all register and LDS indices are compile-time, only validity (slice exists, diagonal
+//     computed) is a wavefront-uniform runtime mask.
+// Each (group, chunk) is one sweep over k with the LDS-DMA double buffer of the fused kernel;
+// every staged slice fragment feeds up to G (A) or LA (B) MFMAs.
+//
+// int32 safety: a diagonal receives at most LA products per sweep.  If all sweeps of a group together
+// stay below 133144 terms per accumulator, int32 suffices (TOTALS = false).  Otherwise (TOTALS) k is
+// cut into blocks of at most 133144 / LA terms and after every block the accumulators are added,
+// exactly, into int64 totals and restart from zero; the totals live in a scratch slot per work-group
+// (the grid is persistent, so the scratch does not grow with the matrix).
+#include "oz_common.h"
+
+namespace oz {
+
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+constexpr int kG = 8, kLA = 4, kLB = kG + kLA - 1;
+constexpr int kWVM = 4, kWVN = 2;                       // 8 wavefronts, 32 x 32 outputs each: tile 128 x 64
+constexpr int kUnitsA = kLA * kWVM, kUnitsB = kLB * kWVN;
+constexpr int kUnits = kUnitsA + kUnitsB;               // 1 KiB fragments per stage
+constexpr int kStageBytes = kUnits * kFragBytes;
+constexpr int kPersistentGroups = 256;                  // work-groups of the persistent grid (one per CU)
+
+__device__ __forceinline__ void lds_dma16(const void *sbase, unsigned voff, unsigned ldsaddr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(ldsaddr), "v"(voff), "s"(sbase)
+                 : "memory", "m0");
+}
+
+__device__ __forceinline__ void wait_all_vm() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// same XCD-aware order as the fused kernel (virtual block id -> tile)
+__device__ __forceinline__ void tile_of_block(int b, int nb, int tiles_m, int tiles_n, int &tm, int &tn)
+{
+    const int xcd = b & 7, idx = b >> 3;
+    const int q = nb >> 3, rem = nb & 7;
+    const int lin = xcd * q + (xcd < rem ? xcd : rem) + idx;
+    constexpr int GM = 4;
+    const int group = GM * tiles_n;
+    const int g = lin / group, in = lin - g * group;
+    const int first = g * GM;
+    const int gm = tiles_m - first < GM ? tiles_m - first : GM;
+    tm = first + in % gm;
+    tn = in / gm;
+}
+
+template <bool TOTALS>
+__global__ __launch_bounds__(64 * kWVM * kWVN) void gemm_banded_kernel(
+    const int8_t *__restrict__ pA, const int8_t *__restrict__ pB, const int32_t *__restrict__ eA,
+    const int32_t *__restrict__ eB, double *__restrict__ C, int ldc, int m, int n, int sA, int sB, int dmax, int KB,
+    int tiles_m, int tiles_n, long long *__restrict__ totals, int stages_per_block)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wm = wave % kWVM, wn = wave / kWVM;
+    const int ntiles = tiles_m * tiles_n;
+    const int nrounds = (ntiles + gridDim.x - 1) / gridDim.x;
+    long long *tot = TOTALS ? totals + ((size_t)blockIdx.x * (kWVM * kWVN) + wave) * (size_t)(kG * 16 * 64) + lane
+                            : nullptr;
+
+    for (int round = 0; round < nrounds; ++round) {
+        int tile_id = round * gridDim.x + blockIdx.x;
+        if (tile_id >= ntiles) break;
+        // one XCD-aware numbering over all tiles; the grid size is a multiple of 8 (or a single
+        // round), so (tile_id % 8) names the XCD this work-group runs on
+        int tm, tn;
+        tile_of_block(tile_id, ntiles, tiles_m, tiles_n, tm, tn);
+
+        const size_t rowA_bytes = (size_t)KB * sA * kFragBytes, rowB_bytes = (size_t)KB * sB * kFragBytes;
+        const int8_t *rowA = pA + (size_t)tm * kWVM * rowA_bytes;
+        const int8_t *rowB = pB + (size_t)tn * kWVN * rowB_bytes;
+
+        double S[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) S[r] = 0.0;
+
+        for (int d0 = 2; d0 <= dmax; d0 += kG) {
+            const int dlast = d0 + kG - 1 < dmax ? d0 + kG - 1 : dmax;
+            v16i acc[kG];
+#pragma unroll
+            for (int a = 0; a < kG; ++a)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[a][r] = 0;
+            bool have_totals = false;
+
+            const int l_lo = d0 - sB > 1 ? d0 - sB : 1;
+            const int l_hi = dlast - 1 < sA ? dlast - 1 : sA;
+            for (int l0 = l_lo; l0 <= l_hi; l0 += kLA) {
+                const int hmin = d0 - (l0 + kLA - 1);          // slice of B in window slot 0
+                // validity of the (la, a) products of this sweep, bit la*G + a
+                unsigned mask = 0;
+#pragma unroll
+                for (int la = 0; la < kLA; ++la)
+#pragma unroll
+                    for (int a = 0; a < kG; ++a) {
+                        const int l = l0 + la, h = d0 + a - l;
+                        if (l <= sA && l <= l_hi && h >= 1 && h <= sB && d0 + a <= dlast) mask |= 1u << (la * kG + a);
+                    }
+                if (mask == 0) continue;
+                unsigned needA = 0, needB = 0;                  // which slices have to be staged
+#pragma unroll
+                for (int la = 0; la < kLA; ++la)
+#pragma unroll
+                    for (int a = 0; a < kG; ++a)
+                        if (mask >> (la * kG + a) & 1u) { needA |= 1u << la; needB |= 1u << (a - la + kLA - 1); }
+
+                auto issue_stage = [&](int st, int buf) {
+#pragma unroll
+                    for (int i = 0; i < (kUnits + 7) / 8; ++i) {
+                        const int u = wave + i * 8;
+                        if (u >= kUnits) break;
+                        const int8_t *src;
+                        if (u < kUnitsA) {
+                            const int la = u / kWVM, c = u % kWVM;
+                            if (!(needA >> la & 1u)) continue;
+                            src = rowA + (size_t)c * rowA_bytes + ((size_t)st * sA + (l0 + la - 1)) * kFragBytes;
+                        } else {
+                            const int hb = (u - kUnitsA) / kWVN, c = (u - kUnitsA) % kWVN;
+                            if (!(needB >> hb & 1u)) continue;
+                            src = rowB + (size_t)c * rowB_bytes + ((size_t)st * sB + (hmin + hb - 1)) * kFragBytes;
+                        }
+                        lds_dma16(src, lane * 16, lds0 + buf * kStageBytes + u * kFragBytes);
+                    }
+                };
+
+                // the sweep over k, in blocks short enough for int32 (one block unless TOTALS)
+                for (int kb0 = 0; kb0 < KB; kb0 += stages_per_block) {
+                    const int kb1 = kb0 + stages_per_block < KB ? kb0 + stages_per_block : KB;
+                    issue_stage(kb0, 0);
+                    wait_all_vm();
+                    __syncthreads();
+                    int buf = 0;
+                    for (int st = kb0; st < kb1; ++st) {
+                        if (st + 1 < kb1) issue_stage(st + 1, buf ^ 1);
+                        const unsigned char *cur = lds + buf * kStageBytes;
+                        v4i bf[kLB];
+#pragma unroll
+                        for (int hb = 0; hb < kLB; ++hb)
+                            if (needB >> hb & 1u)
+                                bf[hb] = *(const v4i *)(cur + (kUnitsA + hb * kWVN + wn) * kFragBytes + lane * 16);
+#pragma unroll
+                        for (int la = 0; la < kLA; ++la) {
+                            if (!(needA >> la & 1u)) continue;
+                            const v4i af = *(const v4i *)(cur + (la * kWVM + wm) * kFragBytes + lane * 16);
+#pragma unroll
+                            for (int a = 0; a < kG; ++a)
+                                if (mask >> (la * kG + a) & 1u)
+                                    acc[a] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bf[a - la + kLA - 1], af, acc[a], 0, 0, 0);
+                        }
+                        wait_all_vm();
+                        __syncthreads();
+                        buf ^= 1;
+                    }
+                    if (TOTALS) {
+                        // end of a k-block: int64 totals (+)= accumulators, accumulators restart from zero.
+                        // (The base is laundered through an empty asm so that the 128 slot addresses are formed
+                        // here, when needed, instead of being hoisted into registers for the whole kernel.)
+                        long long *tb = tot;
+                        asm volatile("" : "+v"(tb));
+#pragma unroll
+                        for (int a = 0; a < kG; ++a) {
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) {
+                                long long *t = tb + ((size_t)a * 16 + r) * 64;
+                                long long v = acc[a][r];
+                                if (have_totals) v += *t;
+                                *t = v;
+                                acc[a][r] = 0;
+                            }
+                            asm volatile("" ::: "memory");   // one diagonal at a time
+                        }
+                        have_totals = true;
+                    }
+                }
+            }
+            // the group's diagonals are complete: S <- S + 2^{-7d} D_d, ascending d
+            long long *te = tot;
+            if (TOTALS) asm volatile("" : "+v"(te));
+#pragma unroll
+            for (int a = 0; a < kG; ++a) {
+                if (d0 + a > dlast) break;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    long long v = acc[a][r];
+                    if (TOTALS && have_totals) v += te[((size_t)a * 16 + r) * 64];
+                    S[r] = S[r] + ldexp((double)v, -kSliceBits * (d0 + a));
+                }
+                asm volatile("" ::: "memory");
+            }
+        }
+
+        const int mi = (tm * kWVM + wm) * 32 + (lane & 31);
+        const int n0 = (tn * kWVN + wn) * 32;
+        if (mi < m) {
+            const int ea = eA[mi];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int nj = n0 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                if (nj < n) C[mi + (size_t)nj * ldc] = ldexp(S[r], ea + eB[nj]);
+            }
+        }
+    }
+}
+
+}  // namespace
+
+size_t banded_totals_bytes(int sA, int sB, int k)
+{
+    // without totals an accumulator of a group receives at most ceil(sm / LA) * LA products of kp terms
+    // each (sm: slices of the chunked operand); that has to fit int32
+    const long long kp = round_up(k > 0 ? k : 1, kPad);
+    const long long chunks = (sA + kLA - 1) / kLA;
+    if (chunks * kLA * kp <= kMaxInt32K) return 0;
+    return (size_t)kPersistentGroups * (kWVM * kWVN) * kG * 16 * 64 * sizeof(long long);
+}
+
+hipError_t launch_gemm_banded(int m, int n, int kp, int sA, int sB, int dmax, const int8_t *pA, const int8_t *pB,
+                              const int32_t *eA, const int32_t *eB, double *C, int ldc, long long *totals,
+                              hipStream_t st)
+{
+    if (m <= 0 || n <= 0) return hipSuccess;
+    static bool configured = false;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute((const void *)gemm_banded_kernel<false>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kStageBytes);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute((const void *)gemm_banded_kernel<true>,
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kStageBytes);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    const int tiles_m = (m + 127) / 128, tiles_n = (n + 63) / 64;
+    const int ntiles = tiles_m * tiles_n;
+    const int grid = ntiles < kPersistentGroups ? ntiles : kPersistentGroups;
+    const int KB = kp / kFrag;
+    if (totals) {
+        // a k-block adds at most LA products of (32 * stages) terms to an accumulator
+        const int stages_per_block = (int)(kMaxInt32K / kLA / kFrag);
+        gemm_banded_kernel<true><<<grid, 64 * kWVM * kWVN, 2 * kStageBytes, st>>>(
+            pA, pB, eA, eB, C, ldc, m, n, sA, sB, dmax, KB, tiles_m, tiles_n, totals, stages_per_block);
+    } else {
+        gemm_banded_kernel<false><<<grid, 64 * kWVM * kWVN, 2 * kStageBytes, st>>>(
+            pA, pB, eA, eB, C, ldc, m, n, sA, sB, dmax, KB, tiles_m, tiles_n, nullptr, KB);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace oz

@@ -20,6 +20,8 @@ constexpr long long kMaxInt32K = 2147483647LL / (127LL * 127LL);   // 133144
 inline int round_up(int x, int q) { return (x + q - 1) / q * q; }
 
 size_t fused_totals_bytes(int s, int m, int n, int k);
+size_t banded_totals_bytes(int sA, int sB, int k);
+int fused_max_slices();
 
 // Workspace carve-up (all offsets multiples of 256 bytes).
 struct Workspace {
@@ -33,7 +35,7 @@ struct Workspace {
     size_t total;
 };
 
-inline Workspace carve(int m, int n, int k, int s)
+inline Workspace carve(int m, int n, int k, int sA, int sB, bool all_products = false)
 {
     Workspace w;
     w.mp = round_up(m > 0 ? m : 1, kPad);
@@ -48,9 +50,10 @@ inline Workspace carve(int m, int n, int k, int s)
     w.off_minB = take(8 * (size_t)w.np);
     w.off_expA = take(4 * (size_t)w.mp);
     w.off_expB = take(4 * (size_t)w.np);
-    w.off_planesA = take((size_t)s * w.mp * w.kp);
-    w.off_planesB = take((size_t)s * w.np * w.kp);
-    w.off_totals = take(fused_totals_bytes(s, m, n, k));
+    w.off_planesA = take((size_t)sA * w.mp * w.kp);
+    w.off_planesB = take((size_t)sB * w.np * w.kp);
+    const bool fused = sA == sB && !all_products && sA <= fused_max_slices();
+    w.off_totals = take(fused ? fused_totals_bytes(sA, m, n, k) : banded_totals_bytes(sA, sB, k));
     w.total = off;
     return w;
 }
@@ -84,6 +87,10 @@ size_t fused_totals_bytes(int s, int m, int n, int k);
 hipError_t launch_gemm_fused(int m, int n, int kp, int s, const int8_t *pA, const int8_t *pB,
                              const int32_t *eA, const int32_t *eB, double *C, int ldc,
                              int32_t *dump, long long *totals, hipStream_t st);
+// general product band (any sA, sB, any k); totals: scratch of banded_totals_bytes() or null when that is 0
+hipError_t launch_gemm_banded(int m, int n, int kp, int sA, int sB, int dmax, const int8_t *pA, const int8_t *pB,
+                              const int32_t *eA, const int32_t *eB, double *C, int ldc, long long *totals,
+                              hipStream_t st);
 hipError_t launch_gemm_generic(int m, int n, int kp, int s, const int8_t *pA, const int8_t *pB,
                                const int32_t *eA, const int32_t *eB, double *C, int ldc,
                                int pair_l, int pair_h, int kb_begin, int kb_end, int32_t *dump,

@@ -29,6 +29,13 @@ _SIGNATURES = {
                                 _c.c_void_p, _c.c_int, _c.c_void_p, _c.c_void_p]),
     "ozimmu_dgemm": (_c.c_int, [_c.c_int, _c.c_int, _c.c_int, _c.c_void_p, _c.c_int, _c.c_void_p, _c.c_int,
                                 _c.c_void_p, _c.c_int, _c.c_int, _c.c_void_p, _c.c_size_t, _c.c_void_p]),
+    "ozimmu_workspace_bytes2": (_c.c_size_t, [_c.c_int] * 6),
+    "ozimmu_dgemm2": (_c.c_int, [_c.c_int, _c.c_int, _c.c_int, _c.c_void_p, _c.c_int, _c.c_void_p, _c.c_int,
+                                 _c.c_void_p, _c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_void_p, _c.c_size_t,
+                                 _c.c_void_p]),
+    "ozimmu_estimate_slices2": (_c.c_int, [_c.c_int, _c.c_int, _c.c_int, _c.c_void_p, _c.c_int, _c.c_void_p, _c.c_int,
+                                           _c.c_double, _c.POINTER(_c.c_int), _c.POINTER(_c.c_int),
+                                           _c.POINTER(_c.c_double), _c.c_void_p, _c.c_size_t, _c.c_void_p]),
     "ozimmu_check": (_c.c_int, [_c.c_void_p, _c.c_void_p]),
     "ozimmu_get_exponents": (_c.c_int, [_c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_void_p, _c.c_void_p,
                                         _c.c_void_p, _c.c_void_p]),
@@ -140,6 +147,53 @@ def dgemm(A, B, s, C=None, workspace=None, check_finite=False):
     if check_finite:
         check(workspace)
     return C
+
+
+def dgemm2(A, B, sA, sB, all_products=False, C=None, workspace=None, check_finite=False):
+    """C = A @ B with sA slices of A and sB slices of B."""
+    lda = _colmajor_ld(A, "A")
+    ldb = _colmajor_ld(B, "B")
+    m, k = A.shape
+    k2, n = B.shape
+    if k != k2:
+        raise ValueError("inner dimensions differ")
+    if C is None:
+        C = colmajor_empty(m, n, device=A.device)
+    ldc = _colmajor_ld(C, "C")
+    if tuple(C.shape) != (m, n):
+        raise ValueError("C has the wrong shape")
+    if workspace is None:
+        nbytes = lib().ozimmu_workspace_bytes2(m, n, k, sA, sB, int(all_products))
+        if nbytes == 0:
+            raise OzimmuError(BAD_ARG, "workspace_bytes2")
+        workspace = torch.empty(nbytes, dtype=torch.uint8, device=A.device)
+    rc = lib().ozimmu_dgemm2(m, n, k, A.data_ptr(), lda, B.data_ptr(), ldb, C.data_ptr(), ldc, sA, sB,
+                             int(all_products), workspace.data_ptr(), workspace.numel(), _stream())
+    if rc != OK:
+        raise OzimmuError(rc, "dgemm2")
+    if check_finite:
+        check(workspace)
+    return C
+
+
+def estimate_slices2(A, B, tol, workspace=None):
+    """Returns (sA, sB, status, kappa_A, kappa_B): the cheapest pair of slice counts meeting tol."""
+    lda = _colmajor_ld(A, "A")
+    ldb = _colmajor_ld(B, "B")
+    m, k = A.shape
+    k2, n = B.shape
+    if k != k2:
+        raise ValueError("inner dimensions differ")
+    if workspace is None:
+        workspace = alloc_workspace(m, n, k, 1, device=A.device)
+    sA = ctypes.c_int(0)
+    sB = ctypes.c_int(0)
+    kap = (ctypes.c_double * 2)()
+    rc = lib().ozimmu_estimate_slices2(m, n, k, A.data_ptr(), lda, B.data_ptr(), ldb, float(tol), ctypes.byref(sA),
+                                       ctypes.byref(sB), kap, workspace.data_ptr(), workspace.numel(), _stream())
+    if rc not in (OK, UNREACHABLE):
+        raise OzimmuError(rc, "estimate_slices2")
+    return sA.value, sB.value, rc, kap[0], kap[1]
 
 
 def estimate_slices(A, B, tol, workspace=None):

@@ -175,7 +175,7 @@ def test_extreme_slices_do_not_overflow_int32_in_fused_kernel():
 
 @pytest.mark.parametrize("kind", ["uniform", "lognormal", "pow2", "special"])
 @pytest.mark.parametrize("m,n,k", SHAPES)
-@pytest.mark.parametrize("s", [1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 12, 13])
+@pytest.mark.parametrize("s", [1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 12, 13, 19, 32])
 def test_dgemm_matches_oracle(kind, m, n, k, s):
     A, B = inputs(kind, m, n, k, 31)
     ws = ozimmu.alloc_workspace(m, n, k, s)
@@ -283,3 +283,67 @@ def test_estimator_on_config_lognormal_1024():
         got = ozimmu.estimate_slices(dA, dB, tol)
         assert got == oracle.estimate_slices(A, B, tol, s_max=ozimmu.MAX_SLICES)
         print("lognormal_1024 tol", tol, "->", got, flush=True)
+
+
+# ----------------------------------------------------------------------------- different slice counts
+
+PAIRS = [(1, 8), (8, 1), (3, 9), (9, 3), (2, 2), (7, 7), (13, 13), (16, 16), (18, 18), (20, 7), (7, 20), (32, 32),
+         (1, 1), (12, 5), (25, 31)]
+
+
+@pytest.mark.parametrize("kind", ["uniform", "lognormal", "special"])
+@pytest.mark.parametrize("m,n,k", [(5, 3, 2), (100, 90, 70), (257, 130, 300)])
+@pytest.mark.parametrize("sA,sB", PAIRS)
+def test_dgemm2_matches_oracle(kind, m, n, k, sA, sB):
+    A, B = inputs(kind, m, n, k, 51)
+    C = ozimmu.dgemm2(dev(A), dev(B), sA, sB, check_finite=True)
+    assert_c_matches(host(C), oracle.dgemm2(A, B, sA, sB), f"{kind} {m}x{n}x{k} sA={sA} sB={sB}")
+
+
+@pytest.mark.parametrize("sA,sB", [(1, 1), (2, 5), (5, 2), (7, 7), (12, 12), (9, 17), (20, 20)])
+def test_dgemm2_all_products_matches_oracle(sA, sB):
+    A, B = workloads.lognormal(130, 70, 200, 2.0, 52)
+    C = ozimmu.dgemm2(dev(A), dev(B), sA, sB, all_products=True)
+    assert_c_matches(host(C), oracle.dgemm2(A, B, sA, sB, full=True), f"all products sA={sA} sB={sB}")
+
+
+def test_dgemm_equals_dgemm2_with_equal_counts():
+    A, B = workloads.lognormal(200, 150, 400, 1.0, 53)
+    dA, dB = dev(A), dev(B)
+    for s in (1, 5, 7, 12, 13, 20):
+        assert bool(torch.equal(ozimmu.dgemm(dA, dB, s), ozimmu.dgemm2(dA, dB, s, s)))
+
+
+def test_band_kernel_with_int64_totals():
+    # 20 slices of A, k = 7000: more than 133144 terms can meet in one diagonal accumulator, so the
+    # band kernel has to spill to its int64 totals; entries chosen so that every slice is +-127 or 120
+    k = 7000
+    x = 1.0 - 2.0 ** -53
+    A = np.full((70, k), x); A[::3, :] = -x
+    B = np.full((k, 40), x); B[:, 1::2] *= 0.5
+    for sA, sB in ((20, 20), (20, 9), (9, 20)):
+        assert_c_matches(host(ozimmu.dgemm2(dev(A), dev(B), sA, sB)), oracle.dgemm2(A, B, sA, sB), f"totals {sA},{sB}")
+    A, B = workloads.lognormal(70, 40, 40000, 2.0, 54)
+    assert_c_matches(host(ozimmu.dgemm2(dev(A), dev(B), 14, 10)), oracle.dgemm2(A, B, 14, 10), "totals long k")
+
+
+def test_well_scaled_operand_single_slice_on_gpu():
+    rng = np.random.default_rng(8)
+    A = rng.integers(-127, 128, size=(150, 300)) * np.ldexp(1.0, rng.integers(-20, 20, size=150))[:, None]
+    _, B = workloads.lognormal(150, 90, 300, 2.0, 9)
+    dA, dB = dev(A), dev(B)
+    for s in (8, 12):
+        assert bool(torch.equal(ozimmu.dgemm2(dA, dB, 1, s), ozimmu.dgemm(dA, dB, s)))
+
+
+@pytest.mark.parametrize("kind", ["uniform", "lognormal", "special"])
+def test_estimator2_matches_oracle(kind):
+    A, B = inputs(kind, 100, 90, 70, 61)
+    dA, dB = dev(A), dev(B)
+    for tol in (1e-2, 1e-8, 1e-15, 1e-300):
+        assert ozimmu.estimate_slices2(dA, dB, tol) == oracle.estimate_slices2(A, B, tol, s_max=ozimmu.MAX_SLICES), tol
+    rng = np.random.default_rng(3)
+    A2 = np.sign(A + 0.5) * np.ldexp(1.0, rng.integers(-5, 6, size=100))[:, None]      # kappa_A = 2
+    got = ozimmu.estimate_slices2(dev(A2), dB, 1e-12)
+    assert got == oracle.estimate_slices2(A2, B, 1e-12, s_max=ozimmu.MAX_SLICES)
+    assert got[0] <= got[1]
