@@ -32,10 +32,8 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int kG = 8, kLA = 4, kLB = kG + kLA - 1;
 constexpr int kWVM = 4, kWVN = 2;                       // 8 wavefronts, 32 x 32 outputs each: tile 128 x 64
-constexpr int kUnitsA = kLA * kWVM, kUnitsB = kLB * kWVN;
-constexpr int kUnits = kUnitsA + kUnitsB;               // 1 KiB fragments per stage
-constexpr int kStageBytes = kUnits * kFragBytes;
 constexpr int kPersistentGroups = 256;                  // work-groups of the persistent grid (one per CU)
+constexpr int kLdsBytes = 160 * 1024;
 
 __device__ __forceinline__ void lds_dma16(const void *sbase, unsigned voff, unsigned ldsaddr)
 {
@@ -60,19 +58,35 @@ __device__ __forceinline__ void tile_of_block(int b, int nb, int tiles_m, int ti
     tn = in / gm;
 }
 
-template <bool TOTALS>
+// Roles: X is the operand whose slices are taken LA at a time (the one with FEWER slices: every
+// staged X slice then meets up to G diagonals), Y the one seen through the window of LB slices.
+//   CHUNK_A   X = A (else X = B); the MFMA operand order (B fragment first) does not change, so the
+//             lanes of the result always run along m
+//   KB32      32-deep k-blocks per LDS stage (1 is used: 2 measured slower, the unrolled masked body grows too long)
+template <bool CHUNK_A, int KB32>
+struct BandGeom {
+    static constexpr int FX = CHUNK_A ? kWVM : kWVN, FY = CHUNK_A ? kWVN : kWVM;   // fragment rows per tile
+    static constexpr int UX = kLA * FX, UY = kLB * FY, UNITS1 = UX + UY;           // 1 KiB units per k-block
+    static constexpr int UNITS = KB32 * UNITS1, STAGE = UNITS * kFragBytes;
+};
+
+template <bool TOTALS, bool CHUNK_A, int KB32>
 __global__ __launch_bounds__(64 * kWVM * kWVN) void gemm_banded_kernel(
     const int8_t *__restrict__ pA, const int8_t *__restrict__ pB, const int32_t *__restrict__ eA,
     const int32_t *__restrict__ eB, double *__restrict__ C, int ldc, int m, int n, int sA, int sB, int dmax, int KB,
     int tiles_m, int tiles_n, long long *__restrict__ totals, int stages_per_block)
 {
+    using Geo = BandGeom<CHUNK_A, KB32>;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wm = wave % kWVM, wn = wave / kWVM;
+    const int wx = CHUNK_A ? wm : wn, wy = CHUNK_A ? wn : wm;
+    const int sX = CHUNK_A ? sA : sB, sY = CHUNK_A ? sB : sA;
     const int ntiles = tiles_m * tiles_n;
     const int nrounds = (ntiles + gridDim.x - 1) / gridDim.x;
+    const int nst = KB / KB32;
     long long *tot = TOTALS ? totals + ((size_t)blockIdx.x * (kWVM * kWVN) + wave) * (size_t)(kG * 16 * 64) + lane
                             : nullptr;
 
@@ -84,9 +98,9 @@ __global__ __launch_bounds__(64 * kWVM * kWVN) void gemm_banded_kernel(
         int tm, tn;
         tile_of_block(tile_id, ntiles, tiles_m, tiles_n, tm, tn);
 
-        const size_t rowA_bytes = (size_t)KB * sA * kFragBytes, rowB_bytes = (size_t)KB * sB * kFragBytes;
-        const int8_t *rowA = pA + (size_t)tm * kWVM * rowA_bytes;
-        const int8_t *rowB = pB + (size_t)tn * kWVN * rowB_bytes;
+        const size_t rowX_bytes = (size_t)KB * sX * kFragBytes, rowY_bytes = (size_t)KB * sY * kFragBytes;
+        const int8_t *rowX = CHUNK_A ? pA + (size_t)tm * kWVM * rowX_bytes : pB + (size_t)tn * kWVN * rowX_bytes;
+        const int8_t *rowY = CHUNK_A ? pB + (size_t)tn * kWVN * rowY_bytes : pA + (size_t)tm * kWVM * rowY_bytes;
 
         double S[16];
 #pragma unroll
@@ -101,69 +115,78 @@ __global__ __launch_bounds__(64 * kWVM * kWVN) void gemm_banded_kernel(
                 for (int r = 0; r < 16; ++r) acc[a][r] = 0;
             bool have_totals = false;
 
-            const int l_lo = d0 - sB > 1 ? d0 - sB : 1;
-            const int l_hi = dlast - 1 < sA ? dlast - 1 : sA;
-            for (int l0 = l_lo; l0 <= l_hi; l0 += kLA) {
-                const int hmin = d0 - (l0 + kLA - 1);          // slice of B in window slot 0
-                // validity of the (la, a) products of this sweep, bit la*G + a
+            const int x_lo = d0 - sY > 1 ? d0 - sY : 1;
+            const int x_hi = dlast - 1 < sX ? dlast - 1 : sX;
+            for (int x0 = x_lo; x0 <= x_hi; x0 += kLA) {
+                const int ymin = d0 - (x0 + kLA - 1);          // slice of Y in window slot 0
+                // validity of the (c, a) products of this sweep, bit c*G + a:  X slice x0+c times Y slice
+                // d0+a-(x0+c) belongs to diagonal d0+a
                 unsigned mask = 0;
 #pragma unroll
-                for (int la = 0; la < kLA; ++la)
+                for (int c = 0; c < kLA; ++c)
 #pragma unroll
                     for (int a = 0; a < kG; ++a) {
-                        const int l = l0 + la, h = d0 + a - l;
-                        if (l <= sA && l <= l_hi && h >= 1 && h <= sB && d0 + a <= dlast) mask |= 1u << (la * kG + a);
+                        const int x = x0 + c, y = d0 + a - x;
+                        if (x <= x_hi && y >= 1 && y <= sY && d0 + a <= dlast) mask |= 1u << (c * kG + a);
                     }
                 if (mask == 0) continue;
-                unsigned needA = 0, needB = 0;                  // which slices have to be staged
+                unsigned needX = 0, needY = 0;                  // which slices have to be staged
 #pragma unroll
-                for (int la = 0; la < kLA; ++la)
+                for (int c = 0; c < kLA; ++c)
 #pragma unroll
                     for (int a = 0; a < kG; ++a)
-                        if (mask >> (la * kG + a) & 1u) { needA |= 1u << la; needB |= 1u << (a - la + kLA - 1); }
+                        if (mask >> (c * kG + a) & 1u) { needX |= 1u << c; needY |= 1u << (a - c + kLA - 1); }
 
                 auto issue_stage = [&](int st, int buf) {
 #pragma unroll
-                    for (int i = 0; i < (kUnits + 7) / 8; ++i) {
+                    for (int i = 0; i < (Geo::UNITS + 7) / 8; ++i) {
                         const int u = wave + i * 8;
-                        if (u >= kUnits) break;
+                        if (u >= Geo::UNITS) break;
+                        const int kbl = u / Geo::UNITS1, v = u % Geo::UNITS1;
+                        const size_t kb = (size_t)st * KB32 + kbl;
                         const int8_t *src;
-                        if (u < kUnitsA) {
-                            const int la = u / kWVM, c = u % kWVM;
-                            if (!(needA >> la & 1u)) continue;
-                            src = rowA + (size_t)c * rowA_bytes + ((size_t)st * sA + (l0 + la - 1)) * kFragBytes;
+                        if (v < Geo::UX) {
+                            const int c = v / Geo::FX, r = v % Geo::FX;
+                            if (!(needX >> c & 1u)) continue;
+                            src = rowX + (size_t)r * rowX_bytes + (kb * sX + (x0 + c - 1)) * kFragBytes;
                         } else {
-                            const int hb = (u - kUnitsA) / kWVN, c = (u - kUnitsA) % kWVN;
-                            if (!(needB >> hb & 1u)) continue;
-                            src = rowB + (size_t)c * rowB_bytes + ((size_t)st * sB + (hmin + hb - 1)) * kFragBytes;
+                            const int yb = (v - Geo::UX) / Geo::FY, r = (v - Geo::UX) % Geo::FY;
+                            if (!(needY >> yb & 1u)) continue;
+                            src = rowY + (size_t)r * rowY_bytes + (kb * sY + (ymin + yb - 1)) * kFragBytes;
                         }
-                        lds_dma16(src, lane * 16, lds0 + buf * kStageBytes + u * kFragBytes);
+                        lds_dma16(src, lane * 16, lds0 + buf * Geo::STAGE + u * kFragBytes);
                     }
                 };
 
                 // the sweep over k, in blocks short enough for int32 (one block unless TOTALS)
-                for (int kb0 = 0; kb0 < KB; kb0 += stages_per_block) {
-                    const int kb1 = kb0 + stages_per_block < KB ? kb0 + stages_per_block : KB;
-                    issue_stage(kb0, 0);
+                for (int b0 = 0; b0 < nst; b0 += stages_per_block) {
+                    const int b1 = b0 + stages_per_block < nst ? b0 + stages_per_block : nst;
+                    issue_stage(b0, 0);
                     wait_all_vm();
                     __syncthreads();
                     int buf = 0;
-                    for (int st = kb0; st < kb1; ++st) {
-                        if (st + 1 < kb1) issue_stage(st + 1, buf ^ 1);
-                        const unsigned char *cur = lds + buf * kStageBytes;
-                        v4i bf[kLB];
+                    for (int st = b0; st < b1; ++st) {
+                        if (st + 1 < b1) issue_stage(st + 1, buf ^ 1);
 #pragma unroll
-                        for (int hb = 0; hb < kLB; ++hb)
-                            if (needB >> hb & 1u)
-                                bf[hb] = *(const v4i *)(cur + (kUnitsA + hb * kWVN + wn) * kFragBytes + lane * 16);
+                        for (int kbl = 0; kbl < KB32; ++kbl) {
+                            const unsigned char *cur = lds + buf * Geo::STAGE + kbl * Geo::UNITS1 * kFragBytes;
+                            v4i yf[kLB];
 #pragma unroll
-                        for (int la = 0; la < kLA; ++la) {
-                            if (!(needA >> la & 1u)) continue;
-                            const v4i af = *(const v4i *)(cur + (la * kWVM + wm) * kFragBytes + lane * 16);
+                            for (int yb = 0; yb < kLB; ++yb)
+                                if (needY >> yb & 1u)
+                                    yf[yb] = *(const v4i *)(cur + (Geo::UX + yb * Geo::FY + wy) * kFragBytes + lane * 16);
 #pragma unroll
-                            for (int a = 0; a < kG; ++a)
-                                if (mask >> (la * kG + a) & 1u)
-                                    acc[a] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bf[a - la + kLA - 1], af, acc[a], 0, 0, 0);
+                            for (int c = 0; c < kLA; ++c) {
+                                if (!(needX >> c & 1u)) continue;
+                                const v4i xf = *(const v4i *)(cur + (c * Geo::FX + wx) * kFragBytes + lane * 16);
+#pragma unroll
+                                for (int a = 0; a < kG; ++a)
+                                    if (mask >> (c * kG + a) & 1u) {
+                                        const v4i yv = yf[a - c + kLA - 1];
+                                        acc[a] = CHUNK_A ? __builtin_amdgcn_mfma_i32_32x32x32_i8(yv, xf, acc[a], 0, 0, 0)
+                                                         : __builtin_amdgcn_mfma_i32_32x32x32_i8(xf, yv, acc[a], 0, 0, 0);
+                                    }
+                            }
                         }
                         wait_all_vm();
                         __syncthreads();
@@ -220,14 +243,39 @@ __global__ __launch_bounds__(64 * kWVM * kWVN) void gemm_banded_kernel(
     }
 }
 
+template <bool TOTALS, bool CHUNK_A, int KB32>
+hipError_t launch_band(int m, int n, int kp, int sA, int sB, int dmax, const int8_t *pA, const int8_t *pB,
+                       const int32_t *eA, const int32_t *eB, double *C, int ldc, long long *totals, hipStream_t st)
+{
+    using Geo = BandGeom<CHUNK_A, KB32>;
+    static_assert(2 * Geo::STAGE <= kLdsBytes, "LDS double buffer too large");
+    auto kern = gemm_banded_kernel<TOTALS, CHUNK_A, KB32>;
+    static bool configured = false;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * Geo::STAGE);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    const int tiles_m = (m + 127) / 128, tiles_n = (n + 63) / 64;
+    const int ntiles = tiles_m * tiles_n;
+    const int grid = ntiles < kPersistentGroups ? ntiles : kPersistentGroups;
+    const int KB = kp / kFrag, nst = KB / KB32;
+    // a k-block adds at most LA products of (32 * KB32 * stages) terms to an accumulator
+    const int stages_per_block = TOTALS ? (int)(kMaxInt32K / kLA / kFrag) / KB32 : nst;
+    kern<<<grid, 64 * kWVM * kWVN, 2 * Geo::STAGE, st>>>(pA, pB, eA, eB, C, ldc, m, n, sA, sB, dmax, KB, tiles_m,
+                                                         tiles_n, totals, stages_per_block);
+    return hipGetLastError();
+}
+
 }  // namespace
 
 size_t banded_totals_bytes(int sA, int sB, int k)
 {
-    // without totals an accumulator of a group receives at most ceil(sm / LA) * LA products of kp terms
-    // each (sm: slices of the chunked operand); that has to fit int32
+    // without totals an accumulator of a group receives at most ceil(sX / LA) * LA products of kp terms
+    // each (sX: slices of the chunked operand, the smaller count); that has to fit int32
     const long long kp = round_up(k > 0 ? k : 1, kPad);
-    const long long chunks = (sA + kLA - 1) / kLA;
+    const long long sX = sA <= sB ? sA : sB;
+    const long long chunks = (sX + kLA - 1) / kLA;
     if (chunks * kLA * kp <= kMaxInt32K) return 0;
     return (size_t)kPersistentGroups * (kWVM * kWVN) * kG * 16 * 64 * sizeof(long long);
 }
@@ -237,30 +285,13 @@ hipError_t launch_gemm_banded(int m, int n, int kp, int sA, int sB, int dmax, co
                               hipStream_t st)
 {
     if (m <= 0 || n <= 0) return hipSuccess;
-    static bool configured = false;
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute((const void *)gemm_banded_kernel<false>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kStageBytes);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute((const void *)gemm_banded_kernel<true>,
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kStageBytes);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
-    const int tiles_m = (m + 127) / 128, tiles_n = (n + 63) / 64;
-    const int ntiles = tiles_m * tiles_n;
-    const int grid = ntiles < kPersistentGroups ? ntiles : kPersistentGroups;
-    const int KB = kp / kFrag;
+    const bool chunk_a = sA <= sB;
     if (totals) {
-        // a k-block adds at most LA products of (32 * stages) terms to an accumulator
-        const int stages_per_block = (int)(kMaxInt32K / kLA / kFrag);
-        gemm_banded_kernel<true><<<grid, 64 * kWVM * kWVN, 2 * kStageBytes, st>>>(
-            pA, pB, eA, eB, C, ldc, m, n, sA, sB, dmax, KB, tiles_m, tiles_n, totals, stages_per_block);
-    } else {
-        gemm_banded_kernel<false><<<grid, 64 * kWVM * kWVN, 2 * kStageBytes, st>>>(
-            pA, pB, eA, eB, C, ldc, m, n, sA, sB, dmax, KB, tiles_m, tiles_n, nullptr, KB);
+        return chunk_a ? launch_band<true, true, 1>(m, n, kp, sA, sB, dmax, pA, pB, eA, eB, C, ldc, totals, st)
+                       : launch_band<true, false, 1>(m, n, kp, sA, sB, dmax, pA, pB, eA, eB, C, ldc, totals, st);
     }
-    return hipGetLastError();
+    return chunk_a ? launch_band<false, true, 1>(m, n, kp, sA, sB, dmax, pA, pB, eA, eB, C, ldc, nullptr, st)
+                   : launch_band<false, false, 1>(m, n, kp, sA, sB, dmax, pA, pB, eA, eB, C, ldc, nullptr, st);
 }
 
 }  // namespace oz
