@@ -347,3 +347,14 @@ def test_estimator2_matches_oracle(kind):
     got = ozimmu.estimate_slices2(dev(A2), dB, 1e-12)
     assert got == oracle.estimate_slices2(A2, B, 1e-12, s_max=ozimmu.MAX_SLICES)
     assert got[0] <= got[1]
+
+
+@pytest.mark.parametrize("kappa_d", [1e10, 1e20, 1e30, 1e40])
+def test_badly_scaled_workload_matches_oracle(kappa_d):
+    # the diagonal-scaling test of the GPU benchmark section, slice counts as used there
+    A, B = workloads.diag_scaled(200, kappa_d, 7)
+    dA, dB = dev(A), dev(B)
+    est = ozimmu.estimate_slices(dA, dB, 2.0 ** -53)
+    assert est == oracle.estimate_slices(A, B, 2.0 ** -53, s_max=ozimmu.MAX_SLICES)
+    for s in sorted({8, 12, 16, 18, est[0]}):
+        assert_c_matches(host(ozimmu.dgemm(dA, dB, s)), oracle.dgemm(A, B, s), f"kappa_D={kappa_d:g} s={s}")

@@ -564,3 +564,28 @@ def test_two_dimensional_estimator_against_brute_force():
     rT = oracle.estimate_slices2(B.T.copy(), A.T.copy(), 1e-12)
     assert oracle.chi(r[0], r[1]) == oracle.chi(rT[0], rT[1])
     assert oracle.estimate_slices2(A, B, 1e-300)[:3] == (32, 32, oracle.UNREACHABLE)
+
+
+def test_badly_scaled_product_outcomes_of_the_gpu_benchmark_section():
+    # A = Abar D, B = D^-1 Bbar, Abar, Bbar ~ U(1,2), geometric D with condition kappa_D, rows of A and
+    # columns of B rotated.  Stated outcomes: 8 slices are not enough already at kappa_D = 1e10; more
+    # slices recover binary64 accuracy for the lower kappa_D; 18 slices fail at 1e30 and 1e40.
+    # (Reference in 80-bit arithmetic: all terms are positive, so it is accurate to ~1e-19.)
+    n = 64
+
+    def err(kd, s):
+        A, B = workloads.diag_scaled(n, kd, 7)
+        ref = A.astype(np.longdouble) @ B.astype(np.longdouble)
+        C = oracle.dgemm(A, B, s).astype(np.longdouble)
+        return float(np.max(np.abs((C - ref) / ref)))
+
+    assert err(1e10, 8) > 1e-9
+    assert err(1e10, 16) < 4 * U * 8
+    assert err(1e20, 12) > 1e-9 and err(1e20, 18) < 4 * U * 8
+    assert err(1e30, 18) > 1e-10
+    assert err(1e40, 18) > 1e-3
+    # the slice estimate asks for enough slices in every case
+    for kd in (1e10, 1e20, 1e30):
+        A, B = workloads.diag_scaled(n, kd, 7)
+        s = oracle.estimate_slices(A, B, 2.0 ** -53)[0]
+        assert err(kd, s) < 4 * U * 8
