@@ -14,34 +14,15 @@
 // The MFMA is issued "transposed": the B-plane fragment is the first operand and the A-plane
 // fragment the second, so that in the 32x32 result lane%32 runs along m.  C is column-major, so
 // each accumulator register then stores 32 consecutive doubles of a column: 256 B segments.
-#include "oz_common.h"
+#include "gemm_dev.h"
 
 namespace oz {
 
 namespace {
 
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v16i __attribute__((ext_vector_type(16)));
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));   // 16-byte copy unit
 
 constexpr int kThreads = 256;   // generic kernel: 4 wavefronts, 2 (m) x 2 (n)
-
-// XCD-aware tile order.  Work-groups are dealt round-robin to the 8 XCDs (id % 8), each with
-// its own L2.  Renumber so that an XCD owns a contiguous run of tiles, and walk the run in
-// groups of GM tile-rows so that tiles resident at the same time share A and B panels in L2.
-__device__ __forceinline__ void tile_of_block(int b, int nb, int tiles_m, int tiles_n, int &tm, int &tn)
-{
-    const int xcd = b & 7, idx = b >> 3;
-    const int q = nb >> 3, rem = nb & 7;
-    const int lin = xcd * q + (xcd < rem ? xcd : rem) + idx;
-    constexpr int GM = 4;
-    const int group = GM * tiles_n;
-    const int g = lin / group, in = lin - g * group;
-    const int first = g * GM;
-    const int gm = tiles_m - first < GM ? tiles_m - first : GM;
-    tm = first + in % gm;
-    tn = in / gm;
-}
 
 // =============================== fused kernel ===========================================
 // All s diagonals live in int32 accumulators for the whole contraction; needs
@@ -63,21 +44,6 @@ __device__ __forceinline__ void tile_of_block(int b, int nb, int tiles_m, int ti
 //                  int64 totals in HBM with integer atomics -- exact, so the totals do not depend on
 //                  the order of arrival and the result stays bit-reproducible; finish_blocked_kernel
 //                  then does the binary64 accumulation
-
-// 16 bytes per lane: global (sbase + voff)  ->  LDS (ldsaddr + lane * 16); ldsaddr is wavefront-uniform
-__device__ __forceinline__ void lds_dma16(const void *sbase, unsigned voff, unsigned ldsaddr)
-{
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(ldsaddr), "v"(voff), "s"(sbase)
-                 : "memory", "m0");
-}
-
-template <int N>
-__device__ __forceinline__ void wait_vmcnt()
-{
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
-
-enum FusedMode { kPlain = 0, kDump = 1, kBlocked = 2 };
 
 template <int S, int WVM, int WVN, int WMF, int WNF, int KB32, int NSTAGE, int MODE>
 __global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t *__restrict__ pA,
@@ -388,8 +354,6 @@ __global__ __launch_bounds__(kThreads) void gemm_generic_kernel(const int8_t *__
 }
 
 // ------------------------------- launch tables --------------------------------------------
-constexpr int kLdsBytes = 160 * 1024;
-
 // Tile shapes per slice count, picked from a sweep at 8192^3 on random slices (all candidates
 // land within a few percent of each other: the kernel is limited by the chip's power budget
 // once the matrix cores are kept fed, not by a single pipe).
@@ -480,7 +444,8 @@ size_t fused_totals_bytes(int s, int m, int n, int k)
 {
     if (s < 1 || s > kFusedMaxS || fused_single_block(s, k) || m <= 0 || n <= 0) return 0;
     int tm = 128, tn = 128;
-    switch (s) {
+    if (fused16_preferred(s)) fused16_tile(s, tm, tn);
+    else switch (s) {
 #define OZ_CASE(S_) case S_: fused_tile<S_>(tm, tn); break;
         OZ_CASE(1) OZ_CASE(2) OZ_CASE(3) OZ_CASE(4) OZ_CASE(5) OZ_CASE(6) OZ_CASE(7) OZ_CASE(8) OZ_CASE(9) OZ_CASE(10) OZ_CASE(11) OZ_CASE(12)
 #undef OZ_CASE
@@ -493,6 +458,9 @@ hipError_t launch_gemm_fused(int m, int n, int kp, int s, const int8_t *pA, cons
                              const int32_t *eB, double *C, int ldc, int32_t *dump, long long *totals, hipStream_t st)
 {
     if (m <= 0 || n <= 0) return hipSuccess;
+    // the 16x16x64 kernel where it is the faster one (except k-blocked s = 9, where it would need more than
+    // 256 registers; both kernels use 128 x 64 tiles there, so the totals buffer has the same size)
+    if (fused16_preferred(s) && !(totals && s == 9)) return launch_gemm_fused16(m, n, kp, s, pA, pB, eA, eB, C, ldc, dump, totals, st);
     if (dump) return dispatch_fused<kDump>(s, m, n, kp, pA, pB, eA, eB, C, ldc, dump, nullptr, st);
     if (totals) return dispatch_fused<kBlocked>(s, m, n, kp, pA, pB, eA, eB, C, ldc, nullptr, totals, st);
     return dispatch_fused<kPlain>(s, m, n, kp, pA, pB, eA, eB, C, ldc, nullptr, nullptr, st);

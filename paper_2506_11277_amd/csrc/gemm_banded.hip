@@ -21,42 +21,17 @@
 // cut into blocks of at most 133144 / LA terms and after every block the accumulators are added,
 // exactly, into int64 totals and restart from zero; the totals live in a scratch slot per work-group
 // (the grid is persistent, so the scratch does not grow with the matrix).
-#include "oz_common.h"
+#include "gemm_dev.h"
 
 namespace oz {
 
 namespace {
 
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v16i __attribute__((ext_vector_type(16)));
-
 constexpr int kG = 8, kLA = 4, kLB = kG + kLA - 1;
 constexpr int kWVM = 4, kWVN = 2;                       // 8 wavefronts, 32 x 32 outputs each: tile 128 x 64
 constexpr int kPersistentGroups = 256;                  // work-groups of the persistent grid (one per CU)
-constexpr int kLdsBytes = 160 * 1024;
 
-__device__ __forceinline__ void lds_dma16(const void *sbase, unsigned voff, unsigned ldsaddr)
-{
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(ldsaddr), "v"(voff), "s"(sbase)
-                 : "memory", "m0");
-}
-
-__device__ __forceinline__ void wait_all_vm() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
-
-// same XCD-aware order as the fused kernel (virtual block id -> tile)
-__device__ __forceinline__ void tile_of_block(int b, int nb, int tiles_m, int tiles_n, int &tm, int &tn)
-{
-    const int xcd = b & 7, idx = b >> 3;
-    const int q = nb >> 3, rem = nb & 7;
-    const int lin = xcd * q + (xcd < rem ? xcd : rem) + idx;
-    constexpr int GM = 4;
-    const int group = GM * tiles_n;
-    const int g = lin / group, in = lin - g * group;
-    const int first = g * GM;
-    const int gm = tiles_m - first < GM ? tiles_m - first : GM;
-    tm = first + in % gm;
-    tn = in / gm;
-}
+__device__ __forceinline__ void wait_all_vm() { wait_vmcnt<0>(); }
 
 // Roles: X is the operand whose slices are taken LA at a time (the one with FEWER slices: every
 // staged X slice then meets up to G diagonals), Y the one seen through the window of LB slices.

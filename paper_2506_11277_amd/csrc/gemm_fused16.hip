@@ -1,0 +1,336 @@
+// Fused slice-product kernel built on v_mfma_i32_16x16x64_i8 (s <= 9).
+//
+// Same computation as gemm_fused_kernel in gemm.hip (all s(s+1)/2 products of Algorithm 1, Sect. 3,
+// per-diagonal int32 sums, binary64 accumulation by ascending diagonal), same plane layout, same
+// LDS-DMA staging.  The difference is the matrix instruction: on MI355X the 16x16x64 shape sustains
+// about 24 % more int8 op/s than 32x32x32 on random operands (the chip is power-limited on real
+// data, and the deeper reduction per accumulator update costs less energy per product).  Inside the
+// whole kernel the gain is smaller and not uniform: see fused16_preferred() below for where it is used.
+//
+// A 16x16x64 operand is 16 rows x 64 k: it is assembled from two consecutive 32x32 fragments of the
+// plane layout (lane l: row l%16 of the half, k-group l/16 -> fragment (l/16)/2, its lane slot
+// row + 32*((l/16)%2)), the same way for A and B, so the k positions of both operands match.
+// A stage therefore holds 64 k, which for s >= 7 no longer fits twice into the 160 KiB of LDS.
+// For those slice counts the stage is split: the slices l >= L0 of the A tile sit in a
+// single-buffered region and are multiplied FIRST; a barrier then frees that region and the next
+// stage's copy of it is issued, to land while the remaining products run.  The rest of the stage
+// (A slices l < L0, all of B) is double-buffered as before.
+#include "gemm_dev.h"
+
+namespace oz {
+
+namespace {
+
+template <int S>
+struct Cfg16 {
+    // tile 128 x 128 (2 x 4 wavefronts of 64 x 32) while 32 * S accumulator registers are affordable and the
+    // stages fit, else 128 x 64 (4 x 2 wavefronts of 32 x 32)
+    static constexpr bool WIDE = S <= 4;
+    static constexpr int WVM = WIDE ? 2 : 4, WVN = WIDE ? 4 : 2, WMF = WIDE ? 2 : 1, WNF = 1;
+    static constexpr int FA = WVM * WMF, FB = WVN * WNF;          // 32-row fragment rows of the tile
+    // A slices [0, L0) are double-buffered with B; A slices [L0, S) single-buffered (L0 == S: no split)
+    static constexpr int L0 = S <= 6 ? S : 20 - 2 * S;
+    static constexpr int P1 = (FA * L0 + FB * S) * 2 * kFragBytes;    // double-buffered part of a 64-k stage
+    static constexpr int P2 = FA * (S - L0) * 2 * kFragBytes;         // single-buffered part
+    static constexpr int NBUF = (L0 == S && 3 * P1 <= kLdsBytes && S <= 3) ? 3 : 2;
+    static constexpr int LDS = NBUF * P1 + P2;
+    static_assert(LDS <= kLdsBytes, "stages do not fit LDS");
+};
+
+template <int S, int MODE>
+__global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused16_kernel(
+    const int8_t *__restrict__ pA, const int8_t *__restrict__ pB, const int32_t *__restrict__ eA,
+    const int32_t *__restrict__ eB, double *__restrict__ C, int ldc, int m, int n, int KB, int tiles_m, int tiles_n,
+    int32_t *__restrict__ dump, long long *__restrict__ totals, int stages_per_block)
+{
+    using G = Cfg16<S>;
+    constexpr int WVM = G::WVM, WVN = G::WVN, WMF = G::WMF, WNF = G::WNF, FA = G::FA, FB = G::FB, L0 = G::L0;
+    constexpr int NW = WVM * WVN, NBUF = G::NBUF;
+    constexpr bool SPLIT = L0 < S;
+    constexpr int NS2 = SPLIT ? S - L0 : 1;                         // slices in the single-buffered region
+    constexpr bool DUMP = MODE == kDump;
+    // 1 KiB copy units of a stage.  P1: A rows c < FA, k-halves kk < 2, slices l < L0, then B rows, kk, all
+    // slices.  P2: A rows, kk, slices l >= L0.  Inside a (row, kk) group slices are contiguous in HBM and LDS.
+    constexpr int U1A = FA * 2 * L0, U1 = U1A + FB * 2 * S, U2 = FA * 2 * (S - L0);
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds;
+    constexpr int Z = NBUF * G::P1;                                  // offset of the single-buffered region
+
+    int tm, tn;
+    tile_of_block(blockIdx.x, gridDim.x, tiles_m, tiles_n, tm, tn);
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wm = wave % WVM, wn = wave / WVM;
+    const size_t row_bytes = (size_t)KB * (S * kFragBytes);
+    const int8_t *rowA = pA + (size_t)tm * FA * row_bytes;
+    const int8_t *rowB = pB + (size_t)tn * FB * row_bytes;
+
+    // stage `st` covers 32-k blocks 2*st and 2*st+1
+    auto issue_p1 = [&](int st, int buf) {
+#pragma unroll
+        for (int i = 0; i < (U1 + NW - 1) / NW; ++i) {
+            const int u = wave + i * NW;
+            if (u >= U1) break;
+            const int8_t *src;
+            if (u < U1A) {
+                const int c = u / (2 * L0), kk = (u / L0) % 2, l = u % L0;
+                src = rowA + (size_t)c * row_bytes + ((size_t)(2 * st + kk) * S + l) * kFragBytes;
+            } else {
+                const int v = u - U1A;
+                const int c = v / (2 * S), kk = (v / S) % 2, h = v % S;
+                src = rowB + (size_t)c * row_bytes + ((size_t)(2 * st + kk) * S + h) * kFragBytes;
+            }
+            lds_dma16(src, lane * 16, lds0 + buf * G::P1 + u * kFragBytes);
+        }
+    };
+    auto issue_p2 = [&](int st) {
+#pragma unroll
+        for (int i = 0; i < (U2 + NW - 1) / NW; ++i) {
+            const int u = wave + i * NW;
+            if (u >= U2) break;
+            const int c = u / (2 * NS2), kk = (u / NS2) % 2, l = L0 + u % NS2;
+            const int8_t *src = rowA + (size_t)c * row_bytes + ((size_t)(2 * st + kk) * S + l) * kFragBytes;
+            lds_dma16(src, lane * 16, lds0 + Z + u * kFragBytes);
+        }
+    };
+
+    // accumulators: per diagonal a and 32x32 fragment (i, j) four 16x16 blocks (i2, j2)
+    v4i acc[S][WMF][WNF][4];
+#pragma unroll
+    for (int a = 0; a < S; ++a)
+#pragma unroll
+        for (int i = 0; i < WMF; ++i)
+#pragma unroll
+            for (int j = 0; j < WNF; ++j)
+#pragma unroll
+                for (int b = 0; b < 4; ++b) acc[a][i][j][b] = v4i{0, 0, 0, 0};
+
+    const int nst_all = KB / 2;
+    const int st0 = MODE == kBlocked ? (int)blockIdx.y * stages_per_block : 0;
+    const int nst = MODE == kBlocked && st0 + stages_per_block < nst_all ? st0 + stages_per_block : nst_all;
+
+    issue_p1(st0, 0);
+    if (SPLIT) issue_p2(st0);
+    if (NBUF == 3 && nst - st0 > 1) issue_p1(st0 + 1, 1);
+    // (a ring of three keeps one stage in flight; its size per wavefront is (U1 + NW - 1) / NW or one less)
+    constexpr int UPW = U1 / NW, UREM = U1 % NW;
+    const bool extra = wave < UREM;
+    auto wait_keep1 = [&]() {
+        if (extra) wait_vmcnt<UPW + 1>(); else wait_vmcnt<UPW>();
+    };
+    if (NBUF == 3 && nst - st0 > 1) wait_keep1(); else wait_vmcnt<0>();
+    __syncthreads();
+
+    // this lane's part of a 16x64 operand: row lane%16 of the half, k-group g = lane/16
+    const int lofs = ((lane >> 4) >> 1) * S * kFragBytes + ((lane & 15) + 32 * ((lane >> 4) & 1)) * 16;
+    const int lofs2 = ((lane >> 4) >> 1) * NS2 * kFragBytes + ((lane & 15) + 32 * ((lane >> 4) & 1)) * 16;
+    const int lofs1 = ((lane >> 4) >> 1) * L0 * kFragBytes + ((lane & 15) + 32 * ((lane >> 4) & 1)) * 16;
+
+    int buf = 0;
+    for (int st = st0; st < nst; ++st) {
+        const bool ahead = st + NBUF - 1 < nst;
+        if (ahead) issue_p1(st + NBUF - 1, buf == 0 ? NBUF - 1 : buf - 1);
+        const unsigned char *cur = lds + buf * G::P1;
+
+        v4i bf[S][WNF][2];
+#pragma unroll
+        for (int h = 0; h < S; ++h)
+#pragma unroll
+            for (int j = 0; j < WNF; ++j)
+#pragma unroll
+                for (int j2 = 0; j2 < 2; ++j2)
+                    bf[h][j][j2] = *(const v4i *)(cur + (U1A + (wn * WNF + j) * 2 * S + h) * kFragBytes + lofs + j2 * 256);
+
+        // slices of A from the last to the first, so that the single-buffered ones (l >= L0) go first
+#pragma unroll
+        for (int l = S - 1; l >= 0; --l) {
+            v4i af[WMF][2];
+#pragma unroll
+            for (int i = 0; i < WMF; ++i)
+#pragma unroll
+                for (int i2 = 0; i2 < 2; ++i2)
+                    af[i][i2] = l >= L0 ? *(const v4i *)(lds + Z + ((wm * WMF + i) * 2 * NS2 + (l - L0)) * kFragBytes +
+                                                          lofs2 + i2 * 256)
+                                        : *(const v4i *)(cur + ((wm * WMF + i) * 2 * L0 + l) * kFragBytes + lofs1 + i2 * 256);
+#pragma unroll
+            for (int h = 0; h < S - l; ++h)
+#pragma unroll
+                for (int i = 0; i < WMF; ++i)
+#pragma unroll
+                    for (int j = 0; j < WNF; ++j)
+#pragma unroll
+                        for (int i2 = 0; i2 < 2; ++i2)
+#pragma unroll
+                            for (int j2 = 0; j2 < 2; ++j2)
+                                acc[l + h][i][j][i2 * 2 + j2] = __builtin_amdgcn_mfma_i32_16x16x64_i8(
+                                    bf[h][j][j2], af[i][i2], acc[l + h][i][j][i2 * 2 + j2], 0, 0, 0);
+            if (SPLIT && l == L0) {
+                // every wavefront is done with the single-buffered slices: refill them for the next stage
+                __syncthreads();
+                if (st + 1 < nst) issue_p2(st + 1);
+            }
+        }
+        if (NBUF == 3 && ahead) wait_keep1(); else wait_vmcnt<0>();
+        __syncthreads();
+        buf = buf + 1 == NBUF ? 0 : buf + 1;
+    }
+
+    // element of accumulator block (i2, j2), register r: m_local = 16*i2 + lane%16, n_local = 16*j2 + 4*(lane/16) + r
+    const int m0 = (tm * FA + wm * WMF) * 32, n0 = (tn * FB + wn * WNF) * 32;
+    if (MODE == kBlocked) {
+        long long *tot = totals + ((size_t)(tm * tiles_n + tn) * NW + wave) * (size_t)(S * WMF * WNF * 16 * 64) + lane;
+#pragma unroll
+        for (int a = 0; a < S; ++a)
+#pragma unroll
+            for (int i = 0; i < WMF; ++i)
+#pragma unroll
+                for (int j = 0; j < WNF; ++j)
+#pragma unroll
+                    for (int b = 0; b < 4; ++b)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            __hip_atomic_fetch_add(tot + ((((size_t)a * WMF + i) * WNF + j) * 16 + b * 4 + r) * 64,
+                                                   (long long)acc[a][i][j][b][r], __ATOMIC_RELAXED,
+                                                   __HIP_MEMORY_SCOPE_AGENT);
+        return;
+    }
+#pragma unroll
+    for (int i = 0; i < WMF; ++i)
+#pragma unroll
+        for (int i2 = 0; i2 < 2; ++i2) {
+            const int mi = m0 + i * 32 + i2 * 16 + (lane & 15);
+            if (mi >= m) continue;
+            const int ea = DUMP ? 0 : eA[mi];
+#pragma unroll
+            for (int j = 0; j < WNF; ++j)
+#pragma unroll
+                for (int j2 = 0; j2 < 2; ++j2)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int nj = n0 + j * 32 + j2 * 16 + 4 * (lane >> 4) + r;
+                        if (nj >= n) continue;
+                        if (DUMP) {
+#pragma unroll
+                            for (int a = 0; a < S; ++a)
+                                dump[(size_t)a * m * n + mi + (size_t)nj * m] = acc[a][i][j][i2 * 2 + j2][r];
+                        } else {
+                            double sum = 0.0;
+#pragma unroll
+                            for (int a = 0; a < S; ++a)
+                                sum = sum + (double)acc[a][i][j][i2 * 2 + j2][r] * __builtin_ldexp(1.0, -kSliceBits * (a + 2));
+                            C[mi + (size_t)nj * ldc] = ldexp(sum, ea + eB[nj]);
+                        }
+                    }
+        }
+}
+
+// Second step of the k-blocked mode: binary64 accumulation from the int64 totals, same element
+// mapping and order of additions as the epilogue above.
+template <int S>
+__global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void finish_blocked16_kernel(
+    const long long *__restrict__ totals, const int32_t *__restrict__ eA, const int32_t *__restrict__ eB,
+    double *__restrict__ C, int ldc, int m, int n, int tiles_n)
+{
+    using G = Cfg16<S>;
+    constexpr int WVM = G::WVM, WVN = G::WVN, WMF = G::WMF, WNF = G::WNF, FA = G::FA, FB = G::FB, NW = WVM * WVN;
+    const int tm = blockIdx.x / tiles_n, tn = blockIdx.x % tiles_n;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave % WVM, wn = wave / WVM;
+    const long long *tot = totals + ((size_t)blockIdx.x * NW + wave) * (size_t)(S * WMF * WNF * 16 * 64) + lane;
+    const int m0 = (tm * FA + wm * WMF) * 32, n0 = (tn * FB + wn * WNF) * 32;
+    for (int i = 0; i < WMF; ++i)
+        for (int i2 = 0; i2 < 2; ++i2) {
+            const int mi = m0 + i * 32 + i2 * 16 + (lane & 15);
+            if (mi >= m) continue;
+            const int ea = eA[mi];
+            for (int j = 0; j < WNF; ++j)
+                for (int j2 = 0; j2 < 2; ++j2)
+                    for (int r = 0; r < 4; ++r) {
+                        const int nj = n0 + j * 32 + j2 * 16 + 4 * (lane >> 4) + r;
+                        if (nj >= n) continue;
+                        double sum = 0.0;
+#pragma unroll
+                        for (int a = 0; a < S; ++a) {
+                            const long long v = tot[((((size_t)a * WMF + i) * WNF + j) * 16 + (i2 * 2 + j2) * 4 + r) * 64];
+                            sum = sum + (double)v * __builtin_ldexp(1.0, -kSliceBits * (a + 2));   // exact conversion
+                        }
+                        C[mi + (size_t)nj * ldc] = ldexp(sum, ea + eB[nj]);
+                    }
+        }
+}
+
+__global__ void zero16_i64_kernel(long long *p, size_t n)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0;
+}
+
+template <int S, int MODE>
+hipError_t launch16_s(int m, int n, int kp, const int8_t *pA, const int8_t *pB, const int32_t *eA, const int32_t *eB,
+                      double *C, int ldc, int32_t *dump, long long *totals, hipStream_t st)
+{
+    using G = Cfg16<S>;
+    constexpr int TM = 32 * G::FA, TN = 32 * G::FB, THREADS = 64 * G::WVM * G::WVN;
+    static_assert(kPad % TM == 0 && kPad % TN == 0, "tiles must divide the padding");
+    auto kern = gemm_fused16_kernel<S, MODE>;
+    static bool configured = false;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    const int tiles_m = (m + TM - 1) / TM, tiles_n = (n + TN - 1) / TN;
+    const int KB = kp / kFrag;
+    if (MODE != kBlocked) {
+        kern<<<tiles_m * tiles_n, THREADS, G::LDS, st>>>(pA, pB, eA, eB, C, ldc, m, n, KB, tiles_m, tiles_n, dump,
+                                                         nullptr, 0);
+        return hipGetLastError();
+    }
+    // longest k-block (in 64-k stages) whose s products per diagonal cannot overflow int32
+    const int stages_per_block = (int)(kMaxInt32K / S / (2 * kFrag));
+    const int nst = KB / 2;
+    const int nblocks = (nst + stages_per_block - 1) / stages_per_block;
+    zero16_i64_kernel<<<2048, 256, 0, st>>>(totals, (size_t)tiles_m * tiles_n * S * TM * TN);
+    dim3 grid(tiles_m * tiles_n, nblocks);
+    kern<<<grid, THREADS, G::LDS, st>>>(pA, pB, eA, eB, C, ldc, m, n, KB, tiles_m, tiles_n, nullptr, totals,
+                                        stages_per_block);
+    finish_blocked16_kernel<S><<<tiles_m * tiles_n, THREADS, 0, st>>>(totals, eA, eB, C, ldc, m, n, tiles_n);
+    return hipGetLastError();
+}
+
+template <int MODE>
+hipError_t dispatch16(int s, int m, int n, int kp, const int8_t *pA, const int8_t *pB, const int32_t *eA,
+                      const int32_t *eB, double *C, int ldc, int32_t *dump, long long *totals, hipStream_t st)
+{
+    switch (s) {
+#define OZ_CASE(S_) \
+    case S_: return launch16_s<S_, MODE>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, st);
+        OZ_CASE(4) OZ_CASE(8) OZ_CASE(9)
+#undef OZ_CASE
+    }
+    return hipErrorInvalidValue;
+}
+
+}  // namespace
+
+// Slice counts for which this kernel is the faster one at 8192^3 (s = 4: +10 %, 8: +12 %, 9: +4 %; equal
+// within noise at 7; the 32x32x32 kernel wins at 2, 3, 5, 6 where this one cannot use its wider tile or
+// issues too many LDS reads per matrix instruction).  Only these are instantiated.
+bool fused16_preferred(int s) { return s == 4 || s == 8 || s == 9; }
+
+void fused16_tile(int s, int &tm, int &tn)
+{
+    tm = 128;
+    tn = s <= 4 ? 128 : 64;
+}
+
+hipError_t launch_gemm_fused16(int m, int n, int kp, int s, const int8_t *pA, const int8_t *pB, const int32_t *eA,
+                               const int32_t *eB, double *C, int ldc, int32_t *dump, long long *totals,
+                               hipStream_t st)
+{
+    if (m <= 0 || n <= 0) return hipSuccess;
+    if (dump) return dispatch16<kDump>(s, m, n, kp, pA, pB, eA, eB, C, ldc, dump, nullptr, st);
+    if (totals) return dispatch16<kBlocked>(s, m, n, kp, pA, pB, eA, eB, C, ldc, nullptr, totals, st);
+    return dispatch16<kPlain>(s, m, n, kp, pA, pB, eA, eB, C, ldc, nullptr, nullptr, st);
+}
+
+}  // namespace oz

@@ -224,6 +224,21 @@ def test_k_blocked_accumulation_beyond_the_int32_range():
     assert_c_matches(host(ozimmu.dgemm(dev(A), dev(B), 7)), oracle.dgemm(A, B, 7), "k-blocked lognormal")
 
 
+@pytest.mark.parametrize("s", [4, 8, 9, 12])
+def test_k_blocked_on_every_fused_kernel(s):
+    # both fused kernels (16x16x64 for s = 4, 8; 32x32x32 otherwise) in split-k mode, several tiles and k-blocks
+    m, n = 130, 70
+    k = 3 * (133144 // s) + 200
+    k = min(k, 70000)
+    print(f"k-blocked s={s} k={k}", flush=True)
+    A, B = workloads.lognormal(m, n, k, 2.0, 80 + s)
+    assert_c_matches(host(ozimmu.dgemm(dev(A), dev(B), s)), oracle.dgemm(A, B, s), f"k-blocked s={s}")
+    x = 1.0 - 2.0 ** -53
+    A = np.full((m, k), x); A[::3, :] = -x
+    B = np.full((k, n), x); B[:, 1::2] *= 0.5
+    assert_c_matches(host(ozimmu.dgemm(dev(A), dev(B), s)), oracle.dgemm(A, B, s), f"k-blocked extreme s={s}")
+
+
 def test_runs_are_bit_identical():
     A, B = workloads.lognormal(300, 200, 500, 1.0, 5)
     dA, dB = dev(A), dev(B)
