@@ -88,6 +88,20 @@ def split(side, X, s, t=7, e=None):
     return planes.transpose(0, 2, 1), e
 
 
+def split_nearest(side, X, s, t=7, e=None):
+    """Round-to-nearest slices relative to the scale 2**(e+1).  Returns (planes[s, rows, cols] int8, e)
+    with e the exponents of Algorithm 1 (not yet increased by one)."""
+    X = _f64(X)
+    rows, cols = X.shape
+    if e is None:
+        e = exponents(side, X)
+    e = np.ascontiguousarray(e, dtype=np.int32)
+    planes = np.zeros((s, cols, rows), dtype=np.int8)
+    _check(lib().oz_oracle_split_nearest(ctypes.c_char(side.encode()), rows, cols, _p(X, ctypes.c_double),
+                                         max(rows, 1), s, t, _p(e, ctypes.c_int32), _p(planes, ctypes.c_int8)))
+    return planes.transpose(0, 2, 1), e
+
+
 def slice_product(Al, Bh):
     """Exact int64 product of two int8 slice matrices."""
     Al = np.asfortranarray(np.asarray(Al, dtype=np.int8))
@@ -132,6 +146,25 @@ def dgemm2(A, B, sA, sB, t=7, order=0, full=False, return_exponents=False):
     _check(lib().oz_oracle_dgemm2(m, n, k, _p(A, ctypes.c_double), max(m, 1), _p(B, ctypes.c_double),
                                   max(k, 1), _p(C, ctypes.c_double), max(m, 1), sA, sB, t, order, int(full),
                                   _p(eA, ctypes.c_int32), _p(eB, ctypes.c_int32)))
+    if return_exponents:
+        return C.T, eA, eB
+    return C.T
+
+
+def dgemm3(A, B, sA, sB, t=7, order=0, full=False, nearest=False, Q=1, return_exponents=False):
+    """dgemm2 with the two variants: slices by round-to-nearest, and diagonals accumulated in exact
+    levels of Q diagonals.  Returned exponents are those of the scales used (e + 1 when nearest)."""
+    A = _f64(A)
+    B = _f64(B)
+    m, k = A.shape
+    k2, n = B.shape
+    assert k == k2
+    C = np.zeros((n, m), dtype=np.float64)
+    eA = np.zeros(m, dtype=np.int32)
+    eB = np.zeros(n, dtype=np.int32)
+    _check(lib().oz_oracle_dgemm3(m, n, k, _p(A, ctypes.c_double), max(m, 1), _p(B, ctypes.c_double),
+                                  max(k, 1), _p(C, ctypes.c_double), max(m, 1), sA, sB, t, order, int(full),
+                                  int(nearest), Q, _p(eA, ctypes.c_int32), _p(eB, ctypes.c_int32)))
     if return_exponents:
         return C.T, eA, eB
     return C.T

@@ -9,8 +9,11 @@
  * MMA unit") step by step, in the paper's notation:
  *   alpha_i, beta_j   eq. (alpha-def), (beta-def)          -> oz_oracle_exponents
  *   A_(l), B^(h)      eq. (bit-splitting-alg), bit view     -> oz_oracle_split
+ *                     the same recursion with round-to-nearest
+ *                     (second tweak of the "Enhanced algorithm") -> oz_oracle_split_nearest
  *   A_(l) B^(h)       exact integer products, eq. (wtc-expr)-> oz_oracle_slice_product
- *   S, C              Alg. 1 accumulation and final scaling -> oz_oracle_dgemm
+ *   S, C              Alg. 1 accumulation and final scaling -> oz_oracle_dgemm, _dgemm2, _dgemm3
+ *                     (by products, by diagonals, by levels of diagonals)
  *   kappa_A, kappa_B  eq. (a-bound-row-2), (b-bound)        -> oz_oracle_kappa
  *   slice estimate    eq. (err-bound) and the recipe of the
  *                     "Discussion" subsection of Sect. 4    -> oz_oracle_estimate_slices
@@ -142,6 +145,64 @@ int oz_oracle_split(char side, int rows, int cols, const double *X, int ldx, int
     return OZ_ORACLE_OK;
 }
 
+/*
+ * Round-to-nearest splitting (second tweak of the "Enhanced algorithm" paragraph of Sect. 3).
+ * The recursion of eq. (bit-splitting-alg),
+ *     A_(l) = [ 2^{lt} ( x - sum_{r<l} 2^{-rt} A_(r) ) ],
+ * with [.] = round to nearest (ties to even) instead of truncation.  Rounding up can carry into
+ * the next higher slice, so the first slice may only use t-1 bits: the block is scaled by
+ * 2^{e+1} instead of 2^e, x = a / 2^{e+1} lies in (-1/2, 1/2), and every slice lies in
+ * [-2^{t-1}, 2^{t-1}].  The paper gives no formula for this variant; this is the reading taken.
+ *
+ * Exact arithmetic: the scaled residual rho = 2^{(l-1)t} (x - sum_{r<l} ...) is kept as the dyadic
+ * number N / 2^G (N a signed integer).  One step: y = 2^t rho, A_(l) = round(y), rho <- y - A_(l).
+ */
+static void slices_nearest(double x, int e, int s, int t, int *out)
+{
+    int neg, q;
+    uint64_t I;
+    decompose(x, &neg, &I, &q);
+    int64_t N = neg ? -(int64_t)I : (int64_t)I;
+    long G = (long)e + 1 - q;                   /* x / 2^{e+1} = N / 2^G */
+    for (int l = 1; l <= s; ++l) {
+        long g = G - t;                         /* y = N / 2^g */
+        int64_t A;
+        if (N == 0) { A = 0; }
+        else if (g <= 0) { A = N * ((int64_t)1 << (-g)); N = 0; }      /* y is an integer */
+        else if (g >= 62) { A = 0; G = g; }                            /* |y| < 2^53 / 2^62 < 1/2 */
+        else {
+            uint64_t mag = (uint64_t)(N < 0 ? -N : N), D = (uint64_t)1 << g;
+            uint64_t a = mag >> g, rem = mag & (D - 1), half = D >> 1;
+            if (rem > half || (rem == half && (a & 1))) ++a;           /* nearest, ties to even */
+            A = N < 0 ? -(int64_t)a : (int64_t)a;
+            N -= A * (int64_t)D;
+            G = g;
+        }
+        out[l - 1] = (int)A;
+    }
+}
+
+/*
+ * planes as in oz_oracle_split, slices by round-to-nearest relative to the scale 2^{e+1}:
+ *     x ~ 2^{e+1} sum_l 2^{-lt} A_(l).     e: the exponents from oz_oracle_exponents.
+ */
+int oz_oracle_split_nearest(char side, int rows, int cols, const double *X, int ldx, int s, int t,
+                            const int32_t *e, int8_t *planes)
+{
+    if ((side != 'A' && side != 'B') || rows < 0 || cols < 0 || ldx < (rows > 1 ? rows : 1) ||
+        s < 1 || s > OZ_ORACLE_MAX_SLICES || t < 2 || t > 7) return OZ_ORACLE_BAD_ARG;
+    size_t plane = (size_t)rows * cols;
+    int sl[OZ_ORACLE_MAX_SLICES];
+    for (int c = 0; c < cols; ++c)
+        for (int r = 0; r < rows; ++r) {
+            double x = X[r + (size_t)c * ldx];
+            if (!isfinite(x)) return OZ_ORACLE_NONFINITE;
+            slices_nearest(x, side == 'A' ? e[r] : e[c], s, t, sl);
+            for (int l = 1; l <= s; ++l) planes[(size_t)(l - 1) * plane + r + (size_t)c * rows] = (int8_t)sl[l - 1];
+        }
+    return OZ_ORACLE_OK;
+}
+
 /* P = Al * Bh exactly, Al m-by-k (ld m), Bh k-by-n (ld k), P m-by-n (ld m), all column-major. */
 int oz_oracle_slice_product(int m, int n, int k, const int8_t *Al, const int8_t *Bh, int64_t *P)
 {
@@ -167,24 +228,33 @@ int oz_oracle_slice_product(int m, int n, int k, const int8_t *Al, const int8_t 
  * start of the subsection "Reduction in number of products".  full = 1: all sA * sB products
  * (subsection "Computation of all products").
  *
+ * nearest = 0: slices by truncation (oz_oracle_split), scales 2^e.
+ * nearest = 1: slices by round-to-nearest (oz_oracle_split_nearest), scales 2^{e+1}.
+ *
  * order 0  "by diagonals" (the accumulation order analysed in the subsection
  *          "Accumulation in floating-point arithmetic" and the first tweak of
  *          the "Enhanced algorithm"): D_d = sum of A_(l) B^(d-l) over the
- *          computed pairs, exactly in integers; then S <- S + 2^{-dt} D_d for
- *          d = 2, 3, ..., one binary64 rounding per addition.
+ *          computed pairs, exactly in integers.  The diagonals d = 2, 3, ... are
+ *          taken Q at a time (a "level" of that subsection): the level's value
+ *              sum_{d in level} 2^{-dt} D_d
+ *          is formed exactly (as an integer multiple of 2^{-t dl}, dl the level's last
+ *          diagonal; it must be below 2^53 units, else OZ_ORACLE_BAD_ARG: such a level is
+ *          not exact in binary64), then S <- S + level, one binary64 rounding per level.
+ *          Q = 1 is the plain diagonal order.
  * order 1  literal loop nest of Algorithm 1: l outer, h inner, one binary64
- *          addition per product.
+ *          addition per product (Q ignored).
  *
- * Final step: C = diag(alpha) S diag(beta), i.e. ldexp(S_ij, eA_i + eB_j).
- * Optional outputs (may be NULL): eA[m], eB[n].
+ * Final step: C = diag(alpha) S diag(beta), i.e. ldexp(S_ij, eA_i + eB_j) with the exponents
+ * of the scales used (e or e + 1).  Optional outputs (may be NULL): eA[m], eB[n], those exponents.
  */
-int oz_oracle_dgemm2(int m, int n, int k, const double *A, int lda, const double *B, int ldb,
-                     double *C, int ldc, int sA, int sB, int t, int order, int full,
+int oz_oracle_dgemm3(int m, int n, int k, const double *A, int lda, const double *B, int ldb,
+                     double *C, int ldc, int sA, int sB, int t, int order, int full, int nearest, int Q,
                      int32_t *eA_out, int32_t *eB_out)
 {
     if (m < 0 || n < 0 || k < 0 || sA < 1 || sA > OZ_ORACLE_MAX_SLICES || sB < 1 || sB > OZ_ORACLE_MAX_SLICES ||
         t < 1 || t > 7 || lda < (m > 1 ? m : 1) || ldb < (k > 1 ? k : 1) || ldc < (m > 1 ? m : 1) ||
-        (order != 0 && order != 1) || (full != 0 && full != 1)) return OZ_ORACLE_BAD_ARG;
+        (order != 0 && order != 1) || (full != 0 && full != 1) || (nearest != 0 && nearest != 1) ||
+        (nearest && t < 2) || Q < 1) return OZ_ORACLE_BAD_ARG;
     if (m == 0 || n == 0) return OZ_ORACLE_OK;
 
     int32_t *eA = malloc(sizeof(int32_t) * (size_t)m);
@@ -195,22 +265,32 @@ int oz_oracle_dgemm2(int m, int n, int k, const double *A, int lda, const double
     if (!eA || !eB || !pa || !pb) goto done;
     if ((rc = oz_oracle_exponents('A', m, k, A, lda, eA))) goto done;
     if ((rc = oz_oracle_exponents('B', k, n, B, ldb, eB))) goto done;
-    if ((rc = oz_oracle_split('A', m, k, A, lda, sA, t, eA, pa))) goto done;
-    if ((rc = oz_oracle_split('B', k, n, B, ldb, sB, t, eB, pb))) goto done;
+    if (nearest) {
+        if ((rc = oz_oracle_split_nearest('A', m, k, A, lda, sA, t, eA, pa))) goto done;
+        if ((rc = oz_oracle_split_nearest('B', k, n, B, ldb, sB, t, eB, pb))) goto done;
+        for (int i = 0; i < m; ++i) eA[i] += 1;
+        for (int j = 0; j < n; ++j) eB[j] += 1;
+    } else {
+        if ((rc = oz_oracle_split('A', m, k, A, lda, sA, t, eA, pa))) goto done;
+        if ((rc = oz_oracle_split('B', k, n, B, ldb, sB, t, eB, pb))) goto done;
+    }
 
     const size_t planeA = (size_t)m * k, planeB = (size_t)k * n;
     const int smax = sA > sB ? sA : sB;
     const int dmax = full ? sA + sB : smax + 1;     /* largest l + h of a computed product */
 
+    int inexact_level = 0;
 #pragma omp parallel
     {
         int64_t *p = malloc(sizeof(int64_t) * (size_t)m);   /* one product column   */
         int64_t *D = malloc(sizeof(int64_t) * (size_t)m);   /* one diagonal column  */
+        __int128 *L = malloc(sizeof(__int128) * (size_t)m); /* one level column, in units of 2^{-t d} */
         double *S = malloc(sizeof(double) * (size_t)m);
 #pragma omp for schedule(dynamic, 1)
         for (int j = 0; j < n; ++j) {
             for (int i = 0; i < m; ++i) S[i] = 0.0;
             if (order == 0) {
+                for (int i = 0; i < m; ++i) L[i] = 0;
                 for (int d = 2; d <= dmax; ++d) {
                     for (int i = 0; i < m; ++i) D[i] = 0;
                     for (int l = 1; l <= sA; ++l) {
@@ -224,7 +304,19 @@ int oz_oracle_dgemm2(int m, int n, int k, const double *A, int lda, const double
                             for (int i = 0; i < m; ++i) D[i] += (int64_t)a[i] * b;
                         }
                     }
-                    for (int i = 0; i < m; ++i) S[i] = S[i] + ldexp((double)D[i], -d * t);
+                    /* level so far, now in units of 2^{-t d}:  L <- 2^t L + D_d  (exact) */
+                    for (int i = 0; i < m; ++i) L[i] = L[i] * ((__int128)1 << t) + D[i];
+                    if ((d - 1) % Q == 0 || d == dmax) {            /* d closes a level */
+                        for (int i = 0; i < m; ++i) {
+                            __int128 a = L[i] < 0 ? -L[i] : L[i];
+                            if (a >= ((__int128)1 << 53)) {
+#pragma omp atomic write
+                                inexact_level = 1;
+                            }
+                            S[i] = S[i] + ldexp((double)(int64_t)L[i], -d * t);
+                            L[i] = 0;
+                        }
+                    }
                 }
             } else {
                 for (int l = 1; l <= sA; ++l) {
@@ -243,14 +335,22 @@ int oz_oracle_dgemm2(int m, int n, int k, const double *A, int lda, const double
             }
             for (int i = 0; i < m; ++i) C[i + (size_t)j * ldc] = ldexp(S[i], eA[i] + eB[j]);
         }
-        free(p); free(D); free(S);
+        free(p); free(D); free(L); free(S);
     }
     if (eA_out) memcpy(eA_out, eA, sizeof(int32_t) * (size_t)m);
     if (eB_out) memcpy(eB_out, eB, sizeof(int32_t) * (size_t)n);
-    rc = OZ_ORACLE_OK;
+    rc = inexact_level ? OZ_ORACLE_BAD_ARG : OZ_ORACLE_OK;
 done:
     free(eA); free(eB); free(pa); free(pb);
     return rc;
+}
+
+/* Slices by truncation, accumulation diagonal by diagonal (or product by product). */
+int oz_oracle_dgemm2(int m, int n, int k, const double *A, int lda, const double *B, int ldb,
+                     double *C, int ldc, int sA, int sB, int t, int order, int full,
+                     int32_t *eA_out, int32_t *eB_out)
+{
+    return oz_oracle_dgemm3(m, n, k, A, lda, B, ldb, C, ldc, sA, sB, t, order, full, 0, 1, eA_out, eB_out);
 }
 
 /* Algorithm 1 as printed: the same number s of slices for A and B. */

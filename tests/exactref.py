@@ -62,6 +62,22 @@ def truncate(x, e, r, t):
     return int_part(x / q) * q
 
 
+def nearest(x, e, r, t):
+    """x rounded to the nearest multiple of 2^{e - r t} (ties: the even multiple); r = 0 gives 0 for
+    |x| < 2^{e-1}.  Python rounds a Fraction to the nearest integer with ties to even."""
+    q = Fraction(2) ** (e - r * t)
+    return round(Fraction(x) / q) * q
+
+
+def slices_nearest(x, e, s, t):
+    """Round-to-nearest slices relative to the scale 2^(e+1), by the closed form: the first l slices
+    together are the nearest integer to x / 2^(e+1) * 2^(lt), so slice l is the difference between
+    that integer and 2^t times the previous one."""
+    y = Fraction(x) / Fraction(2) ** (e + 1)
+    R = [round(y * Fraction(2) ** (l * t)) for l in range(0, s + 1)]
+    return [R[l] - 2 ** t * R[l - 1] for l in range(1, s + 1)]
+
+
 def matmul(A, B):
     m, k, n = len(A), len(B), len(B[0])
     return [[sum((A[i][kk] * B[kk][j] for kk in range(k)), Fraction(0)) for j in range(n)] for i in range(m)]
@@ -71,17 +87,24 @@ def absmat(A):
     return [[abs(v) for v in row] for row in A]
 
 
-def diagonal_terms(A, B, s, t, full=False, sB=None):
+def diagonal_terms(A, B, s, t, full=False, sB=None, rounding=False):
     """Exact value of each diagonal's contribution alpha beta^T o 2^{-dt} sum_{l+h=d} A_(l) B^(h),
     written with truncation operators only:  2^{-lt} alpha A_(l) = T_l(A) - T_{l-1}(A)  (this is
-    eq. (slices-eq) read backwards).  Returns {d: matrix of Fractions}."""
+    eq. (slices-eq) read backwards).  Returns {d: matrix of Fractions}.
+    rounding: the round-to-nearest variant, scales 2^(e+1) and the nearest-multiple operator in
+    place of truncation; the exponents returned are then e + 1."""
     m, k, n = len(A), len(B), len(B[0])
     sA, sB = s, (s if sB is None else sB)
     eA = block_exponents("A", A)
     eB = block_exponents("B", B)
-    dA = {l: [[truncate(A[i][kk], eA[i], l, t) - truncate(A[i][kk], eA[i], l - 1, t) for kk in range(k)]
+    cut = truncate
+    if rounding:
+        eA = [e + 1 for e in eA]
+        eB = [e + 1 for e in eB]
+        cut = nearest
+    dA = {l: [[cut(A[i][kk], eA[i], l, t) - cut(A[i][kk], eA[i], l - 1, t) for kk in range(k)]
               for i in range(m)] for l in range(1, sA + 1)}
-    dB = {h: [[truncate(B[kk][j], eB[j], h, t) - truncate(B[kk][j], eB[j], h - 1, t) for j in range(n)]
+    dB = {h: [[cut(B[kk][j], eB[j], h, t) - cut(B[kk][j], eB[j], h - 1, t) for j in range(n)]
               for kk in range(k)] for h in range(1, sB + 1)}
     out = {}
     dmax = sA + sB if full else max(sA, sB) + 1
@@ -99,10 +122,25 @@ def diagonal_terms(A, B, s, t, full=False, sB=None):
     return out, eA, eB
 
 
-def reduced_product_exact(A, B, s, t, full=False, sB=None):
+def accumulate_levels(terms, eA, eB, Q, i, j):
+    """Entry (i, j) of C from the exact diagonal terms: the diagonals d = 2, 3, ... are taken Q at a
+    time, each level summed exactly (asserted to be a binary64 number once the scales are taken
+    out), the levels added one after the other in binary64.  Returns a float."""
+    scale = Fraction(2) ** (eA[i] + eB[j])
+    ds = sorted(terms)
+    S = 0.0
+    for start in range(0, len(ds), Q):
+        level = sum((terms[d][i][j] for d in ds[start:start + Q]), Fraction(0)) / scale
+        f = float(level)
+        assert Fraction(f) == level, "level is not exact in binary64"
+        S = S + f
+    return math.ldexp(S, eA[i] + eB[j])
+
+
+def reduced_product_exact(A, B, s, t, full=False, sB=None, rounding=False):
     """C' of eq. (c-prime) (or C-tilde of eq. (wtc-expr) when full) as exact Fractions;
     s slices of A and sB (default s) slices of B."""
-    terms, _, _ = diagonal_terms(A, B, s, t, full, sB)
+    terms, _, _ = diagonal_terms(A, B, s, t, full, sB, rounding)
     m, n = len(A), len(B[0])
     C = [[Fraction(0)] * n for _ in range(m)]
     for d in sorted(terms):

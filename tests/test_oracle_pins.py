@@ -589,3 +589,181 @@ def test_badly_scaled_product_outcomes_of_the_gpu_benchmark_section():
         A, B = workloads.diag_scaled(n, kd, 7)
         s = oracle.estimate_slices(A, B, 2.0 ** -53)[0]
         assert err(kd, s) < 4 * U * 8
+
+
+# --------------------------------------------------------------------------- round-to-nearest slices
+
+@pytest.mark.parametrize("name,A,B", small_cases())
+@pytest.mark.parametrize("t,s", [(7, 1), (7, 4), (7, 9), (7, 12), (3, 5), (5, 20), (2, 9)])
+def test_nearest_slices_are_differences_of_nearest_integers(name, A, B, t, s):
+    # the first l slices together are the integer nearest to 2^{lt} x / 2^{e+1} (ties to even), for every l
+    for side, X in (("A", A), ("B", B)):
+        planes, e = oracle.split_nearest(side, X, s, t)
+        assert np.array_equal(e, oracle.exponents(side, X))
+        Xf = ex.frac_matrix(X)
+        for i in range(X.shape[0]):
+            for j in range(X.shape[1]):
+                want = ex.slices_nearest(Xf[i][j], int(e[i] if side == "A" else e[j]), s, t)
+                assert planes[:, i, j].tolist() == want, (side, i, j)
+
+
+def test_nearest_slices_on_ties_and_carries():
+    # scale exponent e = 1 (max = 1.0), so x' = x / 4 and slice values are round(x' 2^{7l}) - 128 round(x' 2^{7(l-1)})
+    t = 7
+    X = np.array([[1.0, 4 * 0.5 / 128, 4 * 1.5 / 128, 4 * 2.5 / 128, 4 * (63.5 / 128), 4 * (1 / 128 + 64 / 128 ** 2),
+                   4 * (1 / 128 + 64.5 / 128 ** 2), -4 * (2 / 128 + 127.75 / 128 ** 2), 1.0 - 2.0 ** -53]])
+    planes, e = oracle.split_nearest("A", X, 3, t)
+    assert e.tolist() == [1]
+    got = planes[:, 0, :].T.tolist()
+    assert got[0] == [32, 0, 0]                 # 1/4 = 32/128
+    assert got[1] == [0, 64, 0]                 # 0.5 -> tie to the even integer 0, remainder +64
+    assert got[2] == [2, -64, 0]                # 1.5 -> 2, remainder -64
+    assert got[3] == [2, 64, 0]                 # 2.5 -> 2
+    assert got[4] == [64, -64, 0]               # 63.5 -> 64: the first slice reaches 2^{t-1}
+    assert got[5] == [2, -64, 0]                # 1.5 again, reached as 1 + 64/128: up to the even integer 2
+    assert got[6] == [2, -64, 64]               # 1 + 64.5/128 -> 2; second: 192.5 -> 192 (even) - 256; third +64
+    assert got[7] == [-3, 0, 32]                # -(2 + 127.75/128) -> -3; -(383.75) -> -384 - (-384) = 0; +0.25*128
+    assert got[8] == [32, 0, 0]                 # 1 - 2^-53 rounds up to 1 at every cut
+
+
+@pytest.mark.parametrize("name,A,B", small_cases())
+@pytest.mark.parametrize("t", [7, 4])
+def test_nearest_reconstruction_error_is_half_a_unit(name, A, B, t):
+    for side, X in (("A", A), ("B", B)):
+        for s in (1, 2, 5, 9):
+            planes, e = oracle.split_nearest(side, X, s, t)
+            assert planes.min() >= -(2 ** (t - 1)) and planes.max() <= 2 ** (t - 1)
+            for i in range(X.shape[0]):
+                for j in range(X.shape[1]):
+                    ee = int(e[i] if side == "A" else e[j]) + 1
+                    x = Fraction(float(X[i, j]))
+                    rec = sum(Fraction(int(planes[l, i, j])) * Fraction(2) ** (ee - (l + 1) * t) for l in range(s))
+                    # nearest multiple of 2^{e+1-st}: at most half of it away, i.e. alpha 2^{-st}, the
+                    # truncation bound of eq. (a-split) with <= in place of <
+                    assert abs(x - rec) * 2 <= Fraction(2) ** (ee - s * t)
+        planes, _ = oracle.split_nearest(side, -X, 6, t)
+        planes2, _ = oracle.split_nearest(side, X, 6, t)
+        assert np.array_equal(planes, -planes2)
+
+
+def test_nearest_slices_are_exact_with_enough_slices_and_beat_truncation_on_average():
+    rng = np.random.default_rng(31)
+    X = rng.standard_normal((6, 40)) * np.exp(rng.standard_normal((6, 40)))
+    s_star = ex.min_exact_slices("A", X.tolist(), 7)
+    planes, e = oracle.split_nearest("A", X, s_star + 1, 7)
+    rec = sum(planes[l].astype(np.float64) * np.ldexp(1.0, (e[:, None] + 1) - 7 * (l + 1)) for l in range(s_star + 1))
+    # (each partial sum of this float reconstruction is exact: all terms are multiples of the last unit below 2^53 units)
+    assert np.array_equal(rec, X)
+    for s in (2, 4):
+        pt, e = oracle.split("A", X, s, 7)
+        pn, _ = oracle.split_nearest("A", X, s, 7)
+        rt = sum(pt[l].astype(np.float64) * np.ldexp(1.0, e[:, None] - 7 * (l + 1)) for l in range(s))
+        rn = sum(pn[l].astype(np.float64) * np.ldexp(1.0, (e[:, None] + 1) - 7 * (l + 1)) for l in range(s))
+        # same worst case and same mean magnitude (the unit is twice as large, the error at most half of it),
+        # but truncation always errs towards zero while the rounding error has no preferred sign
+        bias_t = (np.sign(X) * (X - rt) / np.ldexp(1.0, e[:, None] - 7 * s)).mean()
+        bias_n = (np.sign(X) * (X - rn) / np.ldexp(1.0, e[:, None] - 7 * s)).mean()
+        assert 0.4 < bias_t < 0.6 and abs(bias_n) < 0.15
+
+
+@pytest.mark.parametrize("name,A,B", small_cases()[:4])
+@pytest.mark.parametrize("t,sA,sB", [(7, 1, 1), (7, 3, 3), (7, 2, 5), (3, 6, 6), (4, 7, 3)])
+def test_nearest_variant_in_the_exact_regime(name, A, B, t, sA, sB):
+    k = A.shape[1]
+    assert math.ceil(math.log2(k)) + (max(sA, sB) + 1) * t + 1 <= 53
+    want = ex.reduced_product_exact(ex.frac_matrix(A), ex.frac_matrix(B), sA, t, sB=sB, rounding=True)
+    for order in (0, 1):
+        C, eA, eB = oracle.dgemm3(A, B, sA, sB, t, order=order, nearest=True, return_exponents=True)
+        assert np.array_equal(C, to_float_matrix(want)), order
+        assert np.array_equal(eA, oracle.exponents("A", A) + 1) and np.array_equal(eB, oracle.exponents("B", B) + 1)
+
+
+@pytest.mark.parametrize("name,A,B", small_cases()[:4])
+@pytest.mark.parametrize("s", [7, 9, 13])
+def test_nearest_variant_rounds_once_per_diagonal(name, A, B, s):
+    Af, Bf = ex.frac_matrix(A), ex.frac_matrix(B)
+    terms, eA, eB = ex.diagonal_terms(Af, Bf, s, 7, rounding=True)
+    C = oracle.dgemm3(A, B, s, s, 7, nearest=True)
+    for i in range(A.shape[0]):
+        for j in range(B.shape[1]):
+            assert C[i, j] == ex.accumulate_levels(terms, eA, eB, 1, i, j), (i, j)
+
+
+def test_nearest_variant_error_bound_and_average_gain():
+    # |C - AB| <= (zeta + s kA kB 2^{-st} + gamma (1 + ...)) |A||B| holds with the truncation constants,
+    # since |delta a| <= alpha 2^{-st} still.  On positive matrices (the U(0, 1) inputs of the GPU
+    # benchmark section) truncation errors all have one sign and add up along k; rounding errors cancel
+    rng = np.random.default_rng(77)
+    A, B = rng.random((12, 48)), rng.random((48, 10))
+    Af, Bf = ex.frac_matrix(A), ex.frac_matrix(B)
+    exact = ex.matmul(Af, Bf)
+    bound_base = ex.matmul(ex.absmat(Af), ex.absmat(Bf))
+    kA, kB = ex.kappa("A", Af), ex.kappa("B", Bf)
+    for s in (3, 5):
+        Cn = oracle.dgemm3(A, B, s, s, 7, nearest=True)
+        Ct = oracle.dgemm3(A, B, s, s, 7, nearest=False)
+        u_s = Fraction(2) ** (-7 * s)
+        zeta = kA * u_s + kB * u_s + kA * kB * u_s * u_s
+        coeff = zeta + u_s * s * kA * kB
+        gamma = Fraction(s + 1) * Fraction(U) / (1 - Fraction(s + 1) * Fraction(U))
+        errn = errt = Fraction(0)
+        for i in range(12):
+            for j in range(10):
+                en = abs(Fraction(float(Cn[i, j])) - exact[i][j])
+                assert en <= (coeff + gamma * (1 + coeff)) * bound_base[i][j]
+                errn += en
+                errt += abs(Fraction(float(Ct[i, j])) - exact[i][j])
+        assert errn < errt
+
+
+# --------------------------------------------------------------------------- levels of diagonals
+
+@pytest.mark.parametrize("name,A,B", small_cases()[:4])
+@pytest.mark.parametrize("sA,sB,full,nearest", [(8, 8, False, False), (13, 13, False, False), (5, 11, False, False),
+                                                 (6, 4, True, False), (9, 9, False, True)])
+def test_levels_of_diagonals_round_once_per_level(name, A, B, sA, sB, full, nearest):
+    # k <= 7: a level of up to 4 diagonals is an integer below 2^53 units (3 + 14 + 21 bits and carries)
+    Af, Bf = ex.frac_matrix(A), ex.frac_matrix(B)
+    terms, eA, eB = ex.diagonal_terms(Af, Bf, sA, 7, full=full, sB=sB, rounding=nearest)
+    for Q in (1, 2, 3, 4):
+        C = oracle.dgemm3(A, B, sA, sB, 7, full=full, nearest=nearest, Q=Q)
+        for i in range(A.shape[0]):
+            for j in range(B.shape[1]):
+                assert C[i, j] == ex.accumulate_levels(terms, eA, eB, Q, i, j), (Q, i, j)
+    assert np.array_equal(oracle.dgemm3(A, B, sA, sB, 7, full=full, Q=1), oracle.dgemm2(A, B, sA, sB, 7, full=full))
+
+
+def test_a_single_level_holds_the_exact_sum_of_the_products():
+    # t = 3: all diagonals of s = 9 and 12 fit one level, so nothing is rounded and C is the exact value of
+    # eq. (c-prime) (a level that is exact in binary64 has exact partial sums too, so Q = 1 agrees)
+    A, B = workloads.lognormal(6, 5, 9, 1.0, seed=5)
+    Af, Bf = ex.frac_matrix(A), ex.frac_matrix(B)
+    for s in (9, 12):
+        want = to_float_matrix(ex.reduced_product_exact(Af, Bf, s, 3))
+        assert np.array_equal(oracle.dgemm3(A, B, s, s, 3, Q=s), want)
+        assert np.array_equal(oracle.dgemm3(A, B, s, s, 3, Q=1), want)
+
+
+def test_a_level_that_is_not_exact_in_binary64_is_refused():
+    # all slices at +-127, k = 64: a diagonal of 9 products has 9 * 64 * 127^2 ~ 2^23.1; six diagonals span
+    # 35 more bits -> beyond 2^53 units
+    x = 1.0 - 2.0 ** -53
+    A = np.full((2, 64), x)
+    B = np.full((64, 2), x)
+    oracle.dgemm3(A, B, 9, 9, 7, Q=4)
+    with pytest.raises(oracle.OracleError) as ei:
+        oracle.dgemm3(A, B, 9, 9, 7, Q=6)
+    assert ei.value.code == oracle.BAD_ARG
+
+
+def test_levels_never_lose_accuracy_on_the_benchmark_distribution():
+    # rounding errors only arise across levels (subsection "Accumulation in floating-point arithmetic"):
+    # with fewer roundings the distance to the exact reduced product cannot grow on average
+    A, B = workloads.lognormal(8, 8, 64, 0.5, seed=12)
+    Af, Bf = ex.frac_matrix(A), ex.frac_matrix(B)
+    want = ex.reduced_product_exact(Af, Bf, 10, 7)
+    err = {}
+    for Q in (1, 3):
+        C = oracle.dgemm3(A, B, 10, 10, 7, Q=Q)
+        err[Q] = sum(abs(Fraction(float(C[i, j])) - want[i][j]) for i in range(8) for j in range(8))
+    assert err[3] <= err[1]
