@@ -46,6 +46,11 @@ extern "C" {
 #define OZIMMU_LAYOUT_PLAIN 0 /* plane l (0-based) at planes + l*rows*cols, column-major like X, ld = rows */
 #define OZIMMU_LAYOUT_MFMA 1  /* tiled operand layout read by the GEMM kernel, see ozimmu_split */
 
+/* how an operand is cut into slices (ozimmu_split2, ozimmu_dgemm3) */
+#define OZIMMU_SPLIT_TRUNCATE 0 /* eq. (bit-splitting-alg): round towards zero, slices in [-127, 127], scale 2^e */
+#define OZIMMU_SPLIT_NEAREST 1  /* second tweak of the "Enhanced algorithm" paragraph: round to nearest,
+                                   slices in [-64, 64], scale 2^(e+1) */
+
 /* Human-readable name of a status code (static storage). */
 const char *ozimmu_status_string(int status);
 
@@ -98,6 +103,20 @@ int ozimmu_split(char side, int rows, int cols, const double *X, int ldx, int s,
                  int8_t *planes, int32_t *exps, int layout, void *scratch, void *stream);
 
 /*
+ * ozimmu_split with the way of slicing chosen by `splitting`.  OZIMMU_SPLIT_TRUNCATE is ozimmu_split.
+ * OZIMMU_SPLIT_NEAREST (second tweak of the "Enhanced algorithm" paragraph of Sect. 3, which states the
+ * idea -- round the fixed-point representation to nearest instead of truncating it, the first slice
+ * then has t-1 bits -- but no formula; the reading implemented is the recursion of eq.
+ * (bit-splitting-alg) with round-to-nearest, ties to even, in place of truncation):
+ *   exps[b] = floor(log2 max|x|) + 2 over the block (1 for an all-zero block), i.e. the scale is doubled
+ *   so that |x| / 2^exps < 1/2;  with R_l = the integer nearest to x 2^{7l - exps} and R_0 = 0,
+ *   slice l = R_l - 128 R_{l-1}, a value in [-64, 64];  x ~ 2^exps sum_l 2^{-7l} slice_l  with an error
+ *   of at most 2^{exps - 7s - 1}, zero when enough slices are taken.
+ */
+int ozimmu_split2(char side, int rows, int cols, const double *X, int ldx, int s, int splitting,
+                  int8_t *planes, int32_t *exps, int layout, void *scratch, void *stream);
+
+/*
  * C = A B through s int8 slices (Algorithm 1 with k-blocked exact integer accumulation):
  *   1. scale exponents of the rows of A and the columns of B,
  *   2. s slices of each operand,
@@ -123,6 +142,26 @@ int ozimmu_dgemm(int m, int n, int k, const double *A, int lda, const double *B,
 size_t ozimmu_workspace_bytes2(int m, int n, int k, int sA, int sB, int all_products);
 int ozimmu_dgemm2(int m, int n, int k, const double *A, int lda, const double *B, int ldb,
                   double *C, int ldc, int sA, int sB, int all_products,
+                  void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * The two accuracy variants on top of ozimmu_dgemm2 (same workspace size):
+ *   splitting        OZIMMU_SPLIT_TRUNCATE or OZIMMU_SPLIT_NEAREST (see ozimmu_split2); with the latter the
+ *                    exponents ozimmu_get_exponents returns are those of the doubled scales.
+ *   level_diagonals  Q >= 1: the binary64 accumulation takes the diagonals l + h = 2, 3, ... Q at a time
+ *                    (the "levels" of the subsection "Accumulation in floating-point arithmetic" of
+ *                    Sect. 4): the Q terms 2^{-7d} D_d of a level are added to each other without rounding
+ *                    error, then the level is added to S with one rounding; the last level may be
+ *                    shorter.  Q = 1 is the order of ozimmu_dgemm.  Q must not exceed
+ *                    ozimmu_max_level_diagonals(k, sA, sB), the largest Q for which every level is
+ *                    certain to be a binary64 number: min(sA, sB) k 127^2 (2^{7Q} - 1) / 127 < 2^53
+ *                    (4 at k = 8192, 3 at k = 2^17 for 4 to 32 slices; 3 is the value the paper derives for a
+ *                    full 31-bit accumulator); a larger Q returns OZIMMU_BAD_ARG.
+ * ozimmu_dgemm3(..., all_products, OZIMMU_SPLIT_TRUNCATE, 1, ...) equals ozimmu_dgemm2 bit for bit.
+ */
+int ozimmu_max_level_diagonals(int k, int sA, int sB);
+int ozimmu_dgemm3(int m, int n, int k, const double *A, int lda, const double *B, int ldb,
+                  double *C, int ldc, int sA, int sB, int all_products, int splitting, int level_diagonals,
                   void *workspace, size_t workspace_bytes, void *stream);
 
 /*

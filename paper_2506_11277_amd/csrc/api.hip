@@ -36,7 +36,7 @@ inline void prof_mark(int phase, hipStream_t st)
 
 // scales of both operands into the workspace (optionally with the minima for kappa)
 int scales_into_workspace(const Workspace &w, char *ws, int m, int n, int k, const double *A, int lda,
-                          const double *B, int ldb, bool with_min, hipStream_t st)
+                          const double *B, int ldb, bool with_min, int bias, hipStream_t st)
 {
     auto *hdr = (unsigned long long *)(ws + w.off_header);
     auto *flags = (unsigned int *)(ws + w.off_header);
@@ -45,8 +45,8 @@ int scales_into_workspace(const Workspace &w, char *ws, int m, int n, int k, con
     OZ_TRY(launch_clear_header(hdr, st));
     OZ_TRY(launch_reduce('A', m, k, A, lda, maxA, with_min ? minA : nullptr, flags, st));
     OZ_TRY(launch_reduce('B', k, n, B, ldb, maxB, with_min ? minB : nullptr, flags, st));
-    OZ_TRY(launch_finalize(maxA, minA, (int32_t *)(ws + w.off_expA), m, w.mp, with_min ? hdr + 1 : nullptr, st));
-    OZ_TRY(launch_finalize(maxB, minB, (int32_t *)(ws + w.off_expB), n, w.np, with_min ? hdr + 2 : nullptr, st));
+    OZ_TRY(launch_finalize(maxA, minA, (int32_t *)(ws + w.off_expA), m, w.mp, with_min ? hdr + 1 : nullptr, bias, st));
+    OZ_TRY(launch_finalize(maxB, minB, (int32_t *)(ws + w.off_expB), n, w.np, with_min ? hdr + 2 : nullptr, bias, st));
     return OZIMMU_OK;
 }
 
@@ -102,7 +102,7 @@ static int kappas(int m, int n, int k, const double *A, int lda, const double *B
     if (!workspace || workspace_bytes < w.total || ((uintptr_t)workspace & 255)) return OZIMMU_BAD_ARG;
     hipStream_t st = (hipStream_t)stream;
     char *ws = (char *)workspace;
-    int rc = scales_into_workspace(w, ws, m, n, k, A, lda, B, ldb, true, st);
+    int rc = scales_into_workspace(w, ws, m, n, k, A, lda, B, ldb, true, 0, st);
     if (rc) return rc;
     unsigned long long host[3];
     OZ_TRY(hipMemcpyAsync(host, ws + w.off_header, sizeof(host), hipMemcpyDeviceToHost, st));
@@ -168,10 +168,11 @@ int ozimmu_estimate_slices2(int m, int n, int k, const double *A, int lda, const
     return found ? OZIMMU_OK : OZIMMU_UNREACHABLE;
 }
 
-int ozimmu_split(char side, int rows, int cols, const double *X, int ldx, int s, int8_t *planes, int32_t *exps,
-                 int layout, void *scratch, void *stream)
+int ozimmu_split2(char side, int rows, int cols, const double *X, int ldx, int s, int splitting, int8_t *planes,
+                  int32_t *exps, int layout, void *scratch, void *stream)
 {
     if ((side != 'A' && side != 'B') || bad_matrix(rows, cols, X, ldx) || s < 1 || s > OZIMMU_MAX_SLICES ||
+        (splitting != OZIMMU_SPLIT_TRUNCATE && splitting != OZIMMU_SPLIT_NEAREST) ||
         (layout != OZIMMU_LAYOUT_PLAIN && layout != OZIMMU_LAYOUT_MFMA) || !scratch || ((uintptr_t)scratch & 255))
         return OZIMMU_BAD_ARG;
     const int nblk = side == 'A' ? rows : cols;
@@ -182,41 +183,72 @@ int ozimmu_split(char side, int rows, int cols, const double *X, int ldx, int s,
     auto *maxbits = hdr + 32;
     OZ_TRY(launch_clear_header(hdr, st));
     OZ_TRY(launch_reduce(side, rows, cols, X, ldx, maxbits, nullptr, (unsigned int *)hdr, st));
-    OZ_TRY(launch_finalize(maxbits, nullptr, exps, nblk, nblk, nullptr, st));
-    OZ_TRY(launch_split(side, rows, cols, X, ldx, s, exps, planes, layout, st));
+    const bool nearest = splitting == OZIMMU_SPLIT_NEAREST;
+    OZ_TRY(launch_finalize(maxbits, nullptr, exps, nblk, nblk, nullptr, nearest ? 1 : 0, st));
+    OZ_TRY(launch_split(side, rows, cols, X, ldx, s, exps, planes, layout, nearest, st));
     return OZIMMU_OK;
 }
 
+int ozimmu_split(char side, int rows, int cols, const double *X, int ldx, int s, int8_t *planes, int32_t *exps,
+                 int layout, void *scratch, void *stream)
+{
+    return ozimmu_split2(side, rows, cols, X, ldx, s, OZIMMU_SPLIT_TRUNCATE, planes, exps, layout, scratch, stream);
+}
+
+int ozimmu_max_level_diagonals(int k, int sA, int sB)
+{
+    if (k < 0 || sA < 1 || sA > OZIMMU_MAX_SLICES || sB < 1 || sB > OZIMMU_MAX_SLICES) return 0;
+    // A diagonal holds at most min(sA, sB) products of k terms of magnitude at most 127^2.  In units of the
+    // last diagonal of a level of Q diagonals, the level and each of its partial sums are integers below
+    //     min(sA, sB) k 127^2 (1 + 2^7 + ... + 2^{7(Q-1)});
+    // they are binary64 numbers while that stays below 2^53.
+    const long long per_diag = (long long)(sA < sB ? sA : sB) * (k > 0 ? k : 1) * 127 * 127;   // < 2^51
+    int Q = 0;
+    long long geo = 0;                         // 1 + 2^7 + ... + 2^{7(Q-1)}
+    while (Q < 8) {
+        const long long next = geo * 128 + 1;
+        if ((__int128)per_diag * next >= ((__int128)1 << 53)) break;
+        geo = next;
+        ++Q;
+    }
+    return Q;
+}
+
 static int dgemm_impl(int m, int n, int k, const double *A, int lda, const double *B, int ldb, double *C, int ldc,
-                      int sA, int sB, bool all_products, void *workspace, size_t workspace_bytes, void *stream)
+                      int sA, int sB, bool all_products, int splitting, int Q, void *workspace,
+                      size_t workspace_bytes, void *stream)
 {
     if (bad_matrix(m, k, A, lda) || bad_matrix(k, n, B, ldb) || bad_matrix(m, n, C, ldc) || sA < 1 ||
-        sA > OZIMMU_MAX_SLICES || sB < 1 || sB > OZIMMU_MAX_SLICES)
+        sA > OZIMMU_MAX_SLICES || sB < 1 || sB > OZIMMU_MAX_SLICES ||
+        (splitting != OZIMMU_SPLIT_TRUNCATE && splitting != OZIMMU_SPLIT_NEAREST) || Q < 1 ||
+        Q > ozimmu_max_level_diagonals(k, sA, sB))
         return OZIMMU_BAD_ARG;
+    const bool nearest = splitting == OZIMMU_SPLIT_NEAREST;
     const Workspace w = carve(m, n, k, sA, sB, all_products);
     if (!workspace || workspace_bytes < w.total || ((uintptr_t)workspace & 255)) return OZIMMU_BAD_ARG;
     // exact conversion of a diagonal sum to binary64 needs s * k * 127^2 < 2^53: true for every int k
     hipStream_t st = (hipStream_t)stream;
     char *ws = (char *)workspace;
     prof_mark(0, st);
-    int rc = scales_into_workspace(w, ws, m, n, k, A, lda, B, ldb, false, st);
+    int rc = scales_into_workspace(w, ws, m, n, k, A, lda, B, ldb, false, nearest ? 1 : 0, st);
     if (rc) return rc;
     if (m == 0 || n == 0) return OZIMMU_OK;
     prof_mark(1, st);
     auto *eA = (int32_t *)(ws + w.off_expA), *eB = (int32_t *)(ws + w.off_expB);
     auto *pA = (int8_t *)(ws + w.off_planesA), *pB = (int8_t *)(ws + w.off_planesB);
-    OZ_TRY(launch_split('A', m, k, A, lda, sA, eA, pA, OZIMMU_LAYOUT_MFMA, st));
-    OZ_TRY(launch_split('B', k, n, B, ldb, sB, eB, pB, OZIMMU_LAYOUT_MFMA, st));
+    OZ_TRY(launch_split('A', m, k, A, lda, sA, eA, pA, OZIMMU_LAYOUT_MFMA, nearest, st));
+    OZ_TRY(launch_split('B', k, n, B, ldb, sB, eB, pB, OZIMMU_LAYOUT_MFMA, nearest, st));
     prof_mark(2, st);
     const bool fused = sA == sB && !all_products && sA <= fused_max_slices();
     if (fused && fused_single_block(sA, k)) {
-        OZ_TRY(launch_gemm_fused(m, n, w.kp, sA, pA, pB, eA, eB, C, ldc, nullptr, nullptr, st));
+        OZ_TRY(launch_gemm_fused(m, n, w.kp, sA, pA, pB, eA, eB, C, ldc, nullptr, nullptr, Q, st));
     } else if (fused) {
-        OZ_TRY(launch_gemm_fused(m, n, w.kp, sA, pA, pB, eA, eB, C, ldc, nullptr, (long long *)(ws + w.off_totals), st));
+        OZ_TRY(launch_gemm_fused(m, n, w.kp, sA, pA, pB, eA, eB, C, ldc, nullptr, (long long *)(ws + w.off_totals), Q,
+                                 st));
     } else {
         const int dmax = all_products ? sA + sB : (sA > sB ? sA : sB) + 1;
         long long *totals = banded_totals_bytes(sA, sB, k) ? (long long *)(ws + w.off_totals) : nullptr;
-        OZ_TRY(launch_gemm_banded(m, n, w.kp, sA, sB, dmax, pA, pB, eA, eB, C, ldc, totals, st));
+        OZ_TRY(launch_gemm_banded(m, n, w.kp, sA, sB, dmax, pA, pB, eA, eB, C, ldc, totals, Q, st));
     }
     prof_mark(3, st);
     if (g_prof.on && g_prof.calls < g_prof.capacity) ++g_prof.calls;
@@ -226,14 +258,23 @@ static int dgemm_impl(int m, int n, int k, const double *A, int lda, const doubl
 int ozimmu_dgemm(int m, int n, int k, const double *A, int lda, const double *B, int ldb, double *C, int ldc, int s,
                  void *workspace, size_t workspace_bytes, void *stream)
 {
-    return dgemm_impl(m, n, k, A, lda, B, ldb, C, ldc, s, s, false, workspace, workspace_bytes, stream);
+    return dgemm_impl(m, n, k, A, lda, B, ldb, C, ldc, s, s, false, OZIMMU_SPLIT_TRUNCATE, 1, workspace,
+                      workspace_bytes, stream);
 }
 
 int ozimmu_dgemm2(int m, int n, int k, const double *A, int lda, const double *B, int ldb, double *C, int ldc,
                   int sA, int sB, int all_products, void *workspace, size_t workspace_bytes, void *stream)
 {
-    return dgemm_impl(m, n, k, A, lda, B, ldb, C, ldc, sA, sB, all_products != 0, workspace, workspace_bytes,
-                      stream);
+    return dgemm_impl(m, n, k, A, lda, B, ldb, C, ldc, sA, sB, all_products != 0, OZIMMU_SPLIT_TRUNCATE, 1, workspace,
+                      workspace_bytes, stream);
+}
+
+int ozimmu_dgemm3(int m, int n, int k, const double *A, int lda, const double *B, int ldb, double *C, int ldc,
+                  int sA, int sB, int all_products, int splitting, int level_diagonals, void *workspace,
+                  size_t workspace_bytes, void *stream)
+{
+    return dgemm_impl(m, n, k, A, lda, B, ldb, C, ldc, sA, sB, all_products != 0, splitting, level_diagonals,
+                      workspace, workspace_bytes, stream);
 }
 
 int ozimmu_profile_start(int max_calls)
@@ -299,7 +340,7 @@ int ozimmu_debug_diagonals(int m, int n, int k, int s, const void *workspace, in
     const Workspace w = carve(m, n, k, s, s);
     const char *ws = (const char *)workspace;
     OZ_TRY(launch_gemm_fused(m, n, w.kp, s, (const int8_t *)(ws + w.off_planesA), (const int8_t *)(ws + w.off_planesB),
-                             nullptr, nullptr, nullptr, m, D, nullptr, (hipStream_t)stream));
+                             nullptr, nullptr, nullptr, m, D, nullptr, 1, (hipStream_t)stream));
     return OZIMMU_OK;
 }
 

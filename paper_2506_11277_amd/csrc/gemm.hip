@@ -54,7 +54,7 @@ __global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t
                                                                     int KB, int tiles_m, int tiles_n,
                                                                     int32_t *__restrict__ dump,
                                                                     long long *__restrict__ totals,
-                                                                    int stages_per_block)
+                                                                    int stages_per_block, int Q)
 {
     constexpr bool DUMP = MODE == kDump;
     constexpr int NW = WVM * WVN;                      // wavefronts
@@ -187,12 +187,11 @@ __global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t
 #pragma unroll
                     for (int a = 0; a < S; ++a) dump[(size_t)a * m * n + mi + (size_t)nj * m] = acc[a][i][j][r];
                 } else {
-                    double sum = 0.0;
+                    LevelSum sum;
 #pragma unroll
-                    for (int a = 0; a < S; ++a) {
-                        sum = sum + (double)acc[a][i][j][r] * __builtin_ldexp(1.0, -kSliceBits * (a + 2));
-                    }
-                    C[mi + (size_t)nj * ldc] = ldexp(sum, ea + eB[nj]);
+                    for (int a = 0; a < S; ++a)
+                        sum.add((double)acc[a][i][j][r] * __builtin_ldexp(1.0, -kSliceBits * (a + 2)), Q, a == S - 1);
+                    C[mi + (size_t)nj * ldc] = ldexp(sum.S, ea + eB[nj]);
                 }
             }
         }
@@ -206,7 +205,7 @@ __global__ __launch_bounds__(64 * WVM * WVN) void finish_blocked_kernel(const lo
                                                                         const int32_t *__restrict__ eA,
                                                                         const int32_t *__restrict__ eB,
                                                                         double *__restrict__ C, int ldc, int m, int n,
-                                                                        int tiles_n)
+                                                                        int tiles_n, int Q)
 {
     constexpr int NW = WVM * WVN, FA = WVM * WMF, FB = WVN * WNF;
     const int tm = blockIdx.x / tiles_n, tn = blockIdx.x % tiles_n;
@@ -222,13 +221,14 @@ __global__ __launch_bounds__(64 * WVM * WVN) void finish_blocked_kernel(const lo
             for (int r = 0; r < 16; ++r) {
                 const int nj = n0 + j * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
                 if (nj >= n) continue;
-                double sum = 0.0;
+                LevelSum sum;
 #pragma unroll
                 for (int a = 0; a < S; ++a) {
                     const long long v = tot[((((size_t)a * WMF + i) * WNF + j) * 16 + r) * 64];
-                    sum = sum + (double)v * __builtin_ldexp(1.0, -kSliceBits * (a + 2));   // exact conversion: |v| < 2^53
+                    // (exact conversion: |v| < 2^53)
+                    sum.add((double)v * __builtin_ldexp(1.0, -kSliceBits * (a + 2)), Q, a == S - 1);
                 }
-                C[mi + (size_t)nj * ldc] = ldexp(sum, ea + eB[nj]);
+                C[mi + (size_t)nj * ldc] = ldexp(sum.S, ea + eB[nj]);
             }
     }
 }
@@ -381,7 +381,8 @@ void fused_tile(int &tm, int &tn)
 
 template <int S, int MODE>
 hipError_t launch_fused_s(int m, int n, int kp, const int8_t *pA, const int8_t *pB, const int32_t *eA,
-                          const int32_t *eB, double *C, int ldc, int32_t *dump, long long *totals, hipStream_t st)
+                          const int32_t *eB, double *C, int ldc, int32_t *dump, long long *totals, int Q,
+                          hipStream_t st)
 {
     using Cfg = FusedCfg<S>;
     constexpr int TM = 32 * Cfg::WVM * Cfg::WMF, TN = 32 * Cfg::WVN * Cfg::WNF;
@@ -399,7 +400,7 @@ hipError_t launch_fused_s(int m, int n, int kp, const int8_t *pA, const int8_t *
     const int tiles_m = (m + TM - 1) / TM, tiles_n = (n + TN - 1) / TN;
     if (MODE != kBlocked) {
         kern<<<tiles_m * tiles_n, 64 * Cfg::WVM * Cfg::WVN, Cfg::NSTAGE * STAGE, st>>>(
-            pA, pB, eA, eB, C, ldc, m, n, kp / kFrag, tiles_m, tiles_n, dump, nullptr, 0);
+            pA, pB, eA, eB, C, ldc, m, n, kp / kFrag, tiles_m, tiles_n, dump, nullptr, 0, Q);
         return hipGetLastError();
     }
     // longest k-block whose s products per diagonal cannot overflow int32, in whole stages
@@ -411,19 +412,20 @@ hipError_t launch_fused_s(int m, int n, int kp, const int8_t *pA, const int8_t *
     dim3 grid(tiles_m * tiles_n, nblocks);
     kern<<<grid, 64 * Cfg::WVM * Cfg::WVN, Cfg::NSTAGE * STAGE, st>>>(pA, pB, eA, eB, C, ldc, m, n, kp / kFrag,
                                                                        tiles_m, tiles_n, nullptr, totals,
-                                                                       stages_per_block);
+                                                                       stages_per_block, Q);
     finish_blocked_kernel<S, Cfg::WVM, Cfg::WVN, Cfg::WMF, Cfg::WNF>
-        <<<tiles_m * tiles_n, 64 * Cfg::WVM * Cfg::WVN, 0, st>>>(totals, eA, eB, C, ldc, m, n, tiles_n);
+        <<<tiles_m * tiles_n, 64 * Cfg::WVM * Cfg::WVN, 0, st>>>(totals, eA, eB, C, ldc, m, n, tiles_n, Q);
     return hipGetLastError();
 }
 
 template <int MODE>
 hipError_t dispatch_fused(int s, int m, int n, int kp, const int8_t *pA, const int8_t *pB, const int32_t *eA,
-                          const int32_t *eB, double *C, int ldc, int32_t *dump, long long *totals, hipStream_t st)
+                          const int32_t *eB, double *C, int ldc, int32_t *dump, long long *totals, int Q,
+                          hipStream_t st)
 {
     switch (s) {
 #define OZ_CASE(S_) \
-    case S_: return launch_fused_s<S_, MODE>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, st);
+    case S_: return launch_fused_s<S_, MODE>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, Q, st);
         OZ_CASE(1) OZ_CASE(2) OZ_CASE(3) OZ_CASE(4) OZ_CASE(5) OZ_CASE(6) OZ_CASE(7) OZ_CASE(8) OZ_CASE(9) OZ_CASE(10) OZ_CASE(11) OZ_CASE(12)
 #undef OZ_CASE
     }
@@ -455,15 +457,16 @@ size_t fused_totals_bytes(int s, int m, int n, int k)
 }
 
 hipError_t launch_gemm_fused(int m, int n, int kp, int s, const int8_t *pA, const int8_t *pB, const int32_t *eA,
-                             const int32_t *eB, double *C, int ldc, int32_t *dump, long long *totals, hipStream_t st)
+                             const int32_t *eB, double *C, int ldc, int32_t *dump, long long *totals, int Q,
+                             hipStream_t st)
 {
     if (m <= 0 || n <= 0) return hipSuccess;
-    // the 16x16x64 kernel where it is the faster one (except k-blocked s = 9, where it would need more than
-    // 256 registers; both kernels use 128 x 64 tiles there, so the totals buffer has the same size)
-    if (fused16_preferred(s) && !(totals && s == 9)) return launch_gemm_fused16(m, n, kp, s, pA, pB, eA, eB, C, ldc, dump, totals, st);
-    if (dump) return dispatch_fused<kDump>(s, m, n, kp, pA, pB, eA, eB, C, ldc, dump, nullptr, st);
-    if (totals) return dispatch_fused<kBlocked>(s, m, n, kp, pA, pB, eA, eB, C, ldc, nullptr, totals, st);
-    return dispatch_fused<kPlain>(s, m, n, kp, pA, pB, eA, eB, C, ldc, nullptr, nullptr, st);
+    // the 16x16x64 kernel where it is the faster one
+    if (fused16_preferred(s))
+        return launch_gemm_fused16(m, n, kp, s, pA, pB, eA, eB, C, ldc, dump, totals, Q, st);
+    if (dump) return dispatch_fused<kDump>(s, m, n, kp, pA, pB, eA, eB, C, ldc, dump, nullptr, Q, st);
+    if (totals) return dispatch_fused<kBlocked>(s, m, n, kp, pA, pB, eA, eB, C, ldc, nullptr, totals, Q, st);
+    return dispatch_fused<kPlain>(s, m, n, kp, pA, pB, eA, eB, C, ldc, nullptr, nullptr, Q, st);
 }
 
 hipError_t launch_gemm_generic(int m, int n, int kp, int s, const int8_t *pA, const int8_t *pB, const int32_t *eA,

@@ -49,7 +49,7 @@ template <bool TOTALS, bool CHUNK_A, int KB32>
 __global__ __launch_bounds__(64 * kWVM * kWVN) void gemm_banded_kernel(
     const int8_t *__restrict__ pA, const int8_t *__restrict__ pB, const int32_t *__restrict__ eA,
     const int32_t *__restrict__ eB, double *__restrict__ C, int ldc, int m, int n, int sA, int sB, int dmax, int KB,
-    int tiles_m, int tiles_n, long long *__restrict__ totals, int stages_per_block)
+    int tiles_m, int tiles_n, long long *__restrict__ totals, int stages_per_block, int Q)
 {
     using Geo = BandGeom<CHUNK_A, KB32>;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -81,8 +81,11 @@ __global__ __launch_bounds__(64 * kWVM * kWVN) void gemm_banded_kernel(
 #pragma unroll
         for (int r = 0; r < 16; ++r) S[r] = 0.0;
 
-        for (int d0 = 2; d0 <= dmax; d0 += kG) {
-            const int dlast = d0 + kG - 1 < dmax ? d0 + kG - 1 : dmax;
+        // diagonals per group: the largest multiple of the level size Q within G, so that every group
+        // starts a new level (Q = 1: all G)
+        const int gd = kG - kG % Q;
+        for (int d0 = 2; d0 <= dmax; d0 += gd) {
+            const int dlast = d0 + gd - 1 < dmax ? d0 + gd - 1 : dmax;
             v16i acc[kG];
 #pragma unroll
             for (int a = 0; a < kG; ++a)
@@ -189,19 +192,22 @@ __global__ __launch_bounds__(64 * kWVM * kWVN) void gemm_banded_kernel(
                     }
                 }
             }
-            // the group's diagonals are complete: S <- S + 2^{-7d} D_d, ascending d
+            // the group's diagonals are complete: S <- S + 2^{-7d} D_d, ascending d, in levels of Q diagonals
             long long *te = tot;
             if (TOTALS) asm volatile("" : "+v"(te));
 #pragma unroll
-            for (int a = 0; a < kG; ++a) {
-                if (d0 + a > dlast) break;
+            for (int r = 0; r < 16; ++r) {
+                LevelSum sum;
+                sum.S = S[r];
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
+                for (int a = 0; a < kG; ++a) {
+                    if (d0 + a > dlast) break;
                     long long v = acc[a][r];
                     if (TOTALS && have_totals) v += te[((size_t)a * 16 + r) * 64];
-                    S[r] = S[r] + ldexp((double)v, -kSliceBits * (d0 + a));
+                    sum.add(ldexp((double)v, -kSliceBits * (d0 + a)), Q, d0 + a == dlast);
                 }
-                asm volatile("" ::: "memory");
+                S[r] = sum.S;
+                asm volatile("" ::: "memory");   // one output element at a time
             }
         }
 
@@ -220,7 +226,8 @@ __global__ __launch_bounds__(64 * kWVM * kWVN) void gemm_banded_kernel(
 
 template <bool TOTALS, bool CHUNK_A, int KB32>
 hipError_t launch_band(int m, int n, int kp, int sA, int sB, int dmax, const int8_t *pA, const int8_t *pB,
-                       const int32_t *eA, const int32_t *eB, double *C, int ldc, long long *totals, hipStream_t st)
+                       const int32_t *eA, const int32_t *eB, double *C, int ldc, long long *totals, int Q,
+                       hipStream_t st)
 {
     using Geo = BandGeom<CHUNK_A, KB32>;
     static_assert(2 * Geo::STAGE <= kLdsBytes, "LDS double buffer too large");
@@ -238,7 +245,7 @@ hipError_t launch_band(int m, int n, int kp, int sA, int sB, int dmax, const int
     // a k-block adds at most LA products of (32 * KB32 * stages) terms to an accumulator
     const int stages_per_block = TOTALS ? (int)(kMaxInt32K / kLA / kFrag) / KB32 : nst;
     kern<<<grid, 64 * kWVM * kWVN, 2 * Geo::STAGE, st>>>(pA, pB, eA, eB, C, ldc, m, n, sA, sB, dmax, KB, tiles_m,
-                                                         tiles_n, totals, stages_per_block);
+                                                         tiles_n, totals, stages_per_block, Q);
     return hipGetLastError();
 }
 
@@ -256,17 +263,18 @@ size_t banded_totals_bytes(int sA, int sB, int k)
 }
 
 hipError_t launch_gemm_banded(int m, int n, int kp, int sA, int sB, int dmax, const int8_t *pA, const int8_t *pB,
-                              const int32_t *eA, const int32_t *eB, double *C, int ldc, long long *totals,
+                              const int32_t *eA, const int32_t *eB, double *C, int ldc, long long *totals, int Q,
                               hipStream_t st)
 {
+    if (Q < 1 || Q > kG) return hipErrorInvalidValue;
     if (m <= 0 || n <= 0) return hipSuccess;
     const bool chunk_a = sA <= sB;
     if (totals) {
-        return chunk_a ? launch_band<true, true, 1>(m, n, kp, sA, sB, dmax, pA, pB, eA, eB, C, ldc, totals, st)
-                       : launch_band<true, false, 1>(m, n, kp, sA, sB, dmax, pA, pB, eA, eB, C, ldc, totals, st);
+        return chunk_a ? launch_band<true, true, 1>(m, n, kp, sA, sB, dmax, pA, pB, eA, eB, C, ldc, totals, Q, st)
+                       : launch_band<true, false, 1>(m, n, kp, sA, sB, dmax, pA, pB, eA, eB, C, ldc, totals, Q, st);
     }
-    return chunk_a ? launch_band<false, true, 1>(m, n, kp, sA, sB, dmax, pA, pB, eA, eB, C, ldc, nullptr, st)
-                   : launch_band<false, false, 1>(m, n, kp, sA, sB, dmax, pA, pB, eA, eB, C, ldc, nullptr, st);
+    return chunk_a ? launch_band<false, true, 1>(m, n, kp, sA, sB, dmax, pA, pB, eA, eB, C, ldc, nullptr, Q, st)
+                   : launch_band<false, false, 1>(m, n, kp, sA, sB, dmax, pA, pB, eA, eB, C, ldc, nullptr, Q, st);
 }
 
 }  // namespace oz

@@ -45,4 +45,23 @@ __device__ __forceinline__ void wait_vmcnt()
 
 constexpr int kLdsBytes = 160 * 1024;
 
+// Binary64 accumulation of the scaled diagonal sums 2^{-7d} D_d, d ascending, in levels of Q
+// consecutive diagonals (subsection "Accumulation in floating-point arithmetic" of Sect. 4): the
+// terms of a level are added to each other first, then the level to S.  The host admits only Q for
+// which every partial sum of a level is a binary64 number, so the additions inside a level do not
+// round and S is rounded once per level.  Q = 1: S <- S + (0 + term), the plain diagonal order.
+struct LevelSum {
+    double S = 0.0, L = 0.0;
+    int cnt = 0;
+    __device__ __forceinline__ void add(double term, int Q, bool last)
+    {
+        L = L + term;
+        if (++cnt == Q || last) {
+            S = S + L;
+            L = 0.0;
+            cnt = 0;
+        }
+    }
+};
+
 }  // namespace oz

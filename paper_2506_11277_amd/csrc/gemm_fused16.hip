@@ -1,4 +1,4 @@
-// Fused slice-product kernel built on v_mfma_i32_16x16x64_i8 (s <= 9).
+// Fused slice-product kernel built on v_mfma_i32_16x16x64_i8 (written for s <= 9, used for s = 4 and 8).
 //
 // Same computation as gemm_fused_kernel in gemm.hip (all s(s+1)/2 products of Algorithm 1, Sect. 3,
 // per-diagonal int32 sums, binary64 accumulation by ascending diagonal), same plane layout, same
@@ -41,7 +41,7 @@ template <int S, int MODE>
 __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused16_kernel(
     const int8_t *__restrict__ pA, const int8_t *__restrict__ pB, const int32_t *__restrict__ eA,
     const int32_t *__restrict__ eB, double *__restrict__ C, int ldc, int m, int n, int KB, int tiles_m, int tiles_n,
-    int32_t *__restrict__ dump, long long *__restrict__ totals, int stages_per_block)
+    int32_t *__restrict__ dump, long long *__restrict__ totals, int stages_per_block, int Q)
 {
     using G = Cfg16<S>;
     constexpr int WVM = G::WVM, WVN = G::WVN, WMF = G::WMF, WNF = G::WNF, FA = G::FA, FB = G::FB, L0 = G::L0;
@@ -49,8 +49,9 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
     constexpr bool SPLIT = L0 < S;
     constexpr int NS2 = SPLIT ? S - L0 : 1;                         // slices in the single-buffered region
     constexpr bool DUMP = MODE == kDump;
-    // 1 KiB copy units of a stage.  P1: A rows c < FA, k-halves kk < 2, slices l < L0, then B rows, kk, all
-    // slices.  P2: A rows, kk, slices l >= L0.  Inside a (row, kk) group slices are contiguous in HBM and LDS.
+    // 1 KiB copy units of a stage.  P1: A rows c < FA, slices l < L0, k-halves kk < 2, then B rows, all slices,
+    // kk.  P2: A rows, slices l >= L0, kk.  The two k-halves of a (row, slice) are neighbours in LDS, so one
+    // per-lane offset serves all three regions.
     constexpr int U1A = FA * 2 * L0, U1 = U1A + FB * 2 * S, U2 = FA * 2 * (S - L0);
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds;
@@ -73,11 +74,11 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
             if (u >= U1) break;
             const int8_t *src;
             if (u < U1A) {
-                const int c = u / (2 * L0), kk = (u / L0) % 2, l = u % L0;
+                const int c = u / (2 * L0), l = (u / 2) % L0, kk = u % 2;
                 src = rowA + (size_t)c * row_bytes + ((size_t)(2 * st + kk) * S + l) * kFragBytes;
             } else {
                 const int v = u - U1A;
-                const int c = v / (2 * S), kk = (v / S) % 2, h = v % S;
+                const int c = v / (2 * S), h = (v / 2) % S, kk = v % 2;
                 src = rowB + (size_t)c * row_bytes + ((size_t)(2 * st + kk) * S + h) * kFragBytes;
             }
             lds_dma16(src, lane * 16, lds0 + buf * G::P1 + u * kFragBytes);
@@ -88,7 +89,7 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
         for (int i = 0; i < (U2 + NW - 1) / NW; ++i) {
             const int u = wave + i * NW;
             if (u >= U2) break;
-            const int c = u / (2 * NS2), kk = (u / NS2) % 2, l = L0 + u % NS2;
+            const int c = u / (2 * NS2), l = L0 + (u / 2) % NS2, kk = u % 2;
             const int8_t *src = rowA + (size_t)c * row_bytes + ((size_t)(2 * st + kk) * S + l) * kFragBytes;
             lds_dma16(src, lane * 16, lds0 + Z + u * kFragBytes);
         }
@@ -122,9 +123,8 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
     __syncthreads();
 
     // this lane's part of a 16x64 operand: row lane%16 of the half, k-group g = lane/16
-    const int lofs = ((lane >> 4) >> 1) * S * kFragBytes + ((lane & 15) + 32 * ((lane >> 4) & 1)) * 16;
-    const int lofs2 = ((lane >> 4) >> 1) * NS2 * kFragBytes + ((lane & 15) + 32 * ((lane >> 4) & 1)) * 16;
-    const int lofs1 = ((lane >> 4) >> 1) * L0 * kFragBytes + ((lane & 15) + 32 * ((lane >> 4) & 1)) * 16;
+    // -> fragment kk = g / 2 of the pair, lane slot (row + 32 * (g % 2)) in it
+    const int lofs = ((lane >> 4) >> 1) * kFragBytes + ((lane & 15) + 32 * ((lane >> 4) & 1)) * 16;
 
     int buf = 0;
     for (int st = st0; st < nst; ++st) {
@@ -139,7 +139,7 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
             for (int j = 0; j < WNF; ++j)
 #pragma unroll
                 for (int j2 = 0; j2 < 2; ++j2)
-                    bf[h][j][j2] = *(const v4i *)(cur + (U1A + (wn * WNF + j) * 2 * S + h) * kFragBytes + lofs + j2 * 256);
+                    bf[h][j][j2] = *(const v4i *)(cur + (U1A + ((wn * WNF + j) * S + h) * 2) * kFragBytes + lofs + j2 * 256);
 
         // slices of A from the last to the first, so that the single-buffered ones (l >= L0) go first
 #pragma unroll
@@ -149,9 +149,9 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
             for (int i = 0; i < WMF; ++i)
 #pragma unroll
                 for (int i2 = 0; i2 < 2; ++i2)
-                    af[i][i2] = l >= L0 ? *(const v4i *)(lds + Z + ((wm * WMF + i) * 2 * NS2 + (l - L0)) * kFragBytes +
-                                                          lofs2 + i2 * 256)
-                                        : *(const v4i *)(cur + ((wm * WMF + i) * 2 * L0 + l) * kFragBytes + lofs1 + i2 * 256);
+                    af[i][i2] = l >= L0 ? *(const v4i *)(lds + Z + (((wm * WMF + i) * NS2 + (l - L0)) * 2) * kFragBytes +
+                                                          lofs + i2 * 256)
+                                        : *(const v4i *)(cur + (((wm * WMF + i) * L0 + l) * 2) * kFragBytes + lofs + i2 * 256);
 #pragma unroll
             for (int h = 0; h < S - l; ++h)
 #pragma unroll
@@ -214,11 +214,12 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
                             for (int a = 0; a < S; ++a)
                                 dump[(size_t)a * m * n + mi + (size_t)nj * m] = acc[a][i][j][i2 * 2 + j2][r];
                         } else {
-                            double sum = 0.0;
+                            LevelSum sum;
 #pragma unroll
                             for (int a = 0; a < S; ++a)
-                                sum = sum + (double)acc[a][i][j][i2 * 2 + j2][r] * __builtin_ldexp(1.0, -kSliceBits * (a + 2));
-                            C[mi + (size_t)nj * ldc] = ldexp(sum, ea + eB[nj]);
+                                sum.add((double)acc[a][i][j][i2 * 2 + j2][r] * __builtin_ldexp(1.0, -kSliceBits * (a + 2)),
+                                        Q, a == S - 1);
+                            C[mi + (size_t)nj * ldc] = ldexp(sum.S, ea + eB[nj]);
                         }
                     }
         }
@@ -229,7 +230,7 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
 template <int S>
 __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void finish_blocked16_kernel(
     const long long *__restrict__ totals, const int32_t *__restrict__ eA, const int32_t *__restrict__ eB,
-    double *__restrict__ C, int ldc, int m, int n, int tiles_n)
+    double *__restrict__ C, int ldc, int m, int n, int tiles_n, int Q)
 {
     using G = Cfg16<S>;
     constexpr int WVM = G::WVM, WVN = G::WVN, WMF = G::WMF, WNF = G::WNF, FA = G::FA, FB = G::FB, NW = WVM * WVN;
@@ -248,13 +249,13 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void finish_blo
                     for (int r = 0; r < 4; ++r) {
                         const int nj = n0 + j * 32 + j2 * 16 + 4 * (lane >> 4) + r;
                         if (nj >= n) continue;
-                        double sum = 0.0;
+                        LevelSum sum;
 #pragma unroll
                         for (int a = 0; a < S; ++a) {
                             const long long v = tot[((((size_t)a * WMF + i) * WNF + j) * 16 + (i2 * 2 + j2) * 4 + r) * 64];
-                            sum = sum + (double)v * __builtin_ldexp(1.0, -kSliceBits * (a + 2));   // exact conversion
+                            sum.add((double)v * __builtin_ldexp(1.0, -kSliceBits * (a + 2)), Q, a == S - 1);   // exact conversion
                         }
-                        C[mi + (size_t)nj * ldc] = ldexp(sum, ea + eB[nj]);
+                        C[mi + (size_t)nj * ldc] = ldexp(sum.S, ea + eB[nj]);
                     }
         }
 }
@@ -266,7 +267,7 @@ __global__ void zero16_i64_kernel(long long *p, size_t n)
 
 template <int S, int MODE>
 hipError_t launch16_s(int m, int n, int kp, const int8_t *pA, const int8_t *pB, const int32_t *eA, const int32_t *eB,
-                      double *C, int ldc, int32_t *dump, long long *totals, hipStream_t st)
+                      double *C, int ldc, int32_t *dump, long long *totals, int Q, hipStream_t st)
 {
     using G = Cfg16<S>;
     constexpr int TM = 32 * G::FA, TN = 32 * G::FB, THREADS = 64 * G::WVM * G::WVN;
@@ -282,7 +283,7 @@ hipError_t launch16_s(int m, int n, int kp, const int8_t *pA, const int8_t *pB, 
     const int KB = kp / kFrag;
     if (MODE != kBlocked) {
         kern<<<tiles_m * tiles_n, THREADS, G::LDS, st>>>(pA, pB, eA, eB, C, ldc, m, n, KB, tiles_m, tiles_n, dump,
-                                                         nullptr, 0);
+                                                         nullptr, 0, Q);
         return hipGetLastError();
     }
     // longest k-block (in 64-k stages) whose s products per diagonal cannot overflow int32
@@ -292,19 +293,19 @@ hipError_t launch16_s(int m, int n, int kp, const int8_t *pA, const int8_t *pB, 
     zero16_i64_kernel<<<2048, 256, 0, st>>>(totals, (size_t)tiles_m * tiles_n * S * TM * TN);
     dim3 grid(tiles_m * tiles_n, nblocks);
     kern<<<grid, THREADS, G::LDS, st>>>(pA, pB, eA, eB, C, ldc, m, n, KB, tiles_m, tiles_n, nullptr, totals,
-                                        stages_per_block);
-    finish_blocked16_kernel<S><<<tiles_m * tiles_n, THREADS, 0, st>>>(totals, eA, eB, C, ldc, m, n, tiles_n);
+                                        stages_per_block, Q);
+    finish_blocked16_kernel<S><<<tiles_m * tiles_n, THREADS, 0, st>>>(totals, eA, eB, C, ldc, m, n, tiles_n, Q);
     return hipGetLastError();
 }
 
 template <int MODE>
 hipError_t dispatch16(int s, int m, int n, int kp, const int8_t *pA, const int8_t *pB, const int32_t *eA,
-                      const int32_t *eB, double *C, int ldc, int32_t *dump, long long *totals, hipStream_t st)
+                      const int32_t *eB, double *C, int ldc, int32_t *dump, long long *totals, int Q, hipStream_t st)
 {
     switch (s) {
 #define OZ_CASE(S_) \
-    case S_: return launch16_s<S_, MODE>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, st);
-        OZ_CASE(4) OZ_CASE(8) OZ_CASE(9)
+    case S_: return launch16_s<S_, MODE>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, Q, st);
+        OZ_CASE(4) OZ_CASE(8)
 #undef OZ_CASE
     }
     return hipErrorInvalidValue;
@@ -312,10 +313,11 @@ hipError_t dispatch16(int s, int m, int n, int kp, const int8_t *pA, const int8_
 
 }  // namespace
 
-// Slice counts for which this kernel is the faster one at 8192^3 (s = 4: +10 %, 8: +12 %, 9: +4 %; equal
-// within noise at 7; the 32x32x32 kernel wins at 2, 3, 5, 6 where this one cannot use its wider tile or
-// issues too many LDS reads per matrix instruction).  Only these are instantiated.
-bool fused16_preferred(int s) { return s == 4 || s == 8 || s == 9; }
+// Slice counts for which this kernel is the faster one at 8192^3 (s = 4: +10 %, s = 8: +12 %).  At s = 9 it
+// gains 4 % but sits at the 256-register limit (any change tips it into spilling), at 7 the two are equal
+// within noise, and the 32x32x32 kernel wins at 2, 3, 5, 6, where this one cannot use its wider tile or
+// issues too many LDS reads per matrix instruction.  Only the preferred ones are instantiated.
+bool fused16_preferred(int s) { return s == 4 || s == 8; }
 
 void fused16_tile(int s, int &tm, int &tn)
 {
@@ -324,13 +326,13 @@ void fused16_tile(int s, int &tm, int &tn)
 }
 
 hipError_t launch_gemm_fused16(int m, int n, int kp, int s, const int8_t *pA, const int8_t *pB, const int32_t *eA,
-                               const int32_t *eB, double *C, int ldc, int32_t *dump, long long *totals,
+                               const int32_t *eB, double *C, int ldc, int32_t *dump, long long *totals, int Q,
                                hipStream_t st)
 {
     if (m <= 0 || n <= 0) return hipSuccess;
-    if (dump) return dispatch16<kDump>(s, m, n, kp, pA, pB, eA, eB, C, ldc, dump, nullptr, st);
-    if (totals) return dispatch16<kBlocked>(s, m, n, kp, pA, pB, eA, eB, C, ldc, nullptr, totals, st);
-    return dispatch16<kPlain>(s, m, n, kp, pA, pB, eA, eB, C, ldc, nullptr, nullptr, st);
+    if (dump) return dispatch16<kDump>(s, m, n, kp, pA, pB, eA, eB, C, ldc, dump, nullptr, Q, st);
+    if (totals) return dispatch16<kBlocked>(s, m, n, kp, pA, pB, eA, eB, C, ldc, nullptr, totals, Q, st);
+    return dispatch16<kPlain>(s, m, n, kp, pA, pB, eA, eB, C, ldc, nullptr, nullptr, Q, st);
 }
 
 }  // namespace oz

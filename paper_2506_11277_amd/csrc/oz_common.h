@@ -65,16 +65,18 @@ inline Workspace carve(int m, int n, int k, int sA, int sB, bool all_products = 
 hipError_t launch_reduce(char side, int rows, int cols, const double *X, int ldx,
                          unsigned long long *maxbits, unsigned long long *minbits,
                          unsigned int *flags, hipStream_t st);
-// exps[b] from maxbits[b]; entries b in [nblk, nblk_padded) get 0.  If kappa_bits is non-null
-// (needs minbits) also folds 2*max/min into *kappa_bits with an integer atomic max.
+// exps[b] from maxbits[b], plus `bias` (1 for round-to-nearest slices, whose scale is twice as large);
+// entries b in [nblk, nblk_padded) get 0.  If kappa_bits is non-null (needs minbits) also folds
+// 2*max/min into *kappa_bits with an integer atomic max.
 hipError_t launch_finalize(const unsigned long long *maxbits, const unsigned long long *minbits,
                            int32_t *exps, int nblk, int nblk_padded, unsigned long long *kappa_bits,
-                           hipStream_t st);
+                           int bias, hipStream_t st);
 hipError_t launch_clear_header(void *header, hipStream_t st);
 
 // ---- launchers implemented in split.hip --------------------------------------------------
+// nearest: slices by round-to-nearest (exps must then hold the biased exponents), else by truncation
 hipError_t launch_split(char side, int rows, int cols, const double *X, int ldx, int s,
-                        const int32_t *exps, int8_t *planes, int layout, hipStream_t st);
+                        const int32_t *exps, int8_t *planes, int layout, bool nearest, hipStream_t st);
 
 // ---- launchers implemented in gemm.hip ---------------------------------------------------
 // largest s the fused (all diagonals in registers) kernel handles
@@ -83,20 +85,21 @@ int fused_max_slices();
 bool fused_single_block(int s, int k);
 // bytes of int64 per-tile totals the fused kernel needs when it has to cut k into blocks (else 0)
 size_t fused_totals_bytes(int s, int m, int n, int k);
-// dump != null: write int32 diagonal sums (single block only); totals != null: k-blocked mode
+// dump != null: write int32 diagonal sums (single block only); totals != null: k-blocked mode.
+// Q (all GEMM launchers): diagonals per exactly summed level of the binary64 accumulation, 1 <= Q <= 8.
 hipError_t launch_gemm_fused(int m, int n, int kp, int s, const int8_t *pA, const int8_t *pB,
                              const int32_t *eA, const int32_t *eB, double *C, int ldc,
-                             int32_t *dump, long long *totals, hipStream_t st);
+                             int32_t *dump, long long *totals, int Q, hipStream_t st);
 // the same fused computation on v_mfma_i32_16x16x64_i8, for the slice counts where it is faster (gemm_fused16.hip)
 bool fused16_preferred(int s);
 void fused16_tile(int s, int &tm, int &tn);
 hipError_t launch_gemm_fused16(int m, int n, int kp, int s, const int8_t *pA, const int8_t *pB,
                                const int32_t *eA, const int32_t *eB, double *C, int ldc,
-                               int32_t *dump, long long *totals, hipStream_t st);
+                               int32_t *dump, long long *totals, int Q, hipStream_t st);
 // general product band (any sA, sB, any k); totals: scratch of banded_totals_bytes() or null when that is 0
 hipError_t launch_gemm_banded(int m, int n, int kp, int sA, int sB, int dmax, const int8_t *pA, const int8_t *pB,
                               const int32_t *eA, const int32_t *eB, double *C, int ldc, long long *totals,
-                              hipStream_t st);
+                              int Q, hipStream_t st);
 hipError_t launch_gemm_generic(int m, int n, int kp, int s, const int8_t *pA, const int8_t *pB,
                                const int32_t *eA, const int32_t *eB, double *C, int ldc,
                                int pair_l, int pair_h, int kb_begin, int kb_end, int32_t *dump,

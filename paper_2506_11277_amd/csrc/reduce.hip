@@ -141,13 +141,13 @@ __device__ __forceinline__ int exponent_above(unsigned long long bits)
 
 __global__ void finalize_kernel(const unsigned long long *__restrict__ maxbits,
                                 const unsigned long long *__restrict__ minbits, int32_t *__restrict__ exps,
-                                int nblk, int nblk_padded, unsigned long long *kappa_bits)
+                                int nblk, int nblk_padded, unsigned long long *kappa_bits, int bias)
 {
     int b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b >= nblk_padded) return;
     if (b >= nblk) { exps[b] = 0; return; }
     unsigned long long mx = maxbits[b];
-    exps[b] = exponent_above(mx);
+    exps[b] = exponent_above(mx) + bias;
     if (kappa_bits && mx) {
         double ratio = __longlong_as_double((long long)mx) / __longlong_as_double((long long)minbits[b]);
         atomicMax(kappa_bits, (unsigned long long)__double_as_longlong(ratio));
@@ -183,10 +183,11 @@ hipError_t launch_reduce(char side, int rows, int cols, const double *X, int ldx
 }
 
 hipError_t launch_finalize(const unsigned long long *maxbits, const unsigned long long *minbits, int32_t *exps,
-                           int nblk, int nblk_padded, unsigned long long *kappa_bits, hipStream_t st)
+                           int nblk, int nblk_padded, unsigned long long *kappa_bits, int bias, hipStream_t st)
 {
     if (nblk_padded <= 0) return hipSuccess;
-    finalize_kernel<<<(nblk_padded + 255) / 256, 256, 0, st>>>(maxbits, minbits, exps, nblk, nblk_padded, kappa_bits);
+    finalize_kernel<<<(nblk_padded + 255) / 256, 256, 0, st>>>(maxbits, minbits, exps, nblk, nblk_padded, kappa_bits,
+                                                               bias);
     return hipGetLastError();
 }
 

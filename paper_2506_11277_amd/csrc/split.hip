@@ -5,6 +5,13 @@
 // |x| = I * 2^q with I the integer significand, so  floor(|x| 2^{lt - e}) mod 2^t  is a
 // shift of I by (e - q - lt) places and a mask: integer work only, exact.
 //
+// Round-to-nearest variant (second tweak of the "Enhanced algorithm" paragraph of Sect. 3): the block
+// scale is 2^{e+1}, and with R_l = the integer nearest to |x| 2^{7l - e - 1} (ties to even) slice l is
+// sign(x) (R_l - 128 R_{l-1}), a value in [-64, 64].  R_l = floor(.) + c_l with the round-up decision
+//     c_l = guard & (sticky | lsb)
+// read off the bits of I below the cut, so  slice l = field_l + c_l - 128 c_{l-1}:  still shifts and
+// masks only.
+//
 // The MFMA layout written here is the one the GEMM kernel reads (see include/ozimmu.h):
 // fragments of 32 (R) x 32 (K) bytes, 16 contiguous K-bytes per wavefront lane.
 #include "oz_common.h"
@@ -44,10 +51,38 @@ __device__ __forceinline__ unsigned int slice_byte(const Elem &el, int l)
     return (unsigned int)d & 0xffu;
 }
 
+// round-up decision at the cut below slice l (l >= 0): 1 when |x| 2^{7l - e} is rounded away from zero
+__device__ __forceinline__ int round_up_at(const Elem &el, int l)
+{
+    const int sh = el.base - kSliceBits * l;      // bits of I below the cut
+    if (sh <= 0 || sh > 64) return 0;             // nothing below the cut / I < 2^53 lies below half a unit
+    const unsigned long long guard = (el.I >> (sh - 1)) & 1ULL;
+    const unsigned long long sticky = sh >= 2 ? (el.I & ((1ULL << (sh - 1)) - 1ULL)) : 0ULL;
+    const unsigned long long lsb = sh < 64 ? (el.I >> sh) & 1ULL : 0ULL;
+    return (int)(guard & ((sticky != 0ULL) | lsb));
+}
+
+// slice l by round-to-nearest (el.base taken from the biased exponent e + 1)
+template <bool NEAREST>
+__device__ __forceinline__ unsigned int slice_of(const Elem &el, int l)
+{
+    if (!NEAREST) return slice_byte(el, l);
+    const int sh = el.base - kSliceBits * l;
+    unsigned long long v;
+    if (sh >= 64) v = 0;
+    else if (sh >= 0) v = el.I >> sh;
+    else if (sh <= -kSliceBits) v = 0;
+    else v = el.I << (-sh);
+    int d = (int)(v & 127ULL) + round_up_at(el, l) - 128 * round_up_at(el, l - 1);
+    d = el.neg ? -d : d;
+    return (unsigned int)d & 0xffu;
+}
+
 // ---- side 'A': X is R x K column-major (R contiguous).  lane <-> row, each lane walks 16
 //      consecutive k, so the 16 K-bytes of a lane come out of registers: the transposition to
 //      K-contiguous fragments costs nothing, reads are 512 B per wavefront load, writes are
 //      512 B contiguous per half wavefront.
+template <bool NEAREST>
 __global__ __launch_bounds__(256) void split_rows_kernel(const unsigned long long *__restrict__ X, int ldx, int R,
                                                          int K, int s, const int32_t *__restrict__ exps,
                                                          int8_t *__restrict__ planes, int KB)
@@ -69,8 +104,8 @@ __global__ __launch_bounds__(256) void split_rows_kernel(const unsigned long lon
         unsigned int wd[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q)
-            wd[q] = slice_byte(el[4 * q], l) | (slice_byte(el[4 * q + 1], l) << 8) |
-                    (slice_byte(el[4 * q + 2], l) << 16) | (slice_byte(el[4 * q + 3], l) << 24);
+            wd[q] = slice_of<NEAREST>(el[4 * q], l) | (slice_of<NEAREST>(el[4 * q + 1], l) << 8) |
+                    (slice_of<NEAREST>(el[4 * q + 2], l) << 16) | (slice_of<NEAREST>(el[4 * q + 3], l) << 24);
         dst[(size_t)(l - 1) * (kFragBytes / 16)] = make_uint4(wd[0], wd[1], wd[2], wd[3]);
     }
 }
@@ -82,6 +117,7 @@ constexpr int kColTileK = 128;
 constexpr int kColLdsRow = kColTileK + 16;   // bytes per (slice, column) row in LDS
 constexpr int kColGroup = 8;                 // slices per LDS pass
 
+template <bool NEAREST>
 __global__ __launch_bounds__(256) void split_cols_kernel(const unsigned long long *__restrict__ X, int ldx, int R,
                                                          int K, int s, const int32_t *__restrict__ exps,
                                                          int8_t *__restrict__ planes, int KB)
@@ -113,8 +149,9 @@ __global__ __launch_bounds__(256) void split_cols_kernel(const unsigned long lon
 #pragma unroll
             for (int p = 0; p < 4; ++p) {
                 const int jj = p * 8 + (t >> 5);
-                unsigned int wd = slice_byte(el[p][0], l0 + dl) | (slice_byte(el[p][1], l0 + dl) << 8) |
-                                  (slice_byte(el[p][2], l0 + dl) << 16) | (slice_byte(el[p][3], l0 + dl) << 24);
+                unsigned int wd = slice_of<NEAREST>(el[p][0], l0 + dl) | (slice_of<NEAREST>(el[p][1], l0 + dl) << 8) |
+                                  (slice_of<NEAREST>(el[p][2], l0 + dl) << 16) |
+                                  (slice_of<NEAREST>(el[p][3], l0 + dl) << 24);
                 *(unsigned int *)(lds + ((size_t)dl * 32 + jj) * kColLdsRow + kq) = wd;
             }
         }
@@ -128,6 +165,7 @@ __global__ __launch_bounds__(256) void split_cols_kernel(const unsigned long lon
 }
 
 // ---- plain layout: plane l is a matrix shaped like X (utility / test path) ----
+template <bool NEAREST>
 __global__ __launch_bounds__(256) void split_plain_kernel(const unsigned long long *__restrict__ X, int ldx, int rows,
                                                           int cols, int s, const int32_t *__restrict__ exps,
                                                           int by_row, int8_t *__restrict__ planes)
@@ -139,20 +177,20 @@ __global__ __launch_bounds__(256) void split_plain_kernel(const unsigned long lo
         const int e = by_row ? exps[r] : exps[c];
         const Elem el = decompose(X[r + (size_t)c * ldx], e);
         for (int l = 1; l <= s; ++l)
-            planes[(size_t)(l - 1) * plane + r + (size_t)c * rows] = (int8_t)slice_byte(el, l);
+            planes[(size_t)(l - 1) * plane + r + (size_t)c * rows] = (int8_t)slice_of<NEAREST>(el, l);
     }
 }
 
 }  // namespace
 
 hipError_t launch_split(char side, int rows, int cols, const double *X, int ldx, int s, const int32_t *exps,
-                        int8_t *planes, int layout, hipStream_t st)
+                        int8_t *planes, int layout, bool nearest, hipStream_t st)
 {
     if (layout == OZIMMU_LAYOUT_PLAIN) {
         if (rows <= 0 || cols <= 0) return hipSuccess;
         dim3 grid((rows + 255) / 256, cols < 65535 ? cols : 65535);
-        split_plain_kernel<<<grid, 256, 0, st>>>((const unsigned long long *)X, ldx, rows, cols, s, exps,
-                                                 side == 'A' ? 1 : 0, planes);
+        auto kern = nearest ? split_plain_kernel<true> : split_plain_kernel<false>;
+        kern<<<grid, 256, 0, st>>>((const unsigned long long *)X, ldx, rows, cols, s, exps, side == 'A' ? 1 : 0, planes);
         return hipGetLastError();
     }
     const int R = side == 'A' ? rows : cols, K = side == 'A' ? cols : rows;
@@ -161,11 +199,13 @@ hipError_t launch_split(char side, int rows, int cols, const double *X, int ldx,
     if (side == 'A') {
         dim3 grid(Rp / 64, Kp / 64);
         if (grid.y > 65535) return hipErrorInvalidValue;
-        split_rows_kernel<<<grid, 256, 0, st>>>((const unsigned long long *)X, ldx, R, K, s, exps, planes, KB);
+        auto kern = nearest ? split_rows_kernel<true> : split_rows_kernel<false>;
+        kern<<<grid, 256, 0, st>>>((const unsigned long long *)X, ldx, R, K, s, exps, planes, KB);
     } else {
         dim3 grid(Rp / 32, Kp / kColTileK);
         if (grid.y > 65535) return hipErrorInvalidValue;
-        split_cols_kernel<<<grid, 256, 0, st>>>((const unsigned long long *)X, ldx, R, K, s, exps, planes, KB);
+        auto kern = nearest ? split_cols_kernel<true> : split_cols_kernel<false>;
+        kern<<<grid, 256, 0, st>>>((const unsigned long long *)X, ldx, R, K, s, exps, planes, KB);
     }
     return hipGetLastError();
 }

@@ -15,6 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libozimmu.so")
 OK, BAD_ARG, NONFINITE, HIP_ERROR, UNREACHABLE = 0, 1, 2, 3, 4
 MAX_SLICES = 32
 LAYOUT_PLAIN, LAYOUT_MFMA = 0, 1
+SPLIT_TRUNCATE, SPLIT_NEAREST = 0, 1
 
 _c = ctypes
 _SIGNATURES = {
@@ -33,6 +34,12 @@ _SIGNATURES = {
     "ozimmu_dgemm2": (_c.c_int, [_c.c_int, _c.c_int, _c.c_int, _c.c_void_p, _c.c_int, _c.c_void_p, _c.c_int,
                                  _c.c_void_p, _c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_void_p, _c.c_size_t,
                                  _c.c_void_p]),
+    "ozimmu_split2": (_c.c_int, [_c.c_char, _c.c_int, _c.c_int, _c.c_void_p, _c.c_int, _c.c_int, _c.c_int, _c.c_void_p,
+                                 _c.c_void_p, _c.c_int, _c.c_void_p, _c.c_void_p]),
+    "ozimmu_max_level_diagonals": (_c.c_int, [_c.c_int] * 3),
+    "ozimmu_dgemm3": (_c.c_int, [_c.c_int, _c.c_int, _c.c_int, _c.c_void_p, _c.c_int, _c.c_void_p, _c.c_int,
+                                 _c.c_void_p, _c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_int,
+                                 _c.c_void_p, _c.c_size_t, _c.c_void_p]),
     "ozimmu_estimate_slices2": (_c.c_int, [_c.c_int, _c.c_int, _c.c_int, _c.c_void_p, _c.c_int, _c.c_void_p, _c.c_int,
                                            _c.c_double, _c.POINTER(_c.c_int), _c.POINTER(_c.c_int),
                                            _c.POINTER(_c.c_double), _c.c_void_p, _c.c_size_t, _c.c_void_p]),
@@ -176,6 +183,39 @@ def dgemm2(A, B, sA, sB, all_products=False, C=None, workspace=None, check_finit
     return C
 
 
+def max_level_diagonals(k, sA, sB):
+    return lib().ozimmu_max_level_diagonals(k, sA, sB)
+
+
+def dgemm3(A, B, sA, sB, all_products=False, splitting=SPLIT_TRUNCATE, level_diagonals=1, C=None, workspace=None,
+           check_finite=False):
+    """dgemm2 with the slicing (truncation / round-to-nearest) and the level size of the accumulation chosen."""
+    lda = _colmajor_ld(A, "A")
+    ldb = _colmajor_ld(B, "B")
+    m, k = A.shape
+    k2, n = B.shape
+    if k != k2:
+        raise ValueError("inner dimensions differ")
+    if C is None:
+        C = colmajor_empty(m, n, device=A.device)
+    ldc = _colmajor_ld(C, "C")
+    if tuple(C.shape) != (m, n):
+        raise ValueError("C has the wrong shape")
+    if workspace is None:
+        nbytes = lib().ozimmu_workspace_bytes2(m, n, k, sA, sB, int(all_products))
+        if nbytes == 0:
+            raise OzimmuError(BAD_ARG, "workspace_bytes2")
+        workspace = torch.empty(nbytes, dtype=torch.uint8, device=A.device)
+    rc = lib().ozimmu_dgemm3(m, n, k, A.data_ptr(), lda, B.data_ptr(), ldb, C.data_ptr(), ldc, sA, sB,
+                             int(all_products), int(splitting), int(level_diagonals), workspace.data_ptr(),
+                             workspace.numel(), _stream())
+    if rc != OK:
+        raise OzimmuError(rc, "dgemm3")
+    if check_finite:
+        check(workspace)
+    return C
+
+
 def estimate_slices2(A, B, tol, workspace=None):
     """Returns (sA, sB, status, kappa_A, kappa_B): the cheapest pair of slice counts meeting tol."""
     lda = _colmajor_ld(A, "A")
@@ -215,7 +255,7 @@ def estimate_slices(A, B, tol, workspace=None):
     return s.value, rc, kap[0], kap[1]
 
 
-def split(side, X, s, layout=LAYOUT_PLAIN):
+def split(side, X, s, layout=LAYOUT_PLAIN, splitting=SPLIT_TRUNCATE):
     """Returns (planes, exps): int8 byte buffer in the requested layout and int32 scale exponents."""
     ldx = _colmajor_ld(X, "X")
     rows, cols = X.shape
@@ -225,8 +265,12 @@ def split(side, X, s, layout=LAYOUT_PLAIN):
     planes = torch.empty(max(nbytes, 1), dtype=torch.int8, device=X.device)
     exps = torch.empty(max(nblk, 1), dtype=torch.int32, device=X.device)
     scratch = torch.empty(lib().ozimmu_split_scratch_bytes(side_c, rows, cols), dtype=torch.uint8, device=X.device)
-    rc = lib().ozimmu_split(side_c, rows, cols, X.data_ptr(), ldx, s, planes.data_ptr(), exps.data_ptr(), layout,
-                            scratch.data_ptr(), _stream())
+    if splitting == SPLIT_TRUNCATE:
+        rc = lib().ozimmu_split(side_c, rows, cols, X.data_ptr(), ldx, s, planes.data_ptr(), exps.data_ptr(), layout,
+                                scratch.data_ptr(), _stream())
+    else:
+        rc = lib().ozimmu_split2(side_c, rows, cols, X.data_ptr(), ldx, s, int(splitting), planes.data_ptr(),
+                                 exps.data_ptr(), layout, scratch.data_ptr(), _stream())
     if rc != OK:
         raise OzimmuError(rc, "split")
     rc = lib().ozimmu_check(scratch.data_ptr(), _stream())

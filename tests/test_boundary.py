@@ -78,3 +78,25 @@ def test_size_queries_and_argument_validation_without_gpu(handle):
                                          None) == 1
     assert handle.ozimmu_split(b"X", 4, 4, fake, 4, 2, fake, fake, 0, ws, None) == 1
     assert handle.ozimmu_split(b"A", 4, 4, fake, 4, 2, fake, fake, 7, ws, None) == 1
+
+
+def test_level_size_limit_and_variant_argument_validation_without_gpu(handle):
+    # largest Q with  min(sA, sB) k 127^2 (1 + 2^7 + ... + 2^{7(Q-1)}) < 2^53, recomputed with Python integers
+    for k in (0, 1, 64, 128, 1000, 8192, 2 ** 17, 2 ** 18, 2 ** 31 - 1):
+        for sA, sB in ((1, 1), (7, 7), (4, 12), (12, 4), (32, 32), (32, 1)):
+            per = min(sA, sB) * max(k, 1) * 127 * 127
+            want = max(q for q in range(0, 9) if q == 0 or per * sum(128 ** i for i in range(q)) < 2 ** 53)
+            assert handle.ozimmu_max_level_diagonals(k, sA, sB) == want, (k, sA, sB)
+            assert want >= 1
+    assert handle.ozimmu_max_level_diagonals(8192, 7, 7) == 4
+    assert handle.ozimmu_max_level_diagonals(2 ** 17, 7, 7) == 3      # the paper's value for a full int32 accumulator
+    assert handle.ozimmu_max_level_diagonals(-1, 7, 7) == 0
+    assert handle.ozimmu_max_level_diagonals(8, 0, 7) == 0 and handle.ozimmu_max_level_diagonals(8, 7, 33) == 0
+    ws = ctypes.c_void_p(256)
+    fake = ctypes.c_void_p(4096)
+    args = (4, 4, 4, fake, 4, fake, 4, fake, 4)
+    assert handle.ozimmu_dgemm3(*args, 2, 2, 0, 0, 0, ws, 1 << 30, None) == 1      # Q < 1
+    assert handle.ozimmu_dgemm3(*args, 2, 2, 0, 0, 7, ws, 1 << 30, None) == 1      # Q beyond the exact range
+    assert handle.ozimmu_dgemm3(*args, 2, 2, 0, 2, 1, ws, 1 << 30, None) == 1      # unknown splitting
+    assert handle.ozimmu_dgemm3(*args, 2, 2, 0, 1, 1, ws, 16, None) == 1           # workspace too small
+    assert handle.ozimmu_split2(b"A", 4, 4, fake, 4, 2, 5, fake, fake, 0, ws, None) == 1

@@ -373,3 +373,105 @@ def test_badly_scaled_workload_matches_oracle(kappa_d):
     assert est == oracle.estimate_slices(A, B, 2.0 ** -53, s_max=ozimmu.MAX_SLICES)
     for s in sorted({8, 12, 16, 18, est[0]}):
         assert_c_matches(host(ozimmu.dgemm(dA, dB, s)), oracle.dgemm(A, B, s), f"kappa_D={kappa_d:g} s={s}")
+
+
+# ----------------------------------------------------------------------------- round-to-nearest slices, levels
+
+def tie_heavy(rows, cols, seed):
+    """Entries with few significant bits at many binary positions: rounding ties and carries at every cut."""
+    rng = np.random.default_rng(seed)
+    mant = rng.integers(1, 512, size=(rows, cols)).astype(np.float64)
+    X = np.ldexp(mant, rng.integers(-40, 3, size=(rows, cols))) * rng.choice([-1.0, 1.0], size=(rows, cols))
+    X[rng.random((rows, cols)) < 0.05] = 0.0
+    return X
+
+
+@pytest.mark.parametrize("kind", ["uniform", "lognormal", "special", "ties"])
+@pytest.mark.parametrize("m,n,k", SHAPES)
+@pytest.mark.parametrize("s", [1, 3, 8, 32])
+def test_split_nearest_bit_exact_in_both_layouts(kind, m, n, k, s):
+    A, B = (tie_heavy(m, k, 5), tie_heavy(k, n, 6)) if kind == "ties" else inputs(kind, m, n, k, 13)
+    for side, X in (("A", A), ("B", B)):
+        want_planes, want_e = oracle.split_nearest(side, X, s)
+        rows, cols = X.shape
+        planes, e = ozimmu.split(side, dev(X), s, ozimmu.LAYOUT_PLAIN, splitting=ozimmu.SPLIT_NEAREST)
+        assert np.array_equal(host(e), want_e + 1), (side, "exponents of the doubled scales")
+        assert np.array_equal(host(planes).reshape(s, cols, rows).transpose(0, 2, 1), want_planes), (side, "plain")
+        planes, e = ozimmu.split(side, dev(X), s, ozimmu.LAYOUT_MFMA, splitting=ozimmu.SPLIT_NEAREST)
+        R, K = (rows, cols) if side == "A" else (cols, rows)
+        got, full = untile(host(planes), R, K, s)
+        assert np.array_equal(host(e), want_e + 1)
+        assert np.array_equal(got, want_planes if side == "A" else want_planes.transpose(0, 2, 1)), (side, "mfma")
+        assert not full[:, R:, :].any() and not full[:, :, K:].any(), "padding must be zero"
+
+
+VARIANT_CASES = [
+    # sA, sB, all_products, nearest, Q        kernel that runs
+    (7, 7, False, True, 1),                 # fused 32x32x32
+    (8, 8, False, True, 1),                 # fused 16x16x64
+    (7, 7, False, False, 3),
+    (4, 4, False, False, 2),                # fused 16x16x64, wide tile
+    (8, 8, False, False, 3),
+    (12, 12, False, True, 4),
+    (13, 13, False, False, 3),              # band kernel: groups of 6 diagonals
+    (16, 16, False, True, 2),
+    (5, 11, False, False, 3),
+    (11, 5, False, True, 4),
+    (6, 4, True, False, 3),
+    (9, 9, True, True, 2),
+    (18, 18, False, False, 4),
+    (32, 32, False, False, 3),
+]
+
+
+@pytest.mark.parametrize("sA,sB,allp,nearest,Q", VARIANT_CASES)
+@pytest.mark.parametrize("m,n,k,kind", [(100, 90, 70, "lognormal"), (257, 130, 300, "special"), (150, 200, 1000, "ties")])
+def test_dgemm3_variants_bit_exact(sA, sB, allp, nearest, Q, m, n, k, kind):
+    A, B = (tie_heavy(m, k, 7), tie_heavy(k, n, 8)) if kind == "ties" else inputs(kind, m, n, k, 14)
+    assert Q <= ozimmu.max_level_diagonals(k, sA, sB)
+    print(f"dgemm3 sA={sA} sB={sB} all={allp} nearest={nearest} Q={Q} {m}x{n}x{k} {kind}", flush=True)
+    ws = torch.empty(ozimmu.lib().ozimmu_workspace_bytes2(m, n, k, sA, sB, int(allp)), dtype=torch.uint8, device="cuda")
+    C = ozimmu.dgemm3(dev(A), dev(B), sA, sB, allp, ozimmu.SPLIT_NEAREST if nearest else ozimmu.SPLIT_TRUNCATE, Q,
+                      workspace=ws)
+    want, eA, eB = oracle.dgemm3(A, B, sA, sB, full=allp, nearest=nearest, Q=Q, return_exponents=True)
+    assert_c_matches(host(C), want, "dgemm3")
+    if sA == sB and not allp:
+        gA, gB = ozimmu.get_exponents(m, n, k, sA, ws)
+        assert np.array_equal(host(gA), eA) and np.array_equal(host(gB), eB)
+
+
+@pytest.mark.parametrize("s,Q,nearest", [(4, 3, True), (7, 3, False), (8, 2, True), (12, 3, False), (14, 3, True)])
+def test_dgemm3_variants_in_k_blocked_mode(s, Q, nearest):
+    m, n = 130, 70
+    k = min(2 * (133144 // s) + 200, 70000)
+    assert Q <= ozimmu.max_level_diagonals(k, s, s)
+    print(f"dgemm3 k-blocked s={s} Q={Q} nearest={nearest} k={k}", flush=True)
+    A, B = workloads.lognormal(m, n, k, 2.0, 90 + s)
+    C = ozimmu.dgemm3(dev(A), dev(B), s, s, False, ozimmu.SPLIT_NEAREST if nearest else ozimmu.SPLIT_TRUNCATE, Q)
+    assert_c_matches(host(C), oracle.dgemm3(A, B, s, s, nearest=nearest, Q=Q), "dgemm3 k-blocked")
+
+
+def test_dgemm3_defaults_equal_dgemm2_and_bad_level_size_is_refused():
+    A, B = workloads.lognormal(90, 80, 200, 1.0, 15)
+    dA, dB = dev(A), dev(B)
+    for sA, sB, allp in [(7, 7, False), (5, 9, False), (4, 6, True)]:
+        assert torch.equal(ozimmu.dgemm3(dA, dB, sA, sB, allp), ozimmu.dgemm2(dA, dB, sA, sB, allp))
+    qmax = ozimmu.max_level_diagonals(200, 7, 7)
+    ozimmu.dgemm3(dA, dB, 7, 7, level_diagonals=qmax)
+    for bad in (0, qmax + 1, 9):
+        with pytest.raises(ozimmu.OzimmuError) as ei:
+            ozimmu.dgemm3(dA, dB, 7, 7, level_diagonals=bad)
+        assert ei.value.code == ozimmu.BAD_ARG
+    with pytest.raises(ozimmu.OzimmuError):
+        ozimmu.dgemm3(dA, dB, 7, 7, splitting=2)
+
+
+def test_largest_admitted_level_is_exact_on_the_worst_case_input():
+    # all slices at +-127 and every product of a diagonal of the same sign: the level sums reach the bound
+    # ozimmu_max_level_diagonals is derived from; the oracle refuses a level that is not a binary64 number
+    x = 1.0 - 2.0 ** -53
+    for k, s in [(64, 7), (1000, 7), (8192, 5)]:
+        A, B = np.full((40, k), x), np.full((k, 33), x)
+        Q = ozimmu.max_level_diagonals(k, s, s)
+        want = oracle.dgemm3(A, B, s, s, Q=Q)
+        assert_c_matches(host(ozimmu.dgemm3(dev(A), dev(B), s, s, level_diagonals=Q)), want, f"worst case k={k}")
