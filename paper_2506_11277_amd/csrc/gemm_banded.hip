@@ -7,7 +7,8 @@
 // The pair set is a band of the (l, h) grid, too large to hold in registers at once for big
 // slice counts, so it is cut two ways:
 //   * diagonals are taken G at a time (G int32 accumulator sets per wavefront); binary64 S is
-//     carried in registers from one group to the next, so the additions keep their order;
+//     carried in registers from one group to the next, so the additions keep their order (a level of
+//     the level-wise accumulation that straddles two groups parks its partial sum in C meanwhile);
 //   * inside a group, the slices of A are taken LA at a time.  A chunk of LA slices of A meets,
 //     on the G diagonals of the group, a window of LB = G + LA - 1 consecutive slices of B, and
 //     the product A-slice `la` x window slot `hb` belongs to diagonal slot a = hb + la - (LA-1):
@@ -81,11 +82,11 @@ __global__ __launch_bounds__(64 * kWVM * kWVN) void gemm_banded_kernel(
 #pragma unroll
         for (int r = 0; r < 16; ++r) S[r] = 0.0;
 
-        // diagonals per group: the largest multiple of the level size Q within G, so that every group
-        // starts a new level (Q = 1: all G)
-        const int gd = kG - kG % Q;
-        for (int d0 = 2; d0 <= dmax; d0 += gd) {
-            const int dlast = d0 + gd - 1 < dmax ? d0 + gd - 1 : dmax;
+        const int mi = (tm * kWVM + wm) * 32 + (lane & 31);
+        const int n0 = (tn * kWVN + wn) * 32;
+
+        for (int d0 = 2; d0 <= dmax; d0 += kG) {
+            const int dlast = d0 + kG - 1 < dmax ? d0 + kG - 1 : dmax;
             v16i acc[kG];
 #pragma unroll
             for (int a = 0; a < kG; ++a)
@@ -192,27 +193,38 @@ __global__ __launch_bounds__(64 * kWVM * kWVN) void gemm_banded_kernel(
                     }
                 }
             }
-            // the group's diagonals are complete: S <- S + 2^{-7d} D_d, ascending d, in levels of Q diagonals
+            // the group's diagonals are complete: S <- S + 2^{-7d} D_d, ascending d, in levels of Q diagonals.
+            // A level may straddle two groups (Q does not divide G): its partial sum is then parked in this
+            // lane's own element of C until the next group continues it.  (Read back with a device-scope
+            // load so that it cannot be served from a stale L1 line.)
+            const int open_in = (d0 - 2) % Q;                           // diagonals of the open level summed so far
+            const bool open_out = dlast != dmax && (dlast - 1) % Q != 0;
             long long *te = tot;
             if (TOTALS) asm volatile("" : "+v"(te));
+            int nlane = n0 + 4 * (lane >> 5);   // (laundered like `te`: the 16 element positions are formed here)
+            asm volatile("" : "+v"(nlane));
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
+                const int nj = nlane + 8 * (r >> 2) + (r & 3);
+                const bool inside = mi < m && nj < n;
+                double *park = inside ? C + mi + (size_t)nj * ldc : nullptr;
                 LevelSum sum;
                 sum.S = S[r];
+                sum.cnt = open_in;
+                if (open_in && inside) sum.L = __hip_atomic_load(park, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
                 for (int a = 0; a < kG; ++a) {
                     if (d0 + a > dlast) break;
                     long long v = acc[a][r];
                     if (TOTALS && have_totals) v += te[((size_t)a * 16 + r) * 64];
-                    sum.add(ldexp((double)v, -kSliceBits * (d0 + a)), Q, d0 + a == dlast);
+                    sum.add(ldexp((double)v, -kSliceBits * (d0 + a)), Q, d0 + a == dmax);
                 }
                 S[r] = sum.S;
+                if (open_out && inside) __hip_atomic_store(park, sum.L, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 asm volatile("" ::: "memory");   // one output element at a time
             }
         }
 
-        const int mi = (tm * kWVM + wm) * 32 + (lane & 31);
-        const int n0 = (tn * kWVN + wn) * 32;
         if (mi < m) {
             const int ea = eA[mi];
 #pragma unroll

@@ -10,7 +10,7 @@
 // sign(x) (R_l - 128 R_{l-1}), a value in [-64, 64].  R_l = floor(.) + c_l with the round-up decision
 //     c_l = guard & (sticky | lsb)
 // read off the bits of I below the cut, so  slice l = field_l + c_l - 128 c_{l-1}:  still shifts and
-// masks only.
+// masks only; c_l is carried from one slice to the next.
 //
 // The MFMA layout written here is the one the GEMM kernel reads (see include/ozimmu.h):
 // fragments of 32 (R) x 32 (K) bytes, 16 contiguous K-bytes per wavefront lane.
@@ -51,29 +51,26 @@ __device__ __forceinline__ unsigned int slice_byte(const Elem &el, int l)
     return (unsigned int)d & 0xffu;
 }
 
-// round-up decision at the cut below slice l (l >= 0): 1 when |x| 2^{7l - e} is rounded away from zero
-__device__ __forceinline__ int round_up_at(const Elem &el, int l)
-{
-    const int sh = el.base - kSliceBits * l;      // bits of I below the cut
-    if (sh <= 0 || sh > 64) return 0;             // nothing below the cut / I < 2^53 lies below half a unit
-    const unsigned long long guard = (el.I >> (sh - 1)) & 1ULL;
-    const unsigned long long sticky = sh >= 2 ? (el.I & ((1ULL << (sh - 1)) - 1ULL)) : 0ULL;
-    const unsigned long long lsb = sh < 64 ? (el.I >> sh) & 1ULL : 0ULL;
-    return (int)(guard & ((sticky != 0ULL) | lsb));
-}
-
-// slice l by round-to-nearest (el.base taken from the biased exponent e + 1)
+// slice l by round-to-nearest (el.base taken from the biased exponent e + 1).  `carry` is bit `bit` of a
+// per-lane mask: on entry c_{l-1}, on exit c_l (the caller walks l = 1, 2, ... with the mask cleared first:
+// c_0 = 0 because |x| 2^{-e-1} < 1/2).
 template <bool NEAREST>
-__device__ __forceinline__ unsigned int slice_of(const Elem &el, int l)
+__device__ __forceinline__ unsigned int slice_of(const Elem &el, int l, unsigned int &carry, int bit)
 {
     if (!NEAREST) return slice_byte(el, l);
-    const int sh = el.base - kSliceBits * l;
-    unsigned long long v;
-    if (sh >= 64) v = 0;
-    else if (sh >= 0) v = el.I >> sh;
-    else if (sh <= -kSliceBits) v = 0;
-    else v = el.I << (-sh);
-    int d = (int)(v & 127ULL) + round_up_at(el, l) - 128 * round_up_at(el, l - 1);
+    const int sh = el.base - kSliceBits * l;      // bits of I below the cut
+    int field, c = 0;
+    if (sh > 64) field = 0;                       // I < 2^53 lies below half a unit
+    else if (sh >= 1) {
+        const unsigned long long t = el.I >> (sh - 1);            // guard bit at bit 0, the slice above it
+        const unsigned int lo = (unsigned int)t;
+        const bool sticky = (t << (sh - 1)) != el.I;
+        field = (int)((lo >> 1) & 127u);
+        c = (int)(lo & 1u) & ((int)sticky | (int)((lo >> 1) & 1u));
+    } else if (sh > -kSliceBits) field = (int)((el.I << (-sh)) & 127ULL);   // nothing below the cut
+    else field = 0;
+    int d = field + c - 128 * (int)((carry >> bit) & 1u);
+    carry = (carry & ~(1u << bit)) | ((unsigned int)c << bit);
     d = el.neg ? -d : d;
     return (unsigned int)d & 0xffu;
 }
@@ -100,12 +97,15 @@ __global__ __launch_bounds__(256) void split_rows_kernel(const unsigned long lon
     }
     const int rb = r >> 5, kb = k0 >> 5, half = (k0 >> 4) & 1;
     uint4 *dst = (uint4 *)(planes + ((size_t)rb * KB + kb) * (size_t)s * kFragBytes) + ((r & 31) + 32 * half);
+    unsigned int carry = 0;
     for (int l = 1; l <= s; ++l) {
         unsigned int wd[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q)
-            wd[q] = slice_of<NEAREST>(el[4 * q], l) | (slice_of<NEAREST>(el[4 * q + 1], l) << 8) |
-                    (slice_of<NEAREST>(el[4 * q + 2], l) << 16) | (slice_of<NEAREST>(el[4 * q + 3], l) << 24);
+            wd[q] = slice_of<NEAREST>(el[4 * q], l, carry, 4 * q) |
+                    (slice_of<NEAREST>(el[4 * q + 1], l, carry, 4 * q + 1) << 8) |
+                    (slice_of<NEAREST>(el[4 * q + 2], l, carry, 4 * q + 2) << 16) |
+                    (slice_of<NEAREST>(el[4 * q + 3], l, carry, 4 * q + 3) << 24);
         dst[(size_t)(l - 1) * (kFragBytes / 16)] = make_uint4(wd[0], wd[1], wd[2], wd[3]);
     }
 }
@@ -143,15 +143,17 @@ __global__ __launch_bounds__(256) void split_cols_kernel(const unsigned long lon
     const int rb = j0 >> 5;
     const int kb = (k0 + ch * 16) >> 5, half = ch & 1;
     uint4 *dst = (uint4 *)(planes + ((size_t)rb * KB + kb) * (size_t)s * kFragBytes) + (jj2 + 32 * half);
+    unsigned int carry = 0;
     for (int l0 = 1; l0 <= s; l0 += kColGroup) {
         const int nl = (s - l0 + 1) < kColGroup ? (s - l0 + 1) : kColGroup;
         for (int dl = 0; dl < nl; ++dl) {
 #pragma unroll
             for (int p = 0; p < 4; ++p) {
                 const int jj = p * 8 + (t >> 5);
-                unsigned int wd = slice_of<NEAREST>(el[p][0], l0 + dl) | (slice_of<NEAREST>(el[p][1], l0 + dl) << 8) |
-                                  (slice_of<NEAREST>(el[p][2], l0 + dl) << 16) |
-                                  (slice_of<NEAREST>(el[p][3], l0 + dl) << 24);
+                unsigned int wd = slice_of<NEAREST>(el[p][0], l0 + dl, carry, 4 * p) |
+                                  (slice_of<NEAREST>(el[p][1], l0 + dl, carry, 4 * p + 1) << 8) |
+                                  (slice_of<NEAREST>(el[p][2], l0 + dl, carry, 4 * p + 2) << 16) |
+                                  (slice_of<NEAREST>(el[p][3], l0 + dl, carry, 4 * p + 3) << 24);
                 *(unsigned int *)(lds + ((size_t)dl * 32 + jj) * kColLdsRow + kq) = wd;
             }
         }
@@ -176,8 +178,9 @@ __global__ __launch_bounds__(256) void split_plain_kernel(const unsigned long lo
     for (int c = blockIdx.y; c < cols; c += gridDim.y) {
         const int e = by_row ? exps[r] : exps[c];
         const Elem el = decompose(X[r + (size_t)c * ldx], e);
+        unsigned int carry = 0;
         for (int l = 1; l <= s; ++l)
-            planes[(size_t)(l - 1) * plane + r + (size_t)c * rows] = (int8_t)slice_of<NEAREST>(el, l);
+            planes[(size_t)(l - 1) * plane + r + (size_t)c * rows] = (int8_t)slice_of<NEAREST>(el, l, carry, 0);
     }
 }
 
