@@ -118,7 +118,9 @@ def main():
         "data": "synthetic",
         "config": {"workload": args.workload, "m": m, "n": n, "k": k, "slices": s, "slice_pairs": pairs},
         "roofline": {
-            "kernel": "gemm_fused_kernel",
+            # which GEMM kernel the library runs for equal slice counts (see csrc/gemm.hip, launch_gemm_fused)
+            "kernel": ("gemm_fused16_kernel" if s in (4, 8) else "gemm_fused_kernel") if s <= 12
+                      else "gemm_banded_kernel",
             "bound": "mfma",
             "achieved": int8_tops,
             "peak": INT8_PEAK_TOPS,
@@ -156,6 +158,24 @@ def main():
     normwise, comp = error_measures(C, dA, dB, Cref)
     out["native_dgemm"] = {"tflops": flops / t_native / 1e12, "ms": t_native * 1e3, "library": "rocBLAS/hipBLASLt via torch.matmul"}
     out["error_vs_native"] = {"normwise_err_higham": normwise, "max_componentwise": comp}
+
+    # the two accuracy variants at the same slice count: round-to-nearest slices, levels of 3 diagonals
+    variants = {}
+    ws2 = ozimmu.alloc_workspace(m, n, k, s)
+    for name, splitting, q in (("nearest_slices", ozimmu.SPLIT_NEAREST, 1),
+                               ("levels_of_3_diagonals", ozimmu.SPLIT_TRUNCATE, min(3, ozimmu.max_level_diagonals(k, s, s)))):
+        ozimmu.dgemm3(dA, dB, s, s, False, splitting, q, C=C, workspace=ws2)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(3):
+            ozimmu.dgemm3(dA, dB, s, s, False, splitting, q, C=C, workspace=ws2)
+        torch.cuda.synchronize()
+        tv = (time.perf_counter() - t0) / 3
+        nw, cw = error_measures(C, dA, dB, Cref)
+        variants[name] = {"ms_per_step": tv * 1e3, "tflops_effective": flops / tv / 1e12,
+                          "normwise_err_higham": nw, "max_componentwise": cw}
+    out["variants"] = variants
+    del ws2
 
     # context: what the matrix cores sustain with nothing else running, and the vendor's int8 GEMM
     out["int8_mfma_sustained_TOPs"] = {"constant_operands": ozimmu.measure_int8_ceiling(False),
