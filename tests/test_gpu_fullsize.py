@@ -83,3 +83,29 @@ def test_full_size_long_k_forces_k_blocking():
     dA, dB = workloads.lognormal_device(2048, 2048, 262144, 2.0, 1004)
     print("long-k inputs ready", flush=True)
     check_sampled(dA, dB, 7, "lognormal_longk s=7")
+
+
+def check_sampled_variant(dA, dB, sA, sB, allp, nearest, Q, tag):
+    m, k = dA.shape
+    n = dB.shape[1]
+    C = ozimmu.dgemm3(dA, dB, sA, sB, allp, ozimmu.SPLIT_NEAREST if nearest else ozimmu.SPLIT_TRUNCATE, Q,
+                      check_finite=True)
+    rows, cols = sample_indices(m, 3, 12), sample_indices(n, 4, 12)
+    tr, tc = torch.as_tensor(rows, device="cuda"), torch.as_tensor(cols, device="cuda")
+    want = oracle.dgemm3(dA[tr, :].cpu().numpy(), dB[:, tc].cpu().numpy(), sA, sB, full=allp, nearest=nearest, Q=Q)
+    got = C[tr][:, tc].cpu().numpy()
+    assert np.array_equal(got, want), f"{tag}: not bit-identical"
+
+
+def test_full_size_variants_8192():
+    # the 16x16x64 kernel (s = 4, 8), nearest slices, levels, different slice counts and the band kernel at
+    # the benchmark size
+    cfg = workloads.CONFIGS["pow2_scaled_8192"]
+    A, B = cfg["gen"]()
+    dA, dB = ozimmu.to_colmajor(A), ozimmu.to_colmajor(B)
+    qmax = ozimmu.max_level_diagonals(8192, 7, 7)
+    assert qmax == 4
+    for sA, sB, allp, nearest, Q in [(4, 4, False, False, 1), (8, 8, False, True, 3), (7, 7, False, True, qmax),
+                                     (5, 10, False, False, 3), (13, 13, False, True, 3), (3, 4, True, False, 2)]:
+        print(f"variant sA={sA} sB={sB} all={allp} nearest={nearest} Q={Q}", flush=True)
+        check_sampled_variant(dA, dB, sA, sB, allp, nearest, Q, f"8192 ({sA},{sB}) all={allp} nearest={nearest} Q={Q}")
