@@ -124,9 +124,11 @@ __global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t
         const unsigned char *cur = lds + buf * STAGE;
 #pragma unroll
         for (int kbl = 0; kbl < KB32; ++kbl) {
-            v4i bf[S][WNF];
+            // beyond 16 slices the B slices h >= HP are read when needed instead of being held for the whole stage
+            constexpr int HP = S > 16 ? 8 : S;
+            v4i bf[HP][WNF];
 #pragma unroll
-            for (int h = 0; h < S; ++h)
+            for (int h = 0; h < HP; ++h)
 #pragma unroll
                 for (int j = 0; j < WNF; ++j)
                     bf[h][j] = *(const v4i *)(cur + (FA + wn * WNF + j) * CHUNK + (kbl * S + h) * kFragBytes + lane * 16);
@@ -141,9 +143,12 @@ __global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t
 #pragma unroll
                     for (int i = 0; i < WMF; ++i)
 #pragma unroll
-                        for (int j = 0; j < WNF; ++j)
-                            acc[l + h][i][j] =
-                                __builtin_amdgcn_mfma_i32_32x32x32_i8(bf[h][j], af[i], acc[l + h][i][j], 0, 0, 0);
+                        for (int j = 0; j < WNF; ++j) {
+                            const v4i bv = h < HP ? bf[h < HP ? h : 0][j]
+                                                  : *(const v4i *)(cur + (FA + wn * WNF + j) * CHUNK +
+                                                                   (kbl * S + h) * kFragBytes + lane * 16);
+                            acc[l + h][i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bv, af[i], acc[l + h][i][j], 0, 0, 0);
+                        }
             }
         }
         // stage st+1 must have landed before anyone reads it: with a ring of 3 the stage issued in
@@ -157,16 +162,24 @@ __global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t
         // this k-block's diagonal sums -> int64 totals of the tile, [tile][wavefront][a][i][j][r][lane]
         long long *tot = totals + ((size_t)(tm * tiles_n + tn) * NW + wave) * (size_t)(S * WMF * WNF * 16 * 64) + lane;
 #pragma unroll
-        for (int a = 0; a < S; ++a)
+        for (int a = 0; a < S; ++a) {
+            // (one diagonal at a time, its base address formed here: otherwise all 16 * S slot addresses are
+            // built up front and spill)
+            long long *ta = tot + (size_t)a * (WMF * WNF * 16 * 64);
+            asm volatile("" : "+v"(ta));
 #pragma unroll
             for (int i = 0; i < WMF; ++i)
 #pragma unroll
                 for (int j = 0; j < WNF; ++j)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        __hip_atomic_fetch_add(tot + ((((size_t)a * WMF + i) * WNF + j) * 16 + r) * 64,
-                                               (long long)acc[a][i][j][r], __ATOMIC_RELAXED,
-                                               __HIP_MEMORY_SCOPE_AGENT);
+                    for (int r = 0; r < 16; ++r) {
+                        int v = acc[a][i][j][r];
+                        asm volatile("" : "+v"(v));     // (keeps the widening to 64 bits next to its use)
+                        __hip_atomic_fetch_add(ta + (((size_t)i * WNF + j) * 16 + r) * 64, (long long)v,
+                                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
+            asm volatile("" ::: "memory");
+        }
         return;
     }
 
@@ -360,16 +373,21 @@ __global__ __launch_bounds__(kThreads) void gemm_generic_kernel(const int8_t *__
 //   WIDE: 8 wavefronts as 2 (m) x 4 (n), each 64 x 32 outputs: tile 128 x 128 (fewer L2->LDS bytes
 //         per product; fits the 256 registers of a two-per-SIMD wavefront while 32*S <= 192)
 //   else: 8 wavefronts as 4 (m) x 2 (n), each 32 x 32 outputs: tile 128 x 64
+//   BIG (s > 12): 4 wavefronts as 2 x 2, ONE per SIMD, each 32 x 32 outputs: tile 64 x 64.  A lone wavefront
+//         may use all 512 registers of its SIMD lane (256 of them accumulation registers), which holds
+//         16 * s accumulators up to s = 18; the products per staged byte grow with s, so the small tile
+//         still feeds the matrix cores (3.0 POP/s at s = 16, where the band kernel reaches 1.8).
 template <int S>
 struct FusedCfg {
+    static constexpr bool BIG = S > 12;
     static constexpr bool WIDE = S <= 4 || S == 6;
-    static constexpr int WVM = WIDE ? 2 : 4, WVN = WIDE ? 4 : 2, WMF = WIDE ? 2 : 1, WNF = 1;
+    static constexpr int WVM = BIG ? 2 : WIDE ? 2 : 4, WVN = BIG ? 2 : WIDE ? 4 : 2, WMF = WIDE ? 2 : 1, WNF = 1;
     static constexpr int FR = WVM * WMF + WVN * WNF;
     static constexpr int KB32 = S == 4 ? 2 : 1;
     static constexpr int NSTAGE = S <= 3 ? 3 : 2;
 };
 
-constexpr int kFusedMaxS = 12;   // 16 accumulator registers per diagonal; beyond 12 the wavefront's 256 run out
+constexpr int kFusedMaxS = 18;   // 16 accumulator registers per diagonal: 12 fit 256 registers, 18 fit 512 (BIG)
 
 // Tile geometry of the fused kernel for a slice count (used for the size of the k-block totals).
 template <int S>
@@ -403,10 +421,12 @@ hipError_t launch_fused_s(int m, int n, int kp, const int8_t *pA, const int8_t *
             pA, pB, eA, eB, C, ldc, m, n, kp / kFrag, tiles_m, tiles_n, dump, nullptr, 0, Q);
         return hipGetLastError();
     }
-    // longest k-block whose s products per diagonal cannot overflow int32, in whole stages
-    const int stages_per_block = (int)(kMaxInt32K / S / kFrag) / Cfg::KB32;
+    // longest k-block whose s products per diagonal cannot overflow int32, in whole stages; the blocks are
+    // then made equally long
+    const int max_stages = (int)(kMaxInt32K / S / kFrag) / Cfg::KB32;
     const int nst = kp / kFrag / Cfg::KB32;
-    const int nblocks = (nst + stages_per_block - 1) / stages_per_block;
+    const int nblocks = (nst + max_stages - 1) / max_stages;
+    const int stages_per_block = (nst + nblocks - 1) / nblocks;
     const size_t nslots = (size_t)tiles_m * tiles_n * S * TM * TN;
     zero_i64_kernel<<<2048, 256, 0, st>>>(totals, nslots);
     dim3 grid(tiles_m * tiles_n, nblocks);
@@ -426,7 +446,7 @@ hipError_t dispatch_fused(int s, int m, int n, int kp, const int8_t *pA, const i
     switch (s) {
 #define OZ_CASE(S_) \
     case S_: return launch_fused_s<S_, MODE>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, Q, st);
-        OZ_CASE(1) OZ_CASE(2) OZ_CASE(3) OZ_CASE(4) OZ_CASE(5) OZ_CASE(6) OZ_CASE(7) OZ_CASE(8) OZ_CASE(9) OZ_CASE(10) OZ_CASE(11) OZ_CASE(12)
+        OZ_CASE(1) OZ_CASE(2) OZ_CASE(3) OZ_CASE(4) OZ_CASE(5) OZ_CASE(6) OZ_CASE(7) OZ_CASE(8) OZ_CASE(9) OZ_CASE(10) OZ_CASE(11) OZ_CASE(12) OZ_CASE(13) OZ_CASE(14) OZ_CASE(15) OZ_CASE(16) OZ_CASE(17) OZ_CASE(18)
 #undef OZ_CASE
     }
     return hipErrorInvalidValue;
@@ -449,7 +469,7 @@ size_t fused_totals_bytes(int s, int m, int n, int k)
     if (fused16_preferred(s)) fused16_tile(s, tm, tn);
     else switch (s) {
 #define OZ_CASE(S_) case S_: fused_tile<S_>(tm, tn); break;
-        OZ_CASE(1) OZ_CASE(2) OZ_CASE(3) OZ_CASE(4) OZ_CASE(5) OZ_CASE(6) OZ_CASE(7) OZ_CASE(8) OZ_CASE(9) OZ_CASE(10) OZ_CASE(11) OZ_CASE(12)
+        OZ_CASE(1) OZ_CASE(2) OZ_CASE(3) OZ_CASE(4) OZ_CASE(5) OZ_CASE(6) OZ_CASE(7) OZ_CASE(8) OZ_CASE(9) OZ_CASE(10) OZ_CASE(11) OZ_CASE(12) OZ_CASE(13) OZ_CASE(14) OZ_CASE(15) OZ_CASE(16) OZ_CASE(17) OZ_CASE(18)
 #undef OZ_CASE
     }
     const size_t tiles = (size_t)((m + tm - 1) / tm) * ((n + tn - 1) / tn);

@@ -286,10 +286,11 @@ hipError_t launch16_s(int m, int n, int kp, const int8_t *pA, const int8_t *pB, 
                                                          nullptr, 0, Q);
         return hipGetLastError();
     }
-    // longest k-block (in 64-k stages) whose s products per diagonal cannot overflow int32
-    const int stages_per_block = (int)(kMaxInt32K / S / (2 * kFrag));
+    // longest k-block (in 64-k stages) whose s products per diagonal cannot overflow int32; equally long blocks
+    const int max_stages = (int)(kMaxInt32K / S / (2 * kFrag));
     const int nst = KB / 2;
-    const int nblocks = (nst + stages_per_block - 1) / stages_per_block;
+    const int nblocks = (nst + max_stages - 1) / max_stages;
+    const int stages_per_block = (nst + nblocks - 1) / nblocks;
     zero16_i64_kernel<<<2048, 256, 0, st>>>(totals, (size_t)tiles_m * tiles_n * S * TM * TN);
     dim3 grid(tiles_m * tiles_n, nblocks);
     kern<<<grid, THREADS, G::LDS, st>>>(pA, pB, eA, eB, C, ldc, m, n, KB, tiles_m, tiles_n, nullptr, totals,
