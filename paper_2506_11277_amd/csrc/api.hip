@@ -239,12 +239,12 @@ static int dgemm_impl(int m, int n, int k, const double *A, int lda, const doubl
     OZ_TRY(launch_split('A', m, k, A, lda, sA, eA, pA, OZIMMU_LAYOUT_MFMA, nearest, st));
     OZ_TRY(launch_split('B', k, n, B, ldb, sB, eB, pB, OZIMMU_LAYOUT_MFMA, nearest, st));
     prof_mark(2, st);
-    const bool fused = sA == sB && !all_products && sA <= fused_max_slices();
-    if (fused && fused_single_block(sA, k)) {
-        OZ_TRY(launch_gemm_fused(m, n, w.kp, sA, pA, pB, eA, eB, C, ldc, nullptr, nullptr, Q, st));
+    const bool fused = fused_handles(sA, sB, all_products);
+    if (fused && fused_single_block(sA, sB, k)) {
+        OZ_TRY(launch_gemm_fused(m, n, w.kp, sA, sB, pA, pB, eA, eB, C, ldc, nullptr, nullptr, Q, st));
     } else if (fused) {
-        OZ_TRY(launch_gemm_fused(m, n, w.kp, sA, pA, pB, eA, eB, C, ldc, nullptr, (long long *)(ws + w.off_totals), Q,
-                                 st));
+        OZ_TRY(launch_gemm_fused(m, n, w.kp, sA, sB, pA, pB, eA, eB, C, ldc, nullptr,
+                                 (long long *)(ws + w.off_totals), Q, st));
     } else {
         const int dmax = all_products ? sA + sB : (sA > sB ? sA : sB) + 1;
         long long *totals = banded_totals_bytes(sA, sB, k) ? (long long *)(ws + w.off_totals) : nullptr;
@@ -336,10 +336,10 @@ int ozimmu_get_exponents(int m, int n, int k, int s, const void *workspace, int3
 
 int ozimmu_debug_diagonals(int m, int n, int k, int s, const void *workspace, int32_t *D, void *stream)
 {
-    if (m <= 0 || n <= 0 || k < 0 || !workspace || !D || !fused_single_block(s, k)) return OZIMMU_BAD_ARG;
+    if (m <= 0 || n <= 0 || k < 0 || !workspace || !D || !fused_single_block(s, s, k)) return OZIMMU_BAD_ARG;
     const Workspace w = carve(m, n, k, s, s);
     const char *ws = (const char *)workspace;
-    OZ_TRY(launch_gemm_fused(m, n, w.kp, s, (const int8_t *)(ws + w.off_planesA), (const int8_t *)(ws + w.off_planesB),
+    OZ_TRY(launch_gemm_fused(m, n, w.kp, s, s, (const int8_t *)(ws + w.off_planesA), (const int8_t *)(ws + w.off_planesB),
                              nullptr, nullptr, nullptr, m, D, nullptr, 1, (hipStream_t)stream));
     return OZIMMU_OK;
 }

@@ -44,8 +44,14 @@ constexpr int kThreads = 256;   // generic kernel: 4 wavefronts, 2 (m) x 2 (n)
 //                  int64 totals in HBM with integer atomics -- exact, so the totals do not depend on
 //                  the order of arrival and the result stays bit-reproducible; finish_blocked_kernel
 //                  then does the binary64 accumulation
+//   UNEQ   0: both operands have S slices.  1 / 2: different slice counts (subsection "Reduction in number
+//          of products" of Sect. 4): S is the LARGER count, the operand A (1) or B (2) has only `sm` < S
+//          slices (run time), and the products are l + h <= S + 1 with the short operand's index <= sm.  The
+//          pair loop stays fully unrolled over the long operand; the short operand's loop is the outer one and
+//          simply ends after sm slices, so no product needs a test of its own.  LDS keeps the layout for S
+//          slices of both operands (the short one's upper slots stay unused).
 
-template <int S, int WVM, int WVN, int WMF, int WNF, int KB32, int NSTAGE, int MODE>
+template <int S, int WVM, int WVN, int WMF, int WNF, int KB32, int NSTAGE, int MODE, int UNEQ>
 __global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t *__restrict__ pA,
                                                                     const int8_t *__restrict__ pB,
                                                                     const int32_t *__restrict__ eA,
@@ -54,8 +60,9 @@ __global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t
                                                                     int KB, int tiles_m, int tiles_n,
                                                                     int32_t *__restrict__ dump,
                                                                     long long *__restrict__ totals,
-                                                                    int stages_per_block, int Q)
+                                                                    int stages_per_block, int Q, int sm)
 {
+    static_assert(UNEQ == 0 || (NSTAGE == 2 && MODE != kDump), "different slice counts: ring of two, no dump");
     constexpr bool DUMP = MODE == kDump;
     constexpr int NW = WVM * WVN;                      // wavefronts
     constexpr int FA = WVM * WMF, FB = WVN * WNF;      // fragment rows per work-group tile along m / n
@@ -72,9 +79,11 @@ __global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wm = wave % WVM, wn = wave / WVM;
-    const size_t row_bytes = (size_t)KB * (S * kFragBytes);     // one fragment row of an operand, all k
-    const int8_t *rowA = pA + (size_t)tm * FA * row_bytes;
-    const int8_t *rowB = pB + (size_t)tn * FB * row_bytes;
+    const int sA = UNEQ == 1 ? sm : S, sB = UNEQ == 2 ? sm : S;                 // slices in the planes of A / B
+    const size_t row_bytesA = (size_t)KB * sA * kFragBytes;     // one fragment row of an operand, all k
+    const size_t row_bytesB = (size_t)KB * sB * kFragBytes;
+    const int8_t *rowA = pA + (size_t)tm * FA * row_bytesA;
+    const int8_t *rowB = pB + (size_t)tn * FB * row_bytesB;
     const bool extra = wave < UREM;
 
     // copy of stage `st` into ring buffer `buf`: unit u = wave + i*NW  ->  fragment row c = u / (KB32*S)
@@ -84,8 +93,17 @@ __global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t
             if (i == UPW && !extra) break;
             const int u = wave + i * NW;
             const int c = u / (KB32 * S), o = u % (KB32 * S);
-            const int8_t *src = (c < FA ? rowA + (size_t)c * row_bytes : rowB + (size_t)(c - FA) * row_bytes) +
-                                (size_t)st * CHUNK + (size_t)o * kFragBytes;
+            const int8_t *src;
+            if (UNEQ == 0) {
+                src = (c < FA ? rowA + (size_t)c * row_bytesA : rowB + (size_t)(c - FA) * row_bytesB) +
+                      (size_t)st * CHUNK + (size_t)o * kFragBytes;
+            } else {
+                const int kbl = o / S, sl = o % S;                          // LDS slot (k-block, slice)
+                const int cnt = c < FA ? sA : sB;
+                if (sl >= cnt) continue;                                    // the short operand has no such slice
+                src = (c < FA ? rowA + (size_t)c * row_bytesA : rowB + (size_t)(c - FA) * row_bytesB) +
+                      ((size_t)(st * KB32 + kbl) * cnt + sl) * kFragBytes;
+            }
             lds_dma16(src, lane * 16, lds0 + buf * STAGE + u * kFragBytes);
         }
     };
@@ -124,31 +142,62 @@ __global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t
         const unsigned char *cur = lds + buf * STAGE;
 #pragma unroll
         for (int kbl = 0; kbl < KB32; ++kbl) {
-            // beyond 16 slices the B slices h >= HP are read when needed instead of being held for the whole stage
+            // beyond 16 slices the slices >= HP of the preloaded operand are read when needed instead of being
+            // held for the whole stage
             constexpr int HP = S > 16 ? 8 : S;
-            v4i bf[HP][WNF];
+            if (UNEQ != 2) {
+                v4i bf[HP][WNF];
 #pragma unroll
-            for (int h = 0; h < HP; ++h)
+                for (int h = 0; h < HP; ++h)
 #pragma unroll
-                for (int j = 0; j < WNF; ++j)
-                    bf[h][j] = *(const v4i *)(cur + (FA + wn * WNF + j) * CHUNK + (kbl * S + h) * kFragBytes + lane * 16);
+                    for (int j = 0; j < WNF; ++j)
+                        bf[h][j] = *(const v4i *)(cur + (FA + wn * WNF + j) * CHUNK + (kbl * S + h) * kFragBytes + lane * 16);
 #pragma unroll
-            for (int l = 0; l < S; ++l) {
-                v4i af[WMF];
-#pragma unroll
-                for (int i = 0; i < WMF; ++i)
-                    af[i] = *(const v4i *)(cur + (wm * WMF + i) * CHUNK + (kbl * S + l) * kFragBytes + lane * 16);
-#pragma unroll
-                for (int h = 0; h < S - l; ++h)
+                for (int l = 0; l < S; ++l) {
+                    if (UNEQ == 1 && l >= sm) continue;     // (not `break`: the loop must stay fully unrollable)
+                    v4i af[WMF];
 #pragma unroll
                     for (int i = 0; i < WMF; ++i)
+                        af[i] = *(const v4i *)(cur + (wm * WMF + i) * CHUNK + (kbl * S + l) * kFragBytes + lane * 16);
 #pragma unroll
-                        for (int j = 0; j < WNF; ++j) {
-                            const v4i bv = h < HP ? bf[h < HP ? h : 0][j]
-                                                  : *(const v4i *)(cur + (FA + wn * WNF + j) * CHUNK +
-                                                                   (kbl * S + h) * kFragBytes + lane * 16);
-                            acc[l + h][i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bv, af[i], acc[l + h][i][j], 0, 0, 0);
-                        }
+                    for (int h = 0; h < S - l; ++h)
+#pragma unroll
+                        for (int i = 0; i < WMF; ++i)
+#pragma unroll
+                            for (int j = 0; j < WNF; ++j) {
+                                const v4i bv = h < HP ? bf[h < HP ? h : 0][j]
+                                                      : *(const v4i *)(cur + (FA + wn * WNF + j) * CHUNK +
+                                                                       (kbl * S + h) * kFragBytes + lane * 16);
+                                acc[l + h][i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bv, af[i], acc[l + h][i][j], 0, 0, 0);
+                            }
+                }
+            } else {
+                // B is the short operand: its slices form the outer loop, those of A are held
+                v4i af[HP][WMF];
+#pragma unroll
+                for (int l = 0; l < HP; ++l)
+#pragma unroll
+                    for (int i = 0; i < WMF; ++i)
+                        af[l][i] = *(const v4i *)(cur + (wm * WMF + i) * CHUNK + (kbl * S + l) * kFragBytes + lane * 16);
+#pragma unroll
+                for (int h = 0; h < S; ++h) {
+                    if (h >= sm) continue;
+                    v4i bf[WNF];
+#pragma unroll
+                    for (int j = 0; j < WNF; ++j)
+                        bf[j] = *(const v4i *)(cur + (FA + wn * WNF + j) * CHUNK + (kbl * S + h) * kFragBytes + lane * 16);
+#pragma unroll
+                    for (int l = 0; l < S - h; ++l)
+#pragma unroll
+                        for (int i = 0; i < WMF; ++i)
+#pragma unroll
+                            for (int j = 0; j < WNF; ++j) {
+                                const v4i av = l < HP ? af[l < HP ? l : 0][i]
+                                                      : *(const v4i *)(cur + (wm * WMF + i) * CHUNK +
+                                                                       (kbl * S + l) * kFragBytes + lane * 16);
+                                acc[l + h][i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bf[j], av, acc[l + h][i][j], 0, 0, 0);
+                            }
+                }
             }
         }
         // stage st+1 must have landed before anyone reads it: with a ring of 3 the stage issued in
@@ -397,57 +446,60 @@ void fused_tile(int &tm, int &tn)
     tn = 32 * FusedCfg<S>::WVN * FusedCfg<S>::WNF;
 }
 
-template <int S, int MODE>
+// sm: slices of the short operand (UNEQ = 1: A, 2: B); UNEQ = 0: sm = S
+template <int S, int MODE, int UNEQ>
 hipError_t launch_fused_s(int m, int n, int kp, const int8_t *pA, const int8_t *pB, const int32_t *eA,
-                          const int32_t *eB, double *C, int ldc, int32_t *dump, long long *totals, int Q,
+                          const int32_t *eB, double *C, int ldc, int32_t *dump, long long *totals, int Q, int sm,
                           hipStream_t st)
 {
     using Cfg = FusedCfg<S>;
     constexpr int TM = 32 * Cfg::WVM * Cfg::WMF, TN = 32 * Cfg::WVN * Cfg::WNF;
     constexpr int STAGE = Cfg::FR * Cfg::KB32 * S * kFragBytes;
-    static_assert(Cfg::NSTAGE * STAGE <= kLdsBytes, "LDS ring too large");
+    constexpr int NSTAGE = UNEQ ? 2 : Cfg::NSTAGE;
+    static_assert(NSTAGE * STAGE <= kLdsBytes, "LDS ring too large");
     static_assert(kPad % TM == 0 && kPad % TN == 0 && (kPad / kFrag) % Cfg::KB32 == 0, "tiles must divide the padding");
-    auto kern = gemm_fused_kernel<S, Cfg::WVM, Cfg::WVN, Cfg::WMF, Cfg::WNF, Cfg::KB32, Cfg::NSTAGE, MODE>;
+    auto kern = gemm_fused_kernel<S, Cfg::WVM, Cfg::WVN, Cfg::WMF, Cfg::WNF, Cfg::KB32, NSTAGE, MODE, UNEQ>;
     static bool configured = false;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           Cfg::NSTAGE * STAGE);
+                                           NSTAGE * STAGE);
         if (e != hipSuccess) return e;
         configured = true;
     }
     const int tiles_m = (m + TM - 1) / TM, tiles_n = (n + TN - 1) / TN;
     if (MODE != kBlocked) {
-        kern<<<tiles_m * tiles_n, 64 * Cfg::WVM * Cfg::WVN, Cfg::NSTAGE * STAGE, st>>>(
-            pA, pB, eA, eB, C, ldc, m, n, kp / kFrag, tiles_m, tiles_n, dump, nullptr, 0, Q);
+        kern<<<tiles_m * tiles_n, 64 * Cfg::WVM * Cfg::WVN, NSTAGE * STAGE, st>>>(
+            pA, pB, eA, eB, C, ldc, m, n, kp / kFrag, tiles_m, tiles_n, dump, nullptr, 0, Q, sm);
         return hipGetLastError();
     }
-    // longest k-block whose s products per diagonal cannot overflow int32, in whole stages; the blocks are
+    // longest k-block whose sm products per diagonal cannot overflow int32, in whole stages; the blocks are
     // then made equally long
-    const int max_stages = (int)(kMaxInt32K / S / kFrag) / Cfg::KB32;
+    const int max_stages = (int)(kMaxInt32K / sm / kFrag) / Cfg::KB32;
     const int nst = kp / kFrag / Cfg::KB32;
     const int nblocks = (nst + max_stages - 1) / max_stages;
     const int stages_per_block = (nst + nblocks - 1) / nblocks;
     const size_t nslots = (size_t)tiles_m * tiles_n * S * TM * TN;
     zero_i64_kernel<<<2048, 256, 0, st>>>(totals, nslots);
     dim3 grid(tiles_m * tiles_n, nblocks);
-    kern<<<grid, 64 * Cfg::WVM * Cfg::WVN, Cfg::NSTAGE * STAGE, st>>>(pA, pB, eA, eB, C, ldc, m, n, kp / kFrag,
-                                                                       tiles_m, tiles_n, nullptr, totals,
-                                                                       stages_per_block, Q);
+    kern<<<grid, 64 * Cfg::WVM * Cfg::WVN, NSTAGE * STAGE, st>>>(pA, pB, eA, eB, C, ldc, m, n, kp / kFrag, tiles_m,
+                                                                  tiles_n, nullptr, totals, stages_per_block, Q, sm);
     finish_blocked_kernel<S, Cfg::WVM, Cfg::WVN, Cfg::WMF, Cfg::WNF>
         <<<tiles_m * tiles_n, 64 * Cfg::WVM * Cfg::WVN, 0, st>>>(totals, eA, eB, C, ldc, m, n, tiles_n, Q);
     return hipGetLastError();
 }
 
-template <int MODE>
+template <int MODE, int UNEQ>
 hipError_t dispatch_fused(int s, int m, int n, int kp, const int8_t *pA, const int8_t *pB, const int32_t *eA,
-                          const int32_t *eB, double *C, int ldc, int32_t *dump, long long *totals, int Q,
+                          const int32_t *eB, double *C, int ldc, int32_t *dump, long long *totals, int Q, int sm,
                           hipStream_t st)
 {
     switch (s) {
 #define OZ_CASE(S_) \
-    case S_: return launch_fused_s<S_, MODE>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, Q, st);
-        OZ_CASE(1) OZ_CASE(2) OZ_CASE(3) OZ_CASE(4) OZ_CASE(5) OZ_CASE(6) OZ_CASE(7) OZ_CASE(8) OZ_CASE(9) OZ_CASE(10) OZ_CASE(11) OZ_CASE(12) OZ_CASE(13) OZ_CASE(14) OZ_CASE(15) OZ_CASE(16) OZ_CASE(17) OZ_CASE(18)
+    case S_: return launch_fused_s<S_, MODE, UNEQ>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, Q, sm, st);
+        OZ_CASE(2) OZ_CASE(3) OZ_CASE(4) OZ_CASE(5) OZ_CASE(6) OZ_CASE(7) OZ_CASE(8) OZ_CASE(9) OZ_CASE(10) OZ_CASE(11) OZ_CASE(12) OZ_CASE(13) OZ_CASE(14) OZ_CASE(15) OZ_CASE(16) OZ_CASE(17) OZ_CASE(18)
 #undef OZ_CASE
+        case 1:
+            if (UNEQ == 0) return launch_fused_s<1, MODE, 0>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, Q, sm, st);
     }
     return hipErrorInvalidValue;
 }
@@ -456,17 +508,24 @@ hipError_t dispatch_fused(int s, int m, int n, int kp, const int8_t *pA, const i
 
 int fused_max_slices() { return kFusedMaxS; }
 
-bool fused_single_block(int s, int k)
+bool fused_handles(int sA, int sB, bool all_products)
 {
-    // the longest diagonal has s products of k terms each, every term at most 127^2 in magnitude
-    return s >= 1 && s <= kFusedMaxS && (long long)s * (long long)(k > 0 ? k : 1) <= kMaxInt32K;
+    return !all_products && sA >= 1 && sB >= 1 && (sA > sB ? sA : sB) <= kFusedMaxS;
 }
 
-size_t fused_totals_bytes(int s, int m, int n, int k)
+bool fused_single_block(int sA, int sB, int k)
 {
-    if (s < 1 || s > kFusedMaxS || fused_single_block(s, k) || m <= 0 || n <= 0) return 0;
+    // the longest diagonal has min(sA, sB) products of k terms each, every term at most 127^2 in magnitude
+    const int sm = sA < sB ? sA : sB;
+    return fused_handles(sA, sB, false) && (long long)sm * (long long)(k > 0 ? k : 1) <= kMaxInt32K;
+}
+
+size_t fused_totals_bytes(int sA, int sB, int m, int n, int k)
+{
+    if (!fused_handles(sA, sB, false) || fused_single_block(sA, sB, k) || m <= 0 || n <= 0) return 0;
+    const int s = sA > sB ? sA : sB;
     int tm = 128, tn = 128;
-    if (fused16_preferred(s)) fused16_tile(s, tm, tn);
+    if (sA == sB && fused16_preferred(s)) fused16_tile(s, tm, tn);
     else switch (s) {
 #define OZ_CASE(S_) case S_: fused_tile<S_>(tm, tn); break;
         OZ_CASE(1) OZ_CASE(2) OZ_CASE(3) OZ_CASE(4) OZ_CASE(5) OZ_CASE(6) OZ_CASE(7) OZ_CASE(8) OZ_CASE(9) OZ_CASE(10) OZ_CASE(11) OZ_CASE(12) OZ_CASE(13) OZ_CASE(14) OZ_CASE(15) OZ_CASE(16) OZ_CASE(17) OZ_CASE(18)
@@ -476,17 +535,29 @@ size_t fused_totals_bytes(int s, int m, int n, int k)
     return tiles * (size_t)s * tm * tn * sizeof(long long);
 }
 
-hipError_t launch_gemm_fused(int m, int n, int kp, int s, const int8_t *pA, const int8_t *pB, const int32_t *eA,
-                             const int32_t *eB, double *C, int ldc, int32_t *dump, long long *totals, int Q,
-                             hipStream_t st)
+hipError_t launch_gemm_fused(int m, int n, int kp, int sA, int sB, const int8_t *pA, const int8_t *pB,
+                             const int32_t *eA, const int32_t *eB, double *C, int ldc, int32_t *dump,
+                             long long *totals, int Q, hipStream_t st)
 {
     if (m <= 0 || n <= 0) return hipSuccess;
-    // the 16x16x64 kernel where it is the faster one
-    if (fused16_preferred(s))
-        return launch_gemm_fused16(m, n, kp, s, pA, pB, eA, eB, C, ldc, dump, totals, Q, st);
-    if (dump) return dispatch_fused<kDump>(s, m, n, kp, pA, pB, eA, eB, C, ldc, dump, nullptr, Q, st);
-    if (totals) return dispatch_fused<kBlocked>(s, m, n, kp, pA, pB, eA, eB, C, ldc, nullptr, totals, Q, st);
-    return dispatch_fused<kPlain>(s, m, n, kp, pA, pB, eA, eB, C, ldc, nullptr, nullptr, Q, st);
+    if (sA == sB) {
+        const int s = sA;
+        // the 16x16x64 kernel where it is the faster one
+        if (fused16_preferred(s))
+            return launch_gemm_fused16(m, n, kp, s, pA, pB, eA, eB, C, ldc, dump, totals, Q, st);
+        if (dump) return dispatch_fused<kDump, 0>(s, m, n, kp, pA, pB, eA, eB, C, ldc, dump, nullptr, Q, s, st);
+        if (totals) return dispatch_fused<kBlocked, 0>(s, m, n, kp, pA, pB, eA, eB, C, ldc, nullptr, totals, Q, s, st);
+        return dispatch_fused<kPlain, 0>(s, m, n, kp, pA, pB, eA, eB, C, ldc, nullptr, nullptr, Q, s, st);
+    }
+    if (dump) return hipErrorInvalidValue;
+    // different slice counts: the kernel for the larger count, the short operand's count at run time
+    const int s = sA > sB ? sA : sB, sm = sA > sB ? sB : sA;
+    if (sA < sB) {
+        if (totals) return dispatch_fused<kBlocked, 1>(s, m, n, kp, pA, pB, eA, eB, C, ldc, nullptr, totals, Q, sm, st);
+        return dispatch_fused<kPlain, 1>(s, m, n, kp, pA, pB, eA, eB, C, ldc, nullptr, nullptr, Q, sm, st);
+    }
+    if (totals) return dispatch_fused<kBlocked, 2>(s, m, n, kp, pA, pB, eA, eB, C, ldc, nullptr, totals, Q, sm, st);
+    return dispatch_fused<kPlain, 2>(s, m, n, kp, pA, pB, eA, eB, C, ldc, nullptr, nullptr, Q, sm, st);
 }
 
 hipError_t launch_gemm_generic(int m, int n, int kp, int s, const int8_t *pA, const int8_t *pB, const int32_t *eA,

@@ -453,6 +453,16 @@ def test_dgemm3_variants_in_k_blocked_mode(s, Q, nearest):
     assert_c_matches(host(C), oracle.dgemm3(A, B, s, s, nearest=nearest, Q=Q), "dgemm3 k-blocked")
 
 
+@pytest.mark.parametrize("sA,sB", [(2, 9), (9, 2), (5, 11), (14, 6), (3, 18), (17, 12)])
+def test_different_slice_counts_in_k_blocked_mode(sA, sB):
+    # fused kernel with the short operand's count at run time, split-k: k beyond 133144 / min(sA, sB)
+    m, n = 130, 70
+    k = min(2 * (133144 // min(sA, sB)) + 200, 150000)
+    print(f"k-blocked sA={sA} sB={sB} k={k}", flush=True)
+    A, B = workloads.lognormal(m, n, k, 2.0, 60 + sA)
+    assert_c_matches(host(ozimmu.dgemm2(dev(A), dev(B), sA, sB)), oracle.dgemm2(A, B, sA, sB), "k-blocked unequal")
+
+
 def test_dgemm3_defaults_equal_dgemm2_and_bad_level_size_is_refused():
     A, B = workloads.lognormal(90, 80, 200, 1.0, 15)
     dA, dB = dev(A), dev(B)
