@@ -241,9 +241,9 @@ static int dgemm_impl(int m, int n, int k, const double *A, int lda, const doubl
     prof_mark(2, st);
     const bool fused = fused_handles(sA, sB, all_products);
     if (fused && fused_single_block(sA, sB, k)) {
-        OZ_TRY(launch_gemm_fused(m, n, w.kp, sA, sB, pA, pB, eA, eB, C, ldc, nullptr, nullptr, Q, st));
+        OZ_TRY(launch_gemm_fused(m, n, w.kp, sA, sB, all_products, pA, pB, eA, eB, C, ldc, nullptr, nullptr, Q, st));
     } else if (fused) {
-        OZ_TRY(launch_gemm_fused(m, n, w.kp, sA, sB, pA, pB, eA, eB, C, ldc, nullptr,
+        OZ_TRY(launch_gemm_fused(m, n, w.kp, sA, sB, all_products, pA, pB, eA, eB, C, ldc, nullptr,
                                  (long long *)(ws + w.off_totals), Q, st));
     } else {
         const int dmax = all_products ? sA + sB : (sA > sB ? sA : sB) + 1;
@@ -339,7 +339,8 @@ int ozimmu_debug_diagonals(int m, int n, int k, int s, const void *workspace, in
     if (m <= 0 || n <= 0 || k < 0 || !workspace || !D || !fused_single_block(s, s, k)) return OZIMMU_BAD_ARG;
     const Workspace w = carve(m, n, k, s, s);
     const char *ws = (const char *)workspace;
-    OZ_TRY(launch_gemm_fused(m, n, w.kp, s, s, (const int8_t *)(ws + w.off_planesA), (const int8_t *)(ws + w.off_planesB),
+    OZ_TRY(launch_gemm_fused(m, n, w.kp, s, s, false, (const int8_t *)(ws + w.off_planesA),
+                             (const int8_t *)(ws + w.off_planesB),
                              nullptr, nullptr, nullptr, m, D, nullptr, 1, (hipStream_t)stream));
     return OZIMMU_OK;
 }

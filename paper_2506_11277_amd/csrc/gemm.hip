@@ -44,14 +44,16 @@ constexpr int kThreads = 256;   // generic kernel: 4 wavefronts, 2 (m) x 2 (n)
 //                  int64 totals in HBM with integer atomics -- exact, so the totals do not depend on
 //                  the order of arrival and the result stays bit-reproducible; finish_blocked_kernel
 //                  then does the binary64 accumulation
-//   UNEQ   0: both operands have S slices.  1 / 2: different slice counts (subsection "Reduction in number
+//   PSET   product set.  0: both operands have S slices, products l + h <= S + 1.  3: both have S slices, ALL
+//          S * S products ("Computation of all products", Sect. 4): 2 S - 1 diagonals, so 2 S - 1 accumulator
+//          sets (S <= 9).  1 / 2: different slice counts (subsection "Reduction in number
 //          of products" of Sect. 4): S is the LARGER count, the operand A (1) or B (2) has only `sm` < S
 //          slices (run time), and the products are l + h <= S + 1 with the short operand's index <= sm.  The
 //          pair loop stays fully unrolled over the long operand; the short operand's loop is the outer one and
 //          simply ends after sm slices, so no product needs a test of its own.  LDS keeps the layout for S
 //          slices of both operands (the short one's upper slots stay unused).
 
-template <int S, int WVM, int WVN, int WMF, int WNF, int KB32, int NSTAGE, int MODE, int UNEQ>
+template <int S, int WVM, int WVN, int WMF, int WNF, int KB32, int NSTAGE, int MODE, int PSET>
 __global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t *__restrict__ pA,
                                                                     const int8_t *__restrict__ pB,
                                                                     const int32_t *__restrict__ eA,
@@ -62,8 +64,9 @@ __global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t
                                                                     long long *__restrict__ totals,
                                                                     int stages_per_block, int Q, int sm)
 {
-    static_assert(UNEQ == 0 || (NSTAGE == 2 && MODE != kDump), "different slice counts: ring of two, no dump");
+    static_assert(PSET == 0 || (NSTAGE == 2 && MODE != kDump), "other product sets: ring of two, no dump");
     constexpr bool DUMP = MODE == kDump;
+    constexpr int NA = PSET == 3 ? 2 * S - 1 : S;      // diagonals = accumulator sets
     constexpr int NW = WVM * WVN;                      // wavefronts
     constexpr int FA = WVM * WMF, FB = WVN * WNF;      // fragment rows per work-group tile along m / n
     constexpr int CHUNK = KB32 * S * kFragBytes;       // bytes of one fragment row per stage (contiguous in HBM)
@@ -79,7 +82,7 @@ __global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wm = wave % WVM, wn = wave / WVM;
-    const int sA = UNEQ == 1 ? sm : S, sB = UNEQ == 2 ? sm : S;                 // slices in the planes of A / B
+    const int sA = PSET == 1 ? sm : S, sB = PSET == 2 ? sm : S;                 // slices in the planes of A / B
     const size_t row_bytesA = (size_t)KB * sA * kFragBytes;     // one fragment row of an operand, all k
     const size_t row_bytesB = (size_t)KB * sB * kFragBytes;
     const int8_t *rowA = pA + (size_t)tm * FA * row_bytesA;
@@ -94,7 +97,7 @@ __global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t
             const int u = wave + i * NW;
             const int c = u / (KB32 * S), o = u % (KB32 * S);
             const int8_t *src;
-            if (UNEQ == 0) {
+            if (PSET == 0) {
                 src = (c < FA ? rowA + (size_t)c * row_bytesA : rowB + (size_t)(c - FA) * row_bytesB) +
                       (size_t)st * CHUNK + (size_t)o * kFragBytes;
             } else {
@@ -112,9 +115,9 @@ __global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t
         if (extra) wait_vmcnt<UPW + 1>(); else wait_vmcnt<UPW>();
     };
 
-    v16i acc[S][WMF][WNF];
+    v16i acc[NA][WMF][WNF];
 #pragma unroll
-    for (int a = 0; a < S; ++a)
+    for (int a = 0; a < NA; ++a)
 #pragma unroll
         for (int i = 0; i < WMF; ++i)
 #pragma unroll
@@ -145,7 +148,7 @@ __global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t
             // beyond 16 slices the slices >= HP of the preloaded operand are read when needed instead of being
             // held for the whole stage
             constexpr int HP = S > 16 ? 8 : S;
-            if (UNEQ != 2) {
+            if (PSET != 2) {
                 v4i bf[HP][WNF];
 #pragma unroll
                 for (int h = 0; h < HP; ++h)
@@ -154,13 +157,13 @@ __global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t
                         bf[h][j] = *(const v4i *)(cur + (FA + wn * WNF + j) * CHUNK + (kbl * S + h) * kFragBytes + lane * 16);
 #pragma unroll
                 for (int l = 0; l < S; ++l) {
-                    if (UNEQ == 1 && l >= sm) continue;     // (not `break`: the loop must stay fully unrollable)
+                    if (PSET == 1 && l >= sm) continue;     // (not `break`: the loop must stay fully unrollable)
                     v4i af[WMF];
 #pragma unroll
                     for (int i = 0; i < WMF; ++i)
                         af[i] = *(const v4i *)(cur + (wm * WMF + i) * CHUNK + (kbl * S + l) * kFragBytes + lane * 16);
 #pragma unroll
-                    for (int h = 0; h < S - l; ++h)
+                    for (int h = 0; h < (PSET == 3 ? S : S - l); ++h)
 #pragma unroll
                         for (int i = 0; i < WMF; ++i)
 #pragma unroll
@@ -209,9 +212,9 @@ __global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t
 
     if (MODE == kBlocked) {
         // this k-block's diagonal sums -> int64 totals of the tile, [tile][wavefront][a][i][j][r][lane]
-        long long *tot = totals + ((size_t)(tm * tiles_n + tn) * NW + wave) * (size_t)(S * WMF * WNF * 16 * 64) + lane;
+        long long *tot = totals + ((size_t)(tm * tiles_n + tn) * NW + wave) * (size_t)(NA * WMF * WNF * 16 * 64) + lane;
 #pragma unroll
-        for (int a = 0; a < S; ++a) {
+        for (int a = 0; a < NA; ++a) {
             // (one diagonal at a time, its base address formed here: otherwise all 16 * S slot addresses are
             // built up front and spill)
             long long *ta = tot + (size_t)a * (WMF * WNF * 16 * 64);
@@ -247,12 +250,12 @@ __global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t
                 if (nj >= n) continue;
                 if (DUMP) {
 #pragma unroll
-                    for (int a = 0; a < S; ++a) dump[(size_t)a * m * n + mi + (size_t)nj * m] = acc[a][i][j][r];
+                    for (int a = 0; a < NA; ++a) dump[(size_t)a * m * n + mi + (size_t)nj * m] = acc[a][i][j][r];
                 } else {
                     LevelSum sum;
 #pragma unroll
-                    for (int a = 0; a < S; ++a)
-                        sum.add((double)acc[a][i][j][r] * __builtin_ldexp(1.0, -kSliceBits * (a + 2)), Q, a == S - 1);
+                    for (int a = 0; a < NA; ++a)
+                        sum.add((double)acc[a][i][j][r] * __builtin_ldexp(1.0, -kSliceBits * (a + 2)), Q, a == NA - 1);
                     C[mi + (size_t)nj * ldc] = ldexp(sum.S, ea + eB[nj]);
                 }
             }
@@ -261,7 +264,7 @@ __global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t
 }
 
 // Second step of the k-blocked mode: binary64 accumulation from the int64 totals, same element
-// mapping and the same order of additions as the epilogue of gemm_fused_kernel.
+// mapping and the same order of additions as the epilogue of gemm_fused_kernel.  (S: number of diagonals.)
 template <int S, int WVM, int WVN, int WMF, int WNF>
 __global__ __launch_bounds__(64 * WVM * WVN) void finish_blocked_kernel(const long long *__restrict__ totals,
                                                                         const int32_t *__restrict__ eA,
@@ -446,19 +449,21 @@ void fused_tile(int &tm, int &tn)
     tn = 32 * FusedCfg<S>::WVN * FusedCfg<S>::WNF;
 }
 
-// sm: slices of the short operand (UNEQ = 1: A, 2: B); UNEQ = 0: sm = S
-template <int S, int MODE, int UNEQ>
+// sm: slices of the short operand (PSET = 1: A, 2: B); PSET = 0, 3: sm = S.  The work-group shape is the one
+// tabulated for the number of accumulator sets NA.
+template <int S, int MODE, int PSET>
 hipError_t launch_fused_s(int m, int n, int kp, const int8_t *pA, const int8_t *pB, const int32_t *eA,
                           const int32_t *eB, double *C, int ldc, int32_t *dump, long long *totals, int Q, int sm,
                           hipStream_t st)
 {
-    using Cfg = FusedCfg<S>;
+    constexpr int NA = PSET == 3 ? 2 * S - 1 : S;
+    using Cfg = FusedCfg<NA>;
     constexpr int TM = 32 * Cfg::WVM * Cfg::WMF, TN = 32 * Cfg::WVN * Cfg::WNF;
     constexpr int STAGE = Cfg::FR * Cfg::KB32 * S * kFragBytes;
-    constexpr int NSTAGE = UNEQ ? 2 : Cfg::NSTAGE;
+    constexpr int NSTAGE = PSET ? 2 : Cfg::NSTAGE;
     static_assert(NSTAGE * STAGE <= kLdsBytes, "LDS ring too large");
     static_assert(kPad % TM == 0 && kPad % TN == 0 && (kPad / kFrag) % Cfg::KB32 == 0, "tiles must divide the padding");
-    auto kern = gemm_fused_kernel<S, Cfg::WVM, Cfg::WVN, Cfg::WMF, Cfg::WNF, Cfg::KB32, NSTAGE, MODE, UNEQ>;
+    auto kern = gemm_fused_kernel<S, Cfg::WVM, Cfg::WVN, Cfg::WMF, Cfg::WNF, Cfg::KB32, NSTAGE, MODE, PSET>;
     static bool configured = false;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -478,28 +483,42 @@ hipError_t launch_fused_s(int m, int n, int kp, const int8_t *pA, const int8_t *
     const int nst = kp / kFrag / Cfg::KB32;
     const int nblocks = (nst + max_stages - 1) / max_stages;
     const int stages_per_block = (nst + nblocks - 1) / nblocks;
-    const size_t nslots = (size_t)tiles_m * tiles_n * S * TM * TN;
+    const size_t nslots = (size_t)tiles_m * tiles_n * NA * TM * TN;
     zero_i64_kernel<<<2048, 256, 0, st>>>(totals, nslots);
     dim3 grid(tiles_m * tiles_n, nblocks);
     kern<<<grid, 64 * Cfg::WVM * Cfg::WVN, NSTAGE * STAGE, st>>>(pA, pB, eA, eB, C, ldc, m, n, kp / kFrag, tiles_m,
                                                                   tiles_n, nullptr, totals, stages_per_block, Q, sm);
-    finish_blocked_kernel<S, Cfg::WVM, Cfg::WVN, Cfg::WMF, Cfg::WNF>
+    finish_blocked_kernel<NA, Cfg::WVM, Cfg::WVN, Cfg::WMF, Cfg::WNF>
         <<<tiles_m * tiles_n, 64 * Cfg::WVM * Cfg::WVN, 0, st>>>(totals, eA, eB, C, ldc, m, n, tiles_n, Q);
     return hipGetLastError();
 }
 
-template <int MODE, int UNEQ>
+template <int MODE, int PSET>
 hipError_t dispatch_fused(int s, int m, int n, int kp, const int8_t *pA, const int8_t *pB, const int32_t *eA,
                           const int32_t *eB, double *C, int ldc, int32_t *dump, long long *totals, int Q, int sm,
                           hipStream_t st)
 {
     switch (s) {
 #define OZ_CASE(S_) \
-    case S_: return launch_fused_s<S_, MODE, UNEQ>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, Q, sm, st);
+    case S_: return launch_fused_s<S_, MODE, PSET>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, Q, sm, st);
         OZ_CASE(2) OZ_CASE(3) OZ_CASE(4) OZ_CASE(5) OZ_CASE(6) OZ_CASE(7) OZ_CASE(8) OZ_CASE(9) OZ_CASE(10) OZ_CASE(11) OZ_CASE(12) OZ_CASE(13) OZ_CASE(14) OZ_CASE(15) OZ_CASE(16) OZ_CASE(17) OZ_CASE(18)
 #undef OZ_CASE
         case 1:
-            if (UNEQ == 0) return launch_fused_s<1, MODE, 0>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, Q, sm, st);
+            if (PSET == 0) return launch_fused_s<1, MODE, 0>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, Q, sm, st);
+    }
+    return hipErrorInvalidValue;
+}
+
+// all S * S products, equal counts: 2 S - 1 <= kFusedMaxS accumulator sets
+template <int MODE>
+hipError_t dispatch_fused_all(int s, int m, int n, int kp, const int8_t *pA, const int8_t *pB, const int32_t *eA,
+                              const int32_t *eB, double *C, int ldc, long long *totals, int Q, hipStream_t st)
+{
+    switch (s) {
+#define OZ_CASE(S_) \
+    case S_: return launch_fused_s<S_, MODE, 3>(m, n, kp, pA, pB, eA, eB, C, ldc, nullptr, totals, Q, S_, st);
+        OZ_CASE(2) OZ_CASE(3) OZ_CASE(4) OZ_CASE(5) OZ_CASE(6) OZ_CASE(7) OZ_CASE(8) OZ_CASE(9)
+#undef OZ_CASE
     }
     return hipErrorInvalidValue;
 }
@@ -510,7 +529,9 @@ int fused_max_slices() { return kFusedMaxS; }
 
 bool fused_handles(int sA, int sB, bool all_products)
 {
-    return !all_products && sA >= 1 && sB >= 1 && (sA > sB ? sA : sB) <= kFusedMaxS;
+    if (sA < 1 || sB < 1) return false;
+    if (all_products) return sA == sB && 2 * sA - 1 <= kFusedMaxS;
+    return (sA > sB ? sA : sB) <= kFusedMaxS;
 }
 
 bool fused_single_block(int sA, int sB, int k)
@@ -520,12 +541,13 @@ bool fused_single_block(int sA, int sB, int k)
     return fused_handles(sA, sB, false) && (long long)sm * (long long)(k > 0 ? k : 1) <= kMaxInt32K;
 }
 
-size_t fused_totals_bytes(int sA, int sB, int m, int n, int k)
+size_t fused_totals_bytes(int sA, int sB, bool all_products, int m, int n, int k)
 {
-    if (!fused_handles(sA, sB, false) || fused_single_block(sA, sB, k) || m <= 0 || n <= 0) return 0;
-    const int s = sA > sB ? sA : sB;
+    if (!fused_handles(sA, sB, all_products) || fused_single_block(sA, sB, k) || m <= 0 || n <= 0) return 0;
+    const bool all = all_products && sA > 1;
+    const int s = all ? 2 * sA - 1 : (sA > sB ? sA : sB);        // diagonals; the tile shape is tabulated by them
     int tm = 128, tn = 128;
-    if (sA == sB && fused16_preferred(s)) fused16_tile(s, tm, tn);
+    if (sA == sB && !all && fused16_preferred(s)) fused16_tile(s, tm, tn);
     else switch (s) {
 #define OZ_CASE(S_) case S_: fused_tile<S_>(tm, tn); break;
         OZ_CASE(1) OZ_CASE(2) OZ_CASE(3) OZ_CASE(4) OZ_CASE(5) OZ_CASE(6) OZ_CASE(7) OZ_CASE(8) OZ_CASE(9) OZ_CASE(10) OZ_CASE(11) OZ_CASE(12) OZ_CASE(13) OZ_CASE(14) OZ_CASE(15) OZ_CASE(16) OZ_CASE(17) OZ_CASE(18)
@@ -535,11 +557,17 @@ size_t fused_totals_bytes(int sA, int sB, int m, int n, int k)
     return tiles * (size_t)s * tm * tn * sizeof(long long);
 }
 
-hipError_t launch_gemm_fused(int m, int n, int kp, int sA, int sB, const int8_t *pA, const int8_t *pB,
-                             const int32_t *eA, const int32_t *eB, double *C, int ldc, int32_t *dump,
-                             long long *totals, int Q, hipStream_t st)
+hipError_t launch_gemm_fused(int m, int n, int kp, int sA, int sB, bool all_products, const int8_t *pA,
+                             const int8_t *pB, const int32_t *eA, const int32_t *eB, double *C, int ldc,
+                             int32_t *dump, long long *totals, int Q, hipStream_t st)
 {
     if (m <= 0 || n <= 0) return hipSuccess;
+    if (!fused_handles(sA, sB, all_products)) return hipErrorInvalidValue;
+    if (all_products && sA > 1) {
+        if (dump) return hipErrorInvalidValue;
+        if (totals) return dispatch_fused_all<kBlocked>(sA, m, n, kp, pA, pB, eA, eB, C, ldc, totals, Q, st);
+        return dispatch_fused_all<kPlain>(sA, m, n, kp, pA, pB, eA, eB, C, ldc, nullptr, Q, st);
+    }
     if (sA == sB) {
         const int s = sA;
         // the 16x16x64 kernel where it is the faster one

@@ -20,7 +20,7 @@ constexpr long long kMaxInt32K = 2147483647LL / (127LL * 127LL);   // 133144
 inline int round_up(int x, int q) { return (x + q - 1) / q * q; }
 
 bool fused_handles(int sA, int sB, bool all_products);
-size_t fused_totals_bytes(int sA, int sB, int m, int n, int k);
+size_t fused_totals_bytes(int sA, int sB, bool all_products, int m, int n, int k);
 size_t banded_totals_bytes(int sA, int sB, int k);
 int fused_max_slices();
 
@@ -53,7 +53,7 @@ inline Workspace carve(int m, int n, int k, int sA, int sB, bool all_products = 
     w.off_expB = take(4 * (size_t)w.np);
     w.off_planesA = take((size_t)sA * w.mp * w.kp);
     w.off_planesB = take((size_t)sB * w.np * w.kp);
-    w.off_totals = take(fused_handles(sA, sB, all_products) ? fused_totals_bytes(sA, sB, m, n, k)
+    w.off_totals = take(fused_handles(sA, sB, all_products) ? fused_totals_bytes(sA, sB, all_products, m, n, k)
                                                             : banded_totals_bytes(sA, sB, k));
     w.total = off;
     return w;
@@ -82,16 +82,17 @@ hipError_t launch_split(char side, int rows, int cols, const double *X, int ldx,
 // ---- launchers implemented in gemm.hip ---------------------------------------------------
 // largest s the fused (all diagonals in registers) kernel handles
 int fused_max_slices();
-// true when the fused kernel computes this product set (reduced set, both counts <= fused_max_slices())
+// true when the fused kernel computes this product set: the reduced set with both counts <= fused_max_slices(),
+// or all products of equal counts with 2 s - 1 <= fused_max_slices() diagonals
 bool fused_handles(int sA, int sB, bool all_products);
 // true when it can keep the whole contraction in int32 (min(sA, sB) * k * 127^2 < 2^31)
 bool fused_single_block(int sA, int sB, int k);
 // bytes of int64 per-tile totals the fused kernel needs when it has to cut k into blocks (else 0)
-size_t fused_totals_bytes(int sA, int sB, int m, int n, int k);
+size_t fused_totals_bytes(int sA, int sB, bool all_products, int m, int n, int k);
 // dump != null: write int32 diagonal sums (single block only); totals != null: k-blocked mode.
 // Q (all GEMM launchers): diagonals per exactly summed level of the binary64 accumulation, 1 <= Q <= 8.
-hipError_t launch_gemm_fused(int m, int n, int kp, int sA, int sB, const int8_t *pA, const int8_t *pB,
-                             const int32_t *eA, const int32_t *eB, double *C, int ldc,
+hipError_t launch_gemm_fused(int m, int n, int kp, int sA, int sB, bool all_products, const int8_t *pA,
+                             const int8_t *pB, const int32_t *eA, const int32_t *eB, double *C, int ldc,
                              int32_t *dump, long long *totals, int Q, hipStream_t st);
 // the same fused computation on v_mfma_i32_16x16x64_i8, for the slice counts where it is faster (gemm_fused16.hip)
 bool fused16_preferred(int s);

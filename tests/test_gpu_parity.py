@@ -317,7 +317,8 @@ def test_dgemm2_matches_oracle(kind, m, n, k, sA, sB):
     assert_c_matches(host(C), oracle.dgemm2(A, B, sA, sB), f"{kind} {m}x{n}x{k} sA={sA} sB={sB}")
 
 
-@pytest.mark.parametrize("sA,sB", [(1, 1), (2, 5), (5, 2), (7, 7), (12, 12), (9, 17), (20, 20)])
+@pytest.mark.parametrize("sA,sB", [(1, 1), (2, 5), (5, 2), (2, 2), (3, 3), (4, 4), (5, 5), (6, 6), (7, 7), (8, 8), (9, 9),
+                                   (10, 10), (12, 12), (9, 17), (20, 20)])
 def test_dgemm2_all_products_matches_oracle(sA, sB):
     A, B = workloads.lognormal(130, 70, 200, 2.0, 52)
     C = ozimmu.dgemm2(dev(A), dev(B), sA, sB, all_products=True)
@@ -461,6 +462,17 @@ def test_different_slice_counts_in_k_blocked_mode(sA, sB):
     print(f"k-blocked sA={sA} sB={sB} k={k}", flush=True)
     A, B = workloads.lognormal(m, n, k, 2.0, 60 + sA)
     assert_c_matches(host(ozimmu.dgemm2(dev(A), dev(B), sA, sB)), oracle.dgemm2(A, B, sA, sB), "k-blocked unequal")
+
+
+@pytest.mark.parametrize("s", [3, 6, 7, 9])
+def test_all_products_in_k_blocked_mode(s):
+    # the fused kernel's all-products set (2 s - 1 diagonals) in split-k mode
+    m, n = 130, 70
+    k = min(2 * (133144 // s) + 200, 100000)
+    print(f"k-blocked all products s={s} k={k}", flush=True)
+    A, B = workloads.lognormal(m, n, k, 2.0, 70 + s)
+    got = host(ozimmu.dgemm3(dev(A), dev(B), s, s, True, ozimmu.SPLIT_TRUNCATE, 2))
+    assert_c_matches(got, oracle.dgemm3(A, B, s, s, full=True, Q=2), "k-blocked all products")
 
 
 def test_dgemm3_defaults_equal_dgemm2_and_bad_level_size_is_refused():
