@@ -55,7 +55,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (the method needs no exchange when C is tiled "
-              "over GPUs; see DESIGN.md); --gpus must be 1", file=sys.stderr)
+              "over GPUs: every row of A and column of B carries its own scale); --gpus must be 1", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
