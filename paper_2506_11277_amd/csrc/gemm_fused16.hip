@@ -1,4 +1,4 @@
-// Fused slice-product kernel built on v_mfma_i32_16x16x64_i8 (written for s <= 9, used for s = 4 and 8).
+// Fused slice-product kernel built on v_mfma_i32_16x16x64_i8 (written for s <= 9, used for s = 4, 7 and 8).
 //
 // Same computation as gemm_fused_kernel in gemm.hip (all s(s+1)/2 products of Algorithm 1, Sect. 3,
 // per-diagonal int32 sums, binary64 accumulation by ascending diagonal), same plane layout, same
@@ -29,7 +29,9 @@ struct Cfg16 {
     static constexpr int WVM = WIDE ? 2 : 4, WVN = WIDE ? 4 : 2, WMF = WIDE ? 2 : 1, WNF = 1;
     static constexpr int FA = WVM * WMF, FB = WVN * WNF;          // 32-row fragment rows of the tile
     // A slices [0, L0) are double-buffered with B; A slices [L0, S) single-buffered (L0 == S: no split)
-    static constexpr int L0 = S <= 6 ? S : 20 - 2 * S;
+    // (from a sweep at 8192^3: s = 7 runs 2470 / 2710 / 2880 / 2820 / 2710 TOP/s for L0 = 1 / 2 / 3 / 4 / 6, s = 8
+    // 2670 / 2910 / 3110 / 3090 for L0 = 1 / 2 / 3 / 4)
+    static constexpr int L0 = S <= 6 ? S : S == 7 ? 3 : S == 8 ? 4 : 2;
     static constexpr int P1 = (FA * L0 + FB * S) * 2 * kFragBytes;    // double-buffered part of a 64-k stage
     static constexpr int P2 = FA * (S - L0) * 2 * kFragBytes;         // single-buffered part
     static constexpr int NBUF = (L0 == S && 3 * P1 <= kLdsBytes && S <= 3) ? 3 : 2;
@@ -306,7 +308,7 @@ hipError_t dispatch16(int s, int m, int n, int kp, const int8_t *pA, const int8_
     switch (s) {
 #define OZ_CASE(S_) \
     case S_: return launch16_s<S_, MODE>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, Q, st);
-        OZ_CASE(4) OZ_CASE(8)
+        OZ_CASE(4) OZ_CASE(7) OZ_CASE(8)
 #undef OZ_CASE
     }
     return hipErrorInvalidValue;
@@ -314,11 +316,11 @@ hipError_t dispatch16(int s, int m, int n, int kp, const int8_t *pA, const int8_
 
 }  // namespace
 
-// Slice counts for which this kernel is the faster one at 8192^3 (s = 4: +10 %, s = 8: +12 %).  At s = 9 it
-// gains 4 % but sits at the 256-register limit (any change tips it into spilling), at 7 the two are equal
-// within noise, and the 32x32x32 kernel wins at 2, 3, 5, 6, where this one cannot use its wider tile or
-// issues too many LDS reads per matrix instruction.  Only the preferred ones are instantiated.
-bool fused16_preferred(int s) { return s == 4 || s == 8; }
+// Slice counts for which this kernel is the faster one at 8192^3 (s = 4: +10 %, s = 7: +6.5 %, s = 8: +12 %).
+// At s = 9 it gains 4 % but sits at the 256-register limit (any change tips it into spilling), and the
+// 32x32x32 kernel wins at 2, 3, 5, 6 (with or without a split stage), where this one cannot use its wider
+// tile or issues too many LDS reads per matrix instruction.  Only the preferred ones are instantiated.
+bool fused16_preferred(int s) { return s == 4 || s == 7 || s == 8; }
 
 void fused16_tile(int s, int &tm, int &tn)
 {

@@ -225,9 +225,9 @@ def test_k_blocked_accumulation_beyond_the_int32_range():
     assert_c_matches(host(ozimmu.dgemm(dev(A), dev(B), 7)), oracle.dgemm(A, B, 7), "k-blocked lognormal")
 
 
-@pytest.mark.parametrize("s", [4, 8, 9, 12, 13, 16, 17, 18])
+@pytest.mark.parametrize("s", [4, 7, 8, 9, 12, 13, 16, 17, 18])
 def test_k_blocked_on_every_fused_kernel(s):
-    # the fused kernels (16x16x64 for s = 4, 8; 32x32x32 otherwise, with four 512-register wavefronts beyond
+    # the fused kernels (16x16x64 for s = 4, 7, 8; 32x32x32 otherwise, with four 512-register wavefronts beyond
     # s = 12) in split-k mode, several tiles and k-blocks
     m, n = 130, 70
     k = 3 * (133144 // s) + 200
@@ -410,9 +410,11 @@ def test_split_nearest_bit_exact_in_both_layouts(kind, m, n, k, s):
 
 VARIANT_CASES = [
     # sA, sB, all_products, nearest, Q        kernel that runs
-    (7, 7, False, True, 1),                 # fused 32x32x32
-    (8, 8, False, True, 1),                 # fused 16x16x64
+    (7, 7, False, True, 1),                 # fused 16x16x64, split stage
+    (8, 8, False, True, 1),
     (7, 7, False, False, 3),
+    (6, 6, False, True, 3),                 # fused 32x32x32
+    (9, 9, False, False, 2),
     (4, 4, False, False, 2),                # fused 16x16x64, wide tile
     (8, 8, False, False, 3),
     (12, 12, False, True, 4),
