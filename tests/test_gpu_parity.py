@@ -501,3 +501,39 @@ def test_largest_admitted_level_is_exact_on_the_worst_case_input():
         Q = ozimmu.max_level_diagonals(k, s, s)
         want = oracle.dgemm3(A, B, s, s, Q=Q)
         assert_c_matches(host(ozimmu.dgemm3(dev(A), dev(B), s, s, level_diagonals=Q)), want, f"worst case k={k}")
+
+
+def test_variants_on_degenerate_and_strided_inputs():
+    # empty dimensions, k = 0, a single entry, and leading dimensions larger than the row count, through dgemm2 / dgemm3
+    for sA, sB, allp, nearest, Q in [(3, 9, False, False, 1), (14, 14, False, True, 2), (5, 5, True, False, 2), (20, 6, False, True, 3)]:
+        sp = ozimmu.SPLIT_NEAREST if nearest else ozimmu.SPLIT_TRUNCATE
+        A, B = workloads.uniform(8, 6, 0, 1)
+        C = ozimmu.dgemm3(dev(A), dev(B), sA, sB, allp, sp, Q)
+        assert tuple(C.shape) == (8, 6) and bool((C == 0).all())
+        A, B = workloads.uniform(0, 6, 5, 1)
+        assert tuple(ozimmu.dgemm3(dev(A), dev(B), sA, sB, allp, sp, Q).shape) == (0, 6)
+        A, B = workloads.uniform(4, 0, 5, 1)
+        assert tuple(ozimmu.dgemm3(dev(A), dev(B), sA, sB, allp, sp, Q).shape) == (4, 0)
+        A, B = workloads.lognormal(1, 1, 1, 1.0, 2)
+        assert_c_matches(host(ozimmu.dgemm3(dev(A), dev(B), sA, sB, allp, sp, Q)),
+                         oracle.dgemm3(A, B, sA, sB, full=allp, nearest=nearest, Q=Q), "1x1x1")
+        m, n, k = 70, 50, 90
+        A, B = workloads.lognormal(m, n, k, 1.0, 4)
+        bigA = ozimmu.colmajor_empty(100, k); bigA.fill_(1e300); bigA[:m, :] = torch.as_tensor(A)
+        bigB = ozimmu.colmajor_empty(130, n); bigB.fill_(1e300); bigB[:k, :] = torch.as_tensor(B)
+        bigC = ozimmu.colmajor_empty(77, n); bigC.fill_(-1.0)
+        ozimmu.dgemm3(bigA[:m, :], bigB[:k, :], sA, sB, allp, sp, Q, C=bigC[:m, :])
+        assert_c_matches(host(bigC[:m, :]), oracle.dgemm3(A, B, sA, sB, full=allp, nearest=nearest, Q=Q), "ld")
+        assert bool((bigC[m:, :] == -1.0).all())
+
+
+def test_nonfinite_input_is_reported_in_every_variant():
+    A, B = workloads.uniform(40, 30, 50, 2)
+    A[3, 4] = np.inf
+    for sA, sB, nearest in [(4, 9, False), (15, 15, True), (22, 3, True)]:
+        ws = torch.empty(ozimmu.lib().ozimmu_workspace_bytes2(40, 30, 50, sA, sB, 0), dtype=torch.uint8, device="cuda")
+        ozimmu.dgemm3(dev(A), dev(B), sA, sB, False, ozimmu.SPLIT_NEAREST if nearest else ozimmu.SPLIT_TRUNCATE, 1,
+                      workspace=ws)
+        with pytest.raises(ozimmu.OzimmuError) as ei:
+            ozimmu.check(ws)
+        assert ei.value.code == ozimmu.NONFINITE
