@@ -1,4 +1,4 @@
-// Fused slice-product kernel built on v_mfma_i32_16x16x64_i8 (written for s <= 9, used for s = 4, 7 and 8).
+// Fused slice-product kernel built on v_mfma_i32_16x16x64_i8 (written for s <= 9, used for s = 4, 5, 7 and 8).
 //
 // Same computation as gemm_fused_kernel in gemm.hip (all s(s+1)/2 products of Algorithm 1, Sect. 3,
 // per-diagonal int32 sums, binary64 accumulation by ascending diagonal), same plane layout, same
@@ -24,8 +24,8 @@ namespace {
 template <int S>
 struct Cfg16 {
     // tile 128 x 128 (2 x 4 wavefronts of 64 x 32) while 32 * S accumulator registers are affordable and the
-    // stages fit, else 128 x 64 (4 x 2 wavefronts of 32 x 32)
-    static constexpr bool WIDE = S <= 4;
+    // stages fit (s = 5: two 80 KiB stages, all of LDS), else 128 x 64 (4 x 2 wavefronts of 32 x 32)
+    static constexpr bool WIDE = S <= 5;
     static constexpr int WVM = WIDE ? 2 : 4, WVN = WIDE ? 4 : 2, WMF = WIDE ? 2 : 1, WNF = 1;
     static constexpr int FA = WVM * WMF, FB = WVN * WNF;          // 32-row fragment rows of the tile
     // A slices [0, L0) are double-buffered with B; A slices [L0, S) single-buffered (L0 == S: no split)
@@ -308,7 +308,7 @@ hipError_t dispatch16(int s, int m, int n, int kp, const int8_t *pA, const int8_
     switch (s) {
 #define OZ_CASE(S_) \
     case S_: return launch16_s<S_, MODE>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, Q, st);
-        OZ_CASE(4) OZ_CASE(7) OZ_CASE(8)
+        OZ_CASE(4) OZ_CASE(5) OZ_CASE(7) OZ_CASE(8)
 #undef OZ_CASE
     }
     return hipErrorInvalidValue;
@@ -316,16 +316,16 @@ hipError_t dispatch16(int s, int m, int n, int kp, const int8_t *pA, const int8_
 
 }  // namespace
 
-// Slice counts for which this kernel is the faster one at 8192^3 (s = 4: +10 %, s = 7: +6.5 %, s = 8: +12 %).
-// At s = 9 it gains 4 % but sits at the 256-register limit (any change tips it into spilling), and the
-// 32x32x32 kernel wins at 2, 3, 5, 6 (with or without a split stage), where this one cannot use its wider
-// tile or issues too many LDS reads per matrix instruction.  Only the preferred ones are instantiated.
-bool fused16_preferred(int s) { return s == 4 || s == 7 || s == 8; }
+// Slice counts for which this kernel is the faster one at 8192^3 (s = 4: +10 %, s = 5: +7.5 % with the wide
+// tile, s = 7: +6.5 %, s = 8: +12 %).  At s = 9 it gains 4 % but sits at the 256-register limit (any change
+// tips it into spilling); at s = 6 the wide tile does not fit the registers and the narrow one is no faster;
+// the 32x32x32 kernel wins at 2 and 3.  Only the preferred ones are instantiated.
+bool fused16_preferred(int s) { return s == 4 || s == 5 || s == 7 || s == 8; }
 
 void fused16_tile(int s, int &tm, int &tn)
 {
     tm = 128;
-    tn = s <= 4 ? 128 : 64;
+    tn = s <= 5 ? 128 : 64;
 }
 
 hipError_t launch_gemm_fused16(int m, int n, int kp, int s, const int8_t *pA, const int8_t *pB, const int32_t *eA,
