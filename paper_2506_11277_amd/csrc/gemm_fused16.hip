@@ -1,4 +1,4 @@
-// Fused slice-product kernel built on v_mfma_i32_16x16x64_i8 (written for s <= 9, used for s = 4, 5, 7 and 8).
+// Fused slice-product kernel built on v_mfma_i32_16x16x64_i8 (written for s <= 9, used for s = 4, 5, 7, 8 and 9).
 //
 // Same computation as gemm_fused_kernel in gemm.hip (all s(s+1)/2 products of Algorithm 1, Sect. 3,
 // per-diagonal int32 sums, binary64 accumulation by ascending diagonal), same plane layout, same
@@ -134,9 +134,14 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
         if (ahead) issue_p1(st + NBUF - 1, buf == 0 ? NBUF - 1 : buf - 1);
         const unsigned char *cur = lds + buf * G::P1;
 
-        v4i bf[S][WNF][2];
+        // (s = 9: only the first HP slices of B are held for the whole stage, the others are read when needed;
+        // everything held needs the last of the 256 registers.  Measured 2860 / 2965 / 3040 / 2660 TOP/s for
+        // HP = 4 / 5 / 6 / 7; with 6 the compiler keeps one loop-invariant 16-byte value in scratch, reloaded
+        // once per stage, and is still the fastest)
+        constexpr int HP = S >= 9 ? 6 : S;
+        v4i bf[HP][WNF][2];
 #pragma unroll
-        for (int h = 0; h < S; ++h)
+        for (int h = 0; h < HP; ++h)
 #pragma unroll
             for (int j = 0; j < WNF; ++j)
 #pragma unroll
@@ -163,9 +168,13 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
 #pragma unroll
                         for (int i2 = 0; i2 < 2; ++i2)
 #pragma unroll
-                            for (int j2 = 0; j2 < 2; ++j2)
+                            for (int j2 = 0; j2 < 2; ++j2) {
+                                const v4i bv = h < HP ? bf[h < HP ? h : 0][j][j2]
+                                                      : *(const v4i *)(cur + (U1A + ((wn * WNF + j) * S + h) * 2) * kFragBytes +
+                                                                       lofs + j2 * 256);
                                 acc[l + h][i][j][i2 * 2 + j2] = __builtin_amdgcn_mfma_i32_16x16x64_i8(
-                                    bf[h][j][j2], af[i][i2], acc[l + h][i][j][i2 * 2 + j2], 0, 0, 0);
+                                    bv, af[i][i2], acc[l + h][i][j][i2 * 2 + j2], 0, 0, 0);
+                            }
             if (SPLIT && l == L0) {
                 // every wavefront is done with the single-buffered slices: refill them for the next stage
                 __syncthreads();
@@ -308,7 +317,7 @@ hipError_t dispatch16(int s, int m, int n, int kp, const int8_t *pA, const int8_
     switch (s) {
 #define OZ_CASE(S_) \
     case S_: return launch16_s<S_, MODE>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, Q, st);
-        OZ_CASE(4) OZ_CASE(5) OZ_CASE(7) OZ_CASE(8)
+        OZ_CASE(4) OZ_CASE(5) OZ_CASE(7) OZ_CASE(8) OZ_CASE(9)
 #undef OZ_CASE
     }
     return hipErrorInvalidValue;
@@ -317,10 +326,10 @@ hipError_t dispatch16(int s, int m, int n, int kp, const int8_t *pA, const int8_
 }  // namespace
 
 // Slice counts for which this kernel is the faster one at 8192^3 (s = 4: +10 %, s = 5: +7.5 % with the wide
-// tile, s = 7: +6.5 %, s = 8: +12 %).  At s = 9 it gains 4 % but sits at the 256-register limit (any change
-// tips it into spilling); at s = 6 the wide tile does not fit the registers and the narrow one is no faster;
-// the 32x32x32 kernel wins at 2 and 3.  Only the preferred ones are instantiated.
-bool fused16_preferred(int s) { return s == 4 || s == 5 || s == 7 || s == 8; }
+// tile, s = 7: +6.5 %, s = 8: +12 %, s = 9: +6.7 %).  At s = 6 the wide tile does not fit the registers and the
+// narrow one is no faster; beyond 9 a 64-deep stage of a 128 x 64 tile does not fit LDS; the 32x32x32 kernel
+// wins at 2 and 3.  Only the preferred ones are instantiated.
+bool fused16_preferred(int s) { return s == 4 || s == 5 || (s >= 7 && s <= 9); }
 
 void fused16_tile(int s, int &tm, int &tn)
 {

@@ -227,7 +227,7 @@ def test_k_blocked_accumulation_beyond_the_int32_range():
 
 @pytest.mark.parametrize("s", [4, 5, 7, 8, 9, 12, 13, 16, 17, 18])
 def test_k_blocked_on_every_fused_kernel(s):
-    # the fused kernels (16x16x64 for s = 4, 5, 7, 8; 32x32x32 otherwise, with four 512-register wavefronts beyond
+    # the fused kernels (16x16x64 for s = 4, 5, 7, 8, 9; 32x32x32 otherwise, with four 512-register wavefronts beyond
     # s = 12) in split-k mode, several tiles and k-blocks
     m, n = 130, 70
     k = 3 * (133144 // s) + 200
@@ -414,7 +414,8 @@ VARIANT_CASES = [
     (8, 8, False, True, 1),
     (7, 7, False, False, 3),
     (6, 6, False, True, 3),                 # fused 32x32x32
-    (9, 9, False, False, 2),
+    (9, 9, False, False, 2),                # fused 16x16x64 with part of B read on demand
+    (10, 10, False, True, 2),               # fused 32x32x32
     (4, 4, False, False, 2),                # fused 16x16x64, wide tile
     (8, 8, False, False, 3),
     (12, 12, False, True, 4),
