@@ -90,10 +90,13 @@ __global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t
     const bool extra = wave < UREM;
 
     // copy of stage `st` into ring buffer `buf`: unit u = wave + i*NW  ->  fragment row c = u / (KB32*S)
-    auto issue_stage = [&](int st, int buf) {
+    // part < 0: all units of the stage; else the units i with i % NPART == part (see SPREAD below)
+    constexpr int NPART = S < 4 ? S : 4;
+    auto issue_stage = [&](int st, int buf, int part = -1) {
 #pragma unroll
         for (int i = 0; i < UPW + (UREM ? 1 : 0); ++i) {
             if (i == UPW && !extra) break;
+            if (part >= 0 && i % NPART != part) continue;
             const int u = wave + i * NW;
             const int c = u / (KB32 * S), o = u % (KB32 * S);
             const int8_t *src;
@@ -141,7 +144,15 @@ __global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t
     int buf = 0;
     for (int st = st0; st < nst; ++st) {
         const bool ahead = st + NSTAGE - 1 < nst;
-        if (ahead) issue_stage(st + NSTAGE - 1, buf == 0 ? NSTAGE - 1 : buf - 1);
+        // SPREAD: the copies of the next stage are not issued all at once at the top of the stage but in NPART
+        // portions, one before each of the first NPART slices of the outer loop.  Measured at 8192^3: +7.5 % for
+        // the four-wavefront shape (s = 13: 2855 -> 3075, s = 16: 3087 -> 3316 TOP/s), +2 % at s = 12, nothing at
+        // 10 and 11, -3.5 % at s = 6: used from 12 accumulator sets on.
+        // (Not for different slice counts: with few slices in the outer loop the late portions find no products
+        // left to hide behind, and deciding that at run time costs more than spreading gains.)
+        constexpr bool SPREAD = NSTAGE == 2 && KB32 == 1 && NA >= 12 && (PSET == 0 || PSET == 3);
+        const int nbuf = buf == 0 ? NSTAGE - 1 : buf - 1;
+        if (ahead && !SPREAD) issue_stage(st + NSTAGE - 1, nbuf);
         const unsigned char *cur = lds + buf * STAGE;
 #pragma unroll
         for (int kbl = 0; kbl < KB32; ++kbl) {
@@ -157,6 +168,7 @@ __global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t
                         bf[h][j] = *(const v4i *)(cur + (FA + wn * WNF + j) * CHUNK + (kbl * S + h) * kFragBytes + lane * 16);
 #pragma unroll
                 for (int l = 0; l < S; ++l) {
+                    if (SPREAD && ahead && l < NPART) issue_stage(st + NSTAGE - 1, nbuf, l);
                     if (PSET == 1 && l >= sm) continue;     // (not `break`: the loop must stay fully unrollable)
                     v4i af[WMF];
 #pragma unroll
