@@ -85,8 +85,10 @@ __global__ __launch_bounds__(64 * kWVM * kWVN) void gemm_banded_kernel(
         const int mi = (tm * kWVM + wm) * 32 + (lane & 31);
         const int n0 = (tn * kWVN + wn) * 32;
 
-        for (int d0 = 2; d0 <= dmax; d0 += kG) {
-            const int dlast = d0 + kG - 1 < dmax ? d0 + kG - 1 : dmax;
+        // The short group comes FIRST: the early diagonals hold few products, the late ones many, and a late
+        // group of only a few diagonals would sweep k once per chunk for little work.
+        const int first = (dmax - 1) % kG ? (dmax - 1) % kG : kG;
+        for (int d0 = 2, dlast = 1 + first; d0 <= dmax; d0 = dlast + 1, dlast += kG) {
             v16i acc[kG];
 #pragma unroll
             for (int a = 0; a < kG; ++a)
