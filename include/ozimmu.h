@@ -58,7 +58,7 @@ const char *ozimmu_status_string(int status);
  * Bytes of device workspace ozimmu_dgemm / ozimmu_estimate_slices need for this problem:
  * scale exponents, per-row/column reductions, the int8 slice planes of A and B, and -- only when
  * min(sA, sB) * k > 133144, i.e. when a diagonal's int32 sum could overflow and k has to be cut into
- * blocks -- int64 totals of the diagonals (8 bytes per diagonal and entry of C for up to 18 slices, a
+ * blocks -- int64 totals of the diagonals (8 bytes per diagonal and entry of C for up to 20 slices, a
  * fixed 128 MiB beyond).
  * Returns 0 for invalid arguments.  Alignment required of the workspace pointer: 256 bytes.
  */

@@ -156,9 +156,9 @@ __global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t
         const unsigned char *cur = lds + buf * STAGE;
 #pragma unroll
         for (int kbl = 0; kbl < KB32; ++kbl) {
-            // beyond 16 slices the slices >= HP of the preloaded operand are read when needed instead of being
-            // held for the whole stage
-            constexpr int HP = S > 16 ? 8 : S;
+            // beyond 16 slices only the first HP slices of the preloaded operand are held for the whole stage,
+            // the others are read when needed
+            constexpr int HP = S > 18 ? 4 : S > 16 ? 8 : S;
             if (PSET != 2) {
                 v4i bf[HP][WNF];
 #pragma unroll
@@ -439,7 +439,7 @@ __global__ __launch_bounds__(kThreads) void gemm_generic_kernel(const int8_t *__
 //   else: 8 wavefronts as 4 (m) x 2 (n), each 32 x 32 outputs: tile 128 x 64
 //   BIG (s > 12): 4 wavefronts as 2 x 2, ONE per SIMD, each 32 x 32 outputs: tile 64 x 64.  A lone wavefront
 //         may use all 512 registers of its SIMD lane (256 of them accumulation registers), which holds
-//         16 * s accumulators up to s = 18; the products per staged byte grow with s, so the small tile
+//         16 * s accumulators up to s = 20; the products per staged byte grow with s, so the small tile
 //         still feeds the matrix cores (3.0 POP/s at s = 16, where the band kernel reaches 1.8).
 template <int S>
 struct FusedCfg {
@@ -451,7 +451,9 @@ struct FusedCfg {
     static constexpr int NSTAGE = S <= 3 ? 3 : 2;
 };
 
-constexpr int kFusedMaxS = 18;   // 16 accumulator registers per diagonal: 12 fit 256 registers, 18 fit 512 (BIG)
+constexpr int kFusedMaxUneq = 18; // most accumulator sets for different slice counts and for all products
+constexpr int kFusedMaxS = 20;   // 16 accumulator registers per diagonal: 12 fit 256 registers, 20 fit 512 (BIG);
+                                 // two 32-deep stages of a 64 x 64 tile with 20 slices fill the 160 KiB of LDS
 
 // Tile geometry of the fused kernel for a slice count (used for the size of the k-block totals).
 template <int S>
@@ -515,8 +517,17 @@ hipError_t dispatch_fused(int s, int m, int n, int kp, const int8_t *pA, const i
     case S_: return launch_fused_s<S_, MODE, PSET>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, Q, sm, st);
         OZ_CASE(2) OZ_CASE(3) OZ_CASE(4) OZ_CASE(5) OZ_CASE(6) OZ_CASE(7) OZ_CASE(8) OZ_CASE(9) OZ_CASE(10) OZ_CASE(11) OZ_CASE(12) OZ_CASE(13) OZ_CASE(14) OZ_CASE(15) OZ_CASE(16) OZ_CASE(17) OZ_CASE(18)
 #undef OZ_CASE
+        // equal counts only (a single slice: nothing to distinguish; 19 and 20: the variants for different counts
+        // would spill inside the pair loop)
         case 1:
             if (PSET == 0) return launch_fused_s<1, MODE, 0>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, Q, sm, st);
+            break;
+        case 19:
+            if (PSET == 0) return launch_fused_s<19, MODE, 0>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, Q, sm, st);
+            break;
+        case 20:
+            if (PSET == 0) return launch_fused_s<20, MODE, 0>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, Q, sm, st);
+            break;
     }
     return hipErrorInvalidValue;
 }
@@ -542,8 +553,8 @@ int fused_max_slices() { return kFusedMaxS; }
 bool fused_handles(int sA, int sB, bool all_products)
 {
     if (sA < 1 || sB < 1) return false;
-    if (all_products) return sA == sB && 2 * sA - 1 <= kFusedMaxS;
-    return (sA > sB ? sA : sB) <= kFusedMaxS;
+    if (all_products) return sA == sB && 2 * sA - 1 <= kFusedMaxUneq;
+    return sA == sB ? sA <= kFusedMaxS : (sA > sB ? sA : sB) <= kFusedMaxUneq;
 }
 
 bool fused_single_block(int sA, int sB, int k)
@@ -562,7 +573,7 @@ size_t fused_totals_bytes(int sA, int sB, bool all_products, int m, int n, int k
     if (sA == sB && !all && fused16_preferred(s)) fused16_tile(s, tm, tn);
     else switch (s) {
 #define OZ_CASE(S_) case S_: fused_tile<S_>(tm, tn); break;
-        OZ_CASE(1) OZ_CASE(2) OZ_CASE(3) OZ_CASE(4) OZ_CASE(5) OZ_CASE(6) OZ_CASE(7) OZ_CASE(8) OZ_CASE(9) OZ_CASE(10) OZ_CASE(11) OZ_CASE(12) OZ_CASE(13) OZ_CASE(14) OZ_CASE(15) OZ_CASE(16) OZ_CASE(17) OZ_CASE(18)
+        OZ_CASE(1) OZ_CASE(2) OZ_CASE(3) OZ_CASE(4) OZ_CASE(5) OZ_CASE(6) OZ_CASE(7) OZ_CASE(8) OZ_CASE(9) OZ_CASE(10) OZ_CASE(11) OZ_CASE(12) OZ_CASE(13) OZ_CASE(14) OZ_CASE(15) OZ_CASE(16) OZ_CASE(17) OZ_CASE(18) OZ_CASE(19) OZ_CASE(20)
 #undef OZ_CASE
     }
     const size_t tiles = (size_t)((m + tm - 1) / tm) * ((n + tn - 1) / tn);

@@ -82,8 +82,8 @@ hipError_t launch_split(char side, int rows, int cols, const double *X, int ldx,
 // ---- launchers implemented in gemm.hip ---------------------------------------------------
 // largest s the fused (all diagonals in registers) kernel handles
 int fused_max_slices();
-// true when the fused kernel computes this product set: the reduced set with both counts <= fused_max_slices(),
-// or all products of equal counts with 2 s - 1 <= fused_max_slices() diagonals
+// true when the fused kernel computes this product set: the reduced set with equal counts <= fused_max_slices()
+// (20) or different counts <= 18, or all products of equal counts with 2 s - 1 <= 18 diagonals
 bool fused_handles(int sA, int sB, bool all_products);
 // true when it can keep the whole contraction in int32 (min(sA, sB) * k * 127^2 < 2^31)
 bool fused_single_block(int sA, int sB, int k);

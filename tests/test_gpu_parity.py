@@ -143,7 +143,8 @@ def test_int32_slice_products_bit_exact(m, n, k):
 
 @pytest.mark.parametrize("m,n,k,s", [(33, 70, 17, 3), (128, 128, 128, 3), (100, 90, 70, 7), (257, 130, 300, 9),
                                      (130, 257, 513, 1), (64, 64, 2048, 6), (100, 300, 70, 12), (129, 129, 200, 4), (200, 100, 64, 2),
-                                     (100, 90, 70, 13), (130, 70, 300, 16), (65, 129, 200, 17), (257, 130, 100, 18)])
+                                     (100, 90, 70, 13), (130, 70, 300, 16), (65, 129, 200, 17), (257, 130, 100, 18),
+                                     (70, 130, 150, 19), (130, 130, 96, 20)])
 def test_int32_diagonal_sums_of_fused_kernel_bit_exact(m, n, k, s):
     A, B = workloads.uniform(m, n, k, 22)
     pa, _ = oracle.split("A", A, s)
@@ -176,7 +177,7 @@ def test_extreme_slices_do_not_overflow_int32_in_fused_kernel():
 
 @pytest.mark.parametrize("kind", ["uniform", "lognormal", "pow2", "special"])
 @pytest.mark.parametrize("m,n,k", SHAPES)
-@pytest.mark.parametrize("s", [1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16, 17, 18, 19, 32])
+@pytest.mark.parametrize("s", [1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16, 17, 18, 19, 20, 21, 32])
 def test_dgemm_matches_oracle(kind, m, n, k, s):
     A, B = inputs(kind, m, n, k, 31)
     ws = ozimmu.alloc_workspace(m, n, k, s)
@@ -225,7 +226,7 @@ def test_k_blocked_accumulation_beyond_the_int32_range():
     assert_c_matches(host(ozimmu.dgemm(dev(A), dev(B), 7)), oracle.dgemm(A, B, 7), "k-blocked lognormal")
 
 
-@pytest.mark.parametrize("s", [4, 5, 7, 8, 9, 12, 13, 16, 17, 18])
+@pytest.mark.parametrize("s", [4, 5, 7, 8, 9, 12, 13, 16, 17, 18, 19, 20])
 def test_k_blocked_on_every_fused_kernel(s):
     # the fused kernels (16x16x64 for s = 4, 5, 7, 8, 9; 32x32x32 otherwise, with four 512-register wavefronts beyond
     # s = 12) in split-k mode, several tiles and k-blocks
