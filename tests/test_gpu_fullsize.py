@@ -109,3 +109,13 @@ def test_full_size_variants_8192():
                                      (5, 10, False, False, 3), (13, 13, False, True, 3), (3, 4, True, False, 2)]:
         print(f"variant sA={sA} sB={sB} all={allp} nearest={nearest} Q={Q}", flush=True)
         check_sampled_variant(dA, dB, sA, sB, allp, nearest, Q, f"8192 ({sA},{sB}) all={allp} nearest={nearest} Q={Q}")
+
+
+def test_large_ragged_shapes():
+    # no dimension a multiple of any tile or stage size; several kernels of the family
+    m, n, k = 5003, 7001, 3001
+    dA, dB = workloads.lognormal_device(m, n, k, 1.0, 2024)
+    for sA, sB, allp, nearest, Q in [(7, 7, False, False, 1), (14, 14, False, False, 3), (5, 10, False, True, 2),
+                                     (6, 6, True, False, 1), (22, 22, False, False, 1)]:
+        print(f"ragged sA={sA} sB={sB} all={allp} nearest={nearest} Q={Q}", flush=True)
+        check_sampled_variant(dA, dB, sA, sB, allp, nearest, Q, f"ragged ({sA},{sB}) all={allp}")
