@@ -141,7 +141,7 @@ def main():
         src = torch.empty(1 << 27, dtype=torch.float64, device="cuda").fill_(1.0)
         dst = torch.empty_like(src)
         torch.cuda.synchronize()
-        dst.copy_(src)
+        ozimmu.calibration_copy(dst, src)      # calibration_copy_kernel: exactly 1 GiB read, 1 GiB written
         torch.cuda.synchronize()
         del src, dst
 

@@ -213,6 +213,14 @@ int ozimmu_profile_stop(int *calls, float *phase_ms);
 int ozimmu_measure_int8_ceiling(int random_operands, int *sink, float *tops, void *stream);
 
 /*
+ * Benchmark aid: a plain device-to-device copy kernel (`calibration_copy_kernel`) of `bytes` bytes (a multiple
+ * of 16, both pointers 16-byte aligned), asynchronous on `stream`.  Its HBM traffic is known exactly -- `bytes`
+ * read and `bytes` written -- so the FETCH_SIZE / WRITE_SIZE readings a profiler reports for it give the
+ * factors by which the same counters have to be scaled for the other kernels.
+ */
+int ozimmu_calibration_copy(void *dst, const void *src, size_t bytes, void *stream);
+
+/*
  * Test hooks (used by the parity tests to compare integer intermediates bit for bit).
  * Both read the MFMA-layout planes that ozimmu_dgemm(m, n, k, ..., s, workspace) left in
  * `workspace`, on the same stream.

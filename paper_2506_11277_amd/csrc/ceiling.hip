@@ -40,8 +40,25 @@ __global__ __launch_bounds__(512) void mfma_loop_kernel(int iters, int random_op
     if (s == 0x7fffffff) sink[0] = s;   // keeps the loop alive; practically never taken
 }
 
+// Plain copy of 16-byte words: a kernel whose HBM traffic is known exactly (n16 * 16 bytes read, the same
+// written), against which the readings of the memory counters can be scaled.
+__global__ __launch_bounds__(256) void calibration_copy_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst,
+                                                               size_t n16)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x)
+        dst[i] = src[i];
+}
+
 }  // namespace
 }  // namespace oz
+
+extern "C" int ozimmu_calibration_copy(void *dst, const void *src, size_t bytes, void *stream)
+{
+    if (!dst || !src || (bytes & 15) || ((uintptr_t)dst & 15) || ((uintptr_t)src & 15)) return OZIMMU_BAD_ARG;
+    if (bytes == 0) return OZIMMU_OK;
+    oz::calibration_copy_kernel<<<8192, 256, 0, (hipStream_t)stream>>>((const uint4 *)src, (uint4 *)dst, bytes / 16);
+    return hipGetLastError() == hipSuccess ? OZIMMU_OK : OZIMMU_HIP_ERROR;
+}
 
 extern "C" int ozimmu_measure_int8_ceiling(int random_operands, int *sink, float *tops, void *stream)
 {

@@ -48,6 +48,7 @@ _SIGNATURES = {
                                         _c.c_void_p, _c.c_void_p]),
     "ozimmu_profile_start": (_c.c_int, [_c.c_int]),
     "ozimmu_profile_stop": (_c.c_int, [_c.POINTER(_c.c_int), _c.POINTER(_c.c_float)]),
+    "ozimmu_calibration_copy": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_size_t, _c.c_void_p]),
     "ozimmu_measure_int8_ceiling": (_c.c_int, [_c.c_int, _c.c_void_p, _c.POINTER(_c.c_float), _c.c_void_p]),
     "ozimmu_debug_diagonals": (_c.c_int, [_c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_void_p, _c.c_void_p,
                                           _c.c_void_p]),
@@ -302,6 +303,16 @@ def profile_stop():
     if rc != OK:
         raise OzimmuError(rc, "profile_stop")
     return calls.value, {"scales": ms[0], "split": ms[1], "gemm": ms[2]}
+
+
+def calibration_copy(dst, src):
+    """Plain copy kernel of known traffic (src.nbytes read, the same written) for scaling memory counters."""
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes:
+        raise ValueError("calibration_copy: sizes differ")
+    rc = lib().ozimmu_calibration_copy(dst.data_ptr(), src.data_ptr(), nbytes, _stream())
+    if rc != OK:
+        raise OzimmuError(rc, "calibration_copy")
 
 
 def measure_int8_ceiling(random_operands):
