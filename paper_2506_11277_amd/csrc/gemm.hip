@@ -478,13 +478,8 @@ hipError_t launch_fused_s(int m, int n, int kp, const int8_t *pA, const int8_t *
     static_assert(NSTAGE * STAGE <= kLdsBytes, "LDS ring too large");
     static_assert(kPad % TM == 0 && kPad % TN == 0 && (kPad / kFrag) % Cfg::KB32 == 0, "tiles must divide the padding");
     auto kern = gemm_fused_kernel<S, Cfg::WVM, Cfg::WVN, Cfg::WMF, Cfg::WNF, Cfg::KB32, NSTAGE, MODE, PSET>;
-    static bool configured = false;
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           NSTAGE * STAGE);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+    static unsigned long long configured = 0;
+    if (hipError_t e = allow_dynamic_lds((const void *)kern, NSTAGE * STAGE, configured); e != hipSuccess) return e;
     const int tiles_m = (m + TM - 1) / TM, tiles_n = (n + TN - 1) / TN;
     if (MODE != kBlocked) {
         kern<<<tiles_m * tiles_n, 64 * Cfg::WVM * Cfg::WVN, NSTAGE * STAGE, st>>>(

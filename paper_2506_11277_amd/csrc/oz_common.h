@@ -19,6 +19,19 @@ constexpr long long kMaxInt32K = 2147483647LL / (127LL * 127LL);   // 133144
 
 inline int round_up(int x, int q) { return (x + q - 1) / q * q; }
 
+// Lets a kernel use `bytes` of dynamic LDS (more than the 64 KiB default), once per device: `done` holds one
+// bit per device ordinal.  (Two first calls racing on a device both set the attribute: harmless.)
+inline hipError_t allow_dynamic_lds(const void *kernel, int bytes, unsigned long long &done)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev >= 0 && dev < 64 && (done >> dev & 1ULL)) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess && dev >= 0 && dev < 64) done |= 1ULL << dev;
+    return e;
+}
+
 bool fused_handles(int sA, int sB, bool all_products);
 size_t fused_totals_bytes(int sA, int sB, bool all_products, int m, int n, int k);
 size_t banded_totals_bytes(int sA, int sB, int k);
