@@ -539,3 +539,22 @@ def test_nonfinite_input_is_reported_in_every_variant():
         with pytest.raises(ozimmu.OzimmuError) as ei:
             ozimmu.check(ws)
         assert ei.value.code == ozimmu.NONFINITE
+
+
+def test_seeded_random_configurations():
+    # 60 configurations drawn from a fixed seed: shapes, slice counts, product set, slicing rule and level size
+    rng = np.random.default_rng(20250611)
+    for case in range(60):
+        m, n = int(rng.integers(1, 300)), int(rng.integers(1, 300))
+        k = int(rng.integers(1, 700))
+        sA, sB = int(rng.integers(1, 33)), int(rng.integers(1, 33))
+        if rng.random() < 0.4:
+            sB = sA
+        allp = bool(rng.random() < 0.25)
+        nearest = bool(rng.random() < 0.5)
+        Q = int(rng.integers(1, ozimmu.max_level_diagonals(k, sA, sB) + 1))
+        phi = float(rng.choice([0.5, 2.0, 6.0]))
+        print(f"case {case}: {m}x{n}x{k} sA={sA} sB={sB} all={allp} nearest={nearest} Q={Q} phi={phi}", flush=True)
+        A, B = workloads.lognormal(m, n, k, phi, 5000 + case)
+        got = host(ozimmu.dgemm3(dev(A), dev(B), sA, sB, allp, ozimmu.SPLIT_NEAREST if nearest else ozimmu.SPLIT_TRUNCATE, Q))
+        assert_c_matches(got, oracle.dgemm3(A, B, sA, sB, full=allp, nearest=nearest, Q=Q), f"case {case}")
