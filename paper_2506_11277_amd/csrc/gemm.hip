@@ -43,7 +43,9 @@ constexpr int kThreads = 256;   // generic kernel: 4 wavefronts, 2 (m) x 2 (n)
 //                  per (tile, k-block) (blockIdx.y = k-block).  Each adds its int32 diagonal sums into
 //                  int64 totals in HBM with integer atomics -- exact, so the totals do not depend on
 //                  the order of arrival and the result stays bit-reproducible; finish_blocked_kernel
-//                  then does the binary64 accumulation
+//                  then does the binary64 accumulation.  With exactly two k-blocks (slot_stride != 0) nothing
+//                  has to be added on the way: each block stores its int32 sums into a slot of its own (the two
+//                  slots fill the same buffer), no clearing, no atomics, and the finish kernel adds the two
 //   PSET   product set.  0: both operands have S slices, products l + h <= S + 1.  3: both have S slices, ALL
 //          S * S products ("Computation of all products", Sect. 4): 2 S - 1 diagonals, so 2 S - 1 accumulator
 //          sets (S <= 9).  1 / 2: different slice counts (subsection "Reduction in number
@@ -62,7 +64,8 @@ __global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t
                                                                     int KB, int tiles_m, int tiles_n,
                                                                     int32_t *__restrict__ dump,
                                                                     long long *__restrict__ totals,
-                                                                    int stages_per_block, int Q, int sm)
+                                                                    int stages_per_block, int Q, int sm,
+                                                                    long long slot_stride)
 {
     static_assert(PSET == 0 || (NSTAGE == 2 && MODE != kDump), "other product sets: ring of two, no dump");
     constexpr bool DUMP = MODE == kDump;
@@ -224,7 +227,25 @@ __global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t
 
     if (MODE == kBlocked) {
         // this k-block's diagonal sums -> int64 totals of the tile, [tile][wavefront][a][i][j][r][lane]
-        long long *tot = totals + ((size_t)(tm * tiles_n + tn) * NW + wave) * (size_t)(NA * WMF * WNF * 16 * 64) + lane;
+        const size_t e0 = ((size_t)(tm * tiles_n + tn) * NW + wave) * (size_t)(NA * WMF * WNF * 16 * 64) + lane;
+        if (slot_stride) {
+            // two k-blocks: plain int32 stores into this block's slot
+            int *slot = (int *)totals + (size_t)blockIdx.y * (size_t)slot_stride + e0;
+#pragma unroll
+            for (int a = 0; a < NA; ++a) {
+                int *sa = slot + (size_t)a * (WMF * WNF * 16 * 64);
+                asm volatile("" : "+v"(sa));
+#pragma unroll
+                for (int i = 0; i < WMF; ++i)
+#pragma unroll
+                    for (int j = 0; j < WNF; ++j)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) sa[(((size_t)i * WNF + j) * 16 + r) * 64] = acc[a][i][j][r];
+                asm volatile("" ::: "memory");
+            }
+            return;
+        }
+        long long *tot = totals + e0;
 #pragma unroll
         for (int a = 0; a < NA; ++a) {
             // (one diagonal at a time, its base address formed here: otherwise all 16 * S slot addresses are
@@ -282,13 +303,15 @@ __global__ __launch_bounds__(64 * WVM * WVN) void finish_blocked_kernel(const lo
                                                                         const int32_t *__restrict__ eA,
                                                                         const int32_t *__restrict__ eB,
                                                                         double *__restrict__ C, int ldc, int m, int n,
-                                                                        int tiles_n, int Q)
+                                                                        int tiles_n, int Q, long long slot_stride)
 {
     constexpr int NW = WVM * WVN, FA = WVM * WMF, FB = WVN * WNF;
     const int tm = blockIdx.x / tiles_n, tn = blockIdx.x % tiles_n;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave % WVM, wn = wave / WVM;
-    const long long *tot = totals + ((size_t)blockIdx.x * NW + wave) * (size_t)(S * WMF * WNF * 16 * 64) + lane;
+    const size_t e0 = ((size_t)blockIdx.x * NW + wave) * (size_t)(S * WMF * WNF * 16 * 64) + lane;
+    const long long *tot = totals + e0;
+    const int *slot = (const int *)totals + e0;      // slot_stride != 0: two int32 slots instead of int64 totals
     const int m0 = (tm * FA + wm * WMF) * 32, n0 = (tn * FB + wn * WNF) * 32;
     for (int i = 0; i < WMF; ++i) {
         const int mi = m0 + i * 32 + (lane & 31);
@@ -301,7 +324,8 @@ __global__ __launch_bounds__(64 * WVM * WVN) void finish_blocked_kernel(const lo
                 LevelSum sum;
 #pragma unroll
                 for (int a = 0; a < S; ++a) {
-                    const long long v = tot[((((size_t)a * WMF + i) * WNF + j) * 16 + r) * 64];
+                    const size_t e = ((((size_t)a * WMF + i) * WNF + j) * 16 + r) * 64;
+                    const long long v = slot_stride ? (long long)slot[e] + (long long)slot[(size_t)slot_stride + e] : tot[e];
                     // (exact conversion: |v| < 2^53)
                     sum.add((double)v * __builtin_ldexp(1.0, -kSliceBits * (a + 2)), Q, a == S - 1);
                 }
@@ -483,7 +507,7 @@ hipError_t launch_fused_s(int m, int n, int kp, const int8_t *pA, const int8_t *
     const int tiles_m = (m + TM - 1) / TM, tiles_n = (n + TN - 1) / TN;
     if (MODE != kBlocked) {
         kern<<<tiles_m * tiles_n, 64 * Cfg::WVM * Cfg::WVN, NSTAGE * STAGE, st>>>(
-            pA, pB, eA, eB, C, ldc, m, n, kp / kFrag, tiles_m, tiles_n, dump, nullptr, 0, Q, sm);
+            pA, pB, eA, eB, C, ldc, m, n, kp / kFrag, tiles_m, tiles_n, dump, nullptr, 0, Q, sm, 0);
         return hipGetLastError();
     }
     // longest k-block whose sm products per diagonal cannot overflow int32, in whole stages; the blocks are
@@ -493,12 +517,15 @@ hipError_t launch_fused_s(int m, int n, int kp, const int8_t *pA, const int8_t *
     const int nblocks = (nst + max_stages - 1) / max_stages;
     const int stages_per_block = (nst + nblocks - 1) / nblocks;
     const size_t nslots = (size_t)tiles_m * tiles_n * NA * TM * TN;
-    zero_i64_kernel<<<2048, 256, 0, st>>>(totals, nslots);
+    // exactly two k-blocks: an int32 slot per block (together the size of the int64 totals), nothing to clear
+    const long long slot_stride = nblocks == 2 ? (long long)nslots : 0;
+    if (!slot_stride) zero_i64_kernel<<<2048, 256, 0, st>>>(totals, nslots);
     dim3 grid(tiles_m * tiles_n, nblocks);
     kern<<<grid, 64 * Cfg::WVM * Cfg::WVN, NSTAGE * STAGE, st>>>(pA, pB, eA, eB, C, ldc, m, n, kp / kFrag, tiles_m,
-                                                                  tiles_n, nullptr, totals, stages_per_block, Q, sm);
+                                                                  tiles_n, nullptr, totals, stages_per_block, Q, sm,
+                                                                  slot_stride);
     finish_blocked_kernel<NA, Cfg::WVM, Cfg::WVN, Cfg::WMF, Cfg::WNF>
-        <<<tiles_m * tiles_n, 64 * Cfg::WVM * Cfg::WVN, 0, st>>>(totals, eA, eB, C, ldc, m, n, tiles_n, Q);
+        <<<tiles_m * tiles_n, 64 * Cfg::WVM * Cfg::WVN, 0, st>>>(totals, eA, eB, C, ldc, m, n, tiles_n, Q, slot_stride);
     return hipGetLastError();
 }
 

@@ -43,7 +43,7 @@ template <int S, int MODE>
 __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused16_kernel(
     const int8_t *__restrict__ pA, const int8_t *__restrict__ pB, const int32_t *__restrict__ eA,
     const int32_t *__restrict__ eB, double *__restrict__ C, int ldc, int m, int n, int KB, int tiles_m, int tiles_n,
-    int32_t *__restrict__ dump, long long *__restrict__ totals, int stages_per_block, int Q)
+    int32_t *__restrict__ dump, long long *__restrict__ totals, int stages_per_block, int Q, long long slot_stride)
 {
     using G = Cfg16<S>;
     constexpr int WVM = G::WVM, WVN = G::WVN, WMF = G::WMF, WNF = G::WNF, FA = G::FA, FB = G::FB, L0 = G::L0;
@@ -189,7 +189,28 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
     // element of accumulator block (i2, j2), register r: m_local = 16*i2 + lane%16, n_local = 16*j2 + 4*(lane/16) + r
     const int m0 = (tm * FA + wm * WMF) * 32, n0 = (tn * FB + wn * WNF) * 32;
     if (MODE == kBlocked) {
-        long long *tot = totals + ((size_t)(tm * tiles_n + tn) * NW + wave) * (size_t)(S * WMF * WNF * 16 * 64) + lane;
+        const size_t e0 = ((size_t)(tm * tiles_n + tn) * NW + wave) * (size_t)(S * WMF * WNF * 16 * 64) + lane;
+        if (slot_stride) {
+            // exactly two k-blocks: plain int32 stores into this block's slot, nothing cleared, nothing added
+            int *slot = (int *)totals + (size_t)blockIdx.y * (size_t)slot_stride + e0;
+#pragma unroll
+            for (int a = 0; a < S; ++a) {
+                int *sa = slot + (size_t)a * (WMF * WNF * 16 * 64);
+                asm volatile("" : "+v"(sa));
+#pragma unroll
+                for (int i = 0; i < WMF; ++i)
+#pragma unroll
+                    for (int j = 0; j < WNF; ++j)
+#pragma unroll
+                        for (int b = 0; b < 4; ++b)
+#pragma unroll
+                            for (int r = 0; r < 4; ++r)
+                                sa[(((size_t)i * WNF + j) * 16 + b * 4 + r) * 64] = acc[a][i][j][b][r];
+                asm volatile("" ::: "memory");
+            }
+            return;
+        }
+        long long *tot = totals + e0;
 #pragma unroll
         for (int a = 0; a < S; ++a)
 #pragma unroll
@@ -241,14 +262,16 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
 template <int S>
 __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void finish_blocked16_kernel(
     const long long *__restrict__ totals, const int32_t *__restrict__ eA, const int32_t *__restrict__ eB,
-    double *__restrict__ C, int ldc, int m, int n, int tiles_n, int Q)
+    double *__restrict__ C, int ldc, int m, int n, int tiles_n, int Q, long long slot_stride)
 {
     using G = Cfg16<S>;
     constexpr int WVM = G::WVM, WVN = G::WVN, WMF = G::WMF, WNF = G::WNF, FA = G::FA, FB = G::FB, NW = WVM * WVN;
     const int tm = blockIdx.x / tiles_n, tn = blockIdx.x % tiles_n;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave % WVM, wn = wave / WVM;
-    const long long *tot = totals + ((size_t)blockIdx.x * NW + wave) * (size_t)(S * WMF * WNF * 16 * 64) + lane;
+    const size_t e0 = ((size_t)blockIdx.x * NW + wave) * (size_t)(S * WMF * WNF * 16 * 64) + lane;
+    const long long *tot = totals + e0;
+    const int *slot = (const int *)totals + e0;      // slot_stride != 0: two int32 slots instead of int64 totals
     const int m0 = (tm * FA + wm * WMF) * 32, n0 = (tn * FB + wn * WNF) * 32;
     for (int i = 0; i < WMF; ++i)
         for (int i2 = 0; i2 < 2; ++i2) {
@@ -263,7 +286,9 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void finish_blo
                         LevelSum sum;
 #pragma unroll
                         for (int a = 0; a < S; ++a) {
-                            const long long v = tot[((((size_t)a * WMF + i) * WNF + j) * 16 + (i2 * 2 + j2) * 4 + r) * 64];
+                            const size_t e = ((((size_t)a * WMF + i) * WNF + j) * 16 + (i2 * 2 + j2) * 4 + r) * 64;
+                            const long long v =
+                                slot_stride ? (long long)slot[e] + (long long)slot[(size_t)slot_stride + e] : tot[e];
                             sum.add((double)v * __builtin_ldexp(1.0, -kSliceBits * (a + 2)), Q, a == S - 1);   // exact conversion
                         }
                         C[mi + (size_t)nj * ldc] = ldexp(sum.S, ea + eB[nj]);
@@ -290,7 +315,7 @@ hipError_t launch16_s(int m, int n, int kp, const int8_t *pA, const int8_t *pB, 
     const int KB = kp / kFrag;
     if (MODE != kBlocked) {
         kern<<<tiles_m * tiles_n, THREADS, G::LDS, st>>>(pA, pB, eA, eB, C, ldc, m, n, KB, tiles_m, tiles_n, dump,
-                                                         nullptr, 0, Q);
+                                                         nullptr, 0, Q, 0);
         return hipGetLastError();
     }
     // longest k-block (in 64-k stages) whose s products per diagonal cannot overflow int32; equally long blocks
@@ -298,11 +323,14 @@ hipError_t launch16_s(int m, int n, int kp, const int8_t *pA, const int8_t *pB, 
     const int nst = KB / 2;
     const int nblocks = (nst + max_stages - 1) / max_stages;
     const int stages_per_block = (nst + nblocks - 1) / nblocks;
-    zero16_i64_kernel<<<2048, 256, 0, st>>>(totals, (size_t)tiles_m * tiles_n * S * TM * TN);
+    // exactly two k-blocks: an int32 slot per block (together the size of the int64 totals), nothing to clear
+    const size_t nslots = (size_t)tiles_m * tiles_n * S * TM * TN;
+    const long long slot_stride = nblocks == 2 ? (long long)nslots : 0;
+    if (!slot_stride) zero16_i64_kernel<<<2048, 256, 0, st>>>(totals, nslots);
     dim3 grid(tiles_m * tiles_n, nblocks);
     kern<<<grid, THREADS, G::LDS, st>>>(pA, pB, eA, eB, C, ldc, m, n, KB, tiles_m, tiles_n, nullptr, totals,
-                                        stages_per_block, Q);
-    finish_blocked16_kernel<S><<<tiles_m * tiles_n, THREADS, 0, st>>>(totals, eA, eB, C, ldc, m, n, tiles_n, Q);
+                                        stages_per_block, Q, slot_stride);
+    finish_blocked16_kernel<S><<<tiles_m * tiles_n, THREADS, 0, st>>>(totals, eA, eB, C, ldc, m, n, tiles_n, Q, slot_stride);
     return hipGetLastError();
 }
 

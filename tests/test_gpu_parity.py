@@ -558,3 +558,19 @@ def test_seeded_random_configurations():
         A, B = workloads.lognormal(m, n, k, phi, 5000 + case)
         got = host(ozimmu.dgemm3(dev(A), dev(B), sA, sB, allp, ozimmu.SPLIT_NEAREST if nearest else ozimmu.SPLIT_TRUNCATE, Q))
         assert_c_matches(got, oracle.dgemm3(A, B, sA, sB, full=allp, nearest=nearest, Q=Q), f"case {case}")
+
+
+@pytest.mark.parametrize("sA,sB,allp", [(5, 5, False), (7, 7, False), (8, 8, False), (9, 9, False), (12, 12, False),
+                                        (16, 16, False), (18, 18, False), (20, 20, False), (5, 11, False),
+                                        (13, 4, False), (6, 6, True)])
+def test_exactly_two_k_blocks(sA, sB, allp):
+    # two k-blocks take the path without atomics: an int32 slot per block, added by the finish kernel
+    m, n = 130, 70
+    k = (133144 // min(sA, sB)) * 3 // 2
+    print(f"two k-blocks sA={sA} sB={sB} all={allp} k={k}", flush=True)
+    x = 1.0 - 2.0 ** -53
+    A, B = workloads.lognormal(m, n, k, 2.0, 40 + sA)
+    A[:7, :] = x                      # rows and columns whose slices are all +-127: the largest sums there are
+    B[:, :5] = -x
+    got = host(ozimmu.dgemm3(dev(A), dev(B), sA, sB, allp, ozimmu.SPLIT_TRUNCATE, 1))
+    assert_c_matches(got, oracle.dgemm3(A, B, sA, sB, full=allp), "two k-blocks")
