@@ -574,3 +574,18 @@ def test_exactly_two_k_blocks(sA, sB, allp):
     B[:, :5] = -x
     got = host(ozimmu.dgemm3(dev(A), dev(B), sA, sB, allp, ozimmu.SPLIT_TRUNCATE, 1))
     assert_c_matches(got, oracle.dgemm3(A, B, sA, sB, full=allp), "two k-blocks")
+
+
+@pytest.mark.parametrize("sA,sB,allp,nearest,Q", [(7, 7, False, False, 1), (4, 12, False, False, 1), (12, 4, False, True, 2),
+                                                  (3, 18, False, False, 3), (16, 16, False, True, 1), (6, 6, True, False, 2),
+                                                  (25, 9, False, False, 1)])
+def test_transposed_problem_gives_the_transposed_result(sA, sB, allp, nearest, Q):
+    # (A B)^T = B^T A^T: rows of A become columns, slice counts swap sides, every diagonal sum and the order of
+    # the additions stay the same -> bit-identical.  Exercises the row / column split kernels and the two
+    # short-operand variants of the GEMM against each other.
+    A, B = workloads.lognormal(150, 90, 260, 2.0, 77)
+    sp = ozimmu.SPLIT_NEAREST if nearest else ozimmu.SPLIT_TRUNCATE
+    C = host(ozimmu.dgemm3(dev(A), dev(B), sA, sB, allp, sp, Q))
+    Ct = host(ozimmu.dgemm3(dev(B.T.copy()), dev(A.T.copy()), sB, sA, allp, sp, Q))
+    assert np.array_equal(C, Ct.T)
+    assert_c_matches(C, oracle.dgemm3(A, B, sA, sB, full=allp, nearest=nearest, Q=Q), "transposition")
