@@ -228,11 +228,16 @@ int ozimmu_calibration_copy(void *dst, const void *src, size_t bytes, void *stre
  * ozimmu_debug_diagonals: D[(d-2) * m * n + i + j*m] = sum_{l+h=d} (A_(l) B^(h))_ij as int32,
  *   d = 2..s+1, produced by the main loop of the fused GEMM kernel (needs
  *   s * k * 127^2 < 2^31 and s <= the fused kernel's limit, else OZIMMU_BAD_ARG).
+ * ozimmu_debug_small_tile_limit: ozimmu_dgemm with equal slice counts up to 12 uses a 64 x 64 tile instead of
+ *   the tile tabulated for the slice count when the latter would give fewer than `tiles` work-groups
+ *   (default 256, one per compute unit; 0: never).  Process-wide host state; lets the tests run both
+ *   kernels on the same small inputs.  Returns OZIMMU_BAD_ARG for a negative value.
  * ozimmu_debug_slice_product: P[i + j*m] = sum_{kk = k0}^{k1-1} A_(l)[i,kk] B^(h)[kk,j] as int32
  *   for one pair (l, h), 1-based, over the contraction range [k0, k1) with k0 a multiple of 32
  *   and (k1-k0) * 127^2 < 2^31, produced by the generic (pair-by-pair) GEMM kernel.
  */
 int ozimmu_debug_diagonals(int m, int n, int k, int s, const void *workspace, int32_t *D, void *stream);
+int ozimmu_debug_small_tile_limit(long long tiles);
 int ozimmu_debug_slice_product(int m, int n, int k, int s, const void *workspace, int l, int h,
                                int k0, int k1, int32_t *P, void *stream);
 

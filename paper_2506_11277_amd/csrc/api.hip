@@ -230,14 +230,15 @@ static int dgemm_impl(int m, int n, int k, const double *A, int lda, const doubl
     hipStream_t st = (hipStream_t)stream;
     char *ws = (char *)workspace;
     prof_mark(0, st);
-    int rc = scales_into_workspace(w, ws, m, n, k, A, lda, B, ldb, false, nearest ? 1 : 0, st);
-    if (rc) return rc;
-    if (m == 0 || n == 0) return OZIMMU_OK;
-    prof_mark(1, st);
     auto *eA = (int32_t *)(ws + w.off_expA), *eB = (int32_t *)(ws + w.off_expB);
     auto *pA = (int8_t *)(ws + w.off_planesA), *pB = (int8_t *)(ws + w.off_planesB);
-    OZ_TRY(launch_split('A', m, k, A, lda, sA, eA, pA, OZIMMU_LAYOUT_MFMA, nearest, st));
-    OZ_TRY(launch_split('B', k, n, B, ldb, sB, eB, pB, OZIMMU_LAYOUT_MFMA, nearest, st));
+    // three launches for the scales of both operands, one for their slices
+    OZ_TRY(launch_scales_fused(m, n, k, A, lda, B, ldb, (unsigned long long *)(ws + w.off_header),
+                               (unsigned long long *)(ws + w.off_maxA), (unsigned long long *)(ws + w.off_maxB), eA,
+                               w.mp, eB, w.np, nearest ? 1 : 0, st));
+    if (m == 0 || n == 0) return OZIMMU_OK;
+    prof_mark(1, st);
+    OZ_TRY(launch_split_both(m, n, k, A, lda, B, ldb, sA, sB, eA, eB, pA, pB, nearest, st));
     prof_mark(2, st);
     const bool fused = fused_handles(sA, sB, all_products);
     if (fused && fused_single_block(sA, sB, k)) {
@@ -331,6 +332,13 @@ int ozimmu_get_exponents(int m, int n, int k, int s, const void *workspace, int3
     const char *ws = (const char *)workspace;
     if (eA && m) OZ_TRY(hipMemcpyAsync(eA, ws + w.off_expA, 4 * (size_t)m, hipMemcpyDeviceToDevice, st));
     if (eB && n) OZ_TRY(hipMemcpyAsync(eB, ws + w.off_expB, 4 * (size_t)n, hipMemcpyDeviceToDevice, st));
+    return OZIMMU_OK;
+}
+
+int ozimmu_debug_small_tile_limit(long long tiles)
+{
+    if (tiles < 0) return OZIMMU_BAD_ARG;
+    fused_set_small_tile_limit(tiles);
     return OZIMMU_OK;
 }
 

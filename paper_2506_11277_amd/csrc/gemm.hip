@@ -14,6 +14,8 @@
 // The MFMA is issued "transposed": the B-plane fragment is the first operand and the A-plane
 // fragment the second, so that in the 32x32 result lane%32 runs along m.  C is column-major, so
 // each accumulator register then stores 32 consecutive doubles of a column: 256 B segments.
+#include <type_traits>
+
 #include "gemm_dev.h"
 
 namespace oz {
@@ -475,6 +477,14 @@ struct FusedCfg {
     static constexpr int NSTAGE = S <= 3 ? 3 : 2;
 };
 
+// Shape for problems too small to fill the chip with the tabulated tile: 4 wavefronts, tile 64 x 64 (four times
+// as many work-groups as 128 x 128).  Equal counts up to 12, whole contraction in int32.
+struct FusedCfgSmall {
+    static constexpr int WVM = 2, WVN = 2, WMF = 1, WNF = 1, FR = 4, KB32 = 1, NSTAGE = 2;
+};
+constexpr int kSmallMaxS = 12;
+long long g_small_below_tiles = 256;           // fewer work-groups than CUs of an MI355X (test hook: 0 switches it off)
+
 constexpr int kFusedMaxUneq = 18; // most accumulator sets for different slice counts and for all products
 constexpr int kFusedMaxS = 20;   // 16 accumulator registers per diagonal: 12 fit 256 registers, 20 fit 512 (BIG);
                                  // two 32-deep stages of a 64 x 64 tile with 20 slices fill the 160 KiB of LDS
@@ -489,13 +499,13 @@ void fused_tile(int &tm, int &tn)
 
 // sm: slices of the short operand (PSET = 1: A, 2: B); PSET = 0, 3: sm = S.  The work-group shape is the one
 // tabulated for the number of accumulator sets NA.
-template <int S, int MODE, int PSET>
+template <int S, int MODE, int PSET, bool SMALL = false>
 hipError_t launch_fused_s(int m, int n, int kp, const int8_t *pA, const int8_t *pB, const int32_t *eA,
                           const int32_t *eB, double *C, int ldc, int32_t *dump, long long *totals, int Q, int sm,
                           hipStream_t st)
 {
     constexpr int NA = PSET == 3 ? 2 * S - 1 : S;
-    using Cfg = FusedCfg<NA>;
+    using Cfg = typename std::conditional<SMALL, FusedCfgSmall, FusedCfg<NA>>::type;
     constexpr int TM = 32 * Cfg::WVM * Cfg::WMF, TN = 32 * Cfg::WVN * Cfg::WNF;
     constexpr int STAGE = Cfg::FR * Cfg::KB32 * S * kFragBytes;
     constexpr int NSTAGE = PSET ? 2 : Cfg::NSTAGE;
@@ -554,6 +564,19 @@ hipError_t dispatch_fused(int s, int m, int n, int kp, const int8_t *pA, const i
     return hipErrorInvalidValue;
 }
 
+// equal counts, whole contraction in int32, small tile
+hipError_t dispatch_fused_small(int s, int m, int n, int kp, const int8_t *pA, const int8_t *pB, const int32_t *eA,
+                                const int32_t *eB, double *C, int ldc, int Q, hipStream_t st)
+{
+    switch (s) {
+#define OZ_CASE(S_) \
+    case S_: return launch_fused_s<S_, kPlain, 0, true>(m, n, kp, pA, pB, eA, eB, C, ldc, nullptr, nullptr, Q, S_, st);
+        OZ_CASE(1) OZ_CASE(2) OZ_CASE(3) OZ_CASE(4) OZ_CASE(5) OZ_CASE(6) OZ_CASE(7) OZ_CASE(8) OZ_CASE(9) OZ_CASE(10) OZ_CASE(11) OZ_CASE(12)
+#undef OZ_CASE
+    }
+    return hipErrorInvalidValue;
+}
+
 // all S * S products, equal counts: 2 S - 1 <= kFusedMaxS accumulator sets
 template <int MODE>
 hipError_t dispatch_fused_all(int s, int m, int n, int kp, const int8_t *pA, const int8_t *pB, const int32_t *eA,
@@ -571,6 +594,8 @@ hipError_t dispatch_fused_all(int s, int m, int n, int kp, const int8_t *pA, con
 }  // namespace
 
 int fused_max_slices() { return kFusedMaxS; }
+
+void fused_set_small_tile_limit(long long tiles) { g_small_below_tiles = tiles; }
 
 bool fused_handles(int sA, int sB, bool all_products)
 {
@@ -615,6 +640,17 @@ hipError_t launch_gemm_fused(int m, int n, int kp, int sA, int sB, bool all_prod
     }
     if (sA == sB) {
         const int s = sA;
+        if (!dump && !totals && s <= kSmallMaxS) {
+            // too few tiles of the tabulated shape to occupy the chip: the 64 x 64 tile
+            int tm = 128, tn = 128;
+            if (fused16_preferred(s)) fused16_tile(s, tm, tn);
+            else if (s <= 4 || s == 6) { tm = 128; tn = 128; }
+            else { tm = 128; tn = 64; }
+            const long long tiles = (long long)((m + tm - 1) / tm) * ((n + tn - 1) / tn);
+            const long long small_tiles = (long long)((m + 63) / 64) * ((n + 63) / 64);
+            if (tiles < g_small_below_tiles && small_tiles > tiles)
+                return dispatch_fused_small(s, m, n, kp, pA, pB, eA, eB, C, ldc, Q, st);
+        }
         // the 16x16x64 kernel where it is the faster one
         if (fused16_preferred(s))
             return launch_gemm_fused16(m, n, kp, s, pA, pB, eA, eB, C, ldc, dump, totals, Q, st);

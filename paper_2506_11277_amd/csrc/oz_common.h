@@ -86,15 +86,26 @@ hipError_t launch_finalize(const unsigned long long *maxbits, const unsigned lon
                            int32_t *exps, int nblk, int nblk_padded, unsigned long long *kappa_bits,
                            int bias, hipStream_t st);
 hipError_t launch_clear_header(void *header, hipStream_t st);
+// the whole scale extraction of ozimmu_dgemm in three launches: clear, reduce both operands, exponents of both
+hipError_t launch_scales_fused(int m, int n, int k, const double *A, int lda, const double *B, int ldb,
+                               unsigned long long *hdr, unsigned long long *maxA, unsigned long long *maxB,
+                               int32_t *expA, int mp, int32_t *expB, int np, int bias, hipStream_t st);
 
 // ---- launchers implemented in split.hip --------------------------------------------------
 // nearest: slices by round-to-nearest (exps must then hold the biased exponents), else by truncation
 hipError_t launch_split(char side, int rows, int cols, const double *X, int ldx, int s,
                         const int32_t *exps, int8_t *planes, int layout, bool nearest, hipStream_t st);
 
+// slices of both operands (MFMA layout) in one launch
+hipError_t launch_split_both(int m, int n, int k, const double *A, int lda, const double *B, int ldb, int sA, int sB,
+                             const int32_t *eA, const int32_t *eB, int8_t *pA, int8_t *pB, bool nearest,
+                             hipStream_t st);
+
 // ---- launchers implemented in gemm.hip ---------------------------------------------------
 // largest s the fused (all diagonals in registers) kernel handles
 int fused_max_slices();
+// problems with fewer tiles of the tabulated shape than this use the 64 x 64 tile (default 256; 0: never)
+void fused_set_small_tile_limit(long long tiles);
 // true when the fused kernel computes this product set: the reduced set with equal counts <= fused_max_slices()
 // (20) or different counts <= 18, or all products of equal counts with 2 s - 1 <= 18 diagonals
 bool fused_handles(int sA, int sB, bool all_products);

@@ -29,12 +29,11 @@ __device__ __forceinline__ void fold(Acc &a, unsigned long long bits)
 }
 
 // ---- side 'B': one work-group per column, wavefront-shuffle tree, then 4 partials via LDS ----
-__global__ __launch_bounds__(256) void colreduce_kernel(const unsigned long long *__restrict__ X, int ldx, int rows,
-                                                        unsigned long long *__restrict__ maxbits,
-                                                        unsigned long long *__restrict__ minbits,
-                                                        unsigned int *__restrict__ flags)
+__device__ __forceinline__ void colreduce_block(int j, const unsigned long long *__restrict__ X, int ldx, int rows,
+                                                unsigned long long *__restrict__ maxbits,
+                                                unsigned long long *__restrict__ minbits,
+                                                unsigned int *__restrict__ flags)
 {
-    const int j = blockIdx.x;
     const unsigned long long *col = X + (size_t)j * ldx;
     Acc a{0ULL, kNoMin, 0u};
     int r = threadIdx.x;
@@ -72,18 +71,26 @@ __global__ __launch_bounds__(256) void colreduce_kernel(const unsigned long long
     }
 }
 
+__global__ __launch_bounds__(256) void colreduce_kernel(const unsigned long long *__restrict__ X, int ldx, int rows,
+                                                        unsigned long long *__restrict__ maxbits,
+                                                        unsigned long long *__restrict__ minbits,
+                                                        unsigned int *__restrict__ flags)
+{
+    colreduce_block(blockIdx.x, X, ldx, rows, maxbits, minbits, flags);
+}
+
 // ---- side 'A': lane <-> row (coalesced along the column-major rows), 4 wavefronts split a
 //      chunk of columns, partials meet in LDS, one integer atomic per row and work-group ----
 constexpr int kRowChunk = 256;   // columns per work-group
 
-__global__ __launch_bounds__(256) void rowreduce_kernel(const unsigned long long *__restrict__ X, int ldx, int rows,
-                                                        int cols, unsigned long long *__restrict__ maxbits,
-                                                        unsigned long long *__restrict__ minbits,
-                                                        unsigned int *__restrict__ flags)
+__device__ __forceinline__ void rowreduce_block(int bx, int by, const unsigned long long *__restrict__ X, int ldx,
+                                                int rows, int cols, unsigned long long *__restrict__ maxbits,
+                                                unsigned long long *__restrict__ minbits,
+                                                unsigned int *__restrict__ flags)
 {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const int r = blockIdx.x * 64 + lane;
-    const int c0 = blockIdx.y * kRowChunk + w * (kRowChunk / 4);
+    const int r = bx * 64 + lane;
+    const int c0 = by * kRowChunk + w * (kRowChunk / 4);
     int c1 = c0 + kRowChunk / 4;
     c1 = c1 < cols ? c1 : cols;
     Acc a{0ULL, kNoMin, 0u};
@@ -115,6 +122,35 @@ __global__ __launch_bounds__(256) void rowreduce_kernel(const unsigned long long
         if (minbits && mn != kNoMin) atomicMin(&minbits[r], mn);
         if (bad) atomicOr(flags, 1u);
     }
+}
+
+__global__ __launch_bounds__(256) void rowreduce_kernel(const unsigned long long *__restrict__ X, int ldx, int rows,
+                                                        int cols, unsigned long long *__restrict__ maxbits,
+                                                        unsigned long long *__restrict__ minbits,
+                                                        unsigned int *__restrict__ flags)
+{
+    rowreduce_block(blockIdx.x, blockIdx.y, X, ldx, rows, cols, maxbits, minbits, flags);
+}
+
+// Both operands in one launch (ozimmu_dgemm: fewer, larger launches matter for small problems): the first
+// nblkA work-groups reduce A (numbered rows-block fastest), the others one column of B each.
+__global__ __launch_bounds__(256) void reduce_both_kernel(const unsigned long long *__restrict__ A, int lda, int m, int k,
+                                                          const unsigned long long *__restrict__ B, int ldb, int n,
+                                                          unsigned long long *__restrict__ maxA,
+                                                          unsigned long long *__restrict__ maxB,
+                                                          unsigned int *__restrict__ flags, int gxA, int nblkA)
+{
+    const int b = blockIdx.x;
+    if (b < nblkA) rowreduce_block(b % gxA, b / gxA, A, lda, m, k, maxA, nullptr, flags);
+    else colreduce_block(b - nblkA, B, ldb, k, maxB, nullptr, flags);
+}
+
+// header cleared, row maxima of A set to 0 (they are formed with atomic max)
+__global__ void init_scales_kernel(unsigned long long *hdr, unsigned long long *maxA, int m)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < 32) hdr[i] = 0ULL;
+    if (i < m) maxA[i] = 0ULL;
 }
 
 __global__ void fill_u64_kernel(unsigned long long *p, unsigned long long v, int n)
@@ -154,7 +190,35 @@ __global__ void finalize_kernel(const unsigned long long *__restrict__ maxbits,
     }
 }
 
+// exponents of both operands in one launch (no kappa)
+__global__ void finalize_both_kernel(const unsigned long long *__restrict__ maxA, int32_t *__restrict__ expA, int m,
+                                     int mp, const unsigned long long *__restrict__ maxB, int32_t *__restrict__ expB,
+                                     int n, int np, int bias)
+{
+    int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b < mp) { expA[b] = b < m ? exponent_above(maxA[b]) + bias : 0; return; }
+    b -= mp;
+    if (b < np) expB[b] = b < n ? exponent_above(maxB[b]) + bias : 0;
+}
+
 }  // namespace
+
+hipError_t launch_scales_fused(int m, int n, int k, const double *A, int lda, const double *B, int ldb,
+                               unsigned long long *hdr, unsigned long long *maxA, unsigned long long *maxB,
+                               int32_t *expA, int mp, int32_t *expB, int np, int bias, hipStream_t st)
+{
+    const int mm = m > 0 ? m : 0;
+    init_scales_kernel<<<(mm + 32 + 255) / 256, 256, 0, st>>>(hdr, maxA, mm);
+    const int gxA = (mm + 63) / 64, gyA = k > 0 ? (k + kRowChunk - 1) / kRowChunk : 0;
+    const long long nblkA = (long long)gxA * gyA, nblkB = n > 0 ? n : 0;
+    if (nblkA + nblkB > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (nblkA + nblkB > 0)
+        reduce_both_kernel<<<(unsigned)(nblkA + nblkB), 256, 0, st>>>((const unsigned long long *)A, lda, m, k,
+                                                                      (const unsigned long long *)B, ldb, n, maxA, maxB,
+                                                                      (unsigned int *)hdr, gxA > 0 ? gxA : 1, (int)nblkA);
+    finalize_both_kernel<<<(mp + np + 255) / 256, 256, 0, st>>>(maxA, expA, m, mp, maxB, expB, n, np, bias);
+    return hipGetLastError();
+}
 
 hipError_t launch_clear_header(void *header, hipStream_t st)
 {

@@ -80,13 +80,13 @@ __device__ __forceinline__ unsigned int slice_of(const Elem &el, int l, unsigned
 //      K-contiguous fragments costs nothing, reads are 512 B per wavefront load, writes are
 //      512 B contiguous per half wavefront.
 template <bool NEAREST>
-__global__ __launch_bounds__(256) void split_rows_kernel(const unsigned long long *__restrict__ X, int ldx, int R,
-                                                         int K, int s, const int32_t *__restrict__ exps,
-                                                         int8_t *__restrict__ planes, int KB)
+__device__ __forceinline__ void split_rows_block(int bx, int by, const unsigned long long *__restrict__ X, int ldx,
+                                                 int R, int K, int s, const int32_t *__restrict__ exps,
+                                                 int8_t *__restrict__ planes, int KB)
 {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const int r = blockIdx.x * 64 + lane;
-    const int k0 = blockIdx.y * 64 + w * 16;
+    const int r = bx * 64 + lane;
+    const int k0 = by * 64 + w * 16;
     const int e = r < R ? exps[r] : 0;
     Elem el[16];
 #pragma unroll
@@ -118,13 +118,21 @@ constexpr int kColLdsRow = kColTileK + 16;   // bytes per (slice, column) row in
 constexpr int kColGroup = 8;                 // slices per LDS pass
 
 template <bool NEAREST>
-__global__ __launch_bounds__(256) void split_cols_kernel(const unsigned long long *__restrict__ X, int ldx, int R,
+__global__ __launch_bounds__(256) void split_rows_kernel(const unsigned long long *__restrict__ X, int ldx, int R,
                                                          int K, int s, const int32_t *__restrict__ exps,
                                                          int8_t *__restrict__ planes, int KB)
 {
+    split_rows_block<NEAREST>(blockIdx.x, blockIdx.y, X, ldx, R, K, s, exps, planes, KB);
+}
+
+template <bool NEAREST>
+__device__ __forceinline__ void split_cols_block(int bx, int by, const unsigned long long *__restrict__ X, int ldx,
+                                                 int R, int K, int s, const int32_t *__restrict__ exps,
+                                                 int8_t *__restrict__ planes, int KB)
+{
     __shared__ __attribute__((aligned(16))) unsigned char lds[kColGroup * 32 * kColLdsRow];
     const int t = threadIdx.x;
-    const int j0 = blockIdx.x * 32, k0 = blockIdx.y * kColTileK;
+    const int j0 = bx * 32, k0 = by * kColTileK;
     const int kq = (t & 31) * 4;
     Elem el[4][4];
 #pragma unroll
@@ -164,6 +172,27 @@ __global__ __launch_bounds__(256) void split_cols_kernel(const unsigned long lon
         }
         __syncthreads();
     }
+}
+
+template <bool NEAREST>
+__global__ __launch_bounds__(256) void split_cols_kernel(const unsigned long long *__restrict__ X, int ldx, int R,
+                                                         int K, int s, const int32_t *__restrict__ exps,
+                                                         int8_t *__restrict__ planes, int KB)
+{
+    split_cols_block<NEAREST>(blockIdx.x, blockIdx.y, X, ldx, R, K, s, exps, planes, KB);
+}
+
+// Both operands in one launch: the first nblkA work-groups slice A (numbered rows-block fastest), the others B.
+template <bool NEAREST>
+__global__ __launch_bounds__(256) void split_both_kernel(const unsigned long long *__restrict__ A, int lda, int m,
+                                                         const unsigned long long *__restrict__ B, int ldb, int n, int K,
+                                                         int sA, int sB, const int32_t *__restrict__ eA,
+                                                         const int32_t *__restrict__ eB, int8_t *__restrict__ pA,
+                                                         int8_t *__restrict__ pB, int KB, int gxA, int nblkA, int gxB)
+{
+    const int b = blockIdx.x;
+    if (b < nblkA) split_rows_block<NEAREST>(b % gxA, b / gxA, A, lda, m, K, sA, eA, pA, KB);
+    else split_cols_block<NEAREST>((b - nblkA) % gxB, (b - nblkA) / gxB, B, ldb, n, K, sB, eB, pB, KB);
 }
 
 // ---- plain layout: plane l is a matrix shaped like X (utility / test path) ----
@@ -210,6 +239,20 @@ hipError_t launch_split(char side, int rows, int cols, const double *X, int ldx,
         auto kern = nearest ? split_cols_kernel<true> : split_cols_kernel<false>;
         kern<<<grid, 256, 0, st>>>((const unsigned long long *)X, ldx, R, K, s, exps, planes, KB);
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_split_both(int m, int n, int k, const double *A, int lda, const double *B, int ldb, int sA, int sB,
+                             const int32_t *eA, const int32_t *eB, int8_t *pA, int8_t *pB, bool nearest, hipStream_t st)
+{
+    const int mp = round_up(m > 0 ? m : 1, kPad), np = round_up(n > 0 ? n : 1, kPad), kp = round_up(k > 0 ? k : 1, kPad);
+    const int gxA = mp / 64, gxB = np / 32;
+    const long long nblkA = (long long)gxA * (kp / 64), nblkB = (long long)gxB * (kp / kColTileK);
+    if (nblkA + nblkB > 0x7fffffffLL) return hipErrorInvalidValue;
+    auto kern = nearest ? split_both_kernel<true> : split_both_kernel<false>;
+    kern<<<(unsigned)(nblkA + nblkB), 256, 0, st>>>((const unsigned long long *)A, lda, m,
+                                                    (const unsigned long long *)B, ldb, n, k, sA, sB, eA, eB, pA, pB,
+                                                    kp / kFrag, gxA, (int)nblkA, gxB);
     return hipGetLastError();
 }
 

@@ -50,6 +50,7 @@ _SIGNATURES = {
     "ozimmu_profile_stop": (_c.c_int, [_c.POINTER(_c.c_int), _c.POINTER(_c.c_float)]),
     "ozimmu_calibration_copy": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_size_t, _c.c_void_p]),
     "ozimmu_measure_int8_ceiling": (_c.c_int, [_c.c_int, _c.c_void_p, _c.POINTER(_c.c_float), _c.c_void_p]),
+    "ozimmu_debug_small_tile_limit": (_c.c_int, [_c.c_longlong]),
     "ozimmu_debug_diagonals": (_c.c_int, [_c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_void_p, _c.c_void_p,
                                           _c.c_void_p]),
     "ozimmu_debug_slice_product": (_c.c_int, [_c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_void_p, _c.c_int,
@@ -323,6 +324,13 @@ def measure_int8_ceiling(random_operands):
     if rc != OK:
         raise OzimmuError(rc, "measure_int8_ceiling")
     return tops.value
+
+
+def debug_small_tile_limit(tiles):
+    """Test hook: tile-count threshold below which equal slice counts up to 12 use the 64 x 64 tile (0: never)."""
+    rc = lib().ozimmu_debug_small_tile_limit(int(tiles))
+    if rc != OK:
+        raise OzimmuError(rc, "debug_small_tile_limit")
 
 
 def debug_diagonals(m, n, k, s, workspace):

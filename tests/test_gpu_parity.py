@@ -15,6 +15,26 @@ from paper_2506_11277_amd import ozimmu, workloads
 REL_BAR = 1e-15
 
 
+@pytest.fixture(params=["tabulated tile", "small tile"])
+def tile_choice(request):
+    """Small problems would all run the 64 x 64 tile; tests that take this fixture run once with that choice
+    switched off (the kernels tabulated per slice count) and once with it on."""
+    ozimmu.debug_small_tile_limit(0 if request.param == "tabulated tile" else 256)
+    yield request.param
+    ozimmu.debug_small_tile_limit(256)
+
+
+@pytest.fixture(autouse=True)
+def tabulated_tile_by_default(request):
+    """Every other test runs the kernels tabulated per slice count."""
+    if "tile_choice" not in request.fixturenames:
+        ozimmu.debug_small_tile_limit(0)
+        yield
+        ozimmu.debug_small_tile_limit(256)
+    else:
+        yield
+
+
 def dev(X):
     return ozimmu.to_colmajor(np.asarray(X, dtype=np.float64))
 
@@ -178,7 +198,7 @@ def test_extreme_slices_do_not_overflow_int32_in_fused_kernel():
 @pytest.mark.parametrize("kind", ["uniform", "lognormal", "pow2", "special"])
 @pytest.mark.parametrize("m,n,k", SHAPES)
 @pytest.mark.parametrize("s", [1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16, 17, 18, 19, 20, 21, 32])
-def test_dgemm_matches_oracle(kind, m, n, k, s):
+def test_dgemm_matches_oracle(kind, m, n, k, s, tile_choice):
     A, B = inputs(kind, m, n, k, 31)
     ws = ozimmu.alloc_workspace(m, n, k, s)
     C = ozimmu.dgemm(dev(A), dev(B), s, workspace=ws, check_finite=True)
@@ -195,7 +215,7 @@ def test_dgemm_config_uniform_128():
         assert_c_matches(host(ozimmu.dgemm(dev(A), dev(B), s)), oracle.dgemm(A, B, s), f"uniform_128 s={s}")
 
 
-def test_dgemm_config_lognormal_1024_all_slice_counts():
+def test_dgemm_config_lognormal_1024_all_slice_counts(tile_choice):
     cfg = workloads.CONFIGS["lognormal_1024"]
     A, B = cfg["gen"]()
     dA, dB = dev(A), dev(B)
@@ -204,7 +224,7 @@ def test_dgemm_config_lognormal_1024_all_slice_counts():
         assert_c_matches(host(ozimmu.dgemm(dA, dB, s)), oracle.dgemm(A, B, s), f"lognormal_1024 s={s}")
 
 
-def test_dgemm_with_leading_dimensions_and_c_view():
+def test_dgemm_with_leading_dimensions_and_c_view(tile_choice):
     m, n, k, s = 70, 50, 90, 6
     A, B = workloads.lognormal(m, n, k, 1.0, 4)
     bigA = ozimmu.colmajor_empty(100, k); bigA.fill_(1e300); bigA[:m, :] = torch.as_tensor(A)
@@ -251,7 +271,7 @@ def test_runs_are_bit_identical():
         assert np.array_equal(C1, C2)
 
 
-def test_degenerate_sizes():
+def test_degenerate_sizes(tile_choice):
     A, B = workloads.uniform(8, 6, 0, 1)
     C = ozimmu.dgemm(dev(A), dev(B), 3)
     assert tuple(C.shape) == (8, 6) and bool((C == 0).all())
@@ -433,7 +453,7 @@ VARIANT_CASES = [
 
 @pytest.mark.parametrize("sA,sB,allp,nearest,Q", VARIANT_CASES)
 @pytest.mark.parametrize("m,n,k,kind", [(100, 90, 70, "lognormal"), (257, 130, 300, "special"), (150, 200, 1000, "ties")])
-def test_dgemm3_variants_bit_exact(sA, sB, allp, nearest, Q, m, n, k, kind):
+def test_dgemm3_variants_bit_exact(sA, sB, allp, nearest, Q, m, n, k, kind, tile_choice):
     A, B = (tie_heavy(m, k, 7), tie_heavy(k, n, 8)) if kind == "ties" else inputs(kind, m, n, k, 14)
     assert Q <= ozimmu.max_level_diagonals(k, sA, sB)
     print(f"dgemm3 sA={sA} sB={sB} all={allp} nearest={nearest} Q={Q} {m}x{n}x{k} {kind}", flush=True)
@@ -541,7 +561,7 @@ def test_nonfinite_input_is_reported_in_every_variant():
         assert ei.value.code == ozimmu.NONFINITE
 
 
-def test_seeded_random_configurations():
+def test_seeded_random_configurations(tile_choice):
     # 60 configurations drawn from a fixed seed: shapes, slice counts, product set, slicing rule and level size
     rng = np.random.default_rng(20250611)
     for case in range(60):
