@@ -180,7 +180,9 @@ def main():
     # context: what the matrix cores sustain with nothing else running, and the vendor's int8 GEMM
     out["int8_mfma_sustained_TOPs"] = {"constant_operands": ozimmu.measure_int8_ceiling(False),
                                        "random_operands": ozimmu.measure_int8_ceiling(True),
-                                       "what": "register-only v_mfma_i32_32x32x32_i8 loop, 2 wavefronts per SIMD"}
+                                       "random_operands_16x16x64": ozimmu.measure_int8_ceiling(True, shape16=True),
+                                       "what": "register-only v_mfma_i32_32x32x32_i8 loop (last entry: "
+                                               "v_mfma_i32_16x16x64_i8), 2 wavefronts per SIMD"}
     try:
         ia = torch.randint(-127, 128, (m, k), dtype=torch.int8, device="cuda")
         ib = torch.randint(-127, 128, (n, k), dtype=torch.int8, device="cuda").t()

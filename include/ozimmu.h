@@ -211,6 +211,9 @@ int ozimmu_profile_stop(int *calls, float *phase_ms);
  * GEMM kernel: the sustained clock of the matrix cores depends on the operand data.
  */
 int ozimmu_measure_int8_ceiling(int random_operands, int *sink, float *tops, void *stream);
+/* The same with the matrix instruction chosen: shape 0 = v_mfma_i32_32x32x32_i8, 1 = v_mfma_i32_16x16x64_i8 (the
+ * one the GEMM kernel for 4, 5, 7, 8 and 9 slices uses; it spends less energy per product). */
+int ozimmu_measure_int8_ceiling2(int random_operands, int shape, int *sink, float *tops, void *stream);
 
 /*
  * Benchmark aid: a plain device-to-device copy kernel (`calibration_copy_kernel`) of `bytes` bytes (a multiple

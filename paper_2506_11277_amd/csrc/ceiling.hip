@@ -1,6 +1,6 @@
 // Measurement aid for the benchmark: what int8 rate do the matrix cores of THIS chip sustain
-// when nothing else happens?  A register-only loop of independent v_mfma_i32_32x32x32_i8 (no
-// LDS, no memory), two wavefronts per SIMD, with either constant or pseudo-random operands.
+// when nothing else happens?  A register-only loop of independent v_mfma_i32_32x32x32_i8 or
+// v_mfma_i32_16x16x64_i8 (no LDS, no memory), two wavefronts per SIMD, with either constant or pseudo-random operands.
 // The two differ markedly on MI355X (the clock drops under the switching power of real data),
 // which is the context the roofline fraction of the GEMM kernel has to be read in.
 #include "oz_common.h"
@@ -11,6 +11,9 @@ namespace {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
+// SHAPE16: v_mfma_i32_16x16x64_i8 (16 accumulator sets of 4 registers) instead of 32x32x32 (8 sets of 16): the
+// same number of int8 operations per iteration.
+template <bool SHAPE16>
 __global__ __launch_bounds__(512) void mfma_loop_kernel(int iters, int random_operands, int *sink)
 {
     unsigned x = threadIdx.x * 2654435761u + blockIdx.x * 40503u + 17u;
@@ -23,20 +26,34 @@ __global__ __launch_bounds__(512) void mfma_loop_kernel(int iters, int random_op
         a = v4i{0x01010101, 0x01010101, 0x01010101, 0x01010101};
         b = v4i{0x02020202, 0x02020202, 0x02020202, 0x02020202};
     }
-    v16i acc[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[i][r] = 0;
-    for (int it = 0; it < iters; ++it) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, acc[i], 0, 0, 0);
-    }
     int s = 0;
+    if (SHAPE16) {
+        v4i acc[16];
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
+        for (int i = 0; i < 16; ++i) acc[i] = v4i{0, 0, 0, 0};
+        for (int it = 0; it < iters; ++it) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) s ^= acc[i][r];
+            for (int i = 0; i < 16; ++i) acc[i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, acc[i], 0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) s ^= acc[i][r];
+    } else {
+        v16i acc[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][r] = 0;
+        for (int it = 0; it < iters; ++it) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, acc[i], 0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s ^= acc[i][r];
+    }
     if (s == 0x7fffffff) sink[0] = s;   // keeps the loop alive; practically never taken
 }
 
@@ -60,7 +77,20 @@ extern "C" int ozimmu_calibration_copy(void *dst, const void *src, size_t bytes,
     return hipGetLastError() == hipSuccess ? OZIMMU_OK : OZIMMU_HIP_ERROR;
 }
 
+static int measure_ceiling(int random_operands, bool shape16, int *sink, float *tops, void *stream);
+
 extern "C" int ozimmu_measure_int8_ceiling(int random_operands, int *sink, float *tops, void *stream)
+{
+    return measure_ceiling(random_operands, false, sink, tops, stream);
+}
+
+extern "C" int ozimmu_measure_int8_ceiling2(int random_operands, int shape, int *sink, float *tops, void *stream)
+{
+    if (shape != 0 && shape != 1) return OZIMMU_BAD_ARG;
+    return measure_ceiling(random_operands, shape == 1, sink, tops, stream);
+}
+
+static int measure_ceiling(int random_operands, bool shape16, int *sink, float *tops, void *stream)
 {
     if (!sink || !tops) return OZIMMU_BAD_ARG;
     hipStream_t st = (hipStream_t)stream;
@@ -74,9 +104,10 @@ extern "C" int ozimmu_measure_int8_ceiling(int random_operands, int *sink, float
     const int iters = 12000, wgs = cus * 4;     // about 50-70 ms: long enough for the clock to settle
     int rc = OZIMMU_OK;
     float ms = 0.f;
-    oz::mfma_loop_kernel<<<wgs, 512, 0, st>>>(iters / 8, random_operands, sink);   // warm-up
+    auto kern = shape16 ? oz::mfma_loop_kernel<true> : oz::mfma_loop_kernel<false>;
+    kern<<<wgs, 512, 0, st>>>(iters / 8, random_operands, sink);   // warm-up
     if (hipEventRecord(e0, st) != hipSuccess) rc = OZIMMU_HIP_ERROR;
-    oz::mfma_loop_kernel<<<wgs, 512, 0, st>>>(iters, random_operands, sink);
+    kern<<<wgs, 512, 0, st>>>(iters, random_operands, sink);
     if (hipGetLastError() != hipSuccess) rc = OZIMMU_HIP_ERROR;
     if (hipEventRecord(e1, st) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
         hipEventElapsedTime(&ms, e0, e1) != hipSuccess)

@@ -49,6 +49,7 @@ _SIGNATURES = {
     "ozimmu_profile_start": (_c.c_int, [_c.c_int]),
     "ozimmu_profile_stop": (_c.c_int, [_c.POINTER(_c.c_int), _c.POINTER(_c.c_float)]),
     "ozimmu_calibration_copy": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_size_t, _c.c_void_p]),
+    "ozimmu_measure_int8_ceiling2": (_c.c_int, [_c.c_int, _c.c_int, _c.c_void_p, _c.POINTER(_c.c_float), _c.c_void_p]),
     "ozimmu_measure_int8_ceiling": (_c.c_int, [_c.c_int, _c.c_void_p, _c.POINTER(_c.c_float), _c.c_void_p]),
     "ozimmu_debug_small_tile_limit": (_c.c_int, [_c.c_longlong]),
     "ozimmu_debug_diagonals": (_c.c_int, [_c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_void_p, _c.c_void_p,
@@ -316,11 +317,12 @@ def calibration_copy(dst, src):
         raise OzimmuError(rc, "calibration_copy")
 
 
-def measure_int8_ceiling(random_operands):
-    """Sustained int8 MFMA rate (TOP/s) of a register-only loop on the current device."""
+def measure_int8_ceiling(random_operands, shape16=False):
+    """Sustained int8 MFMA rate (TOP/s) of a register-only loop on the current device (32x32x32 or 16x16x64)."""
     sink = torch.zeros(1, dtype=torch.int32, device="cuda")
     tops = ctypes.c_float(0.0)
-    rc = lib().ozimmu_measure_int8_ceiling(int(bool(random_operands)), sink.data_ptr(), ctypes.byref(tops), _stream())
+    rc = lib().ozimmu_measure_int8_ceiling2(int(bool(random_operands)), int(bool(shape16)), sink.data_ptr(),
+                                            ctypes.byref(tops), _stream())
     if rc != OK:
         raise OzimmuError(rc, "measure_int8_ceiling")
     return tops.value
