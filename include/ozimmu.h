@@ -58,8 +58,8 @@ const char *ozimmu_status_string(int status);
  * Bytes of device workspace ozimmu_dgemm / ozimmu_estimate_slices need for this problem:
  * scale exponents, per-row/column reductions, the int8 slice planes of A and B, and -- only when
  * min(sA, sB) * k > 133144, i.e. when a diagonal's int32 sum could overflow and k has to be cut into
- * blocks -- int64 totals of the diagonals (8 bytes per diagonal and entry of C for up to 20 slices, a
- * fixed 128 MiB beyond).
+ * blocks -- int64 totals of the diagonals (8 bytes per diagonal and entry of a column panel of C, panels of
+ * about 1 GiB, for up to 20 slices; a fixed 128 MiB beyond).
  * Returns 0 for invalid arguments.  Alignment required of the workspace pointer: 256 bytes.
  */
 size_t ozimmu_workspace_bytes(int m, int n, int k, int s);
@@ -235,12 +235,16 @@ int ozimmu_calibration_copy(void *dst, const void *src, size_t bytes, void *stre
  *   the tile tabulated for the slice count when the latter would give fewer than `tiles` work-groups
  *   (default 256, one per compute unit; 0: never).  Process-wide host state; lets the tests run both
  *   kernels on the same small inputs.  Returns OZIMMU_BAD_ARG for a negative value.
+ * ozimmu_debug_panel_bytes: when k has to be cut into blocks, C is computed one column panel after the other so
+ *   that the int64 totals of a panel take about `bytes` (default 1 GiB; <= 0: all of C at once).  Changes what
+ *   ozimmu_workspace_bytes* return: set it before sizing the workspace.  Process-wide host state.
  * ozimmu_debug_slice_product: P[i + j*m] = sum_{kk = k0}^{k1-1} A_(l)[i,kk] B^(h)[kk,j] as int32
  *   for one pair (l, h), 1-based, over the contraction range [k0, k1) with k0 a multiple of 32
  *   and (k1-k0) * 127^2 < 2^31, produced by the generic (pair-by-pair) GEMM kernel.
  */
 int ozimmu_debug_diagonals(int m, int n, int k, int s, const void *workspace, int32_t *D, void *stream);
 int ozimmu_debug_small_tile_limit(long long tiles);
+int ozimmu_debug_panel_bytes(long long bytes);
 int ozimmu_debug_slice_product(int m, int n, int k, int s, const void *workspace, int l, int h,
                                int k0, int k1, int32_t *P, void *stream);
 

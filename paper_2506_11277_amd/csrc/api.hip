@@ -335,6 +335,12 @@ int ozimmu_get_exponents(int m, int n, int k, int s, const void *workspace, int3
     return OZIMMU_OK;
 }
 
+int ozimmu_debug_panel_bytes(long long bytes)
+{
+    fused_set_panel_bytes(bytes);
+    return OZIMMU_OK;
+}
+
 int ozimmu_debug_small_tile_limit(long long tiles)
 {
     if (tiles < 0) return OZIMMU_BAD_ARG;

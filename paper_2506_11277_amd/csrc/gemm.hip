@@ -611,11 +611,28 @@ bool fused_single_block(int sA, int sB, int k)
     return fused_handles(sA, sB, false) && (long long)sm * (long long)(k > 0 ? k : 1) <= kMaxInt32K;
 }
 
+// Split-k runs over column panels of C, one after the other, so that the totals of a panel (8 bytes per diagonal
+// and entry) stay near kPanelBytes whatever the size of C: columns per panel, a multiple of the padding.
+long long g_panel_bytes = 1LL << 30;
+void fused_set_panel_bytes(long long bytes) { g_panel_bytes = bytes > 0 ? bytes : (1LL << 62); }
+
+static int fused_panel_cols(int diagonals, int m, int n)
+{
+    const long long mp = round_up(m > 0 ? m : 1, kPad), np = round_up(n > 0 ? n : 1, kPad);
+    long long w = g_panel_bytes / (8LL * mp * diagonals) / kPad * kPad;
+    if (w < kPad) w = kPad;
+    return (int)(w < np ? w : np);
+}
+
 size_t fused_totals_bytes(int sA, int sB, bool all_products, int m, int n, int k)
 {
     if (!fused_handles(sA, sB, all_products) || fused_single_block(sA, sB, k) || m <= 0 || n <= 0) return 0;
     const bool all = all_products && sA > 1;
     const int s = all ? 2 * sA - 1 : (sA > sB ? sA : sB);        // diagonals; the tile shape is tabulated by them
+    {
+        const int w = fused_panel_cols(s, m, n);
+        if (w < n) n = w;
+    }
     int tm = 128, tn = 128;
     if (sA == sB && !all && fused16_preferred(s)) fused16_tile(s, tm, tn);
     else switch (s) {
@@ -627,12 +644,35 @@ size_t fused_totals_bytes(int sA, int sB, bool all_products, int m, int n, int k
     return tiles * (size_t)s * tm * tn * sizeof(long long);
 }
 
+static hipError_t launch_gemm_fused_once(int m, int n, int kp, int sA, int sB, bool all_products, const int8_t *pA,
+                                         const int8_t *pB, const int32_t *eA, const int32_t *eB, double *C, int ldc,
+                                         int32_t *dump, long long *totals, int Q, hipStream_t st);
+
 hipError_t launch_gemm_fused(int m, int n, int kp, int sA, int sB, bool all_products, const int8_t *pA,
                              const int8_t *pB, const int32_t *eA, const int32_t *eB, double *C, int ldc,
                              int32_t *dump, long long *totals, int Q, hipStream_t st)
 {
     if (m <= 0 || n <= 0) return hipSuccess;
     if (!fused_handles(sA, sB, all_products)) return hipErrorInvalidValue;
+    if (!totals) return launch_gemm_fused_once(m, n, kp, sA, sB, all_products, pA, pB, eA, eB, C, ldc, dump, totals, Q, st);
+    // split-k: one column panel of C after the other, all through the same totals buffer
+    const int diagonals = all_products && sA > 1 ? 2 * sA - 1 : (sA > sB ? sA : sB);
+    const int w = fused_panel_cols(diagonals, m, n);
+    const size_t frag_row_bytes = (size_t)(kp / kFrag) * sB * kFragBytes;      // one 32-column fragment row of B
+    for (int c0 = 0; c0 < n; c0 += w) {
+        const int nc = n - c0 < w ? n - c0 : w;
+        hipError_t e = launch_gemm_fused_once(m, nc, kp, sA, sB, all_products, pA, pB + (size_t)(c0 / kFrag) * frag_row_bytes,
+                                              eA, eB + c0, C + (size_t)c0 * ldc, ldc, dump, totals, Q, st);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+static hipError_t launch_gemm_fused_once(int m, int n, int kp, int sA, int sB, bool all_products, const int8_t *pA,
+                                         const int8_t *pB, const int32_t *eA, const int32_t *eB, double *C, int ldc,
+                                         int32_t *dump, long long *totals, int Q, hipStream_t st)
+{
+    if (m <= 0 || n <= 0) return hipSuccess;
     if (all_products && sA > 1) {
         if (dump) return hipErrorInvalidValue;
         if (totals) return dispatch_fused_all<kBlocked>(sA, m, n, kp, pA, pB, eA, eB, C, ldc, totals, Q, st);

@@ -106,6 +106,8 @@ hipError_t launch_split_both(int m, int n, int k, const double *A, int lda, cons
 int fused_max_slices();
 // problems with fewer tiles of the tabulated shape than this use the 64 x 64 tile (default 256; 0: never)
 void fused_set_small_tile_limit(long long tiles);
+// bytes of split-k totals per column panel of C (default 1 GiB; <= 0: no panels); affects fused_totals_bytes
+void fused_set_panel_bytes(long long bytes);
 // true when the fused kernel computes this product set: the reduced set with equal counts <= fused_max_slices()
 // (20) or different counts <= 18, or all products of equal counts with 2 s - 1 <= 18 diagonals
 bool fused_handles(int sA, int sB, bool all_products);

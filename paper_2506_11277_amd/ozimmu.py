@@ -52,6 +52,7 @@ _SIGNATURES = {
     "ozimmu_measure_int8_ceiling2": (_c.c_int, [_c.c_int, _c.c_int, _c.c_void_p, _c.POINTER(_c.c_float), _c.c_void_p]),
     "ozimmu_measure_int8_ceiling": (_c.c_int, [_c.c_int, _c.c_void_p, _c.POINTER(_c.c_float), _c.c_void_p]),
     "ozimmu_debug_small_tile_limit": (_c.c_int, [_c.c_longlong]),
+    "ozimmu_debug_panel_bytes": (_c.c_int, [_c.c_longlong]),
     "ozimmu_debug_diagonals": (_c.c_int, [_c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_void_p, _c.c_void_p,
                                           _c.c_void_p]),
     "ozimmu_debug_slice_product": (_c.c_int, [_c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_void_p, _c.c_int,
@@ -333,6 +334,11 @@ def debug_small_tile_limit(tiles):
     rc = lib().ozimmu_debug_small_tile_limit(int(tiles))
     if rc != OK:
         raise OzimmuError(rc, "debug_small_tile_limit")
+
+
+def debug_panel_bytes(nbytes):
+    """Test hook: bytes of split-k totals per column panel of C (<= 0: no panels); set before sizing workspaces."""
+    lib().ozimmu_debug_panel_bytes(int(nbytes))
 
 
 def debug_diagonals(m, n, k, s, workspace):

@@ -609,3 +609,20 @@ def test_transposed_problem_gives_the_transposed_result(sA, sB, allp, nearest, Q
     Ct = host(ozimmu.dgemm3(dev(B.T.copy()), dev(A.T.copy()), sB, sA, allp, sp, Q))
     assert np.array_equal(C, Ct.T)
     assert_c_matches(C, oracle.dgemm3(A, B, sA, sB, full=allp, nearest=nearest, Q=Q), "transposition")
+
+
+@pytest.mark.parametrize("sA,sB,allp", [(7, 7, False), (4, 4, False), (16, 16, False), (5, 11, False), (6, 6, True)])
+def test_split_k_over_column_panels(sA, sB, allp):
+    # totals budget of one byte: panels of 128 columns, so n = 300 takes three panels (the last one ragged)
+    m, n = 130, 300
+    k = (133144 // min(sA, sB)) * 5 // 2
+    A, B = workloads.lognormal(m, n, k, 2.0, 30 + sA)
+    want = oracle.dgemm3(A, B, sA, sB, full=allp)
+    try:
+        ozimmu.debug_panel_bytes(1)
+        small_ws = ozimmu.lib().ozimmu_workspace_bytes2(m, n, k, sA, sB, int(allp))
+        got = host(ozimmu.dgemm2(dev(A), dev(B), sA, sB, allp))
+    finally:
+        ozimmu.debug_panel_bytes(1 << 30)
+    assert small_ws < ozimmu.lib().ozimmu_workspace_bytes2(m, n, k, sA, sB, int(allp))
+    assert_c_matches(got, want, "column panels")
