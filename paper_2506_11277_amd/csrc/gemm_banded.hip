@@ -19,9 +19,11 @@
 //
 // int32 safety: a diagonal receives at most LA products per sweep.  If all sweeps of a group together
 // stay below 133144 terms per accumulator, int32 suffices (TOTALS = false).  Otherwise (TOTALS) k is
-// cut into blocks of at most 133144 / LA terms and after every block the accumulators are added,
-// exactly, into int64 totals and restart from zero; the totals live in a scratch slot per work-group
-// (the grid is persistent, so the scratch does not grow with the matrix).
+// cut into blocks of at most 133144 / LA terms; the kernel keeps a bound on the terms an accumulator
+// has received and, whenever one more block could pass 133144, adds the accumulators, exactly, into
+// int64 totals and restarts them from zero (at k = 8192 that is after every fourth sweep, not after
+// each one).  The totals live in a scratch slot per work-group (the grid is persistent, so the scratch
+// does not grow with the matrix).
 #include "gemm_dev.h"
 
 namespace oz {
@@ -95,6 +97,7 @@ __global__ __launch_bounds__(64 * kWVM * kWVN) void gemm_banded_kernel(
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[a][r] = 0;
             bool have_totals = false;
+            int terms = 0;                      // products x k summed into an accumulator since the last flush (bound)
 
             const int x_lo = d0 - sY > 1 ? d0 - sY : 1;
             const int x_hi = dlast - 1 < sX ? dlast - 1 : sX;
@@ -173,8 +176,10 @@ __global__ __launch_bounds__(64 * kWVM * kWVN) void gemm_banded_kernel(
                         __syncthreads();
                         buf ^= 1;
                     }
-                    if (TOTALS) {
-                        // end of a k-block: int64 totals (+)= accumulators, accumulators restart from zero.
+                    terms += kLA * (b1 - b0) * KB32 * kFrag;
+                    if (TOTALS && terms + kLA * (stages_per_block < nst ? stages_per_block : nst) * KB32 * kFrag > (int)kMaxInt32K) {
+                        terms = 0;
+                        // the next k-block could overflow int32: int64 totals (+)= accumulators, accumulators restart from zero.
                         // (The base is laundered through an empty asm so that the 128 slot addresses are formed
                         // here, when needed, instead of being hoisted into registers for the whole kernel.)
                         long long *tb = tot;
