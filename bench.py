@@ -119,7 +119,7 @@ def main():
         "config": {"workload": args.workload, "m": m, "n": n, "k": k, "slices": s, "slice_pairs": pairs},
         "roofline": {
             # which GEMM kernel the library runs for equal slice counts (see csrc/gemm.hip, launch_gemm_fused)
-            "kernel": ("gemm_fused16_kernel" if s in (4, 5, 7, 8, 9) else "gemm_fused_kernel") if s <= 20
+            "kernel": ("gemm_fused16_kernel" if 4 <= s <= 9 else "gemm_fused_kernel") if s <= 20
                       else "gemm_banded_kernel",
             "bound": "mfma",
             "achieved": int8_tops,

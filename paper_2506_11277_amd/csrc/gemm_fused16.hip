@@ -1,4 +1,4 @@
-// Fused slice-product kernel built on v_mfma_i32_16x16x64_i8 (written for s <= 9, used for s = 4, 5, 7, 8 and 9).
+// Fused slice-product kernel built on v_mfma_i32_16x16x64_i8 (written for s <= 9, used for s = 4 ... 9).
 //
 // Same computation as gemm_fused_kernel in gemm.hip (all s(s+1)/2 products of Algorithm 1, Sect. 3,
 // per-diagonal int32 sums, binary64 accumulation by ascending diagonal), same plane layout, same
@@ -15,6 +15,15 @@
 // single-buffered region and are multiplied FIRST; a barrier then frees that region and the next
 // stage's copy of it is issued, to land while the remaining products run.  The rest of the stage
 // (A slices l < L0, all of B) is double-buffered as before.
+//
+// Main loop.  For the wide tile (s <= 5) it is the plain one: copies of the next stage issued at the top of the
+// stage, operands read where they are used, barrier at the end.  From 6 slices on it is software-pipelined by
+// hand: the operands of a slice are read one slice ahead, both barriers stand at the START of a slice's products
+// (whose operands are then already in registers), the first operands of the next stage are read behind the
+// end-of-stage barrier while the last slice's products run, and the copies of the next stage are issued one or
+// two at a time between the products, from source addresses formed once per wavefront.  No wavefront then leaves
+// the matrix pipe alone for long: counters at s = 7, 8192^3: the pipe is busy 78 % of the cycles instead of 70 %
+// (at a clock that the power limit lowers from 1.94 to 1.82 GHz), 2840 -> 2985 TOP/s.
 #include "gemm_dev.h"
 
 namespace oz {
@@ -37,6 +46,8 @@ struct Cfg16 {
     static constexpr int NBUF = (L0 == S && 3 * P1 <= kLdsBytes && S <= 3) ? 3 : 2;
     static constexpr int LDS = NBUF * P1 + P2;
     static_assert(LDS <= kLdsBytes, "stages do not fit LDS");
+    // main loop: the software-pipelined schedule (below) from 6 slices on, the plain one for the wide tile
+    static constexpr bool PIPELINED = !WIDE;
 };
 
 template <int S, int MODE>
@@ -68,35 +79,6 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
     const int8_t *rowA = pA + (size_t)tm * FA * row_bytes;
     const int8_t *rowB = pB + (size_t)tn * FB * row_bytes;
 
-    // stage `st` covers 32-k blocks 2*st and 2*st+1
-    auto issue_p1 = [&](int st, int buf) {
-#pragma unroll
-        for (int i = 0; i < (U1 + NW - 1) / NW; ++i) {
-            const int u = wave + i * NW;
-            if (u >= U1) break;
-            const int8_t *src;
-            if (u < U1A) {
-                const int c = u / (2 * L0), l = (u / 2) % L0, kk = u % 2;
-                src = rowA + (size_t)c * row_bytes + ((size_t)(2 * st + kk) * S + l) * kFragBytes;
-            } else {
-                const int v = u - U1A;
-                const int c = v / (2 * S), h = (v / 2) % S, kk = v % 2;
-                src = rowB + (size_t)c * row_bytes + ((size_t)(2 * st + kk) * S + h) * kFragBytes;
-            }
-            lds_dma16(src, lane * 16, lds0 + buf * G::P1 + u * kFragBytes);
-        }
-    };
-    auto issue_p2 = [&](int st) {
-#pragma unroll
-        for (int i = 0; i < (U2 + NW - 1) / NW; ++i) {
-            const int u = wave + i * NW;
-            if (u >= U2) break;
-            const int c = u / (2 * NS2), l = L0 + (u / 2) % NS2, kk = u % 2;
-            const int8_t *src = rowA + (size_t)c * row_bytes + ((size_t)(2 * st + kk) * S + l) * kFragBytes;
-            lds_dma16(src, lane * 16, lds0 + Z + u * kFragBytes);
-        }
-    };
-
     // accumulators: per diagonal a and 32x32 fragment (i, j) four 16x16 blocks (i2, j2)
     v4i acc[S][WMF][WNF][4];
 #pragma unroll
@@ -112,78 +94,264 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
     const int st0 = MODE == kBlocked ? (int)blockIdx.y * stages_per_block : 0;
     const int nst = MODE == kBlocked && st0 + stages_per_block < nst_all ? st0 + stages_per_block : nst_all;
 
-    issue_p1(st0, 0);
-    if (SPLIT) issue_p2(st0);
-    if (NBUF == 3 && nst - st0 > 1) issue_p1(st0 + 1, 1);
-    // (a ring of three keeps one stage in flight; its size per wavefront is (U1 + NW - 1) / NW or one less)
-    constexpr int UPW = U1 / NW, UREM = U1 % NW;
-    const bool extra = wave < UREM;
-    auto wait_keep1 = [&]() {
-        if (extra) wait_vmcnt<UPW + 1>(); else wait_vmcnt<UPW>();
-    };
-    if (NBUF == 3 && nst - st0 > 1) wait_keep1(); else wait_vmcnt<0>();
-    __syncthreads();
+    if constexpr (!G::PIPELINED) {
+        // stage `st` covers 32-k blocks 2*st and 2*st+1
+        auto issue_p1 = [&](int st, int buf) {
+#pragma unroll
+            for (int i = 0; i < (U1 + NW - 1) / NW; ++i) {
+                const int u = wave + i * NW;
+                if (u >= U1) break;
+                const int8_t *src;
+                if (u < U1A) {
+                    const int c = u / (2 * L0), l = (u / 2) % L0, kk = u % 2;
+                    src = rowA + (size_t)c * row_bytes + ((size_t)(2 * st + kk) * S + l) * kFragBytes;
+                } else {
+                    const int v = u - U1A;
+                    const int c = v / (2 * S), h = (v / 2) % S, kk = v % 2;
+                    src = rowB + (size_t)c * row_bytes + ((size_t)(2 * st + kk) * S + h) * kFragBytes;
+                }
+                lds_dma16(src, lane * 16, lds0 + buf * G::P1 + u * kFragBytes);
+            }
+        };
+        auto issue_p2 = [&](int st) {
+#pragma unroll
+            for (int i = 0; i < (U2 + NW - 1) / NW; ++i) {
+                const int u = wave + i * NW;
+                if (u >= U2) break;
+                const int c = u / (2 * NS2), l = L0 + (u / 2) % NS2, kk = u % 2;
+                const int8_t *src = rowA + (size_t)c * row_bytes + ((size_t)(2 * st + kk) * S + l) * kFragBytes;
+                lds_dma16(src, lane * 16, lds0 + Z + u * kFragBytes);
+            }
+        };
 
-    // this lane's part of a 16x64 operand: row lane%16 of the half, k-group g = lane/16
-    // -> fragment kk = g / 2 of the pair, lane slot (row + 32 * (g % 2)) in it
-    const int lofs = ((lane >> 4) >> 1) * kFragBytes + ((lane & 15) + 32 * ((lane >> 4) & 1)) * 16;
+        issue_p1(st0, 0);
+        if (SPLIT) issue_p2(st0);
+        if (NBUF == 3 && nst - st0 > 1) issue_p1(st0 + 1, 1);
+        // (a ring of three keeps one stage in flight; its size per wavefront is (U1 + NW - 1) / NW or one less)
+        constexpr int UPW = U1 / NW, UREM = U1 % NW;
+        const bool extra = wave < UREM;
+        auto wait_keep1 = [&]() {
+            if (extra) wait_vmcnt<UPW + 1>(); else wait_vmcnt<UPW>();
+        };
+        if (NBUF == 3 && nst - st0 > 1) wait_keep1(); else wait_vmcnt<0>();
+        __syncthreads();
 
-    int buf = 0;
-    for (int st = st0; st < nst; ++st) {
-        const bool ahead = st + NBUF - 1 < nst;
-        if (ahead) issue_p1(st + NBUF - 1, buf == 0 ? NBUF - 1 : buf - 1);
-        const unsigned char *cur = lds + buf * G::P1;
+        // this lane's part of a 16x64 operand: row lane%16 of the half, k-group g = lane/16
+        // -> fragment kk = g / 2 of the pair, lane slot (row + 32 * (g % 2)) in it
+        const int lofs = ((lane >> 4) >> 1) * kFragBytes + ((lane & 15) + 32 * ((lane >> 4) & 1)) * 16;
 
-        // (s = 9: only the first HP slices of B are held for the whole stage, the others are read when needed;
-        // everything held needs the last of the 256 registers.  Measured 2860 / 2965 / 3040 / 2660 TOP/s for
-        // HP = 4 / 5 / 6 / 7; with 6 the compiler keeps one loop-invariant 16-byte value in scratch, reloaded
-        // once per stage, and is still the fastest)
-        constexpr int HP = S >= 9 ? 6 : S;
-        v4i bf[HP][WNF][2];
-#pragma unroll
-        for (int h = 0; h < HP; ++h)
-#pragma unroll
-            for (int j = 0; j < WNF; ++j)
-#pragma unroll
-                for (int j2 = 0; j2 < 2; ++j2)
-                    bf[h][j][j2] = *(const v4i *)(cur + (U1A + ((wn * WNF + j) * S + h) * 2) * kFragBytes + lofs + j2 * 256);
+        int buf = 0;
+        for (int st = st0; st < nst; ++st) {
+            const bool ahead = st + NBUF - 1 < nst;
+            if (ahead) issue_p1(st + NBUF - 1, buf == 0 ? NBUF - 1 : buf - 1);
+            const unsigned char *cur = lds + buf * G::P1;
 
-        // slices of A from the last to the first, so that the single-buffered ones (l >= L0) go first
+            // (s = 9: only the first HP slices of B are held for the whole stage, the others are read when needed;
+            // everything held needs the last of the 256 registers.  Measured 2860 / 2965 / 3040 / 2660 TOP/s for
+            // HP = 4 / 5 / 6 / 7; with 6 the compiler keeps one loop-invariant 16-byte value in scratch, reloaded
+            // once per stage, and is still the fastest)
+            constexpr int HP = S >= 9 ? 6 : S;
+            v4i bf[HP][WNF][2];
 #pragma unroll
-        for (int l = S - 1; l >= 0; --l) {
-            v4i af[WMF][2];
+            for (int h = 0; h < HP; ++h)
 #pragma unroll
-            for (int i = 0; i < WMF; ++i)
+                for (int j = 0; j < WNF; ++j)
 #pragma unroll
-                for (int i2 = 0; i2 < 2; ++i2)
-                    af[i][i2] = l >= L0 ? *(const v4i *)(lds + Z + (((wm * WMF + i) * NS2 + (l - L0)) * 2) * kFragBytes +
-                                                          lofs + i2 * 256)
-                                        : *(const v4i *)(cur + (((wm * WMF + i) * L0 + l) * 2) * kFragBytes + lofs + i2 * 256);
+                    for (int j2 = 0; j2 < 2; ++j2)
+                        bf[h][j][j2] = *(const v4i *)(cur + (U1A + ((wn * WNF + j) * S + h) * 2) * kFragBytes + lofs + j2 * 256);
+
+            // slices of A from the last to the first, so that the single-buffered ones (l >= L0) go first
 #pragma unroll
-            for (int h = 0; h < S - l; ++h)
+            for (int l = S - 1; l >= 0; --l) {
+                v4i af[WMF][2];
 #pragma unroll
                 for (int i = 0; i < WMF; ++i)
 #pragma unroll
-                    for (int j = 0; j < WNF; ++j)
+                    for (int i2 = 0; i2 < 2; ++i2)
+                        af[i][i2] = l >= L0 ? *(const v4i *)(lds + Z + (((wm * WMF + i) * NS2 + (l - L0)) * 2) * kFragBytes +
+                                                              lofs + i2 * 256)
+                                            : *(const v4i *)(cur + (((wm * WMF + i) * L0 + l) * 2) * kFragBytes + lofs + i2 * 256);
 #pragma unroll
-                        for (int i2 = 0; i2 < 2; ++i2)
+                for (int h = 0; h < S - l; ++h)
 #pragma unroll
-                            for (int j2 = 0; j2 < 2; ++j2) {
-                                const v4i bv = h < HP ? bf[h < HP ? h : 0][j][j2]
-                                                      : *(const v4i *)(cur + (U1A + ((wn * WNF + j) * S + h) * 2) * kFragBytes +
-                                                                       lofs + j2 * 256);
-                                acc[l + h][i][j][i2 * 2 + j2] = __builtin_amdgcn_mfma_i32_16x16x64_i8(
-                                    bv, af[i][i2], acc[l + h][i][j][i2 * 2 + j2], 0, 0, 0);
-                            }
-            if (SPLIT && l == L0) {
-                // every wavefront is done with the single-buffered slices: refill them for the next stage
-                __syncthreads();
-                if (st + 1 < nst) issue_p2(st + 1);
+                    for (int i = 0; i < WMF; ++i)
+#pragma unroll
+                        for (int j = 0; j < WNF; ++j)
+#pragma unroll
+                            for (int i2 = 0; i2 < 2; ++i2)
+#pragma unroll
+                                for (int j2 = 0; j2 < 2; ++j2) {
+                                    const v4i bv = h < HP ? bf[h < HP ? h : 0][j][j2]
+                                                          : *(const v4i *)(cur + (U1A + ((wn * WNF + j) * S + h) * 2) * kFragBytes +
+                                                                           lofs + j2 * 256);
+                                    acc[l + h][i][j][i2 * 2 + j2] = __builtin_amdgcn_mfma_i32_16x16x64_i8(
+                                        bv, af[i][i2], acc[l + h][i][j][i2 * 2 + j2], 0, 0, 0);
+                                }
+                if (SPLIT && l == L0) {
+                    // every wavefront is done with the single-buffered slices: refill them for the next stage
+                    __syncthreads();
+                    if (st + 1 < nst) issue_p2(st + 1);
+                }
+            }
+            if (NBUF == 3 && ahead) wait_keep1(); else wait_vmcnt<0>();
+            __syncthreads();
+            buf = buf + 1 == NBUF ? 0 : buf + 1;
+        }
+    } else {
+        // Copy units of this wavefront: unit u = wave + i * NW of a region, its source address for stage 0 formed once
+        // here (a stage advances every source by STG bytes), so that a copy inside the loop costs a 64-bit add and
+        // the instruction itself.
+        static_assert(NBUF == 2, "ring of two");
+        constexpr int NU1 = (U1 + NW - 1) / NW, NU2 = SPLIT ? (U2 + NW - 1) / NW : 0;
+        constexpr size_t STG = (size_t)2 * S * kFragBytes;
+        const int8_t *src1[NU1], *src2[NU2 ? NU2 : 1];
+#pragma unroll
+        for (int i = 0; i < NU1; ++i) {
+            const int u = wave + i * NW;
+            if (u < U1A) {
+                const int c = u / (2 * L0), l = (u / 2) % L0, kk = u % 2;
+                src1[i] = rowA + (size_t)c * row_bytes + (size_t)(kk * S + l) * kFragBytes;
+            } else {
+                const int v = u - U1A;
+                const int c = v / (2 * S), h = (v / 2) % S, kk = v % 2;
+                src1[i] = rowB + (size_t)c * row_bytes + (size_t)(kk * S + h) * kFragBytes;
             }
         }
-        if (NBUF == 3 && ahead) wait_keep1(); else wait_vmcnt<0>();
+#pragma unroll
+        for (int i = 0; i < NU2; ++i) {
+            const int u = wave + i * NW;
+            const int c = u / (2 * NS2), l = L0 + (u / 2) % NS2, kk = u % 2;
+            src2[i] = rowA + (size_t)c * row_bytes + (size_t)(kk * S + l) * kFragBytes;
+        }
+        // unit i of the double-buffered part (issue1) / of the single-buffered part (issue2) of stage st
+        auto issue1 = [&](int i, int st, int buf) {
+            if (i < U1 / NW || wave < U1 % NW)
+                lds_dma16(src1[i] + (size_t)st * STG, lane * 16, lds0 + buf * G::P1 + (wave + i * NW) * kFragBytes);
+        };
+        auto issue2 = [&](int i, int st) {
+            if (i < U2 / NW || wave < U2 % NW)
+                lds_dma16(src2[i] + (size_t)st * STG, lane * 16, lds0 + Z + (wave + i * NW) * kFragBytes);
+        };
+
+#pragma unroll
+        for (int i = 0; i < NU1; ++i) issue1(i, st0, 0);
+#pragma unroll
+        for (int i = 0; i < NU2; ++i) issue2(i, st0);
+        wait_vmcnt<0>();
         __syncthreads();
-        buf = buf + 1 == NBUF ? 0 : buf + 1;
+
+        // this lane's part of a 16x64 operand: row lane%16 of the half, k-group g = lane/16
+        // -> fragment kk = g / 2 of the pair, lane slot (row + 32 * (g % 2)) in it
+        const int lofs = ((lane >> 4) >> 1) * kFragBytes + ((lane & 15) + 32 * ((lane >> 4) & 1)) * 16;
+        auto readA = [&](int l, const unsigned char *stage, int i, int i2) -> v4i {
+            return l >= L0 ? *(const v4i *)(lds + Z + (((wm * WMF + i) * NS2 + (l - L0)) * 2) * kFragBytes + lofs + i2 * 256)
+                           : *(const v4i *)(stage + (((wm * WMF + i) * L0 + l) * 2) * kFragBytes + lofs + i2 * 256);
+        };
+        auto readB = [&](int h, const unsigned char *stage, int j, int j2) -> v4i {
+            return *(const v4i *)(stage + (U1A + ((wn * WNF + j) * S + h) * 2) * kFragBytes + lofs + j2 * 256);
+        };
+
+        // Schedule of a stage.  The slices of A go from the last to the first (the single-buffered ones, l >= L0,
+        // first); the operands of slice l - 1 (its A fragments, the one B slice it needs beyond those of slice l) are
+        // read while the products of slice l run.  Once the fragments of slice L0 - 1 are the next to be read nobody
+        // needs the single-buffered region any more (mid-stage barrier, at the START of slice L0), and when the
+        // products of slice 0 begin every read of the stage is done: the end-of-stage barrier stands there, and the
+        // first operands of the NEXT stage are read while the products of slice 0 run.  The copies of the next stage
+        // are issued one or two at a time between the products (double-buffered part before the mid-stage barrier, the
+        // single-buffered part after it), so that no wavefront leaves the matrix pipe alone for long.
+        // (s = 9: only the first HP slices of B are held in registers, the others are read when needed; at slice 0
+        // they are needed first, so that the end-of-stage barrier still follows the last read.)
+        constexpr int HP = S >= 9 ? 6 : S;
+        constexpr int NSLOT = S * (S - 1) / 2;                                  // products of the slices l > 0
+        constexpr int NPRE = SPLIT ? (S - L0 - 1) * (S - L0) / 2 : NSLOT;        // ... of them before the mid-stage barrier
+        constexpr int PER1 = (NU1 + NSLOT / 2 - 1) / (NSLOT / 2) > 2 ? (NU1 + NSLOT / 2 - 1) / (NSLOT / 2) : 2;
+        static_assert(NSLOT * PER1 >= NU1 && (!SPLIT || NSLOT - NPRE >= NU2), "too few products to issue the copies behind");
+        v4i bf[HP][WNF][2], af[WMF][2];
+#pragma unroll
+        for (int i = 0; i < WMF; ++i)
+#pragma unroll
+            for (int i2 = 0; i2 < 2; ++i2) af[i][i2] = readA(S - 1, lds, i, i2);
+#pragma unroll
+        for (int j = 0; j < WNF; ++j)
+#pragma unroll
+            for (int j2 = 0; j2 < 2; ++j2) bf[0][j][j2] = readB(0, lds, j, j2);
+
+        int buf = 0;
+        for (int st = st0; st < nst; ++st) {
+            const bool more = st + 1 < nst;
+            const unsigned char *cur = lds + buf * G::P1, *nxt = lds + (buf ^ 1) * G::P1;
+            v4i afn[WMF][2], bfn[WNF][2];
+            int slot = 0;
+#pragma unroll
+            for (int l = S - 1; l >= 0; --l) {
+                if (SPLIT && l == L0) __syncthreads();
+                if (l > 0) {
+#pragma unroll
+                    for (int i = 0; i < WMF; ++i)
+#pragma unroll
+                        for (int i2 = 0; i2 < 2; ++i2) afn[i][i2] = readA(l - 1, cur, i, i2);
+                    if (S - l < HP) {
+#pragma unroll
+                        for (int j = 0; j < WNF; ++j)
+#pragma unroll
+                            for (int j2 = 0; j2 < 2; ++j2) bf[S - l < HP ? S - l : 0][j][j2] = readB(S - l, cur, j, j2);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);      // (the reads stay ahead of the products they hide behind)
+                }
+#pragma unroll
+                for (int hh = 0; hh < S - l; ++hh) {
+                    const int h = l == 0 ? S - 1 - hh : hh;
+                    if (l == 0 && h == HP - 1) {
+                        // nothing of this stage is left to read, and the next one must have landed
+                        wait_vmcnt<0>();
+                        __syncthreads();
+                        if (more) {
+#pragma unroll
+                            for (int i = 0; i < WMF; ++i)
+#pragma unroll
+                                for (int i2 = 0; i2 < 2; ++i2) afn[i][i2] = readA(S - 1, nxt, i, i2);
+#pragma unroll
+                            for (int j = 0; j < WNF; ++j)
+#pragma unroll
+                                for (int j2 = 0; j2 < 2; ++j2) bfn[j][j2] = readB(0, nxt, j, j2);
+                        }
+                    }
+#pragma unroll
+                    for (int i = 0; i < WMF; ++i)
+#pragma unroll
+                        for (int j = 0; j < WNF; ++j)
+#pragma unroll
+                            for (int i2 = 0; i2 < 2; ++i2)
+#pragma unroll
+                                for (int j2 = 0; j2 < 2; ++j2) {
+                                    const v4i bv = h < HP ? bf[h < HP ? h : 0][j][j2] : readB(h, cur, j, j2);
+                                    acc[l + h][i][j][i2 * 2 + j2] = __builtin_amdgcn_mfma_i32_16x16x64_i8(
+                                        bv, af[i][i2], acc[l + h][i][j][i2 * 2 + j2], 0, 0, 0);
+                                }
+                    if (l > 0 && more) {
+                        if (SPLIT && slot >= NPRE && slot - NPRE < NU2) issue2(slot - NPRE, st + 1);
+#pragma unroll
+                        for (int q = 0; q < PER1; ++q)
+                            if (slot * PER1 + q < NU1) issue1(slot * PER1 + q, st + 1, buf ^ 1);
+                    }
+                    ++slot;
+                }
+                __builtin_amdgcn_sched_barrier(0);          // (and no product of the next slice moves up to wait for them)
+                if (l > 0 || more) {
+#pragma unroll
+                    for (int i = 0; i < WMF; ++i)
+#pragma unroll
+                        for (int i2 = 0; i2 < 2; ++i2) af[i][i2] = afn[i][i2];
+                }
+            }
+            if (more) {
+#pragma unroll
+                for (int j = 0; j < WNF; ++j)
+#pragma unroll
+                    for (int j2 = 0; j2 < 2; ++j2) bf[0][j][j2] = bfn[j][j2];
+            }
+            buf ^= 1;
+        }
     }
 
     // element of accumulator block (i2, j2), register r: m_local = 16*i2 + lane%16, n_local = 16*j2 + 4*(lane/16) + r
@@ -341,7 +509,7 @@ hipError_t dispatch16(int s, int m, int n, int kp, const int8_t *pA, const int8_
     switch (s) {
 #define OZ_CASE(S_) \
     case S_: return launch16_s<S_, MODE>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, Q, st);
-        OZ_CASE(4) OZ_CASE(5) OZ_CASE(7) OZ_CASE(8) OZ_CASE(9)
+        OZ_CASE(4) OZ_CASE(5) OZ_CASE(6) OZ_CASE(7) OZ_CASE(8) OZ_CASE(9)
 #undef OZ_CASE
     }
     return hipErrorInvalidValue;
@@ -350,10 +518,10 @@ hipError_t dispatch16(int s, int m, int n, int kp, const int8_t *pA, const int8_
 }  // namespace
 
 // Slice counts for which this kernel is the faster one at 8192^3 (s = 4: +10 %, s = 5: +7.5 % with the wide
-// tile, s = 7: +6.5 %, s = 8: +12 %, s = 9: +6.7 %).  At s = 6 the wide tile does not fit the registers and the
-// narrow one is no faster; beyond 9 a 64-deep stage of a 128 x 64 tile does not fit LDS; the 32x32x32 kernel
-// wins at 2 and 3.  Only the preferred ones are instantiated.
-bool fused16_preferred(int s) { return s == 4 || s == 5 || (s >= 7 && s <= 9); }
+// tile, s = 6 ... 9 with the pipelined schedule: +5 %, +12 %, +15 %, +11 % over the 32x32x32 kernel).  With split-k
+// (long contractions) the wide 32x32x32 tile stays ahead at s = 6; beyond 9 a 64-deep stage of a 128 x 64 tile
+// does not fit LDS; the 32x32x32 kernel wins at 2 and 3.  Only the preferred ones are instantiated.
+bool fused16_preferred(int s, bool split_k) { return s >= 4 && s <= 9 && !(s == 6 && split_k); }
 
 void fused16_tile(int s, int &tm, int &tn)
 {
