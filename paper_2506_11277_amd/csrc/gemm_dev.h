@@ -30,11 +30,21 @@ __device__ __forceinline__ void tile_of_block(int b, int nb, int tiles_m, int ti
 
 // 16 bytes per lane: global (sbase + voff)  ->  LDS (ldsaddr + lane * 16); ldsaddr is wavefront-uniform.
 // (global_load_lds: the LDS-DMA form of the vector load, 1 KiB per wavefront instruction; issued
-// from inline asm, so the waits on these loads (vmcnt) are placed by hand)
+// from inline asm, so the waits on these loads (vmcnt) are placed by hand, and so is the wait state between the
+// scalar write of m0 and its use)
 __device__ __forceinline__ void lds_dma16(const void *sbase, unsigned voff, unsigned ldsaddr)
 {
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(ldsaddr), "v"(voff), "s"(sbase)
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(ldsaddr), "v"(voff), "s"(sbase)
                  : "memory", "m0");
+}
+
+// The same copy with the LDS address given as wavefront-uniform base + compile-time constant (one scalar add
+// straight into m0).
+template <int IMM>
+__device__ __forceinline__ void lds_dma16_at(const void *sbase, unsigned voff, unsigned ldsbase)
+{
+    asm volatile("s_add_u32 m0, %0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3" ::"s"(ldsbase), "n"(IMM), "v"(voff), "s"(sbase)
+                 : "memory", "m0", "scc");
 }
 
 template <int N>

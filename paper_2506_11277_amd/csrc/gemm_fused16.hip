@@ -20,10 +20,14 @@
 // stage, operands read where they are used, barrier at the end.  From 6 slices on it is software-pipelined by
 // hand: the operands of a slice are read one slice ahead, both barriers stand at the START of a slice's products
 // (whose operands are then already in registers), the first operands of the next stage are read behind the
-// end-of-stage barrier while the last slice's products run, and the copies of the next stage are issued one or
-// two at a time between the products, from source addresses formed once per wavefront.  No wavefront then leaves
-// the matrix pipe alone for long: counters at s = 7, 8192^3: the pipe is busy 78 % of the cycles instead of 70 %
-// (at a clock that the power limit lowers from 1.94 to 1.82 GHz), 2840 -> 2985 TOP/s.
+// end-of-stage barrier while the last slice's products run, and the copies of the next stage are issued one at a
+// time behind single matrix instructions -- two instructions each: the source addresses are formed once per
+// wavefront, the stage travels in the 32-bit lane offset, the LDS address is one scalar add into m0 -- and
+// the loop body has no branch but a ragged last copy.  Measured at 8192^3 against the plain loop: s = 7
+// 2840 -> 3195 TOP/s, s = 9 3065 -> 3420 (the matrix pipe busy 78 % and more of the cycles instead of 70 %, at a
+// clock that the power limit lowers accordingly).
+#include <type_traits>
+
 #include "gemm_dev.h"
 
 namespace oz {
@@ -223,20 +227,42 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
             const int c = u / (2 * NS2), l = L0 + (u / 2) % NS2, kk = u % 2;
             src2[i] = rowA + (size_t)c * row_bytes + (size_t)(kk * S + l) * kFragBytes;
         }
-        // unit i of the double-buffered part (issue1) / of the single-buffered part (issue2) of stage st
-        auto issue1 = [&](int i, int st, int buf) {
-            if (i < U1 / NW || wave < U1 % NW)
-                lds_dma16(src1[i] + (size_t)st * STG, lane * 16, lds0 + buf * G::P1 + (wave + i * NW) * kFragBytes);
+        // Unit I of the double-buffered part (issue1) / of the single-buffered part (issue2): `voff` carries the
+        // stage (lane * 16 + stage * STG: the host admits only contractions for which that fits 31 bits), `ldsw` the
+        // ring buffer and the wavefront.  Two instructions per copy.
+        const unsigned ldsw = lds0 + wave * kFragBytes;
+        auto issue1 = [&](auto I, unsigned voff, unsigned ldsbuf) {
+            constexpr int i = decltype(I)::value;
+            if (i < U1 / NW || wave < U1 % NW) lds_dma16_at<i * NW * kFragBytes>(src1[i], voff, ldsbuf);
         };
-        auto issue2 = [&](int i, int st) {
-            if (i < U2 / NW || wave < U2 % NW)
-                lds_dma16(src2[i] + (size_t)st * STG, lane * 16, lds0 + Z + (wave + i * NW) * kFragBytes);
+        auto issue2 = [&](auto I, unsigned voff) {
+            constexpr int i = decltype(I)::value;
+            if (i < U2 / NW || wave < U2 % NW) lds_dma16_at<Z + i * NW * kFragBytes>(src2[i], voff, ldsw);
         };
+        // (compile-time dispatch on the unit number)
+        auto issue1_n = [&](int i, unsigned voff, unsigned ldsbuf) {
+            switch (i) {
+#define OZ_U(N_) case N_: if constexpr (N_ < NU1) issue1(std::integral_constant<int, N_>{}, voff, ldsbuf); break;
+                OZ_U(0) OZ_U(1) OZ_U(2) OZ_U(3) OZ_U(4) OZ_U(5) OZ_U(6) OZ_U(7) OZ_U(8) OZ_U(9) OZ_U(10) OZ_U(11)
+#undef OZ_U
+            }
+        };
+        auto issue2_n = [&](int i, unsigned voff) {
+            switch (i) {
+#define OZ_U(N_) case N_: if constexpr (N_ < NU2) issue2(std::integral_constant<int, N_>{}, voff); break;
+                OZ_U(0) OZ_U(1) OZ_U(2) OZ_U(3) OZ_U(4) OZ_U(5) OZ_U(6) OZ_U(7) OZ_U(8) OZ_U(9) OZ_U(10) OZ_U(11)
+#undef OZ_U
+            }
+        };
+        static_assert(NU1 <= 12 && NU2 <= 12, "unit dispatch");
 
+        {
+            const unsigned v0 = lane * 16 + (unsigned)st0 * (unsigned)STG;
 #pragma unroll
-        for (int i = 0; i < NU1; ++i) issue1(i, st0, 0);
+            for (int i = 0; i < NU1; ++i) issue1_n(i, v0, ldsw);
 #pragma unroll
-        for (int i = 0; i < NU2; ++i) issue2(i, st0);
+            for (int i = 0; i < NU2; ++i) issue2_n(i, v0);
+        }
         wait_vmcnt<0>();
         __syncthreads();
 
@@ -264,8 +290,8 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
         constexpr int HP = S >= 9 ? 6 : S;
         constexpr int NSLOT = S * (S - 1) / 2;                                  // products of the slices l > 0
         constexpr int NPRE = SPLIT ? (S - L0 - 1) * (S - L0) / 2 : NSLOT;        // ... of them before the mid-stage barrier
-        constexpr int PER1 = (NU1 + NSLOT / 2 - 1) / (NSLOT / 2) > 2 ? (NU1 + NSLOT / 2 - 1) / (NSLOT / 2) : 2;
-        static_assert(NSLOT * PER1 >= NU1 && (!SPLIT || NSLOT - NPRE >= NU2), "too few products to issue the copies behind");
+        constexpr int MPP = 4 * WMF * WNF;                                       // matrix instructions per product
+        static_assert(NU1 <= NPRE * MPP && (!SPLIT || NU2 <= (NSLOT - NPRE) * MPP), "too few products to issue the copies behind");
         v4i bf[HP][WNF][2], af[WMF][2];
 #pragma unroll
         for (int i = 0; i < WMF; ++i)
@@ -278,7 +304,11 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
 
         int buf = 0;
         for (int st = st0; st < nst; ++st) {
+            // (in the last stage the copies and the reads ahead go on, of that stage again: nobody uses them, and
+            // the loop stays free of branches)
             const bool more = st + 1 < nst;
+            const unsigned vnext = lane * 16 + (unsigned)(more ? st + 1 : st) * (unsigned)STG;
+            const unsigned ldsnext = ldsw + (buf ^ 1) * G::P1;
             const unsigned char *cur = lds + buf * G::P1, *nxt = lds + (buf ^ 1) * G::P1;
             v4i afn[WMF][2], bfn[WNF][2];
             int slot = 0;
@@ -305,16 +335,14 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
                         // nothing of this stage is left to read, and the next one must have landed
                         wait_vmcnt<0>();
                         __syncthreads();
-                        if (more) {
 #pragma unroll
-                            for (int i = 0; i < WMF; ++i)
+                        for (int i = 0; i < WMF; ++i)
 #pragma unroll
-                                for (int i2 = 0; i2 < 2; ++i2) afn[i][i2] = readA(S - 1, nxt, i, i2);
+                            for (int i2 = 0; i2 < 2; ++i2) afn[i][i2] = readA(S - 1, nxt, i, i2);
 #pragma unroll
-                            for (int j = 0; j < WNF; ++j)
+                        for (int j = 0; j < WNF; ++j)
 #pragma unroll
-                                for (int j2 = 0; j2 < 2; ++j2) bfn[j][j2] = readB(0, nxt, j, j2);
-                        }
+                            for (int j2 = 0; j2 < 2; ++j2) bfn[j][j2] = readB(0, nxt, j, j2);
                     }
 #pragma unroll
                     for (int i = 0; i < WMF; ++i)
@@ -327,29 +355,24 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
                                     const v4i bv = h < HP ? bf[h < HP ? h : 0][j][j2] : readB(h, cur, j, j2);
                                     acc[l + h][i][j][i2 * 2 + j2] = __builtin_amdgcn_mfma_i32_16x16x64_i8(
                                         bv, af[i][i2], acc[l + h][i][j][i2 * 2 + j2], 0, 0, 0);
+                                    // one copy of the next stage behind each of the first matrix instructions of
+                                    // the stage (double-buffered part) / after the mid-stage barrier (the rest)
+                                    const int e = slot * MPP + ((i * WNF + j) * 2 + i2) * 2 + j2;
+                                    if (e < NU1) issue1_n(e, vnext, ldsnext);
+                                    if (SPLIT && e >= NPRE * MPP && e - NPRE * MPP < NU2) issue2_n(e - NPRE * MPP, vnext);
                                 }
-                    if (l > 0 && more) {
-                        if (SPLIT && slot >= NPRE && slot - NPRE < NU2) issue2(slot - NPRE, st + 1);
-#pragma unroll
-                        for (int q = 0; q < PER1; ++q)
-                            if (slot * PER1 + q < NU1) issue1(slot * PER1 + q, st + 1, buf ^ 1);
-                    }
                     ++slot;
                 }
                 __builtin_amdgcn_sched_barrier(0);          // (and no product of the next slice moves up to wait for them)
-                if (l > 0 || more) {
 #pragma unroll
-                    for (int i = 0; i < WMF; ++i)
+                for (int i = 0; i < WMF; ++i)
 #pragma unroll
-                        for (int i2 = 0; i2 < 2; ++i2) af[i][i2] = afn[i][i2];
-                }
+                    for (int i2 = 0; i2 < 2; ++i2) af[i][i2] = afn[i][i2];
             }
-            if (more) {
 #pragma unroll
-                for (int j = 0; j < WNF; ++j)
+            for (int j = 0; j < WNF; ++j)
 #pragma unroll
-                    for (int j2 = 0; j2 < 2; ++j2) bf[0][j][j2] = bfn[j][j2];
-            }
+                for (int j2 = 0; j2 < 2; ++j2) bf[0][j][j2] = bfn[j][j2];
             buf ^= 1;
         }
     }
@@ -481,6 +504,7 @@ hipError_t launch16_s(int m, int n, int kp, const int8_t *pA, const int8_t *pB, 
     if (hipError_t e = allow_dynamic_lds((const void *)kern, G::LDS, configured); e != hipSuccess) return e;
     const int tiles_m = (m + TM - 1) / TM, tiles_n = (n + TN - 1) / TN;
     const int KB = kp / kFrag;
+    if ((long long)kp * S * 32 >= (1LL << 31)) return hipErrorInvalidValue;      // (see fused16_preferred)
     if (MODE != kBlocked) {
         kern<<<tiles_m * tiles_n, THREADS, G::LDS, st>>>(pA, pB, eA, eB, C, ldc, m, n, KB, tiles_m, tiles_n, dump,
                                                          nullptr, 0, Q, 0);
@@ -518,10 +542,15 @@ hipError_t dispatch16(int s, int m, int n, int kp, const int8_t *pA, const int8_
 }  // namespace
 
 // Slice counts for which this kernel is the faster one at 8192^3 (s = 4: +10 %, s = 5: +7.5 % with the wide
-// tile, s = 6 ... 9 with the pipelined schedule: +5 %, +12 %, +15 %, +11 % over the 32x32x32 kernel).  With split-k
+// tile, s = 6 ... 9 with the pipelined schedule: +10 %, +17 %, +17 %, +17 % over the 32x32x32 kernel).  With split-k
 // (long contractions) the wide 32x32x32 tile stays ahead at s = 6; beyond 9 a 64-deep stage of a 128 x 64 tile
 // does not fit LDS; the 32x32x32 kernel wins at 2 and 3.  Only the preferred ones are instantiated.
-bool fused16_preferred(int s, bool split_k) { return s >= 4 && s <= 9 && !(s == 6 && split_k); }
+// (Its copies address a fragment row of the planes, kp * s * 32 bytes, with 32-bit offsets: longer contractions
+// stay with the 32x32x32 kernel.)
+bool fused16_preferred(int s, bool split_k, long long kp)
+{
+    return s >= 4 && s <= 9 && !(s == 6 && split_k) && kp * s * 32 < (1LL << 31);
+}
 
 void fused16_tile(int s, int &tm, int &tn)
 {

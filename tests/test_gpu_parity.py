@@ -246,7 +246,7 @@ def test_k_blocked_accumulation_beyond_the_int32_range():
     assert_c_matches(host(ozimmu.dgemm(dev(A), dev(B), 7)), oracle.dgemm(A, B, 7), "k-blocked lognormal")
 
 
-@pytest.mark.parametrize("s", [4, 5, 7, 8, 9, 12, 13, 16, 17, 18, 19, 20])
+@pytest.mark.parametrize("s", [4, 5, 6, 7, 8, 9, 12, 13, 16, 17, 18, 19, 20])
 def test_k_blocked_on_every_fused_kernel(s):
     # the fused kernels (16x16x64 for s = 4, 5, 7, 8, 9; 32x32x32 otherwise, with four 512-register wavefronts beyond
     # s = 12) in split-k mode, several tiles and k-blocks
@@ -260,6 +260,16 @@ def test_k_blocked_on_every_fused_kernel(s):
     A = np.full((m, k), x); A[::3, :] = -x
     B = np.full((k, n), x); B[:, 1::2] *= 0.5
     assert_c_matches(host(ozimmu.dgemm(dev(A), dev(B), s)), oracle.dgemm(A, B, s), f"k-blocked extreme s={s}")
+
+
+def test_contraction_too_long_for_32_bit_plane_offsets():
+    # k * s * 32 >= 2^31 bytes in a fragment row of the planes: the 16x16x64 kernel addresses a row with 32-bit
+    # offsets and must leave such a contraction to the 32x32x32 kernel
+    s = 9
+    k = (1 << 31) // (32 * s) + 1000
+    A, B = workloads.uniform(3, 2, k, 77)
+    print(f"long contraction k={k}", flush=True)
+    assert_c_matches(host(ozimmu.dgemm(dev(A), dev(B), s)), oracle.dgemm(A, B, s), "very long k")
 
 
 def test_runs_are_bit_identical():
