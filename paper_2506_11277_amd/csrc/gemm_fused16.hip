@@ -16,16 +16,14 @@
 // stage's copy of it is issued, to land while the remaining products run.  The rest of the stage
 // (A slices l < L0, all of B) is double-buffered as before.
 //
-// Main loop.  For the wide tile (s <= 5) it is the plain one: copies of the next stage issued at the top of the
-// stage, operands read where they are used, barrier at the end.  From 6 slices on it is software-pipelined by
-// hand: the operands of a slice are read one slice ahead, both barriers stand at the START of a slice's products
-// (whose operands are then already in registers), the first operands of the next stage are read behind the
-// end-of-stage barrier while the last slice's products run, and the copies of the next stage are issued one at a
-// time behind single matrix instructions -- two instructions each: the source addresses are formed once per
-// wavefront, the stage travels in the 32-bit lane offset, the LDS address is one scalar add into m0 -- and
-// the loop body has no branch but a ragged last copy.  Measured at 8192^3 against the plain loop: s = 7
-// 2840 -> 3195 TOP/s, s = 9 3065 -> 3420 (the matrix pipe busy 78 % and more of the cycles instead of 70 %, at a
-// clock that the power limit lowers accordingly).
+// Main loop, software-pipelined by hand: the operands of a slice are read one slice ahead, both barriers stand at
+// the START of a slice's products (whose operands are then already in registers), the first operands of the next
+// stage are read behind the end-of-stage barrier while the last slice's products run, and the copies of the next
+// stage are issued one at a time behind single matrix instructions -- two instructions each: the source addresses
+// are formed once per wavefront, the stage travels in the 32-bit lane offset, the LDS address is one scalar add
+// into m0 -- and the loop body has no branch but a ragged last copy.  (A plain loop -- copies issued at the top of
+// the stage, operands read where they are used, barriers behind the last product -- left the matrix pipe idle
+// 30 % of the cycles at s = 7; this one 20 %, at a clock that the power limit lowers accordingly.)
 #include <type_traits>
 
 #include "gemm_dev.h"
@@ -47,11 +45,8 @@ struct Cfg16 {
     static constexpr int L0 = S <= 6 ? S : S == 7 ? 3 : S == 8 ? 4 : 2;
     static constexpr int P1 = (FA * L0 + FB * S) * 2 * kFragBytes;    // double-buffered part of a 64-k stage
     static constexpr int P2 = FA * (S - L0) * 2 * kFragBytes;         // single-buffered part
-    static constexpr int NBUF = (L0 == S && 3 * P1 <= kLdsBytes && S <= 3) ? 3 : 2;
-    static constexpr int LDS = NBUF * P1 + P2;
+    static constexpr int LDS = 2 * P1 + P2;
     static_assert(LDS <= kLdsBytes, "stages do not fit LDS");
-    // main loop: the software-pipelined schedule (below) from 6 slices on, the plain one for the wide tile
-    static constexpr bool PIPELINED = !WIDE;
 };
 
 template <int S, int MODE>
@@ -62,7 +57,7 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
 {
     using G = Cfg16<S>;
     constexpr int WVM = G::WVM, WVN = G::WVN, WMF = G::WMF, WNF = G::WNF, FA = G::FA, FB = G::FB, L0 = G::L0;
-    constexpr int NW = WVM * WVN, NBUF = G::NBUF;
+    constexpr int NW = WVM * WVN;
     constexpr bool SPLIT = L0 < S;
     constexpr int NS2 = SPLIT ? S - L0 : 1;                         // slices in the single-buffered region
     constexpr bool DUMP = MODE == kDump;
@@ -72,7 +67,7 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
     constexpr int U1A = FA * 2 * L0, U1 = U1A + FB * 2 * S, U2 = FA * 2 * (S - L0);
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds;
-    constexpr int Z = NBUF * G::P1;                                  // offset of the single-buffered region
+    constexpr int Z = 2 * G::P1;                                     // offset of the single-buffered region
 
     int tm, tn;
     tile_of_block(blockIdx.x, gridDim.x, tiles_m, tiles_n, tm, tn);
@@ -98,283 +93,177 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
     const int st0 = MODE == kBlocked ? (int)blockIdx.y * stages_per_block : 0;
     const int nst = MODE == kBlocked && st0 + stages_per_block < nst_all ? st0 + stages_per_block : nst_all;
 
-    if constexpr (!G::PIPELINED) {
-        // stage `st` covers 32-k blocks 2*st and 2*st+1
-        auto issue_p1 = [&](int st, int buf) {
+    // Copy units of this wavefront: unit u = wave + i * NW of a region, its source address for stage 0 formed once
+    // here (a stage advances every source by STG bytes, which the copies carry in their lane offset).
+    constexpr int NU1 = (U1 + NW - 1) / NW, NU2 = SPLIT ? (U2 + NW - 1) / NW : 0;
+    constexpr size_t STG = (size_t)2 * S * kFragBytes;
+    const int8_t *src1[NU1], *src2[NU2 ? NU2 : 1];
 #pragma unroll
-            for (int i = 0; i < (U1 + NW - 1) / NW; ++i) {
-                const int u = wave + i * NW;
-                if (u >= U1) break;
-                const int8_t *src;
-                if (u < U1A) {
-                    const int c = u / (2 * L0), l = (u / 2) % L0, kk = u % 2;
-                    src = rowA + (size_t)c * row_bytes + ((size_t)(2 * st + kk) * S + l) * kFragBytes;
-                } else {
-                    const int v = u - U1A;
-                    const int c = v / (2 * S), h = (v / 2) % S, kk = v % 2;
-                    src = rowB + (size_t)c * row_bytes + ((size_t)(2 * st + kk) * S + h) * kFragBytes;
-                }
-                lds_dma16(src, lane * 16, lds0 + buf * G::P1 + u * kFragBytes);
-            }
-        };
-        auto issue_p2 = [&](int st) {
+    for (int i = 0; i < NU1; ++i) {
+        const int u = wave + i * NW;
+        if (u < U1A) {
+            const int c = u / (2 * L0), l = (u / 2) % L0, kk = u % 2;
+            src1[i] = rowA + (size_t)c * row_bytes + (size_t)(kk * S + l) * kFragBytes;
+        } else {
+            const int v = u - U1A;
+            const int c = v / (2 * S), h = (v / 2) % S, kk = v % 2;
+            src1[i] = rowB + (size_t)c * row_bytes + (size_t)(kk * S + h) * kFragBytes;
+        }
+    }
 #pragma unroll
-            for (int i = 0; i < (U2 + NW - 1) / NW; ++i) {
-                const int u = wave + i * NW;
-                if (u >= U2) break;
-                const int c = u / (2 * NS2), l = L0 + (u / 2) % NS2, kk = u % 2;
-                const int8_t *src = rowA + (size_t)c * row_bytes + ((size_t)(2 * st + kk) * S + l) * kFragBytes;
-                lds_dma16(src, lane * 16, lds0 + Z + u * kFragBytes);
-            }
-        };
+    for (int i = 0; i < NU2; ++i) {
+        const int u = wave + i * NW;
+        const int c = u / (2 * NS2), l = L0 + (u / 2) % NS2, kk = u % 2;
+        src2[i] = rowA + (size_t)c * row_bytes + (size_t)(kk * S + l) * kFragBytes;
+    }
+    // Unit I of the double-buffered part (issue1) / of the single-buffered part (issue2): `voff` carries the
+    // stage (lane * 16 + stage * STG: the host admits only contractions for which that fits 31 bits), `ldsw` the
+    // ring buffer and the wavefront.  Two instructions per copy.
+    const unsigned ldsw = lds0 + wave * kFragBytes;
+    auto issue1 = [&](auto I, unsigned voff, unsigned ldsbuf) {
+        constexpr int i = decltype(I)::value;
+        if (i < U1 / NW || wave < U1 % NW) lds_dma16_at<i * NW * kFragBytes>(src1[i], voff, ldsbuf);
+    };
+    auto issue2 = [&](auto I, unsigned voff) {
+        constexpr int i = decltype(I)::value;
+        if (i < U2 / NW || wave < U2 % NW) lds_dma16_at<Z + i * NW * kFragBytes>(src2[i], voff, ldsw);
+    };
+    // (compile-time dispatch on the unit number)
+    auto issue1_n = [&](int i, unsigned voff, unsigned ldsbuf) {
+        switch (i) {
+#define OZ_U(N_) case N_: if constexpr (N_ < NU1) issue1(std::integral_constant<int, N_>{}, voff, ldsbuf); break;
+            OZ_U(0) OZ_U(1) OZ_U(2) OZ_U(3) OZ_U(4) OZ_U(5) OZ_U(6) OZ_U(7) OZ_U(8) OZ_U(9) OZ_U(10) OZ_U(11)
+#undef OZ_U
+        }
+    };
+    auto issue2_n = [&](int i, unsigned voff) {
+        switch (i) {
+#define OZ_U(N_) case N_: if constexpr (N_ < NU2) issue2(std::integral_constant<int, N_>{}, voff); break;
+            OZ_U(0) OZ_U(1) OZ_U(2) OZ_U(3) OZ_U(4) OZ_U(5) OZ_U(6) OZ_U(7) OZ_U(8) OZ_U(9) OZ_U(10) OZ_U(11)
+#undef OZ_U
+        }
+    };
+    static_assert(NU1 <= 12 && NU2 <= 12, "unit dispatch");
 
-        issue_p1(st0, 0);
-        if (SPLIT) issue_p2(st0);
-        if (NBUF == 3 && nst - st0 > 1) issue_p1(st0 + 1, 1);
-        // (a ring of three keeps one stage in flight; its size per wavefront is (U1 + NW - 1) / NW or one less)
-        constexpr int UPW = U1 / NW, UREM = U1 % NW;
-        const bool extra = wave < UREM;
-        auto wait_keep1 = [&]() {
-            if (extra) wait_vmcnt<UPW + 1>(); else wait_vmcnt<UPW>();
-        };
-        if (NBUF == 3 && nst - st0 > 1) wait_keep1(); else wait_vmcnt<0>();
-        __syncthreads();
-
-        // this lane's part of a 16x64 operand: row lane%16 of the half, k-group g = lane/16
-        // -> fragment kk = g / 2 of the pair, lane slot (row + 32 * (g % 2)) in it
-        const int lofs = ((lane >> 4) >> 1) * kFragBytes + ((lane & 15) + 32 * ((lane >> 4) & 1)) * 16;
-
-        int buf = 0;
-        for (int st = st0; st < nst; ++st) {
-            const bool ahead = st + NBUF - 1 < nst;
-            if (ahead) issue_p1(st + NBUF - 1, buf == 0 ? NBUF - 1 : buf - 1);
-            const unsigned char *cur = lds + buf * G::P1;
-
-            // (s = 9: only the first HP slices of B are held for the whole stage, the others are read when needed;
-            // everything held needs the last of the 256 registers.  Measured 2860 / 2965 / 3040 / 2660 TOP/s for
-            // HP = 4 / 5 / 6 / 7; with 6 the compiler keeps one loop-invariant 16-byte value in scratch, reloaded
-            // once per stage, and is still the fastest)
-            constexpr int HP = S >= 9 ? 6 : S;
-            v4i bf[HP][WNF][2];
+    {
+        const unsigned v0 = lane * 16 + (unsigned)st0 * (unsigned)STG;
 #pragma unroll
-            for (int h = 0; h < HP; ++h)
+        for (int i = 0; i < NU1; ++i) issue1_n(i, v0, ldsw);
 #pragma unroll
-                for (int j = 0; j < WNF; ++j)
-#pragma unroll
-                    for (int j2 = 0; j2 < 2; ++j2)
-                        bf[h][j][j2] = *(const v4i *)(cur + (U1A + ((wn * WNF + j) * S + h) * 2) * kFragBytes + lofs + j2 * 256);
+        for (int i = 0; i < NU2; ++i) issue2_n(i, v0);
+    }
+    wait_vmcnt<0>();
+    __syncthreads();
 
-            // slices of A from the last to the first, so that the single-buffered ones (l >= L0) go first
+    // this lane's part of a 16x64 operand: row lane%16 of the half, k-group g = lane/16
+    // -> fragment kk = g / 2 of the pair, lane slot (row + 32 * (g % 2)) in it
+    const int lofs = ((lane >> 4) >> 1) * kFragBytes + ((lane & 15) + 32 * ((lane >> 4) & 1)) * 16;
+    auto readA = [&](int l, const unsigned char *stage, int i, int i2) -> v4i {
+        return l >= L0 ? *(const v4i *)(lds + Z + (((wm * WMF + i) * NS2 + (l - L0)) * 2) * kFragBytes + lofs + i2 * 256)
+                       : *(const v4i *)(stage + (((wm * WMF + i) * L0 + l) * 2) * kFragBytes + lofs + i2 * 256);
+    };
+    auto readB = [&](int h, const unsigned char *stage, int j, int j2) -> v4i {
+        return *(const v4i *)(stage + (U1A + ((wn * WNF + j) * S + h) * 2) * kFragBytes + lofs + j2 * 256);
+    };
+
+    // Schedule of a stage.  The slices of A go from the last to the first (the single-buffered ones, l >= L0,
+    // first); the operands of slice l - 1 (its A fragments, the one B slice it needs beyond those of slice l) are
+    // read while the products of slice l run.  Once the fragments of slice L0 - 1 are the next to be read nobody
+    // needs the single-buffered region any more (mid-stage barrier, at the START of slice L0), and when the
+    // products of slice 0 begin every read of the stage is done: the end-of-stage barrier stands there, and the
+    // first operands of the NEXT stage are read while the products of slice 0 run.  The copies of the next stage
+    // are issued one or two at a time between the products (double-buffered part before the mid-stage barrier, the
+    // single-buffered part after it), so that no wavefront leaves the matrix pipe alone for long.
+    // (s = 9: only the first HP slices of B are held in registers, the others are read when needed; at slice 0
+    // they are needed first, so that the end-of-stage barrier still follows the last read.)
+    constexpr int HP = S >= 9 ? 7 : S;
+    constexpr int NSLOT = S * (S - 1) / 2;                                  // products of the slices l > 0
+    constexpr int NPRE = SPLIT ? (S - L0 - 1) * (S - L0) / 2 : NSLOT;        // ... of them before the mid-stage barrier
+    constexpr int MPP = 4 * WMF * WNF;                                       // matrix instructions per product
+    static_assert(NU1 <= NPRE * MPP && (!SPLIT || NU2 <= (NSLOT - NPRE) * MPP), "too few products to issue the copies behind");
+    v4i bf[HP][WNF][2], af[WMF][2];
 #pragma unroll
-            for (int l = S - 1; l >= 0; --l) {
-                v4i af[WMF][2];
+    for (int i = 0; i < WMF; ++i)
+#pragma unroll
+        for (int i2 = 0; i2 < 2; ++i2) af[i][i2] = readA(S - 1, lds, i, i2);
+#pragma unroll
+    for (int j = 0; j < WNF; ++j)
+#pragma unroll
+        for (int j2 = 0; j2 < 2; ++j2) bf[0][j][j2] = readB(0, lds, j, j2);
+
+    int buf = 0;
+    for (int st = st0; st < nst; ++st) {
+        // (in the last stage the copies and the reads ahead go on, of that stage again: nobody uses them, and
+        // the loop stays free of branches)
+        const bool more = st + 1 < nst;
+        const unsigned vnext = lane * 16 + (unsigned)(more ? st + 1 : st) * (unsigned)STG;
+        const unsigned ldsnext = ldsw + (buf ^ 1) * G::P1;
+        const unsigned char *cur = lds + buf * G::P1, *nxt = lds + (buf ^ 1) * G::P1;
+        v4i afn[WMF][2], bfn[WNF][2];
+        int slot = 0;
+#pragma unroll
+        for (int l = S - 1; l >= 0; --l) {
+            if (SPLIT && l == L0) __syncthreads();
+            if (l > 0) {
 #pragma unroll
                 for (int i = 0; i < WMF; ++i)
 #pragma unroll
-                    for (int i2 = 0; i2 < 2; ++i2)
-                        af[i][i2] = l >= L0 ? *(const v4i *)(lds + Z + (((wm * WMF + i) * NS2 + (l - L0)) * 2) * kFragBytes +
-                                                              lofs + i2 * 256)
-                                            : *(const v4i *)(cur + (((wm * WMF + i) * L0 + l) * 2) * kFragBytes + lofs + i2 * 256);
+                    for (int i2 = 0; i2 < 2; ++i2) afn[i][i2] = readA(l - 1, cur, i, i2);
+                if (S - l < HP) {
 #pragma unroll
-                for (int h = 0; h < S - l; ++h)
+                    for (int j = 0; j < WNF; ++j)
+#pragma unroll
+                        for (int j2 = 0; j2 < 2; ++j2) bf[S - l < HP ? S - l : 0][j][j2] = readB(S - l, cur, j, j2);
+                }
+                __builtin_amdgcn_sched_barrier(0);      // (the reads stay ahead of the products they hide behind)
+            }
+#pragma unroll
+            for (int hh = 0; hh < S - l; ++hh) {
+                const int h = l == 0 ? S - 1 - hh : hh;
+                if (l == 0 && h == HP - 1) {
+                    // nothing of this stage is left to read, and the next one must have landed
+                    wait_vmcnt<0>();
+                    __syncthreads();
 #pragma unroll
                     for (int i = 0; i < WMF; ++i)
 #pragma unroll
-                        for (int j = 0; j < WNF; ++j)
+                        for (int i2 = 0; i2 < 2; ++i2) afn[i][i2] = readA(S - 1, nxt, i, i2);
 #pragma unroll
-                            for (int i2 = 0; i2 < 2; ++i2)
+                    for (int j = 0; j < WNF; ++j)
 #pragma unroll
-                                for (int j2 = 0; j2 < 2; ++j2) {
-                                    const v4i bv = h < HP ? bf[h < HP ? h : 0][j][j2]
-                                                          : *(const v4i *)(cur + (U1A + ((wn * WNF + j) * S + h) * 2) * kFragBytes +
-                                                                           lofs + j2 * 256);
-                                    acc[l + h][i][j][i2 * 2 + j2] = __builtin_amdgcn_mfma_i32_16x16x64_i8(
-                                        bv, af[i][i2], acc[l + h][i][j][i2 * 2 + j2], 0, 0, 0);
-                                }
-                if (SPLIT && l == L0) {
-                    // every wavefront is done with the single-buffered slices: refill them for the next stage
-                    __syncthreads();
-                    if (st + 1 < nst) issue_p2(st + 1);
+                        for (int j2 = 0; j2 < 2; ++j2) bfn[j][j2] = readB(0, nxt, j, j2);
                 }
+#pragma unroll
+                for (int i = 0; i < WMF; ++i)
+#pragma unroll
+                    for (int j = 0; j < WNF; ++j)
+#pragma unroll
+                        for (int i2 = 0; i2 < 2; ++i2)
+#pragma unroll
+                            for (int j2 = 0; j2 < 2; ++j2) {
+                                const v4i bv = h < HP ? bf[h < HP ? h : 0][j][j2] : readB(h, cur, j, j2);
+                                acc[l + h][i][j][i2 * 2 + j2] = __builtin_amdgcn_mfma_i32_16x16x64_i8(
+                                    bv, af[i][i2], acc[l + h][i][j][i2 * 2 + j2], 0, 0, 0);
+                                // one copy of the next stage behind each of the first matrix instructions of
+                                // the stage (double-buffered part) / after the mid-stage barrier (the rest);
+                                // (spacing them 2 or 4 instructions apart changes nothing)
+                                const int e = slot * MPP + ((i * WNF + j) * 2 + i2) * 2 + j2;
+                                if (e < NU1) issue1_n(e, vnext, ldsnext);
+                                if (SPLIT && e >= NPRE * MPP && e - NPRE * MPP < NU2) issue2_n(e - NPRE * MPP, vnext);
+                            }
+                ++slot;
             }
-            if (NBUF == 3 && ahead) wait_keep1(); else wait_vmcnt<0>();
-            __syncthreads();
-            buf = buf + 1 == NBUF ? 0 : buf + 1;
+            __builtin_amdgcn_sched_barrier(0);          // (and no product of the next slice moves up to wait for them)
+#pragma unroll
+            for (int i = 0; i < WMF; ++i)
+#pragma unroll
+                for (int i2 = 0; i2 < 2; ++i2) af[i][i2] = afn[i][i2];
         }
-    } else {
-        // Copy units of this wavefront: unit u = wave + i * NW of a region, its source address for stage 0 formed once
-        // here (a stage advances every source by STG bytes), so that a copy inside the loop costs a 64-bit add and
-        // the instruction itself.
-        static_assert(NBUF == 2, "ring of two");
-        constexpr int NU1 = (U1 + NW - 1) / NW, NU2 = SPLIT ? (U2 + NW - 1) / NW : 0;
-        constexpr size_t STG = (size_t)2 * S * kFragBytes;
-        const int8_t *src1[NU1], *src2[NU2 ? NU2 : 1];
-#pragma unroll
-        for (int i = 0; i < NU1; ++i) {
-            const int u = wave + i * NW;
-            if (u < U1A) {
-                const int c = u / (2 * L0), l = (u / 2) % L0, kk = u % 2;
-                src1[i] = rowA + (size_t)c * row_bytes + (size_t)(kk * S + l) * kFragBytes;
-            } else {
-                const int v = u - U1A;
-                const int c = v / (2 * S), h = (v / 2) % S, kk = v % 2;
-                src1[i] = rowB + (size_t)c * row_bytes + (size_t)(kk * S + h) * kFragBytes;
-            }
-        }
-#pragma unroll
-        for (int i = 0; i < NU2; ++i) {
-            const int u = wave + i * NW;
-            const int c = u / (2 * NS2), l = L0 + (u / 2) % NS2, kk = u % 2;
-            src2[i] = rowA + (size_t)c * row_bytes + (size_t)(kk * S + l) * kFragBytes;
-        }
-        // Unit I of the double-buffered part (issue1) / of the single-buffered part (issue2): `voff` carries the
-        // stage (lane * 16 + stage * STG: the host admits only contractions for which that fits 31 bits), `ldsw` the
-        // ring buffer and the wavefront.  Two instructions per copy.
-        const unsigned ldsw = lds0 + wave * kFragBytes;
-        auto issue1 = [&](auto I, unsigned voff, unsigned ldsbuf) {
-            constexpr int i = decltype(I)::value;
-            if (i < U1 / NW || wave < U1 % NW) lds_dma16_at<i * NW * kFragBytes>(src1[i], voff, ldsbuf);
-        };
-        auto issue2 = [&](auto I, unsigned voff) {
-            constexpr int i = decltype(I)::value;
-            if (i < U2 / NW || wave < U2 % NW) lds_dma16_at<Z + i * NW * kFragBytes>(src2[i], voff, ldsw);
-        };
-        // (compile-time dispatch on the unit number)
-        auto issue1_n = [&](int i, unsigned voff, unsigned ldsbuf) {
-            switch (i) {
-#define OZ_U(N_) case N_: if constexpr (N_ < NU1) issue1(std::integral_constant<int, N_>{}, voff, ldsbuf); break;
-                OZ_U(0) OZ_U(1) OZ_U(2) OZ_U(3) OZ_U(4) OZ_U(5) OZ_U(6) OZ_U(7) OZ_U(8) OZ_U(9) OZ_U(10) OZ_U(11)
-#undef OZ_U
-            }
-        };
-        auto issue2_n = [&](int i, unsigned voff) {
-            switch (i) {
-#define OZ_U(N_) case N_: if constexpr (N_ < NU2) issue2(std::integral_constant<int, N_>{}, voff); break;
-                OZ_U(0) OZ_U(1) OZ_U(2) OZ_U(3) OZ_U(4) OZ_U(5) OZ_U(6) OZ_U(7) OZ_U(8) OZ_U(9) OZ_U(10) OZ_U(11)
-#undef OZ_U
-            }
-        };
-        static_assert(NU1 <= 12 && NU2 <= 12, "unit dispatch");
-
-        {
-            const unsigned v0 = lane * 16 + (unsigned)st0 * (unsigned)STG;
-#pragma unroll
-            for (int i = 0; i < NU1; ++i) issue1_n(i, v0, ldsw);
-#pragma unroll
-            for (int i = 0; i < NU2; ++i) issue2_n(i, v0);
-        }
-        wait_vmcnt<0>();
-        __syncthreads();
-
-        // this lane's part of a 16x64 operand: row lane%16 of the half, k-group g = lane/16
-        // -> fragment kk = g / 2 of the pair, lane slot (row + 32 * (g % 2)) in it
-        const int lofs = ((lane >> 4) >> 1) * kFragBytes + ((lane & 15) + 32 * ((lane >> 4) & 1)) * 16;
-        auto readA = [&](int l, const unsigned char *stage, int i, int i2) -> v4i {
-            return l >= L0 ? *(const v4i *)(lds + Z + (((wm * WMF + i) * NS2 + (l - L0)) * 2) * kFragBytes + lofs + i2 * 256)
-                           : *(const v4i *)(stage + (((wm * WMF + i) * L0 + l) * 2) * kFragBytes + lofs + i2 * 256);
-        };
-        auto readB = [&](int h, const unsigned char *stage, int j, int j2) -> v4i {
-            return *(const v4i *)(stage + (U1A + ((wn * WNF + j) * S + h) * 2) * kFragBytes + lofs + j2 * 256);
-        };
-
-        // Schedule of a stage.  The slices of A go from the last to the first (the single-buffered ones, l >= L0,
-        // first); the operands of slice l - 1 (its A fragments, the one B slice it needs beyond those of slice l) are
-        // read while the products of slice l run.  Once the fragments of slice L0 - 1 are the next to be read nobody
-        // needs the single-buffered region any more (mid-stage barrier, at the START of slice L0), and when the
-        // products of slice 0 begin every read of the stage is done: the end-of-stage barrier stands there, and the
-        // first operands of the NEXT stage are read while the products of slice 0 run.  The copies of the next stage
-        // are issued one or two at a time between the products (double-buffered part before the mid-stage barrier, the
-        // single-buffered part after it), so that no wavefront leaves the matrix pipe alone for long.
-        // (s = 9: only the first HP slices of B are held in registers, the others are read when needed; at slice 0
-        // they are needed first, so that the end-of-stage barrier still follows the last read.)
-        constexpr int HP = S >= 9 ? 6 : S;
-        constexpr int NSLOT = S * (S - 1) / 2;                                  // products of the slices l > 0
-        constexpr int NPRE = SPLIT ? (S - L0 - 1) * (S - L0) / 2 : NSLOT;        // ... of them before the mid-stage barrier
-        constexpr int MPP = 4 * WMF * WNF;                                       // matrix instructions per product
-        static_assert(NU1 <= NPRE * MPP && (!SPLIT || NU2 <= (NSLOT - NPRE) * MPP), "too few products to issue the copies behind");
-        v4i bf[HP][WNF][2], af[WMF][2];
-#pragma unroll
-        for (int i = 0; i < WMF; ++i)
-#pragma unroll
-            for (int i2 = 0; i2 < 2; ++i2) af[i][i2] = readA(S - 1, lds, i, i2);
 #pragma unroll
         for (int j = 0; j < WNF; ++j)
 #pragma unroll
-            for (int j2 = 0; j2 < 2; ++j2) bf[0][j][j2] = readB(0, lds, j, j2);
-
-        int buf = 0;
-        for (int st = st0; st < nst; ++st) {
-            // (in the last stage the copies and the reads ahead go on, of that stage again: nobody uses them, and
-            // the loop stays free of branches)
-            const bool more = st + 1 < nst;
-            const unsigned vnext = lane * 16 + (unsigned)(more ? st + 1 : st) * (unsigned)STG;
-            const unsigned ldsnext = ldsw + (buf ^ 1) * G::P1;
-            const unsigned char *cur = lds + buf * G::P1, *nxt = lds + (buf ^ 1) * G::P1;
-            v4i afn[WMF][2], bfn[WNF][2];
-            int slot = 0;
-#pragma unroll
-            for (int l = S - 1; l >= 0; --l) {
-                if (SPLIT && l == L0) __syncthreads();
-                if (l > 0) {
-#pragma unroll
-                    for (int i = 0; i < WMF; ++i)
-#pragma unroll
-                        for (int i2 = 0; i2 < 2; ++i2) afn[i][i2] = readA(l - 1, cur, i, i2);
-                    if (S - l < HP) {
-#pragma unroll
-                        for (int j = 0; j < WNF; ++j)
-#pragma unroll
-                            for (int j2 = 0; j2 < 2; ++j2) bf[S - l < HP ? S - l : 0][j][j2] = readB(S - l, cur, j, j2);
-                    }
-                    __builtin_amdgcn_sched_barrier(0);      // (the reads stay ahead of the products they hide behind)
-                }
-#pragma unroll
-                for (int hh = 0; hh < S - l; ++hh) {
-                    const int h = l == 0 ? S - 1 - hh : hh;
-                    if (l == 0 && h == HP - 1) {
-                        // nothing of this stage is left to read, and the next one must have landed
-                        wait_vmcnt<0>();
-                        __syncthreads();
-#pragma unroll
-                        for (int i = 0; i < WMF; ++i)
-#pragma unroll
-                            for (int i2 = 0; i2 < 2; ++i2) afn[i][i2] = readA(S - 1, nxt, i, i2);
-#pragma unroll
-                        for (int j = 0; j < WNF; ++j)
-#pragma unroll
-                            for (int j2 = 0; j2 < 2; ++j2) bfn[j][j2] = readB(0, nxt, j, j2);
-                    }
-#pragma unroll
-                    for (int i = 0; i < WMF; ++i)
-#pragma unroll
-                        for (int j = 0; j < WNF; ++j)
-#pragma unroll
-                            for (int i2 = 0; i2 < 2; ++i2)
-#pragma unroll
-                                for (int j2 = 0; j2 < 2; ++j2) {
-                                    const v4i bv = h < HP ? bf[h < HP ? h : 0][j][j2] : readB(h, cur, j, j2);
-                                    acc[l + h][i][j][i2 * 2 + j2] = __builtin_amdgcn_mfma_i32_16x16x64_i8(
-                                        bv, af[i][i2], acc[l + h][i][j][i2 * 2 + j2], 0, 0, 0);
-                                    // one copy of the next stage behind each of the first matrix instructions of
-                                    // the stage (double-buffered part) / after the mid-stage barrier (the rest)
-                                    const int e = slot * MPP + ((i * WNF + j) * 2 + i2) * 2 + j2;
-                                    if (e < NU1) issue1_n(e, vnext, ldsnext);
-                                    if (SPLIT && e >= NPRE * MPP && e - NPRE * MPP < NU2) issue2_n(e - NPRE * MPP, vnext);
-                                }
-                    ++slot;
-                }
-                __builtin_amdgcn_sched_barrier(0);          // (and no product of the next slice moves up to wait for them)
-#pragma unroll
-                for (int i = 0; i < WMF; ++i)
-#pragma unroll
-                    for (int i2 = 0; i2 < 2; ++i2) af[i][i2] = afn[i][i2];
-            }
-#pragma unroll
-            for (int j = 0; j < WNF; ++j)
-#pragma unroll
-                for (int j2 = 0; j2 < 2; ++j2) bf[0][j][j2] = bfn[j][j2];
-            buf ^= 1;
-        }
+            for (int j2 = 0; j2 < 2; ++j2) bf[0][j][j2] = bfn[j][j2];
+        buf ^= 1;
     }
 
     // element of accumulator block (i2, j2), register r: m_local = 16*i2 + lane%16, n_local = 16*j2 + 4*(lane/16) + r
