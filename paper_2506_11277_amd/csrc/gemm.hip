@@ -634,7 +634,7 @@ size_t fused_totals_bytes(int sA, int sB, bool all_products, int m, int n, int k
         if (w < n) n = w;
     }
     int tm = 128, tn = 128;
-    if (sA == sB && !all && fused16_preferred(s, true, round_up(k > 0 ? k : 1, kPad))) fused16_tile(s, tm, tn);
+    if (sA == sB && !all && fused16_preferred(s, true)) fused16_tile(s, tm, tn);
     else switch (s) {
 #define OZ_CASE(S_) case S_: fused_tile<S_>(tm, tn); break;
         OZ_CASE(1) OZ_CASE(2) OZ_CASE(3) OZ_CASE(4) OZ_CASE(5) OZ_CASE(6) OZ_CASE(7) OZ_CASE(8) OZ_CASE(9) OZ_CASE(10) OZ_CASE(11) OZ_CASE(12) OZ_CASE(13) OZ_CASE(14) OZ_CASE(15) OZ_CASE(16) OZ_CASE(17) OZ_CASE(18) OZ_CASE(19) OZ_CASE(20)
@@ -683,7 +683,7 @@ static hipError_t launch_gemm_fused_once(int m, int n, int kp, int sA, int sB, b
         if (!dump && !totals && s <= kSmallMaxS) {
             // too few tiles of the tabulated shape to occupy the chip: the 64 x 64 tile
             int tm = 128, tn = 128;
-            if (fused16_preferred(s, false, kp)) fused16_tile(s, tm, tn);
+            if (fused16_preferred(s, false)) fused16_tile(s, tm, tn);
             else if (s <= 4 || s == 6) { tm = 128; tn = 128; }
             else { tm = 128; tn = 64; }
             const long long tiles = (long long)((m + tm - 1) / tm) * ((n + tn - 1) / tn);
@@ -692,7 +692,7 @@ static hipError_t launch_gemm_fused_once(int m, int n, int kp, int sA, int sB, b
                 return dispatch_fused_small(s, m, n, kp, pA, pB, eA, eB, C, ldc, Q, st);
         }
         // the 16x16x64 kernel where it is the faster one
-        if (fused16_preferred(s, totals != nullptr, kp))
+        if (fused16_preferred(s, totals != nullptr))
             return launch_gemm_fused16(m, n, kp, s, pA, pB, eA, eB, C, ldc, dump, totals, Q, st);
         if (dump) return dispatch_fused<kDump, 0>(s, m, n, kp, pA, pB, eA, eB, C, ldc, dump, nullptr, Q, s, st);
         if (totals) return dispatch_fused<kBlocked, 0>(s, m, n, kp, pA, pB, eA, eB, C, ldc, nullptr, totals, Q, s, st);

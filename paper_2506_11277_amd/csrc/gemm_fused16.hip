@@ -93,8 +93,9 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
     const int st0 = MODE == kBlocked ? (int)blockIdx.y * stages_per_block : 0;
     const int nst = MODE == kBlocked && st0 + stages_per_block < nst_all ? st0 + stages_per_block : nst_all;
 
-    // Copy units of this wavefront: unit u = wave + i * NW of a region, its source address for stage 0 formed once
-    // here (a stage advances every source by STG bytes, which the copies carry in their lane offset).
+    // Copy units of this wavefront: unit u = wave + i * NW of a region, its source address for the first stage of
+    // this work-group formed once here (a stage advances every source by STG bytes, which the copies carry in their
+    // 32-bit lane offset: a k-block is a few MiB of a fragment row at most, whatever k).
     constexpr int NU1 = (U1 + NW - 1) / NW, NU2 = SPLIT ? (U2 + NW - 1) / NW : 0;
     constexpr size_t STG = (size_t)2 * S * kFragBytes;
     const int8_t *src1[NU1], *src2[NU2 ? NU2 : 1];
@@ -103,21 +104,21 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
         const int u = wave + i * NW;
         if (u < U1A) {
             const int c = u / (2 * L0), l = (u / 2) % L0, kk = u % 2;
-            src1[i] = rowA + (size_t)c * row_bytes + (size_t)(kk * S + l) * kFragBytes;
+            src1[i] = rowA + (size_t)c * row_bytes + (size_t)st0 * STG + (size_t)(kk * S + l) * kFragBytes;
         } else {
             const int v = u - U1A;
             const int c = v / (2 * S), h = (v / 2) % S, kk = v % 2;
-            src1[i] = rowB + (size_t)c * row_bytes + (size_t)(kk * S + h) * kFragBytes;
+            src1[i] = rowB + (size_t)c * row_bytes + (size_t)st0 * STG + (size_t)(kk * S + h) * kFragBytes;
         }
     }
 #pragma unroll
     for (int i = 0; i < NU2; ++i) {
         const int u = wave + i * NW;
         const int c = u / (2 * NS2), l = L0 + (u / 2) % NS2, kk = u % 2;
-        src2[i] = rowA + (size_t)c * row_bytes + (size_t)(kk * S + l) * kFragBytes;
+        src2[i] = rowA + (size_t)c * row_bytes + (size_t)st0 * STG + (size_t)(kk * S + l) * kFragBytes;
     }
     // Unit I of the double-buffered part (issue1) / of the single-buffered part (issue2): `voff` carries the
-    // stage (lane * 16 + stage * STG: the host admits only contractions for which that fits 31 bits), `ldsw` the
+    // stage (lane * 16 + (stage - first stage) * STG), `ldsw` the
     // ring buffer and the wavefront.  Two instructions per copy.
     const unsigned ldsw = lds0 + wave * kFragBytes;
     auto issue1 = [&](auto I, unsigned voff, unsigned ldsbuf) {
@@ -146,7 +147,7 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
     static_assert(NU1 <= 12 && NU2 <= 12, "unit dispatch");
 
     {
-        const unsigned v0 = lane * 16 + (unsigned)st0 * (unsigned)STG;
+        const unsigned v0 = lane * 16;
 #pragma unroll
         for (int i = 0; i < NU1; ++i) issue1_n(i, v0, ldsw);
 #pragma unroll
@@ -196,7 +197,7 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
         // (in the last stage the copies and the reads ahead go on, of that stage again: nobody uses them, and
         // the loop stays free of branches)
         const bool more = st + 1 < nst;
-        const unsigned vnext = lane * 16 + (unsigned)(more ? st + 1 : st) * (unsigned)STG;
+        const unsigned vnext = lane * 16 + (unsigned)((more ? st + 1 : st) - st0) * (unsigned)STG;
         const unsigned ldsnext = ldsw + (buf ^ 1) * G::P1;
         const unsigned char *cur = lds + buf * G::P1, *nxt = lds + (buf ^ 1) * G::P1;
         v4i afn[WMF][2], bfn[WNF][2];
@@ -393,7 +394,6 @@ hipError_t launch16_s(int m, int n, int kp, const int8_t *pA, const int8_t *pB, 
     if (hipError_t e = allow_dynamic_lds((const void *)kern, G::LDS, configured); e != hipSuccess) return e;
     const int tiles_m = (m + TM - 1) / TM, tiles_n = (n + TN - 1) / TN;
     const int KB = kp / kFrag;
-    if ((long long)kp * S * 32 >= (1LL << 31)) return hipErrorInvalidValue;      // (see fused16_preferred)
     if (MODE != kBlocked) {
         kern<<<tiles_m * tiles_n, THREADS, G::LDS, st>>>(pA, pB, eA, eB, C, ldc, m, n, KB, tiles_m, tiles_n, dump,
                                                          nullptr, 0, Q, 0);
@@ -434,12 +434,7 @@ hipError_t dispatch16(int s, int m, int n, int kp, const int8_t *pA, const int8_
 // tile, s = 6 ... 9 with the pipelined schedule: +10 %, +17 %, +17 %, +17 % over the 32x32x32 kernel).  With split-k
 // (long contractions) the wide 32x32x32 tile stays ahead at s = 6; beyond 9 a 64-deep stage of a 128 x 64 tile
 // does not fit LDS; the 32x32x32 kernel wins at 2 and 3.  Only the preferred ones are instantiated.
-// (Its copies address a fragment row of the planes, kp * s * 32 bytes, with 32-bit offsets: longer contractions
-// stay with the 32x32x32 kernel.)
-bool fused16_preferred(int s, bool split_k, long long kp)
-{
-    return s >= 4 && s <= 9 && !(s == 6 && split_k) && kp * s * 32 < (1LL << 31);
-}
+bool fused16_preferred(int s, bool split_k) { return s >= 4 && s <= 9 && !(s == 6 && split_k); }
 
 void fused16_tile(int s, int &tm, int &tn)
 {

@@ -262,9 +262,9 @@ def test_k_blocked_on_every_fused_kernel(s):
     assert_c_matches(host(ozimmu.dgemm(dev(A), dev(B), s)), oracle.dgemm(A, B, s), f"k-blocked extreme s={s}")
 
 
-def test_contraction_too_long_for_32_bit_plane_offsets():
-    # k * s * 32 >= 2^31 bytes in a fragment row of the planes: the 16x16x64 kernel addresses a row with 32-bit
-    # offsets and must leave such a contraction to the 32x32x32 kernel
+def test_contraction_longer_than_32_bit_plane_offsets():
+    # k * s * 32 >= 2^31 bytes in a fragment row of the planes: the copies carry 32-bit offsets, which must be
+    # relative to the k-block of the work-group and not to the row
     s = 9
     k = (1 << 31) // (32 * s) + 1000
     A, B = workloads.uniform(3, 2, k, 77)
