@@ -137,94 +137,206 @@ __global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t
     const int nst_all = KB / KB32;
     const int st0 = MODE == kBlocked ? (int)blockIdx.y * stages_per_block : 0;
     const int nst = MODE == kBlocked && st0 + stages_per_block < nst_all ? st0 + stages_per_block : nst_all;
-    issue_stage(st0, 0);
-    if (NSTAGE == 3 && nst - st0 > 1) {
-        issue_stage(st0 + 1, 1);
-        wait_keep1();
-    } else {
+    // PIPE: the main loop software-pipelined by hand, for equal slice counts 5 ... 11 with one 32-deep k-block per
+    // stage and a ring of two.  The slices of A go from the last to the first; the operands of slice l - 1 (its A
+    // fragments, the one B slice it needs beyond those of slice l) are read while the products of slice l run; the
+    // end-of-stage barrier stands at the START of the products of slice 0 (every read of the stage is issued by
+    // then) and the first operands of the next stage are read behind it while those products run; the copies of
+    // the next stage are issued one at a time behind single matrix instructions, two instructions each (source
+    // addresses formed once per wavefront, the stage in the 32-bit lane offset relative to the work-group's first
+    // stage, the LDS address one scalar add into m0), so that the loop body has no branch but a ragged last copy.
+    // Measured: 8192^3 s = 10 / 11 +4 %; 2048 x 2048 x 262144 s = 6 / 10 / 11 +2 ... 4 %; the 64 x 64 tile of small
+    // problems -12 % time at 512^3 s = 9 (no gain below 7 slices there).  From 12 slices on (and for the
+    // four-wavefront shape of 13 ... 20 slices) it brings nothing over the loop below with its copies issued in
+    // portions, and with part of B read on demand (17 ... 20) it is slower.
+    constexpr bool PIPE = PSET == 0 && NSTAGE == 2 && KB32 == 1 && S >= 5 && S <= 11 && (NW == 8 || S >= 7);
+    if constexpr (PIPE) {
+        constexpr int NU = (UNITS + NW - 1) / NW;
+        const int8_t *src[NU];
+#pragma unroll
+        for (int i = 0; i < NU; ++i) {
+            const int u = wave + i * NW;
+            const int c = u / S, o = u % S;
+            src[i] = (c < FA ? rowA + (size_t)c * row_bytesA : rowB + (size_t)(c - FA) * row_bytesB) +
+                     (size_t)st0 * CHUNK + (size_t)o * kFragBytes;
+        }
+        const unsigned ldsw = lds0 + wave * kFragBytes;
+        auto issue = [&](auto I, unsigned voff, unsigned ldsbuf) {
+            constexpr int i = decltype(I)::value;
+            if (i < UNITS / NW || wave < UNITS % NW) lds_dma16_at<i * NW * kFragBytes>(src[i], voff, ldsbuf);
+        };
+        auto issue_n = [&](int i, unsigned voff, unsigned ldsbuf) {
+            switch (i) {
+#define OZ_U(N_) case N_: if constexpr (N_ < NU) issue(std::integral_constant<int, N_>{}, voff, ldsbuf); break;
+                OZ_U(0) OZ_U(1) OZ_U(2) OZ_U(3) OZ_U(4) OZ_U(5) OZ_U(6) OZ_U(7) OZ_U(8) OZ_U(9) OZ_U(10) OZ_U(11)
+                OZ_U(12) OZ_U(13) OZ_U(14) OZ_U(15) OZ_U(16) OZ_U(17) OZ_U(18) OZ_U(19)
+#undef OZ_U
+            }
+        };
+        static_assert(NU <= 20, "unit dispatch");
+#pragma unroll
+        for (int i = 0; i < NU; ++i) issue_n(i, lane * 16, ldsw);
         wait_vmcnt<0>();
-    }
-    __syncthreads();
+        __syncthreads();
 
-    int buf = 0;
-    for (int st = st0; st < nst; ++st) {
-        const bool ahead = st + NSTAGE - 1 < nst;
-        // SPREAD: the copies of the next stage are not issued all at once at the top of the stage but in NPART
-        // portions, one before each of the first NPART slices of the outer loop.  Measured at 8192^3: +7.5 % for
-        // the four-wavefront shape (s = 13: 2855 -> 3075, s = 16: 3087 -> 3316 TOP/s), +2 % at s = 12, nothing at
-        // 10 and 11, -3.5 % at s = 6: used from 12 accumulator sets on.
-        // (Not for different slice counts: with few slices in the outer loop the late portions find no products
-        // left to hide behind, and deciding that at run time costs more than spreading gains.)
-        constexpr bool SPREAD = NSTAGE == 2 && KB32 == 1 && NA >= 12 && (PSET == 0 || PSET == 3);
-        const int nbuf = buf == 0 ? NSTAGE - 1 : buf - 1;
-        if (ahead && !SPREAD) issue_stage(st + NSTAGE - 1, nbuf);
-        const unsigned char *cur = lds + buf * STAGE;
+        auto readA = [&](int l, const unsigned char *stage, int i) -> v4i {
+            return *(const v4i *)(stage + (wm * WMF + i) * CHUNK + l * kFragBytes + lane * 16);
+        };
+        auto readB = [&](int h, const unsigned char *stage, int j) -> v4i {
+            return *(const v4i *)(stage + (FA + wn * WNF + j) * CHUNK + h * kFragBytes + lane * 16);
+        };
+        // beyond 16 slices only the first HP slices of B are held in registers, the others are read when needed
+        // (at slice 0 they are needed first, so that the barrier still follows the last read of the stage)
+        constexpr int HP = S > 18 ? 4 : S > 16 ? 8 : S;
+        constexpr int MPP = WMF * WNF, NSLOT = S * (S - 1) / 2;
+        static_assert(NU <= NSLOT * MPP, "too few products to issue the copies behind");
+        v4i bf[HP][WNF], af[WMF];
 #pragma unroll
-        for (int kbl = 0; kbl < KB32; ++kbl) {
-            // beyond 16 slices only the first HP slices of the preloaded operand are held for the whole stage,
-            // the others are read when needed
-            constexpr int HP = S > 18 ? 4 : S > 16 ? 8 : S;
-            if (PSET != 2) {
-                v4i bf[HP][WNF];
+        for (int i = 0; i < WMF; ++i) af[i] = readA(S - 1, lds, i);
 #pragma unroll
-                for (int h = 0; h < HP; ++h)
+        for (int j = 0; j < WNF; ++j) bf[0][j] = readB(0, lds, j);
+
+        int buf = 0;
+        for (int st = st0; st < nst; ++st) {
+            // (in the last stage the copies and the reads ahead go on, of that stage again: nobody uses them)
+            const bool more = st + 1 < nst;
+            const unsigned vnext = lane * 16 + (unsigned)((more ? st + 1 : st) - st0) * (unsigned)CHUNK;
+            const unsigned ldsnext = ldsw + (buf ^ 1) * STAGE;
+            const unsigned char *cur = lds + buf * STAGE, *nxt = lds + (buf ^ 1) * STAGE;
+            v4i afn[WMF], bfn[WNF];
+            int slot = 0;
 #pragma unroll
-                    for (int j = 0; j < WNF; ++j)
-                        bf[h][j] = *(const v4i *)(cur + (FA + wn * WNF + j) * CHUNK + (kbl * S + h) * kFragBytes + lane * 16);
+            for (int l = S - 1; l >= 0; --l) {
+                if (l > 0) {
 #pragma unroll
-                for (int l = 0; l < S; ++l) {
-                    if (SPREAD && ahead && l < NPART) issue_stage(st + NSTAGE - 1, nbuf, l);
-                    if (PSET == 1 && l >= sm) continue;     // (not `break`: the loop must stay fully unrollable)
-                    v4i af[WMF];
+                    for (int i = 0; i < WMF; ++i) afn[i] = readA(l - 1, cur, i);
+                    if (S - l < HP) {
 #pragma unroll
-                    for (int i = 0; i < WMF; ++i)
-                        af[i] = *(const v4i *)(cur + (wm * WMF + i) * CHUNK + (kbl * S + l) * kFragBytes + lane * 16);
-#pragma unroll
-                    for (int h = 0; h < (PSET == 3 ? S : S - l); ++h)
-#pragma unroll
-                        for (int i = 0; i < WMF; ++i)
-#pragma unroll
-                            for (int j = 0; j < WNF; ++j) {
-                                const v4i bv = h < HP ? bf[h < HP ? h : 0][j]
-                                                      : *(const v4i *)(cur + (FA + wn * WNF + j) * CHUNK +
-                                                                       (kbl * S + h) * kFragBytes + lane * 16);
-                                acc[l + h][i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bv, af[i], acc[l + h][i][j], 0, 0, 0);
-                            }
+                        for (int j = 0; j < WNF; ++j) bf[S - l < HP ? S - l : 0][j] = readB(S - l, cur, j);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);      // (the reads stay ahead of the products they hide behind)
                 }
-            } else {
-                // B is the short operand: its slices form the outer loop, those of A are held
-                v4i af[HP][WMF];
 #pragma unroll
-                for (int l = 0; l < HP; ++l)
+                for (int hh = 0; hh < S - l; ++hh) {
+                    const int h = l == 0 ? S - 1 - hh : hh;
+                    if (l == 0 && h == HP - 1) {
+                        // nothing of this stage is left to read, and the next one must have landed
+                        wait_vmcnt<0>();
+                        __syncthreads();
+#pragma unroll
+                        for (int i = 0; i < WMF; ++i) afn[i] = readA(S - 1, nxt, i);
+#pragma unroll
+                        for (int j = 0; j < WNF; ++j) bfn[j] = readB(0, nxt, j);
+                    }
 #pragma unroll
                     for (int i = 0; i < WMF; ++i)
-                        af[l][i] = *(const v4i *)(cur + (wm * WMF + i) * CHUNK + (kbl * S + l) * kFragBytes + lane * 16);
 #pragma unroll
-                for (int h = 0; h < S; ++h) {
-                    if (h >= sm) continue;
-                    v4i bf[WNF];
+                        for (int j = 0; j < WNF; ++j) {
+                            const v4i bv = h < HP ? bf[h < HP ? h : 0][j] : readB(h, cur, j);
+                            acc[l + h][i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bv, af[i], acc[l + h][i][j], 0, 0, 0);
+                            const int e = slot * MPP + i * WNF + j;
+                            if (e < NU && l > 0) issue_n(e, vnext, ldsnext);
+                        }
+                    ++slot;
+                }
+                __builtin_amdgcn_sched_barrier(0);          // (and no product of the next slice moves up to wait for them)
 #pragma unroll
-                    for (int j = 0; j < WNF; ++j)
-                        bf[j] = *(const v4i *)(cur + (FA + wn * WNF + j) * CHUNK + (kbl * S + h) * kFragBytes + lane * 16);
+                for (int i = 0; i < WMF; ++i) af[i] = afn[i];
+            }
 #pragma unroll
-                    for (int l = 0; l < S - h; ++l)
+            for (int j = 0; j < WNF; ++j) bf[0][j] = bfn[j];
+            buf ^= 1;
+        }
+    } else {
+        issue_stage(st0, 0);
+        if (NSTAGE == 3 && nst - st0 > 1) {
+            issue_stage(st0 + 1, 1);
+            wait_keep1();
+        } else {
+            wait_vmcnt<0>();
+        }
+        __syncthreads();
+
+        int buf = 0;
+        for (int st = st0; st < nst; ++st) {
+            const bool ahead = st + NSTAGE - 1 < nst;
+            // SPREAD: the copies of the next stage are not issued all at once at the top of the stage but in NPART
+            // portions, one before each of the first NPART slices of the outer loop.  Measured at 8192^3: +7.5 % for
+            // the four-wavefront shape (s = 13: 2855 -> 3075, s = 16: 3087 -> 3316 TOP/s), +2 % at s = 12, nothing at
+            // 10 and 11, -3.5 % at s = 6: used from 12 accumulator sets on.
+            // (Not for different slice counts: with few slices in the outer loop the late portions find no products
+            // left to hide behind, and deciding that at run time costs more than spreading gains.)
+            constexpr bool SPREAD = NSTAGE == 2 && KB32 == 1 && NA >= 12 && (PSET == 0 || PSET == 3);
+            const int nbuf = buf == 0 ? NSTAGE - 1 : buf - 1;
+            if (ahead && !SPREAD) issue_stage(st + NSTAGE - 1, nbuf);
+            const unsigned char *cur = lds + buf * STAGE;
+#pragma unroll
+            for (int kbl = 0; kbl < KB32; ++kbl) {
+                // beyond 16 slices only the first HP slices of the preloaded operand are held for the whole stage,
+                // the others are read when needed
+                constexpr int HP = S > 18 ? 4 : S > 16 ? 8 : S;
+                if (PSET != 2) {
+                    v4i bf[HP][WNF];
+#pragma unroll
+                    for (int h = 0; h < HP; ++h)
+#pragma unroll
+                        for (int j = 0; j < WNF; ++j)
+                            bf[h][j] = *(const v4i *)(cur + (FA + wn * WNF + j) * CHUNK + (kbl * S + h) * kFragBytes + lane * 16);
+#pragma unroll
+                    for (int l = 0; l < S; ++l) {
+                        if (SPREAD && ahead && l < NPART) issue_stage(st + NSTAGE - 1, nbuf, l);
+                        if (PSET == 1 && l >= sm) continue;     // (not `break`: the loop must stay fully unrollable)
+                        v4i af[WMF];
 #pragma unroll
                         for (int i = 0; i < WMF; ++i)
+                            af[i] = *(const v4i *)(cur + (wm * WMF + i) * CHUNK + (kbl * S + l) * kFragBytes + lane * 16);
 #pragma unroll
-                            for (int j = 0; j < WNF; ++j) {
-                                const v4i av = l < HP ? af[l < HP ? l : 0][i]
-                                                      : *(const v4i *)(cur + (wm * WMF + i) * CHUNK +
-                                                                       (kbl * S + l) * kFragBytes + lane * 16);
-                                acc[l + h][i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bf[j], av, acc[l + h][i][j], 0, 0, 0);
-                            }
+                        for (int h = 0; h < (PSET == 3 ? S : S - l); ++h)
+#pragma unroll
+                            for (int i = 0; i < WMF; ++i)
+#pragma unroll
+                                for (int j = 0; j < WNF; ++j) {
+                                    const v4i bv = h < HP ? bf[h < HP ? h : 0][j]
+                                                          : *(const v4i *)(cur + (FA + wn * WNF + j) * CHUNK +
+                                                                           (kbl * S + h) * kFragBytes + lane * 16);
+                                    acc[l + h][i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bv, af[i], acc[l + h][i][j], 0, 0, 0);
+                                }
+                    }
+                } else {
+                    // B is the short operand: its slices form the outer loop, those of A are held
+                    v4i af[HP][WMF];
+#pragma unroll
+                    for (int l = 0; l < HP; ++l)
+#pragma unroll
+                        for (int i = 0; i < WMF; ++i)
+                            af[l][i] = *(const v4i *)(cur + (wm * WMF + i) * CHUNK + (kbl * S + l) * kFragBytes + lane * 16);
+#pragma unroll
+                    for (int h = 0; h < S; ++h) {
+                        if (h >= sm) continue;
+                        v4i bf[WNF];
+#pragma unroll
+                        for (int j = 0; j < WNF; ++j)
+                            bf[j] = *(const v4i *)(cur + (FA + wn * WNF + j) * CHUNK + (kbl * S + h) * kFragBytes + lane * 16);
+#pragma unroll
+                        for (int l = 0; l < S - h; ++l)
+#pragma unroll
+                            for (int i = 0; i < WMF; ++i)
+#pragma unroll
+                                for (int j = 0; j < WNF; ++j) {
+                                    const v4i av = l < HP ? af[l < HP ? l : 0][i]
+                                                          : *(const v4i *)(cur + (wm * WMF + i) * CHUNK +
+                                                                           (kbl * S + l) * kFragBytes + lane * 16);
+                                    acc[l + h][i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bf[j], av, acc[l + h][i][j], 0, 0, 0);
+                                }
+                    }
                 }
             }
+            // stage st+1 must have landed before anyone reads it: with a ring of 3 the stage issued in
+            // this iteration may stay in flight, otherwise everything has to be back
+            if (NSTAGE == 3 && ahead) wait_keep1(); else wait_vmcnt<0>();
+            __syncthreads();
+            buf = buf + 1 == NSTAGE ? 0 : buf + 1;
         }
-        // stage st+1 must have landed before anyone reads it: with a ring of 3 the stage issued in
-        // this iteration may stay in flight, otherwise everything has to be back
-        if (NSTAGE == 3 && ahead) wait_keep1(); else wait_vmcnt<0>();
-        __syncthreads();
-        buf = buf + 1 == NSTAGE ? 0 : buf + 1;
     }
 
     if (MODE == kBlocked) {
