@@ -181,8 +181,11 @@ def main():
     out["int8_mfma_sustained_TOPs"] = {"constant_operands": ozimmu.measure_int8_ceiling(False),
                                        "random_operands": ozimmu.measure_int8_ceiling(True),
                                        "random_operands_16x16x64": ozimmu.measure_int8_ceiling(True, shape16=True),
-                                       "what": "register-only v_mfma_i32_32x32x32_i8 loop (last entry: "
-                                               "v_mfma_i32_16x16x64_i8), 2 wavefronts per SIMD"}
+                                       "random_operand_tile": ozimmu.measure_int8_ceiling(2),
+                                       "random_operand_tile_16x16x64": ozimmu.measure_int8_ceiling(2, shape16=True),
+                                       "what": "register-only v_mfma_i32_32x32x32_i8 loop (entries named 16x16x64: "
+                                               "v_mfma_i32_16x16x64_i8); operand tile: consecutive instructions "
+                                               "read different random operands, as in a GEMM"}
     try:
         ia = torch.randint(-127, 128, (m, k), dtype=torch.int8, device="cuda")
         ib = torch.randint(-127, 128, (n, k), dtype=torch.int8, device="cuda").t()

@@ -212,7 +212,9 @@ int ozimmu_profile_stop(int *calls, float *phase_ms);
  */
 int ozimmu_measure_int8_ceiling(int random_operands, int *sink, float *tops, void *stream);
 /* The same with the matrix instruction chosen: shape 0 = v_mfma_i32_32x32x32_i8, 1 = v_mfma_i32_16x16x64_i8 (the
- * one the GEMM kernel for 4, 5, 7, 8 and 9 slices uses; it spends less energy per product). */
+ * one the GEMM kernel for 4 ... 9 slices uses; it spends less energy per product).  random_operands = 2: a
+ * register tile of pseudo-random operands (4 x 4 fragments, 2 x 4 for 32x32x32), so that consecutive instructions
+ * read different operands, as in a GEMM; other values: OZIMMU_BAD_ARG. */
 int ozimmu_measure_int8_ceiling2(int random_operands, int shape, int *sink, float *tops, void *stream);
 
 /*

@@ -1,6 +1,7 @@
 // Measurement aid for the benchmark: what int8 rate do the matrix cores of THIS chip sustain
 // when nothing else happens?  A register-only loop of independent v_mfma_i32_32x32x32_i8 or
-// v_mfma_i32_16x16x64_i8 (no LDS, no memory), two wavefronts per SIMD, with either constant or pseudo-random operands.
+// v_mfma_i32_16x16x64_i8 (no LDS, no memory), two wavefronts per SIMD, with constant operands, one pseudo-random
+// operand pair, or a register tile of pseudo-random operands.
 // The two differ markedly on MI355X (the clock drops under the switching power of real data),
 // which is the context the roofline fraction of the GEMM kernel has to be read in.
 #include "oz_common.h"
@@ -18,13 +19,23 @@ __global__ __launch_bounds__(512) void mfma_loop_kernel(int iters, int random_op
 {
     unsigned x = threadIdx.x * 2654435761u + blockIdx.x * 40503u + 17u;
     auto next = [&]() { x = x * 1664525u + 1013904223u; return (int)x; };
-    v4i a, b;
-    if (random_operands) {
-        a = v4i{next(), next(), next(), next()};
-        b = v4i{next(), next(), next(), next()};
-    } else {
-        a = v4i{0x01010101, 0x01010101, 0x01010101, 0x01010101};
-        b = v4i{0x02020202, 0x02020202, 0x02020202, 0x02020202};
+    // random_operands 0: constants; 1: one pseudo-random A and B register set for every instruction; 2: a tile of
+    // pseudo-random operands as a GEMM's register tile has it (4 A x 4 B fragments for 16x16x64, 2 x 4 for
+    // 32x32x32), so that consecutive instructions see different operands.
+    v4i a[4], b[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        if (random_operands) {
+            a[q] = v4i{next(), next(), next(), next()};
+            b[q] = v4i{next(), next(), next(), next()};
+        } else {
+            a[q] = v4i{0x01010101, 0x01010101, 0x01010101, 0x01010101};
+            b[q] = v4i{0x02020202, 0x02020202, 0x02020202, 0x02020202};
+        }
+    }
+    if (random_operands != 2) {
+#pragma unroll
+        for (int q = 1; q < 4; ++q) { a[q] = a[0]; b[q] = b[0]; }
     }
     int s = 0;
     if (SHAPE16) {
@@ -33,7 +44,7 @@ __global__ __launch_bounds__(512) void mfma_loop_kernel(int iters, int random_op
         for (int i = 0; i < 16; ++i) acc[i] = v4i{0, 0, 0, 0};
         for (int it = 0; it < iters; ++it) {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) acc[i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, acc[i], 0, 0, 0);
+            for (int i = 0; i < 16; ++i) acc[i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[i & 3], b[i >> 2], acc[i], 0, 0, 0);
         }
 #pragma unroll
         for (int i = 0; i < 16; ++i)
@@ -47,7 +58,7 @@ __global__ __launch_bounds__(512) void mfma_loop_kernel(int iters, int random_op
             for (int r = 0; r < 16; ++r) acc[i][r] = 0;
         for (int it = 0; it < iters; ++it) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, acc[i], 0, 0, 0);
+            for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i & 1], b[i >> 1], acc[i], 0, 0, 0);
         }
 #pragma unroll
         for (int i = 0; i < 8; ++i)
@@ -86,7 +97,7 @@ extern "C" int ozimmu_measure_int8_ceiling(int random_operands, int *sink, float
 
 extern "C" int ozimmu_measure_int8_ceiling2(int random_operands, int shape, int *sink, float *tops, void *stream)
 {
-    if (shape != 0 && shape != 1) return OZIMMU_BAD_ARG;
+    if ((shape != 0 && shape != 1) || random_operands < 0 || random_operands > 2) return OZIMMU_BAD_ARG;
     return measure_ceiling(random_operands, shape == 1, sink, tops, stream);
 }
 

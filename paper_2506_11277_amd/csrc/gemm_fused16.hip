@@ -70,7 +70,7 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
     constexpr int Z = 2 * G::P1;                                     // offset of the single-buffered region
 
     int tm, tn;
-    tile_of_block(blockIdx.x, gridDim.x, tiles_m, tiles_n, tm, tn);
+    if (!tile_of_block_xcd(blockIdx.x, tiles_m, tiles_n, tm, tn)) return;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wm = wave % WVM, wn = wave / WVM;
@@ -395,7 +395,7 @@ hipError_t launch16_s(int m, int n, int kp, const int8_t *pA, const int8_t *pB, 
     const int tiles_m = (m + TM - 1) / TM, tiles_n = (n + TN - 1) / TN;
     const int KB = kp / kFrag;
     if (MODE != kBlocked) {
-        kern<<<tiles_m * tiles_n, THREADS, G::LDS, st>>>(pA, pB, eA, eB, C, ldc, m, n, KB, tiles_m, tiles_n, dump,
+        kern<<<(unsigned)tile_order_blocks(tiles_m, tiles_n), THREADS, G::LDS, st>>>(pA, pB, eA, eB, C, ldc, m, n, KB, tiles_m, tiles_n, dump,
                                                          nullptr, 0, Q, 0);
         return hipGetLastError();
     }
@@ -408,7 +408,7 @@ hipError_t launch16_s(int m, int n, int kp, const int8_t *pA, const int8_t *pB, 
     const size_t nslots = (size_t)tiles_m * tiles_n * S * TM * TN;
     const long long slot_stride = nblocks == 2 ? (long long)nslots : 0;
     if (!slot_stride) zero16_i64_kernel<<<2048, 256, 0, st>>>(totals, nslots);
-    dim3 grid(tiles_m * tiles_n, nblocks);
+    dim3 grid((unsigned)tile_order_blocks(tiles_m, tiles_n), nblocks);
     kern<<<grid, THREADS, G::LDS, st>>>(pA, pB, eA, eB, C, ldc, m, n, KB, tiles_m, tiles_n, nullptr, totals,
                                         stages_per_block, Q, slot_stride);
     finish_blocked16_kernel<S><<<tiles_m * tiles_n, THREADS, 0, st>>>(totals, eA, eB, C, ldc, m, n, tiles_n, Q, slot_stride);

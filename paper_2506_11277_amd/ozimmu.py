@@ -319,10 +319,11 @@ def calibration_copy(dst, src):
 
 
 def measure_int8_ceiling(random_operands, shape16=False):
-    """Sustained int8 MFMA rate (TOP/s) of a register-only loop on the current device (32x32x32 or 16x16x64)."""
+    """Sustained int8 MFMA rate (TOP/s) of a register-only loop on the current device (32x32x32 or 16x16x64);
+    random_operands: 0 constants, 1 one random operand pair, 2 a register tile of random operands."""
     sink = torch.zeros(1, dtype=torch.int32, device="cuda")
     tops = ctypes.c_float(0.0)
-    rc = lib().ozimmu_measure_int8_ceiling2(int(bool(random_operands)), int(bool(shape16)), sink.data_ptr(),
+    rc = lib().ozimmu_measure_int8_ceiling2(int(random_operands), int(bool(shape16)), sink.data_ptr(),
                                             ctypes.byref(tops), _stream())
     if rc != OK:
         raise OzimmuError(rc, "measure_int8_ceiling")
