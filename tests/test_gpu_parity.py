@@ -248,7 +248,7 @@ def test_k_blocked_accumulation_beyond_the_int32_range():
 
 @pytest.mark.parametrize("s", [4, 5, 6, 7, 8, 9, 12, 13, 16, 17, 18, 19, 20])
 def test_k_blocked_on_every_fused_kernel(s):
-    # the fused kernels (16x16x64 for s = 4, 5, 7, 8, 9; 32x32x32 otherwise, with four 512-register wavefronts beyond
+    # the fused kernels (16x16x64 for s = 4, 5, 7, 8, 9 -- 6 only without split-k --; 32x32x32 otherwise, with four 512-register wavefronts beyond
     # s = 12) in split-k mode, several tiles and k-blocks
     m, n = 130, 70
     k = 3 * (133144 // s) + 200
