@@ -141,6 +141,8 @@ int ozimmu_dgemm(int m, int n, int k, const double *A, int lda, const double *B,
  *   all_products = 1:  all sA * sB                                   ("Computation of all products")
  * accumulated by diagonals l + h = 2, 3, ... as in ozimmu_dgemm; ozimmu_dgemm(s) equals
  * ozimmu_dgemm2(s, s, 0) bit for bit.  Workspace: ozimmu_workspace_bytes2(m, n, k, sA, sB, all_products).
+ * (Counts that differ little are run as equal counts with zero slices appended to the short operand, which
+ * leaves every diagonal sum and hence the result unchanged; the workspace size accounts for it.)
  */
 size_t ozimmu_workspace_bytes2(int m, int n, int k, int sA, int sB, int all_products);
 int ozimmu_dgemm2(int m, int n, int k, const double *A, int lda, const double *B, int ldb,

@@ -238,18 +238,20 @@ static int dgemm_impl(int m, int n, int k, const double *A, int lda, const doubl
                                w.mp, eB, w.np, nearest ? 1 : 0, st));
     if (m == 0 || n == 0) return OZIMMU_OK;
     prof_mark(1, st);
-    OZ_TRY(launch_split_both(m, n, k, A, lda, B, ldb, sA, sB, eA, eB, pA, pB, nearest, st));
+    // (w.cA, w.cB: the counts the GEMM runs with -- counts that differ little run as equal ones, zero slices appended)
+    OZ_TRY(launch_split_both(m, n, k, A, lda, B, ldb, sA, sB, w.cA, w.cB, eA, eB, pA, pB, nearest, st));
     prof_mark(2, st);
-    const bool fused = fused_handles(sA, sB, all_products);
-    if (fused && fused_single_block(sA, sB, k)) {
-        OZ_TRY(launch_gemm_fused(m, n, w.kp, sA, sB, all_products, pA, pB, eA, eB, C, ldc, nullptr, nullptr, Q, st));
+    const int cA = w.cA, cB = w.cB;
+    const bool fused = fused_handles(cA, cB, all_products);
+    if (fused && fused_single_block(cA, cB, k)) {
+        OZ_TRY(launch_gemm_fused(m, n, w.kp, cA, cB, all_products, pA, pB, eA, eB, C, ldc, nullptr, nullptr, Q, st));
     } else if (fused) {
-        OZ_TRY(launch_gemm_fused(m, n, w.kp, sA, sB, all_products, pA, pB, eA, eB, C, ldc, nullptr,
+        OZ_TRY(launch_gemm_fused(m, n, w.kp, cA, cB, all_products, pA, pB, eA, eB, C, ldc, nullptr,
                                  (long long *)(ws + w.off_totals), Q, st));
     } else {
-        const int dmax = all_products ? sA + sB : (sA > sB ? sA : sB) + 1;
-        long long *totals = banded_totals_bytes(sA, sB, k) ? (long long *)(ws + w.off_totals) : nullptr;
-        OZ_TRY(launch_gemm_banded(m, n, w.kp, sA, sB, dmax, pA, pB, eA, eB, C, ldc, totals, Q, st));
+        const int dmax = all_products ? cA + cB : (cA > cB ? cA : cB) + 1;
+        long long *totals = banded_totals_bytes(cA, cB, k) ? (long long *)(ws + w.off_totals) : nullptr;
+        OZ_TRY(launch_gemm_banded(m, n, w.kp, cA, cB, dmax, pA, pB, eA, eB, C, ldc, totals, Q, st));
     }
     prof_mark(3, st);
     if (g_prof.on && g_prof.calls < g_prof.capacity) ++g_prof.calls;

@@ -37,9 +37,33 @@ size_t fused_totals_bytes(int sA, int sB, bool all_products, int m, int n, int k
 size_t banded_totals_bytes(int sA, int sB, int k);
 int fused_max_slices();
 
+// Slice counts the GEMM runs with.  Different counts that differ little run as EQUAL counts, the short operand
+// getting zero slices appended by the slicing kernel: a product with a zero slice adds nothing, so every diagonal
+// sum -- and with it the result -- is the one of the product set l <= s_A, h <= s_B, l + h <= max(s_A, s_B) + 1
+// (subsection "Reduction in number of products" of Sect. 4), while the kernels for equal counts are faster by more
+// than the d (d + 1) / 2 surplus products cost (d = the difference of the counts).  Thresholds from timings at
+// 8192^3: (7,8) 14.7 -> 12.2 ms, (5,8) 12.7 -> 12.0, (4,8) 11.6 stays (12.1 as (8,8)), (9,12) 26.5 stays (27.8),
+// (12,16) 48.8 -> 47.0, (17,18) 112 -> 64 and (19,20) 128 -> 83 ms (beyond 16 the kernels for different counts read part of the long operand on demand,
+// beyond 18 only the band kernel is left).
+inline void gemm_slice_counts(int sA, int sB, bool all_products, int &cA, int &cB)
+{
+    cA = sA;
+    cB = sB;
+    if (all_products || sA == sB) return;
+    const int S = sA > sB ? sA : sB, d = S - (sA < sB ? sA : sB);
+    const int full = S * (S + 1) / 2, surplus = d * (d + 1) / 2;
+    const bool pad = S > 20   ? false
+                     : S >= 17 ? 5 * surplus <= 2 * full
+                     : S >= 13 ? 10 * surplus <= full
+                     : S >= 10 ? 14 * surplus <= full
+                               : 5 * surplus <= full;
+    if (pad) cA = cB = S;
+}
+
 // Workspace carve-up (all offsets multiples of 256 bytes).
 struct Workspace {
     int mp, np, kp;                 // padded extents
+    int cA, cB;                     // slice counts of the planes and of the GEMM (gemm_slice_counts)
     size_t off_header;              // 256 B: [0] u32 non-finite flag, [8] u64 kappa_A bits, [16] u64 kappa_B bits
     size_t off_maxA, off_minA;      // u64[mp]: integer view of max |a_ij| / min nonzero |a_ij| per row
     size_t off_maxB, off_minB;      // u64[np]
@@ -64,10 +88,11 @@ inline Workspace carve(int m, int n, int k, int sA, int sB, bool all_products = 
     w.off_minB = take(8 * (size_t)w.np);
     w.off_expA = take(4 * (size_t)w.mp);
     w.off_expB = take(4 * (size_t)w.np);
-    w.off_planesA = take((size_t)sA * w.mp * w.kp);
-    w.off_planesB = take((size_t)sB * w.np * w.kp);
-    w.off_totals = take(fused_handles(sA, sB, all_products) ? fused_totals_bytes(sA, sB, all_products, m, n, k)
-                                                            : banded_totals_bytes(sA, sB, k));
+    gemm_slice_counts(sA, sB, all_products, w.cA, w.cB);
+    w.off_planesA = take((size_t)w.cA * w.mp * w.kp);
+    w.off_planesB = take((size_t)w.cB * w.np * w.kp);
+    w.off_totals = take(fused_handles(w.cA, w.cB, all_products) ? fused_totals_bytes(w.cA, w.cB, all_products, m, n, k)
+                                                                : banded_totals_bytes(w.cA, w.cB, k));
     w.total = off;
     return w;
 }
@@ -96,10 +121,11 @@ hipError_t launch_scales_fused(int m, int n, int k, const double *A, int lda, co
 hipError_t launch_split(char side, int rows, int cols, const double *X, int ldx, int s,
                         const int32_t *exps, int8_t *planes, int layout, bool nearest, hipStream_t st);
 
-// slices of both operands (MFMA layout) in one launch
+// slices of both operands (MFMA layout) in one launch; the planes have room for cA >= sA and cB >= sB slices per
+// entry, the slices beyond sA (sB) are written as zeros
 hipError_t launch_split_both(int m, int n, int k, const double *A, int lda, const double *B, int ldb, int sA, int sB,
-                             const int32_t *eA, const int32_t *eB, int8_t *pA, int8_t *pB, bool nearest,
-                             hipStream_t st);
+                             int cA, int cB, const int32_t *eA, const int32_t *eB, int8_t *pA, int8_t *pB,
+                             bool nearest, hipStream_t st);
 
 // ---- launchers implemented in gemm.hip ---------------------------------------------------
 // largest s the fused (all diagonals in registers) kernel handles

@@ -81,7 +81,7 @@ __device__ __forceinline__ unsigned int slice_of(const Elem &el, int l, unsigned
 //      512 B contiguous per half wavefront.
 template <bool NEAREST>
 __device__ __forceinline__ void split_rows_block(int bx, int by, const unsigned long long *__restrict__ X, int ldx,
-                                                 int R, int K, int s, const int32_t *__restrict__ exps,
+                                                 int R, int K, int s, int cs, const int32_t *__restrict__ exps,
                                                  int8_t *__restrict__ planes, int KB)
 {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -96,7 +96,9 @@ __device__ __forceinline__ void split_rows_block(int bx, int by, const unsigned 
         el[i] = decompose(bits, e);
     }
     const int rb = r >> 5, kb = k0 >> 5, half = (k0 >> 4) & 1;
-    uint4 *dst = (uint4 *)(planes + ((size_t)rb * KB + kb) * (size_t)s * kFragBytes) + ((r & 31) + 32 * half);
+    // (the planes hold cs >= s slices per entry; those beyond s are zeros)
+    uint4 *dst = (uint4 *)(planes + ((size_t)rb * KB + kb) * (size_t)cs * kFragBytes) + ((r & 31) + 32 * half);
+    for (int l = s + 1; l <= cs; ++l) dst[(size_t)(l - 1) * (kFragBytes / 16)] = make_uint4(0, 0, 0, 0);
     unsigned int carry = 0;
     for (int l = 1; l <= s; ++l) {
         unsigned int wd[4];
@@ -122,12 +124,12 @@ __global__ __launch_bounds__(256) void split_rows_kernel(const unsigned long lon
                                                          int K, int s, const int32_t *__restrict__ exps,
                                                          int8_t *__restrict__ planes, int KB)
 {
-    split_rows_block<NEAREST>(blockIdx.x, blockIdx.y, X, ldx, R, K, s, exps, planes, KB);
+    split_rows_block<NEAREST>(blockIdx.x, blockIdx.y, X, ldx, R, K, s, s, exps, planes, KB);
 }
 
 template <bool NEAREST>
 __device__ __forceinline__ void split_cols_block(int bx, int by, const unsigned long long *__restrict__ X, int ldx,
-                                                 int R, int K, int s, const int32_t *__restrict__ exps,
+                                                 int R, int K, int s, int cs, const int32_t *__restrict__ exps,
                                                  int8_t *__restrict__ planes, int KB)
 {
     __shared__ __attribute__((aligned(16))) unsigned char lds[kColGroup * 32 * kColLdsRow];
@@ -150,7 +152,8 @@ __device__ __forceinline__ void split_cols_block(int bx, int by, const unsigned 
     const int jj2 = t & 31, ch = t >> 5;                    // phase 2: column, 16-byte chunk along k
     const int rb = j0 >> 5;
     const int kb = (k0 + ch * 16) >> 5, half = ch & 1;
-    uint4 *dst = (uint4 *)(planes + ((size_t)rb * KB + kb) * (size_t)s * kFragBytes) + (jj2 + 32 * half);
+    uint4 *dst = (uint4 *)(planes + ((size_t)rb * KB + kb) * (size_t)cs * kFragBytes) + (jj2 + 32 * half);
+    for (int l = s + 1; l <= cs; ++l) dst[(size_t)(l - 1) * (kFragBytes / 16)] = make_uint4(0, 0, 0, 0);
     unsigned int carry = 0;
     for (int l0 = 1; l0 <= s; l0 += kColGroup) {
         const int nl = (s - l0 + 1) < kColGroup ? (s - l0 + 1) : kColGroup;
@@ -179,20 +182,21 @@ __global__ __launch_bounds__(256) void split_cols_kernel(const unsigned long lon
                                                          int K, int s, const int32_t *__restrict__ exps,
                                                          int8_t *__restrict__ planes, int KB)
 {
-    split_cols_block<NEAREST>(blockIdx.x, blockIdx.y, X, ldx, R, K, s, exps, planes, KB);
+    split_cols_block<NEAREST>(blockIdx.x, blockIdx.y, X, ldx, R, K, s, s, exps, planes, KB);
 }
 
 // Both operands in one launch: the first nblkA work-groups slice A (numbered rows-block fastest), the others B.
 template <bool NEAREST>
 __global__ __launch_bounds__(256) void split_both_kernel(const unsigned long long *__restrict__ A, int lda, int m,
                                                          const unsigned long long *__restrict__ B, int ldb, int n, int K,
-                                                         int sA, int sB, const int32_t *__restrict__ eA,
+                                                         int sA, int sB, int cA, int cB,
+                                                         const int32_t *__restrict__ eA,
                                                          const int32_t *__restrict__ eB, int8_t *__restrict__ pA,
                                                          int8_t *__restrict__ pB, int KB, int gxA, int nblkA, int gxB)
 {
     const int b = blockIdx.x;
-    if (b < nblkA) split_rows_block<NEAREST>(b % gxA, b / gxA, A, lda, m, K, sA, eA, pA, KB);
-    else split_cols_block<NEAREST>((b - nblkA) % gxB, (b - nblkA) / gxB, B, ldb, n, K, sB, eB, pB, KB);
+    if (b < nblkA) split_rows_block<NEAREST>(b % gxA, b / gxA, A, lda, m, K, sA, cA, eA, pA, KB);
+    else split_cols_block<NEAREST>((b - nblkA) % gxB, (b - nblkA) / gxB, B, ldb, n, K, sB, cB, eB, pB, KB);
 }
 
 // ---- plain layout: plane l is a matrix shaped like X (utility / test path) ----
@@ -243,15 +247,17 @@ hipError_t launch_split(char side, int rows, int cols, const double *X, int ldx,
 }
 
 hipError_t launch_split_both(int m, int n, int k, const double *A, int lda, const double *B, int ldb, int sA, int sB,
-                             const int32_t *eA, const int32_t *eB, int8_t *pA, int8_t *pB, bool nearest, hipStream_t st)
+                             int cA, int cB, const int32_t *eA, const int32_t *eB, int8_t *pA, int8_t *pB, bool nearest,
+                             hipStream_t st)
 {
+    if (cA < sA || cB < sB) return hipErrorInvalidValue;
     const int mp = round_up(m > 0 ? m : 1, kPad), np = round_up(n > 0 ? n : 1, kPad), kp = round_up(k > 0 ? k : 1, kPad);
     const int gxA = mp / 64, gxB = np / 32;
     const long long nblkA = (long long)gxA * (kp / 64), nblkB = (long long)gxB * (kp / kColTileK);
     if (nblkA + nblkB > 0x7fffffffLL) return hipErrorInvalidValue;
     auto kern = nearest ? split_both_kernel<true> : split_both_kernel<false>;
     kern<<<(unsigned)(nblkA + nblkB), 256, 0, st>>>((const unsigned long long *)A, lda, m,
-                                                    (const unsigned long long *)B, ldb, n, k, sA, sB, eA, eB, pA, pB,
+                                                    (const unsigned long long *)B, ldb, n, k, sA, sB, cA, cB, eA, eB, pA, pB,
                                                     kp / kFrag, gxA, (int)nblkA, gxB);
     return hipGetLastError();
 }

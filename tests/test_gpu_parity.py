@@ -336,7 +336,9 @@ def test_estimator_on_config_lognormal_1024():
 # ----------------------------------------------------------------------------- different slice counts
 
 PAIRS = [(1, 8), (8, 1), (3, 9), (9, 3), (2, 2), (7, 7), (13, 13), (16, 16), (18, 18), (20, 7), (7, 20), (32, 32),
-         (1, 1), (12, 5), (25, 31)]
+         (1, 1), (12, 5), (25, 31),
+         # counts that differ little: run as equal counts with zero slices appended to the short operand
+         (7, 8), (8, 7), (5, 8), (4, 8), (6, 9), (8, 10), (12, 13), (12, 16), (17, 18), (20, 19), (11, 20), (3, 4), (1, 2)]
 
 
 @pytest.mark.parametrize("kind", ["uniform", "lognormal", "special"])
@@ -454,6 +456,8 @@ VARIANT_CASES = [
     (16, 16, False, True, 2),
     (5, 11, False, False, 3),
     (11, 5, False, True, 4),
+    (7, 8, False, True, 3),                 # runs as (8, 8) with a zero slice appended to A
+    (9, 7, False, False, 2),
     (6, 4, True, False, 3),
     (9, 9, True, True, 2),
     (18, 18, False, False, 4),
@@ -488,7 +492,7 @@ def test_dgemm3_variants_in_k_blocked_mode(s, Q, nearest):
     assert_c_matches(host(C), oracle.dgemm3(A, B, s, s, nearest=nearest, Q=Q), "dgemm3 k-blocked")
 
 
-@pytest.mark.parametrize("sA,sB", [(2, 9), (9, 2), (5, 11), (14, 6), (3, 18), (17, 12)])
+@pytest.mark.parametrize("sA,sB", [(2, 9), (9, 2), (5, 11), (14, 6), (3, 18), (17, 12), (8, 9), (7, 6), (18, 17), (19, 20)])
 def test_different_slice_counts_in_k_blocked_mode(sA, sB):
     # fused kernel with the short operand's count at run time, split-k: k beyond 133144 / min(sA, sB)
     m, n = 130, 70
