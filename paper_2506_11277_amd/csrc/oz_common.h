@@ -49,8 +49,14 @@ inline void gemm_slice_counts(int sA, int sB, bool all_products, int &cA, int &c
 {
     cA = sA;
     cB = sB;
-    if (all_products || sA == sB) return;
+    if (sA == sB) return;
     const int S = sA > sB ? sA : sB, d = S - (sA < sB ? sA : sB);
+    if (all_products) {
+        // all s_A s_B products: the fused kernel takes equal counts up to 9 (about twice the rate of the band
+        // kernel, which serves different counts), so zero slices pay while they at most double the products
+        if (S <= 9 && 2 * sA * sB >= S * S) cA = cB = S;
+        return;
+    }
     const int full = S * (S + 1) / 2, surplus = d * (d + 1) / 2;
     const bool pad = S > 20   ? false
                      : S >= 17 ? 5 * surplus <= 2 * full

@@ -351,7 +351,8 @@ def test_dgemm2_matches_oracle(kind, m, n, k, sA, sB):
 
 
 @pytest.mark.parametrize("sA,sB", [(1, 1), (2, 5), (5, 2), (2, 2), (3, 3), (4, 4), (5, 5), (6, 6), (7, 7), (8, 8), (9, 9),
-                                   (10, 10), (12, 12), (9, 17), (20, 20)])
+                                   (10, 10), (12, 12), (9, 17), (20, 20),
+                                   (5, 4), (7, 9), (9, 6), (3, 2)])      # run as equal counts, zero slices appended
 def test_dgemm2_all_products_matches_oracle(sA, sB):
     A, B = workloads.lognormal(130, 70, 200, 2.0, 52)
     C = ozimmu.dgemm2(dev(A), dev(B), sA, sB, all_products=True)
