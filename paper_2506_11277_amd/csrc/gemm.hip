@@ -83,7 +83,7 @@ __global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t
     const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds;
 
     int tm, tn;
-    if (!tile_of_block_xcd(blockIdx.x, tiles_m, tiles_n, tm, tn)) return;
+    if (!tile_of_block_xcd(blockIdx.x, tiles_m, tiles_n, MODE == kBlocked, tm, tn)) return;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wm = wave % WVM, wn = wave / WVM;
@@ -628,7 +628,7 @@ hipError_t launch_fused_s(int m, int n, int kp, const int8_t *pA, const int8_t *
     if (hipError_t e = allow_dynamic_lds((const void *)kern, NSTAGE * STAGE, configured); e != hipSuccess) return e;
     const int tiles_m = (m + TM - 1) / TM, tiles_n = (n + TN - 1) / TN;
     if (MODE != kBlocked) {
-        kern<<<(unsigned)tile_order_blocks(tiles_m, tiles_n), 64 * Cfg::WVM * Cfg::WVN, NSTAGE * STAGE, st>>>(
+        kern<<<(unsigned)tile_order_blocks(tiles_m, tiles_n, false), 64 * Cfg::WVM * Cfg::WVN, NSTAGE * STAGE, st>>>(
             pA, pB, eA, eB, C, ldc, m, n, kp / kFrag, tiles_m, tiles_n, dump, nullptr, 0, Q, sm, 0);
         return hipGetLastError();
     }
@@ -642,7 +642,7 @@ hipError_t launch_fused_s(int m, int n, int kp, const int8_t *pA, const int8_t *
     // exactly two k-blocks: an int32 slot per block (together the size of the int64 totals), nothing to clear
     const long long slot_stride = nblocks == 2 ? (long long)nslots : 0;
     if (!slot_stride) zero_i64_kernel<<<2048, 256, 0, st>>>(totals, nslots);
-    dim3 grid((unsigned)tile_order_blocks(tiles_m, tiles_n), nblocks);
+    dim3 grid((unsigned)tile_order_blocks(tiles_m, tiles_n, true), nblocks);
     kern<<<grid, 64 * Cfg::WVM * Cfg::WVN, NSTAGE * STAGE, st>>>(pA, pB, eA, eB, C, ldc, m, n, kp / kFrag, tiles_m,
                                                                   tiles_n, nullptr, totals, stages_per_block, Q, sm,
                                                                   slot_stride);

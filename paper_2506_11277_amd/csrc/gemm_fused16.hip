@@ -40,9 +40,9 @@ struct Cfg16 {
     static constexpr int WVM = WIDE ? 2 : 4, WVN = WIDE ? 4 : 2, WMF = WIDE ? 2 : 1, WNF = 1;
     static constexpr int FA = WVM * WMF, FB = WVN * WNF;          // 32-row fragment rows of the tile
     // A slices [0, L0) are double-buffered with B; A slices [L0, S) single-buffered (L0 == S: no split)
-    // (from a sweep at 8192^3: s = 7 runs 2470 / 2710 / 2880 / 2820 / 2710 TOP/s for L0 = 1 / 2 / 3 / 4 / 6, s = 8
-    // 2670 / 2910 / 3110 / 3090 for L0 = 1 / 2 / 3 / 4)
-    static constexpr int L0 = S <= 6 ? S : S == 7 ? 3 : S == 8 ? 4 : 2;
+    // (from a sweep at 8192^3: s = 7 runs 2820 / 2960 / 2905 / 2840 / 2795 TOP/s for L0 = 2 / 3 / 4 / 5 / 6, s = 8
+    // 2985 / 3150 / 3120 for L0 = 2 / 3 / 4 -- and 3230 against 3110 with split-k --, s = 9 2925 / 3100 for L0 = 1 / 2)
+    static constexpr int L0 = S <= 6 ? S : S <= 8 ? 3 : 2;
     static constexpr int P1 = (FA * L0 + FB * S) * 2 * kFragBytes;    // double-buffered part of a 64-k stage
     static constexpr int P2 = FA * (S - L0) * 2 * kFragBytes;         // single-buffered part
     static constexpr int LDS = 2 * P1 + P2;
@@ -70,7 +70,7 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
     constexpr int Z = 2 * G::P1;                                     // offset of the single-buffered region
 
     int tm, tn;
-    if (!tile_of_block_xcd(blockIdx.x, tiles_m, tiles_n, tm, tn)) return;
+    if (!tile_of_block_xcd(blockIdx.x, tiles_m, tiles_n, MODE == kBlocked, tm, tn)) return;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wm = wave % WVM, wn = wave / WVM;
@@ -395,7 +395,7 @@ hipError_t launch16_s(int m, int n, int kp, const int8_t *pA, const int8_t *pB, 
     const int tiles_m = (m + TM - 1) / TM, tiles_n = (n + TN - 1) / TN;
     const int KB = kp / kFrag;
     if (MODE != kBlocked) {
-        kern<<<(unsigned)tile_order_blocks(tiles_m, tiles_n), THREADS, G::LDS, st>>>(pA, pB, eA, eB, C, ldc, m, n, KB, tiles_m, tiles_n, dump,
+        kern<<<(unsigned)tile_order_blocks(tiles_m, tiles_n, false), THREADS, G::LDS, st>>>(pA, pB, eA, eB, C, ldc, m, n, KB, tiles_m, tiles_n, dump,
                                                          nullptr, 0, Q, 0);
         return hipGetLastError();
     }
@@ -408,7 +408,7 @@ hipError_t launch16_s(int m, int n, int kp, const int8_t *pA, const int8_t *pB, 
     const size_t nslots = (size_t)tiles_m * tiles_n * S * TM * TN;
     const long long slot_stride = nblocks == 2 ? (long long)nslots : 0;
     if (!slot_stride) zero16_i64_kernel<<<2048, 256, 0, st>>>(totals, nslots);
-    dim3 grid((unsigned)tile_order_blocks(tiles_m, tiles_n), nblocks);
+    dim3 grid((unsigned)tile_order_blocks(tiles_m, tiles_n, true), nblocks);
     kern<<<grid, THREADS, G::LDS, st>>>(pA, pB, eA, eB, C, ldc, m, n, KB, tiles_m, tiles_n, nullptr, totals,
                                         stages_per_block, Q, slot_stride);
     finish_blocked16_kernel<S><<<tiles_m * tiles_n, THREADS, 0, st>>>(totals, eA, eB, C, ldc, m, n, tiles_n, Q, slot_stride);
