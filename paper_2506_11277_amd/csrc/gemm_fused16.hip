@@ -216,7 +216,8 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
 #pragma unroll
                         for (int j2 = 0; j2 < 2; ++j2) bf[S - l < HP ? S - l : 0][j][j2] = readB(S - l, cur, j, j2);
                 }
-                __builtin_amdgcn_sched_barrier(0);      // (the reads stay ahead of the products they hide behind)
+                // (the reads stay ahead of the products they hide behind; at s = 4 the compiler's own order is as good)
+                if (S > 4) __builtin_amdgcn_sched_barrier(0);
             }
 #pragma unroll
             for (int hh = 0; hh < S - l; ++hh) {
@@ -254,7 +255,7 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
                             }
                 ++slot;
             }
-            __builtin_amdgcn_sched_barrier(0);          // (and no product of the next slice moves up to wait for them)
+            if (S > 4) __builtin_amdgcn_sched_barrier(0);   // (and no product of the next slice moves up to wait for them)
 #pragma unroll
             for (int i = 0; i < WMF; ++i)
 #pragma unroll
