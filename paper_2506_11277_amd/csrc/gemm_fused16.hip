@@ -117,9 +117,9 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
         const int c = u / (2 * NS2), l = L0 + (u / 2) % NS2, kk = u % 2;
         src2[i] = rowA + (size_t)c * row_bytes + (size_t)st0 * STG + (size_t)(kk * S + l) * kFragBytes;
     }
-    // Unit I of the double-buffered part (issue1) / of the single-buffered part (issue2): `voff` carries the
-    // stage (lane * 16 + (stage - first stage) * STG), `ldsw` the
-    // ring buffer and the wavefront.  Two instructions per copy.
+    // Unit I of the double-buffered part (issue1) / of the single-buffered part (issue2): `voff` carries the stage
+    // (lane * 16 + (stage - first stage) * STG), `ldsbuf` the ring buffer and the wavefront.  Two instructions per
+    // copy.
     const unsigned ldsw = lds0 + wave * kFragBytes;
     auto issue1 = [&](auto I, unsigned voff, unsigned ldsbuf) {
         constexpr int i = decltype(I)::value;
@@ -173,8 +173,9 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
     // needs the single-buffered region any more (mid-stage barrier, at the START of slice L0), and when the
     // products of slice 0 begin every read of the stage is done: the end-of-stage barrier stands there, and the
     // first operands of the NEXT stage are read while the products of slice 0 run.  The copies of the next stage
-    // are issued one or two at a time between the products (double-buffered part before the mid-stage barrier, the
-    // single-buffered part after it), so that no wavefront leaves the matrix pipe alone for long.
+    // are issued one at a time behind single matrix instructions (double-buffered part from the start of the stage,
+    // the single-buffered part from the mid-stage barrier on), so that no wavefront leaves the matrix pipe alone
+    // for long.
     // (s = 9: only the first HP slices of B are held in registers, the others are read when needed; at slice 0
     // they are needed first, so that the end-of-stage barrier still follows the last read.)
     constexpr int HP = S >= 9 ? 7 : S;
