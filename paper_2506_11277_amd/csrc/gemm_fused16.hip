@@ -16,14 +16,16 @@
 // stage's copy of it is issued, to land while the remaining products run.  The rest of the stage
 // (A slices l < L0, all of B) is double-buffered as before.
 //
-// Main loop, software-pipelined by hand: the operands of a slice are read one slice ahead, both barriers stand at
-// the START of a slice's products (whose operands are then already in registers), the first operands of the next
-// stage are read behind the end-of-stage barrier while the last slice's products run, and the copies of the next
-// stage are issued one at a time behind single matrix instructions -- two instructions each: the source addresses
-// are formed once per wavefront, the stage travels in the 32-bit lane offset, the LDS address is one scalar add
-// into m0 -- and the loop body has no branch but a ragged last copy.  (A plain loop -- copies issued at the top of
-// the stage, operands read where they are used, barriers behind the last product -- left the matrix pipe idle
-// 30 % of the cycles at s = 7; this one 20 %, at a clock that the power limit lowers accordingly.)
+// Main loop, software-pipelined by hand with a compile-time schedule (Sched16): the matrix instructions of a
+// stage are numbered in execution order and every operand is read from LDS a fixed number of them ahead of its
+// first use -- the first ones of the NEXT stage behind the end-of-stage barrier, which stands before the products
+// of the last slice (all reads of the stage are issued by then), as the mid-stage barrier stands before the
+// products of slice L0; the copies of the next stage are issued one at a time behind single matrix instructions,
+// two instructions each (source addresses formed once per wavefront, the stage in the 32-bit lane offset, the LDS
+// address one scalar add into m0); the loop body has no branch but a ragged last copy.  (A plain loop -- copies
+// issued at the top of the stage, operands read where they are used, barriers behind the last product -- left
+// the matrix pipe idle 30 % of the cycles at s = 7; this one 17 %, at a clock that the power limit lowers
+// accordingly.)
 #include <type_traits>
 
 #include "gemm_dev.h"
@@ -31,6 +33,52 @@
 namespace oz {
 
 namespace {
+
+template <int B, int E, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (B < E) {
+        f(std::integral_constant<int, B>{});
+        static_for<B + 1, E>(f);
+    }
+}
+
+// Compile-time schedule of a stage of the 16x16x64 kernel: the matrix instructions are numbered in execution order
+// (slices of A from the last to the first, within a slice the slices of B upwards -- downwards for slice 0 --, MPP
+// instructions per product); an operand first needed by instruction q is read D instructions ahead.
+template <int S, int MPP, int HP, int D, int DO>
+struct Sched16 {
+    static constexpr int NM = MPP * S * (S + 1) / 2;
+    static constexpr int gs(int l) { return MPP * ((S - 1 - l) * (S - l) / 2); }              // first instruction of slice l
+    static constexpr int pidx(int l, int h) { return gs(l) + MPP * (l == 0 ? S - 1 - h : h); }  // ... of product (l, h)
+    static constexpr int needB(int h) { return pidx(S - 1 - h, h); }                          // first use of B slice h
+    static constexpr int slice_of(int e)
+    {
+        int l = S - 1;
+        while (l > 0 && gs(l - 1) <= e) --l;
+        return l;
+    }
+    static constexpr int h_of(int e)
+    {
+        const int l = slice_of(e), p = (e - gs(l)) / MPP;
+        return l == 0 ? S - 1 - p : p;
+    }
+    // a read needed at instruction q is issued before instruction q - D of the same stage, or, if that lies before
+    // the stage, in the stage before: behind its end-of-stage barrier (before instruction EB) at the earliest
+    static constexpr bool wrapped(int q) { return q - D < 0; }
+    static constexpr int issue_at(int q, int EB) { return q - D >= 0 ? q - D : (NM + q - D > EB ? NM + q - D : EB); }
+    static constexpr bool any_read(int e, int EB)
+    {
+        for (int l = 0; l < S; ++l)
+            if (issue_at(gs(l), EB) == e) return true;
+        for (int h = 0; h < HP; ++h)
+            if (issue_at(needB(h), EB) == e) return true;
+        for (int l = 0; l < S; ++l)
+            for (int h = HP; h < S - l; ++h)
+                if (pidx(l, h) - DO == e) return true;
+        return false;
+    }
+};
 
 template <int S>
 struct Cfg16 {
@@ -47,6 +95,10 @@ struct Cfg16 {
     static constexpr int P2 = FA * (S - L0) * 2 * kFragBytes;         // single-buffered part
     static constexpr int LDS = 2 * P1 + P2;
     static_assert(LDS <= kLdsBytes, "stages do not fit LDS");
+    // operands are read D matrix instructions ahead of their first use (DO: the B slices that are not held in
+    // registers, ahead of each use).  Measured at s = 7, 8192^3: 3250 / 3200 / 3310 / 3140 / 3240 / 3205 TOP/s for
+    // D = 4 / 6 / 8 / 10 / 12 / 16 (reads one slice ahead, the earlier scheme: 3215); s = 4 is indifferent up to 24.
+    static constexpr int D = S == 4 ? 24 : 8, DO = 4;
 };
 
 template <int S, int MODE>
@@ -168,30 +220,45 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
     };
 
     // Schedule of a stage.  The slices of A go from the last to the first (the single-buffered ones, l >= L0,
-    // first); the operands of slice l - 1 (its A fragments, the one B slice it needs beyond those of slice l) are
-    // read while the products of slice l run.  Once the fragments of slice L0 - 1 are the next to be read nobody
-    // needs the single-buffered region any more (mid-stage barrier, at the START of slice L0), and when the
-    // products of slice 0 begin every read of the stage is done: the end-of-stage barrier stands there, and the
-    // first operands of the NEXT stage are read while the products of slice 0 run.  The copies of the next stage
-    // are issued one at a time behind single matrix instructions (double-buffered part from the start of the stage,
-    // the single-buffered part from the mid-stage barrier on), so that no wavefront leaves the matrix pipe alone
-    // for long.
-    // (s = 9: only the first HP slices of B are held in registers, the others are read when needed; at slice 0
-    // they are needed first, so that the end-of-stage barrier still follows the last read.)
+    // first); within a slice the slices of B go upwards, for slice 0 downwards.  Every operand is read G::D matrix
+    // instructions ahead of its first use.  Before the products of slice L0 nobody needs the single-buffered region
+    // any more (mid-stage barrier); before the products of slice 0 -- after the B slices that are read on demand,
+    // s = 9: only HP slices of B are held in registers -- every read of the stage is issued: the end-of-stage
+    // barrier stands there, and the operands of the first instructions of the NEXT stage are read behind it.  The
+    // copies of the next stage go one at a time behind single matrix instructions (double-buffered part from the
+    // start of the stage, the single-buffered part from the mid-stage barrier on).
     constexpr int HP = S >= 9 ? 7 : S;
     constexpr int NSLOT = S * (S - 1) / 2;                                  // products of the slices l > 0
     constexpr int NPRE = SPLIT ? (S - L0 - 1) * (S - L0) / 2 : NSLOT;        // ... of them before the mid-stage barrier
     constexpr int MPP = 4 * WMF * WNF;                                       // matrix instructions per product
     static_assert(NU1 <= NPRE * MPP && (!SPLIT || NU2 <= (NSLOT - NPRE) * MPP), "too few products to issue the copies behind");
-    v4i bf[HP][WNF][2], af[WMF][2];
+    using T = Sched16<S, MPP, HP, G::D, G::DO>;
+    constexpr int NM = T::NM;                           // matrix instructions of a stage, numbered in execution order
+    constexpr int EB = MPP * (NSLOT + (S - HP));        // the end-of-stage barrier stands before this one
+    constexpr int MB = MPP * NPRE;                      // the mid-stage barrier before this one
+
+    v4i A_[S][WMF][2], B_[HP][WNF][2], An_[S][WMF][2], Bn_[HP][WNF][2], Bo[S][S - HP + 1][WNF][2];
+    auto loadA = [&](v4i (&dst)[WMF][2], int l, const unsigned char *stage) {
 #pragma unroll
-    for (int i = 0; i < WMF; ++i)
+        for (int i = 0; i < WMF; ++i)
 #pragma unroll
-        for (int i2 = 0; i2 < 2; ++i2) af[i][i2] = readA(S - 1, lds, i, i2);
+            for (int i2 = 0; i2 < 2; ++i2) dst[i][i2] = readA(l, stage, i, i2);
+    };
+    auto loadB = [&](v4i (&dst)[WNF][2], int h, const unsigned char *stage) {
 #pragma unroll
-    for (int j = 0; j < WNF; ++j)
+        for (int j = 0; j < WNF; ++j)
 #pragma unroll
-        for (int j2 = 0; j2 < 2; ++j2) bf[0][j][j2] = readB(0, lds, j, j2);
+            for (int j2 = 0; j2 < 2; ++j2) dst[j][j2] = readB(h, stage, j, j2);
+    };
+    // the wrapped reads of the first stage
+    static_for<0, S>([&](auto L) {
+        constexpr int l = decltype(L)::value;
+        if constexpr (T::wrapped(T::gs(l))) loadA(A_[l], l, lds);
+    });
+    static_for<0, HP>([&](auto H) {
+        constexpr int h = decltype(H)::value;
+        if constexpr (T::wrapped(T::needB(h))) loadB(B_[h], h, lds);
+    });
 
     int buf = 0;
     for (int st = st0; st < nst; ++st) {
@@ -201,71 +268,72 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
         const unsigned vnext = lane * 16 + (unsigned)((more ? st + 1 : st) - st0) * (unsigned)STG;
         const unsigned ldsnext = ldsw + (buf ^ 1) * G::P1;
         const unsigned char *cur = lds + buf * G::P1, *nxt = lds + (buf ^ 1) * G::P1;
-        v4i afn[WMF][2], bfn[WNF][2];
-        int slot = 0;
-#pragma unroll
-        for (int l = S - 1; l >= 0; --l) {
-            if (SPLIT && l == L0) __syncthreads();
-            if (l > 0) {
+        static_for<0, NM>([&](auto E) {
+            constexpr int e = decltype(E)::value;
+            constexpr int l = T::slice_of(e), h = T::h_of(e), inner = e % MPP;
+            constexpr int j2 = inner % 2, i2 = (inner / 2) % 2, j = (inner / 4) % WNF, i = inner / 4 / WNF;
+            constexpr bool pin = T::any_read(e, EB) || e == EB || (SPLIT && e == MB);
+            if constexpr (pin) __builtin_amdgcn_sched_barrier(0);
+            // reads of this stage due before instruction e
+            static_for<0, S>([&](auto L2) {
+                constexpr int l2 = decltype(L2)::value;
+                if constexpr (!T::wrapped(T::gs(l2)) && T::issue_at(T::gs(l2), EB) == e) loadA(A_[l2], l2, cur);
+            });
+            static_for<0, HP>([&](auto H2) {
+                constexpr int h2 = decltype(H2)::value;
+                if constexpr (!T::wrapped(T::needB(h2)) && T::issue_at(T::needB(h2), EB) == e) loadB(B_[h2], h2, cur);
+            });
+            static_for<0, S>([&](auto L2) {
+                constexpr int l2 = decltype(L2)::value;
+                static_for<HP, S>([&](auto H2) {
+                    constexpr int h2 = decltype(H2)::value;
+                    if constexpr (h2 < S - l2 && T::pidx(l2, h2) - G::DO == e) loadB(Bo[l2][h2 - HP], h2, cur);
+                });
+            });
+            if constexpr (SPLIT && e == MB) __syncthreads();      // nobody reads the single-buffered region any more
+            if constexpr (e == EB) {
+                // nothing of this stage is left to read, and the next one must have landed
+                wait_vmcnt<0>();
+                __syncthreads();
+            }
+            // reads for the first instructions of the next stage
+            static_for<0, S>([&](auto L2) {
+                constexpr int l2 = decltype(L2)::value;
+                if constexpr (T::wrapped(T::gs(l2)) && T::issue_at(T::gs(l2), EB) == e) loadA(An_[l2], l2, nxt);
+            });
+            static_for<0, HP>([&](auto H2) {
+                constexpr int h2 = decltype(H2)::value;
+                if constexpr (T::wrapped(T::needB(h2)) && T::issue_at(T::needB(h2), EB) == e) loadB(Bn_[h2], h2, nxt);
+            });
+            if constexpr (pin) __builtin_amdgcn_sched_barrier(0);
+
+            const v4i bv = h < HP ? B_[h < HP ? h : 0][j][j2] : Bo[l][h >= HP ? h - HP : 0][j][j2];
+            acc[l + h][i][j][i2 * 2 + j2] =
+                __builtin_amdgcn_mfma_i32_16x16x64_i8(bv, A_[l][i][i2], acc[l + h][i][j][i2 * 2 + j2], 0, 0, 0);
+            // one copy of the next stage behind each of the first matrix instructions of the stage
+            // (double-buffered part) / after the mid-stage barrier (the rest)
+            if constexpr (e < NU1) issue1(std::integral_constant<int, (e < NU1 ? e : 0)>{}, vnext, ldsnext);
+            if constexpr (SPLIT && e >= MB && e - MB < NU2)
+                issue2(std::integral_constant<int, (e >= MB && e - MB < NU2 ? e - MB : 0)>{}, vnext);
+        });
+        static_for<0, S>([&](auto L) {
+            constexpr int l = decltype(L)::value;
+            if constexpr (T::wrapped(T::gs(l))) {
 #pragma unroll
                 for (int i = 0; i < WMF; ++i)
 #pragma unroll
-                    for (int i2 = 0; i2 < 2; ++i2) afn[i][i2] = readA(l - 1, cur, i, i2);
-                if (S - l < HP) {
-#pragma unroll
-                    for (int j = 0; j < WNF; ++j)
-#pragma unroll
-                        for (int j2 = 0; j2 < 2; ++j2) bf[S - l < HP ? S - l : 0][j][j2] = readB(S - l, cur, j, j2);
-                }
-                // (the reads stay ahead of the products they hide behind; at s = 4 the compiler's own order is as good)
-                if (S > 4) __builtin_amdgcn_sched_barrier(0);
+                    for (int i2 = 0; i2 < 2; ++i2) A_[l][i][i2] = An_[l][i][i2];
             }
+        });
+        static_for<0, HP>([&](auto H) {
+            constexpr int h = decltype(H)::value;
+            if constexpr (T::wrapped(T::needB(h))) {
 #pragma unroll
-            for (int hh = 0; hh < S - l; ++hh) {
-                const int h = l == 0 ? S - 1 - hh : hh;
-                if (l == 0 && h == HP - 1) {
-                    // nothing of this stage is left to read, and the next one must have landed
-                    wait_vmcnt<0>();
-                    __syncthreads();
+                for (int j = 0; j < WNF; ++j)
 #pragma unroll
-                    for (int i = 0; i < WMF; ++i)
-#pragma unroll
-                        for (int i2 = 0; i2 < 2; ++i2) afn[i][i2] = readA(S - 1, nxt, i, i2);
-#pragma unroll
-                    for (int j = 0; j < WNF; ++j)
-#pragma unroll
-                        for (int j2 = 0; j2 < 2; ++j2) bfn[j][j2] = readB(0, nxt, j, j2);
-                }
-#pragma unroll
-                for (int i = 0; i < WMF; ++i)
-#pragma unroll
-                    for (int j = 0; j < WNF; ++j)
-#pragma unroll
-                        for (int i2 = 0; i2 < 2; ++i2)
-#pragma unroll
-                            for (int j2 = 0; j2 < 2; ++j2) {
-                                const v4i bv = h < HP ? bf[h < HP ? h : 0][j][j2] : readB(h, cur, j, j2);
-                                acc[l + h][i][j][i2 * 2 + j2] = __builtin_amdgcn_mfma_i32_16x16x64_i8(
-                                    bv, af[i][i2], acc[l + h][i][j][i2 * 2 + j2], 0, 0, 0);
-                                // one copy of the next stage behind each of the first matrix instructions of
-                                // the stage (double-buffered part) / after the mid-stage barrier (the rest);
-                                // (spacing them 2 or 4 instructions apart changes nothing)
-                                const int e = slot * MPP + ((i * WNF + j) * 2 + i2) * 2 + j2;
-                                if (e < NU1) issue1_n(e, vnext, ldsnext);
-                                if (SPLIT && e >= NPRE * MPP && e - NPRE * MPP < NU2) issue2_n(e - NPRE * MPP, vnext);
-                            }
-                ++slot;
+                    for (int j2 = 0; j2 < 2; ++j2) B_[h][j][j2] = Bn_[h][j][j2];
             }
-            if (S > 4) __builtin_amdgcn_sched_barrier(0);   // (and no product of the next slice moves up to wait for them)
-#pragma unroll
-            for (int i = 0; i < WMF; ++i)
-#pragma unroll
-                for (int i2 = 0; i2 < 2; ++i2) af[i][i2] = afn[i][i2];
-        }
-#pragma unroll
-        for (int j = 0; j < WNF; ++j)
-#pragma unroll
-            for (int j2 = 0; j2 < 2; ++j2) bf[0][j][j2] = bfn[j][j2];
+        });
         buf ^= 1;
     }
 
