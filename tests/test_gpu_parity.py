@@ -164,7 +164,8 @@ def test_int32_slice_products_bit_exact(m, n, k):
 @pytest.mark.parametrize("m,n,k,s", [(33, 70, 17, 3), (128, 128, 128, 3), (100, 90, 70, 7), (257, 130, 300, 9),
                                      (130, 257, 513, 1), (64, 64, 2048, 6), (100, 300, 70, 12), (129, 129, 200, 4), (200, 100, 64, 2),
                                      (100, 90, 70, 13), (130, 70, 300, 16), (65, 129, 200, 17), (257, 130, 100, 18),
-                                     (70, 130, 150, 19), (130, 130, 96, 20)])
+                                     (70, 130, 150, 19), (130, 130, 96, 20), (130, 70, 200, 10), (70, 200, 130, 11),
+                                     (300, 200, 260, 5), (200, 300, 520, 8)])
 def test_int32_diagonal_sums_of_fused_kernel_bit_exact(m, n, k, s):
     A, B = workloads.uniform(m, n, k, 22)
     pa, _ = oracle.split("A", A, s)
@@ -246,7 +247,7 @@ def test_k_blocked_accumulation_beyond_the_int32_range():
     assert_c_matches(host(ozimmu.dgemm(dev(A), dev(B), 7)), oracle.dgemm(A, B, 7), "k-blocked lognormal")
 
 
-@pytest.mark.parametrize("s", [4, 5, 6, 7, 8, 9, 12, 13, 16, 17, 18, 19, 20])
+@pytest.mark.parametrize("s", [4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 16, 17, 18, 19, 20])
 def test_k_blocked_on_every_fused_kernel(s):
     # the fused kernels (16x16x64 for s = 4, 5, 7, 8, 9 -- 6 only without split-k --; 32x32x32 otherwise, with four 512-register wavefronts beyond
     # s = 12) in split-k mode, several tiles and k-blocks
