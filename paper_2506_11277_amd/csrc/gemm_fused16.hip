@@ -275,21 +275,23 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
             constexpr bool pin = T::any_read(e, EB) || e == EB || (SPLIT && e == MB);
             if constexpr (pin) __builtin_amdgcn_sched_barrier(0);
             // reads of this stage due before instruction e
-            static_for<0, S>([&](auto L2) {
-                constexpr int l2 = decltype(L2)::value;
-                if constexpr (!T::wrapped(T::gs(l2)) && T::issue_at(T::gs(l2), EB) == e) loadA(A_[l2], l2, cur);
-            });
-            static_for<0, HP>([&](auto H2) {
-                constexpr int h2 = decltype(H2)::value;
-                if constexpr (!T::wrapped(T::needB(h2)) && T::issue_at(T::needB(h2), EB) == e) loadB(B_[h2], h2, cur);
-            });
-            static_for<0, S>([&](auto L2) {
-                constexpr int l2 = decltype(L2)::value;
-                static_for<HP, S>([&](auto H2) {
-                    constexpr int h2 = decltype(H2)::value;
-                    if constexpr (h2 < S - l2 && T::pidx(l2, h2) - G::DO == e) loadB(Bo[l2][h2 - HP], h2, cur);
+            if constexpr (T::any_read(e, EB)) {
+                static_for<0, S>([&](auto L2) {
+                    constexpr int l2 = decltype(L2)::value;
+                    if constexpr (!T::wrapped(T::gs(l2)) && T::issue_at(T::gs(l2), EB) == e) loadA(A_[l2], l2, cur);
                 });
-            });
+                static_for<0, HP>([&](auto H2) {
+                    constexpr int h2 = decltype(H2)::value;
+                    if constexpr (!T::wrapped(T::needB(h2)) && T::issue_at(T::needB(h2), EB) == e) loadB(B_[h2], h2, cur);
+                });
+                static_for<0, S>([&](auto L2) {
+                    constexpr int l2 = decltype(L2)::value;
+                    static_for<HP, S>([&](auto H2) {
+                        constexpr int h2 = decltype(H2)::value;
+                        if constexpr (h2 < S - l2 && T::pidx(l2, h2) - G::DO == e) loadB(Bo[l2][h2 - HP], h2, cur);
+                    });
+                });
+            }
             if constexpr (SPLIT && e == MB) __syncthreads();      // nobody reads the single-buffered region any more
             if constexpr (e == EB) {
                 // nothing of this stage is left to read, and the next one must have landed
@@ -297,14 +299,16 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
                 __syncthreads();
             }
             // reads for the first instructions of the next stage
-            static_for<0, S>([&](auto L2) {
-                constexpr int l2 = decltype(L2)::value;
-                if constexpr (T::wrapped(T::gs(l2)) && T::issue_at(T::gs(l2), EB) == e) loadA(An_[l2], l2, nxt);
-            });
-            static_for<0, HP>([&](auto H2) {
-                constexpr int h2 = decltype(H2)::value;
-                if constexpr (T::wrapped(T::needB(h2)) && T::issue_at(T::needB(h2), EB) == e) loadB(Bn_[h2], h2, nxt);
-            });
+            if constexpr (T::any_read(e, EB)) {
+                static_for<0, S>([&](auto L2) {
+                    constexpr int l2 = decltype(L2)::value;
+                    if constexpr (T::wrapped(T::gs(l2)) && T::issue_at(T::gs(l2), EB) == e) loadA(An_[l2], l2, nxt);
+                });
+                static_for<0, HP>([&](auto H2) {
+                    constexpr int h2 = decltype(H2)::value;
+                    if constexpr (T::wrapped(T::needB(h2)) && T::issue_at(T::needB(h2), EB) == e) loadB(Bn_[h2], h2, nxt);
+                });
+            }
             if constexpr (pin) __builtin_amdgcn_sched_barrier(0);
 
             const v4i bv = h < HP ? B_[h < HP ? h : 0][j][j2] : Bo[l][h >= HP ? h - HP : 0][j][j2];
