@@ -233,6 +233,8 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
     constexpr int MPP = 4 * WMF * WNF;                                       // matrix instructions per product
     static_assert(NU1 <= NPRE * MPP && (!SPLIT || NU2 <= (NSLOT - NPRE) * MPP), "too few products to issue the copies behind");
     using T = Sched16<S, MPP, HP, G::D, G::DO>;
+    // (a B slice that is not held is first needed in slice S - 1 - HP or later: its read-ahead stays inside the stage)
+    static_assert(HP == S || T::pidx(S - 1 - HP, HP) >= G::DO, "on-demand reads must not precede the stage");
     constexpr int NM = T::NM;                           // matrix instructions of a stage, numbered in execution order
     constexpr int EB = MPP * (NSLOT + (S - HP));        // the end-of-stage barrier stands before this one
     constexpr int MB = MPP * NPRE;                      // the mid-stage barrier before this one
