@@ -80,6 +80,20 @@ def test_size_queries_and_argument_validation_without_gpu(handle):
     assert handle.ozimmu_split(b"A", 4, 4, fake, 4, 2, fake, fake, 7, ws, None) == 1
 
 
+def test_workspace_accounts_for_nearly_equal_slice_counts_run_as_equal(handle):
+    # counts that differ little run as equal counts with zero slices appended to the short operand: the workspace
+    # is then that of the equal counts; counts that differ much keep planes of their own sizes
+    w = lambda sA, sB, allp=0: handle.ozimmu_workspace_bytes2(256, 256, 256, sA, sB, allp)
+    assert w(7, 8) == w(8, 8) == w(8, 7)
+    assert w(17, 18) == w(18, 18) and w(19, 20) == w(20, 20)
+    assert w(5, 8) == w(8, 8)
+    assert w(8, 8) - w(4, 8) == 4 * 256 * 256           # (4, 8) is not padded: four slices less of A
+    assert w(12, 12) - w(9, 12) == 3 * 256 * 256
+    assert w(5, 4, 1) == w(5, 5, 1)                     # all products of nearly equal counts
+    assert w(5, 2, 1) < w(5, 5, 1)
+    assert w(25, 31) < w(31, 31)                        # beyond the fused kernels nothing is padded
+
+
 def test_level_size_limit_and_variant_argument_validation_without_gpu(handle):
     # largest Q with  min(sA, sB) k 127^2 (1 + 2^7 + ... + 2^{7(Q-1)}) < 2^53, recomputed with Python integers
     for k in (0, 1, 64, 128, 1000, 8192, 2 ** 17, 2 ** 18, 2 ** 31 - 1):
