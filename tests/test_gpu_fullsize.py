@@ -117,6 +117,28 @@ def test_large_ragged_shapes():
     m, n, k = 5003, 7001, 3001
     dA, dB = workloads.lognormal_device(m, n, k, 1.0, 2024)
     for sA, sB, allp, nearest, Q in [(7, 7, False, False, 1), (14, 14, False, False, 3), (5, 10, False, True, 2),
-                                     (6, 6, True, False, 1), (22, 22, False, False, 1)]:
+                                     (6, 6, True, False, 1), (22, 22, False, False, 1), (4, 4, False, False, 1),
+                                     (7, 8, False, False, 1)]:
         print(f"ragged sA={sA} sB={sB} all={allp} nearest={nearest} Q={Q}", flush=True)
         check_sampled_variant(dA, dB, sA, sB, allp, nearest, Q, f"ragged ({sA},{sB}) all={allp}")
+
+
+def test_uneven_regions_of_the_two_dimensional_tile_order():
+    # 63 tile rows of 128: the four row bands of the XCD grid hold 15, 16, 16, 16 tile rows, the launch is padded
+    # to 8 x the largest region and the surplus work-groups must leave without touching anything
+    m, n, k = 8057, 1000, 700
+    dA, dB = workloads.lognormal_device(m, n, k, 1.0, 2025)
+    for s in (7, 4, 10, 13):
+        print(f"uneven regions s={s}", flush=True)
+        check_sampled_variant(dA, dB, s, s, False, False, 1, f"uneven regions s={s}")
+    # every entry, not only the sampled ones: the kernel with the 64 x 64 tile (another tile grid, other regions)
+    # must give the same matrix bit for bit, and the sampled entries of one of them are the oracle's
+    for s in (7, 4, 10):
+        C1 = ozimmu.dgemm(dA, dB, s)
+        try:
+            ozimmu.debug_small_tile_limit(1 << 40)
+            C2 = ozimmu.dgemm(dA, dB, s)
+        finally:
+            ozimmu.debug_small_tile_limit(256)
+        assert not bool(torch.isnan(C1).any()) and bool(torch.equal(C1, C2)), f"uneven regions s={s}: tile shapes differ"
+
