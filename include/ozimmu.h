@@ -38,6 +38,7 @@ extern "C" {
 #define OZIMMU_NONFINITE 2    /* NaN or Inf met in A or B */
 #define OZIMMU_HIP_ERROR 3    /* a HIP runtime call failed */
 #define OZIMMU_UNREACHABLE 4  /* estimator: tolerance not met by any s <= OZIMMU_MAX_SLICES */
+#define OZIMMU_TOO_LARGE 5    /* ozimmu_dgemm_static: the problem needs more than OZIMMU_STATIC_WORKSPACE_BYTES */
 
 #define OZIMMU_MAX_SLICES 32
 #define OZIMMU_SLICE_BITS 7
@@ -133,6 +134,23 @@ int ozimmu_split2(char side, int rows, int cols, const double *X, int ldx, int s
  */
 int ozimmu_dgemm(int m, int n, int k, const double *A, int lda, const double *B, int ldb,
                  double *C, int ldc, int s, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * ozimmu_dgemm for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  The workspace (scale exponents, slice planes,
+ * split-k totals) is a static device array of OZIMMU_STATIC_WORKSPACE_BYTES inside the library, of which every
+ * GPU the library runs on holds one copy until the process ends; the call allocates nothing and calls no
+ * allocating routine.  Same result as ozimmu_dgemm, bit for bit.
+ *   - Problems with ozimmu_workspace_bytes(m, n, k, s) > OZIMMU_STATIC_WORKSPACE_BYTES return OZIMMU_TOO_LARGE
+ *     and touch nothing (64 MiB: e.g. 2048^3 with 7 slices, 1024^3 with 28).
+ *   - All calls on one GPU share that GPU's array, which keeps the last call's contents (the kernels clear what
+ *     they need cleared): calls that overlap on one GPU -- different streams, different threads -- race.  Calls on
+ *     one stream are ordered and safe.
+ *   - ozimmu_check() is not available for it (the array is not exposed); inputs must be finite.
+ */
+#define OZIMMU_STATIC_WORKSPACE_BYTES (64u << 20)
+int ozimmu_dgemm_static(int m, int n, int k, const double *A, int lda, const double *B, int ldb,
+                        double *C, int ldc, int s, void *stream);
 
 /*
  * The same with sA slices of A and sB slices of B (Sect. 4, subsection "Reduction in number of

@@ -1,6 +1,7 @@
 // extern "C" boundary of libozimmu: argument checks, workspace carve-up, kernel sequencing.
 #include <cmath>
 #include <cstring>
+#include <mutex>
 
 #include "oz_common.h"
 
@@ -62,6 +63,7 @@ const char *ozimmu_status_string(int status)
         case OZIMMU_NONFINITE: return "non-finite input";
         case OZIMMU_HIP_ERROR: return "HIP runtime error";
         case OZIMMU_UNREACHABLE: return "tolerance unreachable";
+        case OZIMMU_TOO_LARGE: return "problem too large for the static workspace";
     }
     return "unknown status";
 }
@@ -278,6 +280,45 @@ int ozimmu_dgemm3(int m, int n, int k, const double *A, int lda, const double *B
 {
     return dgemm_impl(m, n, k, A, lda, B, ldb, C, ldc, sA, sB, all_products != 0, splitting, level_diagonals,
                       workspace, workspace_bytes, stream);
+}
+
+// ---- the entry point that allocates nothing ----------------------------------------------------------------
+// Its workspace is this file-scope device array: every GPU the library runs on holds one copy of it, at an address
+// of its own, until the process ends.  In host code the array's name is only a handle for hipGetSymbolAddress; the
+// address that kernels and copies take is looked up once per device (with that device current) and kept.
+static __device__ __align__(256) unsigned char scratch[OZIMMU_STATIC_WORKSPACE_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+// device address of `scratch` on the current device (null on failure)
+void *static_workspace()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return nullptr;
+        g_scratch_ptr[dev] = p;
+    }
+    return g_scratch_ptr[dev];
+}
+}  // namespace
+
+int ozimmu_dgemm_static(int m, int n, int k, const double *A, int lda, const double *B, int ldb, double *C, int ldc,
+                        int s, void *stream)
+{
+    if (m < 0 || n < 0 || k < 0 || s < 1 || s > OZIMMU_MAX_SLICES) return OZIMMU_BAD_ARG;
+    if (carve(m, n, k, s, s).total > (size_t)OZIMMU_STATIC_WORKSPACE_BYTES) return OZIMMU_TOO_LARGE;
+    void *ws = static_workspace();
+    if (!ws) return OZIMMU_HIP_ERROR;
+    // every kernel of the path clears what it needs to find cleared (header, maxima, split-k totals) with fill
+    // kernels of its own, so the contents the last call left behind do not matter
+    return dgemm_impl(m, n, k, A, lda, B, ldb, C, ldc, s, s, false, OZIMMU_SPLIT_TRUNCATE, 1, ws,
+                      (size_t)OZIMMU_STATIC_WORKSPACE_BYTES, stream);
 }
 
 int ozimmu_profile_start(int max_calls)

@@ -12,7 +12,8 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libozimmu.so")
 
-OK, BAD_ARG, NONFINITE, HIP_ERROR, UNREACHABLE = 0, 1, 2, 3, 4
+OK, BAD_ARG, NONFINITE, HIP_ERROR, UNREACHABLE, TOO_LARGE = 0, 1, 2, 3, 4, 5
+STATIC_WORKSPACE_BYTES = 64 << 20
 MAX_SLICES = 32
 LAYOUT_PLAIN, LAYOUT_MFMA = 0, 1
 SPLIT_TRUNCATE, SPLIT_NEAREST = 0, 1
@@ -30,6 +31,8 @@ _SIGNATURES = {
                                 _c.c_void_p, _c.c_int, _c.c_void_p, _c.c_void_p]),
     "ozimmu_dgemm": (_c.c_int, [_c.c_int, _c.c_int, _c.c_int, _c.c_void_p, _c.c_int, _c.c_void_p, _c.c_int,
                                 _c.c_void_p, _c.c_int, _c.c_int, _c.c_void_p, _c.c_size_t, _c.c_void_p]),
+    "ozimmu_dgemm_static": (_c.c_int, [_c.c_int, _c.c_int, _c.c_int, _c.c_void_p, _c.c_int, _c.c_void_p, _c.c_int,
+                                       _c.c_void_p, _c.c_int, _c.c_int, _c.c_void_p]),
     "ozimmu_workspace_bytes2": (_c.c_size_t, [_c.c_int] * 6),
     "ozimmu_dgemm2": (_c.c_int, [_c.c_int, _c.c_int, _c.c_int, _c.c_void_p, _c.c_int, _c.c_void_p, _c.c_int,
                                  _c.c_void_p, _c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_void_p, _c.c_size_t,
@@ -157,6 +160,22 @@ def dgemm(A, B, s, C=None, workspace=None, check_finite=False):
         raise OzimmuError(rc, "dgemm")
     if check_finite:
         check(workspace)
+    return C
+
+
+def dgemm_static(A, B, s, C):
+    """dgemm through the library's static workspace: the call allocates nothing, so C must be given.
+    Raises OzimmuError(TOO_LARGE) beyond STATIC_WORKSPACE_BYTES of workspace."""
+    lda = _colmajor_ld(A, "A")
+    ldb = _colmajor_ld(B, "B")
+    ldc = _colmajor_ld(C, "C")
+    m, k = A.shape
+    k2, n = B.shape
+    if k != k2 or tuple(C.shape) != (m, n):
+        raise ValueError("shapes do not match")
+    rc = lib().ozimmu_dgemm_static(m, n, k, A.data_ptr(), lda, B.data_ptr(), ldb, C.data_ptr(), ldc, s, _stream())
+    if rc != OK:
+        raise OzimmuError(rc, "dgemm_static")
     return C
 
 
