@@ -40,13 +40,14 @@ def error_measures(C, A, B, Cref):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="pow2_scaled_8192")
     ap.add_argument("--slices", type=int, default=7)
-    ap.add_argument("--sweep", action="store_true", help="also time every slice count of the workload (extra keys)")
+    ap.add_argument("--no-sweep", action="store_true",
+                    help="skip the per-slice-count sweep of the workload (the `sweep` array of the output)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample", type=int, default=2048, help="rows of A and columns of B in the oracle sample")
+    ap.add_argument("--cpu-sample", type=int, default=1536, help="rows of A and columns of B in the oracle sample")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a known amount of HBM traffic) so that "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings can be scaled")
@@ -97,11 +98,19 @@ def main():
     split_bytes = (8.0 + s) * (m * k + k * n)
     scales_bytes = 8.0 * (m * k + k * n)
 
+    # bytes beyond the L2s per GEMM launch, per slice count, from the rocprofv3 --pmc runs summarised under
+    # profiles/ (null for a slice count or workload that has not been measured)
+    measured = {}
+    tfile = os.path.join(ROOT, "paper_2506_11277_amd", "measured_traffic.json")
+    if os.path.exists(tfile):
+        measured = json.load(open(tfile))
     traffic = args.traffic_bytes
     if traffic is None:
-        tfile = os.path.join(ROOT, "paper_2506_11277_amd", "measured_traffic.json")
-        if os.path.exists(tfile):
-            traffic = json.load(open(tfile)).get(f"{args.workload}:{s}")
+        traffic = measured.get(f"{args.workload}:{s}")
+
+    def kernel_name(ss):
+        # which GEMM kernel the library runs for equal slice counts (csrc/gemm.hip, launch_gemm_fused)
+        return ("gemm_fused16_kernel" if 4 <= ss <= 9 else "gemm_fused_kernel") if ss <= 20 else "gemm_banded_kernel"
 
     out = {
         "metric": "effective FP64 TFLOP/s (2mnk/t) vs slices s; % of int8 MFMA peak",
@@ -118,9 +127,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": args.workload, "m": m, "n": n, "k": k, "slices": s, "slice_pairs": pairs},
         "roofline": {
-            # which GEMM kernel the library runs for equal slice counts (see csrc/gemm.hip, launch_gemm_fused)
-            "kernel": ("gemm_fused16_kernel" if 4 <= s <= 9 else "gemm_fused_kernel") if s <= 20
-                      else "gemm_banded_kernel",
+            "kernel": kernel_name(s),
             "bound": "mfma",
             "achieved": int8_tops,
             "peak": INT8_PEAK_TOPS,
@@ -202,16 +209,19 @@ def main():
     except Exception as exc:  # context only
         out["native_int8_gemm"] = {"error": str(exc)[:200]}
 
-    if args.sweep:
+    if not args.no_sweep:
+        # the metric is a curve over the slice count: every s of the workload, each timed like the headline
         sweep = []
         for ss in cfg["s"]:
-            dts, ph = run(ss, max(3, args.steps // 2), 1)
+            dts, ph = run(ss, max(5, args.steps // 2), 2)
             pp = ss * (ss + 1) // 2
             ozimmu.dgemm(dA, dB, ss, C=C)
             nw, cw = error_measures(C, dA, dB, Cref)
+            tops = flops * pp / (ph["gemm"] * 1e-3) / 1e12
             sweep.append({"s": ss, "ms_per_step": dts * 1e3, "tflops_effective": flops / dts / 1e12,
-                          "gemm_ms": ph["gemm"], "int8_tops": flops * pp / (ph["gemm"] * 1e-3) / 1e12,
-                          "frac_int8_peak": flops * pp / (ph["gemm"] * 1e-3) / 1e12 / INT8_PEAK_TOPS,
+                          "kernel": kernel_name(ss), "gemm_ms": ph["gemm"], "scales_ms": ph["scales"],
+                          "split_ms": ph["split"], "int8_tops": tops, "frac_int8_peak": tops / INT8_PEAK_TOPS,
+                          "traffic": measured.get(f"{args.workload}:{ss}"),
                           "normwise_err": nw, "max_componentwise_err": cw})
         out["sweep"] = sweep
         tol = 2.0 ** -53

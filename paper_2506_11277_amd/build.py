@@ -7,7 +7,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libozimmu.so")
 SOURCES = ["api.hip", "reduce.hip", "split.hip", "gemm.hip", "gemm_fused16.hip", "gemm_banded.hip", "ceiling.hip"]
-HEADERS = [os.path.join(CSRC, "oz_common.h"), os.path.join(CSRC, "gemm_dev.h"), os.path.join(HERE, "..", "include", "ozimmu.h")]
+HEADERS = [os.path.join(CSRC, "oz_common.h"), os.path.join(CSRC, "gemm_dev.h"), os.path.join(HERE, "..", "include", "ozimmu.h"),
+           os.path.join(HERE, "..", "include", "ozimmu_bench.h")]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-fast-math", "-ffp-contract=on",

@@ -23,16 +23,27 @@ inline bool bad_matrix(int rows, int cols, const void *p, int ld)
         if (e__ != hipSuccess) return OZIMMU_HIP_ERROR;     \
     } while (0)
 
-// Optional per-phase timing of ozimmu_dgemm with HIP events recorded on the caller's stream.
+// Optional per-phase timing of ozimmu_dgemm with HIP events recorded on the caller's stream.  One timer per
+// process, guarded by a mutex; a call claims its slot of four events when it starts, so calls from several threads
+// never share events (their phases then interleave on the device, which is why the header asks for one thread).
 struct Profile {
+    std::mutex mutex;
     bool on = false;
     int capacity = 0, calls = 0;
     hipEvent_t *ev = nullptr;   // 4 events per call: start, after scales, after split, after gemm
 } g_prof;
 
-inline void prof_mark(int phase, hipStream_t st)
+// slot of this call's events, or null when the timer is off or full
+inline hipEvent_t *prof_claim()
 {
-    if (g_prof.on && g_prof.calls < g_prof.capacity) (void)hipEventRecord(g_prof.ev[4 * g_prof.calls + phase], st);
+    std::lock_guard<std::mutex> lock(g_prof.mutex);
+    if (!g_prof.on || g_prof.calls >= g_prof.capacity) return nullptr;
+    return g_prof.ev + 4 * (size_t)g_prof.calls++;
+}
+
+inline void prof_mark(hipEvent_t *slot, int phase, hipStream_t st)
+{
+    if (slot) (void)hipEventRecord(slot[phase], st);
 }
 
 // scales of both operands into the workspace (optionally with the minima for kappa)
@@ -231,7 +242,8 @@ static int dgemm_impl(int m, int n, int k, const double *A, int lda, const doubl
     // exact conversion of a diagonal sum to binary64 needs s * k * 127^2 < 2^53: true for every int k
     hipStream_t st = (hipStream_t)stream;
     char *ws = (char *)workspace;
-    prof_mark(0, st);
+    hipEvent_t *prof = (m > 0 && n > 0) ? prof_claim() : nullptr;
+    prof_mark(prof, 0, st);
     auto *eA = (int32_t *)(ws + w.off_expA), *eB = (int32_t *)(ws + w.off_expB);
     auto *pA = (int8_t *)(ws + w.off_planesA), *pB = (int8_t *)(ws + w.off_planesB);
     // three launches for the scales of both operands, one for their slices
@@ -239,10 +251,10 @@ static int dgemm_impl(int m, int n, int k, const double *A, int lda, const doubl
                                (unsigned long long *)(ws + w.off_maxA), (unsigned long long *)(ws + w.off_maxB), eA,
                                w.mp, eB, w.np, nearest ? 1 : 0, st));
     if (m == 0 || n == 0) return OZIMMU_OK;
-    prof_mark(1, st);
+    prof_mark(prof, 1, st);
     // (w.cA, w.cB: the counts the GEMM runs with -- counts that differ little run as equal ones, zero slices appended)
     OZ_TRY(launch_split_both(m, n, k, A, lda, B, ldb, sA, sB, w.cA, w.cB, eA, eB, pA, pB, nearest, st));
-    prof_mark(2, st);
+    prof_mark(prof, 2, st);
     const int cA = w.cA, cB = w.cB;
     const bool fused = fused_handles(cA, cB, all_products);
     if (fused && fused_single_block(cA, cB, k)) {
@@ -255,8 +267,7 @@ static int dgemm_impl(int m, int n, int k, const double *A, int lda, const doubl
         long long *totals = banded_totals_bytes(cA, cB, k) ? (long long *)(ws + w.off_totals) : nullptr;
         OZ_TRY(launch_gemm_banded(m, n, w.kp, cA, cB, dmax, pA, pB, eA, eB, C, ldc, totals, Q, st));
     }
-    prof_mark(3, st);
-    if (g_prof.on && g_prof.calls < g_prof.capacity) ++g_prof.calls;
+    prof_mark(prof, 3, st);
     return OZIMMU_OK;
 }
 
@@ -323,10 +334,18 @@ int ozimmu_dgemm_static(int m, int n, int k, const double *A, int lda, const dou
 
 int ozimmu_profile_start(int max_calls)
 {
+    std::lock_guard<std::mutex> lock(g_prof.mutex);
     if (max_calls < 1 || max_calls > 4096 || g_prof.on) return OZIMMU_BAD_ARG;
     g_prof.ev = new hipEvent_t[4 * (size_t)max_calls];
     for (int i = 0; i < 4 * max_calls; ++i)
-        if (hipEventCreate(&g_prof.ev[i]) != hipSuccess) return OZIMMU_HIP_ERROR;
+        if (hipEventCreate(&g_prof.ev[i]) != hipSuccess) {
+            // give back what was created: the timer stays off and empty
+            for (int j = 0; j < i; ++j) (void)hipEventDestroy(g_prof.ev[j]);
+            delete[] g_prof.ev;
+            g_prof.ev = nullptr;
+            g_prof.capacity = g_prof.calls = 0;
+            return OZIMMU_HIP_ERROR;
+        }
     g_prof.capacity = max_calls;
     g_prof.calls = 0;
     g_prof.on = true;
@@ -335,6 +354,7 @@ int ozimmu_profile_start(int max_calls)
 
 int ozimmu_profile_stop(int *calls, float *phase_ms)
 {
+    std::lock_guard<std::mutex> lock(g_prof.mutex);
     if (!g_prof.on || !calls || !phase_ms) return OZIMMU_BAD_ARG;
     g_prof.on = false;
     int rc = OZIMMU_OK;

@@ -595,7 +595,7 @@ struct FusedCfgSmall {
     static constexpr int WVM = 2, WVN = 2, WMF = 1, WNF = 1, FR = 4, KB32 = 1, NSTAGE = 2;
 };
 constexpr int kSmallMaxS = 12;
-long long g_small_below_tiles = 256;           // fewer work-groups than CUs of an MI355X (test hook: 0 switches it off)
+std::atomic<long long> g_small_below_tiles{256};          // fewer work-groups than CUs of an MI355X (test hook: 0 switches it off)
 
 constexpr int kFusedMaxUneq = 18; // most accumulator sets for different slice counts and for all products
 constexpr int kFusedMaxS = 20;   // 16 accumulator registers per diagonal: 12 fit 256 registers, 20 fit 512 (BIG);
@@ -624,7 +624,7 @@ hipError_t launch_fused_s(int m, int n, int kp, const int8_t *pA, const int8_t *
     static_assert(NSTAGE * STAGE <= kLdsBytes, "LDS ring too large");
     static_assert(kPad % TM == 0 && kPad % TN == 0 && (kPad / kFrag) % Cfg::KB32 == 0, "tiles must divide the padding");
     auto kern = gemm_fused_kernel<S, Cfg::WVM, Cfg::WVN, Cfg::WMF, Cfg::WNF, Cfg::KB32, NSTAGE, MODE, PSET>;
-    static unsigned long long configured = 0;
+    static std::atomic<unsigned long long> configured{0};
     if (hipError_t e = allow_dynamic_lds((const void *)kern, NSTAGE * STAGE, configured); e != hipSuccess) return e;
     const int tiles_m = (m + TM - 1) / TM, tiles_n = (n + TN - 1) / TN;
     if (MODE != kBlocked) {
@@ -657,10 +657,11 @@ hipError_t dispatch_fused(int s, int m, int n, int kp, const int8_t *pA, const i
                           hipStream_t st)
 {
     switch (s) {
-    // (equal counts 4 ... 9 run in the 16x16x64 kernel -- 6 except in split-k mode -- and are not instantiated here)
+    // (equal counts 2 ... 9 run in the 16x16x64 kernel -- 2, 3 and 6 except in split-k mode -- and are not
+    // instantiated here)
 #define OZ_CASE(S_) \
     case S_: \
-        if constexpr (PSET != 0 || S_ < 4 || S_ > 9 || (S_ == 6 && MODE == kBlocked)) \
+        if constexpr (PSET != 0 || S_ < 2 || S_ > 9 || ((S_ <= 3 || S_ == 6) && MODE == kBlocked)) \
             return launch_fused_s<S_, MODE, PSET>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, Q, sm, st); \
         break;
         OZ_CASE(2) OZ_CASE(3) OZ_CASE(4) OZ_CASE(5) OZ_CASE(6) OZ_CASE(7) OZ_CASE(8) OZ_CASE(9) OZ_CASE(10) OZ_CASE(11) OZ_CASE(12) OZ_CASE(13) OZ_CASE(14) OZ_CASE(15) OZ_CASE(16) OZ_CASE(17) OZ_CASE(18)
@@ -729,13 +730,13 @@ bool fused_single_block(int sA, int sB, int k)
 
 // Split-k runs over column panels of C, one after the other, so that the totals of a panel (8 bytes per diagonal
 // and entry) stay near kPanelBytes whatever the size of C: columns per panel, a multiple of the padding.
-long long g_panel_bytes = 1LL << 30;
+std::atomic<long long> g_panel_bytes{1LL << 30};
 void fused_set_panel_bytes(long long bytes) { g_panel_bytes = bytes > 0 ? bytes : (1LL << 62); }
 
 static int fused_panel_cols(int diagonals, int m, int n)
 {
     const long long mp = round_up(m > 0 ? m : 1, kPad), np = round_up(n > 0 ? n : 1, kPad);
-    long long w = g_panel_bytes / (8LL * mp * diagonals) / kPad * kPad;
+    long long w = g_panel_bytes.load() / (8LL * mp * diagonals) / kPad * kPad;
     if (w < kPad) w = kPad;
     return (int)(w < np ? w : np);
 }
@@ -804,7 +805,7 @@ static hipError_t launch_gemm_fused_once(int m, int n, int kp, int sA, int sB, b
             else { tm = 128; tn = 64; }
             const long long tiles = (long long)((m + tm - 1) / tm) * ((n + tn - 1) / tn);
             const long long small_tiles = (long long)((m + 63) / 64) * ((n + 63) / 64);
-            if (tiles < g_small_below_tiles && small_tiles > tiles)
+            if (tiles < g_small_below_tiles.load() && small_tiles > tiles)
                 return dispatch_fused_small(s, m, n, kp, pA, pB, eA, eB, C, ldc, Q, st);
         }
         // the 16x16x64 kernel where it is the faster one

@@ -251,7 +251,7 @@ hipError_t launch_band(int m, int n, int kp, int sA, int sB, int dmax, const int
     using Geo = BandGeom<CHUNK_A, KB32>;
     static_assert(2 * Geo::STAGE <= kLdsBytes, "LDS double buffer too large");
     auto kern = gemm_banded_kernel<TOTALS, CHUNK_A, KB32>;
-    static unsigned long long configured = 0;
+    static std::atomic<unsigned long long> configured{0};
     if (hipError_t e = allow_dynamic_lds((const void *)kern, 2 * Geo::STAGE, configured); e != hipSuccess) return e;
     const int tiles_m = (m + 127) / 128, tiles_n = (n + 63) / 64;
     const int ntiles = tiles_m * tiles_n;

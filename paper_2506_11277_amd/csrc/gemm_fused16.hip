@@ -1,4 +1,4 @@
-// Fused slice-product kernel built on v_mfma_i32_16x16x64_i8 (written for s <= 9, used for s = 4 ... 9).
+// Fused slice-product kernel built on v_mfma_i32_16x16x64_i8 (equal slice counts 2 ... 9).
 //
 // Same computation as gemm_fused_kernel in gemm.hip (all s(s+1)/2 products of Algorithm 1, Sect. 3,
 // per-diagonal int32 sums, binary64 accumulation by ascending diagonal), same plane layout, same
@@ -80,25 +80,61 @@ struct Sched16 {
     }
 };
 
+// Experiments: -DOZ_EXP_S=<s> overrides the shape tabulated for that slice count with OZ_EXP_WVM/WVN/WMF/WNF
+// (wavefront grid and 32 x 32 fragments per wavefront), OZ_EXP_L0, OZ_EXP_D, OZ_EXP_HP.
+#ifndef OZ_EXP_S
+#define OZ_EXP_S -1
+#define OZ_EXP_WVM 4
+#define OZ_EXP_WVN 2
+#define OZ_EXP_WMF 1
+#define OZ_EXP_WNF 1
+#endif
+#ifndef OZ_EXP_L0
+#define OZ_EXP_L0 -1
+#endif
+#ifndef OZ_EXP_D
+#define OZ_EXP_D -1
+#endif
+#ifndef OZ_EXP_HP
+#define OZ_EXP_HP -1
+#endif
+#ifndef OZ_EXP_NSTG
+#define OZ_EXP_NSTG -1
+#endif
+
 template <int S>
 struct Cfg16 {
+    static constexpr bool EXP = S == OZ_EXP_S;
+    // s = 2: tile 256 x 128 (4 x 2 wavefronts of 64 x 64: 64 accumulator registers per diagonal);
     // tile 128 x 128 (2 x 4 wavefronts of 64 x 32) while 32 * S accumulator registers are affordable and the
     // stages fit (s = 5: two 80 KiB stages, all of LDS), else 128 x 64 (4 x 2 wavefronts of 32 x 32)
-    static constexpr bool WIDE = S <= 5;
-    static constexpr int WVM = WIDE ? 2 : 4, WVN = WIDE ? 4 : 2, WMF = WIDE ? 2 : 1, WNF = 1;
+    static constexpr bool HUGE = S == 2, WIDE = S >= 3 && S <= 5;
+    static constexpr int WVM = EXP ? OZ_EXP_WVM : WIDE ? 2 : 4, WVN = EXP ? OZ_EXP_WVN : WIDE ? 4 : 2;
+    static constexpr int WMF = EXP ? OZ_EXP_WMF : (WIDE || HUGE) ? 2 : 1, WNF = EXP ? OZ_EXP_WNF : HUGE ? 2 : 1;
     static constexpr int FA = WVM * WMF, FB = WVN * WNF;          // 32-row fragment rows of the tile
     // A slices [0, L0) are double-buffered with B; A slices [L0, S) single-buffered (L0 == S: no split)
     // (from a sweep at 8192^3: s = 7 runs 2820 / 2960 / 2905 / 2840 / 2795 TOP/s for L0 = 2 / 3 / 4 / 5 / 6, s = 8
     // 2985 / 3150 / 3120 for L0 = 2 / 3 / 4 -- and 3230 against 3110 with split-k --, s = 9 2925 / 3100 for L0 = 1 / 2)
-    static constexpr int L0 = S <= 6 ? S : S <= 8 ? 3 : 2;
+    static constexpr int L0 = EXP && OZ_EXP_L0 >= 0 ? OZ_EXP_L0 : S <= 6 ? S : S <= 8 ? 3 : 2;
     static constexpr int P1 = (FA * L0 + FB * S) * 2 * kFragBytes;    // double-buffered part of a 64-k stage
     static constexpr int P2 = FA * (S - L0) * 2 * kFragBytes;         // single-buffered part
-    static constexpr int LDS = 2 * P1 + P2;
+    // ring depth of the double-buffered part.  Few slices make a stage short (s = 2: 48 matrix instructions per
+    // wavefront): a copy issued one stage ahead would have to land within a few hundred cycles, less than the
+    // latency of the L2.  With a ring of three the copies of stage st + 2 are issued while stage st is multiplied
+    // and only those of stage st + 1 are waited for.
+    // Measured at 8192^3: s = 2 (tile 256 x 128) 2150 -> 2370 TOP/s, s = 3 (tile 128 x 128) 2500 -> 2640 against the
+    // 32x32x32 kernel with its ring of three; with a ring of two the same tiles gain nothing (matrix pipe busy half
+    // of the cycles).  From 4 slices on three stages of a 128 x 128 tile do not fit.
+    static constexpr int NSTG = EXP && OZ_EXP_NSTG >= 0 ? OZ_EXP_NSTG : S <= 3 ? 3 : 2;
+    static_assert(NSTG == 2 || (NSTG == 3 && L0 == S), "a ring of three only without the split stage");
+    static constexpr int LDS = NSTG * P1 + P2;
     static_assert(LDS <= kLdsBytes, "stages do not fit LDS");
     // operands are read D matrix instructions ahead of their first use (DO: the B slices that are not held in
     // registers, ahead of each use).  Measured at s = 7, 8192^3: 3250 / 3200 / 3310 / 3140 / 3240 / 3205 TOP/s for
     // D = 4 / 6 / 8 / 10 / 12 / 16 (reads one slice ahead, the earlier scheme: 3215); s = 4 is indifferent up to 24.
-    static constexpr int D = S == 4 ? 24 : 8, DO = 4;
+    static constexpr int D = EXP && OZ_EXP_D >= 0 ? OZ_EXP_D : S == 4 ? 24 : 8, DO = 4;
+    // slices of B held in registers for the whole stage (the others are read when needed)
+    static constexpr int HP = EXP && OZ_EXP_HP >= 0 ? OZ_EXP_HP : S >= 9 ? 7 : S;
 };
 
 template <int S, int MODE>
@@ -119,7 +155,7 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
     constexpr int U1A = FA * 2 * L0, U1 = U1A + FB * 2 * S, U2 = FA * 2 * (S - L0);
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds;
-    constexpr int Z = 2 * G::P1;                                     // offset of the single-buffered region
+    constexpr int Z = G::NSTG * G::P1;                                   // offset of the single-buffered region
 
     int tm, tn;
     if (!tile_of_block_xcd(blockIdx.x, tiles_m, tiles_n, MODE == kBlocked, tm, tn)) return;
@@ -127,8 +163,12 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wm = wave % WVM, wn = wave / WVM;
     const size_t row_bytes = (size_t)KB * (S * kFragBytes);
-    const int8_t *rowA = pA + (size_t)tm * FA * row_bytes;
-    const int8_t *rowB = pB + (size_t)tn * FB * row_bytes;
+    // fragment rows of the planes (padded to kPad entries): a tile taller or wider than the padding may reach
+    // beyond them at the edge; such rows are read from the last valid fragment row instead (their outputs lie
+    // beyond m resp. n and are never stored)
+    const int frA = (m + kPad - 1) / kPad * (kPad / kFrag), frB = (n + kPad - 1) / kPad * (kPad / kFrag);
+    auto rowA_of = [&](int c) { const int r = tm * FA + c; return pA + (size_t)(r < frA ? r : frA - 1) * row_bytes; };
+    auto rowB_of = [&](int c) { const int r = tn * FB + c; return pB + (size_t)(r < frB ? r : frB - 1) * row_bytes; };
 
     // accumulators: per diagonal a and 32x32 fragment (i, j) four 16x16 blocks (i2, j2)
     v4i acc[S][WMF][WNF][4];
@@ -156,18 +196,18 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
         const int u = wave + i * NW;
         if (u < U1A) {
             const int c = u / (2 * L0), l = (u / 2) % L0, kk = u % 2;
-            src1[i] = rowA + (size_t)c * row_bytes + (size_t)st0 * STG + (size_t)(kk * S + l) * kFragBytes;
+            src1[i] = rowA_of(c) + (size_t)st0 * STG + (size_t)(kk * S + l) * kFragBytes;
         } else {
             const int v = u - U1A;
             const int c = v / (2 * S), h = (v / 2) % S, kk = v % 2;
-            src1[i] = rowB + (size_t)c * row_bytes + (size_t)st0 * STG + (size_t)(kk * S + h) * kFragBytes;
+            src1[i] = rowB_of(c) + (size_t)st0 * STG + (size_t)(kk * S + h) * kFragBytes;
         }
     }
 #pragma unroll
     for (int i = 0; i < NU2; ++i) {
         const int u = wave + i * NW;
         const int c = u / (2 * NS2), l = L0 + (u / 2) % NS2, kk = u % 2;
-        src2[i] = rowA + (size_t)c * row_bytes + (size_t)st0 * STG + (size_t)(kk * S + l) * kFragBytes;
+        src2[i] = rowA_of(c) + (size_t)st0 * STG + (size_t)(kk * S + l) * kFragBytes;
     }
     // Unit I of the double-buffered part (issue1) / of the single-buffered part (issue2): `voff` carries the stage
     // (lane * 16 + (stage - first stage) * STG), `ldsbuf` the ring buffer and the wavefront.  Two instructions per
@@ -186,6 +226,7 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
         switch (i) {
 #define OZ_U(N_) case N_: if constexpr (N_ < NU1) issue1(std::integral_constant<int, N_>{}, voff, ldsbuf); break;
             OZ_U(0) OZ_U(1) OZ_U(2) OZ_U(3) OZ_U(4) OZ_U(5) OZ_U(6) OZ_U(7) OZ_U(8) OZ_U(9) OZ_U(10) OZ_U(11)
+            OZ_U(12) OZ_U(13) OZ_U(14) OZ_U(15) OZ_U(16) OZ_U(17) OZ_U(18) OZ_U(19) OZ_U(20) OZ_U(21) OZ_U(22) OZ_U(23)
 #undef OZ_U
         }
     };
@@ -193,19 +234,30 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
         switch (i) {
 #define OZ_U(N_) case N_: if constexpr (N_ < NU2) issue2(std::integral_constant<int, N_>{}, voff); break;
             OZ_U(0) OZ_U(1) OZ_U(2) OZ_U(3) OZ_U(4) OZ_U(5) OZ_U(6) OZ_U(7) OZ_U(8) OZ_U(9) OZ_U(10) OZ_U(11)
+            OZ_U(12) OZ_U(13) OZ_U(14) OZ_U(15) OZ_U(16) OZ_U(17) OZ_U(18) OZ_U(19) OZ_U(20) OZ_U(21) OZ_U(22) OZ_U(23)
 #undef OZ_U
         }
     };
-    static_assert(NU1 <= 12 && NU2 <= 12, "unit dispatch");
+    static_assert(NU1 <= 24 && NU2 <= 24, "unit dispatch");
 
+    constexpr int NSTG = G::NSTG;
+    // (ring of three: every wavefront issues the same number of copies per stage, so that "all but the copies of
+    // the last stage issued" is one compile-time count)
+    static_assert(NSTG == 2 || U1 % NW == 0, "ring of three: copies must divide evenly among the wavefronts");
     {
         const unsigned v0 = lane * 16;
 #pragma unroll
         for (int i = 0; i < NU1; ++i) issue1_n(i, v0, ldsw);
 #pragma unroll
         for (int i = 0; i < NU2; ++i) issue2_n(i, v0);
+        if constexpr (NSTG == 3) {
+            // second stage of the work-group (the first one again if there is no other: nobody reads it)
+            const unsigned v1 = v0 + (st0 + 1 < nst ? (unsigned)STG : 0u);
+#pragma unroll
+            for (int i = 0; i < NU1; ++i) issue1_n(i, v1, ldsw + G::P1);
+        }
+        if constexpr (NSTG == 3) wait_vmcnt<NU1>(); else wait_vmcnt<0>();
     }
-    wait_vmcnt<0>();
     __syncthreads();
 
     // this lane's part of a 16x64 operand: row lane%16 of the half, k-group g = lane/16
@@ -227,11 +279,12 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
     // barrier stands there, and the operands of the first instructions of the NEXT stage are read behind it.  The
     // copies of the next stage go one at a time behind single matrix instructions (double-buffered part from the
     // start of the stage, the single-buffered part from the mid-stage barrier on).
-    constexpr int HP = S >= 9 ? 7 : S;
+    constexpr int HP = G::HP;
     constexpr int NSLOT = S * (S - 1) / 2;                                  // products of the slices l > 0
     constexpr int NPRE = SPLIT ? (S - L0 - 1) * (S - L0) / 2 : NSLOT;        // ... of them before the mid-stage barrier
     constexpr int MPP = 4 * WMF * WNF;                                       // matrix instructions per product
     static_assert(NU1 <= NPRE * MPP && (!SPLIT || NU2 <= (NSLOT - NPRE) * MPP), "too few products to issue the copies behind");
+    static_assert(NSTG == 2 || NU1 <= MPP * NSLOT, "ring of three: the copies of a stage are issued before its end-of-stage barrier");
     using T = Sched16<S, MPP, HP, G::D, G::DO>;
     // (a B slice that is not held is first needed in slice S - 1 - HP or later: its read-ahead stays inside the stage)
     static_assert(HP == S || T::pidx(S - 1 - HP, HP) >= G::DO, "on-demand reads must not precede the stage");
@@ -266,10 +319,12 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
     for (int st = st0; st < nst; ++st) {
         // (in the last stage the copies and the reads ahead go on, of that stage again: nobody uses them, and
         // the loop stays free of branches)
-        const bool more = st + 1 < nst;
-        const unsigned vnext = lane * 16 + (unsigned)((more ? st + 1 : st) - st0) * (unsigned)STG;
-        const unsigned ldsnext = ldsw + (buf ^ 1) * G::P1;
-        const unsigned char *cur = lds + buf * G::P1, *nxt = lds + (buf ^ 1) * G::P1;
+        const int ahead = st + NSTG - 1 < nst ? st + NSTG - 1 : nst - 1;
+        const unsigned vnext = lane * 16 + (unsigned)(ahead - st0) * (unsigned)STG;
+        const int buf1 = buf + 1 == NSTG ? 0 : buf + 1;                       // holds stage st + 1
+        const int bufc = NSTG == 2 ? buf1 : (buf1 + 1 == NSTG ? 0 : buf1 + 1);   // receives stage st + NSTG - 1
+        const unsigned ldsnext = ldsw + bufc * G::P1;
+        const unsigned char *cur = lds + buf * G::P1, *nxt = lds + buf1 * G::P1;
         static_for<0, NM>([&](auto E) {
             constexpr int e = decltype(E)::value;
             constexpr int l = T::slice_of(e), h = T::h_of(e), inner = e % MPP;
@@ -296,8 +351,9 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
             }
             if constexpr (SPLIT && e == MB) __syncthreads();      // nobody reads the single-buffered region any more
             if constexpr (e == EB) {
-                // nothing of this stage is left to read, and the next one must have landed
-                wait_vmcnt<0>();
+                // nothing of this stage is left to read, and the next one must have landed (ring of three: the
+                // copies issued during this stage, of the stage after the next, may stay in flight)
+                if constexpr (NSTG == 3) wait_vmcnt<NU1>(); else wait_vmcnt<0>();
                 __syncthreads();
             }
             // reads for the first instructions of the next stage
@@ -340,7 +396,7 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
                     for (int j2 = 0; j2 < 2; ++j2) B_[h][j][j2] = Bn_[h][j][j2];
             }
         });
-        buf ^= 1;
+        buf = buf1;
     }
 
     // element of accumulator block (i2, j2), register r: m_local = 16*i2 + lane%16, n_local = 16*j2 + 4*(lane/16) + r
@@ -464,9 +520,8 @@ hipError_t launch16_s(int m, int n, int kp, const int8_t *pA, const int8_t *pB, 
 {
     using G = Cfg16<S>;
     constexpr int TM = 32 * G::FA, TN = 32 * G::FB, THREADS = 64 * G::WVM * G::WVN;
-    static_assert(kPad % TM == 0 && kPad % TN == 0, "tiles must divide the padding");
     auto kern = gemm_fused16_kernel<S, MODE>;
-    static unsigned long long configured = 0;
+    static std::atomic<unsigned long long> configured{0};
     if (hipError_t e = allow_dynamic_lds((const void *)kern, G::LDS, configured); e != hipSuccess) return e;
     const int tiles_m = (m + TM - 1) / TM, tiles_n = (n + TN - 1) / TN;
     const int KB = kp / kFrag;
@@ -498,7 +553,7 @@ hipError_t dispatch16(int s, int m, int n, int kp, const int8_t *pA, const int8_
     switch (s) {
 #define OZ_CASE(S_) \
     case S_: return launch16_s<S_, MODE>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, Q, st);
-        OZ_CASE(4) OZ_CASE(5) OZ_CASE(6) OZ_CASE(7) OZ_CASE(8) OZ_CASE(9)
+        OZ_CASE(2) OZ_CASE(3) OZ_CASE(4) OZ_CASE(5) OZ_CASE(6) OZ_CASE(7) OZ_CASE(8) OZ_CASE(9)
 #undef OZ_CASE
     }
     return hipErrorInvalidValue;
@@ -506,16 +561,21 @@ hipError_t dispatch16(int s, int m, int n, int kp, const int8_t *pA, const int8_
 
 }  // namespace
 
-// Slice counts for which this kernel is the faster one at 8192^3 (s = 4: +10 %, s = 5: +7.5 % with the wide
-// tile, s = 6 ... 9 with the pipelined schedule: +10 %, +17 %, +17 %, +17 % over the 32x32x32 kernel).  With split-k
-// (long contractions) the wide 32x32x32 tile stays ahead at s = 6; beyond 9 a 64-deep stage of a 128 x 64 tile
-// does not fit LDS; the 32x32x32 kernel wins at 2 and 3.  Only the preferred ones are instantiated.
-bool fused16_preferred(int s, bool split_k) { return s >= 4 && s <= 9 && !(s == 6 && split_k); }
+// Slice counts for which this kernel is the faster one at 8192^3 (s = 2: +10 % and s = 3: +6 % with the ring of
+// three stages, s = 4: +10 %, s = 5: +7.5 % with the wide tile, s = 6 ... 9 with the pipelined schedule: +10 %, +17 %,
+// +17 %, +17 % over the 32x32x32 kernel).  With split-k (long contractions) the 32x32x32 kernel keeps s = 2, 3 (not
+// measured there) and stays ahead at s = 6; beyond 9 a 64-deep stage of a 128 x 64 tile does not fit LDS.  Only the
+// preferred ones are instantiated.
+bool fused16_preferred(int s, bool split_k) { return s >= 2 && s <= 9 && !((s <= 3 || s == 6) && split_k); }
 
 void fused16_tile(int s, int &tm, int &tn)
 {
-    tm = 128;
+    tm = s == 2 ? 256 : 128;
     tn = s <= 5 ? 128 : 64;
+    if (s == OZ_EXP_S) {
+        tm = 32 * OZ_EXP_WVM * OZ_EXP_WMF;
+        tn = 32 * OZ_EXP_WVN * OZ_EXP_WNF;
+    }
 }
 
 hipError_t launch_gemm_fused16(int m, int n, int kp, int s, const int8_t *pA, const int8_t *pB, const int32_t *eA,

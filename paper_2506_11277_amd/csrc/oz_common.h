@@ -5,7 +5,10 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "../../include/ozimmu.h"
+#include "../../include/ozimmu_bench.h"
 
 namespace oz {
 
@@ -21,14 +24,14 @@ inline int round_up(int x, int q) { return (x + q - 1) / q * q; }
 
 // Lets a kernel use `bytes` of dynamic LDS (more than the 64 KiB default), once per device: `done` holds one
 // bit per device ordinal.  (Two first calls racing on a device both set the attribute: harmless.)
-inline hipError_t allow_dynamic_lds(const void *kernel, int bytes, unsigned long long &done)
+inline hipError_t allow_dynamic_lds(const void *kernel, int bytes, std::atomic<unsigned long long> &done)
 {
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
-    if (dev >= 0 && dev < 64 && (done >> dev & 1ULL)) return hipSuccess;
+    if (dev >= 0 && dev < 64 && (done.load(std::memory_order_acquire) >> dev & 1ULL)) return hipSuccess;
     e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-    if (e == hipSuccess && dev >= 0 && dev < 64) done |= 1ULL << dev;
+    if (e == hipSuccess && dev >= 0 && dev < 64) done.fetch_or(1ULL << dev, std::memory_order_release);
     return e;
 }
 

@@ -140,7 +140,11 @@ def check(workspace):
 
 
 def dgemm(A, B, s, C=None, workspace=None, check_finite=False):
-    """C = A @ B through s int8 slices.  A (m x k), B (k x n): column-major float64 CUDA tensors."""
+    """C = A @ B through s int8 slices.  A (m x k), B (k x n): column-major float64 CUDA tensors.
+
+    The call is asynchronous and does not look at the non-finite flag: if A or B hold a NaN or an Inf, C is
+    unspecified until check(workspace) has been called (it raises OzimmuError(NONFINITE)); check_finite=True
+    does that here, at the price of a synchronisation.  Pass your own workspace to be able to call check()."""
     lda = _colmajor_ld(A, "A")
     ldb = _colmajor_ld(B, "B")
     m, k = A.shape
@@ -180,7 +184,8 @@ def dgemm_static(A, B, s, C):
 
 
 def dgemm2(A, B, sA, sB, all_products=False, C=None, workspace=None, check_finite=False):
-    """C = A @ B with sA slices of A and sB slices of B."""
+    """C = A @ B with sA slices of A and sB slices of B.  As for dgemm, C is unspecified for non-finite input
+    until check(workspace) has passed (check_finite=True calls it)."""
     lda = _colmajor_ld(A, "A")
     ldb = _colmajor_ld(B, "B")
     m, k = A.shape
@@ -212,7 +217,8 @@ def max_level_diagonals(k, sA, sB):
 
 def dgemm3(A, B, sA, sB, all_products=False, splitting=SPLIT_TRUNCATE, level_diagonals=1, C=None, workspace=None,
            check_finite=False):
-    """dgemm2 with the slicing (truncation / round-to-nearest) and the level size of the accumulation chosen."""
+    """dgemm2 with the slicing (truncation / round-to-nearest) and the level size of the accumulation chosen.
+    As for dgemm, C is unspecified for non-finite input until check(workspace) has passed."""
     lda = _colmajor_ld(A, "A")
     ldb = _colmajor_ld(B, "B")
     m, k = A.shape

@@ -122,6 +122,19 @@ def diagonal_terms(A, B, s, t, full=False, sB=None, rounding=False):
     return out, eA, eB
 
 
+def pair_terms(A, B, s, t):
+    """Exact value of every single product's contribution alpha beta^T o 2^{-(l+h)t} A_(l) B^(h), l + h <= s + 1,
+    from truncation operators only (as diagonal_terms).  Returns ({(l, h): matrix of Fractions}, eA, eB)."""
+    m, k, n = len(A), len(B), len(B[0])
+    eA = block_exponents("A", A)
+    eB = block_exponents("B", B)
+    dA = {l: [[truncate(A[i][kk], eA[i], l, t) - truncate(A[i][kk], eA[i], l - 1, t) for kk in range(k)]
+              for i in range(m)] for l in range(1, s + 1)}
+    dB = {h: [[truncate(B[kk][j], eB[j], h, t) - truncate(B[kk][j], eB[j], h - 1, t) for j in range(n)]
+              for kk in range(k)] for h in range(1, s + 1)}
+    return {(l, h): matmul(dA[l], dB[h]) for l in range(1, s + 1) for h in range(1, s + 2 - l)}, eA, eB
+
+
 def accumulate_levels(terms, eA, eB, Q, i, j):
     """Entry (i, j) of C from the exact diagonal terms: the diagonals d = 2, 3, ... are taken Q at a
     time, each level summed exactly (asserted to be a binary64 number once the scales are taken

@@ -7,7 +7,8 @@ import re
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "ozimmu.h")
+HEADER = os.path.join(ROOT, "include", "ozimmu.h")              # the method's calls
+BENCH_HEADER = os.path.join(ROOT, "include", "ozimmu_bench.h")  # benchmark aids and test hooks
 
 
 @pytest.fixture(scope="module")
@@ -19,16 +20,27 @@ def handle():
     return ozimmu.lib()
 
 
-def declared_functions():
-    text = open(HEADER).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(ozimmu_\w+)\s*\(", text)))
+def declared_functions(headers=(HEADER, BENCH_HEADER)):
+    names = set()
+    for header in headers:
+        text = open(header).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(ozimmu_\w+)\s*\(", text))
+    return sorted(names)
 
 
 def test_header_declares_the_three_named_entry_points():
     names = declared_functions()
     for required in ("ozimmu_estimate_slices", "ozimmu_split", "ozimmu_dgemm"):
         assert required in names
+
+
+def test_the_method_header_holds_no_benchmark_aid_or_test_hook():
+    for name in declared_functions((HEADER,)):
+        assert not re.search(r"debug|profile|measure|calibration", name), name
+    assert "ozimmu_dgemm_static" in declared_functions((HEADER,))
+    aids = declared_functions((BENCH_HEADER,))
+    assert "ozimmu_profile_start" in aids and "ozimmu_debug_diagonals" in aids and "ozimmu_calibration_copy" in aids
 
 
 def test_library_exports_every_declared_symbol(handle):

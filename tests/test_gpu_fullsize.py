@@ -16,7 +16,9 @@ from paper_2506_11277_amd import ozimmu, workloads
 
 def sample_indices(n, seed, count=20):
     rng = np.random.default_rng(seed)
-    fixed = [0, 1, 31, 32, 33, 63, 64, 127, 128, 129, 255, 256, n // 2, n - 129, n - 128, n - 65, n - 33, n - 2, n - 1]
+    # first and last tiles, and both sides of the boundaries of the 4 x 2 grid of tile regions (n/4, n/2, 3n/4)
+    fixed = [0, 1, 31, 32, 33, 63, 64, 127, 128, 129, 255, 256, n // 4 - 1, n // 4, n // 2 - 1, n // 2, 3 * n // 4 - 1,
+             3 * n // 4, n - 129, n - 128, n - 65, n - 33, n - 2, n - 1]
     idx = sorted(set(i for i in fixed if 0 <= i < n) | set(rng.integers(0, n, size=count).tolist()))
     return np.array(idx, dtype=np.int64)
 
@@ -44,13 +46,40 @@ def check_sampled(dA, dB, s, tag):
     return C
 
 
+def check_block(dA, dB, C, s, r0, c0, size, tag):
+    """One contiguous size x size block of C (every entry of the tiles it covers) against the oracle."""
+    want = oracle.dgemm(dA[r0:r0 + size, :].cpu().numpy(), dB[:, c0:c0 + size].cpu().numpy(), s)
+    got = C[r0:r0 + size, c0:c0 + size].cpu().numpy()
+    assert np.array_equal(got, want), f"{tag}: block at ({r0}, {c0}) not bit-identical"
+
+
+def check_whole_matrix_against_other_tile_shape(dA, dB, C, s, tag):
+    """Every entry of C: the kernel with the 64 x 64 tile (another tile grid, another order of work-groups) must
+    give the same matrix bit for bit, nothing may be left unwritten, and the result must be a product of A and B."""
+    assert bool(torch.isfinite(C).all()), f"{tag}: non-finite entries"
+    ref = torch.matmul(dA, dB)
+    err = (torch.linalg.norm(C - ref) / torch.linalg.norm(ref)).item()
+    assert err <= max(2.0 ** (-7 * s + 12), 1e-13), f"{tag}: normwise distance to the binary64 product {err:.3e}"
+    del ref
+    try:
+        ozimmu.debug_small_tile_limit(1 << 40)
+        C2 = ozimmu.dgemm(dA, dB, s)
+    finally:
+        ozimmu.debug_small_tile_limit(256)
+    assert bool(torch.equal(C, C2)), f"{tag}: the two tile shapes differ"
+
+
 def test_full_size_pow2_scaled_8192():
     cfg = workloads.CONFIGS["pow2_scaled_8192"]
     A, B = cfg["gen"]()
     dA, dB = ozimmu.to_colmajor(A), ozimmu.to_colmajor(B)
-    for s in (2, 7, 9):
+    m, n = dA.shape[0], dB.shape[1]
+    for s in cfg["s"]:                       # 2 ... 9: every slice count of the benchmark's sweep
         print("pow2_scaled_8192 s =", s, flush=True)
-        check_sampled(dA, dB, s, f"pow2_scaled_8192 s={s}")
+        C = check_sampled(dA, dB, s, f"pow2_scaled_8192 s={s}")
+        # a tile-aligned 256 x 256 block across the corner where four tile regions meet
+        check_block(dA, dB, C, s, 3 * m // 4 - 128, n // 2 - 128, 256, f"pow2_scaled_8192 s={s}")
+        check_whole_matrix_against_other_tile_shape(dA, dB, C, s, f"pow2_scaled_8192 s={s}")
 
 
 def test_power_of_two_scaling_is_removed_exactly_at_full_size():

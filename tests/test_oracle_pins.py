@@ -251,6 +251,45 @@ def test_diagonal_order_rounds_once_per_diagonal_ascending(name, A, B, s):
             assert C[i, j] == math.ldexp(S, eA[i] + eB[j]), (i, j)
 
 
+@pytest.mark.parametrize("name,A,B", small_cases()[:4])
+@pytest.mark.parametrize("s", [7, 8, 9, 10])
+def test_algorithm_1_order_rounds_once_per_product_l_outer_h_inner(name, A, B, s):
+    # the literal loop nest of Algorithm 1 outside the exact regime: exact value of every single product
+    # (rational), one correctly rounded binary64 addition per product, l = 1, 2, ... outside, h = 1, 2, ... inside.
+    # The other nesting (h outside) and the diagonal order are different sequences of roundings: the test also
+    # checks that at least one of its cases tells them apart.
+    t = 7
+    Af, Bf = ex.frac_matrix(A), ex.frac_matrix(B)
+    terms, eA, eB = ex.pair_terms(Af, Bf, s, t)
+    C = oracle.dgemm(A, B, s, t, order=1)
+    swapped_differs = False
+    for i in range(A.shape[0]):
+        for j in range(B.shape[1]):
+            scale = Fraction(2) ** (eA[i] + eB[j])
+            S = 0.0
+            for l in range(1, s + 1):
+                for h in range(1, s + 2 - l):
+                    term = terms[(l, h)][i][j] / scale
+                    f = float(term)
+                    assert Fraction(f) == term          # an integer times 2^{-(l+h)t}: a binary64 number
+                    S = S + f
+            assert C[i, j] == math.ldexp(S, eA[i] + eB[j]), (i, j)
+            S2 = 0.0
+            for h in range(1, s + 1):
+                for l in range(1, s + 2 - h):
+                    S2 = S2 + float(terms[(l, h)][i][j] / scale)
+            swapped_differs = swapped_differs or S2 != S
+    _ORDER1_DISCRIMINATES[(name, s)] = swapped_differs
+
+
+_ORDER1_DISCRIMINATES = {}
+
+
+def test_algorithm_1_order_pin_tells_the_two_loop_nests_apart():
+    # runs after the parametrised cases above (same module, definition order)
+    assert _ORDER1_DISCRIMINATES and any(_ORDER1_DISCRIMINATES.values())
+
+
 @pytest.mark.parametrize("phi,s", [(0.5, 3), (0.5, 6), (0.5, 8), (2.0, 4), (2.0, 9), (4.0, 7), (4.0, 12)])
 def test_error_bound_of_reduced_product_variant(phi, s):
     # |C - C_hat'| <= (zeta + 2^{-st} s kA kB + gamma_psi (1 + zeta + 2^{-st} s kA kB)) |A||B|,
