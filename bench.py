@@ -25,6 +25,58 @@ INT8_PEAK_TOPS = 5000.0          # MI355X dense int8 MFMA, published
 HBM_PEAK_GBS = 8000.0
 
 
+class PowerSampler:
+    """Board power of GPU 0 from the driver's hwmon file (microwatts), read every few milliseconds by a thread
+    while a timed loop runs.  Context for the roofline fraction: the GEMM kernels run at the board's power cap,
+    which is what sets their clock.  Reports nothing where the file is not readable."""
+
+    def __init__(self):
+        import glob
+        hw = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input"))
+        cap = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_cap"))
+        self.path = hw[0] if hw else None
+        self.cap_w = None
+        try:
+            self.cap_w = int(open(cap[0]).read()) / 1e6 if cap else None
+        except (OSError, ValueError):
+            pass
+        self.samples = []
+        self._stop = False
+        self._thread = None
+
+    def _loop(self):
+        while not self._stop:
+            try:
+                self.samples.append((time.perf_counter(), int(open(self.path).read())))
+            except (OSError, ValueError):
+                pass
+            time.sleep(0.004)
+
+    def start(self):
+        import threading
+        self.samples = []
+        self._stop = False
+        if self.path:
+            self._thread = threading.Thread(target=self._loop, daemon=True)
+            self._thread.start()
+        self.t0 = time.perf_counter()
+
+    def stop(self):
+        t1 = time.perf_counter()
+        self._stop = True
+        if self._thread:
+            self._thread.join()
+            self._thread = None
+        # the reading is a moving average over some hundred milliseconds: only the second half of the interval is
+        # used, and nothing is reported for an interval too short for the average to settle
+        lo = self.t0 + 0.5 * (t1 - self.t0)
+        w = [p / 1e6 for (t, p) in self.samples if lo <= t <= t1 and p > 0]
+        if not w or t1 - self.t0 < 0.25:
+            return None
+        return {"avg_W": sum(w) / len(w), "max_W": max(w), "cap_W": self.cap_w, "samples": len(w),
+                "source": "hwmon power1_input sampled during the timed steps"}
+
+
 def error_measures(C, A, B, Cref):
     """Normwise measure eq. (err_higham) with alpha=1, beta=0, and max componentwise relative
     error eq. (fwd-err-def-mat), both against a binary64 reference product."""
@@ -74,6 +126,8 @@ def main():
     C = ozimmu.colmajor_empty(m, n)
     flops = 2.0 * m * n * k
 
+    power = PowerSampler()
+
     def run(s, steps, warmup):
         ws = ozimmu.alloc_workspace(m, n, k, s)
         for _ in range(warmup):
@@ -81,17 +135,19 @@ def main():
         ozimmu.check(ws)
         torch.cuda.synchronize()
         ozimmu.profile_start(steps)
+        power.start()
         t0 = time.perf_counter()
         for _ in range(steps):
             ozimmu.dgemm(dA, dB, s, C=C, workspace=ws)
         torch.cuda.synchronize()
         dt = (time.perf_counter() - t0) / steps
+        watts = power.stop()
         calls, phases = ozimmu.profile_stop()
         assert calls == steps
-        return dt, phases
+        return dt, phases, watts
 
     s = args.slices
-    dt, phases = run(s, args.steps, args.warmup)
+    dt, phases, watts = run(s, args.steps, args.warmup)
     pairs = s * (s + 1) // 2
     gemm_s = phases["gemm"] * 1e-3
     int8_tops = flops * pairs / gemm_s / 1e12
@@ -110,7 +166,7 @@ def main():
 
     def kernel_name(ss):
         # which GEMM kernel the library runs for equal slice counts (csrc/gemm.hip, launch_gemm_fused)
-        return ("gemm_fused16_kernel" if 4 <= ss <= 9 else "gemm_fused_kernel") if ss <= 20 else "gemm_banded_kernel"
+        return ("gemm_fused16_kernel" if 2 <= ss <= 9 else "gemm_fused_kernel") if ss <= 20 else "gemm_banded_kernel"
 
     out = {
         "metric": "effective FP64 TFLOP/s (2mnk/t) vs slices s; % of int8 MFMA peak",
@@ -137,6 +193,7 @@ def main():
             "ms": phases["gemm"],
         },
         "phases_ms": phases,
+        "board_power": watts,
         "hbm_kernels": {
             "scales_GBs": scales_bytes / (phases["scales"] * 1e-3) / 1e9 if phases["scales"] > 0 else None,
             "split_GBs": split_bytes / (phases["split"] * 1e-3) / 1e9 if phases["split"] > 0 else None,
@@ -213,7 +270,9 @@ def main():
         # the metric is a curve over the slice count: every s of the workload, each timed like the headline
         sweep = []
         for ss in cfg["s"]:
-            dts, ph = run(ss, max(5, args.steps // 2), 2)
+            # at least 0.4 s of steps per slice count, so that the board-power reading has settled
+            dts, _, _ = run(ss, 3, 2)
+            dts, ph, pw = run(ss, min(500, max(5, args.steps // 2, int(0.4 / dts) + 1)), 0)
             pp = ss * (ss + 1) // 2
             ozimmu.dgemm(dA, dB, ss, C=C)
             nw, cw = error_measures(C, dA, dB, Cref)
@@ -222,6 +281,7 @@ def main():
                           "kernel": kernel_name(ss), "gemm_ms": ph["gemm"], "scales_ms": ph["scales"],
                           "split_ms": ph["split"], "int8_tops": tops, "frac_int8_peak": tops / INT8_PEAK_TOPS,
                           "traffic": measured.get(f"{args.workload}:{ss}"),
+                          "board_power_W": pw["avg_W"] if pw else None,
                           "normwise_err": nw, "max_componentwise_err": cw})
         out["sweep"] = sweep
         tol = 2.0 ** -53
