@@ -57,10 +57,13 @@ const char *ozimmu_status_string(int status);
 
 /*
  * Bytes of device workspace ozimmu_dgemm / ozimmu_estimate_slices need for this problem:
- * scale exponents, per-row/column reductions, the int8 slice planes of A and B, and -- only when
- * min(sA, sB) * k > 133144, i.e. when a diagonal's int32 sum could overflow and k has to be cut into
- * blocks -- int64 totals of the diagonals (8 bytes per diagonal and entry of a column panel of C, panels of
- * about 1 GiB, for up to 20 slices; a fixed 128 MiB beyond).
+ * scale exponents, per-row/column reductions, the int8 slice planes of A and B, and int64 totals of the
+ * diagonals (8 bytes per diagonal and entry of a column panel of C, panels of about 1 GiB)
+ *   - for up to 20 slices only when min(sA, sB) * k > 133144, i.e. when a diagonal's int32 sum could overflow and
+ *     k has to be cut into blocks,
+ *   - for 21 ... 32 equal slice counts always: the products are formed group of slices by group of slices and meet
+ *     in the totals; the planes then hold a whole number of groups of 7, 8 or 9 slices (up to 2 zero slices
+ *     appended).
  * Returns 0 for invalid arguments.  Alignment required of the workspace pointer: 256 bytes.
  */
 size_t ozimmu_workspace_bytes(int m, int n, int k, int s);

@@ -257,7 +257,9 @@ static int dgemm_impl(int m, int n, int k, const double *A, int lda, const doubl
     prof_mark(prof, 2, st);
     const int cA = w.cA, cB = w.cB;
     const bool fused = fused_handles(cA, cB, all_products);
-    if (fused && fused_single_block(cA, cB, k)) {
+    if (blocks_handles(sA, sB, all_products)) {
+        OZ_TRY(launch_gemm_blocks(m, n, w.kp, sA, pA, pB, eA, eB, C, ldc, (long long *)(ws + w.off_totals), Q, st));
+    } else if (fused && fused_single_block(cA, cB, k)) {
         OZ_TRY(launch_gemm_fused(m, n, w.kp, cA, cB, all_products, pA, pB, eA, eB, C, ldc, nullptr, nullptr, Q, st));
     } else if (fused) {
         OZ_TRY(launch_gemm_fused(m, n, w.kp, cA, cB, all_products, pA, pB, eA, eB, C, ldc, nullptr,

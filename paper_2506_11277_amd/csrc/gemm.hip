@@ -56,6 +56,17 @@ constexpr int kThreads = 256;   // generic kernel: 4 wavefronts, 2 (m) x 2 (n)
 //          pair loop stays fully unrolled over the long operand; the short operand's loop is the outer one and
 //          simply ends after sm slices, so no product needs a test of its own.  LDS keeps the layout for S
 //          slices of both operands (the short one's upper slots stay unused).
+//          4: the product set of 0 on a WINDOW of S consecutive slices of planes that hold more slices per entry
+//          (SliceWindow below); 3 takes its S slices from such a window too.  Together they serve slice counts
+//          beyond the accumulator budget as blocks of the (l, h) grid (launch_gemm_blocks).
+
+// Where a launch finds its S slices in the planes and where its diagonals go in the split-k totals: the planes
+// hold strA / strB slices per entry and the launch multiplies slices offA + 1 ... offA + S of A and
+// offB + 1 ... offB + S of B (PSET >= 3 only); its diagonal a is diagonal a + a0 of the na_tot diagonals the totals
+// hold per entry.
+struct SliceWindow {
+    int strA, strB, offA, offB, a0, na_tot;
+};
 
 template <int S, int WVM, int WVN, int WMF, int WNF, int KB32, int NSTAGE, int MODE, int PSET>
 __global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t *__restrict__ pA,
@@ -67,7 +78,7 @@ __global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t
                                                                     int32_t *__restrict__ dump,
                                                                     long long *__restrict__ totals,
                                                                     int stages_per_block, int Q, int sm,
-                                                                    long long slot_stride)
+                                                                    long long slot_stride, SliceWindow win)
 {
     static_assert(PSET == 0 || (NSTAGE == 2 && MODE != kDump), "other product sets: ring of two, no dump");
     constexpr bool DUMP = MODE == kDump;
@@ -88,8 +99,9 @@ __global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wm = wave % WVM, wn = wave / WVM;
     const int sA = PSET == 1 ? sm : S, sB = PSET == 2 ? sm : S;                 // slices in the planes of A / B
-    const size_t row_bytesA = (size_t)KB * sA * kFragBytes;     // one fragment row of an operand, all k
-    const size_t row_bytesB = (size_t)KB * sB * kFragBytes;
+    const int plA = PSET >= 3 ? win.strA : sA, plB = PSET >= 3 ? win.strB : sB;  // slices per entry in the planes
+    const size_t row_bytesA = (size_t)KB * plA * kFragBytes;    // one fragment row of an operand, all k
+    const size_t row_bytesB = (size_t)KB * plB * kFragBytes;
     const int8_t *rowA = pA + (size_t)tm * FA * row_bytesA;
     const int8_t *rowB = pB + (size_t)tn * FB * row_bytesB;
     const bool extra = wave < UREM;
@@ -112,8 +124,9 @@ __global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t
                 const int kbl = o / S, sl = o % S;                          // LDS slot (k-block, slice)
                 const int cnt = c < FA ? sA : sB;
                 if (sl >= cnt) continue;                                    // the short operand has no such slice
+                const int pl = c < FA ? plA : plB, off = PSET >= 3 ? (c < FA ? win.offA : win.offB) : 0;
                 src = (c < FA ? rowA + (size_t)c * row_bytesA : rowB + (size_t)(c - FA) * row_bytesB) +
-                      ((size_t)(st * KB32 + kbl) * cnt + sl) * kFragBytes;
+                      ((size_t)(st * KB32 + kbl) * pl + off + sl) * kFragBytes;
             }
             lds_dma16(src, lane * 16, lds0 + buf * STAGE + u * kFragBytes);
         }
@@ -341,7 +354,7 @@ __global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t
 
     if (MODE == kBlocked) {
         // this k-block's diagonal sums -> int64 totals of the tile, [tile][wavefront][a][i][j][r][lane]
-        const size_t e0 = ((size_t)(tm * tiles_n + tn) * NW + wave) * (size_t)(NA * WMF * WNF * 16 * 64) + lane;
+        const size_t e0 = ((size_t)(tm * tiles_n + tn) * NW + wave) * (size_t)(win.na_tot * WMF * WNF * 16 * 64) + lane;
         if (slot_stride) {
             // two k-blocks: plain int32 stores into this block's slot
             int *slot = (int *)totals + (size_t)blockIdx.y * (size_t)slot_stride + e0;
@@ -359,7 +372,7 @@ __global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t
             }
             return;
         }
-        long long *tot = totals + e0;
+        long long *tot = totals + e0 + (size_t)win.a0 * (WMF * WNF * 16 * 64);
 #pragma unroll
         for (int a = 0; a < NA; ++a) {
             // (one diagonal at a time, its base address formed here: otherwise all 16 * S slot addresses are
@@ -451,6 +464,41 @@ __global__ __launch_bounds__(64 * WVM * WVN) void finish_blocked_kernel(const lo
 __global__ void zero_i64_kernel(long long *p, size_t n)
 {
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0;
+}
+
+// Binary64 accumulation after the block launches (launch_gemm_blocks): the totals hold na_tot diagonals per entry,
+// the first `diagonals` of them (l + h = 2 ... s + 1 of the requested slice count) are added in ascending order;
+// the rest belongs to products beyond the requested set (zero slices appended to reach a whole number of groups).
+// Same element mapping as the epilogue of gemm_fused_kernel.
+template <int WVM, int WVN, int WMF, int WNF>
+__global__ __launch_bounds__(64 * WVM * WVN) void finish_blocks_kernel(const long long *__restrict__ totals,
+                                                                       const int32_t *__restrict__ eA,
+                                                                       const int32_t *__restrict__ eB,
+                                                                       double *__restrict__ C, int ldc, int m, int n,
+                                                                       int tiles_n, int Q, int diagonals, int na_tot)
+{
+    constexpr int NW = WVM * WVN, FA = WVM * WMF, FB = WVN * WNF;
+    const int tm = blockIdx.x / tiles_n, tn = blockIdx.x % tiles_n;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave % WVM, wn = wave / WVM;
+    const long long *tot = totals + ((size_t)blockIdx.x * NW + wave) * (size_t)(na_tot * WMF * WNF * 16 * 64) + lane;
+    const int m0 = (tm * FA + wm * WMF) * 32, n0 = (tn * FB + wn * WNF) * 32;
+    for (int i = 0; i < WMF; ++i) {
+        const int mi = m0 + i * 32 + (lane & 31);
+        if (mi >= m) continue;
+        const int ea = eA[mi];
+        for (int j = 0; j < WNF; ++j)
+            for (int r = 0; r < 16; ++r) {
+                const int nj = n0 + j * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                if (nj >= n) continue;
+                LevelSum sum;
+                for (int a = 0; a < diagonals; ++a) {
+                    const long long v = tot[((((size_t)a * WMF + i) * WNF + j) * 16 + r) * 64];
+                    sum.add(ldexp((double)v, -kSliceBits * (a + 2)), Q, a == diagonals - 1);   // exact: |v| < 2^53
+                }
+                C[mi + (size_t)nj * ldc] = ldexp(sum.S, ea + eB[nj]);
+            }
+    }
 }
 
 // =============================== generic kernel =========================================
@@ -629,7 +677,8 @@ hipError_t launch_fused_s(int m, int n, int kp, const int8_t *pA, const int8_t *
     const int tiles_m = (m + TM - 1) / TM, tiles_n = (n + TN - 1) / TN;
     if (MODE != kBlocked) {
         kern<<<(unsigned)tile_order_blocks(tiles_m, tiles_n, false), 64 * Cfg::WVM * Cfg::WVN, NSTAGE * STAGE, st>>>(
-            pA, pB, eA, eB, C, ldc, m, n, kp / kFrag, tiles_m, tiles_n, dump, nullptr, 0, Q, sm, 0);
+            pA, pB, eA, eB, C, ldc, m, n, kp / kFrag, tiles_m, tiles_n, dump, nullptr, 0, Q, sm, 0,
+            SliceWindow{S, S, 0, 0, 0, NA});
         return hipGetLastError();
     }
     // longest k-block whose sm products per diagonal cannot overflow int32, in whole stages; the blocks are
@@ -645,7 +694,7 @@ hipError_t launch_fused_s(int m, int n, int kp, const int8_t *pA, const int8_t *
     dim3 grid((unsigned)tile_order_blocks(tiles_m, tiles_n, true), nblocks);
     kern<<<grid, 64 * Cfg::WVM * Cfg::WVN, NSTAGE * STAGE, st>>>(pA, pB, eA, eB, C, ldc, m, n, kp / kFrag, tiles_m,
                                                                   tiles_n, nullptr, totals, stages_per_block, Q, sm,
-                                                                  slot_stride);
+                                                                  slot_stride, SliceWindow{S, S, 0, 0, 0, NA});
     finish_blocked_kernel<NA, Cfg::WVM, Cfg::WVN, Cfg::WMF, Cfg::WNF>
         <<<tiles_m * tiles_n, 64 * Cfg::WVM * Cfg::WVN, 0, st>>>(totals, eA, eB, C, ldc, m, n, tiles_n, Q, slot_stride);
     return hipGetLastError();
@@ -708,9 +757,82 @@ hipError_t dispatch_fused_all(int s, int m, int n, int kp, const int8_t *pA, con
     return hipErrorInvalidValue;
 }
 
+// ---- slice counts beyond the accumulator budget, as blocks of the (l, h) grid -------------------------------
+// The s slices are taken in NG groups of G (zero slices appended by the slicing kernel when s is not a multiple of
+// G).  Block (I, J) -- slices I G + 1 ... (I + 1) G of A times slices J G + 1 ... (J + 1) G of B -- is one launch of
+// the fused kernel on a window of the planes: all G^2 products for I + J < NG - 1, the reduced set l' + h' <= G + 1
+// for I + J = NG - 1 (together exactly the pairs l + h <= G NG + 1), nothing beyond.  Its int32 diagonal sums are
+// added to the int64 totals of the tile, local diagonal a at diagonal a + G (I + J); the finishing kernel then
+// adds the first s diagonals in order.  (The totals of diagonals beyond s + 1 hold products outside the requested
+// set when zero slices were appended; they are not read.)  All blocks share the four-wavefront 64 x 64 tile, so
+// that the layout of the totals is the same for every launch.
+constexpr int kBlkWVM = 2, kBlkWVN = 2, kBlkTile = 64;
+
+template <int G, int PSET>
+hipError_t launch_block(int m, int n, int kp, const int8_t *pA, const int8_t *pB, long long *totals, int Q,
+                        SliceWindow win, hipStream_t st)
+{
+    constexpr int STAGE = 4 * G * kFragBytes;
+    auto kern = gemm_fused_kernel<G, kBlkWVM, kBlkWVN, 1, 1, 1, 2, kBlocked, PSET>;
+    static std::atomic<unsigned long long> configured{0};
+    if (hipError_t e = allow_dynamic_lds((const void *)kern, 2 * STAGE, configured); e != hipSuccess) return e;
+    const int tiles_m = (m + kBlkTile - 1) / kBlkTile, tiles_n = (n + kBlkTile - 1) / kBlkTile;
+    // k-blocks short enough for G products per diagonal in int32, equally long
+    const int max_stages = (int)(kMaxInt32K / G / kFrag);
+    const int nst = kp / kFrag;
+    const int nblocks = (nst + max_stages - 1) / max_stages;
+    const int stages_per_block = (nst + nblocks - 1) / nblocks;
+    dim3 grid((unsigned)tile_order_blocks(tiles_m, tiles_n, true), nblocks);
+    kern<<<grid, 64 * kBlkWVM * kBlkWVN, 2 * STAGE, st>>>(pA, pB, nullptr, nullptr, nullptr, 0, m, n, kp / kFrag, tiles_m,
+                                                          tiles_n, nullptr, totals, stages_per_block, Q, G, 0, win);
+    return hipGetLastError();
+}
+
+template <int G>
+hipError_t launch_blocks_g(int m, int n, int kp, int s, int NG, const int8_t *pA, const int8_t *pB, const int32_t *eA,
+                           const int32_t *eB, double *C, int ldc, long long *totals, int Q, hipStream_t st)
+{
+    const int SP = G * NG;                                  // slices per entry in the planes = diagonals in the totals
+    const int tiles_m = (m + kBlkTile - 1) / kBlkTile, tiles_n = (n + kBlkTile - 1) / kBlkTile;
+    zero_i64_kernel<<<2048, 256, 0, st>>>(totals, (size_t)tiles_m * tiles_n * SP * kBlkTile * kBlkTile);
+    for (int I = 0; I < NG; ++I)
+        for (int J = 0; I + J < NG; ++J) {
+            const SliceWindow win{SP, SP, I * G, J * G, G * (I + J), SP};
+            const hipError_t e = I + J < NG - 1 ? launch_block<G, 3>(m, n, kp, pA, pB, totals, Q, win, st)
+                                                : launch_block<G, 4>(m, n, kp, pA, pB, totals, Q, win, st);
+            if (e != hipSuccess) return e;
+        }
+    finish_blocks_kernel<kBlkWVM, kBlkWVN, 1, 1>
+        <<<tiles_m * tiles_n, 64 * kBlkWVM * kBlkWVN, 0, st>>>(totals, eA, eB, C, ldc, m, n, tiles_n, Q, s, SP);
+    return hipGetLastError();
+}
+
 }  // namespace
 
 int fused_max_slices() { return kFusedMaxS; }
+
+// Group size for equal slice counts beyond the fused kernels (21 ... 32): the G in {7, 8, 9} that appends the fewest
+// zero slices (all products of a group pair need 2 G - 1 <= 18 accumulator sets).
+int blocks_group(int s)
+{
+    int best = 8, pad = 1 << 30;
+    for (int g = 9; g >= 7; --g) {
+        const int p = (s + g - 1) / g * g - s;
+        if (p <= pad) { pad = p; best = g; }        // ties go to the smaller group (fewer accumulators per block)
+    }
+    return best;
+}
+
+bool blocks_handles(int sA, int sB, bool all_products)
+{
+    return !all_products && sA == sB && sA > kFusedMaxS && sA <= OZIMMU_MAX_SLICES;
+}
+
+int blocks_padded_slices(int s)
+{
+    const int g = blocks_group(s);
+    return (s + g - 1) / g * g;
+}
 
 void fused_set_small_tile_limit(long long tiles) { g_small_below_tiles = tiles; }
 
@@ -759,6 +881,39 @@ size_t fused_totals_bytes(int sA, int sB, bool all_products, int m, int n, int k
     }
     const size_t tiles = (size_t)((m + tm - 1) / tm) * ((n + tn - 1) / tn);
     return tiles * (size_t)s * tm * tn * sizeof(long long);
+}
+
+size_t blocks_totals_bytes(int s, int m, int n)
+{
+    if (m <= 0 || n <= 0) return 0;
+    const int sp = blocks_padded_slices(s);
+    const int w = fused_panel_cols(sp, m, n);
+    const size_t tiles = (size_t)((m + kBlkTile - 1) / kBlkTile) * (((w < n ? w : n) + kBlkTile - 1) / kBlkTile);
+    return tiles * (size_t)sp * kBlkTile * kBlkTile * sizeof(long long);
+}
+
+hipError_t launch_gemm_blocks(int m, int n, int kp, int s, const int8_t *pA, const int8_t *pB, const int32_t *eA,
+                              const int32_t *eB, double *C, int ldc, long long *totals, int Q, hipStream_t st)
+{
+    if (m <= 0 || n <= 0) return hipSuccess;
+    if (!blocks_handles(s, s, false) || !totals) return hipErrorInvalidValue;
+    const int G = blocks_group(s), SP = blocks_padded_slices(s), NG = SP / G;
+    // one column panel of C after the other through the same totals
+    const int w = fused_panel_cols(SP, m, n);
+    const size_t frag_row_bytes = (size_t)(kp / kFrag) * SP * kFragBytes;      // one 32-column fragment row of B
+    for (int c0 = 0; c0 < n; c0 += w) {
+        const int nc = n - c0 < w ? n - c0 : w;
+        const int8_t *pBc = pB + (size_t)(c0 / kFrag) * frag_row_bytes;
+        double *Cc = C + (size_t)c0 * ldc;
+        hipError_t e;
+        switch (G) {
+            case 7: e = launch_blocks_g<7>(m, nc, kp, s, NG, pA, pBc, eA, eB + c0, Cc, ldc, totals, Q, st); break;
+            case 8: e = launch_blocks_g<8>(m, nc, kp, s, NG, pA, pBc, eA, eB + c0, Cc, ldc, totals, Q, st); break;
+            default: e = launch_blocks_g<9>(m, nc, kp, s, NG, pA, pBc, eA, eB + c0, Cc, ldc, totals, Q, st); break;
+        }
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 static hipError_t launch_gemm_fused_once(int m, int n, int kp, int sA, int sB, bool all_products, const int8_t *pA,

@@ -39,6 +39,12 @@ bool fused_handles(int sA, int sB, bool all_products);
 size_t fused_totals_bytes(int sA, int sB, bool all_products, int m, int n, int k);
 size_t banded_totals_bytes(int sA, int sB, int k);
 int fused_max_slices();
+// equal slice counts beyond the fused kernels (21 ... 32), run as blocks of the (l, h) grid through the fused
+// kernels: true when that path takes the product set; slices per entry its planes hold (s rounded up to whole
+// groups, the surplus written as zeros); bytes of int64 totals it needs
+bool blocks_handles(int sA, int sB, bool all_products);
+int blocks_padded_slices(int s);
+size_t blocks_totals_bytes(int s, int m, int n);
 
 // Slice counts the GEMM runs with.  Different counts that differ little run as EQUAL counts, the short operand
 // getting zero slices appended by the slicing kernel: a product with a zero slice adds nothing, so every diagonal
@@ -52,6 +58,11 @@ inline void gemm_slice_counts(int sA, int sB, bool all_products, int &cA, int &c
 {
     cA = sA;
     cB = sB;
+    if (blocks_handles(sA, sB, all_products)) {
+        // blocks of the (l, h) grid: a whole number of slice groups, zero slices appended
+        cA = cB = blocks_padded_slices(sA);
+        return;
+    }
     if (sA == sB) return;
     const int S = sA > sB ? sA : sB, d = S - (sA < sB ? sA : sB);
     if (all_products) {
@@ -100,8 +111,9 @@ inline Workspace carve(int m, int n, int k, int sA, int sB, bool all_products = 
     gemm_slice_counts(sA, sB, all_products, w.cA, w.cB);
     w.off_planesA = take((size_t)w.cA * w.mp * w.kp);
     w.off_planesB = take((size_t)w.cB * w.np * w.kp);
-    w.off_totals = take(fused_handles(w.cA, w.cB, all_products) ? fused_totals_bytes(w.cA, w.cB, all_products, m, n, k)
-                                                                : banded_totals_bytes(w.cA, w.cB, k));
+    w.off_totals = take(blocks_handles(sA, sB, all_products)        ? blocks_totals_bytes(sA, m, n)
+                        : fused_handles(w.cA, w.cB, all_products)   ? fused_totals_bytes(w.cA, w.cB, all_products, m, n, k)
+                                                                    : banded_totals_bytes(w.cA, w.cB, k));
     w.total = off;
     return w;
 }
@@ -161,6 +173,9 @@ void fused16_tile(int s, int &tm, int &tn);
 hipError_t launch_gemm_fused16(int m, int n, int kp, int s, const int8_t *pA, const int8_t *pB,
                                const int32_t *eA, const int32_t *eB, double *C, int ldc,
                                int32_t *dump, long long *totals, int Q, hipStream_t st);
+// equal counts 21 ... 32 (planes with blocks_padded_slices(s) slices per entry); totals: blocks_totals_bytes()
+hipError_t launch_gemm_blocks(int m, int n, int kp, int s, const int8_t *pA, const int8_t *pB, const int32_t *eA,
+                              const int32_t *eB, double *C, int ldc, long long *totals, int Q, hipStream_t st);
 // general product band (any sA, sB, any k); totals: scratch of banded_totals_bytes() or null when that is 0
 hipError_t launch_gemm_banded(int m, int n, int kp, int sA, int sB, int dmax, const int8_t *pA, const int8_t *pB,
                               const int32_t *eA, const int32_t *eB, double *C, int ldc, long long *totals,

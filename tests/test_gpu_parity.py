@@ -198,7 +198,7 @@ def test_extreme_slices_do_not_overflow_int32_in_fused_kernel():
 
 @pytest.mark.parametrize("kind", ["uniform", "lognormal", "pow2", "special"])
 @pytest.mark.parametrize("m,n,k", SHAPES)
-@pytest.mark.parametrize("s", [1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16, 17, 18, 19, 20, 21, 32])
+@pytest.mark.parametrize("s", list(range(1, 33)))
 def test_dgemm_matches_oracle(kind, m, n, k, s, tile_choice):
     A, B = inputs(kind, m, n, k, 31)
     ws = ozimmu.alloc_workspace(m, n, k, s)
@@ -625,6 +625,26 @@ def test_transposed_problem_gives_the_transposed_result(sA, sB, allp, nearest, Q
     Ct = host(ozimmu.dgemm3(dev(B.T.copy()), dev(A.T.copy()), sB, sA, allp, sp, Q))
     assert np.array_equal(C, Ct.T)
     assert_c_matches(C, oracle.dgemm3(A, B, sA, sB, full=allp, nearest=nearest, Q=Q), "transposition")
+
+
+@pytest.mark.parametrize("s,k", [(21, 300), (24, 17000), (26, 16000), (28, 257), (32, 17000)])
+def test_blocks_of_slice_groups_over_column_panels_and_k_blocks(s, k):
+    # 21 ... 32 slices run as blocks of the (l, h) grid through shared int64 totals: column panels of 128 (totals
+    # budget of one byte: two or three panels, the last one ragged), k beyond 133144 / G (several k-blocks per
+    # block launch, G = 7, 8 or 9 slices per group), zero slices appended (26 -> 27)
+    m, n = (130, 300) if k < 1000 else (40, 200)
+    A, B = workloads.lognormal(m, n, k, 2.0, 60 + s)
+    want = oracle.dgemm(A, B, s)
+    got_whole = host(ozimmu.dgemm(dev(A), dev(B), s))
+    try:
+        ozimmu.debug_panel_bytes(1)
+        small_ws = ozimmu.workspace_bytes(m, n, k, s)
+        got = host(ozimmu.dgemm(dev(A), dev(B), s))
+    finally:
+        ozimmu.debug_panel_bytes(1 << 30)
+    assert small_ws < ozimmu.workspace_bytes(m, n, k, s)
+    assert_c_matches(got_whole, want, "blocks")
+    assert_c_matches(got, want, "blocks, column panels")
 
 
 @pytest.mark.parametrize("sA,sB,allp", [(7, 7, False), (4, 4, False), (16, 16, False), (5, 11, False), (6, 6, True)])
