@@ -144,6 +144,7 @@ def main():
         watts = power.stop()
         calls, phases = ozimmu.profile_stop()
         assert calls == steps
+        phases["kernel"] = ozimmu.last_gemm_kernel()       # written by the launcher that ran
         return dt, phases, watts
 
     s = args.slices
@@ -164,10 +165,6 @@ def main():
     if traffic is None:
         traffic = measured.get(f"{args.workload}:{s}")
 
-    def kernel_name(ss):
-        # which GEMM kernel the library runs for equal slice counts (csrc/gemm.hip, launch_gemm_fused)
-        return ("gemm_fused16_kernel" if 2 <= ss <= 9 else "gemm_fused_kernel") if ss <= 20 else "gemm_banded_kernel"
-
     out = {
         "metric": "effective FP64 TFLOP/s (2mnk/t) vs slices s; % of int8 MFMA peak",
         "value": flops / dt / 1e12,
@@ -183,7 +180,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": args.workload, "m": m, "n": n, "k": k, "slices": s, "slice_pairs": pairs},
         "roofline": {
-            "kernel": kernel_name(s),
+            "kernel": phases.pop("kernel"),
             "bound": "mfma",
             "achieved": int8_tops,
             "peak": INT8_PEAK_TOPS,
@@ -278,7 +275,7 @@ def main():
             nw, cw = error_measures(C, dA, dB, Cref)
             tops = flops * pp / (ph["gemm"] * 1e-3) / 1e12
             sweep.append({"s": ss, "ms_per_step": dts * 1e3, "tflops_effective": flops / dts / 1e12,
-                          "kernel": kernel_name(ss), "gemm_ms": ph["gemm"], "scales_ms": ph["scales"],
+                          "kernel": ph["kernel"], "gemm_ms": ph["gemm"], "scales_ms": ph["scales"],
                           "split_ms": ph["split"], "int8_tops": tops, "frac_int8_peak": tops / INT8_PEAK_TOPS,
                           "traffic": measured.get(f"{args.workload}:{ss}"),
                           "board_power_W": pw["avg_W"] if pw else None,

@@ -29,6 +29,14 @@ int ozimmu_profile_start(int max_calls);
 int ozimmu_profile_stop(int *calls, float *phase_ms);
 
 /*
+ * Name, slice count and tile of the GEMM kernel the calling thread's last ozimmu_dgemm* call launched (for a call
+ * made of several GEMM launches -- split-k panels, blocks of slice groups -- the path and its last launch), e.g.
+ * "gemm_fused16_kernel<7> tile 128x64".  Static thread-local storage, valid until the thread's next call; "" before
+ * the first one.  Written by the launchers themselves.
+ */
+const char *ozimmu_last_gemm_kernel(void);
+
+/*
  * Benchmark aid: the int8 rate (TOP/s, written to *tops [host]) that a register-only loop of
  * v_mfma_i32_32x32x32_i8 sustains on the current device for some tens of milliseconds, with
  * constant (random_operands = 0) or pseudo-random (1) operand registers.  `sink`: device pointer

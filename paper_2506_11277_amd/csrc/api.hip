@@ -1,11 +1,25 @@
 // extern "C" boundary of libozimmu: argument checks, workspace carve-up, kernel sequencing.
 #include <cmath>
+#include <cstdarg>
+#include <cstdio>
 #include <cstring>
 #include <mutex>
 
 #include "oz_common.h"
 
 using namespace oz;
+
+namespace oz {
+static thread_local char t_last_kernel[160] = "";
+void note_gemm_kernel(const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(t_last_kernel, sizeof(t_last_kernel), fmt, ap);
+    va_end(ap);
+}
+const char *last_gemm_kernel() { return t_last_kernel; }
+}  // namespace oz
 
 namespace {
 
@@ -399,6 +413,8 @@ int ozimmu_get_exponents(int m, int n, int k, int s, const void *workspace, int3
     if (eB && n) OZ_TRY(hipMemcpyAsync(eB, ws + w.off_expB, 4 * (size_t)n, hipMemcpyDeviceToDevice, st));
     return OZIMMU_OK;
 }
+
+const char *ozimmu_last_gemm_kernel(void) { return last_gemm_kernel(); }
 
 int ozimmu_debug_panel_bytes(long long bytes)
 {

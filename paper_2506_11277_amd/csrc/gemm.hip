@@ -675,6 +675,9 @@ hipError_t launch_fused_s(int m, int n, int kp, const int8_t *pA, const int8_t *
     static std::atomic<unsigned long long> configured{0};
     if (hipError_t e = allow_dynamic_lds((const void *)kern, NSTAGE * STAGE, configured); e != hipSuccess) return e;
     const int tiles_m = (m + TM - 1) / TM, tiles_n = (n + TN - 1) / TN;
+    note_gemm_kernel("gemm_fused_kernel<%d> %s tile %dx%d, %d wavefronts%s", S,
+                     PSET == 0 ? "equal counts" : PSET == 3 ? "all products" : "different counts", TM, TN,
+                     Cfg::WVM * Cfg::WVN, MODE == kBlocked ? ", split-k" : "");
     if (MODE != kBlocked) {
         kern<<<(unsigned)tile_order_blocks(tiles_m, tiles_n, false), 64 * Cfg::WVM * Cfg::WVN, NSTAGE * STAGE, st>>>(
             pA, pB, eA, eB, C, ldc, m, n, kp / kFrag, tiles_m, tiles_n, dump, nullptr, 0, Q, sm, 0,
@@ -898,6 +901,8 @@ hipError_t launch_gemm_blocks(int m, int n, int kp, int s, const int8_t *pA, con
     if (m <= 0 || n <= 0) return hipSuccess;
     if (!blocks_handles(s, s, false) || !totals) return hipErrorInvalidValue;
     const int G = blocks_group(s), SP = blocks_padded_slices(s), NG = SP / G;
+    note_gemm_kernel("blocks of slice groups: %d x %d groups of %d slices through gemm_fused_kernel<%d> tile %dx%d", NG,
+                     NG, G, G, kBlkTile, kBlkTile);
     // one column panel of C after the other through the same totals
     const int w = fused_panel_cols(SP, m, n);
     const size_t frag_row_bytes = (size_t)(kp / kFrag) * SP * kFragBytes;      // one 32-column fragment row of B
@@ -987,6 +992,7 @@ hipError_t launch_gemm_generic(int m, int n, int kp, int s, const int8_t *pA, co
 {
     if (m <= 0 || n <= 0) return hipSuccess;
     const int tiles_m = (m + 127) / 128, tiles_n = (n + 63) / 64;
+    note_gemm_kernel("gemm_generic_kernel tile 128x64");
     // int32-safe k-block for one pair: kblk * 127^2 < 2^31, rounded down to a whole number of stages
     const int kblk32 = (int)(kMaxInt32K / kFrag) / 4 * 4;
     gemm_generic_kernel<<<tiles_m * tiles_n, kThreads, 0, st>>>(pA, pB, eA, eB, C, ldc, m, n, s, kp / kFrag, tiles_m,

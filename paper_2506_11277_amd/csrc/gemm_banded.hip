@@ -283,6 +283,7 @@ hipError_t launch_gemm_banded(int m, int n, int kp, int sA, int sB, int dmax, co
 {
     if (Q < 1 || Q > kG) return hipErrorInvalidValue;
     if (m <= 0 || n <= 0) return hipSuccess;
+    note_gemm_kernel("gemm_banded_kernel (%d, %d) slices, tile 128x64", sA, sB);
     const bool chunk_a = sA <= sB;
     if (totals) {
         return chunk_a ? launch_band<true, true, 1>(m, n, kp, sA, sB, dmax, pA, pB, eA, eB, C, ldc, totals, Q, st)

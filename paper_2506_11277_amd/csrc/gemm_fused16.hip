@@ -525,6 +525,8 @@ hipError_t launch16_s(int m, int n, int kp, const int8_t *pA, const int8_t *pB, 
     if (hipError_t e = allow_dynamic_lds((const void *)kern, G::LDS, configured); e != hipSuccess) return e;
     const int tiles_m = (m + TM - 1) / TM, tiles_n = (n + TN - 1) / TN;
     const int KB = kp / kFrag;
+    note_gemm_kernel("gemm_fused16_kernel<%d> tile %dx%d%s%s", S, TM, TN, G::NSTG == 3 ? " ring of 3" : "",
+                     MODE == kBlocked ? " split-k" : "");
     if (MODE != kBlocked) {
         kern<<<(unsigned)tile_order_blocks(tiles_m, tiles_n, false), THREADS, G::LDS, st>>>(pA, pB, eA, eB, C, ldc, m, n, KB, tiles_m, tiles_n, dump,
                                                          nullptr, 0, Q, 0);

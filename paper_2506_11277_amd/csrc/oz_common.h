@@ -22,6 +22,11 @@ constexpr long long kMaxInt32K = 2147483647LL / (127LL * 127LL);   // 133144
 
 inline int round_up(int x, int q) { return (x + q - 1) / q * q; }
 
+// Name and shape of the GEMM kernel the calling thread launched last (reported by ozimmu_last_gemm_kernel for
+// benchmarks and profiles; written by the launchers themselves, so it cannot drift from the routing).
+void note_gemm_kernel(const char *fmt, ...);
+const char *last_gemm_kernel();
+
 // Lets a kernel use `bytes` of dynamic LDS (more than the 64 KiB default), once per device: `done` holds one
 // bit per device ordinal.  (Two first calls racing on a device both set the attribute: harmless.)
 inline hipError_t allow_dynamic_lds(const void *kernel, int bytes, std::atomic<unsigned long long> &done)

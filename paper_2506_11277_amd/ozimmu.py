@@ -49,6 +49,7 @@ _SIGNATURES = {
     "ozimmu_check": (_c.c_int, [_c.c_void_p, _c.c_void_p]),
     "ozimmu_get_exponents": (_c.c_int, [_c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_void_p, _c.c_void_p,
                                         _c.c_void_p, _c.c_void_p]),
+    "ozimmu_last_gemm_kernel": (_c.c_char_p, []),
     "ozimmu_profile_start": (_c.c_int, [_c.c_int]),
     "ozimmu_profile_stop": (_c.c_int, [_c.POINTER(_c.c_int), _c.POINTER(_c.c_float)]),
     "ozimmu_calibration_copy": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_size_t, _c.c_void_p]),
@@ -331,6 +332,11 @@ def profile_stop():
     if rc != OK:
         raise OzimmuError(rc, "profile_stop")
     return calls.value, {"scales": ms[0], "split": ms[1], "gemm": ms[2]}
+
+
+def last_gemm_kernel():
+    """Name and tile of the GEMM kernel this thread's last dgemm* call launched."""
+    return lib().ozimmu_last_gemm_kernel().decode()
 
 
 def calibration_copy(dst, src):
