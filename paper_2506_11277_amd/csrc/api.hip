@@ -270,14 +270,12 @@ static int dgemm_impl(int m, int n, int k, const double *A, int lda, const doubl
     OZ_TRY(launch_split_both(m, n, k, A, lda, B, ldb, sA, sB, w.cA, w.cB, eA, eB, pA, pB, nearest, st));
     prof_mark(prof, 2, st);
     const int cA = w.cA, cB = w.cB;
-    const bool fused = fused_handles(cA, cB, all_products);
-    if (blocks_handles(sA, sB, all_products)) {
-        OZ_TRY(launch_gemm_blocks(m, n, w.kp, sA, pA, pB, eA, eB, C, ldc, (long long *)(ws + w.off_totals), Q, st));
-    } else if (fused && fused_single_block(cA, cB, k)) {
-        OZ_TRY(launch_gemm_fused(m, n, w.kp, cA, cB, all_products, pA, pB, eA, eB, C, ldc, nullptr, nullptr, Q, st));
-    } else if (fused) {
-        OZ_TRY(launch_gemm_fused(m, n, w.kp, cA, cB, all_products, pA, pB, eA, eB, C, ldc, nullptr,
-                                 (long long *)(ws + w.off_totals), Q, st));
+    if (w.path == kPathBlocks) {
+        OZ_TRY(launch_gemm_blocks(m, n, w.kp, sA, sB, all_products, pA, pB, eA, eB, C, ldc,
+                                  (long long *)(ws + w.off_totals), Q, st));
+    } else if (w.path == kPathFused) {
+        long long *totals = fused_single_block(cA, cB, k) ? nullptr : (long long *)(ws + w.off_totals);
+        OZ_TRY(launch_gemm_fused(m, n, w.kp, cA, cB, all_products, pA, pB, eA, eB, C, ldc, nullptr, totals, Q, st));
     } else {
         const int dmax = all_products ? cA + cB : (cA > cB ? cA : cB) + 1;
         long long *totals = banded_totals_bytes(cA, cB, k) ? (long long *)(ws + w.off_totals) : nullptr;

@@ -761,14 +761,15 @@ hipError_t dispatch_fused_all(int s, int m, int n, int kp, const int8_t *pA, con
 }
 
 // ---- slice counts beyond the accumulator budget, as blocks of the (l, h) grid -------------------------------
-// The s slices are taken in NG groups of G (zero slices appended by the slicing kernel when s is not a multiple of
-// G).  Block (I, J) -- slices I G + 1 ... (I + 1) G of A times slices J G + 1 ... (J + 1) G of B -- is one launch of
-// the fused kernel on a window of the planes: all G^2 products for I + J < NG - 1, the reduced set l' + h' <= G + 1
-// for I + J = NG - 1 (together exactly the pairs l + h <= G NG + 1), nothing beyond.  Its int32 diagonal sums are
-// added to the int64 totals of the tile, local diagonal a at diagonal a + G (I + J); the finishing kernel then
-// adds the first s diagonals in order.  (The totals of diagonals beyond s + 1 hold products outside the requested
-// set when zero slices were appended; they are not read.)  All blocks share the four-wavefront 64 x 64 tile, so
-// that the layout of the totals is the same for every launch.
+// The slices of each operand are taken in groups of G (zero slices appended by the slicing kernel where a count is
+// not a multiple of G): NGA groups of A, NGB of B.  Block (I, J) -- slices I G + 1 ... (I + 1) G of A times slices
+// J G + 1 ... (J + 1) G of B -- is one launch of the fused kernel on a window of the planes.  Reduced product set
+// (l + h <= SP + 1 with SP = G max(NGA, NGB)): all G^2 products for I + J < NG - 1, the reduced set l' + h' <= G + 1
+// for I + J = NG - 1, nothing beyond (NG = max(NGA, NGB)); all products: every block whole.  The int32 diagonal sums
+// of a block are added to the int64 totals of the tile, local diagonal a at diagonal a + G (I + J); the finishing
+// kernel then adds the diagonals of the REQUESTED product set in order.  (Appended zero slices add nothing; the
+// diagonals beyond the requested ones, which hold products outside the requested set, are not read.)  All blocks
+// share the four-wavefront 64 x 64 tile, so that the layout of the totals is the same for every launch.
 constexpr int kBlkWVM = 2, kBlkWVN = 2, kBlkTile = 64;
 
 template <int G, int PSET>
@@ -791,51 +792,32 @@ hipError_t launch_block(int m, int n, int kp, const int8_t *pA, const int8_t *pB
     return hipGetLastError();
 }
 
+// one column panel of C: `diagonals` = those of the requested product set, na_tot = those the totals hold
 template <int G>
-hipError_t launch_blocks_g(int m, int n, int kp, int s, int NG, const int8_t *pA, const int8_t *pB, const int32_t *eA,
-                           const int32_t *eB, double *C, int ldc, long long *totals, int Q, hipStream_t st)
+hipError_t launch_blocks_g(int m, int n, int kp, const BlocksPlan &plan, bool all_products, int diagonals, int na_tot,
+                           const int8_t *pA, const int8_t *pB, const int32_t *eA, const int32_t *eB, double *C, int ldc,
+                           long long *totals, int Q, hipStream_t st)
 {
-    const int SP = G * NG;                                  // slices per entry in the planes = diagonals in the totals
+    const int NGA = plan.spA / G, NGB = plan.spB / G, NG = NGA > NGB ? NGA : NGB;
     const int tiles_m = (m + kBlkTile - 1) / kBlkTile, tiles_n = (n + kBlkTile - 1) / kBlkTile;
-    zero_i64_kernel<<<2048, 256, 0, st>>>(totals, (size_t)tiles_m * tiles_n * SP * kBlkTile * kBlkTile);
-    for (int I = 0; I < NG; ++I)
-        for (int J = 0; I + J < NG; ++J) {
-            const SliceWindow win{SP, SP, I * G, J * G, G * (I + J), SP};
-            const hipError_t e = I + J < NG - 1 ? launch_block<G, 3>(m, n, kp, pA, pB, totals, Q, win, st)
-                                                : launch_block<G, 4>(m, n, kp, pA, pB, totals, Q, win, st);
+    zero_i64_kernel<<<2048, 256, 0, st>>>(totals, (size_t)tiles_m * tiles_n * na_tot * kBlkTile * kBlkTile);
+    for (int I = 0; I < NGA; ++I)
+        for (int J = 0; J < NGB; ++J) {
+            if (!all_products && I + J > NG - 1) continue;
+            const SliceWindow win{plan.spA, plan.spB, I * G, J * G, G * (I + J), na_tot};
+            const bool whole = all_products || I + J < NG - 1;
+            const hipError_t e = whole ? launch_block<G, 3>(m, n, kp, pA, pB, totals, Q, win, st)
+                                       : launch_block<G, 4>(m, n, kp, pA, pB, totals, Q, win, st);
             if (e != hipSuccess) return e;
         }
     finish_blocks_kernel<kBlkWVM, kBlkWVN, 1, 1>
-        <<<tiles_m * tiles_n, 64 * kBlkWVM * kBlkWVN, 0, st>>>(totals, eA, eB, C, ldc, m, n, tiles_n, Q, s, SP);
+        <<<tiles_m * tiles_n, 64 * kBlkWVM * kBlkWVN, 0, st>>>(totals, eA, eB, C, ldc, m, n, tiles_n, Q, diagonals, na_tot);
     return hipGetLastError();
 }
 
 }  // namespace
 
 int fused_max_slices() { return kFusedMaxS; }
-
-// Group size for equal slice counts beyond the fused kernels (21 ... 32): the G in {7, 8, 9} that appends the fewest
-// zero slices (all products of a group pair need 2 G - 1 <= 18 accumulator sets).
-int blocks_group(int s)
-{
-    int best = 8, pad = 1 << 30;
-    for (int g = 9; g >= 7; --g) {
-        const int p = (s + g - 1) / g * g - s;
-        if (p <= pad) { pad = p; best = g; }        // ties go to the smaller group (fewer accumulators per block)
-    }
-    return best;
-}
-
-bool blocks_handles(int sA, int sB, bool all_products)
-{
-    return !all_products && sA == sB && sA > kFusedMaxS && sA <= OZIMMU_MAX_SLICES;
-}
-
-int blocks_padded_slices(int s)
-{
-    const int g = blocks_group(s);
-    return (s + g - 1) / g * g;
-}
 
 void fused_set_small_tile_limit(long long tiles) { g_small_below_tiles = tiles; }
 
@@ -851,6 +833,36 @@ bool fused_single_block(int sA, int sB, int k)
     // the longest diagonal has min(sA, sB) products of k terms each, every term at most 127^2 in magnitude
     const int sm = sA < sB ? sA : sB;
     return fused_handles(sA, sB, false) && (long long)sm * (long long)(k > 0 ? k : 1) <= kMaxInt32K;
+}
+
+// Whether a product set runs as blocks of slice groups, and how: every set the fused kernels do not take (after
+// gemm_slice_counts has tried equal counts), unless the zero slices that fill the last groups would cost more
+// than 60 % extra products (then the band kernel, at about two thirds of the rate, is the cheaper one -- small
+// different counts with all products).  G in {7, 8, 9} (all products of a block need 2 G - 1 <= 18 accumulator sets)
+// is the one with the fewest products to compute.
+bool blocks_plan(int sA, int sB, bool all_products, BlocksPlan *plan)
+{
+    if (sA < 1 || sB < 1 || sA > OZIMMU_MAX_SLICES || sB > OZIMMU_MAX_SLICES) return false;
+    const int sM = sA > sB ? sA : sB, sm = sA > sB ? sB : sA;
+    const long long needed = all_products ? (long long)sA * sB : (long long)sm * (2 * sM - sm + 1) / 2;
+    long long best = -1;
+    BlocksPlan bp{0, 0, 0};
+    for (int G = 9; G >= 7; --G) {
+        const int NGA = (sA + G - 1) / G, NGB = (sB + G - 1) / G, NG = NGA > NGB ? NGA : NGB;
+        long long cost = 0;
+        for (int I = 0; I < NGA; ++I)
+            for (int J = 0; J < NGB; ++J) {
+                if (all_products || I + J < NG - 1) cost += G * G;
+                else if (I + J == NG - 1) cost += G * (G + 1) / 2;
+            }
+        if (best < 0 || cost <= best) {         // ties go to the smaller group (fewer accumulators per block)
+            best = cost;
+            bp = BlocksPlan{G, NGA * G, NGB * G};
+        }
+    }
+    if (5 * best > 8 * needed) return false;
+    if (plan) *plan = bp;
+    return true;
 }
 
 // Split-k runs over column panels of C, one after the other, so that the totals of a panel (8 bytes per diagonal
@@ -886,35 +898,48 @@ size_t fused_totals_bytes(int sA, int sB, bool all_products, int m, int n, int k
     return tiles * (size_t)s * tm * tn * sizeof(long long);
 }
 
-size_t blocks_totals_bytes(int s, int m, int n)
+static int blocks_total_diagonals(const BlocksPlan &p, bool all_products)
 {
-    if (m <= 0 || n <= 0) return 0;
-    const int sp = blocks_padded_slices(s);
-    const int w = fused_panel_cols(sp, m, n);
-    const size_t tiles = (size_t)((m + kBlkTile - 1) / kBlkTile) * (((w < n ? w : n) + kBlkTile - 1) / kBlkTile);
-    return tiles * (size_t)sp * kBlkTile * kBlkTile * sizeof(long long);
+    return all_products ? p.spA + p.spB - 1 : (p.spA > p.spB ? p.spA : p.spB);
 }
 
-hipError_t launch_gemm_blocks(int m, int n, int kp, int s, const int8_t *pA, const int8_t *pB, const int32_t *eA,
-                              const int32_t *eB, double *C, int ldc, long long *totals, int Q, hipStream_t st)
+size_t blocks_totals_bytes(int sA, int sB, bool all_products, int m, int n)
+{
+    BlocksPlan p;
+    if (m <= 0 || n <= 0 || !blocks_plan(sA, sB, all_products, &p)) return 0;
+    const int na_tot = blocks_total_diagonals(p, all_products);
+    const int w = fused_panel_cols(na_tot, m, n);
+    const size_t tiles = (size_t)((m + kBlkTile - 1) / kBlkTile) * (((w < n ? w : n) + kBlkTile - 1) / kBlkTile);
+    return tiles * (size_t)na_tot * kBlkTile * kBlkTile * sizeof(long long);
+}
+
+hipError_t launch_gemm_blocks(int m, int n, int kp, int sA, int sB, bool all_products, const int8_t *pA,
+                              const int8_t *pB, const int32_t *eA, const int32_t *eB, double *C, int ldc,
+                              long long *totals, int Q, hipStream_t st)
 {
     if (m <= 0 || n <= 0) return hipSuccess;
-    if (!blocks_handles(s, s, false) || !totals) return hipErrorInvalidValue;
-    const int G = blocks_group(s), SP = blocks_padded_slices(s), NG = SP / G;
-    note_gemm_kernel("blocks of slice groups: %d x %d groups of %d slices through gemm_fused_kernel<%d> tile %dx%d", NG,
-                     NG, G, G, kBlkTile, kBlkTile);
+    BlocksPlan p;
+    if (!blocks_plan(sA, sB, all_products, &p) || !totals) return hipErrorInvalidValue;
+    const int na_tot = blocks_total_diagonals(p, all_products);
+    const int diagonals = all_products ? sA + sB - 1 : (sA > sB ? sA : sB);
+    note_gemm_kernel("blocks of slice groups: %d x %d groups of %d slices through gemm_fused_kernel<%d> tile %dx%d",
+                     p.spA / p.G, p.spB / p.G, p.G, p.G, kBlkTile, kBlkTile);
     // one column panel of C after the other through the same totals
-    const int w = fused_panel_cols(SP, m, n);
-    const size_t frag_row_bytes = (size_t)(kp / kFrag) * SP * kFragBytes;      // one 32-column fragment row of B
+    const int w = fused_panel_cols(na_tot, m, n);
+    const size_t frag_row_bytes = (size_t)(kp / kFrag) * p.spB * kFragBytes;      // one 32-column fragment row of B
     for (int c0 = 0; c0 < n; c0 += w) {
         const int nc = n - c0 < w ? n - c0 : w;
         const int8_t *pBc = pB + (size_t)(c0 / kFrag) * frag_row_bytes;
         double *Cc = C + (size_t)c0 * ldc;
         hipError_t e;
-        switch (G) {
-            case 7: e = launch_blocks_g<7>(m, nc, kp, s, NG, pA, pBc, eA, eB + c0, Cc, ldc, totals, Q, st); break;
-            case 8: e = launch_blocks_g<8>(m, nc, kp, s, NG, pA, pBc, eA, eB + c0, Cc, ldc, totals, Q, st); break;
-            default: e = launch_blocks_g<9>(m, nc, kp, s, NG, pA, pBc, eA, eB + c0, Cc, ldc, totals, Q, st); break;
+        switch (p.G) {
+#define OZ_CASE(G_) \
+    case G_: \
+        e = launch_blocks_g<G_>(m, nc, kp, p, all_products, diagonals, na_tot, pA, pBc, eA, eB + c0, Cc, ldc, totals, Q, st); \
+        break;
+            OZ_CASE(7) OZ_CASE(8) OZ_CASE(9)
+#undef OZ_CASE
+            default: e = hipErrorInvalidValue;
         }
         if (e != hipSuccess) return e;
     }

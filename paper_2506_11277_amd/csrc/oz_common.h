@@ -44,12 +44,15 @@ bool fused_handles(int sA, int sB, bool all_products);
 size_t fused_totals_bytes(int sA, int sB, bool all_products, int m, int n, int k);
 size_t banded_totals_bytes(int sA, int sB, int k);
 int fused_max_slices();
-// equal slice counts beyond the fused kernels (21 ... 32), run as blocks of the (l, h) grid through the fused
-// kernels: true when that path takes the product set; slices per entry its planes hold (s rounded up to whole
-// groups, the surplus written as zeros); bytes of int64 totals it needs
-bool blocks_handles(int sA, int sB, bool all_products);
-int blocks_padded_slices(int s);
-size_t blocks_totals_bytes(int s, int m, int n);
+// Product sets beyond the fused kernels, run as blocks of the (l, h) grid through the fused kernels: group size and
+// slices per entry the planes of A and B hold (the counts rounded up to whole groups, the surplus written as
+// zeros).  blocks_plan() is false where the band kernel is the cheaper choice; call it only for product sets
+// the fused kernels do not take.  blocks_totals_bytes(): bytes of int64 totals the path needs.
+struct BlocksPlan {
+    int G, spA, spB;
+};
+bool blocks_plan(int sA, int sB, bool all_products, BlocksPlan *plan);
+size_t blocks_totals_bytes(int sA, int sB, bool all_products, int m, int n);
 
 // Slice counts the GEMM runs with.  Different counts that differ little run as EQUAL counts, the short operand
 // getting zero slices appended by the slicing kernel: a product with a zero slice adds nothing, so every diagonal
@@ -63,11 +66,6 @@ inline void gemm_slice_counts(int sA, int sB, bool all_products, int &cA, int &c
 {
     cA = sA;
     cB = sB;
-    if (blocks_handles(sA, sB, all_products)) {
-        // blocks of the (l, h) grid: a whole number of slice groups, zero slices appended
-        cA = cB = blocks_padded_slices(sA);
-        return;
-    }
     if (sA == sB) return;
     const int S = sA > sB ? sA : sB, d = S - (sA < sB ? sA : sB);
     if (all_products) {
@@ -85,10 +83,29 @@ inline void gemm_slice_counts(int sA, int sB, bool all_products, int &cA, int &c
     if (pad) cA = cB = S;
 }
 
+// Which GEMM path takes a product set, and with how many slices per entry in the planes: the fused kernels (cA, cB
+// from gemm_slice_counts), else blocks of slice groups (whole groups), else the band kernel (the counts as they are).
+enum GemmPath { kPathFused, kPathBlocks, kPathBand };
+inline GemmPath gemm_path(int sA, int sB, bool all_products, int &cA, int &cB)
+{
+    gemm_slice_counts(sA, sB, all_products, cA, cB);
+    if (fused_handles(cA, cB, all_products)) return kPathFused;
+    BlocksPlan p;
+    if (blocks_plan(sA, sB, all_products, &p)) {
+        cA = p.spA;
+        cB = p.spB;
+        return kPathBlocks;
+    }
+    cA = sA;
+    cB = sB;
+    return kPathBand;
+}
+
 // Workspace carve-up (all offsets multiples of 256 bytes).
 struct Workspace {
     int mp, np, kp;                 // padded extents
-    int cA, cB;                     // slice counts of the planes and of the GEMM (gemm_slice_counts)
+    int cA, cB;                     // slices per entry in the planes (gemm_path)
+    int path;                       // GemmPath
     size_t off_header;              // 256 B: [0] u32 non-finite flag, [8] u64 kappa_A bits, [16] u64 kappa_B bits
     size_t off_maxA, off_minA;      // u64[mp]: integer view of max |a_ij| / min nonzero |a_ij| per row
     size_t off_maxB, off_minB;      // u64[np]
@@ -113,12 +130,12 @@ inline Workspace carve(int m, int n, int k, int sA, int sB, bool all_products = 
     w.off_minB = take(8 * (size_t)w.np);
     w.off_expA = take(4 * (size_t)w.mp);
     w.off_expB = take(4 * (size_t)w.np);
-    gemm_slice_counts(sA, sB, all_products, w.cA, w.cB);
+    w.path = gemm_path(sA, sB, all_products, w.cA, w.cB);
     w.off_planesA = take((size_t)w.cA * w.mp * w.kp);
     w.off_planesB = take((size_t)w.cB * w.np * w.kp);
-    w.off_totals = take(blocks_handles(sA, sB, all_products)        ? blocks_totals_bytes(sA, m, n)
-                        : fused_handles(w.cA, w.cB, all_products)   ? fused_totals_bytes(w.cA, w.cB, all_products, m, n, k)
-                                                                    : banded_totals_bytes(w.cA, w.cB, k));
+    w.off_totals = take(w.path == kPathBlocks  ? blocks_totals_bytes(sA, sB, all_products, m, n)
+                        : w.path == kPathFused ? fused_totals_bytes(w.cA, w.cB, all_products, m, n, k)
+                                               : banded_totals_bytes(w.cA, w.cB, k));
     w.total = off;
     return w;
 }
@@ -178,9 +195,10 @@ void fused16_tile(int s, int &tm, int &tn);
 hipError_t launch_gemm_fused16(int m, int n, int kp, int s, const int8_t *pA, const int8_t *pB,
                                const int32_t *eA, const int32_t *eB, double *C, int ldc,
                                int32_t *dump, long long *totals, int Q, hipStream_t st);
-// equal counts 21 ... 32 (planes with blocks_padded_slices(s) slices per entry); totals: blocks_totals_bytes()
-hipError_t launch_gemm_blocks(int m, int n, int kp, int s, const int8_t *pA, const int8_t *pB, const int32_t *eA,
-                              const int32_t *eB, double *C, int ldc, long long *totals, int Q, hipStream_t st);
+// product sets beyond the fused kernels (planes with the slices per entry of blocks_plan); totals: blocks_totals_bytes()
+hipError_t launch_gemm_blocks(int m, int n, int kp, int sA, int sB, bool all_products, const int8_t *pA,
+                              const int8_t *pB, const int32_t *eA, const int32_t *eB, double *C, int ldc,
+                              long long *totals, int Q, hipStream_t st);
 // general product band (any sA, sB, any k); totals: scratch of banded_totals_bytes() or null when that is 0
 hipError_t launch_gemm_banded(int m, int n, int kp, int sA, int sB, int dmax, const int8_t *pA, const int8_t *pB,
                               const int32_t *eA, const int32_t *eB, double *C, int ldc, long long *totals,

@@ -103,7 +103,11 @@ def test_workspace_accounts_for_nearly_equal_slice_counts_run_as_equal(handle):
     assert w(12, 12) - w(9, 12) == 3 * 256 * 256
     assert w(5, 4, 1) == w(5, 5, 1)                     # all products of nearly equal counts
     assert w(5, 2, 1) < w(5, 5, 1)
-    assert w(25, 31) < w(31, 31)                        # beyond the fused kernels nothing is padded
+    # beyond the fused kernels the products are formed group of slices by group of slices: the planes hold whole
+    # groups (here of 8 and of 7 slices), the same for every count that rounds up to them
+    assert w(25, 31) == w(31, 31) == w(32, 32)
+    assert w(21, 21) - w(20, 20) >= 2 * 256 * 256       # one more slice per operand, plus the totals of the blocks
+    assert w(20, 7) == w(21, 7)                         # (20, 7): three groups of 7 times one group of 7
 
 
 def test_level_size_limit_and_variant_argument_validation_without_gpu(handle):

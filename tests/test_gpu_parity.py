@@ -627,6 +627,29 @@ def test_transposed_problem_gives_the_transposed_result(sA, sB, allp, nearest, Q
     assert_c_matches(C, oracle.dgemm3(A, B, sA, sB, full=allp, nearest=nearest, Q=Q), "transposition")
 
 
+def test_which_kernel_takes_which_product_set():
+    # the launchers report what they ran; one case per path of the routing
+    A, B = workloads.uniform(70, 60, 50, 5)
+    dA, dB = dev(A), dev(B)
+    expect = [((2, 2, False), "gemm_fused16_kernel<2> tile 256x128 ring of 3"),
+              ((7, 7, False), "gemm_fused16_kernel<7> tile 128x64"),
+              ((12, 12, False), "gemm_fused_kernel<12> equal counts tile 128x64, 8 wavefronts"),
+              ((16, 16, False), "gemm_fused_kernel<16> equal counts tile 64x64, 4 wavefronts"),
+              ((7, 8, False), "gemm_fused16_kernel<8> tile 128x64"),                 # run as (8, 8), zero slice appended
+              ((4, 12, False), "gemm_fused_kernel<12> different counts tile 128x64, 8 wavefronts"),
+              ((6, 6, True), "gemm_fused_kernel<6> all products tile 128x64, 8 wavefronts"),
+              ((24, 24, False), "blocks of slice groups: 3 x 3 groups of 8 slices"),
+              ((26, 26, False), "blocks of slice groups: 3 x 3 groups of 9 slices"),
+              ((25, 31, False), "blocks of slice groups: 4 x 4 groups of 8 slices"),
+              ((20, 7, False), "blocks of slice groups: 3 x 1 groups of 7 slices"),
+              ((13, 13, True), "blocks of slice groups: 2 x 2 groups of 7 slices"),
+              ((12, 5, True), "gemm_banded_kernel (12, 5) slices")]
+    for (sA, sB, allp), name in expect:
+        C = ozimmu.dgemm2(dA, dB, sA, sB, allp)
+        assert ozimmu.last_gemm_kernel().startswith(name), (sA, sB, allp, ozimmu.last_gemm_kernel())
+        assert_c_matches(host(C), oracle.dgemm3(A, B, sA, sB, full=allp), f"routing ({sA},{sB},{allp})")
+
+
 @pytest.mark.parametrize("s,k", [(21, 300), (24, 17000), (26, 16000), (28, 257), (32, 17000)])
 def test_blocks_of_slice_groups_over_column_panels_and_k_blocks(s, k):
     # 21 ... 32 slices run as blocks of the (l, h) grid through shared int64 totals: column panels of 128 (totals
