@@ -61,8 +61,9 @@ const char *ozimmu_status_string(int status);
  * diagonals (8 bytes per diagonal and entry of a column panel of C, panels of about 1 GiB)
  *   - for up to 20 slices only when min(sA, sB) * k > 133144, i.e. when a diagonal's int32 sum could overflow and
  *     k has to be cut into blocks,
- *   - for 21 ... 32 equal slice counts always: the products are formed group of slices by group of slices and meet
- *     in the totals; the planes then hold a whole number of groups of 7, 8 or 9 slices (up to 2 zero slices
+ *   - for product sets beyond those kernels (21 ... 32 equal counts; different counts with the larger above 18; all
+ *     products of more than 9 slices) always: the products are formed group of slices by group of slices and meet
+ *     in the totals; the planes then hold a whole number of groups of 7, 8 or 9 slices per operand (zero slices
  *     appended).
  * Returns 0 for invalid arguments.  Alignment required of the workspace pointer: 256 bytes.
  */
