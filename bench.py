@@ -269,12 +269,13 @@ def main():
         for ss in cfg["s"]:
             # at least 0.4 s of steps per slice count, so that the board-power reading has settled
             dts, _, _ = run(ss, 3, 2)
-            dts, ph, pw = run(ss, min(500, max(5, args.steps // 2, int(0.4 / dts) + 1)), 0)
+            nsteps = min(500, max(5, args.steps // 2, int(0.4 / dts) + 1))
+            dts, ph, pw = run(ss, nsteps, 0)
             pp = ss * (ss + 1) // 2
             ozimmu.dgemm(dA, dB, ss, C=C)
             nw, cw = error_measures(C, dA, dB, Cref)
             tops = flops * pp / (ph["gemm"] * 1e-3) / 1e12
-            sweep.append({"s": ss, "ms_per_step": dts * 1e3, "tflops_effective": flops / dts / 1e12,
+            sweep.append({"s": ss, "steps": nsteps, "ms_per_step": dts * 1e3, "tflops_effective": flops / dts / 1e12,
                           "kernel": ph["kernel"], "gemm_ms": ph["gemm"], "scales_ms": ph["scales"],
                           "split_ms": ph["split"], "int8_tops": tops, "frac_int8_peak": tops / INT8_PEAK_TOPS,
                           "traffic": measured.get(f"{args.workload}:{ss}"),
