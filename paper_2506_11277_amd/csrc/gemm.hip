@@ -792,6 +792,34 @@ hipError_t launch_block(int m, int n, int kp, const int8_t *pA, const int8_t *pB
     return hipGetLastError();
 }
 
+// The same plan through the 16x16x64 kernel (tile 128 x 64, two wavefronts per SIMD; the faster one, but its planes
+// must hold the same number of slices per entry for both operands).  It computes reduced sets only, so a whole
+// block is two launches: the reduced set l' + h' <= G + 1 of the pair of groups, and the rest l' + h' >= G + 2, which
+// is the reduced set of G - 1 slices once both groups are walked backwards from their last slice (l'' = G + 1 - l',
+// h'' = G + 1 - h': l'' + h'' <= G, l'', h'' <= G - 1), its diagonals descending from the block's last one.
+inline hipError_t launch_blocks16(int m, int n, int kp, const BlocksPlan &plan, bool all_products, int diagonals,
+                                  int na_tot, const int8_t *pA, const int8_t *pB, const int32_t *eA, const int32_t *eB,
+                                  double *C, int ldc, long long *totals, int Q, hipStream_t st)
+{
+    const int G = plan.G, NGA = plan.spA / G, NGB = plan.spB / G, NG = NGA > NGB ? NGA : NGB;
+    const int tiles_m = (m + 127) / 128, tiles_n = (n + 63) / 64;
+    zero_i64_kernel<<<2048, 256, 0, st>>>(totals, (size_t)tiles_m * tiles_n * na_tot * 128 * 64);
+    for (int I = 0; I < NGA; ++I)
+        for (int J = 0; J < NGB; ++J) {
+            if (!all_products && I + J > NG - 1) continue;
+            const int d0 = G * (I + J);                                       // first diagonal of the block
+            hipError_t e = launch_fused16_window(G, m, n, kp, pA, pB, totals,
+                                                 Window16{plan.spA, I * G, 1, J * G, 1, d0, 1, na_tot}, st);
+            if (e != hipSuccess) return e;
+            if (all_products || I + J < NG - 1) {
+                e = launch_fused16_window(G - 1, m, n, kp, pA, pB, totals,
+                                          Window16{plan.spA, I * G + G - 1, -1, J * G + G - 1, -1, d0 + 2 * G - 2, -1, na_tot}, st);
+                if (e != hipSuccess) return e;
+            }
+        }
+    return launch_finish_blocks16(totals, eA, eB, C, ldc, m, n, Q, diagonals, na_tot, st);
+}
+
 // one column panel of C: `diagonals` = those of the requested product set, na_tot = those the totals hold
 template <int G>
 hipError_t launch_blocks_g(int m, int n, int kp, const BlocksPlan &plan, bool all_products, int diagonals, int na_tot,
@@ -898,6 +926,30 @@ size_t fused_totals_bytes(int sA, int sB, bool all_products, int m, int n, int k
     return tiles * (size_t)s * tm * tn * sizeof(long long);
 }
 
+// Column panel of the block path: about g_panel_bytes of totals as for split-k, then narrowed (by up to a half) to
+// the width whose tiles fill the 256 compute units in whole rounds best -- every block is a launch of its own, so a
+// last round that is half empty is paid once per block (8192 rows, 24 diagonals: 640 columns are 2.5 rounds of
+// 128 x 64 tiles, 512 columns are 2).
+static int blocks_panel_cols(int diagonals, int m, int n, int tile_m, int tile_n)
+{
+    const int w0 = fused_panel_cols(diagonals, m, n);
+    if (w0 >= n) return w0;
+    const long long tm = (m + tile_m - 1) / tile_m;
+    int best = w0;
+    double best_eff = 0.0;
+    for (int w = w0; w >= kPad && 2 * w >= w0; w -= kPad) {
+        const long long tiles = tm * ((w + tile_n - 1) / tile_n), rounds = (tiles + 255) / 256;
+        const double eff = (double)tiles / (double)(rounds * 256);
+        if (eff > best_eff + 0.02) { best_eff = eff; best = w; }
+    }
+    return best;
+}
+
+// The 16x16x64 kernel takes the blocks when both planes hold the same number of slices per entry and the groups have
+// 8 or 9 slices (8192^3: s = 24 2730 -> 2850, s = 27 2850 -> 3000, s = 32 2770 -> 2930 TOP/s; groups of 7, which would
+// run its weakest slice counts 7 and 6, lose 6 %: 21 and 28 slices stay with the 32x32x32 blocks).
+static bool blocks_use16(const BlocksPlan &p) { return p.spA == p.spB && p.G >= 8; }
+
 static int blocks_total_diagonals(const BlocksPlan &p, bool all_products)
 {
     return all_products ? p.spA + p.spB - 1 : (p.spA > p.spB ? p.spA : p.spB);
@@ -908,8 +960,12 @@ size_t blocks_totals_bytes(int sA, int sB, bool all_products, int m, int n)
     BlocksPlan p;
     if (m <= 0 || n <= 0 || !blocks_plan(sA, sB, all_products, &p)) return 0;
     const int na_tot = blocks_total_diagonals(p, all_products);
-    const int w = fused_panel_cols(na_tot, m, n);
-    const size_t tiles = (size_t)((m + kBlkTile - 1) / kBlkTile) * (((w < n ? w : n) + kBlkTile - 1) / kBlkTile);
+    const bool use16 = blocks_use16(p);          // 16x16x64 blocks, tile 128 x 64
+    const int w = blocks_panel_cols(na_tot, m, n, use16 ? 128 : kBlkTile, use16 ? 64 : kBlkTile);
+    const int wn = w < n ? w : n;
+    if (use16)
+        return (size_t)((m + 127) / 128) * ((wn + 63) / 64) * (size_t)na_tot * 128 * 64 * sizeof(long long);
+    const size_t tiles = (size_t)((m + kBlkTile - 1) / kBlkTile) * ((wn + kBlkTile - 1) / kBlkTile);
     return tiles * (size_t)na_tot * kBlkTile * kBlkTile * sizeof(long long);
 }
 
@@ -922,16 +978,26 @@ hipError_t launch_gemm_blocks(int m, int n, int kp, int sA, int sB, bool all_pro
     if (!blocks_plan(sA, sB, all_products, &p) || !totals) return hipErrorInvalidValue;
     const int na_tot = blocks_total_diagonals(p, all_products);
     const int diagonals = all_products ? sA + sB - 1 : (sA > sB ? sA : sB);
-    note_gemm_kernel("blocks of slice groups: %d x %d groups of %d slices through gemm_fused_kernel<%d> tile %dx%d",
-                     p.spA / p.G, p.spB / p.G, p.G, p.G, kBlkTile, kBlkTile);
+    const bool use16 = blocks_use16(p);
+    if (use16)
+        note_gemm_kernel("blocks of slice groups: %d x %d groups of %d slices through gemm_fused16_kernel<%d> and <%d> "
+                         "tile 128x64", p.spA / p.G, p.spB / p.G, p.G, p.G, p.G - 1);
+    else
+        note_gemm_kernel("blocks of slice groups: %d x %d groups of %d slices through gemm_fused_kernel<%d> tile %dx%d",
+                         p.spA / p.G, p.spB / p.G, p.G, p.G, kBlkTile, kBlkTile);
     // one column panel of C after the other through the same totals
-    const int w = fused_panel_cols(na_tot, m, n);
+    const int w = blocks_panel_cols(na_tot, m, n, use16 ? 128 : kBlkTile, use16 ? 64 : kBlkTile);
     const size_t frag_row_bytes = (size_t)(kp / kFrag) * p.spB * kFragBytes;      // one 32-column fragment row of B
     for (int c0 = 0; c0 < n; c0 += w) {
         const int nc = n - c0 < w ? n - c0 : w;
         const int8_t *pBc = pB + (size_t)(c0 / kFrag) * frag_row_bytes;
         double *Cc = C + (size_t)c0 * ldc;
         hipError_t e;
+        if (use16) {
+            e = launch_blocks16(m, nc, kp, p, all_products, diagonals, na_tot, pA, pBc, eA, eB + c0, Cc, ldc, totals, Q, st);
+            if (e != hipSuccess) return e;
+            continue;
+        }
         switch (p.G) {
 #define OZ_CASE(G_) \
     case G_: \

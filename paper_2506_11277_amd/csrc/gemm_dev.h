@@ -71,6 +71,22 @@ __device__ __forceinline__ bool tile_of_block_xcd(int b, int tiles_m, int tiles_
     return true;
 }
 
+// Window of the planes one launch of the 16x16x64 kernel works on, and where its diagonals go in split-k totals
+// (blocks of slice groups: slice counts beyond the accumulator budget are multiplied group by group).  Both planes
+// hold `stride` slices per entry; local slice l (0-based) of A is plane slice baseA + dirA * l, of B likewise
+// (dir = -1 walks a group backwards, which turns the products l' + h' >= G + 2 of a pair of groups into a reduced
+// set); local diagonal a is diagonal abase + adir * a of the na_tot diagonals the totals hold per entry.
+struct Window16 {
+    int stride, baseA, dirA, baseB, dirB, abase, adir, na_tot;
+};
+
+// (gemm_fused16.hip) one block: the reduced product set of s in {6, ..., 9} slices on a window, k-blocked, int32
+// diagonal sums added to `totals` (layout of the 128 x 64 tile) with integer atomics; and the finishing kernel
+hipError_t launch_fused16_window(int s, int m, int n, int kp, const int8_t *pA, const int8_t *pB, long long *totals,
+                                 Window16 win, hipStream_t st);
+hipError_t launch_finish_blocks16(const long long *totals, const int32_t *eA, const int32_t *eB, double *C, int ldc,
+                                  int m, int n, int Q, int diagonals, int na_tot, hipStream_t st);
+
 // 16 bytes per lane: global (sbase + voff)  ->  LDS (ldsaddr + lane * 16); ldsaddr is wavefront-uniform.
 // (global_load_lds: the LDS-DMA form of the vector load, 1 KiB per wavefront instruction; issued
 // from inline asm, so the waits on these loads (vmcnt) are placed by hand, and so is the wait state between the

@@ -141,7 +141,8 @@ template <int S, int MODE>
 __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused16_kernel(
     const int8_t *__restrict__ pA, const int8_t *__restrict__ pB, const int32_t *__restrict__ eA,
     const int32_t *__restrict__ eB, double *__restrict__ C, int ldc, int m, int n, int KB, int tiles_m, int tiles_n,
-    int32_t *__restrict__ dump, long long *__restrict__ totals, int stages_per_block, int Q, long long slot_stride)
+    int32_t *__restrict__ dump, long long *__restrict__ totals, int stages_per_block, int Q, long long slot_stride,
+    Window16 win)
 {
     using G = Cfg16<S>;
     constexpr int WVM = G::WVM, WVN = G::WVN, WMF = G::WMF, WNF = G::WNF, FA = G::FA, FB = G::FB, L0 = G::L0;
@@ -162,7 +163,7 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wm = wave % WVM, wn = wave / WVM;
-    const size_t row_bytes = (size_t)KB * (S * kFragBytes);
+    const size_t row_bytes = (size_t)KB * ((size_t)win.stride * kFragBytes);
     // fragment rows of the planes (padded to kPad entries): a tile taller or wider than the padding may reach
     // beyond them at the edge; such rows are read from the last valid fragment row instead (their outputs lie
     // beyond m resp. n and are never stored)
@@ -189,25 +190,25 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
     // this work-group formed once here (a stage advances every source by STG bytes, which the copies carry in their
     // 32-bit lane offset: a k-block is a few MiB of a fragment row at most, whatever k).
     constexpr int NU1 = (U1 + NW - 1) / NW, NU2 = SPLIT ? (U2 + NW - 1) / NW : 0;
-    constexpr size_t STG = (size_t)2 * S * kFragBytes;
+    const size_t STG = (size_t)2 * win.stride * kFragBytes;      // bytes of a 64-k stage in a fragment row of the planes
     const int8_t *src1[NU1], *src2[NU2 ? NU2 : 1];
 #pragma unroll
     for (int i = 0; i < NU1; ++i) {
         const int u = wave + i * NW;
         if (u < U1A) {
             const int c = u / (2 * L0), l = (u / 2) % L0, kk = u % 2;
-            src1[i] = rowA_of(c) + (size_t)st0 * STG + (size_t)(kk * S + l) * kFragBytes;
+            src1[i] = rowA_of(c) + (size_t)st0 * STG + (size_t)(kk * win.stride + win.baseA + win.dirA * l) * kFragBytes;
         } else {
             const int v = u - U1A;
             const int c = v / (2 * S), h = (v / 2) % S, kk = v % 2;
-            src1[i] = rowB_of(c) + (size_t)st0 * STG + (size_t)(kk * S + h) * kFragBytes;
+            src1[i] = rowB_of(c) + (size_t)st0 * STG + (size_t)(kk * win.stride + win.baseB + win.dirB * h) * kFragBytes;
         }
     }
 #pragma unroll
     for (int i = 0; i < NU2; ++i) {
         const int u = wave + i * NW;
         const int c = u / (2 * NS2), l = L0 + (u / 2) % NS2, kk = u % 2;
-        src2[i] = rowA_of(c) + (size_t)st0 * STG + (size_t)(kk * S + l) * kFragBytes;
+        src2[i] = rowA_of(c) + (size_t)st0 * STG + (size_t)(kk * win.stride + win.baseA + win.dirA * l) * kFragBytes;
     }
     // Unit I of the double-buffered part (issue1) / of the single-buffered part (issue2): `voff` carries the stage
     // (lane * 16 + (stage - first stage) * STG), `ldsbuf` the ring buffer and the wavefront.  Two instructions per
@@ -402,7 +403,7 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
     // element of accumulator block (i2, j2), register r: m_local = 16*i2 + lane%16, n_local = 16*j2 + 4*(lane/16) + r
     const int m0 = (tm * FA + wm * WMF) * 32, n0 = (tn * FB + wn * WNF) * 32;
     if (MODE == kBlocked) {
-        const size_t e0 = ((size_t)(tm * tiles_n + tn) * NW + wave) * (size_t)(S * WMF * WNF * 16 * 64) + lane;
+        const size_t e0 = ((size_t)(tm * tiles_n + tn) * NW + wave) * (size_t)(win.na_tot * WMF * WNF * 16 * 64) + lane;
         if (slot_stride) {
             // exactly two k-blocks: plain int32 stores into this block's slot, nothing cleared, nothing added
             int *slot = (int *)totals + (size_t)blockIdx.y * (size_t)slot_stride + e0;
@@ -434,7 +435,7 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
                     for (int b = 0; b < 4; ++b)
 #pragma unroll
                         for (int r = 0; r < 4; ++r)
-                            __hip_atomic_fetch_add(tot + ((((size_t)a * WMF + i) * WNF + j) * 16 + b * 4 + r) * 64,
+                            __hip_atomic_fetch_add(tot + ((((size_t)(win.abase + win.adir * a) * WMF + i) * WNF + j) * 16 + b * 4 + r) * 64,
                                                    (long long)acc[a][i][j][b][r], __ATOMIC_RELAXED,
                                                    __HIP_MEMORY_SCOPE_AGENT);
         return;
@@ -509,6 +510,38 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void finish_blo
         }
 }
 
+// Binary64 accumulation after the block launches of launch_gemm_blocks: the totals hold na_tot diagonals per entry in
+// the layout of the 128 x 64 tile (4 x 2 wavefronts), the first `diagonals` of them are added in ascending order.
+__global__ __launch_bounds__(512) void finish_blocks16_kernel(const long long *__restrict__ totals,
+                                                              const int32_t *__restrict__ eA,
+                                                              const int32_t *__restrict__ eB, double *__restrict__ C,
+                                                              int ldc, int m, int n, int tiles_n, int Q, int diagonals,
+                                                              int na_tot)
+{
+    constexpr int WVM = 4, NW = 8;
+    const int tm = blockIdx.x / tiles_n, tn = blockIdx.x % tiles_n;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave % WVM, wn = wave / WVM;
+    const long long *tot = totals + ((size_t)blockIdx.x * NW + wave) * (size_t)(na_tot * 16 * 64) + lane;
+    const int m0 = (tm * 4 + wm) * 32, n0 = (tn * 2 + wn) * 32;
+    for (int i2 = 0; i2 < 2; ++i2) {
+        const int mi = m0 + i2 * 16 + (lane & 15);
+        if (mi >= m) continue;
+        const int ea = eA[mi];
+        for (int j2 = 0; j2 < 2; ++j2)
+            for (int r = 0; r < 4; ++r) {
+                const int nj = n0 + j2 * 16 + 4 * (lane >> 4) + r;
+                if (nj >= n) continue;
+                LevelSum sum;
+                for (int a = 0; a < diagonals; ++a) {
+                    const long long v = tot[((size_t)a * 16 + (i2 * 2 + j2) * 4 + r) * 64];
+                    sum.add(ldexp((double)v, -kSliceBits * (a + 2)), Q, a == diagonals - 1);      // exact: |v| < 2^53
+                }
+                C[mi + (size_t)nj * ldc] = ldexp(sum.S, ea + eB[nj]);
+            }
+    }
+}
+
 __global__ void zero16_i64_kernel(long long *p, size_t n)
 {
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0;
@@ -529,7 +562,7 @@ hipError_t launch16_s(int m, int n, int kp, const int8_t *pA, const int8_t *pB, 
                      MODE == kBlocked ? " split-k" : "");
     if (MODE != kBlocked) {
         kern<<<(unsigned)tile_order_blocks(tiles_m, tiles_n, false), THREADS, G::LDS, st>>>(pA, pB, eA, eB, C, ldc, m, n, KB, tiles_m, tiles_n, dump,
-                                                         nullptr, 0, Q, 0);
+                                                         nullptr, 0, Q, 0, Window16{S, 0, 1, 0, 1, 0, 1, S});
         return hipGetLastError();
     }
     // longest k-block (in 64-k stages) whose s products per diagonal cannot overflow int32; equally long blocks
@@ -543,8 +576,31 @@ hipError_t launch16_s(int m, int n, int kp, const int8_t *pA, const int8_t *pB, 
     if (!slot_stride) zero16_i64_kernel<<<2048, 256, 0, st>>>(totals, nslots);
     dim3 grid((unsigned)tile_order_blocks(tiles_m, tiles_n, true), nblocks);
     kern<<<grid, THREADS, G::LDS, st>>>(pA, pB, eA, eB, C, ldc, m, n, KB, tiles_m, tiles_n, nullptr, totals,
-                                        stages_per_block, Q, slot_stride);
+                                        stages_per_block, Q, slot_stride, Window16{S, 0, 1, 0, 1, 0, 1, S});
     finish_blocked16_kernel<S><<<tiles_m * tiles_n, THREADS, 0, st>>>(totals, eA, eB, C, ldc, m, n, tiles_n, Q, slot_stride);
+    return hipGetLastError();
+}
+
+// One block of slice groups: the reduced product set of S slices on a window of the planes, k-blocked, its int32
+// diagonal sums added to the totals with integer atomics (nothing cleared, nothing finished here).
+template <int S>
+hipError_t launch16_window(int m, int n, int kp, const int8_t *pA, const int8_t *pB, long long *totals, Window16 win,
+                           hipStream_t st)
+{
+    using G = Cfg16<S>;
+    constexpr int TM = 32 * G::FA, TN = 32 * G::FB, THREADS = 64 * G::WVM * G::WVN;
+    static_assert(TM == 128 && TN == 64 && G::WVM == 4 && G::WVN == 2, "blocks share the totals layout of the 128 x 64 tile");
+    auto kern = gemm_fused16_kernel<S, kBlocked>;
+    static std::atomic<unsigned long long> configured{0};
+    if (hipError_t e = allow_dynamic_lds((const void *)kern, G::LDS, configured); e != hipSuccess) return e;
+    const int tiles_m = (m + TM - 1) / TM, tiles_n = (n + TN - 1) / TN;
+    const int max_stages = (int)(kMaxInt32K / S / (2 * kFrag));
+    const int nst = kp / kFrag / 2;
+    const int nblocks = (nst + max_stages - 1) / max_stages;
+    const int stages_per_block = (nst + nblocks - 1) / nblocks;
+    dim3 grid((unsigned)tile_order_blocks(tiles_m, tiles_n, true), nblocks);
+    kern<<<grid, THREADS, G::LDS, st>>>(pA, pB, nullptr, nullptr, nullptr, 0, m, n, kp / kFrag, tiles_m, tiles_n, nullptr,
+                                        totals, stages_per_block, 1, 0, win);
     return hipGetLastError();
 }
 
@@ -569,6 +625,27 @@ hipError_t dispatch16(int s, int m, int n, int kp, const int8_t *pA, const int8_
 // measured there) and stays ahead at s = 6; beyond 9 a 64-deep stage of a 128 x 64 tile does not fit LDS.  Only the
 // preferred ones are instantiated.
 bool fused16_preferred(int s, bool split_k) { return s >= 2 && s <= 9 && !((s <= 3 || s == 6) && split_k); }
+
+hipError_t launch_fused16_window(int s, int m, int n, int kp, const int8_t *pA, const int8_t *pB, long long *totals,
+                                 Window16 win, hipStream_t st)
+{
+    if (m <= 0 || n <= 0) return hipSuccess;
+    switch (s) {
+#define OZ_CASE(S_) case S_: return launch16_window<S_>(m, n, kp, pA, pB, totals, win, st);
+        OZ_CASE(6) OZ_CASE(7) OZ_CASE(8) OZ_CASE(9)
+#undef OZ_CASE
+    }
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_finish_blocks16(const long long *totals, const int32_t *eA, const int32_t *eB, double *C, int ldc,
+                                  int m, int n, int Q, int diagonals, int na_tot, hipStream_t st)
+{
+    if (m <= 0 || n <= 0) return hipSuccess;
+    const int tiles_m = (m + 127) / 128, tiles_n = (n + 63) / 64;
+    finish_blocks16_kernel<<<tiles_m * tiles_n, 512, 0, st>>>(totals, eA, eB, C, ldc, m, n, tiles_n, Q, diagonals, na_tot);
+    return hipGetLastError();
+}
 
 void fused16_tile(int s, int &tm, int &tn)
 {

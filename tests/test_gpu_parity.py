@@ -638,11 +638,12 @@ def test_which_kernel_takes_which_product_set():
               ((7, 8, False), "gemm_fused16_kernel<8> tile 128x64"),                 # run as (8, 8), zero slice appended
               ((4, 12, False), "gemm_fused_kernel<12> different counts tile 128x64, 8 wavefronts"),
               ((6, 6, True), "gemm_fused_kernel<6> all products tile 128x64, 8 wavefronts"),
-              ((24, 24, False), "blocks of slice groups: 3 x 3 groups of 8 slices"),
+              ((24, 24, False), "blocks of slice groups: 3 x 3 groups of 8 slices through gemm_fused16_kernel<8> and <7>"),
               ((26, 26, False), "blocks of slice groups: 3 x 3 groups of 9 slices"),
               ((25, 31, False), "blocks of slice groups: 4 x 4 groups of 8 slices"),
               ((20, 7, False), "blocks of slice groups: 3 x 1 groups of 7 slices"),
-              ((13, 13, True), "blocks of slice groups: 2 x 2 groups of 7 slices"),
+              ((13, 13, True), "blocks of slice groups: 2 x 2 groups of 7 slices through gemm_fused_kernel<7>"),
+              ((16, 16, True), "blocks of slice groups: 2 x 2 groups of 8 slices through gemm_fused16_kernel<8> and <7>"),
               ((12, 5, True), "gemm_banded_kernel (12, 5) slices")]
     for (sA, sB, allp), name in expect:
         C = ozimmu.dgemm2(dA, dB, sA, sB, allp)
