@@ -67,6 +67,10 @@ constexpr int kThreads = 256;   // generic kernel: 4 wavefronts, 2 (m) x 2 (n)
 struct SliceWindow {
     int strA, strB, offA, offB, a0, na_tot;
 };
+// several windows in one launch (blockIdx.z picks one): see WindowList16
+struct SliceWindowList {
+    SliceWindow w[kMaxWindows16];
+};
 
 template <int S, int WVM, int WVN, int WMF, int WNF, int KB32, int NSTAGE, int MODE, int PSET>
 __global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t *__restrict__ pA,
@@ -78,8 +82,9 @@ __global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t
                                                                     int32_t *__restrict__ dump,
                                                                     long long *__restrict__ totals,
                                                                     int stages_per_block, int Q, int sm,
-                                                                    long long slot_stride, SliceWindow win)
+                                                                    long long slot_stride, SliceWindowList wins)
 {
+    const SliceWindow win = wins.w[blockIdx.z];
     static_assert(PSET == 0 || (NSTAGE == 2 && MODE != kDump), "other product sets: ring of two, no dump");
     constexpr bool DUMP = MODE == kDump;
     constexpr int NA = PSET == 3 ? 2 * S - 1 : S;      // diagonals = accumulator sets
@@ -681,7 +686,7 @@ hipError_t launch_fused_s(int m, int n, int kp, const int8_t *pA, const int8_t *
     if (MODE != kBlocked) {
         kern<<<(unsigned)tile_order_blocks(tiles_m, tiles_n, false), 64 * Cfg::WVM * Cfg::WVN, NSTAGE * STAGE, st>>>(
             pA, pB, eA, eB, C, ldc, m, n, kp / kFrag, tiles_m, tiles_n, dump, nullptr, 0, Q, sm, 0,
-            SliceWindow{S, S, 0, 0, 0, NA});
+            SliceWindowList{{SliceWindow{S, S, 0, 0, 0, NA}}});
         return hipGetLastError();
     }
     // longest k-block whose sm products per diagonal cannot overflow int32, in whole stages; the blocks are
@@ -697,7 +702,7 @@ hipError_t launch_fused_s(int m, int n, int kp, const int8_t *pA, const int8_t *
     dim3 grid((unsigned)tile_order_blocks(tiles_m, tiles_n, true), nblocks);
     kern<<<grid, 64 * Cfg::WVM * Cfg::WVN, NSTAGE * STAGE, st>>>(pA, pB, eA, eB, C, ldc, m, n, kp / kFrag, tiles_m,
                                                                   tiles_n, nullptr, totals, stages_per_block, Q, sm,
-                                                                  slot_stride, SliceWindow{S, S, 0, 0, 0, NA});
+                                                                  slot_stride, SliceWindowList{{SliceWindow{S, S, 0, 0, 0, NA}}});
     finish_blocked_kernel<NA, Cfg::WVM, Cfg::WVN, Cfg::WMF, Cfg::WNF>
         <<<tiles_m * tiles_n, 64 * Cfg::WVM * Cfg::WVN, 0, st>>>(totals, eA, eB, C, ldc, m, n, tiles_n, Q, slot_stride);
     return hipGetLastError();
@@ -774,8 +779,9 @@ constexpr int kBlkWVM = 2, kBlkWVN = 2, kBlkTile = 64;
 
 template <int G, int PSET>
 hipError_t launch_block(int m, int n, int kp, const int8_t *pA, const int8_t *pB, long long *totals, int Q,
-                        SliceWindow win, hipStream_t st)
+                        const SliceWindowList &wins, int nwin, hipStream_t st)
 {
+    if (nwin <= 0) return hipSuccess;
     constexpr int STAGE = 4 * G * kFragBytes;
     auto kern = gemm_fused_kernel<G, kBlkWVM, kBlkWVN, 1, 1, 1, 2, kBlocked, PSET>;
     static std::atomic<unsigned long long> configured{0};
@@ -786,9 +792,9 @@ hipError_t launch_block(int m, int n, int kp, const int8_t *pA, const int8_t *pB
     const int nst = kp / kFrag;
     const int nblocks = (nst + max_stages - 1) / max_stages;
     const int stages_per_block = (nst + nblocks - 1) / nblocks;
-    dim3 grid((unsigned)tile_order_blocks(tiles_m, tiles_n, true), nblocks);
+    dim3 grid((unsigned)tile_order_blocks(tiles_m, tiles_n, true), nblocks, nwin);
     kern<<<grid, 64 * kBlkWVM * kBlkWVN, 2 * STAGE, st>>>(pA, pB, nullptr, nullptr, nullptr, 0, m, n, kp / kFrag, tiles_m,
-                                                          tiles_n, nullptr, totals, stages_per_block, Q, G, 0, win);
+                                                          tiles_n, nullptr, totals, stages_per_block, Q, G, 0, wins);
     return hipGetLastError();
 }
 
@@ -804,19 +810,30 @@ inline hipError_t launch_blocks16(int m, int n, int kp, const BlocksPlan &plan, 
     const int G = plan.G, NGA = plan.spA / G, NGB = plan.spB / G, NG = NGA > NGB ? NGA : NGB;
     const int tiles_m = (m + 127) / 128, tiles_n = (n + 63) / 64;
     zero_i64_kernel<<<2048, 256, 0, st>>>(totals, (size_t)tiles_m * tiles_n * na_tot * 128 * 64);
+    // all blocks of the panel in two launches: the reduced sets of G slices (every block), the reversed reduced sets of
+    // G - 1 slices (the whole blocks); more than kMaxWindows16 of a kind go in several launches
+    WindowList16 fwd, rev;
+    int nf = 0, nr = 0;
+    auto flush = [&](int s_, WindowList16 &list, int &cnt) {
+        const hipError_t e = launch_fused16_windows(s_, m, n, kp, pA, pB, totals, list, cnt, st);
+        cnt = 0;
+        return e;
+    };
     for (int I = 0; I < NGA; ++I)
         for (int J = 0; J < NGB; ++J) {
             if (!all_products && I + J > NG - 1) continue;
             const int d0 = G * (I + J);                                       // first diagonal of the block
-            hipError_t e = launch_fused16_window(G, m, n, kp, pA, pB, totals,
-                                                 Window16{plan.spA, I * G, 1, J * G, 1, d0, 1, na_tot}, st);
-            if (e != hipSuccess) return e;
+            fwd.w[nf++] = Window16{plan.spA, I * G, 1, J * G, 1, d0, 1, na_tot};
+            if (nf == kMaxWindows16)
+                if (hipError_t e = flush(G, fwd, nf); e != hipSuccess) return e;
             if (all_products || I + J < NG - 1) {
-                e = launch_fused16_window(G - 1, m, n, kp, pA, pB, totals,
-                                          Window16{plan.spA, I * G + G - 1, -1, J * G + G - 1, -1, d0 + 2 * G - 2, -1, na_tot}, st);
-                if (e != hipSuccess) return e;
+                rev.w[nr++] = Window16{plan.spA, I * G + G - 1, -1, J * G + G - 1, -1, d0 + 2 * G - 2, -1, na_tot};
+                if (nr == kMaxWindows16)
+                    if (hipError_t e = flush(G - 1, rev, nr); e != hipSuccess) return e;
             }
         }
+    if (hipError_t e = flush(G, fwd, nf); e != hipSuccess) return e;
+    if (hipError_t e = flush(G - 1, rev, nr); e != hipSuccess) return e;
     return launch_finish_blocks16(totals, eA, eB, C, ldc, m, n, Q, diagonals, na_tot, st);
 }
 
@@ -829,15 +846,29 @@ hipError_t launch_blocks_g(int m, int n, int kp, const BlocksPlan &plan, bool al
     const int NGA = plan.spA / G, NGB = plan.spB / G, NG = NGA > NGB ? NGA : NGB;
     const int tiles_m = (m + kBlkTile - 1) / kBlkTile, tiles_n = (n + kBlkTile - 1) / kBlkTile;
     zero_i64_kernel<<<2048, 256, 0, st>>>(totals, (size_t)tiles_m * tiles_n * na_tot * kBlkTile * kBlkTile);
+    // all whole blocks of the panel in one launch, all reduced ones in another (kMaxWindows16 at a time)
+    SliceWindowList whole, reduced;
+    int nw = 0, nr = 0;
     for (int I = 0; I < NGA; ++I)
         for (int J = 0; J < NGB; ++J) {
             if (!all_products && I + J > NG - 1) continue;
             const SliceWindow win{plan.spA, plan.spB, I * G, J * G, G * (I + J), na_tot};
-            const bool whole = all_products || I + J < NG - 1;
-            const hipError_t e = whole ? launch_block<G, 3>(m, n, kp, pA, pB, totals, Q, win, st)
-                                       : launch_block<G, 4>(m, n, kp, pA, pB, totals, Q, win, st);
-            if (e != hipSuccess) return e;
+            if (all_products || I + J < NG - 1) {
+                whole.w[nw++] = win;
+                if (nw == kMaxWindows16) {
+                    if (hipError_t e = launch_block<G, 3>(m, n, kp, pA, pB, totals, Q, whole, nw, st); e != hipSuccess) return e;
+                    nw = 0;
+                }
+            } else {
+                reduced.w[nr++] = win;
+                if (nr == kMaxWindows16) {
+                    if (hipError_t e = launch_block<G, 4>(m, n, kp, pA, pB, totals, Q, reduced, nr, st); e != hipSuccess) return e;
+                    nr = 0;
+                }
+            }
         }
+    if (hipError_t e = launch_block<G, 3>(m, n, kp, pA, pB, totals, Q, whole, nw, st); e != hipSuccess) return e;
+    if (hipError_t e = launch_block<G, 4>(m, n, kp, pA, pB, totals, Q, reduced, nr, st); e != hipSuccess) return e;
     finish_blocks_kernel<kBlkWVM, kBlkWVN, 1, 1>
         <<<tiles_m * tiles_n, 64 * kBlkWVM * kBlkWVN, 0, st>>>(totals, eA, eB, C, ldc, m, n, tiles_n, Q, diagonals, na_tot);
     return hipGetLastError();

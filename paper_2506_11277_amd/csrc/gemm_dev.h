@@ -79,11 +79,17 @@ __device__ __forceinline__ bool tile_of_block_xcd(int b, int tiles_m, int tiles_
 struct Window16 {
     int stride, baseA, dirA, baseB, dirB, abase, adir, na_tot;
 };
+// Several blocks in ONE launch (blockIdx.z picks the window): a block on a column panel is only a couple of rounds of
+// tiles, and a launch of its own would pay the ramp-up and the half-empty last round once per block.
+constexpr int kMaxWindows16 = 16;
+struct WindowList16 {
+    Window16 w[kMaxWindows16];
+};
 
-// (gemm_fused16.hip) one block: the reduced product set of s in {6, ..., 9} slices on a window, k-blocked, int32
+// (gemm_fused16.hip) nwin <= kMaxWindows16 blocks in one launch, each: the reduced product set of s in {6, ..., 9} slices on a window, k-blocked, int32
 // diagonal sums added to `totals` (layout of the 128 x 64 tile) with integer atomics; and the finishing kernel
-hipError_t launch_fused16_window(int s, int m, int n, int kp, const int8_t *pA, const int8_t *pB, long long *totals,
-                                 Window16 win, hipStream_t st);
+hipError_t launch_fused16_windows(int s, int m, int n, int kp, const int8_t *pA, const int8_t *pB, long long *totals,
+                                  const WindowList16 &wins, int nwin, hipStream_t st);
 hipError_t launch_finish_blocks16(const long long *totals, const int32_t *eA, const int32_t *eB, double *C, int ldc,
                                   int m, int n, int Q, int diagonals, int na_tot, hipStream_t st);
 

@@ -142,9 +142,10 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused
     const int8_t *__restrict__ pA, const int8_t *__restrict__ pB, const int32_t *__restrict__ eA,
     const int32_t *__restrict__ eB, double *__restrict__ C, int ldc, int m, int n, int KB, int tiles_m, int tiles_n,
     int32_t *__restrict__ dump, long long *__restrict__ totals, int stages_per_block, int Q, long long slot_stride,
-    Window16 win)
+    WindowList16 wins)
 {
     using G = Cfg16<S>;
+    const Window16 win = wins.w[blockIdx.z];
     constexpr int WVM = G::WVM, WVN = G::WVN, WMF = G::WMF, WNF = G::WNF, FA = G::FA, FB = G::FB, L0 = G::L0;
     constexpr int NW = WVM * WVN;
     constexpr bool SPLIT = L0 < S;
@@ -562,7 +563,7 @@ hipError_t launch16_s(int m, int n, int kp, const int8_t *pA, const int8_t *pB, 
                      MODE == kBlocked ? " split-k" : "");
     if (MODE != kBlocked) {
         kern<<<(unsigned)tile_order_blocks(tiles_m, tiles_n, false), THREADS, G::LDS, st>>>(pA, pB, eA, eB, C, ldc, m, n, KB, tiles_m, tiles_n, dump,
-                                                         nullptr, 0, Q, 0, Window16{S, 0, 1, 0, 1, 0, 1, S});
+                                                         nullptr, 0, Q, 0, WindowList16{{Window16{S, 0, 1, 0, 1, 0, 1, S}}});
         return hipGetLastError();
     }
     // longest k-block (in 64-k stages) whose s products per diagonal cannot overflow int32; equally long blocks
@@ -576,16 +577,17 @@ hipError_t launch16_s(int m, int n, int kp, const int8_t *pA, const int8_t *pB, 
     if (!slot_stride) zero16_i64_kernel<<<2048, 256, 0, st>>>(totals, nslots);
     dim3 grid((unsigned)tile_order_blocks(tiles_m, tiles_n, true), nblocks);
     kern<<<grid, THREADS, G::LDS, st>>>(pA, pB, eA, eB, C, ldc, m, n, KB, tiles_m, tiles_n, nullptr, totals,
-                                        stages_per_block, Q, slot_stride, Window16{S, 0, 1, 0, 1, 0, 1, S});
+                                        stages_per_block, Q, slot_stride, WindowList16{{Window16{S, 0, 1, 0, 1, 0, 1, S}}});
     finish_blocked16_kernel<S><<<tiles_m * tiles_n, THREADS, 0, st>>>(totals, eA, eB, C, ldc, m, n, tiles_n, Q, slot_stride);
     return hipGetLastError();
 }
 
-// One block of slice groups: the reduced product set of S slices on a window of the planes, k-blocked, its int32
-// diagonal sums added to the totals with integer atomics (nothing cleared, nothing finished here).
+// Blocks of slice groups: for each of the nwin windows the reduced product set of S slices on that window of the
+// planes, k-blocked, its int32 diagonal sums added to the totals with integer atomics (nothing cleared, nothing
+// finished here).
 template <int S>
-hipError_t launch16_window(int m, int n, int kp, const int8_t *pA, const int8_t *pB, long long *totals, Window16 win,
-                           hipStream_t st)
+hipError_t launch16_windows(int m, int n, int kp, const int8_t *pA, const int8_t *pB, long long *totals,
+                            const WindowList16 &wins, int nwin, hipStream_t st)
 {
     using G = Cfg16<S>;
     constexpr int TM = 32 * G::FA, TN = 32 * G::FB, THREADS = 64 * G::WVM * G::WVN;
@@ -598,9 +600,9 @@ hipError_t launch16_window(int m, int n, int kp, const int8_t *pA, const int8_t 
     const int nst = kp / kFrag / 2;
     const int nblocks = (nst + max_stages - 1) / max_stages;
     const int stages_per_block = (nst + nblocks - 1) / nblocks;
-    dim3 grid((unsigned)tile_order_blocks(tiles_m, tiles_n, true), nblocks);
+    dim3 grid((unsigned)tile_order_blocks(tiles_m, tiles_n, true), nblocks, nwin);
     kern<<<grid, THREADS, G::LDS, st>>>(pA, pB, nullptr, nullptr, nullptr, 0, m, n, kp / kFrag, tiles_m, tiles_n, nullptr,
-                                        totals, stages_per_block, 1, 0, win);
+                                        totals, stages_per_block, 1, 0, wins);
     return hipGetLastError();
 }
 
@@ -626,12 +628,13 @@ hipError_t dispatch16(int s, int m, int n, int kp, const int8_t *pA, const int8_
 // preferred ones are instantiated.
 bool fused16_preferred(int s, bool split_k) { return s >= 2 && s <= 9 && !((s <= 3 || s == 6) && split_k); }
 
-hipError_t launch_fused16_window(int s, int m, int n, int kp, const int8_t *pA, const int8_t *pB, long long *totals,
-                                 Window16 win, hipStream_t st)
+hipError_t launch_fused16_windows(int s, int m, int n, int kp, const int8_t *pA, const int8_t *pB, long long *totals,
+                                  const WindowList16 &wins, int nwin, hipStream_t st)
 {
-    if (m <= 0 || n <= 0) return hipSuccess;
+    if (m <= 0 || n <= 0 || nwin <= 0) return hipSuccess;
+    if (nwin > kMaxWindows16) return hipErrorInvalidValue;
     switch (s) {
-#define OZ_CASE(S_) case S_: return launch16_window<S_>(m, n, kp, pA, pB, totals, win, st);
+#define OZ_CASE(S_) case S_: return launch16_windows<S_>(m, n, kp, pA, pB, totals, wins, nwin, st);
         OZ_CASE(6) OZ_CASE(7) OZ_CASE(8) OZ_CASE(9)
 #undef OZ_CASE
     }
