@@ -24,8 +24,13 @@
 // two instructions each (source addresses formed once per wavefront, the stage in the 32-bit lane offset, the LDS
 // address one scalar add into m0); the loop body has no branch but a ragged last copy.  (A plain loop -- copies
 // issued at the top of the stage, operands read where they are used, barriers behind the last product -- left
-// the matrix pipe idle 30 % of the cycles at s = 7; this one 17 %, at a clock that the power limit lowers
+// the matrix pipe idle 30 % of the cycles at s = 7; this one 15 %, at a clock that the board's power cap lowers
 // accordingly.)
+//
+// The kernel also serves slice counts beyond the accumulator budget: a launch works on a window of planes that hold
+// more slices per entry (Window16 in gemm_dev.h; blockIdx.z picks one of up to 16 windows) and adds its int32
+// diagonal sums to shared int64 totals at a diagonal offset (launch_fused16_windows; the plan is in gemm.hip,
+// launch_gemm_blocks).
 #include <type_traits>
 
 #include "gemm_dev.h"
