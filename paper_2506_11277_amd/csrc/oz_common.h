@@ -177,8 +177,9 @@ int fused_max_slices();
 void fused_set_small_tile_limit(long long tiles);
 // bytes of split-k totals per column panel of C (default 1 GiB; <= 0: no panels); affects fused_totals_bytes
 void fused_set_panel_bytes(long long bytes);
-// true when the fused kernel computes this product set: the reduced set with equal counts <= fused_max_slices()
-// (20) or different counts <= 18, or all products of equal counts with 2 s - 1 <= 18 diagonals
+// true when the routing gives this product set to the fused kernels: the reduced set with equal counts <=
+// fused_max_slices() (20; not 18, which runs faster as two groups of 9) or different counts <= 18, or all products of
+// equal counts with 2 s - 1 <= 18 diagonals
 bool fused_handles(int sA, int sB, bool all_products);
 // true when it can keep the whole contraction in int32 (min(sA, sB) * k * 127^2 < 2^31)
 bool fused_single_block(int sA, int sB, int k);

@@ -638,6 +638,8 @@ def test_which_kernel_takes_which_product_set():
               ((7, 8, False), "gemm_fused16_kernel<8> tile 128x64"),                 # run as (8, 8), zero slice appended
               ((4, 12, False), "gemm_fused_kernel<12> different counts tile 128x64, 8 wavefronts"),
               ((6, 6, True), "gemm_fused_kernel<6> all products tile 128x64, 8 wavefronts"),
+              ((18, 18, False), "blocks of slice groups: 2 x 2 groups of 9 slices through gemm_fused16_kernel<9> and <8>"),
+              ((17, 18, False), "blocks of slice groups: 2 x 2 groups of 9 slices through gemm_fused16_kernel<9> and <8>"),
               ((24, 24, False), "blocks of slice groups: 3 x 3 groups of 8 slices through gemm_fused16_kernel<8> and <7>"),
               ((26, 26, False), "blocks of slice groups: 3 x 3 groups of 9 slices"),
               ((25, 31, False), "blocks of slice groups: 4 x 4 groups of 8 slices"),
