@@ -421,7 +421,7 @@ __global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t
 #pragma unroll
                     for (int a = 0; a < NA; ++a)
                         sum.add((double)acc[a][i][j][r] * __builtin_ldexp(1.0, -kSliceBits * (a + 2)), Q, a == NA - 1);
-                    C[mi + (size_t)nj * ldc] = ldexp(sum.S, ea + eB[nj]);
+                    __builtin_nontemporal_store(ldexp(sum.S, ea + eB[nj]), &C[mi + (size_t)nj * ldc]);   // (streaming: as in gemm_fused16_kernel)
                 }
             }
         }
