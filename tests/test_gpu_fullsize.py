@@ -127,8 +127,10 @@ def check_sampled_variant(dA, dB, sA, sB, allp, nearest, Q, tag):
 
 
 def test_full_size_variants_8192():
-    # the 16x16x64 kernel (s = 4, 7, 8), nearest slices, levels, different slice counts, the four-wavefront shape
-    # (13; 18 with two k-blocks), all products and the band kernel (21) at the benchmark size
+    # the 16x16x64 kernel (s = 4, 7, 8), nearest slices, levels, different slice counts, the four-wavefront shape (13),
+    # all products, and the blocks of slice groups over their 13 ... 16 column panels at the benchmark size: groups of
+    # 9 (18), 7 (21, through the 32x32x32 kernel), 8 (24, 32, (25, 31)), different group counts ((20, 7)), all
+    # products of (16, 16)
     cfg = workloads.CONFIGS["pow2_scaled_8192"]
     A, B = cfg["gen"]()
     dA, dB = ozimmu.to_colmajor(A), ozimmu.to_colmajor(B)
@@ -136,7 +138,9 @@ def test_full_size_variants_8192():
     assert qmax == 4
     for sA, sB, allp, nearest, Q in [(4, 4, False, False, 1), (8, 8, False, True, 3), (7, 7, False, True, qmax),
                                      (5, 10, False, False, 3), (13, 13, False, True, 3), (3, 4, True, False, 2),
-                                     (18, 18, False, False, 2), (6, 6, True, False, 1), (21, 21, False, False, 1)]:
+                                     (18, 18, False, False, 2), (6, 6, True, False, 1), (21, 21, False, False, 1),
+                                     (24, 24, False, False, 1), (32, 32, False, True, 3), (25, 31, False, False, 1),
+                                     (20, 7, False, False, 1), (16, 16, True, False, 1)]:
         print(f"variant sA={sA} sB={sB} all={allp} nearest={nearest} Q={Q}", flush=True)
         check_sampled_variant(dA, dB, sA, sB, allp, nearest, Q, f"8192 ({sA},{sB}) all={allp} nearest={nearest} Q={Q}")
 
