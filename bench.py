@@ -247,6 +247,15 @@ def main():
                                        "what": "register-only v_mfma_i32_32x32x32_i8 loop (entries named 16x16x64: "
                                                "v_mfma_i32_16x16x64_i8); operand tile: consecutive instructions "
                                                "read different random operands, as in a GEMM"}
+    out["int8_mfma_with_data_movement_TOPs"] = {
+        "lds_reads_only": ozimmu.measure_int8_with_traffic(4, 0),
+        "lds_dma_only": ozimmu.measure_int8_with_traffic(0, 3),
+        "ratios_of_7_slices": ozimmu.measure_int8_with_traffic(4, 3),
+        "ratios_of_9_slices": ozimmu.measure_int8_with_traffic(3, 2),
+        "what": "the random-operand-tile 16x16x64 loop with, per wavefront, 4 (3) operand registers re-read from LDS "
+                "per 16 matrix instructions and 3 (2) LDS-DMA copies of 1 KiB from an L2-resident buffer per 32: the "
+                "data movement of the fused kernel for 7 (9) slices with no barrier, no wait on the data, no split "
+                "stage, no epilogue and no HBM traffic"}
     try:
         ia = torch.randint(-127, 128, (m, k), dtype=torch.int8, device="cuda")
         ib = torch.randint(-127, 128, (n, k), dtype=torch.int8, device="cuda").t()

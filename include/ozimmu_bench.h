@@ -51,6 +51,20 @@ int ozimmu_measure_int8_ceiling(int random_operands, int *sink, float *tops, voi
 int ozimmu_measure_int8_ceiling2(int random_operands, int shape, int *sink, float *tops, void *stream);
 
 /*
+ * Benchmark aid: the rate of the v_mfma_i32_16x16x64_i8 loop on pseudo-random operands WITH the data movement of the
+ * GEMM kernel going on beside it and nothing else of that kernel (no barriers, no waits on the moving data):
+ * `lds_reads` operand registers re-read from LDS per 16 matrix instructions (one iteration ahead of their use) and
+ * `dma_copies_per_32` LDS-DMA copies of 1 KiB per wavefront per 32 matrix instructions from an L2-resident window of
+ * `src` (device pointer, 16-byte aligned, at least 64 KiB, contents arbitrary).  Combinations built:
+ * (0, 0), (4, 0), (0, 3), (4, 3) -- the ratios of the kernel for 7 slices --, (3, 2) -- close to those for 9 slices --,
+ * (2, 3), (4, 2); others: OZIMMU_BAD_ARG.
+ * Writes TOP/s to *tops [host]; synchronises.  Under the board's power cap this is what is left for the matrix cores
+ * once the bytes move.
+ */
+int ozimmu_measure_int8_with_traffic(int lds_reads, int dma_copies_per_32, const void *src, size_t src_bytes,
+                                     int *sink, float *tops, void *stream);
+
+/*
  * Benchmark aid: a plain device-to-device copy kernel (`calibration_copy_kernel`) of `bytes` bytes (a multiple
  * of 16, both pointers 16-byte aligned), asynchronous on `stream`.  Its HBM traffic is known exactly -- `bytes`
  * read and `bytes` written -- so the FETCH_SIZE / WRITE_SIZE readings a profiler reports for it give the

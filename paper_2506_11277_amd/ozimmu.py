@@ -54,6 +54,8 @@ _SIGNATURES = {
     "ozimmu_profile_stop": (_c.c_int, [_c.POINTER(_c.c_int), _c.POINTER(_c.c_float)]),
     "ozimmu_calibration_copy": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_size_t, _c.c_void_p]),
     "ozimmu_measure_int8_ceiling2": (_c.c_int, [_c.c_int, _c.c_int, _c.c_void_p, _c.POINTER(_c.c_float), _c.c_void_p]),
+    "ozimmu_measure_int8_with_traffic": (_c.c_int, [_c.c_int, _c.c_int, _c.c_void_p, _c.c_size_t, _c.c_void_p,
+                                                    _c.POINTER(_c.c_float), _c.c_void_p]),
     "ozimmu_measure_int8_ceiling": (_c.c_int, [_c.c_int, _c.c_void_p, _c.POINTER(_c.c_float), _c.c_void_p]),
     "ozimmu_debug_small_tile_limit": (_c.c_int, [_c.c_longlong]),
     "ozimmu_debug_panel_bytes": (_c.c_int, [_c.c_longlong]),
@@ -358,6 +360,19 @@ def measure_int8_ceiling(random_operands, shape16=False):
                                             ctypes.byref(tops), _stream())
     if rc != OK:
         raise OzimmuError(rc, "measure_int8_ceiling")
+    return tops.value
+
+
+def measure_int8_with_traffic(lds_reads, dma_copies_per_32):
+    """Sustained rate (TOP/s) of the 16x16x64 loop on random operands with LDS re-reads and LDS-DMA copies from an
+    L2-resident buffer going on beside it (the GEMM kernel for 7 slices: 4 reads per 16, 3 copies per 32)."""
+    src = torch.randint(-127, 128, (4 << 20,), dtype=torch.int8, device="cuda")
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    tops = ctypes.c_float(0.0)
+    rc = lib().ozimmu_measure_int8_with_traffic(int(lds_reads), int(dma_copies_per_32), src.data_ptr(), src.numel(),
+                                                sink.data_ptr(), ctypes.byref(tops), _stream())
+    if rc != OK:
+        raise OzimmuError(rc, "measure_int8_with_traffic")
     return tops.value
 
 
