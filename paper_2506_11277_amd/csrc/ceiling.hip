@@ -160,6 +160,9 @@ extern "C" int ozimmu_measure_int8_with_traffic(int lds_reads, int dma_copies_pe
     else if (lds_reads == 2 && dma_copies_per_32 == 3) kern = oz::mfma_traffic_kernel<2, 3>;
     else if (lds_reads == 4 && dma_copies_per_32 == 2) kern = oz::mfma_traffic_kernel<4, 2>;
     else if (lds_reads == 3 && dma_copies_per_32 == 2) kern = oz::mfma_traffic_kernel<3, 2>;
+    else if (lds_reads == 5 && dma_copies_per_32 == 4) kern = oz::mfma_traffic_kernel<5, 4>;
+    else if (lds_reads == 6 && dma_copies_per_32 == 4) kern = oz::mfma_traffic_kernel<6, 4>;
+    else if (lds_reads == 5 && dma_copies_per_32 == 3) kern = oz::mfma_traffic_kernel<5, 3>;
     else return OZIMMU_BAD_ARG;
     hipStream_t st = (hipStream_t)stream;
     int cus = 0, dev = 0;
