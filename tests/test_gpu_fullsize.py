@@ -156,6 +156,32 @@ def test_large_ragged_shapes():
         check_sampled_variant(dA, dB, sA, sB, allp, nearest, Q, f"ragged ({sA},{sB}) all={allp}")
 
 
+def test_more_than_two_to_the_31_entries_of_C():
+    # 46400 x 46400 (2.15e9 entries, 17 GB): element offsets of C, and of the int64 totals of the block path,
+    # pass 2^31; short k keeps the products cheap.  The sampled rows and columns include the last ones.
+    m = n = 46400
+    k = 192
+    dA, dB = workloads.lognormal_device(m, n, k, 1.0, 2026)
+    for s in (2, 7, 12, 24):
+        print(f"2^31 entries s={s}", flush=True)
+        C = check_sampled(dA, dB, s, f"46400x46400x192 s={s}")
+        assert bool(torch.isfinite(C[:, -1]).all()) and bool(torch.isfinite(C[-1, :]).all())
+        del C
+        torch.cuda.empty_cache()
+
+
+def test_more_than_two_to_the_31_entries_of_A():
+    # 16421 x 140001 (2.3e9 entries, 18 GB; its slice planes up to 16 GB): element offsets of an operand and byte
+    # offsets of its planes pass 2^31 and 2^32, and k is long enough to need k-blocks; nothing a multiple of a tile
+    m, n, k = 16421, 200, 140001
+    dA, dB = workloads.lognormal_device(m, n, k, 1.0, 2027)
+    for s in (3, 7):
+        print(f"2^31 entries of A s={s}", flush=True)
+        C = check_sampled(dA, dB, s, f"16421x200x140001 s={s}")
+        del C
+        torch.cuda.empty_cache()
+
+
 def test_uneven_regions_of_the_two_dimensional_tile_order():
     # 63 tile rows of 128: the four row bands of the XCD grid hold 15, 16, 16, 16 tile rows, the launch is padded
     # to 8 x the largest region and the surplus work-groups must leave without touching anything
