@@ -239,23 +239,32 @@ def main():
     del ws2
 
     # context: what the matrix cores sustain with nothing else running, and the vendor's int8 GEMM
-    out["int8_mfma_sustained_TOPs"] = {"constant_operands": ozimmu.measure_int8_ceiling(False),
-                                       "random_operands": ozimmu.measure_int8_ceiling(True),
-                                       "random_operands_16x16x64": ozimmu.measure_int8_ceiling(True, shape16=True),
-                                       "random_operand_tile": ozimmu.measure_int8_ceiling(2),
-                                       "random_operand_tile_16x16x64": ozimmu.measure_int8_ceiling(2, shape16=True),
-                                       "what": "register-only v_mfma_i32_32x32x32_i8 loop (entries named 16x16x64: "
-                                               "v_mfma_i32_16x16x64_i8); operand tile: consecutive instructions "
-                                               "read different random operands, as in a GEMM"}
+    def settled(fn, seconds=0.3):
+        # median over repeated launches: one launch of 10 ms right after other work reads low while the power
+        # controller settles
+        vals, t_end = [], time.perf_counter() + seconds
+        while not vals or time.perf_counter() < t_end:
+            vals.append(fn())
+        return sorted(vals)[len(vals) // 2]
+
+    out["int8_mfma_sustained_TOPs"] = {
+        "constant_operands": settled(lambda: ozimmu.measure_int8_ceiling(False)),
+        "random_operands": settled(lambda: ozimmu.measure_int8_ceiling(True)),
+        "random_operands_16x16x64": settled(lambda: ozimmu.measure_int8_ceiling(True, shape16=True)),
+        "random_operand_tile": settled(lambda: ozimmu.measure_int8_ceiling(2)),
+        "random_operand_tile_16x16x64": settled(lambda: ozimmu.measure_int8_ceiling(2, shape16=True)),
+        "what": "register-only v_mfma_i32_32x32x32_i8 loop (entries named 16x16x64: v_mfma_i32_16x16x64_i8); operand "
+                "tile: consecutive instructions read different random operands, as in a GEMM; median of the launches "
+                "of 0.3 s"}
     out["int8_mfma_with_data_movement_TOPs"] = {
-        "lds_reads_only": ozimmu.measure_int8_with_traffic(4, 0),
-        "lds_dma_only": ozimmu.measure_int8_with_traffic(0, 3),
-        "ratios_of_7_slices": ozimmu.measure_int8_with_traffic(4, 3),
-        "ratios_of_9_slices": ozimmu.measure_int8_with_traffic(3, 2),
+        "lds_reads_only": settled(lambda: ozimmu.measure_int8_with_traffic(4, 0)),
+        "lds_dma_only": settled(lambda: ozimmu.measure_int8_with_traffic(0, 3)),
+        "ratios_of_7_slices": settled(lambda: ozimmu.measure_int8_with_traffic(4, 3)),
+        "ratios_of_9_slices": settled(lambda: ozimmu.measure_int8_with_traffic(3, 2)),
         "what": "the random-operand-tile 16x16x64 loop with, per wavefront, 4 (3) operand registers re-read from LDS "
                 "per 16 matrix instructions and 3 (2) LDS-DMA copies of 1 KiB from an L2-resident buffer per 32: the "
                 "data movement of the fused kernel for 7 (9) slices with no barrier, no wait on the data, no split "
-                "stage, no epilogue and no HBM traffic"}
+                "stage, no epilogue and no HBM traffic; median of the launches of 0.3 s"}
     try:
         ia = torch.randint(-127, 128, (m, k), dtype=torch.int8, device="cuda")
         ib = torch.randint(-127, 128, (n, k), dtype=torch.int8, device="cuda").t()
