@@ -57,7 +57,8 @@ int ozimmu_measure_int8_ceiling2(int random_operands, int shape, int *sink, floa
  * `dma_copies_per_32` LDS-DMA copies of 1 KiB per wavefront per 32 matrix instructions from an L2-resident window of
  * `src` (device pointer, 16-byte aligned, at least 64 KiB, contents arbitrary).  Combinations built:
  * (0, 0), (4, 0), (0, 3), (4, 3) -- the ratios of the kernel for 7 slices --, (3, 2) -- close to those for 9 slices --,
- * (5, 4), (6, 4), (5, 3) -- close to those for 2, 3, 4 slices --, (2, 3), (4, 2); others: OZIMMU_BAD_ARG.
+ * (5, 4), (6, 4), (5, 3) -- close to those for 2, 3, 4 slices --, (2, 3), (4, 2), and (0, -3), (4, -3): the 3 copies
+ * made through registers (vector load, LDS store) instead of LDS-DMA; others: OZIMMU_BAD_ARG.
  * Writes TOP/s to *tops [host]; synchronises.  Under the board's power cap this is what is left for the matrix cores
  * once the bytes move.
  */

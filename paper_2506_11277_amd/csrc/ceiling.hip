@@ -72,7 +72,7 @@ __global__ __launch_bounds__(512) void mfma_loop_kernel(int iters, int random_op
 // window of `src` into LDS per 16 matrix instructions (global_load_lds_dwordx4).  The GEMM kernel at 7 slices does
 // 4 reads and 1.5 copies per 16 instructions.  What this loop sustains under the board's power cap is what the
 // cap leaves once the bytes move, however well a kernel hides their latency.
-template <int LDSR, int DMA2>     // DMA2: copies per 32 matrix instructions
+template <int LDSR, int DMA2, bool VIAREG = false>     // DMA2: copies per 32 matrix instructions
 __global__ __launch_bounds__(512) void mfma_traffic_kernel(int iters, const int8_t *__restrict__ src, int windows,
                                                            int *sink)
 {
@@ -96,6 +96,7 @@ __global__ __launch_bounds__(512) void mfma_traffic_kernel(int iters, const int8
     for (int i = 0; i < 16; ++i) acc[i] = v4i{0, 0, 0, 0};
     const int8_t *win = src + (size_t)(blockIdx.x % windows) * 65536 + wave * 8192;
     unsigned cnt = 0;
+    v4i pend[4] = {a[0], a[1], a[2], a[3]};
     for (int it = 0; it < iters; it += 2) {
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
@@ -109,7 +110,13 @@ __global__ __launch_bounds__(512) void mfma_traffic_kernel(int iters, const int8
                 acc[i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[i & 3], b[i >> 2], acc[i], 0, 0, 0);
                 if (DMA2 > 0 && (h * 16 + i) * DMA2 / 32 != (h * 16 + i + 1) * DMA2 / 32) {
                     const unsigned o = (cnt++ & 7u) * 1024;
-                    lds_dma16(win + o, lane * 16, lds0 + 65536 + wave * 8192 + o);
+                    if (VIAREG) {
+                        // the same copy through registers: store what was loaded four copies ago, load the next
+                        const int slot = ((h * 16 + i) * DMA2 / 32) & 3;
+                        *(v4i *)(lds + 65536 + wave * 8192 + o + lane * 16) = pend[slot];
+                        pend[slot] = *(const v4i *)(win + o + lane * 16);
+                    } else
+                        lds_dma16(win + o, lane * 16, lds0 + 65536 + wave * 8192 + o);
                 }
             }
 #pragma unroll
@@ -163,6 +170,8 @@ extern "C" int ozimmu_measure_int8_with_traffic(int lds_reads, int dma_copies_pe
     else if (lds_reads == 5 && dma_copies_per_32 == 4) kern = oz::mfma_traffic_kernel<5, 4>;
     else if (lds_reads == 6 && dma_copies_per_32 == 4) kern = oz::mfma_traffic_kernel<6, 4>;
     else if (lds_reads == 5 && dma_copies_per_32 == 3) kern = oz::mfma_traffic_kernel<5, 3>;
+    else if (lds_reads == 4 && dma_copies_per_32 == -3) kern = oz::mfma_traffic_kernel<4, 3, true>;
+    else if (lds_reads == 0 && dma_copies_per_32 == -3) kern = oz::mfma_traffic_kernel<0, 3, true>;
     else return OZIMMU_BAD_ARG;
     hipStream_t st = (hipStream_t)stream;
     int cus = 0, dev = 0;
