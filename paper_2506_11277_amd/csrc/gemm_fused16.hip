@@ -112,15 +112,18 @@ struct Cfg16 {
     static constexpr bool EXP = S == OZ_EXP_S;
     // s = 2: tile 256 x 128 (4 x 2 wavefronts of 64 x 64: 64 accumulator registers per diagonal);
     // tile 128 x 128 (2 x 4 wavefronts of 64 x 32) while 32 * S accumulator registers are affordable and the
-    // stages fit (s = 5: two 80 KiB stages, all of LDS), else 128 x 64 (4 x 2 wavefronts of 32 x 32)
-    static constexpr bool HUGE = S == 2, WIDE = S >= 3 && S <= 5;
+    // stages fit (s = 5: two 80 KiB stages, all of LDS; s = 6: 192 accumulator registers, B and one slice of A
+    // double-buffered, five slices of A single-buffered: 152 KiB), else 128 x 64 (4 x 2 wavefronts of 32 x 32)
+    static constexpr bool HUGE = S == 2, WIDE = S >= 3 && S <= 6;
     static constexpr int WVM = EXP ? OZ_EXP_WVM : WIDE ? 2 : 4, WVN = EXP ? OZ_EXP_WVN : WIDE ? 4 : 2;
     static constexpr int WMF = EXP ? OZ_EXP_WMF : (WIDE || HUGE) ? 2 : 1, WNF = EXP ? OZ_EXP_WNF : HUGE ? 2 : 1;
     static constexpr int FA = WVM * WMF, FB = WVN * WNF;          // 32-row fragment rows of the tile
     // A slices [0, L0) are double-buffered with B; A slices [L0, S) single-buffered (L0 == S: no split)
     // (from a sweep at 8192^3: s = 7 runs 2820 / 2960 / 2905 / 2840 / 2795 TOP/s for L0 = 2 / 3 / 4 / 5 / 6, s = 8
-    // 2985 / 3150 / 3120 for L0 = 2 / 3 / 4 -- and 3230 against 3110 with split-k --, s = 9 2925 / 3100 for L0 = 1 / 2)
-    static constexpr int L0 = EXP && OZ_EXP_L0 >= 0 ? OZ_EXP_L0 : S <= 6 ? S : S <= 8 ? 3 : 2;
+    // 2985 / 3150 / 3120 for L0 = 2 / 3 / 4 -- and 3230 against 3110 with split-k --, s = 9 2925 / 3100 for L0 = 1 / 2;
+    // s = 6 on the 128 x 128 tile: L0 = 1 with two slices of B held 3055-3065, L0 = 2 spills, against 2905 for the
+    // 128 x 64 tile without split, same box)
+    static constexpr int L0 = EXP && OZ_EXP_L0 >= 0 ? OZ_EXP_L0 : S <= 5 ? S : S == 6 ? 1 : S <= 8 ? 3 : 2;
     static constexpr int P1 = (FA * L0 + FB * S) * 2 * kFragBytes;    // double-buffered part of a 64-k stage
     static constexpr int P2 = FA * (S - L0) * 2 * kFragBytes;         // single-buffered part
     // ring depth of the double-buffered part.  Few slices make a stage short (s = 2: 48 matrix instructions per
@@ -139,7 +142,7 @@ struct Cfg16 {
     // D = 4 / 6 / 8 / 10 / 12 / 16 (reads one slice ahead, the earlier scheme: 3215); s = 4 is indifferent up to 24.
     static constexpr int D = EXP && OZ_EXP_D >= 0 ? OZ_EXP_D : S == 4 ? 24 : 8, DO = 4;
     // slices of B held in registers for the whole stage (the others are read when needed)
-    static constexpr int HP = EXP && OZ_EXP_HP >= 0 ? OZ_EXP_HP : S >= 9 ? 7 : S;
+    static constexpr int HP = EXP && OZ_EXP_HP >= 0 ? OZ_EXP_HP : S >= 9 ? 7 : S == 6 ? 2 : S;
 };
 
 template <int S, int MODE>
@@ -642,7 +645,7 @@ hipError_t launch_fused16_windows(int s, int m, int n, int kp, const int8_t *pA,
     if (nwin > kMaxWindows16) return hipErrorInvalidValue;
     switch (s) {
 #define OZ_CASE(S_) case S_: return launch16_windows<S_>(m, n, kp, pA, pB, totals, wins, nwin, st);
-        OZ_CASE(6) OZ_CASE(7) OZ_CASE(8) OZ_CASE(9)
+        OZ_CASE(7) OZ_CASE(8) OZ_CASE(9)      // groups of 8 or 9 slices and their reversed sets of 7 or 8
 #undef OZ_CASE
     }
     return hipErrorInvalidValue;
@@ -660,7 +663,7 @@ hipError_t launch_finish_blocks16(const long long *totals, const int32_t *eA, co
 void fused16_tile(int s, int &tm, int &tn)
 {
     tm = s == 2 ? 256 : 128;
-    tn = s <= 5 ? 128 : 64;
+    tn = s <= 6 ? 128 : 64;
     if (s == OZ_EXP_S) {
         tm = 32 * OZ_EXP_WVM * OZ_EXP_WMF;
         tn = 32 * OZ_EXP_WVN * OZ_EXP_WNF;
