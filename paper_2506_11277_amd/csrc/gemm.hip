@@ -714,11 +714,11 @@ hipError_t dispatch_fused(int s, int m, int n, int kp, const int8_t *pA, const i
                           hipStream_t st)
 {
     switch (s) {
-    // (equal counts 2 ... 9 run in the 16x16x64 kernel -- 2, 3 and 6 except in split-k mode -- and are not
+    // (equal counts 2 ... 9 run in the 16x16x64 kernel -- 2 and 3 except in split-k mode -- and are not
     // instantiated here)
 #define OZ_CASE(S_) \
     case S_: \
-        if constexpr (PSET != 0 || S_ < 2 || S_ > 9 || ((S_ <= 3 || S_ == 6) && MODE == kBlocked)) \
+        if constexpr (PSET != 0 || S_ < 2 || S_ > 9 || (S_ <= 3 && MODE == kBlocked)) \
             return launch_fused_s<S_, MODE, PSET>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, Q, sm, st); \
         break;
         OZ_CASE(2) OZ_CASE(3) OZ_CASE(4) OZ_CASE(5) OZ_CASE(6) OZ_CASE(7) OZ_CASE(8) OZ_CASE(9) OZ_CASE(10) OZ_CASE(11) OZ_CASE(12) OZ_CASE(13) OZ_CASE(14) OZ_CASE(15) OZ_CASE(16) OZ_CASE(17) OZ_CASE(18)

@@ -632,11 +632,12 @@ hipError_t dispatch16(int s, int m, int n, int kp, const int8_t *pA, const int8_
 }  // namespace
 
 // Slice counts for which this kernel is the faster one at 8192^3 (s = 2: +10 % and s = 3: +6 % with the ring of
-// three stages, s = 4: +10 %, s = 5: +7.5 % with the wide tile, s = 6 ... 9 with the pipelined schedule: +10 %, +17 %,
-// +17 %, +17 % over the 32x32x32 kernel).  With split-k (long contractions) the 32x32x32 kernel keeps s = 2, 3 (not
-// measured there) and stays ahead at s = 6; beyond 9 a 64-deep stage of a 128 x 64 tile does not fit LDS.  Only the
+// three stages, s = 4: +10 %, s = 5: +7.5 % with the wide tile, s = 6: +16 % with the wide tile and the split stage,
+// s = 7 ... 9 with the pipelined schedule: +17 % over the 32x32x32 kernel).  With split-k (long contractions) the
+// 32x32x32 kernel keeps s = 2, 3 (not measured there); s = 6 is 9-11 % faster here with split-k as well (2048 x 2048
+// x 262144: 3465 against 3170 TOP/s).  Beyond 9 a 64-deep stage of a 128 x 64 tile does not fit LDS.  Only the
 // preferred ones are instantiated.
-bool fused16_preferred(int s, bool split_k) { return s >= 2 && s <= 9 && !((s <= 3 || s == 6) && split_k); }
+bool fused16_preferred(int s, bool split_k) { return s >= 2 && s <= 9 && !(s <= 3 && split_k); }
 
 hipError_t launch_fused16_windows(int s, int m, int n, int kp, const int8_t *pA, const int8_t *pB, long long *totals,
                                   const WindowList16 &wins, int nwin, hipStream_t st)

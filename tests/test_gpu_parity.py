@@ -249,7 +249,7 @@ def test_k_blocked_accumulation_beyond_the_int32_range():
 
 @pytest.mark.parametrize("s", [4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 16, 17, 18, 19, 20])
 def test_k_blocked_on_every_fused_kernel(s):
-    # the fused kernels (16x16x64 for s = 4, 5, 7, 8, 9 -- 6 only without split-k --; 32x32x32 otherwise, with four 512-register wavefronts beyond
+    # the fused kernels (16x16x64 for s = 4 ... 9; 32x32x32 otherwise, with four 512-register wavefronts beyond
     # s = 12) in split-k mode, several tiles and k-blocks
     m, n = 130, 70
     k = 3 * (133144 // s) + 200
@@ -596,7 +596,7 @@ def test_seeded_random_configurations(tile_choice):
         assert_c_matches(got, oracle.dgemm3(A, B, sA, sB, full=allp, nearest=nearest, Q=Q), f"case {case}")
 
 
-@pytest.mark.parametrize("sA,sB,allp", [(5, 5, False), (7, 7, False), (8, 8, False), (9, 9, False), (12, 12, False),
+@pytest.mark.parametrize("sA,sB,allp", [(4, 4, False), (5, 5, False), (6, 6, False), (7, 7, False), (8, 8, False), (9, 9, False), (12, 12, False),
                                         (16, 16, False), (18, 18, False), (20, 20, False), (5, 11, False),
                                         (13, 4, False), (6, 6, True)])
 def test_exactly_two_k_blocks(sA, sB, allp):
@@ -632,6 +632,7 @@ def test_which_kernel_takes_which_product_set():
     A, B = workloads.uniform(70, 60, 50, 5)
     dA, dB = dev(A), dev(B)
     expect = [((2, 2, False), "gemm_fused16_kernel<2> tile 256x128 ring of 3"),
+              ((6, 6, False), "gemm_fused16_kernel<6> tile 128x128"),
               ((7, 7, False), "gemm_fused16_kernel<7> tile 128x64"),
               ((12, 12, False), "gemm_fused_kernel<12> equal counts tile 128x64, 8 wavefronts"),
               ((16, 16, False), "gemm_fused_kernel<16> equal counts tile 64x64, 4 wavefronts"),
