@@ -85,6 +85,9 @@ int ozimmu_calibration_copy(void *dst, const void *src, size_t bytes, void *stre
  *   the tile tabulated for the slice count when the latter would give fewer than `tiles` work-groups
  *   (default 256, one per compute unit; 0: never).  Process-wide host state; lets the tests run both
  *   kernels on the same small inputs.  Returns OZIMMU_BAD_ARG for a negative value.
+ * ozimmu_debug_tile_choice: with 4 slices ozimmu_dgemm picks between the tabulated 128 x 128 tile and a 192 x 128
+ *   tile by the number of rounds of the compute units each needs; 1 forces the tabulated tile, 2 the alternative,
+ *   0 (default) restores the choice.  Process-wide host state.  Returns OZIMMU_BAD_ARG for other values.
  * ozimmu_debug_panel_bytes: when k has to be cut into blocks, C is computed one column panel after the other so
  *   that the int64 totals of a panel take about `bytes` (default 1 GiB; <= 0: all of C at once).  Changes what
  *   ozimmu_workspace_bytes* return: set it before sizing the workspace.  Process-wide host state.
@@ -94,6 +97,7 @@ int ozimmu_calibration_copy(void *dst, const void *src, size_t bytes, void *stre
  */
 int ozimmu_debug_diagonals(int m, int n, int k, int s, const void *workspace, int32_t *D, void *stream);
 int ozimmu_debug_small_tile_limit(long long tiles);
+int ozimmu_debug_tile_choice(int choice);
 int ozimmu_debug_panel_bytes(long long bytes);
 int ozimmu_debug_slice_product(int m, int n, int k, int s, const void *workspace, int l, int h,
                                int k0, int k1, int32_t *P, void *stream);

@@ -427,6 +427,13 @@ int ozimmu_debug_small_tile_limit(long long tiles)
     return OZIMMU_OK;
 }
 
+int ozimmu_debug_tile_choice(int choice)
+{
+    if (choice < 0 || choice > 2) return OZIMMU_BAD_ARG;
+    fused16_set_tile_choice(choice);
+    return OZIMMU_OK;
+}
+
 int ozimmu_debug_diagonals(int m, int n, int k, int s, const void *workspace, int32_t *D, void *stream)
 {
     if (m <= 0 || n <= 0 || k < 0 || !workspace || !D || !fused_single_block(s, s, k)) return OZIMMU_BAD_ARG;

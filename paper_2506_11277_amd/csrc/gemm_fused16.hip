@@ -107,16 +107,21 @@ struct Sched16 {
 #define OZ_EXP_NSTG -1
 #endif
 
-template <int S>
+template <int S, int ALT = 0>
 struct Cfg16 {
-    static constexpr bool EXP = S == OZ_EXP_S;
-    // s = 2: tile 256 x 128 (4 x 2 wavefronts of 64 x 64: 64 accumulator registers per diagonal);
+    static constexpr bool EXP = S == OZ_EXP_S && ALT == 0;
+    // s = 2, 3: tile 256 x 128 (4 x 2 wavefronts of 64 x 64: 64 accumulator registers per diagonal; s = 3: 192
+    // accumulator registers, so one slice of B held and operands read one instruction ahead, or the loop spills);
     // tile 128 x 128 (2 x 4 wavefronts of 64 x 32) while 32 * S accumulator registers are affordable and the
     // stages fit (s = 5: two 80 KiB stages, all of LDS; s = 6: 192 accumulator registers, B and one slice of A
-    // double-buffered, five slices of A single-buffered: 152 KiB), else 128 x 64 (4 x 2 wavefronts of 32 x 32)
-    static constexpr bool HUGE = S == 2, WIDE = S >= 3 && S <= 6;
+    // double-buffered, five slices of A single-buffered: 152 KiB), else 128 x 64 (4 x 2 wavefronts of 32 x 32).
+    // ALT = 1 (s = 4 only): tile 192 x 128 (2 x 4 wavefronts of 96 x 32, 192 accumulator registers, two 80 KiB
+    // stages): 17 % fewer L2 -> LDS bytes and 11 % fewer LDS reads per product than 128 x 128; the launcher takes
+    // it where the tile grid of the problem does not lose more in partial rounds than that gains.
+    static_assert(ALT == 0 || (ALT == 1 && S == 4), "an alternative tile exists for 4 slices only");
+    static constexpr bool HUGE = S == 2 || S == 3, WIDE = (S >= 4 && S <= 6);
     static constexpr int WVM = EXP ? OZ_EXP_WVM : WIDE ? 2 : 4, WVN = EXP ? OZ_EXP_WVN : WIDE ? 4 : 2;
-    static constexpr int WMF = EXP ? OZ_EXP_WMF : (WIDE || HUGE) ? 2 : 1, WNF = EXP ? OZ_EXP_WNF : HUGE ? 2 : 1;
+    static constexpr int WMF = EXP ? OZ_EXP_WMF : ALT == 1 ? 3 : (WIDE || HUGE) ? 2 : 1, WNF = EXP ? OZ_EXP_WNF : HUGE ? 2 : 1;
     static constexpr int FA = WVM * WMF, FB = WVN * WNF;          // 32-row fragment rows of the tile
     // A slices [0, L0) are double-buffered with B; A slices [L0, S) single-buffered (L0 == S: no split)
     // (from a sweep at 8192^3: s = 7 runs 2820 / 2960 / 2905 / 2840 / 2795 TOP/s for L0 = 2 / 3 / 4 / 5 / 6, s = 8
@@ -133,26 +138,29 @@ struct Cfg16 {
     // Measured at 8192^3: s = 2 (tile 256 x 128) 2150 -> 2370 TOP/s, s = 3 (tile 128 x 128) 2500 -> 2640 against the
     // 32x32x32 kernel with its ring of three; with a ring of two the same tiles gain nothing (matrix pipe busy half
     // of the cycles).  From 4 slices on three stages of a 128 x 128 tile do not fit.
-    static constexpr int NSTG = EXP && OZ_EXP_NSTG >= 0 ? OZ_EXP_NSTG : S <= 3 ? 3 : 2;
+    // s = 3 on the 256 x 128 tile has stages as long as those of s = 7 (96 matrix instructions per wavefront) and
+    // runs with two: 2800 against 2670 TOP/s for the 128 x 128 tile with its ring of three, same box.
+    static constexpr int NSTG = EXP && OZ_EXP_NSTG >= 0 ? OZ_EXP_NSTG : S == 2 ? 3 : 2;
     static_assert(NSTG == 2 || (NSTG == 3 && L0 == S), "a ring of three only without the split stage");
     static constexpr int LDS = NSTG * P1 + P2;
     static_assert(LDS <= kLdsBytes, "stages do not fit LDS");
     // operands are read D matrix instructions ahead of their first use (DO: the B slices that are not held in
     // registers, ahead of each use).  Measured at s = 7, 8192^3: 3250 / 3200 / 3310 / 3140 / 3240 / 3205 TOP/s for
     // D = 4 / 6 / 8 / 10 / 12 / 16 (reads one slice ahead, the earlier scheme: 3215); s = 4 is indifferent up to 24.
-    static constexpr int D = EXP && OZ_EXP_D >= 0 ? OZ_EXP_D : S == 4 ? 24 : 8, DO = 4;
+    // (s = 3 on 256 x 128 and s = 4 on 192 x 128 spill with any longer read-ahead: 2190 against 2800 TOP/s at s = 3)
+    static constexpr int D = EXP && OZ_EXP_D >= 0 ? OZ_EXP_D : (S == 3 || ALT == 1) ? 1 : S == 4 ? 24 : 8, DO = 4;
     // slices of B held in registers for the whole stage (the others are read when needed)
-    static constexpr int HP = EXP && OZ_EXP_HP >= 0 ? OZ_EXP_HP : S >= 9 ? 7 : S == 6 ? 2 : S;
+    static constexpr int HP = EXP && OZ_EXP_HP >= 0 ? OZ_EXP_HP : S >= 9 ? 7 : (S == 6 || ALT == 1) ? 2 : S == 3 ? 1 : S;
 };
 
-template <int S, int MODE>
-__global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void gemm_fused16_kernel(
+template <int S, int MODE, int ALT = 0>
+__global__ __launch_bounds__((64 * Cfg16<S, ALT>::WVM * Cfg16<S, ALT>::WVN)) void gemm_fused16_kernel(
     const int8_t *__restrict__ pA, const int8_t *__restrict__ pB, const int32_t *__restrict__ eA,
     const int32_t *__restrict__ eB, double *__restrict__ C, int ldc, int m, int n, int KB, int tiles_m, int tiles_n,
     int32_t *__restrict__ dump, long long *__restrict__ totals, int stages_per_block, int Q, long long slot_stride,
     WindowList16 wins)
 {
-    using G = Cfg16<S>;
+    using G = Cfg16<S, ALT>;
     const Window16 win = wins.w[blockIdx.z];
     constexpr int WVM = G::WVM, WVN = G::WVN, WMF = G::WMF, WNF = G::WNF, FA = G::FA, FB = G::FB, L0 = G::L0;
     constexpr int NW = WVM * WVN;
@@ -558,13 +566,14 @@ __global__ void zero16_i64_kernel(long long *p, size_t n)
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0;
 }
 
-template <int S, int MODE>
+template <int S, int MODE, int ALT = 0>
 hipError_t launch16_s(int m, int n, int kp, const int8_t *pA, const int8_t *pB, const int32_t *eA, const int32_t *eB,
                       double *C, int ldc, int32_t *dump, long long *totals, int Q, hipStream_t st)
 {
-    using G = Cfg16<S>;
+    using G = Cfg16<S, ALT>;
+    static_assert(ALT == 0 || MODE != kBlocked, "split-k keeps the tabulated tile: the totals are laid out for it");
     constexpr int TM = 32 * G::FA, TN = 32 * G::FB, THREADS = 64 * G::WVM * G::WVN;
-    auto kern = gemm_fused16_kernel<S, MODE>;
+    auto kern = gemm_fused16_kernel<S, MODE, ALT>;
     static std::atomic<unsigned long long> configured{0};
     if (hipError_t e = allow_dynamic_lds((const void *)kern, G::LDS, configured); e != hipSuccess) return e;
     const int tiles_m = (m + TM - 1) / TM, tiles_n = (n + TN - 1) / TN;
@@ -616,10 +625,29 @@ hipError_t launch16_windows(int m, int n, int kp, const int8_t *pA, const int8_t
     return hipGetLastError();
 }
 
+// 4 slices: the 192 x 128 tile runs its products about 6.5 % faster than the 128 x 128 tile (8192^3: +3.3 % although
+// its 43 x 64 tiles make 10.75 rounds of the 256 CUs, 3 % more padded work than the 16 whole rounds of 128 x 128).  It
+// is taken where (rounds of the CUs) x (tile area) / 1.065 comes out below that of the tabulated tile.
+std::atomic<int> g_tile_choice{0};      // test knob: 0 as described, 1 always the tabulated tile, 2 always the alternative
+
+bool alt_tile_pays(int m, int n)
+{
+    const int choice = g_tile_choice.load();
+    if (choice) return choice == 2;
+    if (OZ_EXP_S == 4) return false;
+    int cus = 0, dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+        cus = 256;
+    auto rounds = [&](int tm, int tn) { return ((long long)((m + tm - 1) / tm) * ((n + tn - 1) / tn) + cus - 1) / cus; };
+    return (double)rounds(192, 128) * 192 * 128 / 1.065 < (double)rounds(128, 128) * 128 * 128;
+}
+
 template <int MODE>
 hipError_t dispatch16(int s, int m, int n, int kp, const int8_t *pA, const int8_t *pB, const int32_t *eA,
                       const int32_t *eB, double *C, int ldc, int32_t *dump, long long *totals, int Q, hipStream_t st)
 {
+    if constexpr (MODE != kBlocked)
+        if (s == 4 && alt_tile_pays(m, n)) return launch16_s<4, MODE, 1>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, Q, st);
     switch (s) {
 #define OZ_CASE(S_) \
     case S_: return launch16_s<S_, MODE>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, Q, st);
@@ -661,9 +689,11 @@ hipError_t launch_finish_blocks16(const long long *totals, const int32_t *eA, co
     return hipGetLastError();
 }
 
+void fused16_set_tile_choice(int choice) { g_tile_choice.store(choice < 0 || choice > 2 ? 0 : choice); }
+
 void fused16_tile(int s, int &tm, int &tn)
 {
-    tm = s == 2 ? 256 : 128;
+    tm = s <= 3 ? 256 : 128;
     tn = s <= 6 ? 128 : 64;
     if (s == OZ_EXP_S) {
         tm = 32 * OZ_EXP_WVM * OZ_EXP_WMF;

@@ -193,6 +193,7 @@ hipError_t launch_gemm_fused(int m, int n, int kp, int sA, int sB, bool all_prod
 // the same fused computation on v_mfma_i32_16x16x64_i8, for the slice counts where it is faster (gemm_fused16.hip)
 bool fused16_preferred(int s, bool split_k);
 void fused16_tile(int s, int &tm, int &tn);
+void fused16_set_tile_choice(int choice);   // test knob: 0 automatic, 1 tabulated tile, 2 alternative tile (4 slices)
 hipError_t launch_gemm_fused16(int m, int n, int kp, int s, const int8_t *pA, const int8_t *pB,
                                const int32_t *eA, const int32_t *eB, double *C, int ldc,
                                int32_t *dump, long long *totals, int Q, hipStream_t st);

@@ -58,6 +58,7 @@ _SIGNATURES = {
                                                     _c.POINTER(_c.c_float), _c.c_void_p]),
     "ozimmu_measure_int8_ceiling": (_c.c_int, [_c.c_int, _c.c_void_p, _c.POINTER(_c.c_float), _c.c_void_p]),
     "ozimmu_debug_small_tile_limit": (_c.c_int, [_c.c_longlong]),
+    "ozimmu_debug_tile_choice": (_c.c_int, [_c.c_int]),
     "ozimmu_debug_panel_bytes": (_c.c_int, [_c.c_longlong]),
     "ozimmu_debug_diagonals": (_c.c_int, [_c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_void_p, _c.c_void_p,
                                           _c.c_void_p]),
@@ -381,6 +382,13 @@ def debug_small_tile_limit(tiles):
     rc = lib().ozimmu_debug_small_tile_limit(int(tiles))
     if rc != OK:
         raise OzimmuError(rc, "debug_small_tile_limit")
+
+
+def debug_tile_choice(choice):
+    """Test hook: 4 slices on the tabulated 128 x 128 tile (1), on the 192 x 128 tile (2), or chosen by size (0)."""
+    rc = lib().ozimmu_debug_tile_choice(int(choice))
+    if rc != OK:
+        raise OzimmuError(rc, "debug_tile_choice")
 
 
 def debug_panel_bytes(nbytes):

@@ -178,6 +178,36 @@ def test_int32_diagonal_sums_of_fused_kernel_bit_exact(m, n, k, s):
         assert np.array_equal(D[d - 2].T.astype(np.int64), want), d
 
 
+@pytest.fixture
+def alternative_tile():
+    ozimmu.debug_tile_choice(2)
+    yield
+    ozimmu.debug_tile_choice(0)
+
+
+@pytest.mark.parametrize("kind", ["uniform", "lognormal", "pow2", "special"])
+@pytest.mark.parametrize("m,n,k", SHAPES + [(192, 128, 64), (193, 129, 65), (400, 300, 200), (577, 257, 130), (96, 500, 1000)])
+def test_four_slices_on_the_192_by_128_tile(kind, m, n, k, alternative_tile):
+    # at these sizes the launcher would take the tabulated 128 x 128 tile; the knob forces the alternative, whose
+    # wavefronts hold three fragment rows (tiles that end inside the first, second and third of them, one and
+    # several tiles each way)
+    A, B = inputs(kind, m, n, k, 37)
+    ws = ozimmu.alloc_workspace(m, n, k, 4)
+    C = ozimmu.dgemm(dev(A), dev(B), 4, workspace=ws, check_finite=True)
+    assert ozimmu.last_gemm_kernel().startswith("gemm_fused16_kernel<4> tile 192x128"), ozimmu.last_gemm_kernel()
+    assert_c_matches(host(C), oracle.dgemm(A, B, 4), f"192x128 tile {kind} {m}x{n}x{k}")
+    pa, _ = oracle.split("A", A, 4)
+    pb, _ = oracle.split("B", B, 4)
+    D = host(ozimmu.debug_diagonals(m, n, k, 4, ws))
+    for d in range(2, 6):
+        want = sum(oracle.slice_product(pa[l - 1], pb[d - l - 1]) for l in range(1, d) if l <= 4 and d - l <= 4)
+        assert np.array_equal(D[d - 2].T.astype(np.int64), want), d
+    # nearest slices and levels of two diagonals run the same kernel
+    C3 = ozimmu.dgemm3(dev(A), dev(B), 4, 4, False, ozimmu.SPLIT_NEAREST, 2)
+    assert ozimmu.last_gemm_kernel().startswith("gemm_fused16_kernel<4> tile 192x128")
+    assert_c_matches(host(C3), oracle.dgemm3(A, B, 4, 4, nearest=True, Q=2), "192x128 tile, nearest, Q = 2")
+
+
 def test_extreme_slices_do_not_overflow_int32_in_fused_kernel():
     # 1 - 2^-53 has 53 one-bits: slices 1..7 all equal 127, the largest magnitude there is.  With
     # s = 7 and k = 19008 (s * k just under the fused kernel's limit of 133144) the last diagonal
@@ -632,6 +662,8 @@ def test_which_kernel_takes_which_product_set():
     A, B = workloads.uniform(70, 60, 50, 5)
     dA, dB = dev(A), dev(B)
     expect = [((2, 2, False), "gemm_fused16_kernel<2> tile 256x128 ring of 3"),
+              ((3, 3, False), "gemm_fused16_kernel<3> tile 256x128"),
+              ((4, 4, False), "gemm_fused16_kernel<4> tile 128x128"),       # (192 x 128 where the tile grid favours it)
               ((6, 6, False), "gemm_fused16_kernel<6> tile 128x128"),
               ((7, 7, False), "gemm_fused16_kernel<7> tile 128x64"),
               ((12, 12, False), "gemm_fused_kernel<12> equal counts tile 128x64, 8 wavefronts"),
