@@ -82,9 +82,10 @@ int ozimmu_calibration_copy(void *dst, const void *src, size_t bytes, void *stre
  *   d = 2..s+1, produced by the main loop of the fused GEMM kernel (needs
  *   s * k * 127^2 < 2^31 and s <= the fused kernel's limit, else OZIMMU_BAD_ARG).
  * ozimmu_debug_small_tile_limit: ozimmu_dgemm with equal slice counts up to 12 uses a 64 x 64 tile instead of
- *   the tile tabulated for the slice count when the latter would give fewer than `tiles` work-groups
- *   (default 256, one per compute unit; 0: never).  Process-wide host state; lets the tests run both
- *   kernels on the same small inputs.  Returns OZIMMU_BAD_ARG for a negative value.
+ *   the tile tabulated for the slice count where that finishes sooner by (rounds of the compute units) x (tile
+ *   area) / (relative speed of the kernel); that rule is the default (-1).  0: never the small tile; n > 0: the
+ *   small tile whenever the tabulated one would give fewer than n work-groups.  Process-wide host state; lets
+ *   the tests run both kernels on the same small inputs.  Returns OZIMMU_BAD_ARG for a value below -1.
  * ozimmu_debug_tile_choice: with 4 slices ozimmu_dgemm picks between the tabulated 128 x 128 tile and a 192 x 128
  *   tile by the number of rounds of the compute units each needs; 1 forces the tabulated tile, 2 the alternative,
  *   0 (default) restores the choice.  Process-wide host state.  Returns OZIMMU_BAD_ARG for other values.

@@ -422,7 +422,7 @@ int ozimmu_debug_panel_bytes(long long bytes)
 
 int ozimmu_debug_small_tile_limit(long long tiles)
 {
-    if (tiles < 0) return OZIMMU_BAD_ARG;
+    if (tiles < -1) return OZIMMU_BAD_ARG;
     fused_set_small_tile_limit(tiles);
     return OZIMMU_OK;
 }

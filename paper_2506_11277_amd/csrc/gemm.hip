@@ -648,7 +648,7 @@ struct FusedCfgSmall {
     static constexpr int WVM = 2, WVN = 2, WMF = 1, WNF = 1, FR = 4, KB32 = 1, NSTAGE = 2;
 };
 constexpr int kSmallMaxS = 12;
-std::atomic<long long> g_small_below_tiles{256};          // fewer work-groups than CUs of an MI355X (test hook: 0 switches it off)
+std::atomic<long long> g_small_below_tiles{-1};           // test hook: -1 the cost rule below, 0 never, n: below n tiles
 
 constexpr int kFusedMaxUneq = 18; // most accumulator sets for different slice counts and for all products
 constexpr int kFusedMaxS = 20;   // 16 accumulator registers per diagonal: 12 fit 256 registers, 20 fit 512 (BIG);
@@ -1090,14 +1090,28 @@ static hipError_t launch_gemm_fused_once(int m, int n, int kp, int sA, int sB, b
     if (sA == sB) {
         const int s = sA;
         if (!dump && !totals && s <= kSmallMaxS) {
-            // too few tiles of the tabulated shape to occupy the chip: the 64 x 64 tile
+            // The 64 x 64 tile where it finishes sooner.  A launch takes (rounds of the compute units) x (time of a
+            // tile), a partly filled round nearly as long as a full one; the small tile runs its products at the fraction
+            // kSmallSpeed of the tabulated tile's rate (8192^3, both kernels measured per slice count).  So few tiles
+            // of the tabulated shape lose to many small ones (2048^2, s = 2: 128 tiles of 256 x 128 against 4 rounds of
+            // 64 x 64: the small tile is 18 % faster), but not always (2560^2: 200 large tiles are 57 % faster than 7
+            // rounds of small ones, which a plain "fewer tiles than compute units" rule gets wrong).
             int tm = 128, tn = 128;
             if (fused16_preferred(s, false)) fused16_tile(s, tm, tn);
             else if (s <= 4 || s == 6) { tm = 128; tn = 128; }
             else { tm = 128; tn = 64; }
             const long long tiles = (long long)((m + tm - 1) / tm) * ((n + tn - 1) / tn);
             const long long small_tiles = (long long)((m + 63) / 64) * ((n + 63) / 64);
-            if (tiles < g_small_below_tiles.load() && small_tiles > tiles)
+            const long long limit = g_small_below_tiles.load();
+            bool small;
+            if (limit < 0) {
+                static constexpr double kSmallSpeed[kSmallMaxS + 1] = {0, 0.7, 0.63, 0.69, 0.74, 0.70, 0.76, 0.87, 0.72, 0.80, 0.93, 0.9, 0.9};
+                const int cus = device_cus();
+                const double tabulated = fused16_preferred(s, false) ? fused16_launch_cost(s, m, n, cus) : launch_cost(m, n, tm, tn, cus);
+                small = small_tiles > tiles && launch_cost(m, n, 64, 64, cus) / kSmallSpeed[s] < tabulated;
+            } else
+                small = tiles < limit && small_tiles > tiles;     // test knob: a plain threshold on the tile count
+            if (small)
                 return dispatch_fused_small(s, m, n, kp, pA, pB, eA, eB, C, ldc, Q, st);
         }
         // the 16x16x64 kernel where it is the faster one

@@ -630,16 +630,15 @@ hipError_t launch16_windows(int m, int n, int kp, const int8_t *pA, const int8_t
 // is taken where (rounds of the CUs) x (tile area) / 1.065 comes out below that of the tabulated tile.
 std::atomic<int> g_tile_choice{0};      // test knob: 0 as described, 1 always the tabulated tile, 2 always the alternative
 
+constexpr double kAltSpeed = 1.065;
+
 bool alt_tile_pays(int m, int n)
 {
     const int choice = g_tile_choice.load();
     if (choice) return choice == 2;
     if (OZ_EXP_S == 4) return false;
-    int cus = 0, dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
-        cus = 256;
-    auto rounds = [&](int tm, int tn) { return ((long long)((m + tm - 1) / tm) * ((n + tn - 1) / tn) + cus - 1) / cus; };
-    return (double)rounds(192, 128) * 192 * 128 / 1.065 < (double)rounds(128, 128) * 128 * 128;
+    const int cus = device_cus();
+    return launch_cost(m, n, 192, 128, cus) / kAltSpeed < launch_cost(m, n, 128, 128, cus);
 }
 
 template <int MODE>
@@ -687,6 +686,14 @@ hipError_t launch_finish_blocks16(const long long *totals, const int32_t *eA, co
     const int tiles_m = (m + 127) / 128, tiles_n = (n + 63) / 64;
     finish_blocks16_kernel<<<tiles_m * tiles_n, 512, 0, st>>>(totals, eA, eB, C, ldc, m, n, tiles_n, Q, diagonals, na_tot);
     return hipGetLastError();
+}
+
+double fused16_launch_cost(int s, int m, int n, int cus)
+{
+    if (s == 4 && alt_tile_pays(m, n)) return launch_cost(m, n, 192, 128, cus) / kAltSpeed;
+    int tm, tn;
+    fused16_tile(s, tm, tn);
+    return launch_cost(m, n, tm, tn, cus);
 }
 
 void fused16_set_tile_choice(int choice) { g_tile_choice.store(choice < 0 || choice > 2 ? 0 : choice); }

@@ -193,6 +193,24 @@ hipError_t launch_gemm_fused(int m, int n, int kp, int sA, int sB, bool all_prod
 // the same fused computation on v_mfma_i32_16x16x64_i8, for the slice counts where it is faster (gemm_fused16.hip)
 bool fused16_preferred(int s, bool split_k);
 void fused16_tile(int s, int &tm, int &tn);
+// (rounds of the compute units) x (tile area) of a launch with that tile, a measure of its duration; for the
+// 16x16x64 kernel with the tile it would choose (4 slices: the cheaper of its two, the alternative's speed counted in)
+// (a partly filled last round counts 0.8 of a full one plus 0.2 of its share: the fit over 99 measured pairs of
+// launches, sizes 512 ... 6000 and 2 ... 12 slices, picks the faster kernel in all but one, which it misses by 4 %)
+inline double launch_cost(int m, int n, int tm, int tn, int cus)
+{
+    const long long tiles = (long long)((m + tm - 1) / tm) * ((n + tn - 1) / tn);
+    const double exact = (double)tiles / cus, whole = (double)((tiles + cus - 1) / cus);
+    return (0.8 * whole + 0.2 * exact) * tm * tn;
+}
+double fused16_launch_cost(int s, int m, int n, int cus);
+inline int device_cus()
+{
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+        return 256;
+    return cus;
+}
 void fused16_set_tile_choice(int choice);   // test knob: 0 automatic, 1 tabulated tile, 2 alternative tile (4 slices)
 hipError_t launch_gemm_fused16(int m, int n, int kp, int s, const int8_t *pA, const int8_t *pB,
                                const int32_t *eA, const int32_t *eB, double *C, int ldc,

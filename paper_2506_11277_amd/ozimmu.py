@@ -378,7 +378,8 @@ def measure_int8_with_traffic(lds_reads, dma_copies_per_32):
 
 
 def debug_small_tile_limit(tiles):
-    """Test hook: tile-count threshold below which equal slice counts up to 12 use the 64 x 64 tile (0: never)."""
+    """Test hook: tile-count threshold below which equal slice counts up to 12 use the 64 x 64 tile (0: never;
+    -1, the default: wherever the small tile finishes sooner by the library's cost rule)."""
     rc = lib().ozimmu_debug_small_tile_limit(int(tiles))
     if rc != OK:
         raise OzimmuError(rc, "debug_small_tile_limit")

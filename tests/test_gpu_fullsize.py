@@ -65,7 +65,7 @@ def check_whole_matrix_against_other_tile_shape(dA, dB, C, s, tag):
         ozimmu.debug_small_tile_limit(1 << 40)
         C2 = ozimmu.dgemm(dA, dB, s)
     finally:
-        ozimmu.debug_small_tile_limit(256)
+        ozimmu.debug_small_tile_limit(-1)
     assert bool(torch.equal(C, C2)), f"{tag}: the two tile shapes differ"
 
 
@@ -198,6 +198,6 @@ def test_uneven_regions_of_the_two_dimensional_tile_order():
             ozimmu.debug_small_tile_limit(1 << 40)
             C2 = ozimmu.dgemm(dA, dB, s)
         finally:
-            ozimmu.debug_small_tile_limit(256)
+            ozimmu.debug_small_tile_limit(-1)
         assert not bool(torch.isnan(C1).any()) and bool(torch.equal(C1, C2)), f"uneven regions s={s}: tile shapes differ"
 

@@ -21,7 +21,7 @@ def tile_choice(request):
     switched off (the kernels tabulated per slice count) and once with it on."""
     ozimmu.debug_small_tile_limit(0 if request.param == "tabulated tile" else 256)
     yield request.param
-    ozimmu.debug_small_tile_limit(256)
+    ozimmu.debug_small_tile_limit(-1)
 
 
 @pytest.fixture(autouse=True)
@@ -30,7 +30,7 @@ def tabulated_tile_by_default(request):
     if "tile_choice" not in request.fixturenames:
         ozimmu.debug_small_tile_limit(0)
         yield
-        ozimmu.debug_small_tile_limit(256)
+        ozimmu.debug_small_tile_limit(-1)
     else:
         yield
 
@@ -655,6 +655,28 @@ def test_transposed_problem_gives_the_transposed_result(sA, sB, allp, nearest, Q
     Ct = host(ozimmu.dgemm3(dev(B.T.copy()), dev(A.T.copy()), sB, sA, allp, sp, Q))
     assert np.array_equal(C, Ct.T)
     assert_c_matches(C, oracle.dgemm3(A, B, sA, sB, full=allp, nearest=nearest, Q=Q), "transposition")
+
+
+def test_small_tile_is_taken_where_it_finishes_sooner():
+    # the default rule: (rounds of the compute units) x (tile area) / (relative speed).  2048^2 with 2 slices: 128
+    # tiles of 256 x 128 (one round) lose to 4 rounds of 64 x 64; 2560^2: 200 such tiles win against 7 rounds; both
+    # kernels give the same bits
+    if torch.cuda.get_device_properties(0).multi_processor_count != 256:
+        pytest.skip("the expectations are worked out for 256 compute units")
+    for n, s, want in [(2048, 2, "gemm_fused_kernel<2> equal counts tile 64x64"), (2560, 2, "gemm_fused16_kernel<2> tile 256x128"),
+                       (3000, 3, "gemm_fused_kernel<3> equal counts tile 64x64"), (3000, 7, "gemm_fused16_kernel<7> tile 128x64"),
+                       (100, 7, "gemm_fused_kernel<7> equal counts tile 64x64")]:
+        dA, dB = workloads.lognormal_device(n, n, 96, 1.0, 91)
+        ozimmu.debug_small_tile_limit(-1)
+        C = ozimmu.dgemm(dA, dB, s)
+        assert ozimmu.last_gemm_kernel().startswith(want), (n, s, ozimmu.last_gemm_kernel())
+        ozimmu.debug_small_tile_limit(0 if "64x64" in want else 1 << 40)
+        C2 = ozimmu.dgemm(dA, dB, s)
+        assert not ozimmu.last_gemm_kernel().startswith(want)
+        assert bool(torch.equal(C, C2)), (n, s)
+        rows = np.array([0, 1, 63, 64, n // 2, n - 65, n - 1])
+        tr = torch.as_tensor(rows, device="cuda")
+        assert_c_matches(host(C[tr][:, tr]), oracle.dgemm(host(dA[tr, :]), host(dB[:, tr]), s), f"tile rule {n} s={s}")
 
 
 def test_which_kernel_takes_which_product_set():
