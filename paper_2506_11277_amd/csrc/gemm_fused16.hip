@@ -118,8 +118,10 @@ struct Cfg16 {
     // ALT = 1 (s = 4 only): tile 192 x 128 (2 x 4 wavefronts of 96 x 32, 192 accumulator registers, two 80 KiB
     // stages): 17 % fewer L2 -> LDS bytes and 11 % fewer LDS reads per product than 128 x 128; the launcher takes
     // it where the tile grid of the problem does not lose more in partial rounds than that gains.
-    static_assert(ALT == 0 || (ALT == 1 && S == 4), "an alternative tile exists for 4 slices only");
-    static constexpr bool HUGE = S == 2 || S == 3, WIDE = (S >= 4 && S <= 6);
+    // ALT = 2 (s = 2, 3): tile 128 x 128 with a ring of three stages, for problems of a few thousand rows and
+    // columns whose 256 x 128 tiles would leave most of a round of the compute units empty.
+    static_assert(ALT == 0 || (ALT == 1 && S == 4) || (ALT == 2 && (S == 2 || S == 3)), "no such alternative tile");
+    static constexpr bool HUGE = (S == 2 || S == 3) && ALT != 2, WIDE = (S >= 4 && S <= 6) || ALT == 2;
     static constexpr int WVM = EXP ? OZ_EXP_WVM : WIDE ? 2 : 4, WVN = EXP ? OZ_EXP_WVN : WIDE ? 4 : 2;
     static constexpr int WMF = EXP ? OZ_EXP_WMF : ALT == 1 ? 3 : (WIDE || HUGE) ? 2 : 1, WNF = EXP ? OZ_EXP_WNF : HUGE ? 2 : 1;
     static constexpr int FA = WVM * WMF, FB = WVN * WNF;          // 32-row fragment rows of the tile
@@ -140,7 +142,7 @@ struct Cfg16 {
     // of the cycles).  From 4 slices on three stages of a 128 x 128 tile do not fit.
     // s = 3 on the 256 x 128 tile has stages as long as those of s = 7 (96 matrix instructions per wavefront) and
     // runs with two: 2800 against 2670 TOP/s for the 128 x 128 tile with its ring of three, same box.
-    static constexpr int NSTG = EXP && OZ_EXP_NSTG >= 0 ? OZ_EXP_NSTG : S == 2 ? 3 : 2;
+    static constexpr int NSTG = EXP && OZ_EXP_NSTG >= 0 ? OZ_EXP_NSTG : (S == 2 || ALT == 2) ? 3 : 2;
     static_assert(NSTG == 2 || (NSTG == 3 && L0 == S), "a ring of three only without the split stage");
     static constexpr int LDS = NSTG * P1 + P2;
     static_assert(LDS <= kLdsBytes, "stages do not fit LDS");
@@ -148,9 +150,9 @@ struct Cfg16 {
     // registers, ahead of each use).  Measured at s = 7, 8192^3: 3250 / 3200 / 3310 / 3140 / 3240 / 3205 TOP/s for
     // D = 4 / 6 / 8 / 10 / 12 / 16 (reads one slice ahead, the earlier scheme: 3215); s = 4 is indifferent up to 24.
     // (s = 3 on 256 x 128 and s = 4 on 192 x 128 spill with any longer read-ahead: 2190 against 2800 TOP/s at s = 3)
-    static constexpr int D = EXP && OZ_EXP_D >= 0 ? OZ_EXP_D : (S == 3 || ALT == 1) ? 1 : S == 4 ? 24 : 8, DO = 4;
+    static constexpr int D = EXP && OZ_EXP_D >= 0 ? OZ_EXP_D : ((S == 3 && ALT == 0) || ALT == 1) ? 1 : S == 4 ? 24 : 8, DO = 4;
     // slices of B held in registers for the whole stage (the others are read when needed)
-    static constexpr int HP = EXP && OZ_EXP_HP >= 0 ? OZ_EXP_HP : S >= 9 ? 7 : (S == 6 || ALT == 1) ? 2 : S == 3 ? 1 : S;
+    static constexpr int HP = EXP && OZ_EXP_HP >= 0 ? OZ_EXP_HP : S >= 9 ? 7 : (S == 6 || ALT == 1) ? 2 : (S == 3 && ALT == 0) ? 1 : S;
 };
 
 template <int S, int MODE, int ALT = 0>
@@ -625,28 +627,39 @@ hipError_t launch16_windows(int m, int n, int kp, const int8_t *pA, const int8_t
     return hipGetLastError();
 }
 
-// 4 slices: the 192 x 128 tile runs its products about 6.5 % faster than the 128 x 128 tile (8192^3: +3.3 % although
-// its 43 x 64 tiles make 10.75 rounds of the 256 CUs, 3 % more padded work than the 16 whole rounds of 128 x 128).  It
-// is taken where (rounds of the CUs) x (tile area) / 1.065 comes out below that of the tabulated tile.
-std::atomic<int> g_tile_choice{0};      // test knob: 0 as described, 1 always the tabulated tile, 2 always the alternative
+// Alternative tiles.  4 slices: the 192 x 128 tile runs its products about 6.5 % faster than the 128 x 128 tile
+// (8192^3: +3.3 % although its 43 x 64 tiles make 10.75 rounds of the 256 CUs, 3 % more padded work than the 16 whole
+// rounds of 128 x 128).  2 and 3 slices: the 128 x 128 tile with a ring of three stages runs at 0.87 and 0.95 of the
+// 256 x 128 tile's rate at 8192^3, but a problem of a few thousand rows and columns fills the compute units with it
+// where 256 x 128 tiles leave half of them idle (2048^3, s = 3: 43 us against 66 us, and 51 us for the 64 x 64 tile).
+std::atomic<int> g_tile_choice{0};      // test knob: 0 by cost, 1 always the tabulated tile, 2 always the alternative
 
-constexpr double kAltSpeed = 1.065;
+constexpr double kAltSpeed = 1.065;                  // 192 x 128 against 128 x 128, 4 slices
+constexpr double kMidSpeed[4] = {0, 0, 0.87, 0.95};   // 128 x 128 (ring of three) against 256 x 128, 2 and 3 slices
 
-bool alt_tile_pays(int m, int n)
+// Which tile a launch without split-k takes: 0 the tabulated one, 1 the 192 x 128 tile (4 slices), 2 the 128 x 128 tile
+// (2, 3 slices), by the launch cost of oz_common.h divided by the relative speed of the shape.
+int alt_tile(int s, int m, int n)
 {
+    if (s < 2 || s > 4 || s == OZ_EXP_S) return 0;
+    const int other = s == 4 ? 1 : 2;
     const int choice = g_tile_choice.load();
-    if (choice) return choice == 2;
-    if (OZ_EXP_S == 4) return false;
+    if (choice) return choice == 2 ? other : 0;
     const int cus = device_cus();
-    return launch_cost(m, n, 192, 128, cus) / kAltSpeed < launch_cost(m, n, 128, 128, cus);
+    if (s == 4) return launch_cost(m, n, 192, 128, cus) / kAltSpeed < launch_cost(m, n, 128, 128, cus) ? 1 : 0;
+    return launch_cost(m, n, 128, 128, cus) / kMidSpeed[s] < launch_cost(m, n, 256, 128, cus) ? 2 : 0;
 }
 
 template <int MODE>
 hipError_t dispatch16(int s, int m, int n, int kp, const int8_t *pA, const int8_t *pB, const int32_t *eA,
                       const int32_t *eB, double *C, int ldc, int32_t *dump, long long *totals, int Q, hipStream_t st)
 {
-    if constexpr (MODE != kBlocked)
-        if (s == 4 && alt_tile_pays(m, n)) return launch16_s<4, MODE, 1>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, Q, st);
+    if constexpr (MODE != kBlocked) {
+        const int alt = alt_tile(s, m, n);
+        if (alt == 1) return launch16_s<4, MODE, 1>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, Q, st);
+        if (alt == 2 && s == 2) return launch16_s<2, MODE, 2>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, Q, st);
+        if (alt == 2 && s == 3) return launch16_s<3, MODE, 2>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, Q, st);
+    }
     switch (s) {
 #define OZ_CASE(S_) \
     case S_: return launch16_s<S_, MODE>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, Q, st);
@@ -690,7 +703,9 @@ hipError_t launch_finish_blocks16(const long long *totals, const int32_t *eA, co
 
 double fused16_launch_cost(int s, int m, int n, int cus)
 {
-    if (s == 4 && alt_tile_pays(m, n)) return launch_cost(m, n, 192, 128, cus) / kAltSpeed;
+    const int alt = alt_tile(s, m, n);
+    if (alt == 1) return launch_cost(m, n, 192, 128, cus) / kAltSpeed;
+    if (alt == 2) return launch_cost(m, n, 128, 128, cus) / kMidSpeed[s];
     int tm, tn;
     fused16_tile(s, tm, tn);
     return launch_cost(m, n, tm, tn, cus);

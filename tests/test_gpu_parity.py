@@ -20,17 +20,22 @@ def tile_choice(request):
     """Small problems would all run the 64 x 64 tile; tests that take this fixture run once with that choice
     switched off (the kernels tabulated per slice count) and once with it on."""
     ozimmu.debug_small_tile_limit(0 if request.param == "tabulated tile" else 256)
+    ozimmu.debug_tile_choice(1)
     yield request.param
     ozimmu.debug_small_tile_limit(-1)
+    ozimmu.debug_tile_choice(0)
 
 
 @pytest.fixture(autouse=True)
 def tabulated_tile_by_default(request):
-    """Every other test runs the kernels tabulated per slice count."""
+    """Every other test runs the kernels tabulated per slice count (neither the 64 x 64 tile nor the alternative
+    tiles of 2, 3 and 4 slices, which the library would take at these sizes)."""
     if "tile_choice" not in request.fixturenames:
         ozimmu.debug_small_tile_limit(0)
+        ozimmu.debug_tile_choice(1)
         yield
         ozimmu.debug_small_tile_limit(-1)
+        ozimmu.debug_tile_choice(0)
     else:
         yield
 
@@ -187,25 +192,27 @@ def alternative_tile():
 
 @pytest.mark.parametrize("kind", ["uniform", "lognormal", "pow2", "special"])
 @pytest.mark.parametrize("m,n,k", SHAPES + [(192, 128, 64), (193, 129, 65), (400, 300, 200), (577, 257, 130), (96, 500, 1000)])
-def test_four_slices_on_the_192_by_128_tile(kind, m, n, k, alternative_tile):
-    # at these sizes the launcher would take the tabulated 128 x 128 tile; the knob forces the alternative, whose
-    # wavefronts hold three fragment rows (tiles that end inside the first, second and third of them, one and
-    # several tiles each way)
+@pytest.mark.parametrize("s,tile", [(2, "128x128 ring of 3"), (3, "128x128 ring of 3"), (4, "192x128")])
+def test_alternative_tiles_of_few_slices(kind, m, n, k, s, tile, alternative_tile):
+    # at these sizes the launcher would not take them by itself; the knob forces the alternative: for 4 slices the
+    # 192 x 128 tile, whose wavefronts hold three fragment rows (tiles that end inside the first, second and third
+    # of them, one and several tiles each way); for 2 and 3 slices the 128 x 128 tile with its ring of three stages
     A, B = inputs(kind, m, n, k, 37)
-    ws = ozimmu.alloc_workspace(m, n, k, 4)
-    C = ozimmu.dgemm(dev(A), dev(B), 4, workspace=ws, check_finite=True)
-    assert ozimmu.last_gemm_kernel().startswith("gemm_fused16_kernel<4> tile 192x128"), ozimmu.last_gemm_kernel()
-    assert_c_matches(host(C), oracle.dgemm(A, B, 4), f"192x128 tile {kind} {m}x{n}x{k}")
-    pa, _ = oracle.split("A", A, 4)
-    pb, _ = oracle.split("B", B, 4)
-    D = host(ozimmu.debug_diagonals(m, n, k, 4, ws))
-    for d in range(2, 6):
-        want = sum(oracle.slice_product(pa[l - 1], pb[d - l - 1]) for l in range(1, d) if l <= 4 and d - l <= 4)
+    ws = ozimmu.alloc_workspace(m, n, k, s)
+    C = ozimmu.dgemm(dev(A), dev(B), s, workspace=ws, check_finite=True)
+    name = f"gemm_fused16_kernel<{s}> tile {tile}"
+    assert ozimmu.last_gemm_kernel().startswith(name), ozimmu.last_gemm_kernel()
+    assert_c_matches(host(C), oracle.dgemm(A, B, s), f"{tile} tile {kind} {m}x{n}x{k}")
+    pa, _ = oracle.split("A", A, s)
+    pb, _ = oracle.split("B", B, s)
+    D = host(ozimmu.debug_diagonals(m, n, k, s, ws))
+    for d in range(2, s + 2):
+        want = sum(oracle.slice_product(pa[l - 1], pb[d - l - 1]) for l in range(1, d) if l <= s and d - l <= s)
         assert np.array_equal(D[d - 2].T.astype(np.int64), want), d
     # nearest slices and levels of two diagonals run the same kernel
-    C3 = ozimmu.dgemm3(dev(A), dev(B), 4, 4, False, ozimmu.SPLIT_NEAREST, 2)
-    assert ozimmu.last_gemm_kernel().startswith("gemm_fused16_kernel<4> tile 192x128")
-    assert_c_matches(host(C3), oracle.dgemm3(A, B, 4, 4, nearest=True, Q=2), "192x128 tile, nearest, Q = 2")
+    C3 = ozimmu.dgemm3(dev(A), dev(B), s, s, False, ozimmu.SPLIT_NEAREST, 2)
+    assert ozimmu.last_gemm_kernel().startswith(name)
+    assert_c_matches(host(C3), oracle.dgemm3(A, B, s, s, nearest=True, Q=2), f"{tile} tile, nearest, Q = 2")
 
 
 def test_extreme_slices_do_not_overflow_int32_in_fused_kernel():
@@ -658,16 +665,19 @@ def test_transposed_problem_gives_the_transposed_result(sA, sB, allp, nearest, Q
 
 
 def test_small_tile_is_taken_where_it_finishes_sooner():
-    # the default rule: (rounds of the compute units) x (tile area) / (relative speed).  2048^2 with 2 slices: 128
-    # tiles of 256 x 128 (one round) lose to 4 rounds of 64 x 64; 2560^2: 200 such tiles win against 7 rounds; both
-    # kernels give the same bits
+    # the default rule: (rounds of the compute units) x (tile area) / (relative speed), over the tabulated tile, the
+    # alternative tile of 2, 3 and 4 slices and the 64 x 64 tile.  2048^2 with 2 slices: 128 tiles of 256 x 128 (half a
+    # round) lose to one round of 128 x 128; 2560^2: 200 such tiles win against two rounds; every kernel gives the
+    # same bits
     if torch.cuda.get_device_properties(0).multi_processor_count != 256:
         pytest.skip("the expectations are worked out for 256 compute units")
-    for n, s, want in [(2048, 2, "gemm_fused_kernel<2> equal counts tile 64x64"), (2560, 2, "gemm_fused16_kernel<2> tile 256x128"),
-                       (3000, 3, "gemm_fused_kernel<3> equal counts tile 64x64"), (3000, 7, "gemm_fused16_kernel<7> tile 128x64"),
-                       (100, 7, "gemm_fused_kernel<7> equal counts tile 64x64")]:
+    for n, s, want in [(1024, 3, "gemm_fused_kernel<3> equal counts tile 64x64"), (2048, 2, "gemm_fused16_kernel<2> tile 128x128 ring of 3"),
+                       (2560, 2, "gemm_fused16_kernel<2> tile 256x128"), (3000, 3, "gemm_fused16_kernel<3> tile 128x128 ring of 3"),
+                       (2304, 4, "gemm_fused16_kernel<4> tile 192x128"), (2560, 4, "gemm_fused16_kernel<4> tile 128x128"),
+                       (3000, 7, "gemm_fused16_kernel<7> tile 128x64"), (100, 7, "gemm_fused_kernel<7> equal counts tile 64x64")]:
         dA, dB = workloads.lognormal_device(n, n, 96, 1.0, 91)
         ozimmu.debug_small_tile_limit(-1)
+        ozimmu.debug_tile_choice(0)
         C = ozimmu.dgemm(dA, dB, s)
         assert ozimmu.last_gemm_kernel().startswith(want), (n, s, ozimmu.last_gemm_kernel())
         ozimmu.debug_small_tile_limit(0 if "64x64" in want else 1 << 40)
