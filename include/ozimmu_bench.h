@@ -86,9 +86,9 @@ int ozimmu_calibration_copy(void *dst, const void *src, size_t bytes, void *stre
  *   area) / (relative speed of the kernel); that rule is the default (-1).  0: never the small tile; n > 0: the
  *   small tile whenever the tabulated one would give fewer than n work-groups.  Process-wide host state; lets
  *   the tests run both kernels on the same small inputs.  Returns OZIMMU_BAD_ARG for a value below -1.
- * ozimmu_debug_tile_choice: with 2, 3 and 4 slices ozimmu_dgemm picks between the tabulated tile (256 x 128,
- *   256 x 128, 128 x 128) and an alternative (128 x 128, 128 x 128, 192 x 128) by the number of rounds of the compute
- *   units each needs; 1 forces the tabulated tile, 2 the alternative, 0 (default) restores the choice.
+ * ozimmu_debug_tile_choice: with 2 ... 6 slices ozimmu_dgemm picks between the tabulated tile (256 x 128,
+ *   256 x 128, 128 x 128, 128 x 128, 128 x 128) and an alternative (128 x 128, 128 x 128, 192 x 128, 128 x 64,
+ *   128 x 64) by the number of rounds of the compute units each needs; 1 forces the tabulated tile, 2 the alternative, 0 (default) restores the choice.
  *   Process-wide host state.  Returns OZIMMU_BAD_ARG for other values.
  * ozimmu_debug_panel_bytes: when k has to be cut into blocks, C is computed one column panel after the other so
  *   that the int64 totals of a panel take about `bytes` (default 1 GiB; <= 0: all of C at once).  Changes what

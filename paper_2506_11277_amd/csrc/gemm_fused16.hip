@@ -120,8 +120,10 @@ struct Cfg16 {
     // it where the tile grid of the problem does not lose more in partial rounds than that gains.
     // ALT = 2 (s = 2, 3): tile 128 x 128 with a ring of three stages, for problems of a few thousand rows and
     // columns whose 256 x 128 tiles would leave most of a round of the compute units empty.
-    static_assert(ALT == 0 || (ALT == 1 && S == 4) || (ALT == 2 && (S == 2 || S == 3)), "no such alternative tile");
-    static constexpr bool HUGE = (S == 2 || S == 3) && ALT != 2, WIDE = (S >= 4 && S <= 6) || ALT == 2;
+    // ALT = 3 (s = 5, 6): tile 128 x 64, whole stage double-buffered, for the same purpose.
+    static_assert(ALT == 0 || (ALT == 1 && S == 4) || (ALT == 2 && (S == 2 || S == 3)) || (ALT == 3 && (S == 5 || S == 6)),
+                  "no such alternative tile");
+    static constexpr bool HUGE = (S == 2 || S == 3) && ALT != 2, WIDE = ((S >= 4 && S <= 6) || ALT == 2) && ALT != 3;
     static constexpr int WVM = EXP ? OZ_EXP_WVM : WIDE ? 2 : 4, WVN = EXP ? OZ_EXP_WVN : WIDE ? 4 : 2;
     static constexpr int WMF = EXP ? OZ_EXP_WMF : ALT == 1 ? 3 : (WIDE || HUGE) ? 2 : 1, WNF = EXP ? OZ_EXP_WNF : HUGE ? 2 : 1;
     static constexpr int FA = WVM * WMF, FB = WVN * WNF;          // 32-row fragment rows of the tile
@@ -130,7 +132,7 @@ struct Cfg16 {
     // 2985 / 3150 / 3120 for L0 = 2 / 3 / 4 -- and 3230 against 3110 with split-k --, s = 9 2925 / 3100 for L0 = 1 / 2;
     // s = 6 on the 128 x 128 tile: L0 = 1 with two slices of B held 3055-3065, L0 = 2 spills, against 2905 for the
     // 128 x 64 tile without split, same box)
-    static constexpr int L0 = EXP && OZ_EXP_L0 >= 0 ? OZ_EXP_L0 : S <= 5 ? S : S == 6 ? 1 : S <= 8 ? 3 : 2;
+    static constexpr int L0 = EXP && OZ_EXP_L0 >= 0 ? OZ_EXP_L0 : (S <= 5 || ALT == 3) ? S : S == 6 ? 1 : S <= 8 ? 3 : 2;
     static constexpr int P1 = (FA * L0 + FB * S) * 2 * kFragBytes;    // double-buffered part of a 64-k stage
     static constexpr int P2 = FA * (S - L0) * 2 * kFragBytes;         // single-buffered part
     // ring depth of the double-buffered part.  Few slices make a stage short (s = 2: 48 matrix instructions per
@@ -152,7 +154,7 @@ struct Cfg16 {
     // (s = 3 on 256 x 128 and s = 4 on 192 x 128 spill with any longer read-ahead: 2190 against 2800 TOP/s at s = 3)
     static constexpr int D = EXP && OZ_EXP_D >= 0 ? OZ_EXP_D : ((S == 3 && ALT == 0) || ALT == 1) ? 1 : S == 4 ? 24 : 8, DO = 4;
     // slices of B held in registers for the whole stage (the others are read when needed)
-    static constexpr int HP = EXP && OZ_EXP_HP >= 0 ? OZ_EXP_HP : S >= 9 ? 7 : (S == 6 || ALT == 1) ? 2 : (S == 3 && ALT == 0) ? 1 : S;
+    static constexpr int HP = EXP && OZ_EXP_HP >= 0 ? OZ_EXP_HP : S >= 9 ? 7 : ((S == 6 && ALT == 0) || ALT == 1) ? 2 : (S == 3 && ALT == 0) ? 1 : S;
 };
 
 template <int S, int MODE, int ALT = 0>
@@ -632,21 +634,24 @@ hipError_t launch16_windows(int m, int n, int kp, const int8_t *pA, const int8_t
 // rounds of 128 x 128).  2 and 3 slices: the 128 x 128 tile with a ring of three stages runs at 0.87 and 0.95 of the
 // 256 x 128 tile's rate at 8192^3, but a problem of a few thousand rows and columns fills the compute units with it
 // where 256 x 128 tiles leave half of them idle (2048^3, s = 3: 43 us against 66 us, and 51 us for the 64 x 64 tile).
+// 5 and 6 slices: the 128 x 64 tile (0.82-0.90 and 0.94 of the 128 x 128 tile's rate) likewise (2304^3, s = 6: 183 us
+// against 223 us).
 std::atomic<int> g_tile_choice{0};      // test knob: 0 by cost, 1 always the tabulated tile, 2 always the alternative
 
 constexpr double kAltSpeed = 1.065;                  // 192 x 128 against 128 x 128, 4 slices
-constexpr double kMidSpeed[4] = {0, 0, 0.87, 0.95};   // 128 x 128 (ring of three) against 256 x 128, 2 and 3 slices
+constexpr double kMidSpeed[7] = {0, 0, 0.87, 0.95, 0, 0.88, 0.94};   // 128 x 128 (ring of three) against 256 x 128 for 2 and 3 slices, 128 x 64 against 128 x 128 for 5 and 6
 
 // Which tile a launch without split-k takes: 0 the tabulated one, 1 the 192 x 128 tile (4 slices), 2 the 128 x 128 tile
-// (2, 3 slices), by the launch cost of oz_common.h divided by the relative speed of the shape.
+// (2, 3 slices), 3 the 128 x 64 tile (5, 6 slices), by the launch cost of oz_common.h divided by the relative speed of the shape.
 int alt_tile(int s, int m, int n)
 {
-    if (s < 2 || s > 4 || s == OZ_EXP_S) return 0;
-    const int other = s == 4 ? 1 : 2;
+    if (s < 2 || s > 6 || s == OZ_EXP_S) return 0;
+    const int other = s == 4 ? 1 : s <= 3 ? 2 : 3;
     const int choice = g_tile_choice.load();
     if (choice) return choice == 2 ? other : 0;
     const int cus = device_cus();
     if (s == 4) return launch_cost(m, n, 192, 128, cus) / kAltSpeed < launch_cost(m, n, 128, 128, cus) ? 1 : 0;
+    if (s >= 5) return launch_cost(m, n, 128, 64, cus) / kMidSpeed[s] < launch_cost(m, n, 128, 128, cus) ? 3 : 0;
     return launch_cost(m, n, 128, 128, cus) / kMidSpeed[s] < launch_cost(m, n, 256, 128, cus) ? 2 : 0;
 }
 
@@ -659,6 +664,8 @@ hipError_t dispatch16(int s, int m, int n, int kp, const int8_t *pA, const int8_
         if (alt == 1) return launch16_s<4, MODE, 1>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, Q, st);
         if (alt == 2 && s == 2) return launch16_s<2, MODE, 2>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, Q, st);
         if (alt == 2 && s == 3) return launch16_s<3, MODE, 2>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, Q, st);
+        if (alt == 3 && s == 5) return launch16_s<5, MODE, 3>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, Q, st);
+        if (alt == 3 && s == 6) return launch16_s<6, MODE, 3>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, Q, st);
     }
     switch (s) {
 #define OZ_CASE(S_) \
@@ -706,6 +713,7 @@ double fused16_launch_cost(int s, int m, int n, int cus)
     const int alt = alt_tile(s, m, n);
     if (alt == 1) return launch_cost(m, n, 192, 128, cus) / kAltSpeed;
     if (alt == 2) return launch_cost(m, n, 128, 128, cus) / kMidSpeed[s];
+    if (alt == 3) return launch_cost(m, n, 128, 64, cus) / kMidSpeed[s];
     int tm, tn;
     fused16_tile(s, tm, tn);
     return launch_cost(m, n, tm, tn, cus);

@@ -386,7 +386,7 @@ def debug_small_tile_limit(tiles):
 
 
 def debug_tile_choice(choice):
-    """Test hook: 2, 3, 4 slices on the tabulated tile (1), on the alternative tile (2), or chosen by size (0)."""
+    """Test hook: 2 ... 6 slices on the tabulated tile (1), on the alternative tile (2), or chosen by size (0)."""
     rc = lib().ozimmu_debug_tile_choice(int(choice))
     if rc != OK:
         raise OzimmuError(rc, "debug_tile_choice")

@@ -192,11 +192,12 @@ def alternative_tile():
 
 @pytest.mark.parametrize("kind", ["uniform", "lognormal", "pow2", "special"])
 @pytest.mark.parametrize("m,n,k", SHAPES + [(192, 128, 64), (193, 129, 65), (400, 300, 200), (577, 257, 130), (96, 500, 1000)])
-@pytest.mark.parametrize("s,tile", [(2, "128x128 ring of 3"), (3, "128x128 ring of 3"), (4, "192x128")])
+@pytest.mark.parametrize("s,tile", [(2, "128x128 ring of 3"), (3, "128x128 ring of 3"), (4, "192x128"), (5, "128x64"), (6, "128x64")])
 def test_alternative_tiles_of_few_slices(kind, m, n, k, s, tile, alternative_tile):
     # at these sizes the launcher would not take them by itself; the knob forces the alternative: for 4 slices the
     # 192 x 128 tile, whose wavefronts hold three fragment rows (tiles that end inside the first, second and third
-    # of them, one and several tiles each way); for 2 and 3 slices the 128 x 128 tile with its ring of three stages
+    # of them, one and several tiles each way); for 2 and 3 slices the 128 x 128 tile with its ring of three stages;
+    # for 5 and 6 slices the 128 x 64 tile
     A, B = inputs(kind, m, n, k, 37)
     ws = ozimmu.alloc_workspace(m, n, k, s)
     C = ozimmu.dgemm(dev(A), dev(B), s, workspace=ws, check_finite=True)
@@ -666,7 +667,7 @@ def test_transposed_problem_gives_the_transposed_result(sA, sB, allp, nearest, Q
 
 def test_small_tile_is_taken_where_it_finishes_sooner():
     # the default rule: (rounds of the compute units) x (tile area) / (relative speed), over the tabulated tile, the
-    # alternative tile of 2, 3 and 4 slices and the 64 x 64 tile.  2048^2 with 2 slices: 128 tiles of 256 x 128 (half a
+    # alternative tile of 2 ... 6 slices and the 64 x 64 tile.  2048^2 with 2 slices: 128 tiles of 256 x 128 (half a
     # round) lose to one round of 128 x 128; 2560^2: 200 such tiles win against two rounds; every kernel gives the
     # same bits
     if torch.cuda.get_device_properties(0).multi_processor_count != 256:
@@ -674,6 +675,7 @@ def test_small_tile_is_taken_where_it_finishes_sooner():
     for n, s, want in [(1024, 3, "gemm_fused_kernel<3> equal counts tile 64x64"), (2048, 2, "gemm_fused16_kernel<2> tile 128x128 ring of 3"),
                        (2560, 2, "gemm_fused16_kernel<2> tile 256x128"), (3000, 3, "gemm_fused16_kernel<3> tile 128x128 ring of 3"),
                        (2304, 4, "gemm_fused16_kernel<4> tile 192x128"), (2560, 4, "gemm_fused16_kernel<4> tile 128x128"),
+                       (2304, 6, "gemm_fused16_kernel<6> tile 128x64"), (2560, 6, "gemm_fused16_kernel<6> tile 128x128"),
                        (3000, 7, "gemm_fused16_kernel<7> tile 128x64"), (100, 7, "gemm_fused_kernel<7> equal counts tile 64x64")]:
         dA, dB = workloads.lognormal_device(n, n, 96, 1.0, 91)
         ozimmu.debug_small_tile_limit(-1)
