@@ -634,6 +634,54 @@ def test_seeded_random_configurations(tile_choice):
         assert_c_matches(got, oracle.dgemm3(A, B, sA, sB, full=allp, nearest=nearest, Q=Q), f"case {case}")
 
 
+def test_seeded_random_configurations_with_special_values_and_every_tile_rule():
+    # 150 more from a fixed seed, larger shapes and contraction lengths up to 30000 (k-blocks), with every setting
+    # of the two tile knobs (automatic, forced either way), and in 40 % of the cases a zero row and column, a
+    # subnormal, a huge, a negative-zero entry, a column scaled by a power of two and a row of powers of two
+    rng = np.random.default_rng(2506112771)
+    try:
+        done = 0
+        while done < 150:
+            big = rng.random() < 0.25
+            m, n = int(rng.integers(1, 1400 if big else 400)), int(rng.integers(1, 1400 if big else 400))
+            k = int(rng.choice([rng.integers(1, 300), rng.integers(300, 3000), rng.integers(3000, 30000)], p=[.4, .35, .25]))
+            if big:
+                k = min(k, 600)
+            sA = int(rng.integers(1, 33))
+            sB = sA if rng.random() < 0.5 else int(rng.integers(1, 33))
+            allp, nearest = bool(rng.random() < 0.15), bool(rng.random() < 0.3)
+            Q = int(rng.integers(1, min(ozimmu.max_level_diagonals(k, sA, sB), 4) + 1))
+            small, tile = int(rng.choice([-1, 0, 256])), int(rng.choice([0, 1, 2]))
+            phi = float(rng.choice([0.5, 2.0, 6.0]))
+            special = rng.random() < 0.4
+            if m * n * k * (sA * sB if allp else max(sA, sB) ** 2 / 2) > 2e10:
+                continue
+            A, B = workloads.lognormal(m, n, k, phi, 7000 + done)
+            if special:
+                if m > 2:
+                    A[int(rng.integers(0, m)), :] = 0.0
+                if n > 2:
+                    B[:, int(rng.integers(0, n))] = 0.0
+                A[int(rng.integers(0, m)), int(rng.integers(0, k))] = 5e-324 * float(rng.integers(1, 1000))
+                B[int(rng.integers(0, k)), int(rng.integers(0, n))] = -1.0e300
+                B[int(rng.integers(0, k)), int(rng.integers(0, n))] = -0.0
+                A[:, int(rng.integers(0, k))] *= 2.0 ** int(rng.integers(-300, 300))
+                A[int(rng.integers(0, m)), :] = np.ldexp(1.0, int(rng.integers(-1000, -300)))
+                A *= 1e-100                               # keeps the exact product finite
+            print(f"case {done}: {m}x{n}x{k} sA={sA} sB={sB} all={allp} nearest={nearest} Q={Q} small={small} tile={tile} "
+                  f"phi={phi} special={special}", flush=True)
+            ozimmu.debug_small_tile_limit(small)
+            ozimmu.debug_tile_choice(tile)
+            got = host(ozimmu.dgemm3(dev(A), dev(B), sA, sB, allp, ozimmu.SPLIT_NEAREST if nearest else ozimmu.SPLIT_TRUNCATE, Q))
+            want = oracle.dgemm3(A, B, sA, sB, full=allp, nearest=nearest, Q=Q)
+            assert np.isfinite(want).all()
+            assert_c_matches(got, want, f"case {done} ({ozimmu.last_gemm_kernel()})")
+            done += 1
+    finally:
+        ozimmu.debug_small_tile_limit(-1)
+        ozimmu.debug_tile_choice(0)
+
+
 @pytest.mark.parametrize("sA,sB,allp", [(4, 4, False), (5, 5, False), (6, 6, False), (7, 7, False), (8, 8, False), (9, 9, False), (12, 12, False),
                                         (16, 16, False), (18, 18, False), (20, 20, False), (5, 11, False),
                                         (13, 4, False), (6, 6, True)])
