@@ -803,10 +803,80 @@ hipError_t launch_block(int m, int n, int kp, const int8_t *pA, const int8_t *pB
 // block is two launches: the reduced set l' + h' <= G + 1 of the pair of groups, and the rest l' + h' >= G + 2, which
 // is the reduced set of G - 1 slices once both groups are walked backwards from their last slice (l'' = G + 1 - l',
 // h'' = G + 1 - h': l'' + h'' <= G, l'', h'' <= G - 1), its diagonals descending from the block's last one.
+// Windows of the plan: nf blocks in all (each contributes the reduced set of G slices), nr of them whole (they also
+// contribute the reversed reduced set of G - 1 slices).
+inline void blocks_window_counts(const BlocksPlan &plan, bool all_products, int &nf, int &nr)
+{
+    const int G = plan.G, NGA = plan.spA / G, NGB = plan.spB / G, NG = NGA > NGB ? NGA : NGB;
+    nf = nr = 0;
+    for (int I = 0; I < NGA; ++I)
+        for (int J = 0; J < NGB; ++J) {
+            if (!all_products && I + J > NG - 1) continue;
+            ++nf;
+            if (all_products || I + J < NG - 1) ++nr;
+        }
+}
+
+// A slot of int32 diagonal sums per window instead of int64 totals shared through atomics: when the contraction is
+// one k-block for G slices and the windows fit one launch of each kind.
+inline bool blocks_slots(const BlocksPlan &plan, bool all_products, int kp)
+{
+    if (plan.spA != plan.spB) return false;
+    int nf, nr;
+    blocks_window_counts(plan, all_products, nf, nr);
+    return nf <= kMaxWindows16 && nr <= kMaxWindows16 && kp / (2 * kFrag) <= (int)(kMaxInt32K / plan.G / (2 * kFrag));
+}
+
+inline hipError_t launch_blocks16_slots(int m, int n, int kp, const BlocksPlan &plan, bool all_products, int diagonals,
+                                        const int8_t *pA, const int8_t *pB, const int32_t *eA, const int32_t *eB,
+                                        double *C, int ldc, long long *totals, int Q, hipStream_t st)
+{
+    const int G = plan.G, NGA = plan.spA / G, NGB = plan.spB / G, NG = NGA > NGB ? NGA : NGB;
+    const int tiles_m = (m + 127) / 128, tiles_n = (n + 63) / 64;
+    WindowList16 fwd, rev;
+    int abase_f[kMaxWindows16], abase_r[kMaxWindows16];
+    int nf = 0, nr = 0;
+    for (int I = 0; I < NGA; ++I)
+        for (int J = 0; J < NGB; ++J) {
+            if (!all_products && I + J > NG - 1) continue;
+            const int d0 = G * (I + J);                                       // first diagonal of the block
+            if (nf >= kMaxWindows16 || nr >= kMaxWindows16) return hipErrorInvalidValue;
+            abase_f[nf] = d0;
+            fwd.w[nf++] = Window16{plan.spA, I * G, 1, J * G, 1, 0, 1, G};
+            if (all_products || I + J < NG - 1) {
+                abase_r[nr] = d0 + 2 * G - 2;
+                rev.w[nr++] = Window16{plan.spA, I * G + G - 1, -1, J * G + G - 1, -1, 0, 1, G - 1};
+            }
+        }
+    if (diagonals > kMaxSlotDiagonals) return hipErrorInvalidValue;
+    // the terms of each requested diagonal: local diagonal a of a block is diagonal d0 + a, local diagonal a of its
+    // reversed set diagonal d0 + 2 G - 2 - a
+    SlotTerms terms;
+    int nt = 0;
+    for (int d = 0; d < diagonals; ++d) {
+        terms.first[d] = (unsigned short)nt;
+        for (int q = 0; q < nf; ++q)
+            if (d >= abase_f[q] && d < abase_f[q] + G) terms.term[nt++] = (unsigned short)(q * 16 + (d - abase_f[q]));
+        for (int q = 0; q < nr; ++q)
+            if (d <= abase_r[q] && d > abase_r[q] - (G - 1)) terms.term[nt++] = (unsigned short)((nf + q) * 16 + (abase_r[q] - d));
+    }
+    for (int d = diagonals; d <= kMaxSlotDiagonals; ++d) terms.first[d] = (unsigned short)nt;
+    const size_t tile_values = (size_t)tiles_m * tiles_n * 128 * 64;
+    int32_t *slots = (int32_t *)totals;
+    if (hipError_t e = launch_fused16_windows(G, m, n, kp, pA, pB, totals, fwd, nf, true, st); e != hipSuccess) return e;
+    if (hipError_t e = launch_fused16_windows(G - 1, m, n, kp, pA, pB, (long long *)(slots + (size_t)nf * tile_values * G), rev, nr,
+                                              true, st);
+        e != hipSuccess)
+        return e;
+    return launch_finish_slots16(slots, nf, G, terms, eA, eB, C, ldc, m, n, Q, diagonals, st);
+}
+
 inline hipError_t launch_blocks16(int m, int n, int kp, const BlocksPlan &plan, bool all_products, int diagonals,
                                   int na_tot, const int8_t *pA, const int8_t *pB, const int32_t *eA, const int32_t *eB,
                                   double *C, int ldc, long long *totals, int Q, hipStream_t st)
 {
+    if (blocks_slots(plan, all_products, kp))
+        return launch_blocks16_slots(m, n, kp, plan, all_products, diagonals, pA, pB, eA, eB, C, ldc, totals, Q, st);
     const int G = plan.G, NGA = plan.spA / G, NGB = plan.spB / G, NG = NGA > NGB ? NGA : NGB;
     const int tiles_m = (m + 127) / 128, tiles_n = (n + 63) / 64;
     zero_i64_kernel<<<2048, 256, 0, st>>>(totals, (size_t)tiles_m * tiles_n * na_tot * 128 * 64);
@@ -815,7 +885,7 @@ inline hipError_t launch_blocks16(int m, int n, int kp, const BlocksPlan &plan, 
     WindowList16 fwd, rev;
     int nf = 0, nr = 0;
     auto flush = [&](int s_, WindowList16 &list, int &cnt) {
-        const hipError_t e = launch_fused16_windows(s_, m, n, kp, pA, pB, totals, list, cnt, st);
+        const hipError_t e = launch_fused16_windows(s_, m, n, kp, pA, pB, totals, list, cnt, false, st);
         cnt = 0;
         return e;
     };
@@ -888,12 +958,15 @@ static bool fused_capable(int sA, int sB, bool all_products)
     return sA == sB ? sA <= kFusedMaxS : (sA > sB ? sA : sB) <= kFusedMaxUneq;
 }
 
-// ... and what the routing gives them: all of it but 18 equal slices, which are two groups of 9 and run 10 % faster
-// as blocks through the 16x16x64 kernel than in the four-wavefront shape with two k-blocks (8192^3: 66.7 -> 60.8 ms;
-// 16, 17, 19 and 20 slices do not gain)
-bool fused_handles(int sA, int sB, bool all_products)
+// ... and what the routing gives them: all of it but 18 equal slices of larger problems.  They are two groups of 9
+// and run faster as blocks through the 16x16x64 kernel than in the four-wavefront shape: 8192^3 (two k-blocks there)
+// 66.7 -> 54.8 ms, 4096^3 8.0 -> 7.4 ms, the same at 2048^3, slower below.  (14 and 16 slices, two groups of 7 and 8,
+// gain 2-3 % at 8192^3 and lose as much at 4096^3: they stay; 17 runs as 18, 19 and 20 have no such grouping.)
+bool fused_handles(int sA, int sB, bool all_products, int m, int n, int k)
 {
-    if (!all_products && sA == sB && sA == 18) return false;
+    if (!all_products && sA == sB && sA == 18 &&
+        (18LL * (k > 0 ? k : 1) > kMaxInt32K || (long long)m * n >= 2048LL * 2048LL))
+        return false;
     return fused_capable(sA, sB, all_products);
 }
 
@@ -989,18 +1062,28 @@ static int blocks_panel_cols(int diagonals, int m, int n, int tile_m, int tile_n
 // The 16x16x64 kernel takes the blocks when both planes hold the same number of slices per entry and the groups have
 // 8 or 9 slices (8192^3: s = 24 2730 -> 2850, s = 27 2850 -> 3000, s = 32 2770 -> 2930 TOP/s; groups of 7, which would
 // run its weakest slice counts 7 and 6, lose 6 %: 21 and 28 slices stay with the 32x32x32 blocks).
-static bool blocks_use16(const BlocksPlan &p) { return p.spA == p.spB && p.G >= 8; }
+static bool blocks_use16(const BlocksPlan &p) { return p.spA == p.spB; }
 
 static int blocks_total_diagonals(const BlocksPlan &p, bool all_products)
 {
     return all_products ? p.spA + p.spB - 1 : (p.spA > p.spB ? p.spA : p.spB);
 }
 
-size_t blocks_totals_bytes(int sA, int sB, bool all_products, int m, int n)
+// int64 values the buffer holds per entry of C: the diagonals of the totals, or -- with a slot per window -- half the
+// int32 values of all slots (rounded up); the column panels are sized by it.
+static int blocks_values_per_entry(const BlocksPlan &p, bool all_products, int kp)
+{
+    if (!blocks_slots(p, all_products, kp)) return blocks_total_diagonals(p, all_products);
+    int nf, nr;
+    blocks_window_counts(p, all_products, nf, nr);
+    return (nf * p.G + nr * (p.G - 1) + 1) / 2;
+}
+
+size_t blocks_totals_bytes(int sA, int sB, bool all_products, int m, int n, int k)
 {
     BlocksPlan p;
     if (m <= 0 || n <= 0 || !blocks_plan(sA, sB, all_products, &p)) return 0;
-    const int na_tot = blocks_total_diagonals(p, all_products);
+    const int na_tot = blocks_values_per_entry(p, all_products, round_up(k > 0 ? k : 1, kPad));
     const bool use16 = blocks_use16(p);          // 16x16x64 blocks, tile 128 x 64
     const int w = blocks_panel_cols(na_tot, m, n, use16 ? 128 : kBlkTile, use16 ? 64 : kBlkTile);
     const int wn = w < n ? w : n;
@@ -1022,12 +1105,13 @@ hipError_t launch_gemm_blocks(int m, int n, int kp, int sA, int sB, bool all_pro
     const bool use16 = blocks_use16(p);
     if (use16)
         note_gemm_kernel("blocks of slice groups: %d x %d groups of %d slices through gemm_fused16_kernel<%d> and <%d> "
-                         "tile 128x64", p.spA / p.G, p.spB / p.G, p.G, p.G, p.G - 1);
+                         "tile 128x64%s", p.spA / p.G, p.spB / p.G, p.G, p.G, p.G - 1,
+                         blocks_slots(p, all_products, kp) ? ", a slot per block" : ", shared totals");
     else
         note_gemm_kernel("blocks of slice groups: %d x %d groups of %d slices through gemm_fused_kernel<%d> tile %dx%d",
                          p.spA / p.G, p.spB / p.G, p.G, p.G, kBlkTile, kBlkTile);
     // one column panel of C after the other through the same totals
-    const int w = blocks_panel_cols(na_tot, m, n, use16 ? 128 : kBlkTile, use16 ? 64 : kBlkTile);
+    const int w = blocks_panel_cols(blocks_values_per_entry(p, all_products, kp), m, n, use16 ? 128 : kBlkTile, use16 ? 64 : kBlkTile);
     const size_t frag_row_bytes = (size_t)(kp / kFrag) * p.spB * kFragBytes;      // one 32-column fragment row of B
     for (int c0 = 0; c0 < n; c0 += w) {
         const int nc = n - c0 < w ? n - c0 : w;

@@ -86,12 +86,27 @@ struct WindowList16 {
     Window16 w[kMaxWindows16];
 };
 
-// (gemm_fused16.hip) nwin <= kMaxWindows16 blocks in one launch, each: the reduced product set of s in {6, ..., 9} slices on a window, k-blocked, int32
-// diagonal sums added to `totals` (layout of the 128 x 64 tile) with integer atomics; and the finishing kernel
+// (gemm_fused16.hip) nwin <= kMaxWindows16 blocks in one launch, each: the reduced product set of s in {7, 8, 9}
+// slices on a window, k-blocked, int32 diagonal sums added to `totals` (layout of the 128 x 64 tile) with integer
+// atomics; and the finishing kernel.
+// With `slots` (one k-block only: s * kp within the int32 range) nothing is added: window z stores its s int32
+// diagonal sums per entry into a slot of its own, slot z of `totals` read as int32 (a slot: tiles * s * 128 * 64
+// values, windows' na_tot = s), nothing has to be cleared, and launch_finish_slots16 adds what belongs to each
+// diagonal.  (The atomics of nine blocks cost 14 % of the time of 24 slices at 8192^3, 27 % at 4096^3, 36 % at 2048^3.)
 hipError_t launch_fused16_windows(int s, int m, int n, int kp, const int8_t *pA, const int8_t *pB, long long *totals,
-                                  const WindowList16 &wins, int nwin, hipStream_t st);
+                                  const WindowList16 &wins, int nwin, bool slots, hipStream_t st);
 hipError_t launch_finish_blocks16(const long long *totals, const int32_t *eA, const int32_t *eB, double *C, int ldc,
                                   int m, int n, int Q, int diagonals, int na_tot, hipStream_t st);
+// Which slot values add up to each diagonal: the terms of diagonal d are term[first[d]] ... term[first[d + 1] - 1],
+// each (slot index) * 16 + (local diagonal).  Slots 0 ... nf - 1 hold G diagonals per entry (the reduced sets of the
+// blocks), the slots from nf on G - 1 (the reversed sets of the whole blocks), one after the other.
+constexpr int kMaxSlotDiagonals = 2 * OZIMMU_MAX_SLICES + 8;
+struct SlotTerms {
+    unsigned short first[kMaxSlotDiagonals + 1];
+    unsigned short term[kMaxWindows16 * 9 + kMaxWindows16 * 8];
+};
+hipError_t launch_finish_slots16(const int32_t *slots, int nf, int G, const SlotTerms &terms, const int32_t *eA,
+                                 const int32_t *eB, double *C, int ldc, int m, int n, int Q, int diagonals, hipStream_t st);
 
 // 16 bytes per lane: global (sbase + voff)  ->  LDS (ldsaddr + lane * 16); ldsaddr is wavefront-uniform.
 // (global_load_lds: the LDS-DMA form of the vector load, 1 KiB per wavefront instruction; issued

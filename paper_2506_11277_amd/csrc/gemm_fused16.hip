@@ -427,7 +427,8 @@ __global__ __launch_bounds__((64 * Cfg16<S, ALT>::WVM * Cfg16<S, ALT>::WVN)) voi
         const size_t e0 = ((size_t)(tm * tiles_n + tn) * NW + wave) * (size_t)(win.na_tot * WMF * WNF * 16 * 64) + lane;
         if (slot_stride) {
             // exactly two k-blocks: plain int32 stores into this block's slot, nothing cleared, nothing added
-            int *slot = (int *)totals + (size_t)blockIdx.y * (size_t)slot_stride + e0;
+            // (blocks of slice groups with a slot per window: blockIdx.z picks the slot)
+            int *slot = (int *)totals + (size_t)(blockIdx.y + gridDim.y * blockIdx.z) * (size_t)slot_stride + e0;
 #pragma unroll
             for (int a = 0; a < S; ++a) {
                 int *sa = slot + (size_t)a * (WMF * WNF * 16 * 64);
@@ -565,6 +566,47 @@ __global__ __launch_bounds__(512) void finish_blocks16_kernel(const long long *_
     }
 }
 
+// The same after block launches that stored a slot per window (launch_fused16_windows with `slots`): the int32 values
+// that belong to a diagonal are added exactly in int64, the diagonals then in ascending order as everywhere.
+__global__ __launch_bounds__(512) void finish_slots16_kernel(const int32_t *__restrict__ slots, int nf, int G,
+                                                             long long stride_f, long long stride_r, SlotTerms terms,
+                                                             const int32_t *__restrict__ eA,
+                                                             const int32_t *__restrict__ eB, double *__restrict__ C,
+                                                             int ldc, int m, int n, int tiles_n, int Q, int diagonals)
+{
+    constexpr int WVM = 4, NW = 8;
+    const int tm = blockIdx.x / tiles_n, tn = blockIdx.x % tiles_n;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave % WVM, wn = wave / WVM;
+    const int32_t *base_f = slots + ((size_t)blockIdx.x * NW + wave) * (size_t)(G * 16 * 64) + lane;
+    const int32_t *base_r = slots + (size_t)nf * (size_t)stride_f + ((size_t)blockIdx.x * NW + wave) * (size_t)((G - 1) * 16 * 64) + lane;
+    const int m0 = (tm * 4 + wm) * 32, n0 = (tn * 2 + wn) * 32;
+    // blockIdx.y picks one of the lane's four 16 x 16 blocks (i2, j2); its four entries (registers r: value
+    // el = (i2 * 2 + j2) * 4 + r of a local diagonal) go together, so that the loads of a term are independent, and the
+    // launch has four times the wavefronts of the GEMM's tile grid to hide their latency
+    const int blk = blockIdx.y, i2 = blk >> 1, j2 = blk & 1;
+    LevelSum sum[4];
+    for (int d = 0; d < diagonals; ++d) {
+        long long v[4] = {0, 0, 0, 0};
+        for (int t = terms.first[d]; t < terms.first[d + 1]; ++t) {
+            const int q = terms.term[t] >> 4, a = terms.term[t] & 15;
+            const int32_t *p = (q < nf ? base_f + (size_t)q * (size_t)stride_f : base_r + (size_t)(q - nf) * (size_t)stride_r) +
+                               a * (16 * 64) + blk * (4 * 64);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) v[r] += p[r * 64];
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            sum[r].add(ldexp((double)v[r], -kSliceBits * (d + 2)), Q, d == diagonals - 1);      // exact: |v| < 2^53
+    }
+    const int mi = m0 + i2 * 16 + (lane & 15);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int nj = n0 + j2 * 16 + 4 * (lane >> 4) + r;
+        if (mi < m && nj < n) C[mi + (size_t)nj * ldc] = ldexp(sum[r].S, eA[mi] + eB[nj]);
+    }
+}
+
 __global__ void zero16_i64_kernel(long long *p, size_t n)
 {
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0;
@@ -608,14 +650,14 @@ hipError_t launch16_s(int m, int n, int kp, const int8_t *pA, const int8_t *pB, 
 // Blocks of slice groups: for each of the nwin windows the reduced product set of S slices on that window of the
 // planes, k-blocked, its int32 diagonal sums added to the totals with integer atomics (nothing cleared, nothing
 // finished here).
-template <int S>
+template <int S, int ALT = 0>
 hipError_t launch16_windows(int m, int n, int kp, const int8_t *pA, const int8_t *pB, long long *totals,
-                            const WindowList16 &wins, int nwin, hipStream_t st)
+                            const WindowList16 &wins, int nwin, bool slots, hipStream_t st)
 {
-    using G = Cfg16<S>;
+    using G = Cfg16<S, ALT>;
     constexpr int TM = 32 * G::FA, TN = 32 * G::FB, THREADS = 64 * G::WVM * G::WVN;
     static_assert(TM == 128 && TN == 64 && G::WVM == 4 && G::WVN == 2, "blocks share the totals layout of the 128 x 64 tile");
-    auto kern = gemm_fused16_kernel<S, kBlocked>;
+    auto kern = gemm_fused16_kernel<S, kBlocked, ALT>;
     static std::atomic<unsigned long long> configured{0};
     if (hipError_t e = allow_dynamic_lds((const void *)kern, G::LDS, configured); e != hipSuccess) return e;
     const int tiles_m = (m + TM - 1) / TM, tiles_n = (n + TN - 1) / TN;
@@ -623,9 +665,11 @@ hipError_t launch16_windows(int m, int n, int kp, const int8_t *pA, const int8_t
     const int nst = kp / kFrag / 2;
     const int nblocks = (nst + max_stages - 1) / max_stages;
     const int stages_per_block = (nst + nblocks - 1) / nblocks;
+    if (slots && nblocks != 1) return hipErrorInvalidValue;
+    const long long slot_stride = slots ? (long long)tiles_m * tiles_n * S * TM * TN : 0;
     dim3 grid((unsigned)tile_order_blocks(tiles_m, tiles_n, true), nblocks, nwin);
     kern<<<grid, THREADS, G::LDS, st>>>(pA, pB, nullptr, nullptr, nullptr, 0, m, n, kp / kFrag, tiles_m, tiles_n, nullptr,
-                                        totals, stages_per_block, 1, 0, wins);
+                                        totals, stages_per_block, 1, slot_stride, wins);
     return hipGetLastError();
 }
 
@@ -687,13 +731,14 @@ hipError_t dispatch16(int s, int m, int n, int kp, const int8_t *pA, const int8_
 bool fused16_preferred(int s, bool split_k) { return s >= 2 && s <= 9 && !(s <= 3 && split_k); }
 
 hipError_t launch_fused16_windows(int s, int m, int n, int kp, const int8_t *pA, const int8_t *pB, long long *totals,
-                                  const WindowList16 &wins, int nwin, hipStream_t st)
+                                  const WindowList16 &wins, int nwin, bool slots, hipStream_t st)
 {
     if (m <= 0 || n <= 0 || nwin <= 0) return hipSuccess;
     if (nwin > kMaxWindows16) return hipErrorInvalidValue;
     switch (s) {
-#define OZ_CASE(S_) case S_: return launch16_windows<S_>(m, n, kp, pA, pB, totals, wins, nwin, st);
-        OZ_CASE(7) OZ_CASE(8) OZ_CASE(9)      // groups of 8 or 9 slices and their reversed sets of 7 or 8
+#define OZ_CASE(S_) case S_: return launch16_windows<S_>(m, n, kp, pA, pB, totals, wins, nwin, slots, st);
+        case 6: return launch16_windows<6, 3>(m, n, kp, pA, pB, totals, wins, nwin, slots, st);   // (its 128 x 64 tile)
+        OZ_CASE(7) OZ_CASE(8) OZ_CASE(9)      // groups of 7, 8 or 9 slices and their reversed sets of 6, 7 or 8
 #undef OZ_CASE
     }
     return hipErrorInvalidValue;
@@ -705,6 +750,18 @@ hipError_t launch_finish_blocks16(const long long *totals, const int32_t *eA, co
     if (m <= 0 || n <= 0) return hipSuccess;
     const int tiles_m = (m + 127) / 128, tiles_n = (n + 63) / 64;
     finish_blocks16_kernel<<<tiles_m * tiles_n, 512, 0, st>>>(totals, eA, eB, C, ldc, m, n, tiles_n, Q, diagonals, na_tot);
+    return hipGetLastError();
+}
+
+hipError_t launch_finish_slots16(const int32_t *slots, int nf, int G, const SlotTerms &terms, const int32_t *eA,
+                                 const int32_t *eB, double *C, int ldc, int m, int n, int Q, int diagonals, hipStream_t st)
+{
+    if (m <= 0 || n <= 0) return hipSuccess;
+    if (diagonals < 1 || diagonals > kMaxSlotDiagonals || G < 7 || G > 9) return hipErrorInvalidValue;
+    const int tiles_m = (m + 127) / 128, tiles_n = (n + 63) / 64;
+    const long long tile_values = (long long)tiles_m * tiles_n * 128 * 64;
+    finish_slots16_kernel<<<dim3(tiles_m * tiles_n, 4), 512, 0, st>>>(slots, nf, G, tile_values * G, tile_values * (G - 1), terms, eA,
+                                                             eB, C, ldc, m, n, tiles_n, Q, diagonals);
     return hipGetLastError();
 }
 

@@ -40,7 +40,7 @@ inline hipError_t allow_dynamic_lds(const void *kernel, int bytes, std::atomic<u
     return e;
 }
 
-bool fused_handles(int sA, int sB, bool all_products);
+bool fused_handles(int sA, int sB, bool all_products, int m, int n, int k);
 size_t fused_totals_bytes(int sA, int sB, bool all_products, int m, int n, int k);
 size_t banded_totals_bytes(int sA, int sB, int k);
 int fused_max_slices();
@@ -52,7 +52,7 @@ struct BlocksPlan {
     int G, spA, spB;
 };
 bool blocks_plan(int sA, int sB, bool all_products, BlocksPlan *plan);
-size_t blocks_totals_bytes(int sA, int sB, bool all_products, int m, int n);
+size_t blocks_totals_bytes(int sA, int sB, bool all_products, int m, int n, int k);
 
 // Slice counts the GEMM runs with.  Different counts that differ little run as EQUAL counts, the short operand
 // getting zero slices appended by the slicing kernel: a product with a zero slice adds nothing, so every diagonal
@@ -86,10 +86,10 @@ inline void gemm_slice_counts(int sA, int sB, bool all_products, int &cA, int &c
 // Which GEMM path takes a product set, and with how many slices per entry in the planes: the fused kernels (cA, cB
 // from gemm_slice_counts), else blocks of slice groups (whole groups), else the band kernel (the counts as they are).
 enum GemmPath { kPathFused, kPathBlocks, kPathBand };
-inline GemmPath gemm_path(int sA, int sB, bool all_products, int &cA, int &cB)
+inline GemmPath gemm_path(int sA, int sB, bool all_products, int m, int n, int k, int &cA, int &cB)
 {
     gemm_slice_counts(sA, sB, all_products, cA, cB);
-    if (fused_handles(cA, cB, all_products)) return kPathFused;
+    if (fused_handles(cA, cB, all_products, m, n, k)) return kPathFused;
     BlocksPlan p;
     if (blocks_plan(sA, sB, all_products, &p)) {
         cA = p.spA;
@@ -130,10 +130,10 @@ inline Workspace carve(int m, int n, int k, int sA, int sB, bool all_products = 
     w.off_minB = take(8 * (size_t)w.np);
     w.off_expA = take(4 * (size_t)w.mp);
     w.off_expB = take(4 * (size_t)w.np);
-    w.path = gemm_path(sA, sB, all_products, w.cA, w.cB);
+    w.path = gemm_path(sA, sB, all_products, m, n, k, w.cA, w.cB);
     w.off_planesA = take((size_t)w.cA * w.mp * w.kp);
     w.off_planesB = take((size_t)w.cB * w.np * w.kp);
-    w.off_totals = take(w.path == kPathBlocks  ? blocks_totals_bytes(sA, sB, all_products, m, n)
+    w.off_totals = take(w.path == kPathBlocks  ? blocks_totals_bytes(sA, sB, all_products, m, n, k)
                         : w.path == kPathFused ? fused_totals_bytes(w.cA, w.cB, all_products, m, n, k)
                                                : banded_totals_bytes(w.cA, w.cB, k));
     w.total = off;
@@ -180,7 +180,7 @@ void fused_set_panel_bytes(long long bytes);
 // true when the routing gives this product set to the fused kernels: the reduced set with equal counts <=
 // fused_max_slices() (20; not 18, which runs faster as two groups of 9) or different counts <= 18, or all products of
 // equal counts with 2 s - 1 <= 18 diagonals
-bool fused_handles(int sA, int sB, bool all_products);
+bool fused_handles(int sA, int sB, bool all_products, int m, int n, int k);
 // true when it can keep the whole contraction in int32 (min(sA, sB) * k * 127^2 < 2^31)
 bool fused_single_block(int sA, int sB, int k);
 // bytes of int64 per-tile totals the fused kernel needs when it has to cut k into blocks (else 0)

@@ -753,26 +753,34 @@ def test_which_kernel_takes_which_product_set():
               ((7, 8, False), "gemm_fused16_kernel<8> tile 128x64"),                 # run as (8, 8), zero slice appended
               ((4, 12, False), "gemm_fused_kernel<12> different counts tile 128x64, 8 wavefronts"),
               ((6, 6, True), "gemm_fused_kernel<6> all products tile 128x64, 8 wavefronts"),
-              ((18, 18, False), "blocks of slice groups: 2 x 2 groups of 9 slices through gemm_fused16_kernel<9> and <8>"),
-              ((17, 18, False), "blocks of slice groups: 2 x 2 groups of 9 slices through gemm_fused16_kernel<9> and <8>"),
+              ((18, 18, False), "gemm_fused_kernel<18> equal counts tile 64x64, 4 wavefronts"),   # one k-block
+              ((17, 18, False), "gemm_fused_kernel<18> equal counts tile 64x64, 4 wavefronts"),
               ((24, 24, False), "blocks of slice groups: 3 x 3 groups of 8 slices through gemm_fused16_kernel<8> and <7>"),
               ((26, 26, False), "blocks of slice groups: 3 x 3 groups of 9 slices"),
               ((25, 31, False), "blocks of slice groups: 4 x 4 groups of 8 slices"),
               ((20, 7, False), "blocks of slice groups: 3 x 1 groups of 7 slices"),
-              ((13, 13, True), "blocks of slice groups: 2 x 2 groups of 7 slices through gemm_fused_kernel<7>"),
+              ((13, 13, True), "blocks of slice groups: 2 x 2 groups of 7 slices through gemm_fused16_kernel<7> and <6>"),
+              ((21, 21, False), "blocks of slice groups: 3 x 3 groups of 7 slices through gemm_fused16_kernel<7> and <6> tile 128x64, a slot per block"),
               ((16, 16, True), "blocks of slice groups: 2 x 2 groups of 8 slices through gemm_fused16_kernel<8> and <7>"),
               ((12, 5, True), "gemm_banded_kernel (12, 5) slices")]
     for (sA, sB, allp), name in expect:
         C = ozimmu.dgemm2(dA, dB, sA, sB, allp)
         assert ozimmu.last_gemm_kernel().startswith(name), (sA, sB, allp, ozimmu.last_gemm_kernel())
         assert_c_matches(host(C), oracle.dgemm3(A, B, sA, sB, full=allp), f"routing ({sA},{sB},{allp})")
+    # 18 slices whose contraction needs two k-blocks (18 k > 133144) run as two groups of 9 instead
+    A, B = workloads.uniform(70, 60, 7424, 6)
+    for sA in (18, 17):
+        C = ozimmu.dgemm2(dev(A), dev(B), sA, 18)
+        assert ozimmu.last_gemm_kernel().startswith("blocks of slice groups: 2 x 2 groups of 9 slices through gemm_fused16_kernel<9> and <8> tile 128x64, a slot per block")
+        assert_c_matches(host(C), oracle.dgemm2(A, B, sA, 18), f"routing ({sA},18) long k")
 
 
-@pytest.mark.parametrize("s,k", [(21, 300), (24, 17000), (26, 16000), (28, 257), (32, 17000)])
+@pytest.mark.parametrize("s,k", [(21, 300), (21, 19200), (24, 300), (24, 17000), (26, 16000), (27, 2000), (28, 257), (32, 17000), (32, 1000)])
 def test_blocks_of_slice_groups_over_column_panels_and_k_blocks(s, k):
-    # 21 ... 32 slices run as blocks of the (l, h) grid through shared int64 totals: column panels of 128 (totals
-    # budget of one byte: two or three panels, the last one ragged), k beyond 133144 / G (several k-blocks per
-    # block launch, G = 7, 8 or 9 slices per group), zero slices appended (26 -> 27)
+    # 21 ... 32 slices run as blocks of the (l, h) grid, each block storing its int32 diagonal sums into a slot of
+    # its own (k within 133144 / G) or adding them to shared int64 totals (k beyond: several k-blocks per block
+    # launch; G = 7, 8 or 9 slices per group): column panels of 128 (buffer budget of one byte: two or three
+    # panels, the last one ragged), zero slices appended (26 -> 27)
     m, n = (130, 300) if k < 1000 else (40, 200)
     A, B = workloads.lognormal(m, n, k, 2.0, 60 + s)
     want = oracle.dgemm(A, B, s)
