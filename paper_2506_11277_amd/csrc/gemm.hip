@@ -56,13 +56,11 @@ constexpr int kThreads = 256;   // generic kernel: 4 wavefronts, 2 (m) x 2 (n)
 //          pair loop stays fully unrolled over the long operand; the short operand's loop is the outer one and
 //          simply ends after sm slices, so no product needs a test of its own.  LDS keeps the layout for S
 //          slices of both operands (the short one's upper slots stay unused).
-//          4: the product set of 0 on a WINDOW of S consecutive slices of planes that hold more slices per entry
-//          (SliceWindow below); 3 takes its S slices from such a window too.  Together they serve slice counts
-//          beyond the accumulator budget as blocks of the (l, h) grid (launch_gemm_blocks).
+//          3 takes its S slices from a WINDOW of planes that hold more slices per entry (SliceWindow below).
 
 // Where a launch finds its S slices in the planes and where its diagonals go in the split-k totals: the planes
 // hold strA / strB slices per entry and the launch multiplies slices offA + 1 ... offA + S of A and
-// offB + 1 ... offB + S of B (PSET >= 3 only); its diagonal a is diagonal a + a0 of the na_tot diagonals the totals
+// offB + 1 ... offB + S of B (PSET == 3 only); its diagonal a is diagonal a + a0 of the na_tot diagonals the totals
 // hold per entry.
 struct SliceWindow {
     int strA, strB, offA, offB, a0, na_tot;
@@ -104,7 +102,7 @@ __global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wm = wave % WVM, wn = wave / WVM;
     const int sA = PSET == 1 ? sm : S, sB = PSET == 2 ? sm : S;                 // slices in the planes of A / B
-    const int plA = PSET >= 3 ? win.strA : sA, plB = PSET >= 3 ? win.strB : sB;  // slices per entry in the planes
+    const int plA = PSET == 3 ? win.strA : sA, plB = PSET == 3 ? win.strB : sB;  // slices per entry in the planes
     const size_t row_bytesA = (size_t)KB * plA * kFragBytes;    // one fragment row of an operand, all k
     const size_t row_bytesB = (size_t)KB * plB * kFragBytes;
     const int8_t *rowA = pA + (size_t)tm * FA * row_bytesA;
@@ -129,7 +127,7 @@ __global__ __launch_bounds__(64 * WVM * WVN) void gemm_fused_kernel(const int8_t
                 const int kbl = o / S, sl = o % S;                          // LDS slot (k-block, slice)
                 const int cnt = c < FA ? sA : sB;
                 if (sl >= cnt) continue;                                    // the short operand has no such slice
-                const int pl = c < FA ? plA : plB, off = PSET >= 3 ? (c < FA ? win.offA : win.offB) : 0;
+                const int pl = c < FA ? plA : plB, off = PSET == 3 ? (c < FA ? win.offA : win.offB) : 0;
                 src = (c < FA ? rowA + (size_t)c * row_bytesA : rowB + (size_t)(c - FA) * row_bytesB) +
                       ((size_t)(st * KB32 + kbl) * pl + off + sl) * kFragBytes;
             }
@@ -471,41 +469,6 @@ __global__ void zero_i64_kernel(long long *p, size_t n)
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0;
 }
 
-// Binary64 accumulation after the block launches (launch_gemm_blocks): the totals hold na_tot diagonals per entry,
-// the first `diagonals` of them (l + h = 2 ... s + 1 of the requested slice count) are added in ascending order;
-// the rest belongs to products beyond the requested set (zero slices appended to reach a whole number of groups).
-// Same element mapping as the epilogue of gemm_fused_kernel.
-template <int WVM, int WVN, int WMF, int WNF>
-__global__ __launch_bounds__(64 * WVM * WVN) void finish_blocks_kernel(const long long *__restrict__ totals,
-                                                                       const int32_t *__restrict__ eA,
-                                                                       const int32_t *__restrict__ eB,
-                                                                       double *__restrict__ C, int ldc, int m, int n,
-                                                                       int tiles_n, int Q, int diagonals, int na_tot)
-{
-    constexpr int NW = WVM * WVN, FA = WVM * WMF, FB = WVN * WNF;
-    const int tm = blockIdx.x / tiles_n, tn = blockIdx.x % tiles_n;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int wm = wave % WVM, wn = wave / WVM;
-    const long long *tot = totals + ((size_t)blockIdx.x * NW + wave) * (size_t)(na_tot * WMF * WNF * 16 * 64) + lane;
-    const int m0 = (tm * FA + wm * WMF) * 32, n0 = (tn * FB + wn * WNF) * 32;
-    for (int i = 0; i < WMF; ++i) {
-        const int mi = m0 + i * 32 + (lane & 31);
-        if (mi >= m) continue;
-        const int ea = eA[mi];
-        for (int j = 0; j < WNF; ++j)
-            for (int r = 0; r < 16; ++r) {
-                const int nj = n0 + j * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                if (nj >= n) continue;
-                LevelSum sum;
-                for (int a = 0; a < diagonals; ++a) {
-                    const long long v = tot[((((size_t)a * WMF + i) * WNF + j) * 16 + r) * 64];
-                    sum.add(ldexp((double)v, -kSliceBits * (a + 2)), Q, a == diagonals - 1);   // exact: |v| < 2^53
-                }
-                C[mi + (size_t)nj * ldc] = ldexp(sum.S, ea + eB[nj]);
-            }
-    }
-}
-
 // =============================== generic kernel =========================================
 // Any s and any k: one slice pair at a time.  Each pair's product is accumulated in int32 over
 // k-blocks short enough not to overflow, k-block results are added exactly into an int64
@@ -767,39 +730,16 @@ hipError_t dispatch_fused_all(int s, int m, int n, int kp, const int8_t *pA, con
 
 // ---- slice counts beyond the accumulator budget, as blocks of the (l, h) grid -------------------------------
 // The slices of each operand are taken in groups of G (zero slices appended by the slicing kernel where a count is
-// not a multiple of G): NGA groups of A, NGB of B.  Block (I, J) -- slices I G + 1 ... (I + 1) G of A times slices
-// J G + 1 ... (J + 1) G of B -- is one launch of the fused kernel on a window of the planes.  Reduced product set
+// not a multiple of G, and to the operand with fewer groups, so that both planes hold the same number of slices per
+// entry): NGA groups of A, NGB of B.  Block (I, J) -- slices I G + 1 ... (I + 1) G of A times slices
+// J G + 1 ... (J + 1) G of B -- is the work of the 16x16x64 kernel on a window of the planes.  Reduced product set
 // (l + h <= SP + 1 with SP = G max(NGA, NGB)): all G^2 products for I + J < NG - 1, the reduced set l' + h' <= G + 1
-// for I + J = NG - 1, nothing beyond (NG = max(NGA, NGB)); all products: every block whole.  The int32 diagonal sums
-// of a block are added to the int64 totals of the tile, local diagonal a at diagonal a + G (I + J); the finishing
-// kernel then adds the diagonals of the REQUESTED product set in order.  (Appended zero slices add nothing; the
-// diagonals beyond the requested ones, which hold products outside the requested set, are not read.)  All blocks
-// share the four-wavefront 64 x 64 tile, so that the layout of the totals is the same for every launch.
-constexpr int kBlkWVM = 2, kBlkWVN = 2, kBlkTile = 64;
-
-template <int G, int PSET>
-hipError_t launch_block(int m, int n, int kp, const int8_t *pA, const int8_t *pB, long long *totals, int Q,
-                        const SliceWindowList &wins, int nwin, hipStream_t st)
-{
-    if (nwin <= 0) return hipSuccess;
-    constexpr int STAGE = 4 * G * kFragBytes;
-    auto kern = gemm_fused_kernel<G, kBlkWVM, kBlkWVN, 1, 1, 1, 2, kBlocked, PSET>;
-    static std::atomic<unsigned long long> configured{0};
-    if (hipError_t e = allow_dynamic_lds((const void *)kern, 2 * STAGE, configured); e != hipSuccess) return e;
-    const int tiles_m = (m + kBlkTile - 1) / kBlkTile, tiles_n = (n + kBlkTile - 1) / kBlkTile;
-    // k-blocks short enough for G products per diagonal in int32, equally long
-    const int max_stages = (int)(kMaxInt32K / G / kFrag);
-    const int nst = kp / kFrag;
-    const int nblocks = (nst + max_stages - 1) / max_stages;
-    const int stages_per_block = (nst + nblocks - 1) / nblocks;
-    dim3 grid((unsigned)tile_order_blocks(tiles_m, tiles_n, true), nblocks, nwin);
-    kern<<<grid, 64 * kBlkWVM * kBlkWVN, 2 * STAGE, st>>>(pA, pB, nullptr, nullptr, nullptr, 0, m, n, kp / kFrag, tiles_m,
-                                                          tiles_n, nullptr, totals, stages_per_block, Q, G, 0, wins);
-    return hipGetLastError();
-}
-
-// The same plan through the 16x16x64 kernel (tile 128 x 64, two wavefronts per SIMD; the faster one, but its planes
-// must hold the same number of slices per entry for both operands).  It computes reduced sets only, so a whole
+// for I + J = NG - 1, nothing beyond (NG = max(NGA, NGB)); all products: every block whole.  Local diagonal a of a
+// block is diagonal a + G (I + J); the finishing kernel adds the diagonals of the REQUESTED product set in order.
+// (Appended zero slices add nothing; the diagonals beyond the requested ones, which hold products outside the
+// requested set, are not read.)
+//
+// The kernel computes reduced sets only (tile 128 x 64, two wavefronts per SIMD), so a whole
 // block is two launches: the reduced set l' + h' <= G + 1 of the pair of groups, and the rest l' + h' >= G + 2, which
 // is the reduced set of G - 1 slices once both groups are walked backwards from their last slice (l'' = G + 1 - l',
 // h'' = G + 1 - h': l'' + h'' <= G, l'', h'' <= G - 1), its diagonals descending from the block's last one.
@@ -821,7 +761,6 @@ inline void blocks_window_counts(const BlocksPlan &plan, bool all_products, int 
 // one k-block for G slices and the windows fit one launch of each kind.
 inline bool blocks_slots(const BlocksPlan &plan, bool all_products, int kp)
 {
-    if (plan.spA != plan.spB) return false;
     int nf, nr;
     blocks_window_counts(plan, all_products, nf, nr);
     return nf <= kMaxWindows16 && nr <= kMaxWindows16 && kp / (2 * kFrag) <= (int)(kMaxInt32K / plan.G / (2 * kFrag));
@@ -832,6 +771,7 @@ inline hipError_t launch_blocks16_slots(int m, int n, int kp, const BlocksPlan &
                                         double *C, int ldc, long long *totals, int Q, hipStream_t st)
 {
     const int G = plan.G, NGA = plan.spA / G, NGB = plan.spB / G, NG = NGA > NGB ? NGA : NGB;
+    const int stride = plan.spA > plan.spB ? plan.spA : plan.spB;      // slices per entry in both planes
     const int tiles_m = (m + 127) / 128, tiles_n = (n + 63) / 64;
     WindowList16 fwd, rev;
     int abase_f[kMaxWindows16], abase_r[kMaxWindows16];
@@ -842,10 +782,10 @@ inline hipError_t launch_blocks16_slots(int m, int n, int kp, const BlocksPlan &
             const int d0 = G * (I + J);                                       // first diagonal of the block
             if (nf >= kMaxWindows16 || nr >= kMaxWindows16) return hipErrorInvalidValue;
             abase_f[nf] = d0;
-            fwd.w[nf++] = Window16{plan.spA, I * G, 1, J * G, 1, 0, 1, G};
+            fwd.w[nf++] = Window16{stride, I * G, 1, J * G, 1, 0, 1, G};
             if (all_products || I + J < NG - 1) {
                 abase_r[nr] = d0 + 2 * G - 2;
-                rev.w[nr++] = Window16{plan.spA, I * G + G - 1, -1, J * G + G - 1, -1, 0, 1, G - 1};
+                rev.w[nr++] = Window16{stride, I * G + G - 1, -1, J * G + G - 1, -1, 0, 1, G - 1};
             }
         }
     if (diagonals > kMaxSlotDiagonals) return hipErrorInvalidValue;
@@ -878,6 +818,7 @@ inline hipError_t launch_blocks16(int m, int n, int kp, const BlocksPlan &plan, 
     if (blocks_slots(plan, all_products, kp))
         return launch_blocks16_slots(m, n, kp, plan, all_products, diagonals, pA, pB, eA, eB, C, ldc, totals, Q, st);
     const int G = plan.G, NGA = plan.spA / G, NGB = plan.spB / G, NG = NGA > NGB ? NGA : NGB;
+    const int stride = plan.spA > plan.spB ? plan.spA : plan.spB;
     const int tiles_m = (m + 127) / 128, tiles_n = (n + 63) / 64;
     zero_i64_kernel<<<2048, 256, 0, st>>>(totals, (size_t)tiles_m * tiles_n * na_tot * 128 * 64);
     // all blocks of the panel in two launches: the reduced sets of G slices (every block), the reversed reduced sets of
@@ -893,11 +834,11 @@ inline hipError_t launch_blocks16(int m, int n, int kp, const BlocksPlan &plan, 
         for (int J = 0; J < NGB; ++J) {
             if (!all_products && I + J > NG - 1) continue;
             const int d0 = G * (I + J);                                       // first diagonal of the block
-            fwd.w[nf++] = Window16{plan.spA, I * G, 1, J * G, 1, d0, 1, na_tot};
+            fwd.w[nf++] = Window16{stride, I * G, 1, J * G, 1, d0, 1, na_tot};
             if (nf == kMaxWindows16)
                 if (hipError_t e = flush(G, fwd, nf); e != hipSuccess) return e;
             if (all_products || I + J < NG - 1) {
-                rev.w[nr++] = Window16{plan.spA, I * G + G - 1, -1, J * G + G - 1, -1, d0 + 2 * G - 2, -1, na_tot};
+                rev.w[nr++] = Window16{stride, I * G + G - 1, -1, J * G + G - 1, -1, d0 + 2 * G - 2, -1, na_tot};
                 if (nr == kMaxWindows16)
                     if (hipError_t e = flush(G - 1, rev, nr); e != hipSuccess) return e;
             }
@@ -905,43 +846,6 @@ inline hipError_t launch_blocks16(int m, int n, int kp, const BlocksPlan &plan, 
     if (hipError_t e = flush(G, fwd, nf); e != hipSuccess) return e;
     if (hipError_t e = flush(G - 1, rev, nr); e != hipSuccess) return e;
     return launch_finish_blocks16(totals, eA, eB, C, ldc, m, n, Q, diagonals, na_tot, st);
-}
-
-// one column panel of C: `diagonals` = those of the requested product set, na_tot = those the totals hold
-template <int G>
-hipError_t launch_blocks_g(int m, int n, int kp, const BlocksPlan &plan, bool all_products, int diagonals, int na_tot,
-                           const int8_t *pA, const int8_t *pB, const int32_t *eA, const int32_t *eB, double *C, int ldc,
-                           long long *totals, int Q, hipStream_t st)
-{
-    const int NGA = plan.spA / G, NGB = plan.spB / G, NG = NGA > NGB ? NGA : NGB;
-    const int tiles_m = (m + kBlkTile - 1) / kBlkTile, tiles_n = (n + kBlkTile - 1) / kBlkTile;
-    zero_i64_kernel<<<2048, 256, 0, st>>>(totals, (size_t)tiles_m * tiles_n * na_tot * kBlkTile * kBlkTile);
-    // all whole blocks of the panel in one launch, all reduced ones in another (kMaxWindows16 at a time)
-    SliceWindowList whole, reduced;
-    int nw = 0, nr = 0;
-    for (int I = 0; I < NGA; ++I)
-        for (int J = 0; J < NGB; ++J) {
-            if (!all_products && I + J > NG - 1) continue;
-            const SliceWindow win{plan.spA, plan.spB, I * G, J * G, G * (I + J), na_tot};
-            if (all_products || I + J < NG - 1) {
-                whole.w[nw++] = win;
-                if (nw == kMaxWindows16) {
-                    if (hipError_t e = launch_block<G, 3>(m, n, kp, pA, pB, totals, Q, whole, nw, st); e != hipSuccess) return e;
-                    nw = 0;
-                }
-            } else {
-                reduced.w[nr++] = win;
-                if (nr == kMaxWindows16) {
-                    if (hipError_t e = launch_block<G, 4>(m, n, kp, pA, pB, totals, Q, reduced, nr, st); e != hipSuccess) return e;
-                    nr = 0;
-                }
-            }
-        }
-    if (hipError_t e = launch_block<G, 3>(m, n, kp, pA, pB, totals, Q, whole, nw, st); e != hipSuccess) return e;
-    if (hipError_t e = launch_block<G, 4>(m, n, kp, pA, pB, totals, Q, reduced, nr, st); e != hipSuccess) return e;
-    finish_blocks_kernel<kBlkWVM, kBlkWVN, 1, 1>
-        <<<tiles_m * tiles_n, 64 * kBlkWVM * kBlkWVN, 0, st>>>(totals, eA, eB, C, ldc, m, n, tiles_n, Q, diagonals, na_tot);
-    return hipGetLastError();
 }
 
 }  // namespace
@@ -1059,11 +963,6 @@ static int blocks_panel_cols(int diagonals, int m, int n, int tile_m, int tile_n
     return best;
 }
 
-// The 16x16x64 kernel takes the blocks when both planes hold the same number of slices per entry and the groups have
-// 8 or 9 slices (8192^3: s = 24 2730 -> 2850, s = 27 2850 -> 3000, s = 32 2770 -> 2930 TOP/s; groups of 7, which would
-// run its weakest slice counts 7 and 6, lose 6 %: 21 and 28 slices stay with the 32x32x32 blocks).
-static bool blocks_use16(const BlocksPlan &p) { return p.spA == p.spB; }
-
 static int blocks_total_diagonals(const BlocksPlan &p, bool all_products)
 {
     return all_products ? p.spA + p.spB - 1 : (p.spA > p.spB ? p.spA : p.spB);
@@ -1084,13 +983,9 @@ size_t blocks_totals_bytes(int sA, int sB, bool all_products, int m, int n, int 
     BlocksPlan p;
     if (m <= 0 || n <= 0 || !blocks_plan(sA, sB, all_products, &p)) return 0;
     const int na_tot = blocks_values_per_entry(p, all_products, round_up(k > 0 ? k : 1, kPad));
-    const bool use16 = blocks_use16(p);          // 16x16x64 blocks, tile 128 x 64
-    const int w = blocks_panel_cols(na_tot, m, n, use16 ? 128 : kBlkTile, use16 ? 64 : kBlkTile);
+    const int w = blocks_panel_cols(na_tot, m, n, 128, 64);          // tile 128 x 64
     const int wn = w < n ? w : n;
-    if (use16)
-        return (size_t)((m + 127) / 128) * ((wn + 63) / 64) * (size_t)na_tot * 128 * 64 * sizeof(long long);
-    const size_t tiles = (size_t)((m + kBlkTile - 1) / kBlkTile) * ((wn + kBlkTile - 1) / kBlkTile);
-    return tiles * (size_t)na_tot * kBlkTile * kBlkTile * sizeof(long long);
+    return (size_t)((m + 127) / 128) * ((wn + 63) / 64) * (size_t)na_tot * 128 * 64 * sizeof(long long);
 }
 
 hipError_t launch_gemm_blocks(int m, int n, int kp, int sA, int sB, bool all_products, const int8_t *pA,
@@ -1102,37 +997,19 @@ hipError_t launch_gemm_blocks(int m, int n, int kp, int sA, int sB, bool all_pro
     if (!blocks_plan(sA, sB, all_products, &p) || !totals) return hipErrorInvalidValue;
     const int na_tot = blocks_total_diagonals(p, all_products);
     const int diagonals = all_products ? sA + sB - 1 : (sA > sB ? sA : sB);
-    const bool use16 = blocks_use16(p);
-    if (use16)
-        note_gemm_kernel("blocks of slice groups: %d x %d groups of %d slices through gemm_fused16_kernel<%d> and <%d> "
-                         "tile 128x64%s", p.spA / p.G, p.spB / p.G, p.G, p.G, p.G - 1,
-                         blocks_slots(p, all_products, kp) ? ", a slot per block" : ", shared totals");
-    else
-        note_gemm_kernel("blocks of slice groups: %d x %d groups of %d slices through gemm_fused_kernel<%d> tile %dx%d",
-                         p.spA / p.G, p.spB / p.G, p.G, p.G, kBlkTile, kBlkTile);
-    // one column panel of C after the other through the same totals
-    const int w = blocks_panel_cols(blocks_values_per_entry(p, all_products, kp), m, n, use16 ? 128 : kBlkTile, use16 ? 64 : kBlkTile);
-    const size_t frag_row_bytes = (size_t)(kp / kFrag) * p.spB * kFragBytes;      // one 32-column fragment row of B
+    note_gemm_kernel("blocks of slice groups: %d x %d groups of %d slices through gemm_fused16_kernel<%d> and <%d> "
+                     "tile 128x64%s", p.spA / p.G, p.spB / p.G, p.G, p.G, p.G - 1,
+                     blocks_slots(p, all_products, kp) ? ", a slot per block" : ", shared totals");
+    // one column panel of C after the other through the same buffer
+    const int w = blocks_panel_cols(blocks_values_per_entry(p, all_products, kp), m, n, 128, 64);
+    const size_t frag_row_bytes = (size_t)(kp / kFrag) * (p.spA > p.spB ? p.spA : p.spB) * kFragBytes;      // one 32-column fragment row of B
     for (int c0 = 0; c0 < n; c0 += w) {
         const int nc = n - c0 < w ? n - c0 : w;
         const int8_t *pBc = pB + (size_t)(c0 / kFrag) * frag_row_bytes;
         double *Cc = C + (size_t)c0 * ldc;
-        hipError_t e;
-        if (use16) {
-            e = launch_blocks16(m, nc, kp, p, all_products, diagonals, na_tot, pA, pBc, eA, eB + c0, Cc, ldc, totals, Q, st);
-            if (e != hipSuccess) return e;
-            continue;
-        }
-        switch (p.G) {
-#define OZ_CASE(G_) \
-    case G_: \
-        e = launch_blocks_g<G_>(m, nc, kp, p, all_products, diagonals, na_tot, pA, pBc, eA, eB + c0, Cc, ldc, totals, Q, st); \
-        break;
-            OZ_CASE(7) OZ_CASE(8) OZ_CASE(9)
-#undef OZ_CASE
-            default: e = hipErrorInvalidValue;
-        }
-        if (e != hipSuccess) return e;
+        if (hipError_t e = launch_blocks16(m, nc, kp, p, all_products, diagonals, na_tot, pA, pBc, eA, eB + c0, Cc, ldc, totals, Q, st);
+            e != hipSuccess)
+            return e;
     }
     return hipSuccess;
 }

@@ -92,8 +92,7 @@ inline GemmPath gemm_path(int sA, int sB, bool all_products, int m, int n, int k
     if (fused_handles(cA, cB, all_products, m, n, k)) return kPathFused;
     BlocksPlan p;
     if (blocks_plan(sA, sB, all_products, &p)) {
-        cA = p.spA;
-        cB = p.spB;
+        cA = cB = p.spA > p.spB ? p.spA : p.spB;       // the block kernel wants the same number of slices per entry in both
         return kPathBlocks;
     }
     cA = sA;
