@@ -892,7 +892,7 @@ bool blocks_plan(int sA, int sB, bool all_products, BlocksPlan *plan)
     const int sM = sA > sB ? sA : sB, sm = sA > sB ? sB : sA;
     const long long needed = all_products ? (long long)sA * sB : (long long)sm * (2 * sM - sm + 1) / 2;
     long long best = -1;
-    BlocksPlan bp{0, 0, 0};
+    BlocksPlan bp{0, 0, 0, 0, 0};
     for (int G = 9; G >= 7; --G) {
         const int NGA = (sA + G - 1) / G, NGB = (sB + G - 1) / G, NG = NGA > NGB ? NGA : NGB;
         long long cost = 0;
@@ -903,7 +903,7 @@ bool blocks_plan(int sA, int sB, bool all_products, BlocksPlan *plan)
             }
         if (best < 0 || cost <= best) {         // ties go to the smaller group (fewer accumulators per block)
             best = cost;
-            bp = BlocksPlan{G, NGA * G, NGB * G};
+            bp = BlocksPlan{G, NGA * G, NGB * G, cost, needed};
         }
     }
     if (5 * best > 8 * needed) return false;

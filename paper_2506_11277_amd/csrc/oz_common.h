@@ -50,6 +50,7 @@ int fused_max_slices();
 // the fused kernels do not take.  blocks_totals_bytes(): bytes of int64 totals the path needs.
 struct BlocksPlan {
     int G, spA, spB;
+    long long cost, needed;      // products the blocks compute / products of the requested set
 };
 bool blocks_plan(int sA, int sB, bool all_products, BlocksPlan *plan);
 size_t blocks_totals_bytes(int sA, int sB, bool all_products, int m, int n, int k);
@@ -89,8 +90,14 @@ enum GemmPath { kPathFused, kPathBlocks, kPathBand };
 inline GemmPath gemm_path(int sA, int sB, bool all_products, int m, int n, int k, int &cA, int &cB)
 {
     gemm_slice_counts(sA, sB, all_products, cA, cB);
-    if (fused_handles(cA, cB, all_products, m, n, k)) return kPathFused;
     BlocksPlan p;
+    // Different counts with the larger one from 13 on run in the four-wavefront shape of the fused kernel (2450-2580
+    // TOP/s at 8192^3); where the groups of the block path fit them with at most 18 % surplus products, that path is
+    // the faster one: (7,14) 2450 -> 2950, (8,16) 2560 -> 3095, (6,14) 2440 -> 2680, (9,16) 2580 -> 2780 TOP/s of
+    // useful products (and (7,12), 22 % surplus, against the eight-wavefront shape: 2870 -> 2430, so not there).
+    const bool blocks_first = !all_products && cA != cB && (cA > cB ? cA : cB) >= 13 && blocks_plan(sA, sB, false, &p) &&
+                              100 * p.cost <= 118 * p.needed;
+    if (!blocks_first && fused_handles(cA, cB, all_products, m, n, k)) return kPathFused;
     if (blocks_plan(sA, sB, all_products, &p)) {
         cA = cB = p.spA > p.spB ? p.spA : p.spB;       // the block kernel wants the same number of slices per entry in both
         return kPathBlocks;

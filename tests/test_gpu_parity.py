@@ -752,6 +752,10 @@ def test_which_kernel_takes_which_product_set():
               ((16, 16, False), "gemm_fused_kernel<16> equal counts tile 64x64, 4 wavefronts"),
               ((7, 8, False), "gemm_fused16_kernel<8> tile 128x64"),                 # run as (8, 8), zero slice appended
               ((4, 12, False), "gemm_fused_kernel<12> different counts tile 128x64, 8 wavefronts"),
+              ((7, 12, False), "gemm_fused_kernel<12> different counts tile 128x64, 8 wavefronts"),
+              ((5, 14, False), "gemm_fused_kernel<14> different counts tile 64x64, 4 wavefronts"),     # 28 % surplus as blocks
+              ((8, 16, False), "blocks of slice groups: 1 x 2 groups of 8 slices through gemm_fused16_kernel<8> and <7>"),
+              ((14, 6, False), "blocks of slice groups: 2 x 1 groups of 7 slices through gemm_fused16_kernel<7> and <6>"),
               ((6, 6, True), "gemm_fused_kernel<6> all products tile 128x64, 8 wavefronts"),
               ((18, 18, False), "gemm_fused_kernel<18> equal counts tile 64x64, 4 wavefronts"),   # one k-block
               ((17, 18, False), "gemm_fused_kernel<18> equal counts tile 64x64, 4 wavefronts"),
