@@ -548,21 +548,21 @@ __global__ __launch_bounds__(512) void finish_blocks16_kernel(const long long *_
     const int wm = wave % WVM, wn = wave / WVM;
     const long long *tot = totals + ((size_t)blockIdx.x * NW + wave) * (size_t)(na_tot * 16 * 64) + lane;
     const int m0 = (tm * 4 + wm) * 32, n0 = (tn * 2 + wn) * 32;
-    for (int i2 = 0; i2 < 2; ++i2) {
-        const int mi = m0 + i2 * 16 + (lane & 15);
-        if (mi >= m) continue;
-        const int ea = eA[mi];
-        for (int j2 = 0; j2 < 2; ++j2)
-            for (int r = 0; r < 4; ++r) {
-                const int nj = n0 + j2 * 16 + 4 * (lane >> 4) + r;
-                if (nj >= n) continue;
-                LevelSum sum;
-                for (int a = 0; a < diagonals; ++a) {
-                    const long long v = tot[((size_t)a * 16 + (i2 * 2 + j2) * 4 + r) * 64];
-                    sum.add(ldexp((double)v, -kSliceBits * (a + 2)), Q, a == diagonals - 1);      // exact: |v| < 2^53
-                }
-                C[mi + (size_t)nj * ldc] = ldexp(sum.S, ea + eB[nj]);
-            }
+    // blockIdx.y picks one of the lane's four 16 x 16 blocks (i2, j2): four times the wavefronts of the tile grid
+    const int blk = blockIdx.y, i2 = blk >> 1, j2 = blk & 1;
+    LevelSum sum[4];
+    for (int a = 0; a < diagonals; ++a) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const long long v = tot[((size_t)a * 16 + blk * 4 + r) * 64];
+            sum[r].add(ldexp((double)v, -kSliceBits * (a + 2)), Q, a == diagonals - 1);      // exact: |v| < 2^53
+        }
+    }
+    const int mi = m0 + i2 * 16 + (lane & 15);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int nj = n0 + j2 * 16 + 4 * (lane >> 4) + r;
+        if (mi < m && nj < n) C[mi + (size_t)nj * ldc] = ldexp(sum[r].S, eA[mi] + eB[nj]);
     }
 }
 
@@ -749,7 +749,7 @@ hipError_t launch_finish_blocks16(const long long *totals, const int32_t *eA, co
 {
     if (m <= 0 || n <= 0) return hipSuccess;
     const int tiles_m = (m + 127) / 128, tiles_n = (n + 63) / 64;
-    finish_blocks16_kernel<<<tiles_m * tiles_n, 512, 0, st>>>(totals, eA, eB, C, ldc, m, n, tiles_n, Q, diagonals, na_tot);
+    finish_blocks16_kernel<<<dim3(tiles_m * tiles_n, 4), 512, 0, st>>>(totals, eA, eB, C, ldc, m, n, tiles_n, Q, diagonals, na_tot);
     return hipGetLastError();
 }
 
