@@ -862,15 +862,19 @@ static bool fused_capable(int sA, int sB, bool all_products)
     return sA == sB ? sA <= kFusedMaxS : (sA > sB ? sA : sB) <= kFusedMaxUneq;
 }
 
-// ... and what the routing gives them: all of it but 18 equal slices of larger problems.  They are two groups of 9
-// and run faster as blocks through the 16x16x64 kernel than in the four-wavefront shape: 8192^3 (two k-blocks there)
-// 66.7 -> 54.8 ms, 4096^3 8.0 -> 7.4 ms, the same at 2048^3, slower below.  (14 and 16 slices, two groups of 7 and 8,
-// gain 2-3 % at 8192^3 and lose as much at 4096^3: they stay; 17 runs as 18, 19 and 20 have no such grouping.)
+// ... and what the routing gives them: all of it but 17, 18 and 20 equal slices where the groups of the block path
+// serve them better.  18 slices are two groups of 9 and run faster as blocks through the 16x16x64 kernel than in the
+// four-wavefront shape: 8192^3 (two k-blocks there) 66.7 -> 52.8 ms, 4096^3 8.0 -> 7.4 ms, the same at 2048^3, slower
+// below.  17 (as 18, one zero slice) and 20 (as three groups of 7) gain where the contraction needs two k-blocks in
+// the fused kernel: 8192^3 55.6 -> 52.8 ms and 81.6 -> 78.4 ms.  (14 and 16 slices, two groups of 7 and 8, gain 2-3 %
+// at 8192^3 and lose as much at 4096^3: they stay; 19 as 21 would lose.)
 bool fused_handles(int sA, int sB, bool all_products, int m, int n, int k)
 {
-    if (!all_products && sA == sB && sA == 18 &&
-        (18LL * (k > 0 ? k : 1) > kMaxInt32K || (long long)m * n >= 2048LL * 2048LL))
-        return false;
+    if (!all_products && sA == sB) {
+        const bool two_k_blocks = (long long)sA * (k > 0 ? k : 1) > kMaxInt32K;
+        if ((sA == 17 || sA == 18 || sA == 20) && two_k_blocks) return false;
+        if (sA == 18 && (long long)m * n >= 2048LL * 2048LL) return false;
+    }
     return fused_capable(sA, sB, all_products);
 }
 
