@@ -928,13 +928,36 @@ static int fused_panel_cols(int diagonals, int m, int n)
     return (int)(w < np ? w : np);
 }
 
+// int64 values the split-k buffer holds per entry of C: the diagonals, or -- where the 16x16x64 kernel gives every
+// k-block an int32 slot -- half the int32 values of all slots (rounded up).  The slots are taken when all of C fits
+// four times the panel budget in ONE panel (2048 x 2048 x 262144, 7 slices, 14 k-blocks: 1.6 GB; 18.9 -> 18.1 ms,
+// while two panels of slots ran 19.4 ms); else int64 totals over column panels as before.
+static int fused_values_per_entry(int sA, int sB, bool all_products, int kp, int m, int n, bool *kslots)
+{
+    const bool all = all_products && sA > 1;
+    const int s = all ? 2 * sA - 1 : (sA > sB ? sA : sB);
+    *kslots = false;
+    if (sA == sB && !all && fused16_preferred(s, true))
+        if (const int nb = fused16_split_k_slots(s, kp)) {
+            const int values = (nb * s + 1) / 2;
+            const long long mp = round_up(m > 0 ? m : 1, kPad), np = round_up(n > 0 ? n : 1, kPad);
+            if (nb == 2 || 2LL * values * mp * np <= g_panel_bytes.load()) {
+                *kslots = nb > 2;
+                return values;
+            }
+        }
+    return s;
+}
+
 size_t fused_totals_bytes(int sA, int sB, bool all_products, int m, int n, int k)
 {
     if (!fused_capable(sA, sB, all_products) || fused_single_block(sA, sB, k) || m <= 0 || n <= 0) return 0;
     const bool all = all_products && sA > 1;
     const int s = all ? 2 * sA - 1 : (sA > sB ? sA : sB);        // diagonals; the tile shape is tabulated by them
-    {
-        const int w = fused_panel_cols(s, m, n);
+    bool kslots = false;
+    const int values = fused_values_per_entry(sA, sB, all_products, round_up(k > 0 ? k : 1, kPad), m, n, &kslots);
+    if (!kslots) {
+        const int w = fused_panel_cols(values, m, n);
         if (w < n) n = w;
     }
     int tm = 128, tn = 128;
@@ -945,7 +968,7 @@ size_t fused_totals_bytes(int sA, int sB, bool all_products, int m, int n, int k
 #undef OZ_CASE
     }
     const size_t tiles = (size_t)((m + tm - 1) / tm) * ((n + tn - 1) / tn);
-    return tiles * (size_t)s * tm * tn * sizeof(long long);
+    return tiles * (size_t)values * tm * tn * sizeof(long long);
 }
 
 // Column panel of the block path: about g_panel_bytes of totals as for split-k, then narrowed (by up to a half) to
@@ -1020,7 +1043,7 @@ hipError_t launch_gemm_blocks(int m, int n, int kp, int sA, int sB, bool all_pro
 
 static hipError_t launch_gemm_fused_once(int m, int n, int kp, int sA, int sB, bool all_products, const int8_t *pA,
                                          const int8_t *pB, const int32_t *eA, const int32_t *eB, double *C, int ldc,
-                                         int32_t *dump, long long *totals, int Q, hipStream_t st);
+                                         int32_t *dump, long long *totals, int Q, bool kslots, hipStream_t st);
 
 hipError_t launch_gemm_fused(int m, int n, int kp, int sA, int sB, bool all_products, const int8_t *pA,
                              const int8_t *pB, const int32_t *eA, const int32_t *eB, double *C, int ldc,
@@ -1028,15 +1051,16 @@ hipError_t launch_gemm_fused(int m, int n, int kp, int sA, int sB, bool all_prod
 {
     if (m <= 0 || n <= 0) return hipSuccess;
     if (!fused_capable(sA, sB, all_products)) return hipErrorInvalidValue;
-    if (!totals) return launch_gemm_fused_once(m, n, kp, sA, sB, all_products, pA, pB, eA, eB, C, ldc, dump, totals, Q, st);
+    if (!totals) return launch_gemm_fused_once(m, n, kp, sA, sB, all_products, pA, pB, eA, eB, C, ldc, dump, totals, Q, false, st);
     // split-k: one column panel of C after the other, all through the same totals buffer
-    const int diagonals = all_products && sA > 1 ? 2 * sA - 1 : (sA > sB ? sA : sB);
-    const int w = fused_panel_cols(diagonals, m, n);
+    bool kslots = false;
+    const int values = fused_values_per_entry(sA, sB, all_products, kp, m, n, &kslots);
+    const int w = kslots ? round_up(n, kPad) : fused_panel_cols(values, m, n);
     const size_t frag_row_bytes = (size_t)(kp / kFrag) * sB * kFragBytes;      // one 32-column fragment row of B
     for (int c0 = 0; c0 < n; c0 += w) {
         const int nc = n - c0 < w ? n - c0 : w;
         hipError_t e = launch_gemm_fused_once(m, nc, kp, sA, sB, all_products, pA, pB + (size_t)(c0 / kFrag) * frag_row_bytes,
-                                              eA, eB + c0, C + (size_t)c0 * ldc, ldc, dump, totals, Q, st);
+                                              eA, eB + c0, C + (size_t)c0 * ldc, ldc, dump, totals, Q, kslots, st);
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
@@ -1044,7 +1068,7 @@ hipError_t launch_gemm_fused(int m, int n, int kp, int sA, int sB, bool all_prod
 
 static hipError_t launch_gemm_fused_once(int m, int n, int kp, int sA, int sB, bool all_products, const int8_t *pA,
                                          const int8_t *pB, const int32_t *eA, const int32_t *eB, double *C, int ldc,
-                                         int32_t *dump, long long *totals, int Q, hipStream_t st)
+                                         int32_t *dump, long long *totals, int Q, bool kslots, hipStream_t st)
 {
     if (m <= 0 || n <= 0) return hipSuccess;
     if (all_products && sA > 1) {
@@ -1081,7 +1105,7 @@ static hipError_t launch_gemm_fused_once(int m, int n, int kp, int sA, int sB, b
         }
         // the 16x16x64 kernel where it is the faster one
         if (fused16_preferred(s, totals != nullptr))
-            return launch_gemm_fused16(m, n, kp, s, pA, pB, eA, eB, C, ldc, dump, totals, Q, st);
+            return launch_gemm_fused16(m, n, kp, s, pA, pB, eA, eB, C, ldc, dump, totals, Q, kslots, st);
         if (dump) return dispatch_fused<kDump, 0>(s, m, n, kp, pA, pB, eA, eB, C, ldc, dump, nullptr, Q, s, st);
         if (totals) return dispatch_fused<kBlocked, 0>(s, m, n, kp, pA, pB, eA, eB, C, ldc, nullptr, totals, Q, s, st);
         return dispatch_fused<kPlain, 0>(s, m, n, kp, pA, pB, eA, eB, C, ldc, nullptr, nullptr, Q, s, st);

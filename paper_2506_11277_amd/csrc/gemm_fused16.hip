@@ -500,7 +500,7 @@ __global__ __launch_bounds__((64 * Cfg16<S, ALT>::WVM * Cfg16<S, ALT>::WVN)) voi
 template <int S>
 __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void finish_blocked16_kernel(
     const long long *__restrict__ totals, const int32_t *__restrict__ eA, const int32_t *__restrict__ eB,
-    double *__restrict__ C, int ldc, int m, int n, int tiles_n, int Q, long long slot_stride)
+    double *__restrict__ C, int ldc, int m, int n, int tiles_n, int Q, long long slot_stride, int nslot)
 {
     using G = Cfg16<S>;
     constexpr int WVM = G::WVM, WVN = G::WVN, WMF = G::WMF, WNF = G::WNF, FA = G::FA, FB = G::FB, NW = WVM * WVN;
@@ -509,29 +509,36 @@ __global__ __launch_bounds__(64 * Cfg16<S>::WVM * Cfg16<S>::WVN) void finish_blo
     const int wm = wave % WVM, wn = wave / WVM;
     const size_t e0 = ((size_t)blockIdx.x * NW + wave) * (size_t)(S * WMF * WNF * 16 * 64) + lane;
     const long long *tot = totals + e0;
-    const int *slot = (const int *)totals + e0;      // slot_stride != 0: two int32 slots instead of int64 totals
+    const int *slot = (const int *)totals + e0;      // slot_stride != 0: nslot int32 slots (one per k-block) instead of int64 totals
     const int m0 = (tm * FA + wm * WMF) * 32, n0 = (tn * FB + wn * WNF) * 32;
-    for (int i = 0; i < WMF; ++i)
-        for (int i2 = 0; i2 < 2; ++i2) {
-            const int mi = m0 + i * 32 + i2 * 16 + (lane & 15);
-            if (mi >= m) continue;
-            const int ea = eA[mi];
-            for (int j = 0; j < WNF; ++j)
-                for (int j2 = 0; j2 < 2; ++j2)
-                    for (int r = 0; r < 4; ++r) {
-                        const int nj = n0 + j * 32 + j2 * 16 + 4 * (lane >> 4) + r;
-                        if (nj >= n) continue;
-                        LevelSum sum;
+    // blockIdx.y picks one 16 x 16 block of the wavefront's fragments (i, j, i2, j2): WMF * WNF * 4 times the wavefronts
+    // of the tile grid, and the four entries of a lane (registers r) go together, so that the loads are independent
+    const int blk = blockIdx.y, f = blk >> 2, i = f / WNF, j = f % WNF, i2 = (blk >> 1) & 1, j2 = blk & 1;
+    LevelSum sum[4];
 #pragma unroll
-                        for (int a = 0; a < S; ++a) {
-                            const size_t e = ((((size_t)a * WMF + i) * WNF + j) * 16 + (i2 * 2 + j2) * 4 + r) * 64;
-                            const long long v =
-                                slot_stride ? (long long)slot[e] + (long long)slot[(size_t)slot_stride + e] : tot[e];
-                            sum.add((double)v * __builtin_ldexp(1.0, -kSliceBits * (a + 2)), Q, a == S - 1);   // exact conversion
-                        }
-                        C[mi + (size_t)nj * ldc] = ldexp(sum.S, ea + eB[nj]);
-                    }
+    for (int a = 0; a < S; ++a) {
+        const size_t e = ((((size_t)a * WMF + i) * WNF + j) * 16 + (i2 * 2 + j2) * 4) * 64;
+        long long v[4] = {0, 0, 0, 0};
+        if (slot_stride) {
+            for (int y = 0; y < nslot; ++y) {
+                const int *p = slot + (size_t)y * (size_t)slot_stride + e;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) v[r] += p[r * 64];
+            }
+        } else {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) v[r] = tot[e + r * 64];
         }
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            sum[r].add((double)v[r] * __builtin_ldexp(1.0, -kSliceBits * (a + 2)), Q, a == S - 1);   // exact conversion
+    }
+    const int mi = m0 + i * 32 + i2 * 16 + (lane & 15);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int nj = n0 + j * 32 + j2 * 16 + 4 * (lane >> 4) + r;
+        if (mi < m && nj < n) C[mi + (size_t)nj * ldc] = ldexp(sum[r].S, eA[mi] + eB[nj]);
+    }
 }
 
 // Binary64 accumulation after the block launches of launch_gemm_blocks: the totals hold na_tot diagonals per entry in
@@ -614,7 +621,7 @@ __global__ void zero16_i64_kernel(long long *p, size_t n)
 
 template <int S, int MODE, int ALT = 0>
 hipError_t launch16_s(int m, int n, int kp, const int8_t *pA, const int8_t *pB, const int32_t *eA, const int32_t *eB,
-                      double *C, int ldc, int32_t *dump, long long *totals, int Q, hipStream_t st)
+                      double *C, int ldc, int32_t *dump, long long *totals, int Q, bool kslots, hipStream_t st)
 {
     using G = Cfg16<S, ALT>;
     static_assert(ALT == 0 || MODE != kBlocked, "split-k keeps the tabulated tile: the totals are laid out for it");
@@ -636,14 +643,16 @@ hipError_t launch16_s(int m, int n, int kp, const int8_t *pA, const int8_t *pB, 
     const int nst = KB / 2;
     const int nblocks = (nst + max_stages - 1) / max_stages;
     const int stages_per_block = (nst + nblocks - 1) / nblocks;
-    // exactly two k-blocks: an int32 slot per block (together the size of the int64 totals), nothing to clear
+    // two k-blocks, or up to kMaxSplitKSlots where the caller has the buffer for it (`kslots`): an int32 slot per block,
+    // nothing to clear and no atomics (which cost 4-9 % of the launch at 2048 x 2048 x 65536 ... 262144); else int64
+    // totals shared through atomics
     const size_t nslots = (size_t)tiles_m * tiles_n * S * TM * TN;
-    const long long slot_stride = nblocks == 2 ? (long long)nslots : 0;
+    const long long slot_stride = nblocks == 2 || (kslots && fused16_split_k_slots(S, kp)) ? (long long)nslots : 0;
     if (!slot_stride) zero16_i64_kernel<<<2048, 256, 0, st>>>(totals, nslots);
     dim3 grid((unsigned)tile_order_blocks(tiles_m, tiles_n, true), nblocks);
     kern<<<grid, THREADS, G::LDS, st>>>(pA, pB, eA, eB, C, ldc, m, n, KB, tiles_m, tiles_n, nullptr, totals,
                                         stages_per_block, Q, slot_stride, WindowList16{{Window16{S, 0, 1, 0, 1, 0, 1, S}}});
-    finish_blocked16_kernel<S><<<tiles_m * tiles_n, THREADS, 0, st>>>(totals, eA, eB, C, ldc, m, n, tiles_n, Q, slot_stride);
+    finish_blocked16_kernel<S><<<dim3(tiles_m * tiles_n, G::WMF * G::WNF * 4), THREADS, 0, st>>>(totals, eA, eB, C, ldc, m, n, tiles_n, Q, slot_stride, nblocks);
     return hipGetLastError();
 }
 
@@ -701,19 +710,20 @@ int alt_tile(int s, int m, int n)
 
 template <int MODE>
 hipError_t dispatch16(int s, int m, int n, int kp, const int8_t *pA, const int8_t *pB, const int32_t *eA,
-                      const int32_t *eB, double *C, int ldc, int32_t *dump, long long *totals, int Q, hipStream_t st)
+                      const int32_t *eB, double *C, int ldc, int32_t *dump, long long *totals, int Q, bool kslots,
+                      hipStream_t st)
 {
     if constexpr (MODE != kBlocked) {
         const int alt = alt_tile(s, m, n);
-        if (alt == 1) return launch16_s<4, MODE, 1>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, Q, st);
-        if (alt == 2 && s == 2) return launch16_s<2, MODE, 2>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, Q, st);
-        if (alt == 2 && s == 3) return launch16_s<3, MODE, 2>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, Q, st);
-        if (alt == 3 && s == 5) return launch16_s<5, MODE, 3>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, Q, st);
-        if (alt == 3 && s == 6) return launch16_s<6, MODE, 3>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, Q, st);
+        if (alt == 1) return launch16_s<4, MODE, 1>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, Q, kslots, st);
+        if (alt == 2 && s == 2) return launch16_s<2, MODE, 2>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, Q, kslots, st);
+        if (alt == 2 && s == 3) return launch16_s<3, MODE, 2>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, Q, kslots, st);
+        if (alt == 3 && s == 5) return launch16_s<5, MODE, 3>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, Q, kslots, st);
+        if (alt == 3 && s == 6) return launch16_s<6, MODE, 3>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, Q, kslots, st);
     }
     switch (s) {
 #define OZ_CASE(S_) \
-    case S_: return launch16_s<S_, MODE>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, Q, st);
+    case S_: return launch16_s<S_, MODE>(m, n, kp, pA, pB, eA, eB, C, ldc, dump, totals, Q, kslots, st);
         OZ_CASE(2) OZ_CASE(3) OZ_CASE(4) OZ_CASE(5) OZ_CASE(6) OZ_CASE(7) OZ_CASE(8) OZ_CASE(9)
 #undef OZ_CASE
     }
@@ -776,6 +786,14 @@ double fused16_launch_cost(int s, int m, int n, int cus)
     return launch_cost(m, n, tm, tn, cus);
 }
 
+int fused16_split_k_slots(int s, int kp)
+{
+    if (s < 2 || s > 9) return 0;
+    const int max_stages = (int)(kMaxInt32K / s / (2 * kFrag)), nst = kp / (2 * kFrag);
+    const int nblocks = (nst + max_stages - 1) / max_stages;
+    return nblocks >= 2 && nblocks <= kMaxSplitKSlots ? nblocks : 0;
+}
+
 void fused16_set_tile_choice(int choice) { g_tile_choice.store(choice < 0 || choice > 2 ? 0 : choice); }
 
 void fused16_tile(int s, int &tm, int &tn)
@@ -790,12 +808,12 @@ void fused16_tile(int s, int &tm, int &tn)
 
 hipError_t launch_gemm_fused16(int m, int n, int kp, int s, const int8_t *pA, const int8_t *pB, const int32_t *eA,
                                const int32_t *eB, double *C, int ldc, int32_t *dump, long long *totals, int Q,
-                               hipStream_t st)
+                               bool kslots, hipStream_t st)
 {
     if (m <= 0 || n <= 0) return hipSuccess;
-    if (dump) return dispatch16<kDump>(s, m, n, kp, pA, pB, eA, eB, C, ldc, dump, nullptr, Q, st);
-    if (totals) return dispatch16<kBlocked>(s, m, n, kp, pA, pB, eA, eB, C, ldc, nullptr, totals, Q, st);
-    return dispatch16<kPlain>(s, m, n, kp, pA, pB, eA, eB, C, ldc, nullptr, nullptr, Q, st);
+    if (dump) return dispatch16<kDump>(s, m, n, kp, pA, pB, eA, eB, C, ldc, dump, nullptr, Q, false, st);
+    if (totals) return dispatch16<kBlocked>(s, m, n, kp, pA, pB, eA, eB, C, ldc, nullptr, totals, Q, kslots, st);
+    return dispatch16<kPlain>(s, m, n, kp, pA, pB, eA, eB, C, ldc, nullptr, nullptr, Q, false, st);
 }
 
 }  // namespace oz

@@ -199,6 +199,9 @@ hipError_t launch_gemm_fused(int m, int n, int kp, int sA, int sB, bool all_prod
 // the same fused computation on v_mfma_i32_16x16x64_i8, for the slice counts where it is faster (gemm_fused16.hip)
 bool fused16_preferred(int s, bool split_k);
 void fused16_tile(int s, int &tm, int &tn);
+// k-blocks of the 16x16x64 kernel's split-k mode when each gets an int32 slot of its own (2 ... kMaxSplitKSlots), else 0
+constexpr int kMaxSplitKSlots = 14;   // (16 slots at 8 slices, 2048 x 2048 x 262144, were 1-2 % behind the totals)
+int fused16_split_k_slots(int s, int kp);
 // (rounds of the compute units) x (tile area) of a launch with that tile, a measure of its duration; for the
 // 16x16x64 kernel with the tile it would choose (4 slices: the cheaper of its two, the alternative's speed counted in)
 // (a partly filled last round counts 0.8 of a full one plus 0.2 of its share: the fit over 99 measured pairs of
@@ -218,9 +221,10 @@ inline int device_cus()
     return cus;
 }
 void fused16_set_tile_choice(int choice);   // test knob: 0 automatic, 1 tabulated tile, 2 alternative tile (4 slices)
+// (kslots: split-k with an int32 slot per k-block -- fused16_split_k_slots() of them -- instead of int64 totals)
 hipError_t launch_gemm_fused16(int m, int n, int kp, int s, const int8_t *pA, const int8_t *pB,
                                const int32_t *eA, const int32_t *eB, double *C, int ldc,
-                               int32_t *dump, long long *totals, int Q, hipStream_t st);
+                               int32_t *dump, long long *totals, int Q, bool kslots, hipStream_t st);
 // product sets beyond the fused kernels (planes with the slices per entry of blocks_plan); totals: blocks_totals_bytes()
 hipError_t launch_gemm_blocks(int m, int n, int kp, int sA, int sB, bool all_products, const int8_t *pA,
                               const int8_t *pB, const int32_t *eA, const int32_t *eB, double *C, int ldc,
