@@ -260,14 +260,14 @@ static int dgemm_impl(int m, int n, int k, const double *A, int lda, const doubl
     prof_mark(prof, 0, st);
     auto *eA = (int32_t *)(ws + w.off_expA), *eB = (int32_t *)(ws + w.off_expB);
     auto *pA = (int8_t *)(ws + w.off_planesA), *pB = (int8_t *)(ws + w.off_planesB);
-    // three launches for the scales of both operands, one for their slices
-    OZ_TRY(launch_scales_fused(m, n, k, A, lda, B, ldb, (unsigned long long *)(ws + w.off_header),
-                               (unsigned long long *)(ws + w.off_maxA), (unsigned long long *)(ws + w.off_maxB), eA,
-                               w.mp, eB, w.np, nearest ? 1 : 0, st));
+    // two launches for the maxima of both operands, one for their exponents and slices
+    auto *maxA = (unsigned long long *)(ws + w.off_maxA), *maxB = (unsigned long long *)(ws + w.off_maxB);
+    OZ_TRY(launch_scales_fused(m, n, k, A, lda, B, ldb, (unsigned long long *)(ws + w.off_header), maxA, maxB, eA, w.mp,
+                               eB, w.np, nearest ? 1 : 0, m == 0 || n == 0, st));
     if (m == 0 || n == 0) return OZIMMU_OK;
     prof_mark(prof, 1, st);
     // (w.cA, w.cB: the counts the GEMM runs with -- counts that differ little run as equal ones, zero slices appended)
-    OZ_TRY(launch_split_both(m, n, k, A, lda, B, ldb, sA, sB, w.cA, w.cB, eA, eB, pA, pB, nearest, st));
+    OZ_TRY(launch_split_both(m, n, k, A, lda, B, ldb, sA, sB, w.cA, w.cB, maxA, maxB, eA, eB, pA, pB, nearest, st));
     prof_mark(prof, 2, st);
     const int cA = w.cA, cB = w.cB;
     if (w.path == kPathBlocks) {

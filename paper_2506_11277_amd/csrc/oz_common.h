@@ -163,7 +163,18 @@ hipError_t launch_clear_header(void *header, hipStream_t st);
 // the whole scale extraction of ozimmu_dgemm in three launches: clear, reduce both operands, exponents of both
 hipError_t launch_scales_fused(int m, int n, int k, const double *A, int lda, const double *B, int ldb,
                                unsigned long long *hdr, unsigned long long *maxA, unsigned long long *maxB,
-                               int32_t *expA, int mp, int32_t *expB, int np, int bias, hipStream_t st);
+                               int32_t *expA, int mp, int32_t *expB, int np, int bias, bool finalize, hipStream_t st);
+
+// e = floor(log2 M) + 1 from the bit pattern of M >= 0 (eq. (alpha-def)); the exponent-field
+// shortcut described after eq. (beta-def) for normal numbers, leading-zero count for
+// subnormal ones, 0 for M = 0.
+__device__ __forceinline__ int exponent_above(unsigned long long bits)
+{
+    if (bits == 0) return 0;
+    int E = (int)(bits >> 52);
+    if (E) return E - 1022;
+    return (64 - __clzll((long long)bits)) - 1074;
+}
 
 // ---- launchers implemented in split.hip --------------------------------------------------
 // nearest: slices by round-to-nearest (exps must then hold the biased exponents), else by truncation
@@ -172,9 +183,11 @@ hipError_t launch_split(char side, int rows, int cols, const double *X, int ldx,
 
 // slices of both operands (MFMA layout) in one launch; the planes have room for cA >= sA and cB >= sB slices per
 // entry, the slices beyond sA (sB) are written as zeros
+// (the exponents are formed here from the maxima of launch_scales_fused -- bit patterns of max |x| per row of A /
+// column of B -- and stored to eA, eB, their padding as zeros)
 hipError_t launch_split_both(int m, int n, int k, const double *A, int lda, const double *B, int ldb, int sA, int sB,
-                             int cA, int cB, const int32_t *eA, const int32_t *eB, int8_t *pA, int8_t *pB,
-                             bool nearest, hipStream_t st);
+                             int cA, int cB, const unsigned long long *maxA, const unsigned long long *maxB,
+                             int32_t *eA, int32_t *eB, int8_t *pA, int8_t *pB, bool nearest, hipStream_t st);
 
 // ---- launchers implemented in gemm.hip ---------------------------------------------------
 // largest s the fused (all diagonals in registers) kernel handles

@@ -168,17 +168,6 @@ __global__ void clear_header_kernel(unsigned long long *hdr)
     if (threadIdx.x < 32) hdr[threadIdx.x] = 0ULL;
 }
 
-// e = floor(log2 M) + 1 from the bit pattern of M >= 0 (eq. (alpha-def)); the exponent-field
-// shortcut described after eq. (beta-def) for normal numbers, leading-zero count for
-// subnormal ones, 0 for M = 0.
-__device__ __forceinline__ int exponent_above(unsigned long long bits)
-{
-    if (bits == 0) return 0;
-    int E = (int)(bits >> 52);
-    if (E) return E - 1022;
-    return (64 - __clzll((long long)bits)) - 1074;
-}
-
 __global__ void finalize_kernel(const unsigned long long *__restrict__ maxbits,
                                 const unsigned long long *__restrict__ minbits, int32_t *__restrict__ exps,
                                 int nblk, int nblk_padded, unsigned long long *kappa_bits, int bias)
@@ -209,7 +198,7 @@ __global__ void finalize_both_kernel(const unsigned long long *__restrict__ maxA
 
 hipError_t launch_scales_fused(int m, int n, int k, const double *A, int lda, const double *B, int ldb,
                                unsigned long long *hdr, unsigned long long *maxA, unsigned long long *maxB,
-                               int32_t *expA, int mp, int32_t *expB, int np, int bias, hipStream_t st)
+                               int32_t *expA, int mp, int32_t *expB, int np, int bias, bool finalize, hipStream_t st)
 {
     const int mm = m > 0 ? m : 0;
     init_scales_kernel<<<(mm + 32 + 255) / 256, 256, 0, st>>>(hdr, maxA, mm);
@@ -220,7 +209,9 @@ hipError_t launch_scales_fused(int m, int n, int k, const double *A, int lda, co
         reduce_both_kernel<<<(unsigned)(nblkA + nblkB), 256, 0, st>>>((const unsigned long long *)A, lda, m, k,
                                                                       (const unsigned long long *)B, ldb, n, maxA, maxB,
                                                                       (unsigned int *)hdr, gxA > 0 ? gxA : 1, (int)nblkA);
-    finalize_both_kernel<<<(mp + np + 255) / 256, 256, 0, st>>>(maxA, expA, m, mp, maxB, expB, n, np, bias);
+    // (the slicing kernel that follows forms the exponents from the maxima itself and stores them; only a call that
+    // ends here, an empty product, needs them from this launch)
+    if (finalize) finalize_both_kernel<<<(mp + np + 255) / 256, 256, 0, st>>>(maxA, expA, m, mp, maxB, expB, n, np, bias);
     return hipGetLastError();
 }
 

@@ -82,12 +82,17 @@ __device__ __forceinline__ unsigned int slice_of(const Elem &el, int l, unsigned
 template <bool NEAREST>
 __device__ __forceinline__ void split_rows_block(int bx, int by, const unsigned long long *__restrict__ X, int ldx,
                                                  int R, int K, int s, int cs, const int32_t *__restrict__ exps,
-                                                 int8_t *__restrict__ planes, int KB)
+                                                 int8_t *__restrict__ planes, int KB,
+                                                 const unsigned long long *__restrict__ maxbits = nullptr,
+                                                 int32_t *__restrict__ exps_out = nullptr)
 {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int r = bx * 64 + lane;
     const int k0 = by * 64 + w * 16;
-    const int e = r < R ? exps[r] : 0;
+    // (maxbits given: the exponent comes from the row's maximum, biased by one for nearest slices, and the
+    // work-groups of the first k-block store it, zero for the padding rows)
+    const int e = r >= R ? 0 : maxbits ? exponent_above(maxbits[r]) + (NEAREST ? 1 : 0) : exps[r];
+    if (exps_out && by == 0 && w == 0) exps_out[r] = e;
     Elem el[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
@@ -130,7 +135,9 @@ __global__ __launch_bounds__(256) void split_rows_kernel(const unsigned long lon
 template <bool NEAREST>
 __device__ __forceinline__ void split_cols_block(int bx, int by, const unsigned long long *__restrict__ X, int ldx,
                                                  int R, int K, int s, int cs, const int32_t *__restrict__ exps,
-                                                 int8_t *__restrict__ planes, int KB)
+                                                 int8_t *__restrict__ planes, int KB,
+                                                 const unsigned long long *__restrict__ maxbits = nullptr,
+                                                 int32_t *__restrict__ exps_out = nullptr)
 {
     __shared__ __attribute__((aligned(16))) unsigned char lds[kColGroup * 32 * kColLdsRow];
     const int t = threadIdx.x;
@@ -141,7 +148,8 @@ __device__ __forceinline__ void split_cols_block(int bx, int by, const unsigned 
     for (int p = 0; p < 4; ++p) {
         const int jj = p * 8 + (t >> 5);
         const int j = j0 + jj;
-        const int e = j < R ? exps[j] : 0;
+        const int e = j >= R ? 0 : maxbits ? exponent_above(maxbits[j]) + (NEAREST ? 1 : 0) : exps[j];
+        if (exps_out && by == 0 && (t & 31) == 0) exps_out[j] = e;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int kk = k0 + kq + i;
@@ -190,13 +198,15 @@ template <bool NEAREST>
 __global__ __launch_bounds__(256) void split_both_kernel(const unsigned long long *__restrict__ A, int lda, int m,
                                                          const unsigned long long *__restrict__ B, int ldb, int n, int K,
                                                          int sA, int sB, int cA, int cB,
-                                                         const int32_t *__restrict__ eA,
-                                                         const int32_t *__restrict__ eB, int8_t *__restrict__ pA,
-                                                         int8_t *__restrict__ pB, int KB, int gxA, int nblkA, int gxB)
+                                                         const unsigned long long *__restrict__ maxA,
+                                                         const unsigned long long *__restrict__ maxB,
+                                                         int32_t *__restrict__ eA, int32_t *__restrict__ eB,
+                                                         int8_t *__restrict__ pA, int8_t *__restrict__ pB, int KB,
+                                                         int gxA, int nblkA, int gxB)
 {
     const int b = blockIdx.x;
-    if (b < nblkA) split_rows_block<NEAREST>(b % gxA, b / gxA, A, lda, m, K, sA, cA, eA, pA, KB);
-    else split_cols_block<NEAREST>((b - nblkA) % gxB, (b - nblkA) / gxB, B, ldb, n, K, sB, cB, eB, pB, KB);
+    if (b < nblkA) split_rows_block<NEAREST>(b % gxA, b / gxA, A, lda, m, K, sA, cA, nullptr, pA, KB, maxA, eA);
+    else split_cols_block<NEAREST>((b - nblkA) % gxB, (b - nblkA) / gxB, B, ldb, n, K, sB, cB, nullptr, pB, KB, maxB, eB);
 }
 
 // ---- plain layout: plane l is a matrix shaped like X (utility / test path) ----
@@ -247,8 +257,8 @@ hipError_t launch_split(char side, int rows, int cols, const double *X, int ldx,
 }
 
 hipError_t launch_split_both(int m, int n, int k, const double *A, int lda, const double *B, int ldb, int sA, int sB,
-                             int cA, int cB, const int32_t *eA, const int32_t *eB, int8_t *pA, int8_t *pB, bool nearest,
-                             hipStream_t st)
+                             int cA, int cB, const unsigned long long *maxA, const unsigned long long *maxB, int32_t *eA,
+                             int32_t *eB, int8_t *pA, int8_t *pB, bool nearest, hipStream_t st)
 {
     if (cA < sA || cB < sB) return hipErrorInvalidValue;
     const int mp = round_up(m > 0 ? m : 1, kPad), np = round_up(n > 0 ? n : 1, kPad), kp = round_up(k > 0 ? k : 1, kPad);
@@ -257,8 +267,8 @@ hipError_t launch_split_both(int m, int n, int k, const double *A, int lda, cons
     if (nblkA + nblkB > 0x7fffffffLL) return hipErrorInvalidValue;
     auto kern = nearest ? split_both_kernel<true> : split_both_kernel<false>;
     kern<<<(unsigned)(nblkA + nblkB), 256, 0, st>>>((const unsigned long long *)A, lda, m,
-                                                    (const unsigned long long *)B, ldb, n, k, sA, sB, cA, cB, eA, eB, pA, pB,
-                                                    kp / kFrag, gxA, (int)nblkA, gxB);
+                                                    (const unsigned long long *)B, ldb, n, k, sA, sB, cA, cB, maxA, maxB, eA, eB,
+                                                    pA, pB, kp / kFrag, gxA, (int)nblkA, gxB);
     return hipGetLastError();
 }
 
